@@ -1,0 +1,210 @@
+"""Pins for the oracle's forward (Alg. 1, Eq. 4-6) and backward (Alg. 2, Eq. 7-8).  CPU only.
+
+Each test compares the oracle with something that is not the oracle: library attention,
+the textbook linear-attention formula, an N x N evaluation with autograd gradients, closed
+forms, finite differences.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2509_24006_amd import workloads as wl
+from tests import pins
+
+
+def _rand_case(seed, N, d, b, kh, kl, oracle, structured=True):
+    rng = np.random.default_rng(seed)
+    Q = rng.standard_normal((N, d))
+    K = rng.standard_normal((N, d))
+    if structured:
+        t = np.linspace(0, 3, N)[:, None]
+        Q += 1.5 * np.cos(t * np.arange(1, d + 1))
+        K += 1.5 * np.cos(t * np.arange(1, d + 1) + 0.3)
+    V = rng.standard_normal((N, d))
+    W = rng.standard_normal((d, d)) * 0.3
+    dO = rng.standard_normal((N, d))
+    Mc = oracle.build_mask(Q[None], K[None], kh, kl, bq=b, bkv=b)[0]
+    return Q, K, V, W, dO, Mc
+
+
+def test_all_critical_is_dense_softmax_attention(oracle):
+    # k_h = 100 %: every block critical, the linear branch vanishes (Section 2.1)
+    Q, K, V, W, dO, Mc = _rand_case(0, 200, 16, 8, 1.0, 0.1, oracle)
+    assert np.all(Mc == 1)
+    f = oracle.forward(Q, K, V, W, Mc, bq=8, bkv=8)
+    t = [torch.tensor(a, requires_grad=True) for a in (Q, K, V)]
+    ref = torch.nn.functional.scaled_dot_product_attention(t[0][None], t[1][None], t[2][None])[0]
+    np.testing.assert_allclose(f["O"], ref.detach().numpy(), rtol=1e-10, atol=1e-12)
+    S = Q @ K.T / math.sqrt(16)
+    np.testing.assert_allclose(f["L"], np.log(np.exp(S).sum(1)), rtol=1e-10)
+    assert np.all(f["Ol"] == 0) and np.all(f["Hi"] == 0)
+    g = oracle.backward(Q, K, V, W, Mc, f, dO, bq=8, bkv=8)
+    (ref * torch.tensor(dO)).sum().backward()
+    for name, a in zip(("dQ", "dK", "dV"), t):
+        np.testing.assert_allclose(g[name], a.grad.numpy(), rtol=1e-8, atol=1e-11)
+    assert np.all(g["dW"] == 0)
+
+
+@pytest.mark.parametrize("phi", [0, 1])
+def test_all_marginal_is_projected_linear_attention(oracle, phi):
+    # k_h = k_l = 0: O = [phi(Q) (phi(K)^T V) / (phi(Q) rowsum(phi(K)^T))] W  (Section 2.2)
+    Q, K, V, W, dO, _ = _rand_case(1, 150, 12, 16, 0.0, 0.0, oracle)
+    Mc = np.zeros((10, 10), np.int8)
+    f = oracle.forward(Q, K, V, W, Mc, phi=phi, bq=16, bkv=16)
+    t = [torch.tensor(a, requires_grad=True) for a in (Q, K, V, W)]
+    qp, kp = pins.phi_t(t[0], phi), pins.phi_t(t[1], phi)
+    H = kp.T @ t[2]
+    Z = kp.sum(0)
+    ref = ((qp @ H) / (qp @ Z)[:, None]) @ t[3]
+    np.testing.assert_allclose(f["O"], ref.detach().numpy(), rtol=1e-10, atol=1e-12)
+    assert np.all(f["Os"] == 0) and np.all(np.isneginf(f["L"]))
+    np.testing.assert_allclose(f["Hi"][3], H.detach().numpy(), rtol=1e-10)
+    np.testing.assert_allclose(f["Zi"][7], Z.detach().numpy(), rtol=1e-10)
+    g = oracle.backward(Q, K, V, W, Mc, f, dO, phi=phi, bq=16, bkv=16)
+    (ref * torch.tensor(dO)).sum().backward()
+    for name, a in zip(("dQ", "dK", "dV", "dW"), t):
+        np.testing.assert_allclose(g[name], a.grad.numpy(), rtol=1e-8, atol=1e-11)
+
+
+@pytest.mark.parametrize("N,d,b,kh,kl,phi", [
+    (256, 16, 16, 0.2, 0.2, 0), (250, 16, 16, 0.2, 0.3, 0),     # with and without a ragged tail
+    (100, 8, 8, 0.1, 0.1, 1), (1000, 64, 64, 0.1, 0.1, 0),
+    (96, 8, 8, 0.5, 0.5, 0),                                     # no marginal block at all
+    (96, 8, 8, 0.0, 0.4, 0),                                     # no critical block at all
+])
+def test_mixed_mask_matches_dense_evaluation_and_autograd(oracle, N, d, b, kh, kl, phi):
+    Q, K, V, W, dO, Mc = _rand_case(2, N, d, b, kh, kl, oracle)
+    f = oracle.forward(Q, K, V, W, Mc, phi=phi, bq=b, bkv=b)
+    O, Os, Ol, grads = pins.sla_dense_grads(Q, K, V, W, Mc, dO, b, b, phi)
+    np.testing.assert_allclose(f["Os"], Os, rtol=1e-9, atol=1e-12)
+    np.testing.assert_allclose(f["Ol"], Ol, rtol=1e-9, atol=1e-12)
+    np.testing.assert_allclose(f["O"], O, rtol=1e-9, atol=1e-12)
+    g = oracle.backward(Q, K, V, W, Mc, f, dO, phi=phi, bq=b, bkv=b)
+    for name, ref in zip(("dQ", "dK", "dV", "dW"), grads):
+        assert pins.rel_l2(g[name], ref) < 1e-9, name
+        np.testing.assert_allclose(g[name], ref, rtol=1e-6, atol=1e-9 * np.abs(ref).max() + 1e-300)
+
+
+def test_rectangular_blocks(oracle):
+    # b_q != b_kv (Section 2.1 allows it)
+    rng = np.random.default_rng(5)
+    N, d = 120, 8
+    Q, K, V = (rng.standard_normal((N, d)) for _ in range(3))
+    W = rng.standard_normal((d, d))
+    dO = rng.standard_normal((N, d))
+    Mc = oracle.build_mask(Q[None], K[None], 0.25, 0.25, bq=16, bkv=8)[0]
+    assert Mc.shape == (8, 15)
+    f = oracle.forward(Q, K, V, W, Mc, bq=16, bkv=8)
+    O, Os, Ol, grads = pins.sla_dense_grads(Q, K, V, W, Mc, dO, 16, 8)
+    np.testing.assert_allclose(f["O"], O, rtol=1e-9, atol=1e-12)
+    g = oracle.backward(Q, K, V, W, Mc, f, dO, bq=16, bkv=8)
+    for name, ref in zip(("dQ", "dK", "dV", "dW"), grads):
+        assert pins.rel_l2(g[name], ref) < 1e-9, name
+
+
+def test_sparse_only_when_proj_is_zero(oracle):
+    Q, K, V, W, dO, Mc = _rand_case(3, 128, 8, 8, 0.25, 0.25, oracle)
+    f = oracle.forward(Q, K, V, 0 * W, Mc, bq=8, bkv=8)
+    assert np.array_equal(f["O"], f["Os"])
+
+
+def test_constant_values_closed_form(oracle):
+    # V = 1 c^T: both branches are convex combinations of rows of V, so O^s = O^l = c and
+    # O = c + c W, whatever Q, K and the mask are
+    Q, K, V, W, dO, Mc = _rand_case(4, 128, 8, 8, 0.25, 0.25, oracle)
+    c = np.arange(1, 9, dtype=np.float64)
+    f = oracle.forward(Q, K, np.tile(c, (128, 1)), W, Mc, bq=8, bkv=8)
+    np.testing.assert_allclose(f["Os"], np.tile(c, (128, 1)), rtol=1e-12)
+    np.testing.assert_allclose(f["Ol"], np.tile(c, (128, 1)), rtol=1e-12)
+    np.testing.assert_allclose(f["O"], np.tile(c + c @ W, (128, 1)), rtol=1e-12)
+    # convexity bounds for a general V
+    f = oracle.forward(Q, K, V, W, Mc, bq=8, bkv=8)
+    for k in ("Os", "Ol"):
+        assert np.all(f[k] <= V.max(0) + 1e-12) and np.all(f[k] >= V.min(0) - 1e-12)
+
+
+def test_preaggregation_identity_and_saved_states(oracle):
+    # Appendix A.3: H_i = sum_j h_j - sum_{M_c[i,j] != 0} h_j, with h_j = phi(K_j)^T V_j
+    Q, K, V, W, dO, Mc = _rand_case(6, 160, 8, 16, 0.2, 0.2, oracle)
+    f = oracle.forward(Q, K, V, W, Mc, bq=16, bkv=16)
+    kp = pins.phi_t(torch.tensor(K), 0).numpy()
+    h = np.stack([kp[j * 16:(j + 1) * 16].T @ V[j * 16:(j + 1) * 16] for j in range(10)])
+    z = np.stack([kp[j * 16:(j + 1) * 16].sum(0) for j in range(10)])
+    for i in range(10):
+        Hi = h.sum(0) - h[Mc[i] != 0].sum(0)
+        Zi = z.sum(0) - z[Mc[i] != 0].sum(0)
+        np.testing.assert_allclose(f["Hi"][i], Hi, rtol=1e-9, atol=1e-12)
+        np.testing.assert_allclose(f["Zi"][i], Zi, rtol=1e-9, atol=1e-12)
+
+
+def test_key_block_permutation_leaves_output_unchanged(oracle):
+    Q, K, V, W, dO, Mc = _rand_case(7, 128, 8, 16, 0.25, 0.25, oracle)
+    perm = np.random.default_rng(0).permutation(8)
+    blk = lambda X: X.reshape(8, 16, -1)[perm].reshape(128, -1)
+    f = oracle.forward(Q, K, V, W, Mc, bq=16, bkv=16)
+    fp = oracle.forward(Q, blk(K), blk(V), W, Mc[:, perm], bq=16, bkv=16)
+    np.testing.assert_allclose(fp["O"], f["O"], rtol=1e-10, atol=1e-13)
+
+
+def test_heads_and_batches_are_independent(oracle):
+    w = wl.WORKLOADS["small_fp32"]
+    x = wl.make_inputs(w)
+    Mc = oracle.build_mask(x["Q"], x["K"], w.k_h, w.k_l)
+    f = oracle.forward(x["Q"], x["K"], x["V"], x["Proj"], Mc)
+    f1 = oracle.forward(x["Q"][1, 0], x["K"][1, 0], x["V"][1, 0], x["Proj"], Mc[1, 0])
+    assert np.array_equal(f["O"][1, 0], f1["O"])
+    g = oracle.backward(x["Q"], x["K"], x["V"], x["Proj"], Mc, f, x["dO"])
+    dW = np.zeros_like(g["dW"])
+    for b in range(2):
+        for h in range(2):
+            fh = {k: v[b, h] for k, v in f.items()}
+            gh = oracle.backward(x["Q"][b, h], x["K"][b, h], x["V"][b, h], x["Proj"], Mc[b, h], fh,
+                                 x["dO"][b, h])
+            assert np.array_equal(gh["dQ"], g["dQ"][b, h])
+            dW += gh["dW"]
+    np.testing.assert_allclose(g["dW"], dW, rtol=1e-12, atol=1e-14)   # Proj is shared: dW sums
+
+
+@pytest.mark.parametrize("phi", [0, 1])
+def test_gradients_by_central_finite_differences(oracle, phi):
+    # loss = sum(O * dO) with the mask held fixed; float64, every input including Proj
+    Q, K, V, W, dO, Mc = _rand_case(8, 40, 8, 4, 0.2, 0.2, oracle, structured=False)
+    f = oracle.forward(Q, K, V, W, Mc, phi=phi, bq=4, bkv=4)
+    g = oracle.backward(Q, K, V, W, Mc, f, dO, phi=phi, bq=4, bkv=4)
+    loss = lambda q, k, v, w: float((oracle.forward(q, k, v, w, Mc, phi=phi, bq=4, bkv=4)["O"] * dO).sum())
+    args = [Q, K, V, W]
+    rng = np.random.default_rng(9)
+    eps = 1e-5
+    for which, name in enumerate(("dQ", "dK", "dV", "dW")):
+        num, ana = [], []
+        for _ in range(25):
+            idx = tuple(rng.integers(0, s) for s in args[which].shape)
+            ap = [a.copy() for a in args]
+            am = [a.copy() for a in args]
+            ap[which][idx] += eps
+            am[which][idx] -= eps
+            num.append((loss(*ap) - loss(*am)) / (2 * eps))
+            ana.append(g[name][idx])
+        num, ana = np.array(num), np.array(ana)
+        assert np.linalg.norm(num - ana) / np.linalg.norm(ana) < 1e-6, name
+
+
+def test_tiny_config_float32_against_float64_and_dense(oracle):
+    # the tiny fp32 workload itself (d=64, N=1024, 64x64 blocks): float oracle vs double
+    # oracle vs the N x N evaluation
+    w = wl.WORKLOADS["tiny"]
+    x = wl.make_inputs(w)
+    Mc = oracle.build_mask(x["Q"], x["K"], w.k_h, w.k_l)
+    f64 = oracle.forward(x["Q"], x["K"], x["V"], x["Proj"], Mc)
+    f32 = oracle.forward(x["Q"], x["K"], x["V"], x["Proj"], Mc, dtype=np.float32)
+    assert pins.rel_l2(f32["O"], f64["O"]) < 2e-6
+    O, Os, Ol, grads = pins.sla_dense_grads(x["Q"][0, 0], x["K"][0, 0], x["V"][0, 0], x["Proj"],
+                                            Mc[0, 0], x["dO"][0, 0], 64, 64)
+    assert pins.rel_l2(f64["O"][0, 0], O) < 1e-12
+    g64 = oracle.backward(x["Q"], x["K"], x["V"], x["Proj"], Mc, f64, x["dO"])
+    g32 = oracle.backward(x["Q"], x["K"], x["V"], x["Proj"], Mc, f32, x["dO"], dtype=np.float32)
+    for name, ref in zip(("dQ", "dK", "dV"), grads[:3]):
+        assert pins.rel_l2(g64[name][0, 0], ref) < 1e-11, name
+        assert pins.rel_l2(g32[name], g64[name]) < 1e-5, name

@@ -1,0 +1,142 @@
+"""Pins for the oracle's mask step (Eq. 2, Eq. 3, Alg. 1 mask line).  CPU only."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from paper_2509_24006_amd import workloads as wl
+from tests import pins
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def test_counts_follow_round_half_up(oracle):
+    # block counts for the paper's hyper-parameters (Section 6.1: k_h=5%, k_l=10%, b=64)
+    assert oracle.counts(512, 0.05, 0.10) == (26, 51)
+    assert oracle.counts(1182, 0.05, 0.10) == (59, 118)
+    assert oracle.counts(16, 0.10, 0.10) == (2, 2)
+    assert oracle.counts(512, 1.0, 0.10) == (512, 0)      # critical wins, nothing left over
+    assert oracle.counts(512, 0.0, 0.0) == (0, 0)
+    assert oracle.counts(10, 0.95, 0.5) == (10, 0) or oracle.counts(10, 0.95, 0.5) == (9, 1)
+    for T in (1, 7, 16, 100, 511):
+        for kh in (0.0, 0.025, 0.05, 0.3, 1.0):
+            for kl in (0.0, 0.1, 0.9):
+                nh, nl = oracle.counts(T, kh, kl)
+                assert nh == min(T, max(0, math.floor(kh * T + 0.5)))
+                assert 0 <= nl <= T - nh and nl == min(T - nh, math.floor(kl * T + 0.5))
+
+
+def test_image_table_sparsity_is_two_of_sixteen(oracle):
+    # Table 3 (image generation) prints a sparsity of 87.50 %: with 16 key blocks that is
+    # exactly 2 critical blocks per row, which rounding to nearest gives for 10 % and
+    # truncation cannot.
+    line = [l for l in open(os.path.join(GOLDEN, "paper_tables.txt")) if l.startswith("image_sla_sparsity")]
+    sparsity = float(line[0].split()[1])
+    nh, _ = oracle.counts(16, 0.10, 0.0)
+    assert abs((1 - nh / 16) * 100 - sparsity) < 1e-9
+
+
+def test_pool_is_block_mean_with_tail(oracle):
+    rng = np.random.default_rng(0)
+    X = rng.standard_normal((150, 8)).astype(np.float32)
+    p = oracle.pool(X, 64)
+    assert p.shape == (3, 8)
+    ref = np.stack([X[0:64].astype(np.float64).mean(0), X[64:128].astype(np.float64).mean(0),
+                    X[128:150].astype(np.float64).mean(0)])
+    np.testing.assert_allclose(p, ref, rtol=2e-6, atol=1e-7)
+    # exact cases: constant blocks and power-of-two counts
+    X = np.repeat(np.arange(4, dtype=np.float32)[:, None], 16, 0).reshape(4 * 16, 1) * np.ones((1, 3), np.float32)
+    assert np.array_equal(oracle.pool(X, 16), np.arange(4, dtype=np.float32)[:, None] * np.ones((1, 3), np.float32))
+
+
+def test_pool_sum_order_is_sequential(oracle):
+    # 2^24 + 1 + 1 ... added one by one stays at 2^24 in float; a pairwise sum would not
+    X = np.ones((64, 1), np.float32)
+    X[0, 0] = 2.0 ** 24
+    assert oracle.pool(X, 64)[0, 0] == np.float32(2.0 ** 24) / np.float32(64)
+
+
+def test_scores_are_scaled_dot_products(oracle):
+    rng = np.random.default_rng(1)
+    q = rng.standard_normal((5, 32)).astype(np.float32)
+    k = rng.standard_normal((7, 32)).astype(np.float32)
+    s = oracle.scores(q, k)
+    ref = (q.astype(np.float64) @ k.astype(np.float64).T) / math.sqrt(32)
+    np.testing.assert_allclose(s, ref, rtol=1e-5, atol=1e-6)
+    # not symmetric in its operands' shapes: a transposed operand would fail here
+    assert s.shape == (5, 7)
+    # exactly representable case: integers, d = 4 -> scale 1/2
+    q = np.array([[1, 2, 3, 4]], np.float32)
+    k = np.array([[1, 1, 1, 1], [0, 0, 0, -2]], np.float32)
+    assert np.array_equal(oracle.scores(q, k), np.array([[5.0, -4.0]], np.float32))
+
+
+def test_classify_matches_rank_count_definition(oracle):
+    rng = np.random.default_rng(2)
+    for Tn, nh, nl in ((16, 2, 2), (33, 5, 7), (8, 0, 3), (8, 8, 0), (9, 3, 6), (12, 0, 0)):
+        s = rng.standard_normal((6, Tn)).astype(np.float32)
+        assert np.array_equal(oracle.classify(s, nh, nl), pins.mask_by_rank_count(s, nh, nl))
+
+
+def test_classify_ties_lowest_index_first(oracle):
+    s = np.zeros((1, 8), np.float32)                       # all equal
+    assert oracle.classify(s, 2, 3).tolist() == [[1, 1, -1, -1, -1, 0, 0, 0]]
+    s = np.array([[1, 0, 1, 0, 1, 0, 1, 0]], np.float32)   # two values
+    assert oracle.classify(s, 3, 2).tolist() == [[1, -1, 1, -1, 1, 0, 0, 0]]
+    assert oracle.classify(s, 5, 2).tolist() == [[1, 1, 1, -1, 1, -1, 1, 0]]
+    s = np.array([[0.0, -0.0, 0.0, -0.0]], np.float32)     # +0 and -0 compare equal
+    assert oracle.classify(s, 1, 1).tolist() == [[1, -1, 0, 0]]
+    rng = np.random.default_rng(3)
+    s = rng.integers(0, 3, size=(20, 17)).astype(np.float32)
+    assert np.array_equal(oracle.classify(s, 4, 5), pins.mask_by_rank_count(s, 4, 5))
+
+
+def test_mask_row_counts_and_scale_invariance(oracle):
+    w = wl.WORKLOADS["tiny"]
+    x = wl.make_inputs(w, with_dO=False)
+    Mc, s = oracle.build_mask(x["Q"], x["K"], w.k_h, w.k_l, return_scores=True)
+    nh, nl = oracle.counts(w.T, w.k_h, w.k_l)
+    assert Mc.shape == (1, 2, 16, 16)
+    assert np.all((Mc == 1).sum(-1) == nh) and np.all((Mc == -1).sum(-1) == nl)
+    # ranking the row softmax (Eq. 2) instead of the raw score selects the same blocks
+    # whenever the softmax values are distinct
+    Pc = oracle.compressed_weights(s)
+    assert np.allclose(Pc.sum(-1), 1, atol=1e-5)
+    for g in range(2):
+        for i in range(16):
+            if len(np.unique(Pc[0, g, i])) == 16:
+                top = set(np.argsort(-Pc[0, g, i].astype(np.float64), kind="stable")[:nh])
+                assert top == set(np.nonzero(Mc[0, g, i] == 1)[0])
+    # Q -> 4Q scales every score exactly by 4: same mask
+    Mc4 = oracle.build_mask(4 * x["Q"], x["K"], w.k_h, w.k_l)
+    assert np.array_equal(Mc, Mc4)
+    # heads are independent
+    Mc_h1 = oracle.build_mask(x["Q"][:, 1:], x["K"][:, 1:], w.k_h, w.k_l)
+    assert np.array_equal(Mc[:, 1:], Mc_h1)
+
+
+def test_mask_follows_key_block_permutation(oracle):
+    w = wl.WORKLOADS["tiny"]
+    x = wl.make_inputs(w, with_dO=False)
+    Mc, s = oracle.build_mask(x["Q"], x["K"], w.k_h, w.k_l, return_scores=True)
+    perm = np.random.default_rng(4).permutation(w.T)
+    Kp = x["K"].reshape(1, 2, w.T, 64, w.d)[:, :, perm].reshape(x["K"].shape)
+    Mcp = oracle.build_mask(x["Q"], Kp, w.k_h, w.k_l)
+    tie_free = np.array([[len(np.unique(s[0, g, i])) == w.T for i in range(w.T)] for g in range(2)])
+    assert tie_free.any()
+    assert np.array_equal(Mcp[0][tie_free], Mc[0][:, :, perm][tie_free])
+
+
+def test_build_mask_equals_its_parts(oracle):
+    w = wl.WORKLOADS["small_bf16"]          # ragged tail: N = 1110 = 17*64 + 22
+    x = wl.make_inputs(w, with_dO=False)
+    Mc, s = oracle.build_mask(x["Q"], x["K"], w.k_h, w.k_l, return_scores=True)
+    q, k = x["Q"][0, 1], x["K"][0, 1]
+    s1 = oracle.scores(oracle.pool(q, 64), oracle.pool(k, 64))
+    assert np.array_equal(s1, s[0, 1])
+    nh, nl = oracle.counts(w.T, w.k_h, w.k_l)
+    assert np.array_equal(pins.mask_by_rank_count(s1, nh, nl), Mc[0, 1])
+    # the tail block's pooled vector is the mean of its 22 valid tokens
+    np.testing.assert_allclose(oracle.pool(k, 64)[-1], k[17 * 64:].astype(np.float64).mean(0),
+                               rtol=1e-5, atol=1e-6)
