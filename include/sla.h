@@ -1,0 +1,120 @@
+/* sla.h - C ABI of the MI355X sparse-linear attention (SLA) library.
+ *
+ * SLA (arxiv 2509.24006) computes, per batch and head, for Q, K, V in R^{N x d}
+ * (Section 2.1; tensors here are packed [B, H, N, d], d contiguous):
+ *
+ *   1. block scores  s = pool(Q) pool(K)^T / sqrt(d), pool = mean over each block of
+ *      b = 64 consecutive tokens (Eq. 2; the last block may be short);
+ *   2. a three-way block mask M_c[i, j] in {1, 0, -1}: per query-block row the n_h
+ *      highest scores are critical (1), the n_l lowest of the rest negligible (-1),
+ *      the others marginal (0) (Eq. 3, Alg. 1 mask line);
+ *   3. O^s: online-softmax attention over the critical blocks only (Eq. 4);
+ *   4. O^l = phi(Q_i) H_i / (phi(Q_i) Z_i) with H_i, Z_i the sums of the per-key-block
+ *      states h_j = phi(K_j)^T V_j, z_j = rowsum(phi(K_j)^T) over the marginal blocks
+ *      of row i (Eq. 5, Alg. 1);
+ *   5. O = O^s + O^l W with a learned d x d matrix W ("Proj", Eq. 6);
+ * and the matching gradients dQ, dK, dV, dW (Alg. 2, Eq. 7-8, plus the chain rule
+ * through phi and W).  The mask is a constant of the backward pass.
+ *
+ * Conventions
+ *   - Every pointer except `sla_params*` / `sla_sizes_t*` is DEVICE memory owned by the
+ *     caller.  The library never allocates, frees or keeps device memory, and holds no
+ *     state between calls.  Buffers must be 256-byte aligned (any allocator's default).
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the null
+ *     stream); no call synchronises the host.
+ *   - Outputs are overwritten, never accumulated into.
+ *   - Return value: SLA_OK, or a negative error code; nothing was enqueued when the code
+ *     is SLA_EINVAL, SLA_EUNSUPPORTED or SLA_ENOSPACE.
+ *   - Block counts: n_h = floor(k_h*T + 1/2) clamped to [0, T];
+ *     n_l = min(floor(k_l*T + 1/2), T - n_h); n_0 = T - n_h - n_l.  Every row of M_c has
+ *     exactly n_h ones and n_l minus-ones.  Ties: critical = first n_h under (score
+ *     descending, block index ascending); negligible = first n_l of the remaining
+ *     entries under (score ascending, index ascending).
+ *   - n_h = 0 gives O^s = 0 and L = -inf; n_0 = 0 gives O^l = 0, H_i = Z_i = 0.
+ */
+#ifndef SLA_H_
+#define SLA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { SLA_OK = 0, SLA_EINVAL = -1, SLA_EUNSUPPORTED = -2, SLA_ENOSPACE = -3, SLA_EHIP = -4 };
+enum { SLA_PHI_SOFTMAX = 0, SLA_PHI_ELU1 = 1 };   /* feature map of the linear branch */
+enum { SLA_F32 = 0, SLA_BF16 = 1 };               /* storage type of Q,K,V,W,O,dO,dQ,dK,dV */
+
+/* Problem statement (Alg. 1 input line: Q, K, V, block sizes, k_h, k_l; Section 6.1: phi). */
+typedef struct sla_params {
+  int32_t B, H, N, d; /* batch, heads, tokens, head dim; d in {64, 128}; N >= 1            */
+  int32_t bq, bkv;    /* query / key block size; only 64, 64 is supported                  */
+  double k_h, k_l;    /* fractions in [0, 1] of critical / negligible blocks per row       */
+  int32_t phi;        /* SLA_PHI_*                                                         */
+  int32_t dtype;      /* SLA_F32 or SLA_BF16; statistics and dW are always float           */
+} sla_params;
+
+/* Derived sizes and the layout of the opaque buffers (all offsets in bytes).
+ * "state row" below means one block's linear-attention state stored as d*d + d floats:
+ * first the d x d matrix TRANSPOSED (element [c][e] of the paper's matrix at e*d + c),
+ * then the d-vector. */
+typedef struct sla_sizes_t {
+  int32_t T, n_h, n_l, n_0;
+  uint64_t mask_bytes;        /* int8  [B,H,T,T]                                            */
+  uint64_t luts_bytes;
+  uint64_t lut_row_idx;       /* int32 [B,H,T,n_h]   ascending critical key blocks per row  */
+  uint64_t lut_col_ptr;       /* int32 [B,H,T+1]     CSC pointers of the critical entries   */
+  uint64_t lut_col_rows;      /* int32 [B,H,T*n_h]   ascending query blocks per key block   */
+  uint64_t saved_bytes;
+  uint64_t saved_Os;          /* dtype [B,H,N,d]     O^s                                    */
+  uint64_t saved_Ol;          /* dtype [B,H,N,d]     O^l                                    */
+  uint64_t saved_L;           /* float [B,H,N]       L = m + log l                          */
+  uint64_t saved_HZ;          /* float [B,H,T] state rows: H_i (transposed), Z_i            */
+  uint64_t ws_mask_bytes;
+  uint64_t ws_mask_qbar;      /* float [B,H,T,d]     pool(Q), left in the workspace         */
+  uint64_t ws_mask_kbar;      /* float [B,H,T,d]     pool(K)                                */
+  uint64_t ws_mask_scores;    /* float [B,H,T,T]     pre-softmax block scores s             */
+  uint64_t ws_forward_bytes;
+  uint64_t ws_backward_bytes;
+} sla_sizes_t;
+
+/* Fills *out for the given problem.  Host-only, touches no device. */
+int sla_sizes(const sla_params* p, sla_sizes_t* out);
+
+/* Eq. 2 - Eq. 3 and the lookup tables of Appendix A.3.
+ * Q, K: dtype [B,H,N,d].  Mc: int8 [B,H,T,T] (out).  luts: luts_bytes (out).
+ * workspace: >= ws_mask_bytes; on return it holds pool(Q), pool(K) and s at the offsets
+ * above.  Scores are computed in float in one fixed order (sequential sum over a block's
+ * tokens, IEEE division by the token count, fused multiply-add chain over the features,
+ * times the float 1/sqrt(d)), so the mask is reproducible bit for bit. */
+int sla_build_mask(const sla_params* p, const void* Q, const void* K, int8_t* Mc, void* luts,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/* Eq. 3 alone: classify given float scores s [B,H,T,T] (device) and build the tables. */
+int sla_classify_scores(const sla_params* p, const float* s, int8_t* Mc, void* luts, void* stream);
+
+/* Algorithm 1 + Eq. 6.  Q, K, V, O: dtype [B,H,N,d]; W: dtype [d,d] row-major,
+ * O = O^s + O^l W.  Mc, luts: from sla_build_mask for the same params.
+ * saved: saved_bytes (out) for sla_backward, or NULL for inference.
+ * workspace: >= ws_forward_bytes. */
+int sla_forward(const sla_params* p, const void* Q, const void* K, const void* V, const void* W,
+                const int8_t* Mc, const void* luts, void* O, void* saved, void* workspace,
+                size_t workspace_bytes, void* stream);
+
+/* Algorithm 2, with dQ, dK scaled by 1/sqrt(d), dV accumulated over both branches, and the
+ * chain rule through phi and W.  dO, dQ, dK, dV: dtype [B,H,N,d]; dW: float [d,d] (out,
+ * summed over batch, heads and tokens).  saved: as written by sla_forward with the same
+ * inputs.  workspace: >= ws_backward_bytes. */
+int sla_backward(const sla_params* p, const void* Q, const void* K, const void* V, const void* W,
+                 const int8_t* Mc, const void* luts, const void* saved, const void* dO, void* dQ,
+                 void* dK, void* dV, float* dW, void* workspace, size_t workspace_bytes,
+                 void* stream);
+
+/* Static description of an error code. */
+const char* sla_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLA_H_ */

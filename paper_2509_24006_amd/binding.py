@@ -1,0 +1,200 @@
+"""Thin ctypes binding of libsla_hip.so (the C ABI of include/sla.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP kernels.
+PyTorch supplies device memory (torch.empty) and the current HIP stream; nothing is
+computed with torch ops.  There is no fallback: if the library is missing or a call
+fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsla_hip.so")
+
+SLA_F32, SLA_BF16 = 0, 1
+SLA_PHI_SOFTMAX, SLA_PHI_ELU1 = 0, 1
+EXPORTS = ("sla_sizes", "sla_build_mask", "sla_classify_scores", "sla_forward", "sla_backward",
+           "sla_strerror")
+
+
+class sla_params(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32),
+                ("d", ctypes.c_int32), ("bq", ctypes.c_int32), ("bkv", ctypes.c_int32),
+                ("k_h", ctypes.c_double), ("k_l", ctypes.c_double), ("phi", ctypes.c_int32),
+                ("dtype", ctypes.c_int32)]
+
+
+class sla_sizes_t(ctypes.Structure):
+    _fields_ = [("T", ctypes.c_int32), ("n_h", ctypes.c_int32), ("n_l", ctypes.c_int32),
+                ("n_0", ctypes.c_int32)] + [(n, ctypes.c_uint64) for n in (
+                    "mask_bytes", "luts_bytes", "lut_row_idx", "lut_col_ptr", "lut_col_rows",
+                    "saved_bytes", "saved_Os", "saved_Ol", "saved_L", "saved_HZ",
+                    "ws_mask_bytes", "ws_mask_qbar", "ws_mask_kbar", "ws_mask_scores",
+                    "ws_forward_bytes", "ws_backward_bytes")]
+
+
+class SLAError(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads the HIP library; raises if it has not been built (python -m paper_2509_24006_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise SLAError(f"{LIB_PATH} is missing: build it with paper_2509_24006_amd/build.py "
+                           "(there is no CPU or PyTorch fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz = ctypes.c_void_p, ctypes.c_size_t
+        pp = ctypes.POINTER(sla_params)
+        L.sla_sizes.argtypes = [pp, ctypes.POINTER(sla_sizes_t)]
+        L.sla_build_mask.argtypes = [pp, vp, vp, vp, vp, vp, sz, vp]
+        L.sla_classify_scores.argtypes = [pp, vp, vp, vp, vp]
+        L.sla_forward.argtypes = [pp] + [vp] * 9 + [sz, vp]
+        L.sla_backward.argtypes = [pp] + [vp] * 13 + [sz, vp]
+        L.sla_strerror.argtypes = [ctypes.c_int]
+        L.sla_strerror.restype = ctypes.c_char_p
+        for n in EXPORTS[:-1]:
+            getattr(L, n).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise SLAError(f"{what} failed: {lib().sla_strerror(rc).decode()} (code {rc})")
+
+
+def make_params(B: int, H: int, N: int, d: int, k_h: float, k_l: float, dtype: torch.dtype,
+                phi: int = SLA_PHI_SOFTMAX, bq: int = 64, bkv: int = 64) -> sla_params:
+    code = {torch.float32: SLA_F32, torch.bfloat16: SLA_BF16}[dtype]
+    return sla_params(B, H, N, d, bq, bkv, k_h, k_l, phi, code)
+
+
+def sla_sizes(p: sla_params) -> sla_sizes_t:
+    z = sla_sizes_t()
+    _check(lib().sla_sizes(ctypes.byref(p), ctypes.byref(z)), "sla_sizes")
+    return z
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream() -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _buf(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def _dense(t: torch.Tensor, p: sla_params, what: str) -> torch.Tensor:
+    want = (p.B, p.H, p.N, p.d)
+    if tuple(t.shape) != want or not t.is_contiguous() or not t.is_cuda:
+        raise SLAError(f"{what}: expected a contiguous device tensor of shape {want}")
+    return t
+
+
+def sla_build_mask(p: sla_params, Q: torch.Tensor, K: torch.Tensor,
+                   workspace: Optional[torch.Tensor] = None
+                   ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+    """Returns (Mc int8 [B,H,T,T], luts, workspace); the workspace keeps pool(Q), pool(K), s."""
+    z = sla_sizes(p)
+    _dense(Q, p, "Q"); _dense(K, p, "K")
+    Mc = torch.empty((p.B, p.H, z.T, z.T), dtype=torch.int8, device=Q.device)
+    luts = _buf(z.luts_bytes, Q.device)
+    ws = workspace if workspace is not None else _buf(z.ws_mask_bytes, Q.device)
+    _check(lib().sla_build_mask(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(Mc), _ptr(luts), _ptr(ws),
+                                ws.numel(), _stream()), "sla_build_mask")
+    return Mc, luts, ws
+
+
+def sla_classify_scores(p: sla_params, s: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor]:
+    z = sla_sizes(p)
+    assert s.dtype == torch.float32 and s.is_contiguous() and tuple(s.shape) == (p.B, p.H, z.T, z.T)
+    Mc = torch.empty((p.B, p.H, z.T, z.T), dtype=torch.int8, device=s.device)
+    luts = _buf(z.luts_bytes, s.device)
+    _check(lib().sla_classify_scores(ctypes.byref(p), _ptr(s), _ptr(Mc), _ptr(luts), _stream()),
+           "sla_classify_scores")
+    return Mc, luts
+
+
+def sla_forward(p: sla_params, Q, K, V, W, Mc, luts, O: Optional[torch.Tensor] = None,
+                saved: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                need_saved: bool = True) -> Tuple[torch.Tensor, Optional[torch.Tensor]]:
+    """Returns (O, saved).  saved is None when need_saved is False (inference)."""
+    z = sla_sizes(p)
+    for n, t in (("Q", Q), ("K", K), ("V", V)):
+        _dense(t, p, n)
+    if O is None:
+        O = torch.empty_like(Q)
+    if saved is None and need_saved:
+        saved = _buf(z.saved_bytes, Q.device)
+    ws = workspace if workspace is not None else _buf(z.ws_forward_bytes, Q.device)
+    _check(lib().sla_forward(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(W), _ptr(Mc),
+                             _ptr(luts), _ptr(O), _ptr(saved), _ptr(ws), ws.numel(), _stream()),
+           "sla_forward")
+    return O, saved
+
+
+def sla_backward(p: sla_params, Q, K, V, W, Mc, luts, saved, dO,
+                 workspace: Optional[torch.Tensor] = None, out=None):
+    """Returns (dQ, dK, dV, dW); dW is float32 [d, d]."""
+    z = sla_sizes(p)
+    _dense(dO, p, "dO")
+    if out is None:
+        dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+        dW = torch.empty((p.d, p.d), dtype=torch.float32, device=Q.device)
+    else:
+        dQ, dK, dV, dW = out
+    ws = workspace if workspace is not None else _buf(z.ws_backward_bytes, Q.device)
+    _check(lib().sla_backward(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(W), _ptr(Mc),
+                              _ptr(luts), _ptr(saved), _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV),
+                              _ptr(dW), _ptr(ws), ws.numel(), _stream()), "sla_backward")
+    return dQ, dK, dV, dW
+
+
+# ---- views into the opaque buffers (layout documented in include/sla.h)
+
+def _view(buf: torch.Tensor, off: int, shape, dtype: torch.dtype) -> torch.Tensor:
+    n = 1
+    for s in shape:
+        n *= s
+    nbytes = n * torch.empty((), dtype=dtype).element_size()
+    return buf[off:off + nbytes].view(dtype).view(*shape)
+
+
+def saved_views(p: sla_params, saved: torch.Tensor) -> Dict[str, torch.Tensor]:
+    z = sla_sizes(p)
+    dt = torch.float32 if p.dtype == SLA_F32 else torch.bfloat16
+    d = p.d
+    HZ = _view(saved, z.saved_HZ, (p.B, p.H, z.T, d * d + d), torch.float32)
+    return {"Os": _view(saved, z.saved_Os, (p.B, p.H, p.N, d), dt),
+            "Ol": _view(saved, z.saved_Ol, (p.B, p.H, p.N, d), dt),
+            "L": _view(saved, z.saved_L, (p.B, p.H, p.N), torch.float32),
+            # H_i[c][e] is stored transposed: element e*d + c
+            "Hi": HZ[..., :d * d].view(p.B, p.H, z.T, d, d).transpose(-1, -2),
+            "Zi": HZ[..., d * d:]}
+
+
+def lut_views(p: sla_params, luts: torch.Tensor) -> Dict[str, torch.Tensor]:
+    z = sla_sizes(p)
+    return {"row_idx": _view(luts, z.lut_row_idx, (p.B, p.H, z.T, z.n_h), torch.int32),
+            "col_ptr": _view(luts, z.lut_col_ptr, (p.B, p.H, z.T + 1), torch.int32),
+            "col_rows": _view(luts, z.lut_col_rows, (p.B, p.H, z.T * z.n_h), torch.int32)}
+
+
+def mask_ws_views(p: sla_params, ws: torch.Tensor) -> Dict[str, torch.Tensor]:
+    z = sla_sizes(p)
+    return {"qbar": _view(ws, z.ws_mask_qbar, (p.B, p.H, z.T, p.d), torch.float32),
+            "kbar": _view(ws, z.ws_mask_kbar, (p.B, p.H, z.T, p.d), torch.float32),
+            "scores": _view(ws, z.ws_mask_scores, (p.B, p.H, z.T, z.T), torch.float32)}

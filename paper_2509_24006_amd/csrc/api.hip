@@ -1,0 +1,212 @@
+// C ABI of the SLA library (declared in include/sla.h): argument checks, buffer layout and
+// kernel dispatch.  Host code only; every kernel lives in the other translation units.
+#include <math.h>
+#include <string.h>
+
+#include "../../include/sla.h"
+#include "sla_internal.h"
+
+using namespace sla;
+
+namespace {
+
+constexpr int kMaxT = 3072;  // classify keeps 4 rows of keys and labels in 64 KB of LDS
+
+int make_shape(const sla_params* p, Shape* s) {
+  if (!p) return SLA_EINVAL;
+  if (p->B <= 0 || p->H <= 0 || p->N <= 0 || p->d <= 0) return SLA_EINVAL;
+  if (!(p->k_h >= 0.0 && p->k_h <= 1.0) || !(p->k_l >= 0.0 && p->k_l <= 1.0)) return SLA_EINVAL;
+  if (p->bq != kBlk || p->bkv != kBlk) return SLA_EUNSUPPORTED;
+  if (p->d != 64 && p->d != 128) return SLA_EUNSUPPORTED;
+  if (p->phi != SLA_PHI_SOFTMAX && p->phi != SLA_PHI_ELU1) return SLA_EUNSUPPORTED;
+  if (p->dtype != SLA_F32 && p->dtype != SLA_BF16) return SLA_EUNSUPPORTED;
+  const long long T = ((long long)p->N + kBlk - 1) / kBlk;
+  if (T > kMaxT) return SLA_EUNSUPPORTED;
+  if ((long long)p->B * p->H > 65535) return SLA_EUNSUPPORTED;  // grid.y / grid.z limit
+  s->BH = p->B * p->H;
+  s->N = p->N;
+  s->d = p->d;
+  s->T = (int)T;
+  long long nh = (long long)floor(p->k_h * (double)T + 0.5);
+  nh = nh < 0 ? 0 : (nh > T ? T : nh);
+  long long nl = (long long)floor(p->k_l * (double)T + 0.5);
+  nl = nl < 0 ? 0 : (nl > T - nh ? T - nh : nl);
+  s->n_h = (int)nh;
+  s->n_l = (int)nl;
+  s->n_0 = (int)(T - nh - nl);
+  s->phi = p->phi;
+  s->dtype = p->dtype;
+  s->scale = 1.0f / sqrtf((float)p->d);
+  return SLA_OK;
+}
+
+void fill_sizes(const Shape& s, sla_sizes_t* o) {
+  memset(o, 0, sizeof(*o));
+  const size_t BH = s.BH, T = s.T, N = s.N, d = s.d;
+  const size_t esz = s.dtype == SLA_F32 ? 4 : 2;
+  o->T = s.T;
+  o->n_h = s.n_h;
+  o->n_l = s.n_l;
+  o->n_0 = s.n_0;
+  o->mask_bytes = BH * T * T;
+  size_t off = 0;
+  o->lut_row_idx = off;
+  off += align_up(BH * T * (size_t)s.n_h * 4 + 4);
+  o->lut_col_ptr = off;
+  off += align_up(BH * (T + 1) * 4);
+  o->lut_col_rows = off;
+  off += align_up(BH * T * (size_t)s.n_h * 4 + 4);
+  o->luts_bytes = off;
+  off = 0;
+  o->saved_Os = off;
+  off += align_up(BH * N * d * esz);
+  o->saved_Ol = off;
+  off += align_up(BH * N * d * esz);
+  o->saved_L = off;
+  off += align_up(BH * N * 4);
+  o->saved_HZ = off;
+  const size_t state = align_up(BH * T * (size_t)s.state_row() * 4);
+  off += state;
+  o->saved_bytes = off;
+  off = 0;
+  o->ws_mask_qbar = off;
+  off += align_up(BH * T * d * 4);
+  o->ws_mask_kbar = off;
+  off += align_up(BH * T * d * 4);
+  o->ws_mask_scores = off;
+  off += align_up(BH * T * T * 4);
+  o->ws_mask_bytes = off;
+  o->ws_forward_bytes = 2 * state;
+  o->ws_backward_bytes = simt_backward_ws_bytes(s);
+}
+
+inline bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+
+int hip_status(hipError_t e) { return e == hipSuccess ? SLA_OK : SLA_EHIP; }
+
+}  // namespace
+
+extern "C" {
+
+int sla_sizes(const sla_params* p, sla_sizes_t* out) {
+  Shape s;
+  if (!out) return SLA_EINVAL;
+  const int rc = make_shape(p, &s);
+  if (rc != SLA_OK) return rc;
+  fill_sizes(s, out);
+  return SLA_OK;
+}
+
+int sla_classify_scores(const sla_params* p, const float* scores, int8_t* Mc, void* luts,
+                        void* stream) {
+  Shape s;
+  const int rc = make_shape(p, &s);
+  if (rc != SLA_OK) return rc;
+  if (!scores || !Mc || !luts || misaligned(scores) || misaligned(luts)) return SLA_EINVAL;
+  sla_sizes_t z;
+  fill_sizes(s, &z);
+  hipStream_t st = (hipStream_t)stream;
+  char* l = (char*)luts;
+  hipError_t e = launch_classify(scores, s, Mc, (int32_t*)(l + z.lut_row_idx), st);
+  if (e == hipSuccess)
+    e = launch_csc(Mc, s, (int32_t*)(l + z.lut_col_ptr), (int32_t*)(l + z.lut_col_rows), st);
+  return hip_status(e);
+}
+
+int sla_build_mask(const sla_params* p, const void* Q, const void* K, int8_t* Mc, void* luts,
+                   void* workspace, size_t workspace_bytes, void* stream) {
+  Shape s;
+  const int rc = make_shape(p, &s);
+  if (rc != SLA_OK) return rc;
+  if (!Q || !K || !Mc || !luts || !workspace) return SLA_EINVAL;
+  if (misaligned(Q) || misaligned(K) || misaligned(luts) || misaligned(workspace)) return SLA_EINVAL;
+  sla_sizes_t z;
+  fill_sizes(s, &z);
+  if (workspace_bytes < z.ws_mask_bytes) return SLA_ENOSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  float* qbar = (float*)(ws + z.ws_mask_qbar);
+  float* kbar = (float*)(ws + z.ws_mask_kbar);
+  float* sc = (float*)(ws + z.ws_mask_scores);
+  hipError_t e = launch_pool(Q, s, qbar, st);
+  if (e == hipSuccess) e = launch_pool(K, s, kbar, st);
+  if (e == hipSuccess) e = launch_scores(qbar, kbar, s, sc, st);
+  if (e != hipSuccess) return SLA_EHIP;
+  return sla_classify_scores(p, sc, Mc, luts, stream);
+}
+
+int sla_forward(const sla_params* p, const void* Q, const void* K, const void* V, const void* W,
+                const int8_t* Mc, const void* luts, void* O, void* saved, void* workspace,
+                size_t workspace_bytes, void* stream) {
+  Shape s;
+  const int rc = make_shape(p, &s);
+  if (rc != SLA_OK) return rc;
+  if (!Q || !K || !V || !W || !Mc || !luts || !O || !workspace) return SLA_EINVAL;
+  if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(W) || misaligned(O) ||
+      misaligned(luts) || misaligned(saved) || misaligned(workspace))
+    return SLA_EINVAL;
+  sla_sizes_t z;
+  fill_sizes(s, &z);
+  if (workspace_bytes < z.ws_forward_bytes) return SLA_ENOSPACE;
+  char* ws = (char*)workspace;
+  char* sv = (char*)saved;
+  const char* l = (const char*)luts;
+  FwdArgs a;
+  a.Q = Q; a.K = K; a.V = V; a.W = W;
+  a.Mc = Mc;
+  a.row_idx = (const int32_t*)(l + z.lut_row_idx);
+  a.O = O;
+  a.Os = sv ? sv + z.saved_Os : nullptr;
+  a.Ol = sv ? sv + z.saved_Ol : nullptr;
+  a.L = sv ? (float*)(sv + z.saved_L) : nullptr;
+  a.hz = (float*)ws;
+  a.HZ = sv ? (float*)(sv + z.saved_HZ) : (float*)(ws + z.ws_forward_bytes / 2);
+  return hip_status(simt_forward(s, a, (hipStream_t)stream));
+}
+
+int sla_backward(const sla_params* p, const void* Q, const void* K, const void* V, const void* W,
+                 const int8_t* Mc, const void* luts, const void* saved, const void* dO, void* dQ,
+                 void* dK, void* dV, float* dW, void* workspace, size_t workspace_bytes,
+                 void* stream) {
+  Shape s;
+  const int rc = make_shape(p, &s);
+  if (rc != SLA_OK) return rc;
+  if (!Q || !K || !V || !W || !Mc || !luts || !saved || !dO || !dQ || !dK || !dV || !dW || !workspace)
+    return SLA_EINVAL;
+  if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(W) || misaligned(dO) ||
+      misaligned(dQ) || misaligned(dK) || misaligned(dV) || misaligned(dW) || misaligned(luts) ||
+      misaligned(saved) || misaligned(workspace))
+    return SLA_EINVAL;
+  sla_sizes_t z;
+  fill_sizes(s, &z);
+  if (workspace_bytes < z.ws_backward_bytes) return SLA_ENOSPACE;
+  const char* sv = (const char*)saved;
+  const char* l = (const char*)luts;
+  BwdArgs a;
+  a.Q = Q; a.K = K; a.V = V; a.W = W; a.dO = dO;
+  a.Mc = Mc;
+  a.row_idx = (const int32_t*)(l + z.lut_row_idx);
+  a.col_ptr = (const int32_t*)(l + z.lut_col_ptr);
+  a.col_rows = (const int32_t*)(l + z.lut_col_rows);
+  a.Os = sv + z.saved_Os;
+  a.Ol = sv + z.saved_Ol;
+  a.L = (const float*)(sv + z.saved_L);
+  a.HZ = (const float*)(sv + z.saved_HZ);
+  a.dQ = dQ; a.dK = dK; a.dV = dV;
+  a.dW = dW;
+  a.ws = (char*)workspace;
+  return hip_status(simt_backward(s, a, (hipStream_t)stream));
+}
+
+const char* sla_strerror(int code) {
+  switch (code) {
+    case SLA_OK: return "ok";
+    case SLA_EINVAL: return "invalid argument (null or misaligned pointer, non-positive size, k outside [0,1])";
+    case SLA_EUNSUPPORTED: return "unsupported configuration (block size, head dim, dtype, phi or sequence length)";
+    case SLA_ENOSPACE: return "workspace too small (see sla_sizes)";
+    case SLA_EHIP: return "a HIP call or kernel launch failed";
+    default: return "unknown error code";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,259 @@
+// Mask step of SLA on gfx950: block mean-pooling, pooled scores, three-way classification
+// (Eq. 2, Eq. 3, Alg. 1 mask line) and the row / column lookup tables of Appendix A.3.
+//
+// All arithmetic that decides the mask is float in one fixed order so that the integer
+// result is reproducible: sequential add over a block's tokens, one IEEE division, a
+// fused multiply-add chain over the features, one multiply by 1/sqrt(d).
+#include "sla_internal.h"
+
+namespace sla {
+namespace {
+
+// ---------------------------------------------------------------- pool
+// One wavefront per token block; lane owns VEC adjacent feature columns and walks the
+// block's rows in order.  Rows are 64*VEC elements, so a wavefront reads whole rows.
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ X, int nblk, int N, int Tn,
+                                                   float* __restrict__ out) {
+  const int lane = threadIdx.x & 63;
+  const long blk = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (blk >= nblk) return;
+  const int d = 64 * VEC;
+  const int bh = (int)(blk / Tn), i = (int)(blk % Tn);
+  const int cnt = min(kBlk, N - i * kBlk);
+  const T* p = X + ((size_t)bh * N + (size_t)i * kBlk) * d + lane * VEC;
+  float s[VEC];
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) s[v] = 0.0f;
+#pragma unroll 8
+  for (int r = 0; r < cnt; ++r) {
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) s[v] = s[v] + to_f32(p[(size_t)r * d + v]);
+  }
+  const float c = (float)cnt;
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) out[(size_t)blk * d + lane * VEC + v] = __fdiv_rn(s[v], c);
+}
+
+// ---------------------------------------------------------------- scores
+// 64x64 output tile per workgroup, 4x4 outputs per thread, features staged through LDS in
+// chunks of 64; each output keeps one fused multiply-add chain in ascending feature order.
+__global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ qbar,
+                                                    const float* __restrict__ kbar, int T, int d,
+                                                    float scale, float* __restrict__ s) {
+  __shared__ float qs[64][65];
+  __shared__ float ks[64][65];
+  const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
+  const int bh = blockIdx.z, i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
+  const float* qb = qbar + (size_t)bh * T * d;
+  const float* kb = kbar + (size_t)bh * T * d;
+  float acc[4][4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b) acc[a][b] = 0.0f;
+  for (int k0 = 0; k0 < d; k0 += 64) {
+    for (int idx = tid; idx < 64 * 64; idx += 256) {
+      const int r = idx >> 6, c = idx & 63;
+      qs[r][c] = (i0 + r < T) ? qb[(size_t)(i0 + r) * d + k0 + c] : 0.0f;
+      ks[r][c] = (j0 + r < T) ? kb[(size_t)(j0 + r) * d + k0 + c] : 0.0f;
+    }
+    __syncthreads();
+    for (int k = 0; k < 64; ++k) {
+      float av[4], bv[4];
+#pragma unroll
+      for (int a = 0; a < 4; ++a) av[a] = qs[ty + 16 * a][k];
+#pragma unroll
+      for (int b = 0; b < 4; ++b) bv[b] = ks[tx + 16 * b][k];
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) acc[a][b] = __fmaf_rn(av[a], bv[b], acc[a][b]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int a = 0; a < 4; ++a) {
+    const int i = i0 + ty + 16 * a;
+    if (i >= T) continue;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      const int j = j0 + tx + 16 * b;
+      if (j < T) s[((size_t)bh * T + i) * T + j] = __fmul_rn(acc[a][b], scale);
+    }
+  }
+}
+
+// ---------------------------------------------------------------- classify
+// Order-preserving map float -> uint32 (larger float <=> larger key); +0 and -0 coincide.
+__device__ __forceinline__ uint32_t order_key(float f) {
+  uint32_t b = __float_as_uint(f);
+  if (b == 0x80000000u) b = 0u;
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+__device__ __forceinline__ int wave_sum(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// k-th largest key of a row held in LDS (k >= 1), found bit by bit: the result is the
+// largest t with #{key >= t} >= k.  Entries whose key is 0 never count.
+__device__ uint32_t kth_largest(const uint32_t* keys, int T, int k, int lane) {
+  uint32_t prefix = 0;
+  for (int bit = 31; bit >= 0; --bit) {
+    const uint32_t cand = prefix | (1u << bit);
+    int c = 0;
+    for (int j = lane; j < T; j += 64) c += (keys[j] >= cand);
+    if (wave_sum(c) >= k) prefix = cand;
+  }
+  return prefix;
+}
+
+// Marks with `label` the k entries that come first under (key descending, index
+// ascending) among the entries with a non-zero key.
+__device__ void mark_top(const uint32_t* keys, int8_t* lab, int T, int k, int8_t label, int lane) {
+  if (k <= 0) return;
+  const uint32_t thr = kth_largest(keys, T, k, lane);
+  int c = 0;
+  for (int j = lane; j < T; j += 64) c += (keys[j] > thr);
+  int need = k - wave_sum(c);  // how many of the entries equal to thr are taken, lowest index first
+  for (int j0 = 0; j0 < T; j0 += 64) {
+    const int j = j0 + lane;
+    const uint32_t key = (j < T) ? keys[j] : 0u;
+    const bool eq = (j < T) && (key == thr);
+    const unsigned long long m = __ballot(eq);
+    const int before = __popcll(m & ((1ull << lane) - 1ull));
+    if (j < T && (key > thr || (eq && before < need))) lab[j] = label;
+    need -= __popcll(m);
+  }
+}
+
+// One wavefront per row of the score matrix.
+__global__ __launch_bounds__(256) void classify_kernel(const float* __restrict__ s, int rows, int T,
+                                                       int n_h, int n_l, int8_t* __restrict__ Mc,
+                                                       int32_t* __restrict__ row_idx) {
+  extern __shared__ unsigned char smem[];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  uint32_t* keys = reinterpret_cast<uint32_t*>(smem) + (size_t)wave * T;
+  int8_t* lab = reinterpret_cast<int8_t*>(smem + (size_t)4 * T * sizeof(uint32_t)) + (size_t)wave * T;
+  const long row_raw = (long)blockIdx.x * 4 + wave;
+  const bool live = row_raw < rows;  // surplus wavefronts redo the last row and store nothing
+  const long row = live ? row_raw : rows - 1;
+  const float* sr = s + (size_t)row * T;
+  for (int j = lane; j < T; j += 64) {
+    keys[j] = order_key(sr[j]);
+    lab[j] = 0;
+  }
+  __syncthreads();
+  mark_top(keys, lab, T, n_h, (int8_t)1, lane);
+  __syncthreads();
+  // negligible: lowest scores among the rest = largest inverted keys; critical entries get
+  // key 0 and drop out
+  for (int j = lane; j < T; j += 64) keys[j] = (lab[j] == 1) ? 0u : ~keys[j];
+  __syncthreads();
+  mark_top(keys, lab, T, n_l, (int8_t)-1, lane);
+  __syncthreads();
+  int base = 0;
+  for (int j0 = 0; j0 < T; j0 += 64) {
+    const int j = j0 + lane;
+    const int8_t v = (j < T) ? lab[j] : (int8_t)0;
+    if (live && j < T) Mc[(size_t)row * T + j] = v;
+    const unsigned long long m = __ballot(v == 1);
+    if (live && v == 1) row_idx[(size_t)row * n_h + base + __popcll(m & ((1ull << lane) - 1ull))] = j;
+    base += __popcll(m);
+  }
+}
+
+// ---------------------------------------------------------------- column tables (CSC)
+__global__ void col_count_kernel(const int8_t* __restrict__ Mc, int T, int32_t* __restrict__ cnt) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x, bh = blockIdx.y;
+  if (j >= T) return;
+  const int8_t* m = Mc + (size_t)bh * T * T + j;
+  int c = 0;
+  for (int i = 0; i < T; ++i) c += (m[(size_t)i * T] == 1);
+  cnt[(size_t)bh * (T + 1) + j] = c;
+}
+
+// In-place exclusive scan of T counts per head -> T+1 pointers.
+__global__ __launch_bounds__(256) void col_scan_kernel(int32_t* __restrict__ ptr, int T) {
+  __shared__ int part[256];
+  int32_t* p = ptr + (size_t)blockIdx.x * (T + 1);
+  const int tid = threadIdx.x, chunk = (T + 255) / 256;
+  const int lo = min(T, tid * chunk), hi = min(T, lo + chunk);
+  int sum = 0;
+  for (int j = lo; j < hi; ++j) sum += p[j];
+  part[tid] = sum;
+  __syncthreads();
+  if (tid == 0) {
+    int run = 0;
+    for (int t = 0; t < 256; ++t) {
+      const int v = part[t];
+      part[t] = run;
+      run += v;
+    }
+    p[T] = run;
+  }
+  __syncthreads();
+  int run = part[tid];
+  for (int j = lo; j < hi; ++j) {
+    const int v = p[j];
+    p[j] = run;
+    run += v;
+  }
+}
+
+__global__ void col_fill_kernel(const int8_t* __restrict__ Mc, int T, int n_h,
+                                const int32_t* __restrict__ ptr, int32_t* __restrict__ rows) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x, bh = blockIdx.y;
+  if (j >= T) return;
+  const int8_t* m = Mc + (size_t)bh * T * T + j;
+  int32_t* out = rows + (size_t)bh * T * n_h;
+  int w = ptr[(size_t)bh * (T + 1) + j];
+  for (int i = 0; i < T; ++i)
+    if (m[(size_t)i * T] == 1) out[w++] = i;
+}
+
+}  // namespace
+
+hipError_t launch_pool(const void* X, const Shape& s, float* out, hipStream_t st) {
+  const int nblk = s.BH * s.T;
+  dim3 grid((nblk + 3) / 4), block(256);
+  if (s.dtype == 0) {
+    if (s.d == 64) pool_kernel<float, 1><<<grid, block, 0, st>>>((const float*)X, nblk, s.N, s.T, out);
+    else pool_kernel<float, 2><<<grid, block, 0, st>>>((const float*)X, nblk, s.N, s.T, out);
+  } else {
+    if (s.d == 64)
+      pool_kernel<__hip_bfloat16, 1><<<grid, block, 0, st>>>((const __hip_bfloat16*)X, nblk, s.N, s.T, out);
+    else
+      pool_kernel<__hip_bfloat16, 2><<<grid, block, 0, st>>>((const __hip_bfloat16*)X, nblk, s.N, s.T, out);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_scores(const float* qbar, const float* kbar, const Shape& s, float* scores,
+                         hipStream_t st) {
+  const int nt = (s.T + 63) / 64;
+  score_kernel<<<dim3(nt, nt, s.BH), 256, 0, st>>>(qbar, kbar, s.T, s.d, s.scale, scores);
+  return hipGetLastError();
+}
+
+hipError_t launch_classify(const float* scores, const Shape& s, int8_t* Mc, int32_t* row_idx,
+                           hipStream_t st) {
+  const int rows = s.BH * s.T;
+  const size_t lds = (size_t)4 * s.T * (sizeof(uint32_t) + 1);
+  classify_kernel<<<(rows + 3) / 4, 256, lds, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx);
+  return hipGetLastError();
+}
+
+hipError_t launch_csc(const int8_t* Mc, const Shape& s, int32_t* col_ptr, int32_t* col_rows,
+                      hipStream_t st) {
+  dim3 grid((s.T + 255) / 256, s.BH);
+  col_count_kernel<<<grid, 256, 0, st>>>(Mc, s.T, col_ptr);
+  col_scan_kernel<<<s.BH, 256, 0, st>>>(col_ptr, s.T);
+  if (s.n_h > 0) col_fill_kernel<<<grid, 256, 0, st>>>(Mc, s.T, s.n_h, col_ptr, col_rows);
+  return hipGetLastError();
+}
+
+}  // namespace sla

@@ -1,0 +1,65 @@
+// Internal declarations shared by the HIP translation units of the SLA library.
+#ifndef SLA_INTERNAL_H_
+#define SLA_INTERNAL_H_
+
+#include <hip/hip_bf16.h>
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sla {
+
+constexpr int kBlk = 64;  // b_q = b_kv (Section 6.1 hyper-parameters)
+
+// Shape of one call, derived on the host.
+struct Shape {
+  int BH, N, d, T, n_h, n_l, n_0;
+  int phi;    // 0 softmax over features, 1 elu+1
+  int dtype;  // 0 float, 1 bf16
+  float scale;  // float 1/sqrt(d)
+  __host__ __device__ int state_row() const { return d * d + d; }
+};
+
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(__hip_bfloat16 x) { return __bfloat162float(x); }
+__device__ __forceinline__ void from_f32(float& dst, float x) { dst = x; }
+__device__ __forceinline__ void from_f32(__hip_bfloat16& dst, float x) { dst = __float2bfloat16(x); }
+
+// ---- mask step (mask_kernels.hip)
+hipError_t launch_pool(const void* X, const Shape& s, float* out, hipStream_t st);
+hipError_t launch_scores(const float* qbar, const float* kbar, const Shape& s, float* scores,
+                         hipStream_t st);
+hipError_t launch_classify(const float* scores, const Shape& s, int8_t* Mc, int32_t* row_idx,
+                           hipStream_t st);
+hipError_t launch_csc(const int8_t* Mc, const Shape& s, int32_t* col_ptr, int32_t* col_rows,
+                      hipStream_t st);
+
+// ---- float-arithmetic path (simt_kernels.hip): every contraction in fp32 FMA
+struct FwdArgs {
+  const void *Q, *K, *V, *W;
+  const int8_t* Mc;
+  const int32_t* row_idx;
+  void* O;
+  void *Os, *Ol;   // may be null (inference)
+  float* L;        // may be null
+  float* HZ;       // [BH,T] state rows (saved or workspace)
+  float* hz;       // [BH,T] state rows of the key blocks (workspace)
+};
+hipError_t simt_forward(const Shape& s, const FwdArgs& a, hipStream_t st);
+
+struct BwdArgs {
+  const void *Q, *K, *V, *W, *dO;
+  const int8_t* Mc;
+  const int32_t *row_idx, *col_ptr, *col_rows;
+  const void *Os, *Ol;
+  const float *L, *HZ;
+  void *dQ, *dK, *dV;
+  float* dW;
+  char* ws;  // workspace, ws_backward_bytes
+};
+size_t simt_backward_ws_bytes(const Shape& s);
+hipError_t simt_backward(const Shape& s, const BwdArgs& a, hipStream_t st);
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+}  // namespace sla
+#endif

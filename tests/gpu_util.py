@@ -1,0 +1,53 @@
+"""Helpers for the GPU parity tests: upload seeded inputs, run the C-ABI path, fetch results."""
+import numpy as np
+import torch
+
+from paper_2509_24006_amd import binding as sla
+
+TOL = {"fp32": 1e-5, "bf16": 1e-2}   # relative L2, per tensor
+
+
+def to_dev(x: np.ndarray, dtype: str) -> torch.Tensor:
+    t = torch.from_numpy(np.ascontiguousarray(x, np.float32))
+    return t.to(torch.bfloat16 if dtype == "bf16" else torch.float32).cuda()
+
+
+def f64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+def run_gpu(x, dtype: str, k_h: float, k_l: float, phi: int = 0, backward: bool = True):
+    """x: dict of float32 arrays Q,K,V[,dO] [B,H,N,d] and Proj [d,d].  Runs mask, forward
+    and (optionally) backward through the C ABI and returns numpy results."""
+    B, H, N, d = x["Q"].shape
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    p = sla.make_params(B, H, N, d, k_h, k_l, tdt, phi)
+    Q, K, V = (to_dev(x[k], dtype) for k in ("Q", "K", "V"))
+    W = to_dev(x["Proj"], dtype)
+    Mc, luts, ws = sla.sla_build_mask(p, Q, K)
+    O, saved = sla.sla_forward(p, Q, K, V, W, Mc, luts)
+    torch.cuda.synchronize()
+    sv = sla.saved_views(p, saved)
+    out = {"Mc": Mc.cpu().numpy(), "O": f64(O)}
+    out.update({k: f64(v) for k, v in sv.items()})
+    out.update({k: v.cpu().numpy() for k, v in sla.mask_ws_views(p, ws).items()})
+    out.update({k: v.cpu().numpy() for k, v in sla.lut_views(p, luts).items()})
+    if backward:
+        dO = to_dev(x["dO"], dtype)
+        dQ, dK, dV, dW = sla.sla_backward(p, Q, K, V, W, Mc, luts, saved, dO)
+        torch.cuda.synchronize()
+        out.update({"dQ": f64(dQ), "dK": f64(dK), "dV": f64(dV), "dW": f64(dW)})
+    return out
+
+
+def check_luts(Mc: np.ndarray, row_idx: np.ndarray, col_ptr: np.ndarray, col_rows: np.ndarray):
+    B, H, T, _ = Mc.shape
+    for b in range(B):
+        for h in range(H):
+            crit = Mc[b, h] == 1
+            for i in range(T):
+                assert np.array_equal(row_idx[b, h, i], np.nonzero(crit[i])[0])
+            ptr = col_ptr[b, h]
+            assert ptr[0] == 0 and np.array_equal(np.diff(ptr), crit.sum(0))
+            for j in range(T):
+                assert np.array_equal(col_rows[b, h, ptr[j]:ptr[j + 1]], np.nonzero(crit[:, j])[0])

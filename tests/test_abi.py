@@ -1,0 +1,71 @@
+"""The C-ABI library loads, exports what include/sla.h declares, and rejects bad arguments
+before touching a device (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+from paper_2509_24006_amd import binding as sla
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_exports_match_header():
+    hdr = open(os.path.join(ROOT, "include", "sla.h")).read()
+    declared = set(re.findall(r"^(?:int|const char\*)\s+(sla_\w+)\s*\(", hdr, re.M))
+    assert declared == set(sla.EXPORTS)
+    L = sla.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_struct_layout_matches_header():
+    assert ctypes.sizeof(sla.sla_params) == 48
+    assert ctypes.sizeof(sla.sla_sizes_t) == 16 + 16 * 8
+
+
+def test_sizes_and_counts():
+    p = sla.make_params(1, 12, 32760, 128, 0.05, 0.10, torch.bfloat16)
+    z = sla.sla_sizes(p)
+    assert (z.T, z.n_h, z.n_l, z.n_0) == (512, 26, 51, 435)
+    assert z.mask_bytes == 12 * 512 * 512
+    p = sla.make_params(1, 40, 75600, 128, 0.05, 0.10, torch.bfloat16)
+    z = sla.sla_sizes(p)
+    assert (z.T, z.n_h, z.n_l, z.n_0) == (1182, 59, 118, 1005)
+    p = sla.make_params(1, 2, 1024, 64, 1.0, 0.1, torch.float32)
+    z = sla.sla_sizes(p)
+    assert (z.n_h, z.n_l, z.n_0) == (16, 0, 0)
+
+
+def test_counts_agree_with_oracle(oracle):
+    for N in (1, 64, 65, 1000, 32760, 75600):
+        for kh, kl in ((0.05, 0.1), (0.1, 0.1), (0.025, 0.1), (0.2, 0.1), (1.0, 0.0), (0.0, 0.0), (0.5, 0.5)):
+            z = sla.sla_sizes(sla.make_params(1, 1, N, 64, kh, kl, torch.float32))
+            assert (z.n_h, z.n_l) == oracle.counts(z.T, kh, kl)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(N=0), -1), (dict(k_h=1.5), -1), (dict(k_l=-0.1), -1), (dict(d=96), -2),
+    (dict(bq=128), -2), (dict(phi=7), -2), (dict(N=64 * 4000), -2),
+])
+def test_bad_params_are_rejected(kw, code):
+    base = dict(B=1, H=2, N=1024, d=64, bq=64, bkv=64, k_h=0.1, k_l=0.1, phi=0, dtype=0)
+    base.update(kw)
+    p = sla.sla_params(*[base[k] for k in ("B", "H", "N", "d", "bq", "bkv", "k_h", "k_l", "phi", "dtype")])
+    z = sla.sla_sizes_t()
+    assert sla.lib().sla_sizes(ctypes.byref(p), ctypes.byref(z)) == code
+    assert sla.lib().sla_build_mask(ctypes.byref(p), None, None, None, None, None, 0, None) == code
+
+
+def test_null_and_small_workspace_are_rejected():
+    p = sla.make_params(1, 2, 1024, 64, 0.1, 0.1, torch.float32)
+    L = sla.lib()
+    assert L.sla_build_mask(ctypes.byref(p), None, None, None, None, None, 0, None) == -1
+    fake = ctypes.c_void_p(4096)   # never dereferenced: the size check comes first
+    assert L.sla_build_mask(ctypes.byref(p), fake, fake, fake, fake, fake, 16, None) == -3
+    assert L.sla_forward(ctypes.byref(p), fake, fake, fake, fake, fake, fake, fake, None, fake, 16, None) == -3
+    assert L.sla_backward(ctypes.byref(p), *([fake] * 13), 16, None) == -3
+    assert L.sla_forward(ctypes.byref(p), ctypes.c_void_p(4097), fake, fake, fake, fake, fake, fake, None, fake, 1 << 40, None) == -1
+    assert b"workspace" in L.sla_strerror(-3)
