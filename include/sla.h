@@ -111,6 +111,13 @@ int sla_backward(const sla_params* p, const void* Q, const void* K, const void* 
                  void* dK, void* dV, float* dW, void* workspace, size_t workspace_bytes,
                  void* stream);
 
+/* Optional per-kernel timing for benchmarks.  While enabled, each kernel the library
+ * launches is bracketed by a pair of HIP events on the caller's stream.
+ * sla_profile_read waits for the recorded events, writes one line "name count total_ms"
+ * per kernel into buf (NUL-terminated) and forgets them.  Disabled by default. */
+int sla_profile_enable(int on);
+int sla_profile_read(char* buf, size_t buf_bytes);
+
 /* Static description of an error code. */
 const char* sla_strerror(int code);
 

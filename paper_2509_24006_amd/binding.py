@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libsla_hip.so")
 SLA_F32, SLA_BF16 = 0, 1
 SLA_PHI_SOFTMAX, SLA_PHI_ELU1 = 0, 1
 EXPORTS = ("sla_sizes", "sla_build_mask", "sla_classify_scores", "sla_forward", "sla_backward",
-           "sla_strerror")
+           "sla_profile_enable", "sla_profile_read", "sla_strerror")
 
 
 class sla_params(ctypes.Structure):
@@ -60,6 +60,8 @@ def lib() -> ctypes.CDLL:
         L.sla_classify_scores.argtypes = [pp, vp, vp, vp, vp]
         L.sla_forward.argtypes = [pp] + [vp] * 9 + [sz, vp]
         L.sla_backward.argtypes = [pp] + [vp] * 13 + [sz, vp]
+        L.sla_profile_enable.argtypes = [ctypes.c_int]
+        L.sla_profile_read.argtypes = [ctypes.c_char_p, sz]
         L.sla_strerror.argtypes = [ctypes.c_int]
         L.sla_strerror.restype = ctypes.c_char_p
         for n in EXPORTS[:-1]:
@@ -105,13 +107,16 @@ def _dense(t: torch.Tensor, p: sla_params, what: str) -> torch.Tensor:
 
 
 def sla_build_mask(p: sla_params, Q: torch.Tensor, K: torch.Tensor,
-                   workspace: Optional[torch.Tensor] = None
+                   workspace: Optional[torch.Tensor] = None, Mc: Optional[torch.Tensor] = None,
+                   luts: Optional[torch.Tensor] = None
                    ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
     """Returns (Mc int8 [B,H,T,T], luts, workspace); the workspace keeps pool(Q), pool(K), s."""
     z = sla_sizes(p)
     _dense(Q, p, "Q"); _dense(K, p, "K")
-    Mc = torch.empty((p.B, p.H, z.T, z.T), dtype=torch.int8, device=Q.device)
-    luts = _buf(z.luts_bytes, Q.device)
+    if Mc is None:
+        Mc = torch.empty((p.B, p.H, z.T, z.T), dtype=torch.int8, device=Q.device)
+    if luts is None:
+        luts = _buf(z.luts_bytes, Q.device)
     ws = workspace if workspace is not None else _buf(z.ws_mask_bytes, Q.device)
     _check(lib().sla_build_mask(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(Mc), _ptr(luts), _ptr(ws),
                                 ws.numel(), _stream()), "sla_build_mask")
@@ -161,6 +166,21 @@ def sla_backward(p: sla_params, Q, K, V, W, Mc, luts, saved, dO,
                               _ptr(luts), _ptr(saved), _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV),
                               _ptr(dW), _ptr(ws), ws.numel(), _stream()), "sla_backward")
     return dQ, dK, dV, dW
+
+
+def sla_profile_enable(on: bool) -> None:
+    _check(lib().sla_profile_enable(1 if on else 0), "sla_profile_enable")
+
+
+def sla_profile_read() -> Dict[str, Tuple[int, float]]:
+    """{kernel name: (launch count, total ms)} of the kernels timed since the last read."""
+    buf = ctypes.create_string_buffer(1 << 16)
+    _check(lib().sla_profile_read(buf, len(buf)), "sla_profile_read")
+    out = {}
+    for line in buf.value.decode().splitlines():
+        n, c, ms = line.split()
+        out[n] = (int(c), float(ms))
+    return out
 
 
 # ---- views into the opaque buffers (layout documented in include/sla.h)

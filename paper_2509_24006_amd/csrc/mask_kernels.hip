@@ -220,22 +220,25 @@ __global__ void col_fill_kernel(const int8_t* __restrict__ Mc, int T, int n_h,
 hipError_t launch_pool(const void* X, const Shape& s, float* out, hipStream_t st) {
   const int nblk = s.BH * s.T;
   dim3 grid((nblk + 3) / 4), block(256);
-  if (s.dtype == 0) {
-    if (s.d == 64) pool_kernel<float, 1><<<grid, block, 0, st>>>((const float*)X, nblk, s.N, s.T, out);
-    else pool_kernel<float, 2><<<grid, block, 0, st>>>((const float*)X, nblk, s.N, s.T, out);
-  } else {
-    if (s.d == 64)
-      pool_kernel<__hip_bfloat16, 1><<<grid, block, 0, st>>>((const __hip_bfloat16*)X, nblk, s.N, s.T, out);
-    else
-      pool_kernel<__hip_bfloat16, 2><<<grid, block, 0, st>>>((const __hip_bfloat16*)X, nblk, s.N, s.T, out);
-  }
+  KernelTimer kt("pool", st);
+  if (s.dtype == 0 && s.d == 64)
+    pool_kernel<float, 1><<<grid, block, 0, st>>>((const float*)X, nblk, s.N, s.T, out);
+  else if (s.dtype == 0)
+    pool_kernel<float, 2><<<grid, block, 0, st>>>((const float*)X, nblk, s.N, s.T, out);
+  else if (s.d == 64)
+    pool_kernel<__hip_bfloat16, 1><<<grid, block, 0, st>>>((const __hip_bfloat16*)X, nblk, s.N, s.T, out);
+  else
+    pool_kernel<__hip_bfloat16, 2><<<grid, block, 0, st>>>((const __hip_bfloat16*)X, nblk, s.N, s.T, out);
   return hipGetLastError();
 }
 
 hipError_t launch_scores(const float* qbar, const float* kbar, const Shape& s, float* scores,
                          hipStream_t st) {
   const int nt = (s.T + 63) / 64;
-  score_kernel<<<dim3(nt, nt, s.BH), 256, 0, st>>>(qbar, kbar, s.T, s.d, s.scale, scores);
+  {
+    KernelTimer kt("score", st);
+    score_kernel<<<dim3(nt, nt, s.BH), 256, 0, st>>>(qbar, kbar, s.T, s.d, s.scale, scores);
+  }
   return hipGetLastError();
 }
 
@@ -243,16 +246,28 @@ hipError_t launch_classify(const float* scores, const Shape& s, int8_t* Mc, int3
                            hipStream_t st) {
   const int rows = s.BH * s.T;
   const size_t lds = (size_t)4 * s.T * (sizeof(uint32_t) + 1);
-  classify_kernel<<<(rows + 3) / 4, 256, lds, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx);
+  {
+    KernelTimer kt("classify", st);
+    classify_kernel<<<(rows + 3) / 4, 256, lds, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx);
+  }
   return hipGetLastError();
 }
 
 hipError_t launch_csc(const int8_t* Mc, const Shape& s, int32_t* col_ptr, int32_t* col_rows,
                       hipStream_t st) {
   dim3 grid((s.T + 255) / 256, s.BH);
-  col_count_kernel<<<grid, 256, 0, st>>>(Mc, s.T, col_ptr);
-  col_scan_kernel<<<s.BH, 256, 0, st>>>(col_ptr, s.T);
-  if (s.n_h > 0) col_fill_kernel<<<grid, 256, 0, st>>>(Mc, s.T, s.n_h, col_ptr, col_rows);
+  {
+    KernelTimer kt("col_count", st);
+    col_count_kernel<<<grid, 256, 0, st>>>(Mc, s.T, col_ptr);
+  }
+  {
+    KernelTimer kt("col_scan", st);
+    col_scan_kernel<<<s.BH, 256, 0, st>>>(col_ptr, s.T);
+  }
+  if (s.n_h > 0) {
+    KernelTimer kt("col_fill", st);
+    col_fill_kernel<<<grid, 256, 0, st>>>(Mc, s.T, s.n_h, col_ptr, col_rows);
+  }
   return hipGetLastError();
 }
 

@@ -770,17 +770,29 @@ hipError_t forward_impl(const Shape& s, const FwdArgs& a, hipStream_t st) {
   if (s.n_0 > 0) {
     const size_t lds1 = sizeof(float) * 2 * kBlk * LD;
     SLA_TRY(set_lds(states_kernel<T, D>, lds1));
-    states_kernel<T, D><<<grid, kThreads, lds1, st>>>((const T*)a.K, (const T*)a.V, s.N, s.T, s.phi, a.hz);
-    aggregate_kernel<<<dim3((row_len + kThreads - 1) / kThreads, s.T, s.BH), kThreads, 0, st>>>(
+    {
+      KernelTimer kt("states", st);
+      states_kernel<T, D><<<grid, kThreads, lds1, st>>>((const T*)a.K, (const T*)a.V, s.N, s.T, s.phi, a.hz);
+    }
+    {
+      KernelTimer kt("aggregate", st);
+      aggregate_kernel<<<dim3((row_len + kThreads - 1) / kThreads, s.T, s.BH), kThreads, 0, st>>>(
         a.hz, a.Mc, s.T, row_len, 0, a.HZ);
+    }
   } else {
-    fill_zero_kernel<<<1024, 256, 0, st>>>(a.HZ, (size_t)s.BH * s.T * row_len);
+    {
+      KernelTimer kt("fill_zero", st);
+      fill_zero_kernel<<<1024, 256, 0, st>>>(a.HZ, (size_t)s.BH * s.T * row_len);
+    }
   }
   const size_t lds2 = sizeof(float) * (2 * kBlk * LD + kBlk * 65 + 64);
   SLA_TRY(set_lds(forward_kernel<T, D>, lds2));
-  forward_kernel<T, D><<<grid, kThreads, lds2, st>>>(
+  {
+    KernelTimer kt("forward", st);
+    forward_kernel<T, D><<<grid, kThreads, lds2, st>>>(
       (const T*)a.Q, (const T*)a.K, (const T*)a.V, (const T*)a.W, a.row_idx, a.HZ, s.N, s.T, s.n_h,
       s.n_0, s.phi, s.scale, (T*)a.O, (T*)a.Os, (T*)a.Ol, a.L);
+  }
   return hipGetLastError();
 }
 
@@ -824,36 +836,60 @@ hipError_t backward_impl(const Shape& s, const BwdArgs& a, hipStream_t st) {
   {
     const size_t lds = sizeof(float) * 2 * kBlk * LD;
     SLA_TRY(set_lds(bwd_prologue_kernel<T, D>, lds));
-    bwd_prologue_kernel<T, D><<<grid, kThreads, lds, st>>>((const T*)a.dO, (const T*)a.W, (const T*)a.Os,
+    {
+      KernelTimer kt("bwd_prologue", st);
+      bwd_prologue_kernel<T, D><<<grid, kThreads, lds, st>>>((const T*)a.dO, (const T*)a.W, (const T*)a.Os,
                                                           (const T*)a.Ol, s.N, w.dOl, w.Ds, w.Dl);
+    }
     SLA_TRY(set_lds(dw_partial_kernel<T, D>, lds));
-    dw_partial_kernel<T, D><<<w.nparts, kThreads, lds, st>>>((const T*)a.Ol, (const T*)a.dO, s.BH, s.N,
+    {
+      KernelTimer kt("dw_partial", st);
+      dw_partial_kernel<T, D><<<w.nparts, kThreads, lds, st>>>((const T*)a.Ol, (const T*)a.dO, s.BH, s.N,
                                                             s.T, w.dWpart);
-    dw_reduce_kernel<<<(D * D + 255) / 256, 256, 0, st>>>(w.dWpart, w.nparts, D * D, a.dW);
+    }
+    {
+      KernelTimer kt("dw_reduce", st);
+      dw_reduce_kernel<<<(D * D + 255) / 256, 256, 0, st>>>(w.dWpart, w.nparts, D * D, a.dW);
+    }
   }
   if (lin) {
     const size_t lds = sizeof(float) * (3 * kBlk * LD + 32 * LD + 64);
     SLA_TRY(set_lds(bwd_linear_q_kernel<T, D>, lds));
-    bwd_linear_q_kernel<T, D><<<grid, kThreads, lds, st>>>((const T*)a.Q, w.dOl, w.Dl, a.HZ, s.N, s.T,
+    {
+      KernelTimer kt("bwd_linear_q", st);
+      bwd_linear_q_kernel<T, D><<<grid, kThreads, lds, st>>>((const T*)a.Q, w.dOl, w.Dl, a.HZ, s.N, s.T,
                                                           s.phi, w.dHZ, w.dQlin);
-    aggregate_kernel<<<dim3((row_len + kThreads - 1) / kThreads, s.T, s.BH), kThreads, 0, st>>>(
+    }
+    {
+      KernelTimer kt("aggregate", st);
+      aggregate_kernel<<<dim3((row_len + kThreads - 1) / kThreads, s.T, s.BH), kThreads, 0, st>>>(
         w.dHZ, a.Mc, s.T, row_len, 1, w.dHZcol);
+    }
     const size_t lds2 = sizeof(float) * 4 * kBlk * LD;
     SLA_TRY(set_lds(bwd_linear_k_kernel<T, D>, lds2));
-    bwd_linear_k_kernel<T, D><<<grid, kThreads, lds2, st>>>((const T*)a.K, (const T*)a.V, w.dHZcol, s.N,
+    {
+      KernelTimer kt("bwd_linear_k", st);
+      bwd_linear_k_kernel<T, D><<<grid, kThreads, lds2, st>>>((const T*)a.K, (const T*)a.V, w.dHZcol, s.N,
                                                            s.T, s.phi, w.dKlin, w.dVlin);
+    }
   }
   {
     const size_t lds = sizeof(float) * (3 * kBlk * LD + 2 * kBlk * 65);
     SLA_TRY(set_lds(bwd_sparse_kv_kernel<T, D>, lds));
-    bwd_sparse_kv_kernel<T, D><<<grid, kThreads, lds, st>>>(
+    {
+      KernelTimer kt("bwd_sparse_kv", st);
+      bwd_sparse_kv_kernel<T, D><<<grid, kThreads, lds, st>>>(
         (const T*)a.Q, (const T*)a.K, (const T*)a.V, (const T*)a.dO, a.L, w.Ds, a.col_ptr, a.col_rows,
         lin ? w.dKlin : nullptr, lin ? w.dVlin : nullptr, s.N, s.T, s.n_h, s.scale, (T*)a.dK, (T*)a.dV);
+    }
     const size_t lds2 = sizeof(float) * (3 * kBlk * LD + kBlk * 65);
     SLA_TRY(set_lds(bwd_sparse_q_kernel<T, D>, lds2));
-    bwd_sparse_q_kernel<T, D><<<grid, kThreads, lds2, st>>>(
+    {
+      KernelTimer kt("bwd_sparse_q", st);
+      bwd_sparse_q_kernel<T, D><<<grid, kThreads, lds2, st>>>(
         (const T*)a.Q, (const T*)a.K, (const T*)a.V, (const T*)a.dO, a.L, w.Ds, a.row_idx,
         lin ? w.dQlin : nullptr, s.N, s.T, s.n_h, s.scale, (T*)a.dQ);
+    }
   }
   return hipGetLastError();
 }

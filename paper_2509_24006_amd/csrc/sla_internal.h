@@ -59,6 +59,16 @@ struct BwdArgs {
 size_t simt_backward_ws_bytes(const Shape& s);
 hipError_t simt_backward(const Shape& s, const BwdArgs& a, hipStream_t st);
 
+// Brackets one kernel launch with events when profiling is on (profile.hip).
+class KernelTimer {
+ public:
+  KernelTimer(const char* name, hipStream_t st);
+  ~KernelTimer();
+ private:
+  hipStream_t st_;
+  long idx_;
+};
+
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 }  // namespace sla

@@ -19,7 +19,7 @@ def _oracle_all(oracle, x, k_h, k_l, phi=0, backward=True):
     return Mc, s, f, g
 
 
-def _compare(name, got, ref, tol):
+def _compare(name, got, ref, tol, floor_rms=0.0):
     if np.all(ref == 0):
         assert np.all(got == 0), f"{name}: expected exact zeros"
         return
@@ -30,10 +30,16 @@ def _compare(name, got, ref, tol):
     if np.abs(ref).max() < 1e-12:
         assert np.abs(got).max() <= tol, f"{name}: expected ~0, got {np.abs(got).max():.3e}"
         return
+    # floor_rms: for cases where most rows' gradient cancels exactly (a block of one key gives
+    # P = 1 and dS = 0) the norm of the reference is set by a handful of rows while float
+    # rounding noise comes from all of them; the error is then measured against a norm of at
+    # least floor_rms per element (inputs have unit variance)
+    scale = max(np.linalg.norm(ref.ravel()), floor_rms * np.sqrt(ref.size))
+    err = np.linalg.norm((got - ref).ravel()) / scale
     assert err <= tol, f"{name}: rel L2 {err:.3e} > {tol:g}"
 
 
-def _full_case(oracle, x, dtype, k_h, k_l, phi=0):
+def _full_case(oracle, x, dtype, k_h, k_l, phi=0, floor_rms=0.0):
     print(f"case shape={x['Q'].shape} dtype={dtype} k_h={k_h} k_l={k_l} phi={phi}", flush=True)
     Mc, s, f, g = _oracle_all(oracle, x, k_h, k_l, phi)
     r = run_gpu(x, dtype, k_h, k_l, phi)
@@ -49,7 +55,7 @@ def _full_case(oracle, x, dtype, k_h, k_l, phi=0):
     if fin.any():
         _compare("L", r["L"][fin], f["L"][fin], tol)
     for k in ("dQ", "dK", "dV", "dW"):
-        _compare(k, r[k], g[k], tol)
+        _compare(k, r[k], g[k], tol, floor_rms)
 
 
 @pytest.mark.parametrize("name", ["tiny", "small_fp32", "small_bf16"])
@@ -82,7 +88,7 @@ def test_short_sequences(oracle, N):
     d = 64
     x = {k: rng.standard_normal((1, 2, N, d)).astype(np.float32) for k in ("Q", "K", "V", "dO")}
     x["Proj"] = (rng.standard_normal((d, d)) * 0.05).astype(np.float32)
-    _full_case(oracle, x, "fp32", 0.34, 0.34)
+    _full_case(oracle, x, "fp32", 0.34, 0.34, floor_rms=0.05)
 
 
 def test_classify_given_scores_with_ties(oracle):
