@@ -76,7 +76,9 @@ void fill_sizes(const Shape& s, sla_sizes_t* o) {
   o->ws_mask_scores = off;
   off += align_up(BH * T * T * 4);
   o->ws_mask_bytes = off;
-  o->ws_forward_bytes = 2 * state;
+  // [0, state): H_i, Z_i when the caller passes no `saved`; then the key-block states
+  const size_t hz_ws = s.dtype == SLA_BF16 ? mfma_forward_ws_bytes(s) : state;
+  o->ws_forward_bytes = state + hz_ws;
   o->ws_backward_bytes = simt_backward_ws_bytes(s);
 }
 
@@ -159,8 +161,10 @@ int sla_forward(const sla_params* p, const void* Q, const void* K, const void* V
   a.Os = sv ? sv + z.saved_Os : nullptr;
   a.Ol = sv ? sv + z.saved_Ol : nullptr;
   a.L = sv ? (float*)(sv + z.saved_L) : nullptr;
-  a.hz = (float*)ws;
-  a.HZ = sv ? (float*)(sv + z.saved_HZ) : (float*)(ws + z.ws_forward_bytes / 2);
+  const size_t state = z.saved_bytes - z.saved_HZ;
+  a.hz = (float*)(ws + state);
+  a.HZ = sv ? (float*)(sv + z.saved_HZ) : (float*)ws;
+  if (s.dtype == SLA_BF16) return hip_status(mfma_forward(s, a, ws + state, (hipStream_t)stream));
   return hip_status(simt_forward(s, a, (hipStream_t)stream));
 }
 

@@ -1,0 +1,98 @@
+// Device helpers for the bf16 matrix-core (MFMA) kernels on gfx950.
+//
+// One v_mfma_f32_32x32x16_bf16 multiplies A (32 x 16) by B (16 x 32) into C (32 x 32) per
+// wavefront.  Register layout, lane l = 32 g + n (g = l / 32, n = l % 32):
+//   A: lane holds row n,    eight k-values (slot s = 0..7) of k-group g
+//   B: lane holds column n, eight k-values (slot s) of k-group g
+//   C: lane holds column n, sixteen rows: register i -> row 8 (i / 4) + 4 g + (i % 4)
+// The contraction runs over all 16 (g, s) pairs, so any assignment of k-indices to (g, s)
+// gives the right product as long as A and B use the same one.  That freedom is what lets
+// a C tile be fed back as a B operand without shuffling: registers 8 u .. 8 u + 7 of a C
+// tile hold, for lane group g, the rows  16 u + {4g..4g+3} and 16 u + 8 + {4g..4g+3}.
+// An A operand that has to match stores its k-index in the permuted order perm16() below.
+#ifndef SLA_MFMA_COMMON_H_
+#define SLA_MFMA_COMMON_H_
+
+#include "sla_internal.h"
+
+namespace sla {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// row of C register i for lane group g
+__device__ __forceinline__ int c_row(int i, int g) { return ((i >> 2) << 3) + (g << 2) + (i & 3); }
+
+// Position, inside a run of 16 consecutive k-indices, at which index kk is stored so that
+// slots s = 0..7 of lane group g read positions 8 g + s and obtain the k-indices
+// {4g..4g+3, 8+4g..8+4g+3}, the rows a C tile hands to lane group g.
+__device__ __host__ __forceinline__ int perm16(int kk) {
+  const int a = (kk >> 3) & 1, gg = (kk >> 2) & 1, r = kk & 3;
+  return (gg << 3) + (a << 2) + r;
+}
+
+__device__ __forceinline__ bf16x8 zero_bf16x8() {
+  bf16x8 z;
+#pragma unroll
+  for (int s = 0; s < 8; ++s) z[s] = (__bf16)0.0f;
+  return z;
+}
+
+__device__ __forceinline__ f32x16 zero_f32x16() {
+  f32x16 z;
+#pragma unroll
+  for (int s = 0; s < 16; ++s) z[s] = 0.0f;
+  return z;
+}
+
+// eight consecutive floats -> bf16x8 (round to nearest even)
+__device__ __forceinline__ bf16x8 cvt8(const float* p) {
+  const f32x4 a = *reinterpret_cast<const f32x4*>(p);
+  const f32x4 b = *reinterpret_cast<const f32x4*>(p + 4);
+  bf16x8 r;
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    r[s] = (__bf16)a[s];
+    r[4 + s] = (__bf16)b[s];
+  }
+  return r;
+}
+
+// registers 8u..8u+7 of a C tile as a bf16 operand
+__device__ __forceinline__ bf16x8 c_to_operand(const f32x16& c, int u) {
+  bf16x8 r;
+#pragma unroll
+  for (int s = 0; s < 8; ++s) r[s] = (__bf16)c[8 * u + s];
+  return r;
+}
+
+// 4 x 4 transpose of bf16 held as four 8-byte rows: out[i] = (in[0][i], in[1][i], in[2][i], in[3][i])
+__device__ __forceinline__ void transpose4x4(const u32x2 (&in)[4], u32x2 (&out)[4]) {
+  // in[k].x = (e0, e1), in[k].y = (e2, e3) of key k
+  out[0].x = (in[0].x & 0xffffu) | (in[1].x << 16);
+  out[0].y = (in[2].x & 0xffffu) | (in[3].x << 16);
+  out[1].x = (in[0].x >> 16) | (in[1].x & 0xffff0000u);
+  out[1].y = (in[2].x >> 16) | (in[3].x & 0xffff0000u);
+  out[2].x = (in[0].y & 0xffffu) | (in[1].y << 16);
+  out[2].y = (in[2].y & 0xffffu) | (in[3].y << 16);
+  out[3].x = (in[0].y >> 16) | (in[1].y & 0xffff0000u);
+  out[3].y = (in[2].y >> 16) | (in[3].y & 0xffff0000u);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+}  // namespace sla
+#endif

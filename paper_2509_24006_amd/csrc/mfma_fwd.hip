@@ -1,0 +1,639 @@
+// bf16 matrix-core forward path of SLA on gfx950 (Algorithm 1 and Eq. 6):
+//   states_mfma     h_j = phi(K_j)^T V_j, z_j = rowsum(phi(K_j)^T)            (precompute line)
+//   aggregate_mfma  H_i = sum_{j marginal} h_j as a dense GEMM with the 0/1 indicator of
+//                   the marginal blocks (the accumulation line, batched over all rows)
+//   fwd_mfma        online-softmax attention over the critical blocks of a query block,
+//                   the closing line (O^s, L, O^l) and O = O^s + O^l W
+// All contractions run on v_mfma_f32_32x32x16_bf16 with float accumulation.
+#include "mfma_common.h"
+
+namespace sla {
+namespace {
+
+typedef __hip_bfloat16 bf16;
+
+// ------------------------------------------------------------------ W^T, k-permuted
+// WTp[e'][16 u + perm16(r)] = W[16 u + r][e']: the A operand of O^l W in the transposed
+// product (O^T = W^T (O^l)^T), whose B operand comes straight out of C registers.
+template <int D>
+__global__ void prep_w_kernel(const bf16* __restrict__ W, bf16* __restrict__ WTp) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= D * D) return;
+  const int e = idx / D, ep = idx - e * D;
+  WTp[ep * D + (e & ~15) + perm16(e & 15)] = W[idx];
+}
+
+// ------------------------------------------------------------------ transposing tile stage
+// Loads a 4-key x 4-feature patch (keys k4..k4+3, features f4..f4+3) of a row-major
+// [rows][D] bf16 tile and stores it transposed into an LDS tile laid out [feature][key
+// position], stride LDS elements per feature, at key position `pos` (4 consecutive).
+__device__ __forceinline__ void load_patch(const bf16* __restrict__ src, int D, int k4, int f4,
+                                           int rows_valid, u32x2 (&x)[4]) {
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    if (k4 + kk < rows_valid)
+      x[kk] = *reinterpret_cast<const u32x2*>(src + (size_t)(k4 + kk) * D + f4);
+    else
+      x[kk] = u32x2{0u, 0u};
+  }
+}
+
+__device__ __forceinline__ void store_patch_t(bf16* dst, int stride, int f4, int pos,
+                                              const u32x2 (&x)[4]) {
+  u32x2 y[4];
+  transpose4x4(x, y);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x2*>(dst + (f4 + i) * stride + pos) = y[i];
+}
+
+// key position of key group kg (keys 4kg..4kg+3) under perm16
+__device__ __forceinline__ int pos_of_kg(int kg) { return ((kg >> 2) << 4) + perm16((kg & 3) << 2); }
+
+// ------------------------------------------------------------------ key-block states
+constexpr int kVS = kBlk + 8;  // LDS stride (elements) of a transposed [feature][64 keys] tile
+
+template <int D>
+__global__ __launch_bounds__(256) void states_mfma_kernel(const bf16* __restrict__ K,
+                                                          const bf16* __restrict__ V, int N, int Tn,
+                                                          int phi, bf16* __restrict__ hz) {
+  constexpr int OS = D + 8;             // stride of the output staging tile
+  constexpr int NT = D / 32;            // 32-wide tiles per feature dimension
+  __shared__ __attribute__((aligned(16))) bf16 Kt[D * kVS];   // phi(K)^T  [c][key pos]
+  __shared__ __attribute__((aligned(16))) bf16 Vt[D * kVS];   // V^T       [e][key pos]
+  __shared__ __attribute__((aligned(16))) bf16 Out[D * OS];   // h^T       [e][c]
+  __shared__ float stat_m[kBlk], stat_inv[kBlk];
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
+  const int j = blockIdx.x, bh = blockIdx.y;
+  const int n0 = j * kBlk, cnt = min(kBlk, N - n0);
+  const bf16* Kb = K + ((size_t)bh * N + n0) * D;
+  const bf16* Vb = V + ((size_t)bh * N + n0) * D;
+  // pass 1: softmax statistics of each key row (four threads per row)
+  if (phi == 0) {
+    const int row = tid >> 2, part = tid & 3;
+    float mx = -INFINITY, sum = 0.0f;
+    float v[D / 4];
+    if (row < cnt) {
+#pragma unroll
+      for (int c8 = 0; c8 < D / 32; ++c8) {
+        const bf16x8 x = *reinterpret_cast<const bf16x8*>(Kb + (size_t)row * D + part * (D / 4) + 8 * c8);
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+          v[8 * c8 + s] = (float)x[s];
+          mx = fmaxf(mx, v[8 * c8 + s]);
+        }
+      }
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 1, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 2, 64));
+    if (row < cnt) {
+#pragma unroll
+      for (int c = 0; c < D / 4; ++c) sum += fast_exp2((v[c] - mx) * kLog2e);
+    }
+    sum += __shfl_xor(sum, 1, 64);
+    sum += __shfl_xor(sum, 2, 64);
+    if (part == 0) {
+      stat_m[row] = row < cnt ? mx : 0.0f;
+      stat_inv[row] = row < cnt ? 1.0f / sum : 0.0f;
+    }
+  }
+  __syncthreads();
+  // pass 2: transposing stage of phi(K) and V
+  constexpr int UNITS = 16 * (D / 4);
+#pragma unroll
+  for (int r = 0; r < UNITS / 256; ++r) {
+    const int u = tid + 256 * r;
+    const int fg = u % (D / 4), kg = u / (D / 4);
+    u32x2 x[4];
+    load_patch(Vb, D, 4 * kg, 4 * fg, cnt, x);
+    store_patch_t(Vt, kVS, 4 * fg, pos_of_kg(kg), x);
+    load_patch(Kb, D, 4 * kg, 4 * fg, cnt, x);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const int key = 4 * kg + kk;
+      const bool ok = key < cnt;
+      float f[4];
+      f[0] = __uint_as_float(x[kk].x << 16);
+      f[1] = __uint_as_float(x[kk].x & 0xffff0000u);
+      f[2] = __uint_as_float(x[kk].y << 16);
+      f[3] = __uint_as_float(x[kk].y & 0xffff0000u);
+      if (phi == 0) {
+        const float m = stat_m[key], inv = stat_inv[key];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) f[i] = fast_exp2((f[i] - m) * kLog2e) * inv;
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) f[i] = f[i] > 0.0f ? f[i] + 1.0f : fast_exp2(f[i] * kLog2e);
+      }
+      bf16x4 pk;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) pk[i] = (__bf16)(ok ? f[i] : 0.0f);
+      x[kk] = *reinterpret_cast<u32x2*>(&pk);
+    }
+    store_patch_t(Kt, kVS, 4 * fg, pos_of_kg(kg), x);
+  }
+  __syncthreads();
+  // h^T[e][c] = sum_keys V[key][e] phi(K)[key][c]; wave w owns e-tiles w, w+4, ...
+  bf16x8 ones;
+#pragma unroll
+  for (int s = 0; s < 8; ++s) ones[s] = (__bf16)1.0f;
+  for (int et = w; et < NT; et += 4) {
+    f32x16 acc[NT];
+#pragma unroll
+    for (int ct = 0; ct < NT; ++ct) acc[ct] = zero_f32x16();
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(Vt + (32 * et + ln) * kVS + 16 * t + 8 * g);
+#pragma unroll
+      for (int ct = 0; ct < NT; ++ct) {
+        const bf16x8 b = *reinterpret_cast<const bf16x8*>(Kt + (32 * ct + ln) * kVS + 16 * t + 8 * g);
+        acc[ct] = mfma32(a, b, acc[ct]);
+      }
+    }
+#pragma unroll
+    for (int ct = 0; ct < NT; ++ct)
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        Out[(32 * et + c_row(i, g)) * OS + 32 * ct + ln] = __float2bfloat16(acc[ct][i]);
+  }
+  bf16* out = hz + ((size_t)bh * Tn + j) * (D * D + D);
+  // z[c] = sum_keys phi(K)[key][c]: a ones operand against c-tile w
+  if (w < NT) {
+    f32x16 zc = zero_f32x16();
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const bf16x8 b = *reinterpret_cast<const bf16x8*>(Kt + (32 * w + ln) * kVS + 16 * t + 8 * g);
+      zc = mfma32(ones, b, zc);
+    }
+    if (g == 0) out[(size_t)D * D + 32 * w + ln] = __float2bfloat16(zc[0]);
+  }
+  __syncthreads();
+  for (int idx = tid; idx < D * (D / 8); idx += 256) {
+    const int e = idx / (D / 8), c8 = idx - e * (D / 8);
+    *reinterpret_cast<u32x4*>(out + (size_t)e * D + 8 * c8) =
+        *reinterpret_cast<const u32x4*>(Out + e * OS + 8 * c8);
+  }
+}
+
+// ------------------------------------------------------------------ state aggregation GEMM
+// out[i][col] = sum_k ind(i, k) in[k][col], ind(i, k) = (M[i][k] == 0), for one head:
+// a T x T by T x row_len product.  M is the mask (rows = query blocks) for H_i, Z_i, or its
+// transpose for the column sums of the backward pass.  Workgroup tile 256 x 128, k-step 32;
+// the indicator operand is built in registers from the int8 mask, the state operand is
+// staged transposed through LDS (double-buffered).
+constexpr int kAggBS = 32 + 8;  // LDS stride of the [col][32 k] tile
+
+__global__ __launch_bounds__(256) void aggregate_mfma_kernel(const bf16* __restrict__ in,
+                                                             const int8_t* __restrict__ M, int T,
+                                                             int row_len,
+                                                             float* __restrict__ out) {
+  __shared__ __attribute__((aligned(16))) bf16 Bt[2][128 * kAggBS];
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
+  const int n0 = blockIdx.x * 128, m0 = blockIdx.y * 256, bh = blockIdx.z;
+  const int8_t* Mb = M + (size_t)bh * T * T;
+  const bf16* inb = in + (size_t)bh * T * row_len;
+  f32x16 acc[2][4];
+#pragma unroll
+  for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = zero_f32x16();
+  // staging patch of this thread: 4 k-rows x 4 columns
+  const int fg = tid & 31, kg = tid >> 5;             // columns 4fg.., k-rows 4kg..
+  const int ksteps = (T + 31) / 32;
+  auto stage = [&](int ks, int buf) {
+    u32x2 x[4];
+    const int k0 = ks * 32 + 4 * kg;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      if (k0 + kk < T && n0 + 4 * fg + 3 < row_len)
+        x[kk] = *reinterpret_cast<const u32x2*>(inb + (size_t)(k0 + kk) * row_len + n0 + 4 * fg);
+      else
+        x[kk] = u32x2{0u, 0u};
+    }
+    store_patch_t(Bt[buf], kAggBS, 4 * fg, 4 * kg, x);
+  };
+  stage(0, 0);
+  __syncthreads();
+  for (int ks = 0; ks < ksteps; ++ks) {
+    const int buf = ks & 1;
+    if (ks + 1 < ksteps) stage(ks + 1, buf ^ 1);
+    // indicator operand: rows m0 + 64 w + 32 mt + ln, k = 32 ks + 16 tt + 8 g + s
+    bf16x8 a[2][2];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+      const int i = m0 + 64 * w + 32 * mt + ln;
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        const int k = 32 * ks + 16 * tt + 8 * g;
+        unsigned long long bytes = 0x0101010101010101ull;   // non-zero labels: indicator 0
+        if (i < T && k < T) {
+          if (k + 8 <= T && (T & 7) == 0) {
+            bytes = *reinterpret_cast<const unsigned long long*>(Mb + (size_t)i * T + k);
+          } else {
+            bytes = 0;
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+              const unsigned long long v = (k + s < T) ? (unsigned char)Mb[(size_t)i * T + k + s] : 1u;
+              bytes |= v << (8 * s);
+            }
+          }
+        }
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+          a[mt][tt][s] = (__bf16)((((bytes >> (8 * s)) & 0xffull) == 0ull) ? 1.0f : 0.0f);
+      }
+    }
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt) {
+        const bf16x8 b =
+            *reinterpret_cast<const bf16x8*>(Bt[buf] + (32 * nt + ln) * kAggBS + 16 * tt + 8 * g);
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) acc[mt][nt] = mfma32(a[mt][tt], b, acc[mt][nt]);
+      }
+    __syncthreads();
+  }
+  float* outb = out + (size_t)bh * T * row_len;
+#pragma unroll
+  for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) {
+      const int col = n0 + 32 * nt + ln;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int row = m0 + 64 * w + 32 * mt + c_row(i, g);
+        if (row < T && col < row_len) outb[(size_t)row * row_len + col] = acc[mt][nt][i];
+      }
+    }
+}
+
+// ------------------------------------------------------------------ forward main kernel
+// One workgroup (4 wavefronts) per query block.  Wavefront (qh, par): qh = which 32 of the 64
+// query rows, par = which of the two key tiles of a step.  Everything is held transposed
+// (S^T = K Q^T, O^T = V^T P^T) so that each lane owns one query: softmax statistics are
+// per-lane scalars and P goes from C registers straight into the B operand of the second
+// product.
+template <int D>
+struct FwdLds {
+  static constexpr int KS = D + 8;                       // K tile row stride (elements)
+  static constexpr int K_ELEMS = 2 * kBlk * KS;          // two K tiles
+  static constexpr int V_ELEMS = 2 * D * kVS;            // two transposed V tiles
+  static constexpr int XCH_BYTES = 2 * (D / 2) * 64 * 4; // exchange of C registers between par 0/1
+  static constexpr int TILE_BYTES = (K_ELEMS + V_ELEMS) * 2;
+  static constexpr int BYTES = (TILE_BYTES > XCH_BYTES ? TILE_BYTES : XCH_BYTES) + 1024;
+};
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
+    const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
+    const bf16* __restrict__ WTp, const int32_t* __restrict__ row_idx, const float* __restrict__ HZ,
+    int N, int Tn, int n_h, int n_0, int phi, float scale_log2e, bf16* __restrict__ O,
+    bf16* __restrict__ Os, bf16* __restrict__ Ol, float* __restrict__ L) {
+  using Lds = FwdLds<D>;
+  constexpr int KS = Lds::KS, NT = D / 32, KT = D / 16;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16* Ks = reinterpret_cast<bf16*>(smem);
+  bf16* Vt = Ks + Lds::K_ELEMS;
+  float* xch = reinterpret_cast<float*>(smem);
+  float* ml = reinterpret_cast<float*>(smem + Lds::BYTES - 1024);   // [par][qh][32][2]
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
+  const int qh = w & 1, par = w >> 1;
+  const int i = blockIdx.x, bh = blockIdx.y;
+  const int q0 = i * kBlk, rows = min(kBlk, N - q0);
+  const int qrow = qh * 32 + ln;                  // this lane's query inside the block
+  const bool qok = qrow < rows;
+  const size_t qoff = ((size_t)bh * N + q0 + qrow) * D;
+  bf16x8 qf[KT];
+#pragma unroll
+  for (int t = 0; t < KT; ++t)
+    qf[t] = qok ? *reinterpret_cast<const bf16x8*>(Q + qoff + 16 * t + 8 * g) : zero_bf16x8();
+  f32x16 oT[NT];
+#pragma unroll
+  for (int et = 0; et < NT; ++et) oT[et] = zero_f32x16();
+  float m = -INFINITY, lsum = 0.0f;
+  const int32_t* lut = row_idx + ((size_t)bh * Tn + i) * n_h;
+  const bf16* Kb = K + (size_t)bh * N * D;
+  const bf16* Vb = V + (size_t)bh * N * D;
+  const int steps = (n_h + 1) >> 1;
+  for (int s = 0; s < steps; ++s) {
+    const int j0 = lut[2 * s];
+    const bool two = 2 * s + 1 < n_h;
+    const int j1 = two ? lut[2 * s + 1] : j0;
+    // ---- global loads of both K tiles and both V tiles (V patches stay in registers)
+    constexpr int KCH = 2 * kBlk * (D / 8) / 256;   // 16-byte chunks per thread
+    u32x4 kreg[KCH];
+#pragma unroll
+    for (int r = 0; r < KCH; ++r) {
+      const int c = tid + 256 * r;
+      const int p = c / (kBlk * (D / 8)), cc = c - p * (kBlk * (D / 8));
+      const int row = cc / (D / 8), c8 = cc - row * (D / 8);
+      const int jj = p ? j1 : j0;
+      const int cols = min(kBlk, N - jj * kBlk);
+      if (row < cols && (p == 0 || two))
+        kreg[r] = *reinterpret_cast<const u32x4*>(Kb + ((size_t)jj * kBlk + row) * D + 8 * c8);
+      else
+        kreg[r] = u32x4{0u, 0u, 0u, 0u};
+    }
+    constexpr int VU = 2 * 16 * (D / 4) / 256;      // 4x4 patches per thread
+    u32x2 vreg[VU][4];
+#pragma unroll
+    for (int r = 0; r < VU; ++r) {
+      const int u = tid + 256 * r;
+      const int p = u / (16 * (D / 4)), uu = u - p * (16 * (D / 4));
+      const int fg = uu % (D / 4), kg = uu / (D / 4);
+      const int jj = p ? j1 : j0;
+      const int cols = (p == 0 || two) ? min(kBlk, N - jj * kBlk) : 0;
+      load_patch(Vb + (size_t)jj * kBlk * D, D, 4 * kg, 4 * fg, cols, vreg[r]);
+    }
+#pragma unroll
+    for (int r = 0; r < KCH; ++r) {
+      const int c = tid + 256 * r;
+      const int p = c / (kBlk * (D / 8)), cc = c - p * (kBlk * (D / 8));
+      const int row = cc / (D / 8), c8 = cc - row * (D / 8);
+      *reinterpret_cast<u32x4*>(Ks + (p * kBlk + row) * KS + 8 * c8) = kreg[r];
+    }
+    __syncthreads();   // K tiles visible; every wave is past the previous step's P V
+    const bool active = par == 0 || two;
+    const int jmine = par ? j1 : j0;
+    const int cols = min(kBlk, N - jmine * kBlk);
+    f32x16 sT[2];
+    if (active) {
+      sT[0] = zero_f32x16();
+      sT[1] = zero_f32x16();
+#pragma unroll
+      for (int t = 0; t < KT; ++t) {
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+          const bf16x8 a = *reinterpret_cast<const bf16x8*>(Ks + (par * kBlk + 32 * mt + ln) * KS + 16 * t + 8 * g);
+          sT[mt] = mfma32(a, qf[t], sT[mt]);
+        }
+      }
+    }
+    // ---- V tiles into LDS, transposed (previous step's readers are behind the barrier above)
+#pragma unroll
+    for (int r = 0; r < VU; ++r) {
+      const int u = tid + 256 * r;
+      const int p = u / (16 * (D / 4)), uu = u - p * (16 * (D / 4));
+      const int fg = uu % (D / 4), kg = uu / (D / 4);
+      store_patch_t(Vt + p * D * kVS, kVS, 4 * fg, pos_of_kg(kg), vreg[r]);
+    }
+    bf16x8 pf[4];
+    if (active) {
+      // ---- online softmax in the exp2 domain; one query per lane
+      float mx = -INFINITY;
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = 32 * mt + c_row(r, g);
+          const float v = key < cols ? sT[mt][r] * scale_log2e : -INFINITY;
+          sT[mt][r] = v;
+          mx = fmaxf(mx, v);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float mnew = fmaxf(m, mx);
+      const float alpha = fast_exp2(m - mnew);
+      float psum = 0.0f;
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float pv = fast_exp2(sT[mt][r] - mnew);
+          sT[mt][r] = pv;
+          psum += pv;
+        }
+      lsum = lsum * alpha + psum;
+      m = mnew;
+#pragma unroll
+      for (int et = 0; et < NT; ++et)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oT[et][r] *= alpha;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) pf[t] = c_to_operand(sT[t >> 1], t & 1);
+    }
+    __syncthreads();   // V tiles visible
+    if (active) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int et = 0; et < NT; ++et) {
+          const bf16x8 a = *reinterpret_cast<const bf16x8*>(Vt + (par * D + 32 * et + ln) * kVS + 16 * t + 8 * g);
+          oT[et] = mfma32(a, pf[t], oT[et]);
+        }
+    }
+  }
+  // ---- merge the two key-tile streams (par 0 / par 1) of each query half
+  lsum += __shfl_xor(lsum, 32, 64);
+  if (g == 0) {
+    ml[((par * 2 + qh) * 32 + ln) * 2 + 0] = m;
+    ml[((par * 2 + qh) * 32 + ln) * 2 + 1] = lsum;
+  }
+  __syncthreads();   // also: all waves are done with the K / V tiles
+  const float m_o = ml[(((par ^ 1) * 2 + qh) * 32 + ln) * 2 + 0];
+  const float l_o = ml[(((par ^ 1) * 2 + qh) * 32 + ln) * 2 + 1];
+  float cw = 0.0f, Lval = -INFINITY;
+  if (n_h > 0) {
+    const float mstar = fmaxf(m, m_o);
+    const float a_me = fast_exp2(m - mstar), a_ot = fast_exp2(m_o - mstar);
+    const float ltot = lsum * a_me + l_o * a_ot;
+    cw = a_me / ltot;
+    Lval = mstar * kLn2 + logf(ltot);
+  }
+#pragma unroll
+  for (int et = 0; et < NT; ++et)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oT[et][r] *= cw;
+  float* myx = xch + (size_t)qh * (D / 2) * 64;
+  if (par == 1) {
+#pragma unroll
+    for (int et = 0; et < NT; ++et)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) myx[(et * 16 + r) * 64 + l] = oT[et][r];
+  }
+  __syncthreads();
+  const size_t orow = ((size_t)bh * N + q0 + qrow) * D;
+  if (par == 0) {
+#pragma unroll
+    for (int et = 0; et < NT; ++et)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oT[et][r] += myx[(et * 16 + r) * 64 + l];
+    if (L && g == 0 && qok) L[(size_t)bh * N + q0 + qrow] = Lval;
+    if (Os && qok) {
+#pragma unroll
+      for (int et = 0; et < NT; ++et)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          bf16x4 pk;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) pk[r] = (__bf16)oT[et][4 * r4 + r];
+          *reinterpret_cast<bf16x4*>(Os + orow + 32 * et + 8 * r4 + 4 * g) = pk;
+        }
+    }
+  }
+  // ---- linear branch: wave par computes O^l for features [par D/2, (par+1) D/2) of its queries
+  // (both waves accumulate their share of O^l W into oT; par 1 starts again from zero)
+  if (par == 1) {
+#pragma unroll
+    for (int et = 0; et < NT; ++et) oT[et] = zero_f32x16();
+  }
+  if (n_0 > 0) {
+    // phi(Q) of this lane's query: the lane holds features 16 t + 8 g + s, its partner the rest
+    float qmx = 0.0f, qinv = 1.0f;
+    if (phi == 0) {
+      qmx = -INFINITY;
+#pragma unroll
+      for (int t = 0; t < KT; ++t)
+#pragma unroll
+        for (int s2 = 0; s2 < 8; ++s2) qmx = fmaxf(qmx, (float)qf[t][s2]);
+      qmx = fmaxf(qmx, __shfl_xor(qmx, 32, 64));
+      float sum = 0.0f;
+#pragma unroll
+      for (int t = 0; t < KT; ++t)
+#pragma unroll
+        for (int s2 = 0; s2 < 8; ++s2) sum += fast_exp2(((float)qf[t][s2] - qmx) * kLog2e);
+      sum += __shfl_xor(sum, 32, 64);
+      qinv = 1.0f / sum;
+    }
+    const float* Hrow = HZ + ((size_t)bh * Tn + i) * (D * D + D);
+    const float* Z = Hrow + D * D;
+    bf16x8 qp[KT];
+    float den = 0.0f;
+#pragma unroll
+    for (int t = 0; t < KT; ++t) {
+      const f32x4 z0 = *reinterpret_cast<const f32x4*>(Z + 16 * t + 8 * g);
+      const f32x4 z1 = *reinterpret_cast<const f32x4*>(Z + 16 * t + 8 * g + 4);
+#pragma unroll
+      for (int s2 = 0; s2 < 8; ++s2) {
+        const float x = (float)qf[t][s2];
+        const float y = phi == 0 ? fast_exp2((x - qmx) * kLog2e) * qinv
+                                 : (x > 0.0f ? x + 1.0f : fast_exp2(x * kLog2e));
+        qp[t][s2] = (__bf16)y;
+        den = fmaf((float)qp[t][s2], s2 < 4 ? z0[s2] : z1[s2 - 4], den);
+      }
+    }
+    den += __shfl_xor(den, 32, 64);
+    const float dinv = 1.0f / den;
+    constexpr int HT = NT / 2;     // e-tiles per wave
+#pragma unroll
+    for (int h2 = 0; h2 < HT; ++h2) {
+      const int et = par * HT + h2;
+      f32x16 acc = zero_f32x16();
+#pragma unroll
+      for (int t = 0; t < KT; ++t) {
+        const bf16x8 a = cvt8(Hrow + (size_t)(32 * et + ln) * D + 16 * t + 8 * g);
+        acc = mfma32(a, qp[t], acc);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[r] *= dinv;
+      if (Ol && qok) {
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          bf16x4 pk;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) pk[r] = (__bf16)acc[4 * r4 + r];
+          *reinterpret_cast<bf16x4*>(Ol + orow + 32 * et + 8 * r4 + 4 * g) = pk;
+        }
+      }
+      // O^T[e'][q] += sum_{e in this tile} W[e][e'] O^l[q][e]
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const bf16x8 b = c_to_operand(acc, u);
+#pragma unroll
+        for (int ep = 0; ep < NT; ++ep) {
+          const bf16x8 a = *reinterpret_cast<const bf16x8*>(WTp + (size_t)(32 * ep + ln) * D + 32 * et + 16 * u + 8 * g);
+          oT[ep] = mfma32(a, b, oT[ep]);
+        }
+      }
+    }
+    __syncthreads();   // par 0 has consumed the first exchange
+    if (par == 1) {
+#pragma unroll
+      for (int et = 0; et < NT; ++et)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) myx[(et * 16 + r) * 64 + l] = oT[et][r];
+    }
+    __syncthreads();
+    if (par == 0) {
+#pragma unroll
+      for (int et = 0; et < NT; ++et)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oT[et][r] += myx[(et * 16 + r) * 64 + l];
+    }
+  }
+  if (par == 0 && qok) {
+#pragma unroll
+    for (int et = 0; et < NT; ++et)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        bf16x4 pk;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) pk[r] = (__bf16)oT[et][4 * r4 + r];
+        *reinterpret_cast<bf16x4*>(O + orow + 32 * et + 8 * r4 + 4 * g) = pk;
+        if (n_0 == 0 && Ol) {   // no marginal block: O^l is identically zero
+          bf16x4 zz;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) zz[r] = (__bf16)0.0f;
+          *reinterpret_cast<bf16x4*>(Ol + orow + 32 * et + 8 * r4 + 4 * g) = zz;
+        }
+      }
+  }
+}
+
+__global__ void fill_zero_f32_kernel(float* __restrict__ p, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+    p[i] = 0.0f;
+}
+
+#define SLA_TRY(x)                   \
+  do {                               \
+    hipError_t e_ = (x);             \
+    if (e_ != hipSuccess) return e_; \
+  } while (0)
+
+template <int D>
+hipError_t forward_impl(const Shape& s, const FwdArgs& a, bf16* hz16, bf16* WTp, hipStream_t st) {
+  const int row_len = s.state_row();
+  if (s.n_0 > 0) {
+    {
+      KernelTimer kt("prep_w", st);
+      prep_w_kernel<D><<<(D * D + 255) / 256, 256, 0, st>>>((const bf16*)a.W, WTp);
+    }
+    {
+      KernelTimer kt("states", st);
+      states_mfma_kernel<D><<<dim3(s.T, s.BH), 256, 0, st>>>((const bf16*)a.K, (const bf16*)a.V, s.N, s.T,
+                                                           s.phi, hz16);
+    }
+    {
+      KernelTimer kt("aggregate", st);
+      aggregate_mfma_kernel<<<dim3((row_len + 127) / 128, (s.T + 255) / 256, s.BH), 256, 0, st>>>(
+          hz16, a.Mc, s.T, row_len, a.HZ);
+    }
+  } else if (a.Os) {   // saved states must read as zero
+    KernelTimer kt("fill_zero", st);
+    fill_zero_f32_kernel<<<1024, 256, 0, st>>>(a.HZ, (size_t)s.BH * s.T * row_len);
+  }
+  constexpr int lds = FwdLds<D>::BYTES;
+  SLA_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_mfma_kernel<D>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+  {
+    KernelTimer kt("fwd_sparse", st);
+    fwd_mfma_kernel<D><<<dim3(s.T, s.BH), 256, lds, st>>>(
+        (const bf16*)a.Q, (const bf16*)a.K, (const bf16*)a.V, WTp, a.row_idx, a.HZ, s.N, s.T, s.n_h,
+        s.n_0, s.phi, s.scale * kLog2e, (bf16*)a.O, (bf16*)a.Os, (bf16*)a.Ol, a.L);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace
+
+size_t mfma_forward_ws_bytes(const Shape& s) {
+  return align_up((size_t)s.BH * s.T * s.state_row() * 2) + align_up((size_t)s.d * s.d * 2);
+}
+
+hipError_t mfma_forward(const Shape& s, const FwdArgs& a, char* ws, hipStream_t st) {
+  bf16* hz16 = reinterpret_cast<bf16*>(ws);
+  bf16* WTp = reinterpret_cast<bf16*>(ws + align_up((size_t)s.BH * s.T * s.state_row() * 2));
+  return s.d == 64 ? forward_impl<64>(s, a, hz16, WTp, st) : forward_impl<128>(s, a, hz16, WTp, st);
+}
+
+}  // namespace sla

@@ -59,6 +59,10 @@ struct BwdArgs {
 size_t simt_backward_ws_bytes(const Shape& s);
 hipError_t simt_backward(const Shape& s, const BwdArgs& a, hipStream_t st);
 
+// ---- bf16 matrix-core path (mfma_fwd.hip)
+size_t mfma_forward_ws_bytes(const Shape& s);
+hipError_t mfma_forward(const Shape& s, const FwdArgs& a, char* ws, hipStream_t st);
+
 // Brackets one kernel launch with events when profiling is on (profile.hip).
 class KernelTimer {
  public:

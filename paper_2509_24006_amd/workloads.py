@@ -67,6 +67,8 @@ WORKLOADS: Dict[str, Workload] = {
     # reduced-size relatives used by the parity tests (ragged tails, several tiles)
     "small_bf16": Workload("small_bf16", 1, 2, 128, (3, 10, 37), "bf16", 0.10, 0.10,
                            seed=BASE_SEED + 11),
+    "small_bf16_d64": Workload("small_bf16_d64", 1, 3, 64, (2, 11, 41), "bf16", 0.12, 0.15,
+                               seed=BASE_SEED + 13),
     "small_fp32": Workload("small_fp32", 2, 2, 64, (2, 9, 29), "fp32", 0.15, 0.20,
                            v_white=True, unit_var=False, seed=BASE_SEED + 12),
 }

@@ -58,7 +58,7 @@ def _full_case(oracle, x, dtype, k_h, k_l, phi=0, floor_rms=0.0):
         _compare(k, r[k], g[k], tol, floor_rms)
 
 
-@pytest.mark.parametrize("name", ["tiny", "small_fp32", "small_bf16"])
+@pytest.mark.parametrize("name", ["tiny", "small_fp32", "small_bf16", "small_bf16_d64"])
 def test_workload_parity(oracle, name):
     w = wl.WORKLOADS[name]
     x = wl.make_inputs(w)
@@ -66,7 +66,7 @@ def test_workload_parity(oracle, name):
 
 
 @pytest.mark.parametrize("k_h,k_l", [(1.0, 0.1), (0.0, 0.0), (0.0, 0.3), (0.4, 0.6), (0.05, 0.9)])
-@pytest.mark.parametrize("name", ["small_fp32", "small_bf16"])
+@pytest.mark.parametrize("name", ["small_fp32", "small_bf16", "small_bf16_d64"])
 def test_degenerate_masks(oracle, name, k_h, k_l):
     # all critical (dense attention), all marginal (linear attention), no critical block,
     # no marginal block
