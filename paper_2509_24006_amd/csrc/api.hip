@@ -56,6 +56,8 @@ void fill_sizes(const Shape& s, sla_sizes_t* o) {
   off += align_up(BH * (T + 1) * 4);
   o->lut_col_rows = off;
   off += align_up(BH * T * (size_t)s.n_h * 4 + 4);
+  o->lut_mask_t = off;
+  off += align_up(BH * T * T);
   o->luts_bytes = off;
   off = 0;
   o->saved_Os = off;
@@ -111,7 +113,8 @@ int sla_classify_scores(const sla_params* p, const float* scores, int8_t* Mc, vo
   char* l = (char*)luts;
   hipError_t e = launch_classify(scores, s, Mc, (int32_t*)(l + z.lut_row_idx), st);
   if (e == hipSuccess)
-    e = launch_csc(Mc, s, (int32_t*)(l + z.lut_col_ptr), (int32_t*)(l + z.lut_col_rows), st);
+    e = launch_csc(Mc, s, (int32_t*)(l + z.lut_col_ptr), (int32_t*)(l + z.lut_col_rows),
+                   (int8_t*)(l + z.lut_mask_t), st);
   return hip_status(e);
 }
 
@@ -192,6 +195,7 @@ int sla_backward(const sla_params* p, const void* Q, const void* K, const void* 
   a.row_idx = (const int32_t*)(l + z.lut_row_idx);
   a.col_ptr = (const int32_t*)(l + z.lut_col_ptr);
   a.col_rows = (const int32_t*)(l + z.lut_col_rows);
+  a.McT = (const int8_t*)(l + z.lut_mask_t);
   a.Os = sv + z.saved_Os;
   a.Ol = sv + z.saved_Ol;
   a.L = (const float*)(sv + z.saved_L);

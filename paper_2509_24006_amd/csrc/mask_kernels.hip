@@ -215,6 +215,21 @@ __global__ void col_fill_kernel(const int8_t* __restrict__ Mc, int T, int n_h,
     if (m[(size_t)i * T] == 1) out[w++] = i;
 }
 
+// McT[j][i] = Mc[i][j], 32 x 32 tiles through LDS
+__global__ __launch_bounds__(256) void mask_transpose_kernel(const int8_t* __restrict__ Mc, int T,
+                                                             int8_t* __restrict__ McT) {
+  __shared__ int8_t tile[32][33];
+  const int bh = blockIdx.z, i0 = blockIdx.y * 32, j0 = blockIdx.x * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const int8_t* src = Mc + (size_t)bh * T * T;
+  int8_t* dst = McT + (size_t)bh * T * T;
+  for (int r = ty; r < 32; r += 8)
+    if (i0 + r < T && j0 + tx < T) tile[r][tx] = src[(size_t)(i0 + r) * T + j0 + tx];
+  __syncthreads();
+  for (int r = ty; r < 32; r += 8)
+    if (j0 + r < T && i0 + tx < T) dst[(size_t)(j0 + r) * T + i0 + tx] = tile[tx][r];
+}
+
 }  // namespace
 
 hipError_t launch_pool(const void* X, const Shape& s, float* out, hipStream_t st) {
@@ -254,7 +269,11 @@ hipError_t launch_classify(const float* scores, const Shape& s, int8_t* Mc, int3
 }
 
 hipError_t launch_csc(const int8_t* Mc, const Shape& s, int32_t* col_ptr, int32_t* col_rows,
-                      hipStream_t st) {
+                      int8_t* McT, hipStream_t st) {
+  {
+    KernelTimer kt("mask_transpose", st);
+    mask_transpose_kernel<<<dim3((s.T + 31) / 32, (s.T + 31) / 32, s.BH), 256, 0, st>>>(Mc, s.T, McT);
+  }
   dim3 grid((s.T + 255) / 256, s.BH);
   {
     KernelTimer kt("col_count", st);

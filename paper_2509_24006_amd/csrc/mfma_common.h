@@ -89,6 +89,67 @@ __device__ __forceinline__ void transpose4x4(const u32x2 (&in)[4], u32x2 (&out)[
   out[3].y = (in[2].y >> 16) | (in[3].y & 0xffff0000u);
 }
 
+typedef __hip_bfloat16 bf16;
+
+// ---- transposing tile stage
+// A 4-row x 4-feature patch (rows k4..k4+3, features f4..f4+3) of a row-major [rows][D]
+// bf16 tile is loaded as four 8-byte pieces and stored transposed into an LDS tile laid out
+// [feature][row position] (stride elements per feature) at row position `pos`.
+__device__ __forceinline__ void load_patch(const bf16* __restrict__ src, int D, int k4, int f4,
+                                           int rows_valid, u32x2 (&x)[4]) {
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    if (k4 + kk < rows_valid)
+      x[kk] = *reinterpret_cast<const u32x2*>(src + (size_t)(k4 + kk) * D + f4);
+    else
+      x[kk] = u32x2{0u, 0u};
+  }
+}
+
+__device__ __forceinline__ void store_patch_t(bf16* dst, int stride, int f4, int pos,
+                                              const u32x2 (&x)[4]) {
+  u32x2 y[4];
+  transpose4x4(x, y);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x2*>(dst + (f4 + i) * stride + pos) = y[i];
+}
+
+// position of row group kg (rows 4kg..4kg+3 of a 64-row tile) under perm16
+__device__ __forceinline__ int pos_of_kg(int kg) { return ((kg >> 2) << 4) + perm16((kg & 3) << 2); }
+
+constexpr int kVS = kBlk + 8;  // LDS stride (elements) of a transposed [feature][64 rows] tile
+
+// One staging unit = rows 4rg..4rg+3, features 8fg..8fg+7 of a 64 x D row-major tile, loaded
+// as four 16-byte pieces (zero beyond rows_valid).
+__device__ __forceinline__ void load_unit(const bf16* __restrict__ src, int D, int rg, int fg,
+                                          int rows_valid, u32x4 (&x)[4]) {
+#pragma unroll
+  for (int rr = 0; rr < 4; ++rr) {
+    if (4 * rg + rr < rows_valid)
+      x[rr] = *reinterpret_cast<const u32x4*>(src + (size_t)(4 * rg + rr) * D + 8 * fg);
+    else
+      x[rr] = u32x4{0u, 0u, 0u, 0u};
+  }
+}
+
+// row-major copy: dst[row][feature], stride RS elements
+__device__ __forceinline__ void store_unit_rows(bf16* dst, int RS, int rg, int fg, const u32x4 (&x)[4]) {
+#pragma unroll
+  for (int rr = 0; rr < 4; ++rr) *reinterpret_cast<u32x4*>(dst + (4 * rg + rr) * RS + 8 * fg) = x[rr];
+}
+
+// transposed copy: dst[feature][perm16 row position], stride kVS
+__device__ __forceinline__ void store_unit_t(bf16* dst, int rg, int fg, const u32x4 (&x)[4]) {
+  u32x2 lo[4], hi[4];
+#pragma unroll
+  for (int rr = 0; rr < 4; ++rr) {
+    lo[rr] = u32x2{x[rr].x, x[rr].y};
+    hi[rr] = u32x2{x[rr].z, x[rr].w};
+  }
+  store_patch_t(dst, kVS, 8 * fg, pos_of_kg(rg), lo);
+  store_patch_t(dst, kVS, 8 * fg + 4, pos_of_kg(rg), hi);
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 constexpr float kLog2e = 1.4426950408889634f;

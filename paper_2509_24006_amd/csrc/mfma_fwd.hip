@@ -23,34 +23,7 @@ __global__ void prep_w_kernel(const bf16* __restrict__ W, bf16* __restrict__ WTp
   WTp[ep * D + (e & ~15) + perm16(e & 15)] = W[idx];
 }
 
-// ------------------------------------------------------------------ transposing tile stage
-// Loads a 4-key x 4-feature patch (keys k4..k4+3, features f4..f4+3) of a row-major
-// [rows][D] bf16 tile and stores it transposed into an LDS tile laid out [feature][key
-// position], stride LDS elements per feature, at key position `pos` (4 consecutive).
-__device__ __forceinline__ void load_patch(const bf16* __restrict__ src, int D, int k4, int f4,
-                                           int rows_valid, u32x2 (&x)[4]) {
-#pragma unroll
-  for (int kk = 0; kk < 4; ++kk) {
-    if (k4 + kk < rows_valid)
-      x[kk] = *reinterpret_cast<const u32x2*>(src + (size_t)(k4 + kk) * D + f4);
-    else
-      x[kk] = u32x2{0u, 0u};
-  }
-}
-
-__device__ __forceinline__ void store_patch_t(bf16* dst, int stride, int f4, int pos,
-                                              const u32x2 (&x)[4]) {
-  u32x2 y[4];
-  transpose4x4(x, y);
-#pragma unroll
-  for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x2*>(dst + (f4 + i) * stride + pos) = y[i];
-}
-
-// key position of key group kg (keys 4kg..4kg+3) under perm16
-__device__ __forceinline__ int pos_of_kg(int kg) { return ((kg >> 2) << 4) + perm16((kg & 3) << 2); }
-
 // ------------------------------------------------------------------ key-block states
-constexpr int kVS = kBlk + 8;  // LDS stride (elements) of a transposed [feature][64 keys] tile
 
 template <int D>
 __global__ __launch_bounds__(256) void states_mfma_kernel(const bf16* __restrict__ K,
@@ -182,7 +155,17 @@ __global__ __launch_bounds__(256) void states_mfma_kernel(const bf16* __restrict
 // staged transposed through LDS (double-buffered).
 constexpr int kAggBS = 32 + 8;  // LDS stride of the [col][32 k] tile
 
-__global__ __launch_bounds__(256) void aggregate_mfma_kernel(const bf16* __restrict__ in,
+__device__ __forceinline__ u32x2 load4_bf16(const bf16* p) { return *reinterpret_cast<const u32x2*>(p); }
+__device__ __forceinline__ u32x2 load4_bf16(const float* p) {
+  const f32x4 v = *reinterpret_cast<const f32x4*>(p);
+  bf16x4 b;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) b[i] = (__bf16)v[i];
+  return *reinterpret_cast<u32x2*>(&b);
+}
+
+template <typename TIN>
+__global__ __launch_bounds__(256) void aggregate_mfma_kernel(const TIN* __restrict__ in,
                                                              const int8_t* __restrict__ M, int T,
                                                              int row_len,
                                                              float* __restrict__ out) {
@@ -190,7 +173,7 @@ __global__ __launch_bounds__(256) void aggregate_mfma_kernel(const bf16* __restr
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
   const int n0 = blockIdx.x * 128, m0 = blockIdx.y * 256, bh = blockIdx.z;
   const int8_t* Mb = M + (size_t)bh * T * T;
-  const bf16* inb = in + (size_t)bh * T * row_len;
+  const TIN* inb = in + (size_t)bh * T * row_len;
   f32x16 acc[2][4];
 #pragma unroll
   for (int mt = 0; mt < 2; ++mt)
@@ -205,7 +188,7 @@ __global__ __launch_bounds__(256) void aggregate_mfma_kernel(const bf16* __restr
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       if (k0 + kk < T && n0 + 4 * fg + 3 < row_len)
-        x[kk] = *reinterpret_cast<const u32x2*>(inb + (size_t)(k0 + kk) * row_len + n0 + 4 * fg);
+        x[kk] = load4_bf16(inb + (size_t)(k0 + kk) * row_len + n0 + 4 * fg);
       else
         x[kk] = u32x2{0u, 0u};
     }
@@ -605,7 +588,7 @@ hipError_t forward_impl(const Shape& s, const FwdArgs& a, bf16* hz16, bf16* WTp,
     }
     {
       KernelTimer kt("aggregate", st);
-      aggregate_mfma_kernel<<<dim3((row_len + 127) / 128, (s.T + 255) / 256, s.BH), 256, 0, st>>>(
+      aggregate_mfma_kernel<bf16><<<dim3((row_len + 127) / 128, (s.T + 255) / 256, s.BH), 256, 0, st>>>(
           hz16, a.Mc, s.T, row_len, a.HZ);
     }
   } else if (a.Os) {   // saved states must read as zero
@@ -625,6 +608,15 @@ hipError_t forward_impl(const Shape& s, const FwdArgs& a, bf16* hz16, bf16* WTp,
 }
 
 }  // namespace
+
+hipError_t mfma_aggregate_f32(const float* in, const int8_t* M, const Shape& s, float* out,
+                              hipStream_t st) {
+  const int row_len = s.state_row();
+  KernelTimer kt("aggregate", st);
+  aggregate_mfma_kernel<float><<<dim3((row_len + 127) / 128, (s.T + 255) / 256, s.BH), 256, 0, st>>>(
+      in, M, s.T, row_len, out);
+  return hipGetLastError();
+}
 
 size_t mfma_forward_ws_bytes(const Shape& s) {
   return align_up((size_t)s.BH * s.T * s.state_row() * 2) + align_up((size_t)s.d * s.d * 2);

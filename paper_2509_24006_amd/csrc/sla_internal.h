@@ -31,7 +31,7 @@ hipError_t launch_scores(const float* qbar, const float* kbar, const Shape& s, f
 hipError_t launch_classify(const float* scores, const Shape& s, int8_t* Mc, int32_t* row_idx,
                            hipStream_t st);
 hipError_t launch_csc(const int8_t* Mc, const Shape& s, int32_t* col_ptr, int32_t* col_rows,
-                      hipStream_t st);
+                      int8_t* McT, hipStream_t st);
 
 // ---- float-arithmetic path (simt_kernels.hip): every contraction in fp32 FMA
 struct FwdArgs {
@@ -49,6 +49,7 @@ hipError_t simt_forward(const Shape& s, const FwdArgs& a, hipStream_t st);
 struct BwdArgs {
   const void *Q, *K, *V, *W, *dO;
   const int8_t* Mc;
+  const int8_t* McT;   // transposed mask
   const int32_t *row_idx, *col_ptr, *col_rows;
   const void *Os, *Ol;
   const float *L, *HZ;
@@ -57,11 +58,18 @@ struct BwdArgs {
   char* ws;  // workspace, ws_backward_bytes
 };
 size_t simt_backward_ws_bytes(const Shape& s);
+// critical-block gradients on the matrix cores (mfma_bwd.hip); the *lin pointers may be null
+hipError_t mfma_backward_sparse(const Shape& s, const BwdArgs& a, const float* Ds,
+                                const float* dQlin, const float* dKlin, const float* dVlin,
+                                hipStream_t st);
 hipError_t simt_backward(const Shape& s, const BwdArgs& a, hipStream_t st);
 
 // ---- bf16 matrix-core path (mfma_fwd.hip)
 size_t mfma_forward_ws_bytes(const Shape& s);
 hipError_t mfma_forward(const Shape& s, const FwdArgs& a, char* ws, hipStream_t st);
+// out[i] = sum of the float state rows in[k] with M[i][k] == 0 (bf16 products, float sums)
+hipError_t mfma_aggregate_f32(const float* in, const int8_t* M, const Shape& s, float* out,
+                              hipStream_t st);
 
 // Brackets one kernel launch with events when profiling is on (profile.hip).
 class KernelTimer {

@@ -40,8 +40,11 @@ def run_gpu(x, dtype: str, k_h: float, k_l: float, phi: int = 0, backward: bool 
     return out
 
 
-def check_luts(Mc: np.ndarray, row_idx: np.ndarray, col_ptr: np.ndarray, col_rows: np.ndarray):
+def check_luts(Mc: np.ndarray, row_idx: np.ndarray, col_ptr: np.ndarray, col_rows: np.ndarray,
+               mask_t: np.ndarray = None):
     B, H, T, _ = Mc.shape
+    if mask_t is not None:
+        assert np.array_equal(mask_t, np.swapaxes(Mc, -1, -2))
     for b in range(B):
         for h in range(H):
             crit = Mc[b, h] == 1
