@@ -150,6 +150,11 @@ __device__ __forceinline__ void store_unit_t(bf16* dst, int rg, int fg, const u3
   store_patch_t(dst, kVS, 8 * fg + 4, pos_of_kg(rg), hi);
 }
 
+// Buffer resource over `bytes` bytes starting at p: loads through it return zero beyond the end.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const void* p, int bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 constexpr float kLog2e = 1.4426950408889634f;

@@ -298,36 +298,44 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
   const bf16* Kb = K + (size_t)bh * N * D;
   const bf16* Vb = V + (size_t)bh * N * D;
   const int steps = (n_h + 1) >> 1;
-  for (int s = 0; s < steps; ++s) {
+  const float c2 = scale_log2e;                    // exp(x / sqrt(d)) = exp2(x * c2)
+  constexpr int KCH = 2 * kBlk * (D / 8) / 256;    // 16-byte K chunks per thread and step
+  constexpr int VU = 2 * 16 * (D / 4) / 256;       // 4x4 V patches per thread and step
+  u32x4 kreg[KCH];
+  u32x2 vreg[VU][4];
+  // Global loads of one step (two K tiles, two V tiles) into registers.  Buffer loads return
+  // zero past the end of a tile's valid rows, so tails and a missing second tile need no branch.
+  auto load_step = [&](int s) {
     const int j0 = lut[2 * s];
     const bool two = 2 * s + 1 < n_h;
     const int j1 = two ? lut[2 * s + 1] : j0;
-    // ---- global loads of both K tiles and both V tiles (V patches stay in registers)
-    constexpr int KCH = 2 * kBlk * (D / 8) / 256;   // 16-byte chunks per thread
-    u32x4 kreg[KCH];
+    const int cols0 = min(kBlk, N - j0 * kBlk), cols1 = two ? min(kBlk, N - j1 * kBlk) : 0;
+    const __amdgpu_buffer_rsrc_t rk0 = tile_rsrc(Kb + (size_t)j0 * kBlk * D, cols0 * D * 2);
+    const __amdgpu_buffer_rsrc_t rk1 = tile_rsrc(Kb + (size_t)j1 * kBlk * D, cols1 * D * 2);
+    const __amdgpu_buffer_rsrc_t rv0 = tile_rsrc(Vb + (size_t)j0 * kBlk * D, cols0 * D * 2);
+    const __amdgpu_buffer_rsrc_t rv1 = tile_rsrc(Vb + (size_t)j1 * kBlk * D, cols1 * D * 2);
 #pragma unroll
     for (int r = 0; r < KCH; ++r) {
       const int c = tid + 256 * r;
-      const int p = c / (kBlk * (D / 8)), cc = c - p * (kBlk * (D / 8));
-      const int row = cc / (D / 8), c8 = cc - row * (D / 8);
-      const int jj = p ? j1 : j0;
-      const int cols = min(kBlk, N - jj * kBlk);
-      if (row < cols && (p == 0 || two))
-        kreg[r] = *reinterpret_cast<const u32x4*>(Kb + ((size_t)jj * kBlk + row) * D + 8 * c8);
-      else
-        kreg[r] = u32x4{0u, 0u, 0u, 0u};
+      const int p = c / (kBlk * (D / 8)), cc = c - p * (kBlk * (D / 8));   // p is a constant per r
+      kreg[r] = __builtin_amdgcn_raw_buffer_load_b128(p ? rk1 : rk0, cc * 16, 0, 0);
     }
-    constexpr int VU = 2 * 16 * (D / 4) / 256;      // 4x4 patches per thread
-    u32x2 vreg[VU][4];
 #pragma unroll
     for (int r = 0; r < VU; ++r) {
       const int u = tid + 256 * r;
       const int p = u / (16 * (D / 4)), uu = u - p * (16 * (D / 4));
       const int fg = uu % (D / 4), kg = uu / (D / 4);
-      const int jj = p ? j1 : j0;
-      const int cols = (p == 0 || two) ? min(kBlk, N - jj * kBlk) : 0;
-      load_patch(Vb + (size_t)jj * kBlk * D, D, 4 * kg, 4 * fg, cols, vreg[r]);
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+        vreg[r][kk] = __builtin_amdgcn_raw_buffer_load_b64(p ? rv1 : rv0, ((4 * kg + kk) * D + 4 * fg) * 2, 0, 0);
     }
+  };
+  if (steps > 0) load_step(0);
+  for (int s = 0; s < steps; ++s) {
+    const bool two = 2 * s + 1 < n_h;
+    const int jmine = lut[par && two ? 2 * s + 1 : 2 * s];
+    const int cols = min(kBlk, N - jmine * kBlk);
+    __syncthreads();   // every wave is done reading the previous step's tiles
 #pragma unroll
     for (int r = 0; r < KCH; ++r) {
       const int c = tid + 256 * r;
@@ -335,12 +343,17 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
       const int row = cc / (D / 8), c8 = cc - row * (D / 8);
       *reinterpret_cast<u32x4*>(Ks + (p * kBlk + row) * KS + 8 * c8) = kreg[r];
     }
-    __syncthreads();   // K tiles visible; every wave is past the previous step's P V
-    const bool active = par == 0 || two;
-    const int jmine = par ? j1 : j0;
-    const int cols = min(kBlk, N - jmine * kBlk);
-    f32x16 sT[2];
-    if (active) {
+#pragma unroll
+    for (int r = 0; r < VU; ++r) {
+      const int u = tid + 256 * r;
+      const int p = u / (16 * (D / 4)), uu = u - p * (16 * (D / 4));
+      const int fg = uu % (D / 4), kg = uu / (D / 4);
+      store_patch_t(Vt + p * D * kVS, kVS, 4 * fg, pos_of_kg(kg), vreg[r]);
+    }
+    __syncthreads();   // tiles visible
+    if (s + 1 < steps) load_step(s + 1);   // in flight during this step's arithmetic
+    if (par == 0 || two) {
+      f32x16 sT[2];
       sT[0] = zero_f32x16();
       sT[1] = zero_f32x16();
 #pragma unroll
@@ -351,51 +364,45 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
           sT[mt] = mfma32(a, qf[t], sT[mt]);
         }
       }
-    }
-    // ---- V tiles into LDS, transposed (previous step's readers are behind the barrier above)
+      // ---- online softmax on raw scores (the 1/sqrt(d) and log2 e factors ride on the exp2
+      // argument); one query per lane
+      if (cols < kBlk) {
 #pragma unroll
-    for (int r = 0; r < VU; ++r) {
-      const int u = tid + 256 * r;
-      const int p = u / (16 * (D / 4)), uu = u - p * (16 * (D / 4));
-      const int fg = uu % (D / 4), kg = uu / (D / 4);
-      store_patch_t(Vt + p * D * kVS, kVS, 4 * fg, pos_of_kg(kg), vreg[r]);
-    }
-    bf16x8 pf[4];
-    if (active) {
-      // ---- online softmax in the exp2 domain; one query per lane
-      float mx = -INFINITY;
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (32 * mt + c_row(r, g) >= cols) sT[mt][r] = -INFINITY;
+      }
+      float mx = sT[0][0];
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = 32 * mt + c_row(r, g);
-          const float v = key < cols ? sT[mt][r] * scale_log2e : -INFINITY;
-          sT[mt][r] = v;
-          mx = fmaxf(mx, v);
-        }
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sT[mt][r]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       const float mnew = fmaxf(m, mx);
-      const float alpha = fast_exp2(m - mnew);
+      const float moff = -mnew * c2;
       float psum = 0.0f;
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float pv = fast_exp2(sT[mt][r] - mnew);
+          const float pv = fast_exp2(fmaf(sT[mt][r], c2, moff));
           sT[mt][r] = pv;
           psum += pv;
         }
-      lsum = lsum * alpha + psum;
-      m = mnew;
+      if (__any(mnew != m)) {   // rescale only when some query's running maximum moved
+        const float alpha = fast_exp2((m - mnew) * c2);
+        lsum *= alpha;
 #pragma unroll
-      for (int et = 0; et < NT; ++et)
+        for (int et = 0; et < NT; ++et)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) oT[et][r] *= alpha;
+          for (int r = 0; r < 16; ++r) oT[et][r] *= alpha;
+        m = mnew;
+      }
+      lsum += psum;
+      bf16x8 pf[4];
 #pragma unroll
       for (int t = 0; t < 4; ++t) pf[t] = c_to_operand(sT[t >> 1], t & 1);
-    }
-    __syncthreads();   // V tiles visible
-    if (active) {
 #pragma unroll
       for (int t = 0; t < 4; ++t)
 #pragma unroll
@@ -416,11 +423,11 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
   const float l_o = ml[(((par ^ 1) * 2 + qh) * 32 + ln) * 2 + 1];
   float cw = 0.0f, Lval = -INFINITY;
   if (n_h > 0) {
-    const float mstar = fmaxf(m, m_o);
-    const float a_me = fast_exp2(m - mstar), a_ot = fast_exp2(m_o - mstar);
+    const float mstar = fmaxf(m, m_o);   // raw-score units
+    const float a_me = fast_exp2((m - mstar) * c2), a_ot = fast_exp2((m_o - mstar) * c2);
     const float ltot = lsum * a_me + l_o * a_ot;
     cw = a_me / ltot;
-    Lval = mstar * kLn2 + logf(ltot);
+    Lval = mstar * c2 * kLn2 + logf(ltot);
   }
 #pragma unroll
   for (int et = 0; et < NT; ++et)
