@@ -1,0 +1,467 @@
+// bf16 matrix-core backward kernels of the linear branch and of Proj (Algorithm 2 first loop and
+// last line, Eq. 8, plus the chain rule of Eq. 6 and through phi):
+//   bwd_pre_mfma    per query block: dO^l = dO W^T, D^s, D^l, dH_i, dZ_i, dQ^phi_i -> dQ (linear part)
+//   bwd_link_mfma   per key block:   dK^phi_j = V_j dH^T + 1 dZ^T -> dK (linear part), dV_j (linear part)
+//   dw_mfma         dW = sum_n (O^l_n)^T dO_n, per-workgroup partial sums
+// One lane owns one token (query or key) in every product whose result is per token, so the
+// row-wise quantities (softmax statistics of phi, D^l, the normaliser phi(Q) Z) are per-lane scalars.
+#include "mfma_common.h"
+
+namespace sla {
+namespace {
+
+constexpr int kRSl(int D) { return D + 8; }
+
+// phi statistics of a token whose features sit in B-operand fragments (lane holds features
+// 16 t + 8 g + s, its partner lane l ^ 32 the others): softmax max and 1 / sum.
+template <int KT>
+__device__ __forceinline__ void phi_stats(const bf16x8 (&xf)[KT], int phi, float& mx, float& inv) {
+  mx = 0.0f;
+  inv = 1.0f;
+  if (phi != 0) return;
+  mx = -INFINITY;
+#pragma unroll
+  for (int t = 0; t < KT; ++t)
+#pragma unroll
+    for (int s = 0; s < 8; ++s) mx = fmaxf(mx, (float)xf[t][s]);
+  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  float sum = 0.0f;
+#pragma unroll
+  for (int t = 0; t < KT; ++t)
+#pragma unroll
+    for (int s = 0; s < 8; ++s) sum += fast_exp2(((float)xf[t][s] - mx) * kLog2e);
+  sum += __shfl_xor(sum, 32, 64);
+  inv = 1.0f / sum;
+}
+
+__device__ __forceinline__ float phi_val(float x, int phi, float mx, float inv) {
+  return phi == 0 ? fast_exp2((x - mx) * kLog2e) * inv : (x > 0.0f ? x + 1.0f : fast_exp2(x * kLog2e));
+}
+
+// Stages a d x d float matrix stored [b][a] (b-major) into LDS as bf16 [a][b] (stride RS).
+template <int D>
+__device__ __forceinline__ void stage_matrix_t(const float* __restrict__ src, bf16* dst, int RS) {
+  for (int pidx = threadIdx.x; pidx < (D / 4) * (D / 4); pidx += 256) {
+    const int a4 = pidx % (D / 4), b4 = pidx / (D / 4);
+    u32x2 x[4];
+#pragma unroll
+    for (int bb = 0; bb < 4; ++bb) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(src + (size_t)(4 * b4 + bb) * D + 4 * a4);
+      bf16x4 h;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) h[i] = (__bf16)v[i];
+      x[bb] = *reinterpret_cast<u32x2*>(&h);
+    }
+    store_patch_t(dst, RS, 4 * a4, 4 * b4, x);
+  }
+}
+
+// ------------------------------------------------------------------ query side
+template <int D>
+struct PreLds {
+  static constexpr int RS = kRSl(D);
+  static constexpr int G_ELEMS = kBlk * RS;     // dO^l row-major [q][b]
+  static constexpr int GT_ELEMS = D * kVS;      // dO^l transposed [b][q]
+  static constexpr int AT_ELEMS = D * kVS;      // (phi(Q)/den)^T [c][q]
+  static constexpr int H_ELEMS = D * RS;        // H_i [a][b]
+  static constexpr int F_OFF = (G_ELEMS + GT_ELEMS + AT_ELEMS + H_ELEMS) * 2;
+  static constexpr int BYTES = F_OFF + 4 * kBlk * 4;   // Dl partial [par][q], dot partial [par][q]
+};
+
+template <int D>
+__global__ __launch_bounds__(256) void bwd_pre_mfma_kernel(
+    const bf16* __restrict__ Q, const bf16* __restrict__ dO, const bf16* __restrict__ W,
+    const bf16* __restrict__ Os, const bf16* __restrict__ Ol, const float* __restrict__ HZ, int N,
+    int Tn, int n_0, int phi, float* __restrict__ Ds, float* __restrict__ dHZ,
+    float* __restrict__ dQlin) {
+  using Lds = PreLds<D>;
+  constexpr int RS = Lds::RS, NT = D / 32, KT = D / 16, HT = NT / 2;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16* Gs = reinterpret_cast<bf16*>(smem);
+  bf16* Gt = Gs + Lds::G_ELEMS;
+  bf16* At = Gt + Lds::GT_ELEMS;
+  bf16* Hs = At + Lds::AT_ELEMS;
+  float* dlp = reinterpret_cast<float*>(smem + Lds::F_OFF);   // [par][64]
+  float* dotp = dlp + 2 * kBlk;                               // [par][64]
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
+  const int qh = w & 1, par = w >> 1;
+  const int i = blockIdx.x, bh = blockIdx.y;
+  const int q0 = i * kBlk, rows = min(kBlk, N - q0);
+  const int qrow = qh * 32 + ln;
+  const bool qok = qrow < rows;
+  const size_t qoff = ((size_t)bh * N + q0 + qrow) * D;
+  bf16x8 gf[KT];
+#pragma unroll
+  for (int t = 0; t < KT; ++t)
+    gf[t] = qok ? *reinterpret_cast<const bf16x8*>(dO + qoff + 16 * t + 8 * g) : zero_bf16x8();
+  // D^s = rowsum(dO * O^s)
+  if (par == 0) {
+    float ds = 0.0f;
+    if (qok) {
+#pragma unroll
+      for (int t = 0; t < KT; ++t) {
+        const bf16x8 o = *reinterpret_cast<const bf16x8*>(Os + qoff + 16 * t + 8 * g);
+#pragma unroll
+        for (int s = 0; s < 8; ++s) ds = fmaf((float)gf[t][s], (float)o[s], ds);
+      }
+    }
+    ds += __shfl_xor(ds, 32, 64);
+    if (g == 0 && qok) Ds[(size_t)bh * N + q0 + qrow] = ds;
+  }
+  if (n_0 == 0) return;   // no linear branch: nothing else to do (uniform over the grid)
+  const float* Hrow = HZ + ((size_t)bh * Tn + i) * (D * D + D);
+  const float* Z = Hrow + D * D;
+  stage_matrix_t<D>(Hrow, Hs, RS);
+  // dO^l^T[b][q] = sum_e W[b][e] dO[q][e]; this wave: b-tiles par*HT .. par*HT+HT-1
+  f32x16 gl[HT];
+  float dl = 0.0f;
+#pragma unroll
+  for (int h2 = 0; h2 < HT; ++h2) {
+    const int bt = par * HT + h2;
+    gl[h2] = zero_f32x16();
+#pragma unroll
+    for (int t = 0; t < KT; ++t) {
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(W + (size_t)(32 * bt + ln) * D + 16 * t + 8 * g);
+      gl[h2] = mfma32(a, gf[t], gl[h2]);
+    }
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+      const int b0 = 32 * bt + 8 * r4 + 4 * g;
+      bf16x4 ol4;
+      if (qok) ol4 = *reinterpret_cast<const bf16x4*>(Ol + qoff + b0);
+      bf16x4 pk;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float v = gl[h2][4 * r4 + r];
+        pk[r] = (__bf16)v;
+        if (qok) dl = fmaf(v, (float)ol4[r], dl);
+        Gt[(b0 + r) * kVS + qrow] = __float2bfloat16(v);
+      }
+      *reinterpret_cast<bf16x4*>(Gs + qrow * RS + b0) = pk;
+    }
+  }
+  dl += __shfl_xor(dl, 32, 64);
+  if (g == 0) dlp[par * kBlk + qrow] = dl;
+  // phi(Q), its normaliser, and a = phi(Q) / den transposed into LDS (this wave: half of the features)
+  bf16x8 qf[KT];
+#pragma unroll
+  for (int t = 0; t < KT; ++t)
+    qf[t] = qok ? *reinterpret_cast<const bf16x8*>(Q + qoff + 16 * t + 8 * g) : zero_bf16x8();
+  float qmx, qinv;
+  phi_stats<KT>(qf, phi, qmx, qinv);
+  float den = 0.0f;
+  float yq[KT][8];
+#pragma unroll
+  for (int t = 0; t < KT; ++t) {
+    const f32x4 z0 = *reinterpret_cast<const f32x4*>(Z + 16 * t + 8 * g);
+    const f32x4 z1 = *reinterpret_cast<const f32x4*>(Z + 16 * t + 8 * g + 4);
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      const float y = (float)(__bf16)phi_val((float)qf[t][s], phi, qmx, qinv);
+      yq[t][s] = y;
+      den = fmaf(y, s < 4 ? z0[s] : z1[s - 4], den);
+    }
+  }
+  den += __shfl_xor(den, 32, 64);
+  const float dinv = qok ? 1.0f / den : 0.0f;
+#pragma unroll
+  for (int t = 0; t < KT; ++t) {
+    if ((t >= KT / 2) != (par == 1)) continue;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) At[(16 * t + 8 * g + s) * kVS + qrow] = __float2bfloat16(yq[t][s] * dinv);
+  }
+  __syncthreads();
+  const float Dl = dlp[qrow] + dlp[kBlk + qrow];
+  float* out = dHZ + ((size_t)bh * Tn + i) * (D * D + D);
+  // dH_i^T[b][c] = sum_q dO^l[q][b] a[q][c]; wave w owns b-tiles w, w+4, ...
+  for (int bt = w; bt < NT; bt += 4) {
+    f32x16 acc[NT];
+#pragma unroll
+    for (int ct = 0; ct < NT; ++ct) acc[ct] = zero_f32x16();
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(Gt + (32 * bt + ln) * kVS + 16 * u + 8 * g);
+#pragma unroll
+      for (int ct = 0; ct < NT; ++ct) {
+        const bf16x8 b = *reinterpret_cast<const bf16x8*>(At + (32 * ct + ln) * kVS + 16 * u + 8 * g);
+        acc[ct] = mfma32(a, b, acc[ct]);
+      }
+    }
+#pragma unroll
+    for (int ct = 0; ct < NT; ++ct)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) out[(size_t)(32 * bt + c_row(r, g)) * D + 32 * ct + ln] = acc[ct][r];
+  }
+  // dZ_i[c] = - sum_q a[q][c] D^l_q
+  if (tid < D) {
+    float z = 0.0f;
+    for (int q = 0; q < kBlk; ++q)
+      z = fmaf(__bfloat162float(At[tid * kVS + q]), dlp[q] + dlp[kBlk + q], z);
+    out[(size_t)D * D + tid] = -z;
+  }
+  // dQ^phi^T[c][q] = (sum_b H[c][b] dO^l[q][b] - D^l_q Z[c]) / den_q; this wave: c-tiles of par
+  f32x16 dq[HT];
+  float dot = 0.0f;
+  float yc[HT][16];
+#pragma unroll
+  for (int h2 = 0; h2 < HT; ++h2) {
+    const int ct = par * HT + h2;
+    dq[h2] = zero_f32x16();
+#pragma unroll
+    for (int t = 0; t < KT; ++t) {
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(Hs + (32 * ct + ln) * RS + 16 * t + 8 * g);
+      const bf16x8 b = *reinterpret_cast<const bf16x8*>(Gs + qrow * RS + 16 * t + 8 * g);
+      dq[h2] = mfma32(a, b, dq[h2]);
+    }
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+      const int c0 = 32 * ct + 8 * r4 + 4 * g;
+      const f32x4 z4 = *reinterpret_cast<const f32x4*>(Z + c0);
+      bf16x4 q4;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) q4[r] = (__bf16)0.0f;
+      if (qok) q4 = *reinterpret_cast<const bf16x4*>(Q + qoff + c0);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float v = (dq[h2][4 * r4 + r] - Dl * z4[r]) * dinv;
+        const float x = (float)q4[r];
+        const float y = phi == 0 ? phi_val(x, 0, qmx, qinv) : (x > 0.0f ? 1.0f : fast_exp2(x * kLog2e));
+        dq[h2][4 * r4 + r] = v;
+        yc[h2][4 * r4 + r] = y;
+        dot = fmaf(v, y, dot);
+      }
+    }
+  }
+  dot += __shfl_xor(dot, 32, 64);
+  if (g == 0) dotp[par * kBlk + qrow] = dot;
+  __syncthreads();
+  const float dtot = phi == 0 ? dotp[qrow] + dotp[kBlk + qrow] : 0.0f;
+  if (qok) {
+#pragma unroll
+    for (int h2 = 0; h2 < HT; ++h2) {
+      const int ct = par * HT + h2;
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        f32x4 o4;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) o4[r] = yc[h2][4 * r4 + r] * (dq[h2][4 * r4 + r] - dtot);
+        *reinterpret_cast<f32x4*>(dQlin + qoff + 32 * ct + 8 * r4 + 4 * g) = o4;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------ key side
+template <int D>
+struct LinkLds {
+  static constexpr int RS = kRSl(D);
+  static constexpr int H_ELEMS = D * RS;   // dH [a][b]
+  static constexpr int BYTES = H_ELEMS * 2 + 2 * kBlk * 4;
+};
+
+template <int D>
+__global__ __launch_bounds__(256) void bwd_link_mfma_kernel(
+    const bf16* __restrict__ K, const bf16* __restrict__ V, const float* __restrict__ dHZcol, int N,
+    int Tn, int phi, float* __restrict__ dKlin, float* __restrict__ dVlin) {
+  using Lds = LinkLds<D>;
+  constexpr int RS = Lds::RS, NT = D / 32, KT = D / 16, HT = NT / 2;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16* Hs = reinterpret_cast<bf16*>(smem);
+  float* dotp = reinterpret_cast<float*>(smem + Lds::H_ELEMS * 2);
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
+  const int nh = w & 1, par = w >> 1;
+  const int j = blockIdx.x, bh = blockIdx.y;
+  const int n0 = j * kBlk, cnt = min(kBlk, N - n0);
+  const int nrow = nh * 32 + ln;
+  const bool nok = nrow < cnt;
+  const size_t noff = ((size_t)bh * N + n0 + nrow) * D;
+  const float* Hrow = dHZcol + ((size_t)bh * Tn + j) * (D * D + D);   // dH^T stored [b][a]
+  const float* dZ = Hrow + D * D;
+  stage_matrix_t<D>(Hrow, Hs, RS);
+  bf16x8 kf[KT], vf[KT];
+#pragma unroll
+  for (int t = 0; t < KT; ++t) {
+    kf[t] = nok ? *reinterpret_cast<const bf16x8*>(K + noff + 16 * t + 8 * g) : zero_bf16x8();
+    vf[t] = nok ? *reinterpret_cast<const bf16x8*>(V + noff + 16 * t + 8 * g) : zero_bf16x8();
+  }
+  float kmx, kinv;
+  phi_stats<KT>(kf, phi, kmx, kinv);
+  bf16x8 kp[KT];
+#pragma unroll
+  for (int t = 0; t < KT; ++t)
+#pragma unroll
+    for (int s = 0; s < 8; ++s) kp[t][s] = (__bf16)(nok ? phi_val((float)kf[t][s], phi, kmx, kinv) : 0.0f);
+  // linear part of dV^T[b][n] = sum_a dH[a][b] phi(K)[n][a]; rows b of the stored matrix are the A operand
+#pragma unroll
+  for (int h2 = 0; h2 < HT; ++h2) {
+    const int bt = par * HT + h2;
+    f32x16 acc = zero_f32x16();
+#pragma unroll
+    for (int t = 0; t < KT; ++t) {
+      const bf16x8 a = cvt8(Hrow + (size_t)(32 * bt + ln) * D + 16 * t + 8 * g);
+      acc = mfma32(a, kp[t], acc);
+    }
+    if (nok) {
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        f32x4 o4;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) o4[r] = acc[4 * r4 + r];
+        *reinterpret_cast<f32x4*>(dVlin + noff + 32 * bt + 8 * r4 + 4 * g) = o4;
+      }
+    }
+  }
+  __syncthreads();
+  // dK^phi^T[a][n] = sum_b dH[a][b] V[n][b] + dZ[a]; then through phi
+  f32x16 dk[HT];
+  float yc[HT][16];
+  float dot = 0.0f;
+#pragma unroll
+  for (int h2 = 0; h2 < HT; ++h2) {
+    const int at = par * HT + h2;
+    dk[h2] = zero_f32x16();
+#pragma unroll
+    for (int t = 0; t < KT; ++t) {
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(Hs + (32 * at + ln) * RS + 16 * t + 8 * g);
+      dk[h2] = mfma32(a, vf[t], dk[h2]);
+    }
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+      const int a0 = 32 * at + 8 * r4 + 4 * g;
+      const f32x4 z4 = *reinterpret_cast<const f32x4*>(dZ + a0);
+      bf16x4 k4;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) k4[r] = (__bf16)0.0f;
+      if (nok) k4 = *reinterpret_cast<const bf16x4*>(K + noff + a0);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float v = dk[h2][4 * r4 + r] + z4[r];
+        const float x = (float)k4[r];
+        const float y = phi == 0 ? phi_val(x, 0, kmx, kinv) : (x > 0.0f ? 1.0f : fast_exp2(x * kLog2e));
+        dk[h2][4 * r4 + r] = v;
+        yc[h2][4 * r4 + r] = y;
+        dot = fmaf(v, y, dot);
+      }
+    }
+  }
+  dot += __shfl_xor(dot, 32, 64);
+  if (g == 0) dotp[par * kBlk + nrow] = dot;
+  __syncthreads();
+  const float dtot = phi == 0 ? dotp[nrow] + dotp[kBlk + nrow] : 0.0f;
+  if (nok) {
+#pragma unroll
+    for (int h2 = 0; h2 < HT; ++h2) {
+      const int at = par * HT + h2;
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        f32x4 o4;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) o4[r] = yc[h2][4 * r4 + r] * (dk[h2][4 * r4 + r] - dtot);
+        *reinterpret_cast<f32x4*>(dKlin + noff + 32 * at + 8 * r4 + 4 * g) = o4;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------ dW partial sums
+// Workgroup g sums (O^l)^T dO over token tiles g, g + G, ...; wave w owns rows 32w.. of dW.
+template <int D>
+__global__ __launch_bounds__(256) void dw_mfma_kernel(const bf16* __restrict__ Ol,
+                                                      const bf16* __restrict__ dO, int BH, int N,
+                                                      int Tn, float* __restrict__ part) {
+  constexpr int NT = D / 32;
+  __shared__ __attribute__((aligned(16))) bf16 At[D * kVS];   // (O^l)^T [c][token pos]
+  __shared__ __attribute__((aligned(16))) bf16 Bt[D * kVS];   // dO^T    [e][token pos]
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
+  f32x16 acc[NT];
+#pragma unroll
+  for (int et = 0; et < NT; ++et) acc[et] = zero_f32x16();
+  for (int t = blockIdx.x; t < BH * Tn; t += gridDim.x) {
+    const int bh = t / Tn, i = t - bh * Tn;
+    const int rows = min(kBlk, N - i * kBlk);
+    const size_t base = ((size_t)bh * N + (size_t)i * kBlk) * D;
+    u32x4 xa[4], xb[4];
+    const int fg = tid % (D / 8), rg = tid / (D / 8);
+    if (rg < 16) {
+      load_unit(Ol + base, D, rg, fg, rows, xa);
+      load_unit(dO + base, D, rg, fg, rows, xb);
+    }
+    __syncthreads();
+    if (rg < 16) {
+      store_unit_t(At, rg, fg, xa);
+      store_unit_t(Bt, rg, fg, xb);
+    }
+    __syncthreads();
+    if (w < NT) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(At + (32 * w + ln) * kVS + 16 * u + 8 * g);
+#pragma unroll
+        for (int et = 0; et < NT; ++et) {
+          const bf16x8 b = *reinterpret_cast<const bf16x8*>(Bt + (32 * et + ln) * kVS + 16 * u + 8 * g);
+          acc[et] = mfma32(a, b, acc[et]);
+        }
+      }
+    }
+  }
+  if (w < NT) {
+    float* out = part + (size_t)blockIdx.x * D * D;
+#pragma unroll
+    for (int et = 0; et < NT; ++et)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) out[(size_t)(32 * w + c_row(r, g)) * D + 32 * et + ln] = acc[et][r];
+  }
+}
+
+#define SLA_TRY(x)                   \
+  do {                               \
+    hipError_t e_ = (x);             \
+    if (e_ != hipSuccess) return e_; \
+  } while (0)
+
+template <int D>
+hipError_t pre_impl(const Shape& s, const BwdArgs& a, float* Ds, float* dHZ, float* dQlin,
+                    float* dWpart, int nparts, hipStream_t st) {
+  constexpr int lds = PreLds<D>::BYTES;
+  SLA_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_pre_mfma_kernel<D>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+  {
+    KernelTimer kt("bwd_pre", st);
+    bwd_pre_mfma_kernel<D><<<dim3(s.T, s.BH), 256, lds, st>>>(
+        (const bf16*)a.Q, (const bf16*)a.dO, (const bf16*)a.W, (const bf16*)a.Os, (const bf16*)a.Ol,
+        a.HZ, s.N, s.T, s.n_0, s.phi, Ds, dHZ, dQlin);
+  }
+  {
+    KernelTimer kt("dw_partial", st);
+    dw_mfma_kernel<D><<<nparts, 256, 0, st>>>((const bf16*)a.Ol, (const bf16*)a.dO, s.BH, s.N, s.T, dWpart);
+  }
+  return hipGetLastError();
+}
+
+template <int D>
+hipError_t link_impl(const Shape& s, const BwdArgs& a, const float* dHZcol, float* dKlin,
+                     float* dVlin, hipStream_t st) {
+  constexpr int lds = LinkLds<D>::BYTES;
+  SLA_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_link_mfma_kernel<D>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+  KernelTimer kt("bwd_link", st);
+  bwd_link_mfma_kernel<D><<<dim3(s.T, s.BH), 256, lds, st>>>((const bf16*)a.K, (const bf16*)a.V, dHZcol,
+                                                           s.N, s.T, s.phi, dKlin, dVlin);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t mfma_backward_pre(const Shape& s, const BwdArgs& a, float* Ds, float* dHZ, float* dQlin,
+                             float* dWpart, int nparts, hipStream_t st) {
+  return s.d == 64 ? pre_impl<64>(s, a, Ds, dHZ, dQlin, dWpart, nparts, st)
+                   : pre_impl<128>(s, a, Ds, dHZ, dQlin, dWpart, nparts, st);
+}
+
+hipError_t mfma_backward_link(const Shape& s, const BwdArgs& a, const float* dHZcol, float* dKlin,
+                              float* dVlin, hipStream_t st) {
+  return s.d == 64 ? link_impl<64>(s, a, dHZcol, dKlin, dVlin, st)
+                   : link_impl<128>(s, a, dHZcol, dKlin, dVlin, st);
+}
+
+}  // namespace sla

@@ -812,7 +812,7 @@ BwdWs carve_bwd(const Shape& s, char* ws) {
   };
   const size_t nd = (size_t)s.BH * s.N * s.d, n = (size_t)s.BH * s.N;
   const size_t st = (size_t)s.BH * s.T * s.state_row();
-  w.nparts = s.BH * s.T < 128 ? s.BH * s.T : 128;
+  w.nparts = s.BH * s.T < 256 ? s.BH * s.T : 256;
   w.dOl = take(nd);
   w.Ds = take(n);
   w.Dl = take(n);
@@ -899,6 +899,23 @@ hipError_t backward_impl(const Shape& s, const BwdArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
+// bf16 tensors: every step on the matrix cores; this file only contributes the dW reduction
+hipError_t backward_bf16(const Shape& s, const BwdArgs& a, hipStream_t st) {
+  const BwdWs w = carve_bwd(s, a.ws);
+  const bool lin = s.n_0 > 0;
+  SLA_TRY(mfma_backward_pre(s, a, w.Ds, w.dHZ, w.dQlin, w.dWpart, w.nparts, st));
+  {
+    KernelTimer kt("dw_reduce", st);
+    dw_reduce_kernel<<<(s.d * s.d + 255) / 256, 256, 0, st>>>(w.dWpart, w.nparts, s.d * s.d, a.dW);
+  }
+  if (lin) {
+    SLA_TRY(mfma_aggregate_f32(w.dHZ, a.McT, s, w.dHZcol, st));
+    SLA_TRY(mfma_backward_link(s, a, w.dHZcol, w.dKlin, w.dVlin, st));
+  }
+  return mfma_backward_sparse(s, a, w.Ds, lin ? w.dQlin : nullptr, lin ? w.dKlin : nullptr,
+                              lin ? w.dVlin : nullptr, st);
+}
+
 }  // namespace
 
 hipError_t simt_forward(const Shape& s, const FwdArgs& a, hipStream_t st) {
@@ -911,8 +928,7 @@ size_t simt_backward_ws_bytes(const Shape& s) { return carve_bwd(s, nullptr).byt
 
 hipError_t simt_backward(const Shape& s, const BwdArgs& a, hipStream_t st) {
   if (s.dtype == 0) return s.d == 64 ? backward_impl<float, 64>(s, a, st) : backward_impl<float, 128>(s, a, st);
-  return s.d == 64 ? backward_impl<__hip_bfloat16, 64>(s, a, st)
-                   : backward_impl<__hip_bfloat16, 128>(s, a, st);
+  return backward_bf16(s, a, st);
 }
 
 }  // namespace sla

@@ -71,6 +71,12 @@ hipError_t mfma_forward(const Shape& s, const FwdArgs& a, char* ws, hipStream_t 
 hipError_t mfma_aggregate_f32(const float* in, const int8_t* M, const Shape& s, float* out,
                               hipStream_t st);
 
+// linear branch and Proj gradients on the matrix cores (mfma_bwd_linear.hip)
+hipError_t mfma_backward_pre(const Shape& s, const BwdArgs& a, float* Ds, float* dHZ, float* dQlin,
+                             float* dWpart, int nparts, hipStream_t st);
+hipError_t mfma_backward_link(const Shape& s, const BwdArgs& a, const float* dHZcol, float* dKlin,
+                              float* dVlin, hipStream_t st);
+
 // Brackets one kernel launch with events when profiling is on (profile.hip).
 class KernelTimer {
  public:
