@@ -150,6 +150,28 @@ __device__ __forceinline__ void store_unit_t(bf16* dst, int rg, int fg, const u3
   store_patch_t(dst, kVS, 8 * fg + 4, pos_of_kg(rg), hi);
 }
 
+// A operand (rows = 32 features f0.., k = 16 tile rows r0.. in the order a C tile hands them
+// over, see perm16) read from a ROW-MAJOR LDS tile [row][feature] (stride elements) with the
+// transposing LDS read: in each group of 16 lanes, lane 4e + a supplies the address of 4
+// consecutive features of one row, and lane 4a + c receives feature c of the rows of lanes
+// a, 4 + a, 8 + a, 12 + a.  Two reads give the eight k-values of a lane.
+__device__ __forceinline__ bf16x8 read_tr_operand(const bf16* tile, int stride, int r0, int f0, int l) {
+  typedef __attribute__((ext_vector_type(4))) short s16x4;
+  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+  const int G = l >> 4, e = (l >> 2) & 3, a = l & 3;
+  const bf16* p = tile + (r0 + 4 * (G >> 1) + e) * stride + f0 + 16 * (G & 1) + 4 * a;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * stride));
+  bf16x8 r;
+  const bf16x4 lo4 = *reinterpret_cast<const bf16x4*>(&lo), hi4 = *reinterpret_cast<const bf16x4*>(&hi);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    r[i] = lo4[i];
+    r[4 + i] = hi4[i];
+  }
+  return r;
+}
+
 // Buffer resource over `bytes` bytes starting at p: loads through it return zero beyond the end.
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const void* p, int bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);

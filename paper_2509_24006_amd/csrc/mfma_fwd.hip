@@ -260,7 +260,8 @@ template <int D>
 struct FwdLds {
   static constexpr int KS = D + 8;                       // K tile row stride (elements)
   static constexpr int K_ELEMS = 2 * kBlk * KS;          // two K tiles
-  static constexpr int V_ELEMS = 2 * D * kVS;            // two transposed V tiles
+  static constexpr int VS = D + 32;                      // V tile row stride: rows 64 B apart modulo 256 B
+  static constexpr int V_ELEMS = 2 * kBlk * VS;          // two row-major V tiles (read transposed)
   static constexpr int XCH_BYTES = 2 * (D / 2) * 64 * 4; // exchange of C registers between par 0/1
   static constexpr int TILE_BYTES = (K_ELEMS + V_ELEMS) * 2;
   static constexpr int BYTES = (TILE_BYTES > XCH_BYTES ? TILE_BYTES : XCH_BYTES) + 1024;
@@ -276,7 +277,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
   constexpr int KS = Lds::KS, NT = D / 32, KT = D / 16;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16* Ks = reinterpret_cast<bf16*>(smem);
-  bf16* Vt = Ks + Lds::K_ELEMS;
+  bf16* Vs = Ks + Lds::K_ELEMS;
   float* xch = reinterpret_cast<float*>(smem);
   float* ml = reinterpret_cast<float*>(smem + Lds::BYTES - 1024);   // [par][qh][32][2]
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
@@ -300,9 +301,8 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
   const int steps = (n_h + 1) >> 1;
   const float c2 = scale_log2e;                    // exp(x / sqrt(d)) = exp2(x * c2)
   constexpr int KCH = 2 * kBlk * (D / 8) / 256;    // 16-byte K chunks per thread and step
-  constexpr int VU = 2 * 16 * (D / 4) / 256;       // 4x4 V patches per thread and step
-  u32x4 kreg[KCH];
-  u32x2 vreg[VU][4];
+  constexpr int VS = Lds::VS;
+  u32x4 kreg[KCH], vreg[KCH];
   // Global loads of one step (two K tiles, two V tiles) into registers.  Buffer loads return
   // zero past the end of a tile's valid rows, so tails and a missing second tile need no branch.
   auto load_step = [&](int s) {
@@ -321,13 +321,10 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
       kreg[r] = __builtin_amdgcn_raw_buffer_load_b128(p ? rk1 : rk0, cc * 16, 0, 0);
     }
 #pragma unroll
-    for (int r = 0; r < VU; ++r) {
-      const int u = tid + 256 * r;
-      const int p = u / (16 * (D / 4)), uu = u - p * (16 * (D / 4));
-      const int fg = uu % (D / 4), kg = uu / (D / 4);
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk)
-        vreg[r][kk] = __builtin_amdgcn_raw_buffer_load_b64(p ? rv1 : rv0, ((4 * kg + kk) * D + 4 * fg) * 2, 0, 0);
+    for (int r = 0; r < KCH; ++r) {
+      const int c = tid + 256 * r;
+      const int p = c / (kBlk * (D / 8)), cc = c - p * (kBlk * (D / 8));
+      vreg[r] = __builtin_amdgcn_raw_buffer_load_b128(p ? rv1 : rv0, cc * 16, 0, 0);
     }
   };
   if (steps > 0) load_step(0);
@@ -342,13 +339,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
       const int p = c / (kBlk * (D / 8)), cc = c - p * (kBlk * (D / 8));
       const int row = cc / (D / 8), c8 = cc - row * (D / 8);
       *reinterpret_cast<u32x4*>(Ks + (p * kBlk + row) * KS + 8 * c8) = kreg[r];
-    }
-#pragma unroll
-    for (int r = 0; r < VU; ++r) {
-      const int u = tid + 256 * r;
-      const int p = u / (16 * (D / 4)), uu = u - p * (16 * (D / 4));
-      const int fg = uu % (D / 4), kg = uu / (D / 4);
-      store_patch_t(Vt + p * D * kVS, kVS, 4 * fg, pos_of_kg(kg), vreg[r]);
+      *reinterpret_cast<u32x4*>(Vs + (p * kBlk + row) * VS + 8 * c8) = vreg[r];
     }
     __syncthreads();   // tiles visible
     if (s + 1 < steps) load_step(s + 1);   // in flight during this step's arithmetic
@@ -407,7 +398,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
       for (int t = 0; t < 4; ++t)
 #pragma unroll
         for (int et = 0; et < NT; ++et) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(Vt + (par * D + 32 * et + ln) * kVS + 16 * t + 8 * g);
+          const bf16x8 a = read_tr_operand(Vs + par * kBlk * VS, VS, 16 * t, 32 * et, l);
           oT[et] = mfma32(a, pf[t], oT[et]);
         }
     }
