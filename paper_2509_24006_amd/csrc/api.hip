@@ -58,6 +58,8 @@ void fill_sizes(const Shape& s, sla_sizes_t* o) {
   off += align_up(BH * T * (size_t)s.n_h * 4 + 4);
   o->lut_mask_t = off;
   off += align_up(BH * T * T);
+  o->lut_col_order = off;
+  off += align_up(BH * T * 4);
   o->luts_bytes = off;
   off = 0;
   o->saved_Os = off;
@@ -114,7 +116,7 @@ int sla_classify_scores(const sla_params* p, const float* scores, int8_t* Mc, vo
   hipError_t e = launch_classify(scores, s, Mc, (int32_t*)(l + z.lut_row_idx), st);
   if (e == hipSuccess)
     e = launch_csc(Mc, s, (int32_t*)(l + z.lut_col_ptr), (int32_t*)(l + z.lut_col_rows),
-                   (int8_t*)(l + z.lut_mask_t), st);
+                   (int8_t*)(l + z.lut_mask_t), (int32_t*)(l + z.lut_col_order), st);
   return hip_status(e);
 }
 
@@ -196,6 +198,7 @@ int sla_backward(const sla_params* p, const void* Q, const void* K, const void* 
   a.col_ptr = (const int32_t*)(l + z.lut_col_ptr);
   a.col_rows = (const int32_t*)(l + z.lut_col_rows);
   a.McT = (const int8_t*)(l + z.lut_mask_t);
+  a.col_order = (const int32_t*)(l + z.lut_col_order);
   a.Os = sv + z.saved_Os;
   a.Ol = sv + z.saved_Ol;
   a.L = (const float*)(sv + z.saved_L);

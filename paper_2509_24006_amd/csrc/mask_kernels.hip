@@ -230,6 +230,22 @@ __global__ __launch_bounds__(256) void mask_transpose_kernel(const int8_t* __res
     if (j0 + r < T && i0 + tx < T) dst[(size_t)(j0 + r) * T + i0 + tx] = tile[tx][r];
 }
 
+// col_order[rank] = j with rank = position of column j under (count descending, index ascending):
+// workgroups of the column-wise backward kernel take the longest lists first.
+__global__ __launch_bounds__(256) void col_order_kernel(const int32_t* __restrict__ ptr, int T,
+                                                        int32_t* __restrict__ order) {
+  extern __shared__ int cnt[];
+  const int32_t* p = ptr + (size_t)blockIdx.x * (T + 1);
+  for (int j = threadIdx.x; j < T; j += 256) cnt[j] = p[j + 1] - p[j];
+  __syncthreads();
+  for (int j = threadIdx.x; j < T; j += 256) {
+    const int c = cnt[j];
+    int rank = 0;
+    for (int k = 0; k < T; ++k) rank += (cnt[k] > c) || (cnt[k] == c && k < j);
+    order[(size_t)blockIdx.x * T + rank] = j;
+  }
+}
+
 }  // namespace
 
 hipError_t launch_pool(const void* X, const Shape& s, float* out, hipStream_t st) {
@@ -269,7 +285,7 @@ hipError_t launch_classify(const float* scores, const Shape& s, int8_t* Mc, int3
 }
 
 hipError_t launch_csc(const int8_t* Mc, const Shape& s, int32_t* col_ptr, int32_t* col_rows,
-                      int8_t* McT, hipStream_t st) {
+                      int8_t* McT, int32_t* col_order, hipStream_t st) {
   {
     KernelTimer kt("mask_transpose", st);
     mask_transpose_kernel<<<dim3((s.T + 31) / 32, (s.T + 31) / 32, s.BH), 256, 0, st>>>(Mc, s.T, McT);
@@ -282,6 +298,10 @@ hipError_t launch_csc(const int8_t* Mc, const Shape& s, int32_t* col_ptr, int32_
   {
     KernelTimer kt("col_scan", st);
     col_scan_kernel<<<s.BH, 256, 0, st>>>(col_ptr, s.T);
+  }
+  {
+    KernelTimer kt("col_order", st);
+    col_order_kernel<<<s.BH, 256, s.T * sizeof(int), st>>>(col_ptr, s.T, col_order);
   }
   if (s.n_h > 0) {
     KernelTimer kt("col_fill", st);

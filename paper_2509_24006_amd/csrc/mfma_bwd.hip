@@ -5,43 +5,70 @@
 //   bwd_dq_mfma    one workgroup per query block i, walking the row table:
 //                  dQ_i += dS K_j / sqrt(d)   (S, dP are recomputed; no atomics, one owner)
 // P = exp(S - L) and dS = P (dP - D^s) are formed in float from MFMA accumulators.
+//
+// Streaming tiles are staged ROW-MAJOR in LDS once (double-buffered: the next step's tiles are
+// in flight in registers during the arithmetic and written to the other buffer before the
+// single barrier of a step).  Where a product needs the tile transposed (contraction over its
+// rows) the operand is read with the transposing LDS read instead of keeping a second copy.
 #include "mfma_common.h"
 
 namespace sla {
 namespace {
 
-constexpr int kRS(int D) { return D + 8; }   // row-major tile stride (elements)
+// Row stride (elements) of a row-major tile that is read both by rows (16-byte reads, one row
+// per lane) and transposed: 304 bytes keeps both patterns off the worst bank conflicts.
+constexpr int kRS(int D) { return D + 24; }
+
+template <int D>
+struct StreamLds {
+  static constexpr int RS = kRS(D);
+  static constexpr int TILE = kBlk * RS;          // elements of one row-major tile
+  static constexpr int STEP = 4 * TILE;           // two pairs x two tensors
+  static constexpr int STAT_BYTES = 2 * 2 * 2 * kBlk * 4;   // [buf][tile][L, D^s][64]
+  static constexpr int BYTES = 2 * STEP * 2 + STAT_BYTES;
+};
+
+// Loads one 64 x D tile (rows beyond `valid_rows` read as zero) into registers / stores it.
+template <int D>
+__device__ __forceinline__ void load_tile_regs(const bf16* base, int valid_rows, u32x4 (&x)[D / 32]) {
+  const __amdgpu_buffer_rsrc_t r = tile_rsrc(base, valid_rows * D * 2);
+#pragma unroll
+  for (int c = 0; c < D / 32; ++c) x[c] = __builtin_amdgcn_raw_buffer_load_b128(r, (threadIdx.x + 256 * c) * 16, 0, 0);
+}
+
+template <int D>
+__device__ __forceinline__ void store_tile_regs(bf16* dst, const u32x4 (&x)[D / 32]) {
+  constexpr int RS = kRS(D);
+#pragma unroll
+  for (int c = 0; c < D / 32; ++c) {
+    const int ch = threadIdx.x + 256 * c;
+    const int row = ch / (D / 8), c8 = ch - row * (D / 8);
+    *reinterpret_cast<u32x4*>(dst + row * RS + 8 * c8) = x[c];
+  }
+}
 
 // ------------------------------------------------------------------ dK, dV
 // Wavefront (kh, par): kh = which 32 of the block's 64 keys, par = which of the two query
 // tiles of a step.  S and dP are formed as [query][key] so that each lane owns one key; P
 // and dS then feed the second products (contraction over queries) straight from registers.
 template <int D>
-struct KvLds {
-  static constexpr int RS = kRS(D);
-  static constexpr int ROW_ELEMS = kBlk * RS;       // one row-major tile
-  static constexpr int T_ELEMS = D * kVS;           // one transposed tile
-  static constexpr int TILE_ELEMS = 2 * ROW_ELEMS + 2 * T_ELEMS;   // Q, dO, Q^T, dO^T
-  static constexpr int STAT_BYTES = 2 * 2 * kBlk * 4;              // L*log2e and D^s of both tiles
-  static constexpr int BYTES = 2 * TILE_ELEMS * 2 + STAT_BYTES;
-};
-
-template <int D>
 __global__ __launch_bounds__(256) void bwd_dkdv_mfma_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
     const bf16* __restrict__ dO, const float* __restrict__ L, const float* __restrict__ Ds,
     const int32_t* __restrict__ col_ptr, const int32_t* __restrict__ col_rows,
-    const float* __restrict__ dKlin, const float* __restrict__ dVlin, int N, int Tn, int n_h,
-    float scale, bf16* __restrict__ dK, bf16* __restrict__ dV) {
-  using Lds = KvLds<D>;
-  constexpr int RS = Lds::RS, NT = D / 32, KT = D / 16;
+    const int32_t* __restrict__ col_order, const float* __restrict__ dKlin,
+    const float* __restrict__ dVlin, int N, int Tn, int n_h, float scale, bf16* __restrict__ dK,
+    bf16* __restrict__ dV) {
+  using Lds = StreamLds<D>;
+  constexpr int RS = Lds::RS, NT = D / 32, KT = D / 16, CH = D / 32;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16* tiles = reinterpret_cast<bf16*>(smem);
-  float* stats = reinterpret_cast<float*>(smem + 2 * Lds::TILE_ELEMS * 2);   // [tile][2][64]
+  float* stats = reinterpret_cast<float*>(smem + 2 * Lds::STEP * 2);
   float* xch = reinterpret_cast<float*>(smem);
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
   const int kh = w & 1, par = w >> 1;
-  const int j = blockIdx.x, bh = blockIdx.y;
+  const int bh = blockIdx.y;
+  const int j = col_order[(size_t)bh * Tn + blockIdx.x];   // heaviest key blocks first
   const int k0 = j * kBlk, cols = min(kBlk, N - k0);
   const int krow = kh * 32 + ln;
   const bool kok = krow < cols;
@@ -67,57 +94,46 @@ __global__ __launch_bounds__(256) void bwd_dkdv_mfma_kernel(
   const float* Lb = L + (size_t)bh * N;
   const float* Dsb = Ds + (size_t)bh * N;
   const int steps = (cnt + 1) >> 1;
-  constexpr int UPT = (16 * (D / 8) + 255) / 256;   // staging units per thread per tile
-  for (int s = 0; s < steps; ++s) {
+  u32x4 qreg[2][CH], greg[2][CH];
+  float streg = 0.0f;
+  auto load_step = [&](int s) {
     const bool two = 2 * s + 1 < cnt;
     const int i0 = list[beg + 2 * s];
     const int i1 = two ? list[beg + 2 * s + 1] : i0;
-    u32x4 qreg[2][UPT][4], greg[2][UPT][4];
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {
-      const int ii = p ? i1 : i0;
-      const int rows = (p == 0 || two) ? min(kBlk, N - ii * kBlk) : 0;
-#pragma unroll
-      for (int r = 0; r < UPT; ++r) {
-        const int u = tid + 256 * r;
-        const int fg = u % (D / 8), rg = u / (D / 8);
-        if (rg < 16) {
-          load_unit(Qb + (size_t)ii * kBlk * D, D, rg, fg, rows, qreg[p][r]);
-          load_unit(dOb + (size_t)ii * kBlk * D, D, rg, fg, rows, greg[p][r]);
-        }
-      }
-    }
-    __syncthreads();   // every wave is done with the previous step's tiles
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {
-      bf16* base = tiles + p * Lds::TILE_ELEMS;
-#pragma unroll
-      for (int r = 0; r < UPT; ++r) {
-        const int u = tid + 256 * r;
-        const int fg = u % (D / 8), rg = u / (D / 8);
-        if (rg < 16) {
-          store_unit_rows(base, RS, rg, fg, qreg[p][r]);
-          store_unit_rows(base + Lds::ROW_ELEMS, RS, rg, fg, greg[p][r]);
-          store_unit_t(base + 2 * Lds::ROW_ELEMS, rg, fg, qreg[p][r]);
-          store_unit_t(base + 2 * Lds::ROW_ELEMS + Lds::T_ELEMS, rg, fg, greg[p][r]);
-        }
-      }
-    }
-    if (tid < 128) {   // per-query statistics of both tiles; rows past the end never contribute
-      const int p = tid >> 6, q = tid & 63;
-      const int ii = p ? i1 : i0;
-      const bool ok = (p == 0 || two) && ii * kBlk + q < N;
-      stats[(p * 2 + 0) * kBlk + q] = ok ? Lb[ii * kBlk + q] * kLog2e : INFINITY;
-      stats[(p * 2 + 1) * kBlk + q] = ok ? Dsb[ii * kBlk + q] : 0.0f;
-    }
-    __syncthreads();
+    const int r0 = min(kBlk, N - i0 * kBlk), r1 = two ? min(kBlk, N - i1 * kBlk) : 0;
+    load_tile_regs<D>(Qb + (size_t)i0 * kBlk * D, r0, qreg[0]);
+    load_tile_regs<D>(dOb + (size_t)i0 * kBlk * D, r0, greg[0]);
+    load_tile_regs<D>(Qb + (size_t)i1 * kBlk * D, r1, qreg[1]);
+    load_tile_regs<D>(dOb + (size_t)i1 * kBlk * D, r1, greg[1]);
+    // thread t < 256: tile p = t / 128, kind = (t / 64) % 2 (L or D^s), query t % 64
+    const int p = tid >> 7, kind = (tid >> 6) & 1, q = tid & 63;
+    const int ii = p ? i1 : i0;
+    const bool ok = q < (p ? r1 : r0);
+    if (kind == 0) streg = ok ? Lb[ii * kBlk + q] * kLog2e : INFINITY;   // rows past the end give P = 0
+    else streg = ok ? Dsb[ii * kBlk + q] : 0.0f;
+  };
+  auto store_step = [&](int buf) {
+    bf16* base = tiles + buf * Lds::STEP;
+    store_tile_regs<D>(base, qreg[0]);
+    store_tile_regs<D>(base + Lds::TILE, greg[0]);
+    store_tile_regs<D>(base + 2 * Lds::TILE, qreg[1]);
+    store_tile_regs<D>(base + 3 * Lds::TILE, greg[1]);
+    stats[buf * 4 * kBlk + tid] = streg;
+  };
+  if (steps > 0) {
+    load_step(0);
+    store_step(0);
+  }
+  __syncthreads();
+  for (int s = 0; s < steps; ++s) {
+    const int buf = s & 1;
+    const bool two = 2 * s + 1 < cnt;
+    if (s + 1 < steps) load_step(s + 1);
     if (par == 0 || two) {
-      const bf16* Qs = tiles + par * Lds::TILE_ELEMS;
-      const bf16* Gs = Qs + Lds::ROW_ELEMS;
-      const bf16* Qt = Qs + 2 * Lds::ROW_ELEMS;
-      const bf16* Gt = Qt + Lds::T_ELEMS;
-      const float* Ls = stats + (par * 2 + 0) * kBlk;
-      const float* Dq = stats + (par * 2 + 1) * kBlk;
+      const bf16* Qs = tiles + buf * Lds::STEP + par * 2 * Lds::TILE;
+      const bf16* Gs = Qs + Lds::TILE;
+      const float* Ls = stats + buf * 4 * kBlk + par * 2 * kBlk;
+      const float* Dq = Ls + kBlk;
       f32x16 sm[2], dp[2];
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt) {
@@ -142,7 +158,7 @@ __global__ __launch_bounds__(256) void bwd_dkdv_mfma_kernel(
           const f32x4 dq = *reinterpret_cast<const f32x4*>(Dq + 32 * mt + 8 * r4 + 4 * g);
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
-            const float pv = kok ? fast_exp2(sm[mt][4 * r4 + r] * sl2 - lq[r]) : 0.0f;
+            const float pv = kok ? fast_exp2(fmaf(sm[mt][4 * r4 + r], sl2, -lq[r])) : 0.0f;
             sm[mt][4 * r4 + r] = pv;
             dp[mt][4 * r4 + r] = pv * (dp[mt][4 * r4 + r] - dq[r]);
           }
@@ -153,16 +169,17 @@ __global__ __launch_bounds__(256) void bwd_dkdv_mfma_kernel(
         const bf16x8 sb = c_to_operand(dp[u >> 1], u & 1);
 #pragma unroll
         for (int et = 0; et < NT; ++et) {
-          const bf16x8 ag = *reinterpret_cast<const bf16x8*>(Gt + (32 * et + ln) * kVS + 16 * u + 8 * g);
+          const bf16x8 ag = read_tr_operand(Gs, RS, 16 * u, 32 * et, l);   // dO_i^T
           dvT[et] = mfma32(ag, pb, dvT[et]);
-          const bf16x8 aq = *reinterpret_cast<const bf16x8*>(Qt + (32 * et + ln) * kVS + 16 * u + 8 * g);
+          const bf16x8 aq = read_tr_operand(Qs, RS, 16 * u, 32 * et, l);   // Q_i^T
           dkT[et] = mfma32(aq, sb, dkT[et]);
         }
       }
     }
+    if (s + 1 < steps) store_step(buf ^ 1);
+    __syncthreads();
   }
   // ---- add the two query-tile streams, then the linear-branch parts, and store
-  __syncthreads();
   float* myx = xch + (size_t)kh * (2 * NT * 16) * 64;
   if (par == 1) {
 #pragma unroll
@@ -200,22 +217,13 @@ __global__ __launch_bounds__(256) void bwd_dkdv_mfma_kernel(
 // Wavefront (qh, par) as in the forward kernel; S^T and dP^T are [key][query], one query per
 // lane, so L and D^s are per-lane scalars and dS^T feeds dQ^T = K^T dS^T from registers.
 template <int D>
-struct QLds {
-  static constexpr int RS = kRS(D);
-  static constexpr int ROW_ELEMS = kBlk * RS;
-  static constexpr int T_ELEMS = D * kVS;
-  static constexpr int TILE_ELEMS = 2 * ROW_ELEMS + T_ELEMS;   // K, V, K^T
-  static constexpr int BYTES = 2 * TILE_ELEMS * 2;
-};
-
-template <int D>
 __global__ __launch_bounds__(256) void bwd_dq_mfma_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
     const bf16* __restrict__ dO, const float* __restrict__ L, const float* __restrict__ Ds,
     const int32_t* __restrict__ row_idx, const float* __restrict__ dQlin, int N, int Tn, int n_h,
     float scale, bf16* __restrict__ dQ) {
-  using Lds = QLds<D>;
-  constexpr int RS = Lds::RS, NT = D / 32, KT = D / 16;
+  using Lds = StreamLds<D>;
+  constexpr int RS = Lds::RS, NT = D / 32, KT = D / 16, CH = D / 32;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16* tiles = reinterpret_cast<bf16*>(smem);
   float* xch = reinterpret_cast<float*>(smem);
@@ -242,48 +250,38 @@ __global__ __launch_bounds__(256) void bwd_dq_mfma_kernel(
   const bf16* Vb = V + (size_t)bh * N * D;
   const float sl2 = scale * kLog2e;
   const int steps = (n_h + 1) >> 1;
-  constexpr int UPT = (16 * (D / 8) + 255) / 256;
-  for (int s = 0; s < steps; ++s) {
+  u32x4 kreg[2][CH], vreg[2][CH];
+  auto load_step = [&](int s) {
     const bool two = 2 * s + 1 < n_h;
     const int j0 = lut[2 * s];
     const int j1 = two ? lut[2 * s + 1] : j0;
-    u32x4 kreg[2][UPT][4], vreg[2][UPT][4];
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {
-      const int jj = p ? j1 : j0;
-      const int cols = (p == 0 || two) ? min(kBlk, N - jj * kBlk) : 0;
-#pragma unroll
-      for (int r = 0; r < UPT; ++r) {
-        const int u = tid + 256 * r;
-        const int fg = u % (D / 8), rg = u / (D / 8);
-        if (rg < 16) {
-          load_unit(Kb + (size_t)jj * kBlk * D, D, rg, fg, cols, kreg[p][r]);
-          load_unit(Vb + (size_t)jj * kBlk * D, D, rg, fg, cols, vreg[p][r]);
-        }
-      }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {
-      bf16* base = tiles + p * Lds::TILE_ELEMS;
-#pragma unroll
-      for (int r = 0; r < UPT; ++r) {
-        const int u = tid + 256 * r;
-        const int fg = u % (D / 8), rg = u / (D / 8);
-        if (rg < 16) {
-          store_unit_rows(base, RS, rg, fg, kreg[p][r]);
-          store_unit_rows(base + Lds::ROW_ELEMS, RS, rg, fg, vreg[p][r]);
-          store_unit_t(base + 2 * Lds::ROW_ELEMS, rg, fg, kreg[p][r]);
-        }
-      }
-    }
-    __syncthreads();
+    const int c0 = min(kBlk, N - j0 * kBlk), c1 = two ? min(kBlk, N - j1 * kBlk) : 0;
+    load_tile_regs<D>(Kb + (size_t)j0 * kBlk * D, c0, kreg[0]);
+    load_tile_regs<D>(Vb + (size_t)j0 * kBlk * D, c0, vreg[0]);
+    load_tile_regs<D>(Kb + (size_t)j1 * kBlk * D, c1, kreg[1]);
+    load_tile_regs<D>(Vb + (size_t)j1 * kBlk * D, c1, vreg[1]);
+  };
+  auto store_step = [&](int buf) {
+    bf16* base = tiles + buf * Lds::STEP;
+    store_tile_regs<D>(base, kreg[0]);
+    store_tile_regs<D>(base + Lds::TILE, vreg[0]);
+    store_tile_regs<D>(base + 2 * Lds::TILE, kreg[1]);
+    store_tile_regs<D>(base + 3 * Lds::TILE, vreg[1]);
+  };
+  if (steps > 0) {
+    load_step(0);
+    store_step(0);
+  }
+  __syncthreads();
+  for (int s = 0; s < steps; ++s) {
+    const int buf = s & 1;
+    const bool two = 2 * s + 1 < n_h;
+    const int jmine = lut[par && two ? 2 * s + 1 : 2 * s];
+    const int cols = min(kBlk, N - jmine * kBlk);
+    if (s + 1 < steps) load_step(s + 1);
     if (par == 0 || two) {
-      const int jmine = par ? j1 : j0;
-      const int cols = min(kBlk, N - jmine * kBlk);
-      const bf16* Ks = tiles + par * Lds::TILE_ELEMS;
-      const bf16* Vs = Ks + Lds::ROW_ELEMS;
-      const bf16* Kt = Ks + 2 * Lds::ROW_ELEMS;
+      const bf16* Ks = tiles + buf * Lds::STEP + par * 2 * Lds::TILE;
+      const bf16* Vs = Ks + Lds::TILE;
       f32x16 sT[2], dpT[2];
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt) {
@@ -303,8 +301,8 @@ __global__ __launch_bounds__(256) void bwd_dq_mfma_kernel(
       for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int key = 32 * mt + c_row(r, g);
-          const float pv = key < cols ? fast_exp2(sT[mt][r] * sl2 - Lq) : 0.0f;
+          float pv = fast_exp2(fmaf(sT[mt][r], sl2, -Lq));
+          if (cols < kBlk && 32 * mt + c_row(r, g) >= cols) pv = 0.0f;
           dpT[mt][r] = pv * (dpT[mt][r] - Dq);
         }
 #pragma unroll
@@ -312,13 +310,14 @@ __global__ __launch_bounds__(256) void bwd_dq_mfma_kernel(
         const bf16x8 sb = c_to_operand(dpT[u >> 1], u & 1);
 #pragma unroll
         for (int dt = 0; dt < NT; ++dt) {
-          const bf16x8 ak = *reinterpret_cast<const bf16x8*>(Kt + (32 * dt + ln) * kVS + 16 * u + 8 * g);
+          const bf16x8 ak = read_tr_operand(Ks, RS, 16 * u, 32 * dt, l);   // K_j^T
           dqT[dt] = mfma32(ak, sb, dqT[dt]);
         }
       }
     }
+    if (s + 1 < steps) store_step(buf ^ 1);
+    __syncthreads();
   }
-  __syncthreads();
   float* myx = xch + (size_t)qh * (NT * 16) * 64;
   if (par == 1) {
 #pragma unroll
@@ -356,20 +355,20 @@ template <int D>
 hipError_t sparse_impl(const Shape& s, const BwdArgs& a, const float* Ds, const float* dQlin,
                        const float* dKlin, const float* dVlin, hipStream_t st) {
   const dim3 grid(s.T, s.BH);
-  constexpr int lds_kv = KvLds<D>::BYTES, lds_q = QLds<D>::BYTES;
+  constexpr int lds = StreamLds<D>::BYTES;
   SLA_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dkdv_mfma_kernel<D>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, lds_kv));
+                              hipFuncAttributeMaxDynamicSharedMemorySize, lds));
   {
     KernelTimer kt("bwd_sparse_kv", st);
-    bwd_dkdv_mfma_kernel<D><<<grid, 256, lds_kv, st>>>(
+    bwd_dkdv_mfma_kernel<D><<<grid, 256, lds, st>>>(
         (const bf16*)a.Q, (const bf16*)a.K, (const bf16*)a.V, (const bf16*)a.dO, a.L, Ds, a.col_ptr,
-        a.col_rows, dKlin, dVlin, s.N, s.T, s.n_h, s.scale, (bf16*)a.dK, (bf16*)a.dV);
+        a.col_rows, a.col_order, dKlin, dVlin, s.N, s.T, s.n_h, s.scale, (bf16*)a.dK, (bf16*)a.dV);
   }
   SLA_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dq_mfma_kernel<D>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, lds_q));
+                              hipFuncAttributeMaxDynamicSharedMemorySize, lds));
   {
     KernelTimer kt("bwd_sparse_q", st);
-    bwd_dq_mfma_kernel<D><<<grid, 256, lds_q, st>>>(
+    bwd_dq_mfma_kernel<D><<<grid, 256, lds, st>>>(
         (const bf16*)a.Q, (const bf16*)a.K, (const bf16*)a.V, (const bf16*)a.dO, a.L, Ds, a.row_idx,
         dQlin, s.N, s.T, s.n_h, s.scale, (bf16*)a.dQ);
   }

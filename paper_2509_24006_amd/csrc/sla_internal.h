@@ -31,7 +31,7 @@ hipError_t launch_scores(const float* qbar, const float* kbar, const Shape& s, f
 hipError_t launch_classify(const float* scores, const Shape& s, int8_t* Mc, int32_t* row_idx,
                            hipStream_t st);
 hipError_t launch_csc(const int8_t* Mc, const Shape& s, int32_t* col_ptr, int32_t* col_rows,
-                      int8_t* McT, hipStream_t st);
+                      int8_t* McT, int32_t* col_order, hipStream_t st);
 
 // ---- float-arithmetic path (simt_kernels.hip): every contraction in fp32 FMA
 struct FwdArgs {
@@ -50,7 +50,7 @@ struct BwdArgs {
   const void *Q, *K, *V, *W, *dO;
   const int8_t* Mc;
   const int8_t* McT;   // transposed mask
-  const int32_t *row_idx, *col_ptr, *col_rows;
+  const int32_t *row_idx, *col_ptr, *col_rows, *col_order;
   const void *Os, *Ol;
   const float *L, *HZ;
   void *dQ, *dK, *dV;

@@ -41,10 +41,16 @@ def run_gpu(x, dtype: str, k_h: float, k_l: float, phi: int = 0, backward: bool 
 
 
 def check_luts(Mc: np.ndarray, row_idx: np.ndarray, col_ptr: np.ndarray, col_rows: np.ndarray,
-               mask_t: np.ndarray = None):
+               mask_t: np.ndarray = None, col_order: np.ndarray = None):
     B, H, T, _ = Mc.shape
     if mask_t is not None:
         assert np.array_equal(mask_t, np.swapaxes(Mc, -1, -2))
+    if col_order is not None:
+        cnt = (Mc == 1).sum(-2)
+        for b in range(B):
+            for h in range(H):
+                want = np.lexsort((np.arange(T), -cnt[b, h]))   # count descending, index ascending
+                assert np.array_equal(col_order[b, h], want)
     for b in range(B):
         for h in range(H):
             crit = Mc[b, h] == 1
