@@ -67,8 +67,11 @@ __global__ __launch_bounds__(256) void bwd_dkdv_mfma_kernel(
   float* xch = reinterpret_cast<float*>(smem);
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
   const int kh = w & 1, par = w >> 1;
-  const int bh = blockIdx.y;
-  const int j = col_order[(size_t)bh * Tn + blockIdx.x];   // heaviest key blocks first
+  // longest column lists first, across all heads: the r-th heaviest key block of every head
+  // precedes the (r+1)-th of any head, so the tail of the launch is made of short lists
+  const int BH = gridDim.x / Tn;
+  const int bh = blockIdx.x % BH;
+  const int j = col_order[(size_t)bh * Tn + blockIdx.x / BH];
   const int k0 = j * kBlk, cols = min(kBlk, N - k0);
   const int krow = kh * 32 + ln;
   const bool kok = krow < cols;
@@ -360,7 +363,7 @@ hipError_t sparse_impl(const Shape& s, const BwdArgs& a, const float* Ds, const 
                               hipFuncAttributeMaxDynamicSharedMemorySize, lds));
   {
     KernelTimer kt("bwd_sparse_kv", st);
-    bwd_dkdv_mfma_kernel<D><<<grid, 256, lds, st>>>(
+    bwd_dkdv_mfma_kernel<D><<<dim3(s.T * s.BH), 256, lds, st>>>(
         (const bf16*)a.Q, (const bf16*)a.K, (const bf16*)a.V, (const bf16*)a.dO, a.L, Ds, a.col_ptr,
         a.col_rows, a.col_order, dKlin, dVlin, s.N, s.T, s.n_h, s.scale, (bf16*)a.dK, (bf16*)a.dV);
   }
