@@ -6,67 +6,46 @@
 //                  dQ_i += dS K_j / sqrt(d)   (S, dP are recomputed; no atomics, one owner)
 // P = exp(S - L) and dS = P (dP - D^s) are formed in float from MFMA accumulators.
 //
-// Streaming tiles are staged ROW-MAJOR in LDS once (double-buffered: the next step's tiles are
-// in flight in registers during the arithmetic and written to the other buffer before the
-// single barrier of a step).  Where a product needs the tile transposed (contraction over its
-// rows) the operand is read with the transposing LDS read instead of keeping a second copy.
+// One critical pair per step.  The two streaming tiles of a pair go global -> LDS directly
+// (no registers), row-major and chunk-swizzled, double-buffered: the loads of step s+1 are in
+// flight during the arithmetic of step s and a step has a single barrier.  A product that
+// needs a tile transposed (contraction over its rows) reads it with the transposing LDS read.
+// The four waves split the 64 x 64 pair into 32 x 32 quarters; two workgroups share a CU so
+// that one's matrix work overlaps the other's vector work.
 #include "mfma_common.h"
 
 namespace sla {
 namespace {
 
-// Row stride (elements) of a row-major tile that is read both by rows (16-byte reads, one row
-// per lane) and transposed: 304 bytes keeps both patterns off the worst bank conflicts.
-constexpr int kRS(int D) { return D + 24; }
-
 template <int D>
-struct StreamLds {
-  static constexpr int RS = kRS(D);
-  static constexpr int TILE = kBlk * RS;          // elements of one row-major tile
-  static constexpr int STEP = 4 * TILE;           // two pairs x two tensors
-  static constexpr int STAT_BYTES = 2 * 2 * 2 * kBlk * 4;   // [buf][tile][L, D^s][64]
-  static constexpr int BYTES = 2 * STEP * 2 + STAT_BYTES;
+struct PairLds {
+  static constexpr int TILE = SwzTile<D>::BYTES;
+  static constexpr int BUF = 2 * TILE;                   // the two tiles of a pair
+  static constexpr int STAT_OFF = 2 * BUF;
+  static constexpr int XCH = 2 * 2 * (D / 32) * 16 * 64 * 4;   // final exchange (dK/dV kernel)
+  static constexpr int TILES = 2 * BUF > XCH ? 2 * BUF : XCH;
+  static constexpr int BYTES = TILES + 2 * 2 * kBlk * 4; // + [buf][L, D^s][64]
 };
 
-// Loads one 64 x D tile (rows beyond `valid_rows` read as zero) into registers / stores it.
-template <int D>
-__device__ __forceinline__ void load_tile_regs(const bf16* base, int valid_rows, u32x4 (&x)[D / 32]) {
-  const __amdgpu_buffer_rsrc_t r = tile_rsrc(base, valid_rows * D * 2);
-#pragma unroll
-  for (int c = 0; c < D / 32; ++c) x[c] = __builtin_amdgcn_raw_buffer_load_b128(r, (threadIdx.x + 256 * c) * 16, 0, 0);
-}
-
-template <int D>
-__device__ __forceinline__ void store_tile_regs(bf16* dst, const u32x4 (&x)[D / 32]) {
-  constexpr int RS = kRS(D);
-#pragma unroll
-  for (int c = 0; c < D / 32; ++c) {
-    const int ch = threadIdx.x + 256 * c;
-    const int row = ch / (D / 8), c8 = ch - row * (D / 8);
-    *reinterpret_cast<u32x4*>(dst + row * RS + 8 * c8) = x[c];
-  }
-}
-
 // ------------------------------------------------------------------ dK, dV
-// Wavefront (kh, par): kh = which 32 of the block's 64 keys, par = which of the two query
-// tiles of a step.  S and dP are formed as [query][key] so that each lane owns one key; P
-// and dS then feed the second products (contraction over queries) straight from registers.
+// Wave (kh, qh): keys 32 kh .., queries 32 qh .. of the pair.  S and dP are [query][key] so
+// that each lane owns one key; P and dS feed the second products from registers.  The two qh
+// waves hold partial sums over their queries and are added at the end.
 template <int D>
-__global__ __launch_bounds__(256) void bwd_dkdv_mfma_kernel(
+__global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
     const bf16* __restrict__ dO, const float* __restrict__ L, const float* __restrict__ Ds,
     const int32_t* __restrict__ col_ptr, const int32_t* __restrict__ col_rows,
     const int32_t* __restrict__ col_order, const float* __restrict__ dKlin,
     const float* __restrict__ dVlin, int N, int Tn, int n_h, float scale, bf16* __restrict__ dK,
     bf16* __restrict__ dV) {
-  using Lds = StreamLds<D>;
-  constexpr int RS = Lds::RS, NT = D / 32, KT = D / 16, CH = D / 32;
+  using Lds = PairLds<D>;
+  constexpr int NT = D / 32, KT = D / 16;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  bf16* tiles = reinterpret_cast<bf16*>(smem);
-  float* stats = reinterpret_cast<float*>(smem + 2 * Lds::STEP * 2);
+  float* stats = reinterpret_cast<float*>(smem + Lds::TILES);   // [buf][2][64]
   float* xch = reinterpret_cast<float*>(smem);
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
-  const int kh = w & 1, par = w >> 1;
+  const int kh = w & 1, qh = w >> 1;
   // longest column lists first, across all heads: the r-th heaviest key block of every head
   // precedes the (r+1)-th of any head, so the tail of the launch is made of short lists
   const int BH = gridDim.x / Tn;
@@ -96,95 +75,67 @@ __global__ __launch_bounds__(256) void bwd_dkdv_mfma_kernel(
   const bf16* dOb = dO + (size_t)bh * N * D;
   const float* Lb = L + (size_t)bh * N;
   const float* Dsb = Ds + (size_t)bh * N;
-  const int steps = (cnt + 1) >> 1;
-  u32x4 qreg[2][CH], greg[2][CH];
   float streg = 0.0f;
-  auto load_step = [&](int s) {
-    const bool two = 2 * s + 1 < cnt;
-    const int i0 = list[beg + 2 * s];
-    const int i1 = two ? list[beg + 2 * s + 1] : i0;
-    const int r0 = min(kBlk, N - i0 * kBlk), r1 = two ? min(kBlk, N - i1 * kBlk) : 0;
-    load_tile_regs<D>(Qb + (size_t)i0 * kBlk * D, r0, qreg[0]);
-    load_tile_regs<D>(dOb + (size_t)i0 * kBlk * D, r0, greg[0]);
-    load_tile_regs<D>(Qb + (size_t)i1 * kBlk * D, r1, qreg[1]);
-    load_tile_regs<D>(dOb + (size_t)i1 * kBlk * D, r1, greg[1]);
-    // thread t < 256: tile p = t / 128, kind = (t / 64) % 2 (L or D^s), query t % 64
-    const int p = tid >> 7, kind = (tid >> 6) & 1, q = tid & 63;
-    const int ii = p ? i1 : i0;
-    const bool ok = q < (p ? r1 : r0);
-    if (kind == 0) streg = ok ? Lb[ii * kBlk + q] * kLog2e : INFINITY;   // rows past the end give P = 0
-    else streg = ok ? Dsb[ii * kBlk + q] : 0.0f;
+  auto issue = [&](int s) {
+    const int ii = list[beg + s];
+    const int rows = min(kBlk, N - ii * kBlk);
+    const int off = (s & 1) * Lds::BUF;
+    issue_tile_load<D>(Qb + (size_t)ii * kBlk * D, rows, smem, off, w, l);
+    issue_tile_load<D>(dOb + (size_t)ii * kBlk * D, rows, smem, off + Lds::TILE, w, l);
+    if (tid < 128) {   // per-query statistics; rows past the end give P = 0
+      const int q = tid & 63;
+      const bool ok = q < rows;
+      if (tid < 64) streg = ok ? Lb[ii * kBlk + q] * kLog2e : INFINITY;
+      else streg = ok ? Dsb[ii * kBlk + q] : 0.0f;
+    }
   };
-  auto store_step = [&](int buf) {
-    bf16* base = tiles + buf * Lds::STEP;
-    store_tile_regs<D>(base, qreg[0]);
-    store_tile_regs<D>(base + Lds::TILE, greg[0]);
-    store_tile_regs<D>(base + 2 * Lds::TILE, qreg[1]);
-    store_tile_regs<D>(base + 3 * Lds::TILE, greg[1]);
-    stats[buf * 4 * kBlk + tid] = streg;
-  };
-  if (steps > 0) {
-    load_step(0);
-    store_step(0);
+  if (cnt > 0) {
+    issue(0);
+    if (tid < 128) stats[tid] = streg;
   }
-  __syncthreads();
-  for (int s = 0; s < steps; ++s) {
+  for (int s = 0; s < cnt; ++s) {
     const int buf = s & 1;
-    const bool two = 2 * s + 1 < cnt;
-    if (s + 1 < steps) load_step(s + 1);
-    if (par == 0 || two) {
-      const bf16* Qs = tiles + buf * Lds::STEP + par * 2 * Lds::TILE;
-      const bf16* Gs = Qs + Lds::TILE;
-      const float* Ls = stats + buf * 4 * kBlk + par * 2 * kBlk;
-      const float* Dq = Ls + kBlk;
-      f32x16 sm[2], dp[2];
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();   // tiles of step s have landed for every wave; step s-1 is fully consumed
+    if (s + 1 < cnt) issue(s + 1);
+    const unsigned char* Qs = smem + buf * Lds::BUF;
+    const unsigned char* Gs = Qs + Lds::TILE;
+    const float* Ls = stats + buf * 2 * kBlk;
+    const float* Dq = Ls + kBlk;
+    f32x16 sm = zero_f32x16(), dp = zero_f32x16();
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
-        sm[mt] = zero_f32x16();
-        dp[mt] = zero_f32x16();
-      }
+    for (int t = 0; t < KT; ++t) {
+      sm = mfma32(read_row_swz<D>(Qs, 32 * qh, t, l), kf[t], sm);
+      dp = mfma32(read_row_swz<D>(Gs, 32 * qh, t, l), vf[t], dp);
+    }
+    // P[q][key] = exp(S - L_q), dS = P (dP - D^s_q); rows q = 32 qh + c_row(r, g)
 #pragma unroll
-      for (int t = 0; t < KT; ++t)
+    for (int r4 = 0; r4 < 4; ++r4) {
+      const f32x4 lq = *reinterpret_cast<const f32x4*>(Ls + 32 * qh + 8 * r4 + 4 * g);
+      const f32x4 dq = *reinterpret_cast<const f32x4*>(Dq + 32 * qh + 8 * r4 + 4 * g);
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
-          const bf16x8 aq = *reinterpret_cast<const bf16x8*>(Qs + (32 * mt + ln) * RS + 16 * t + 8 * g);
-          sm[mt] = mfma32(aq, kf[t], sm[mt]);
-          const bf16x8 ag = *reinterpret_cast<const bf16x8*>(Gs + (32 * mt + ln) * RS + 16 * t + 8 * g);
-          dp[mt] = mfma32(ag, vf[t], dp[mt]);
-        }
-      // P[q][key] = exp(S - L_q), dS = P (dP - D^s_q); rows q = 32 mt + c_row(r, g)
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          const f32x4 lq = *reinterpret_cast<const f32x4*>(Ls + 32 * mt + 8 * r4 + 4 * g);
-          const f32x4 dq = *reinterpret_cast<const f32x4*>(Dq + 32 * mt + 8 * r4 + 4 * g);
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const float pv = kok ? fast_exp2(fmaf(sm[mt][4 * r4 + r], sl2, -lq[r])) : 0.0f;
-            sm[mt][4 * r4 + r] = pv;
-            dp[mt][4 * r4 + r] = pv * (dp[mt][4 * r4 + r] - dq[r]);
-          }
-        }
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const bf16x8 pb = c_to_operand(sm[u >> 1], u & 1);
-        const bf16x8 sb = c_to_operand(dp[u >> 1], u & 1);
-#pragma unroll
-        for (int et = 0; et < NT; ++et) {
-          const bf16x8 ag = read_tr_operand(Gs, RS, 16 * u, 32 * et, l);   // dO_i^T
-          dvT[et] = mfma32(ag, pb, dvT[et]);
-          const bf16x8 aq = read_tr_operand(Qs, RS, 16 * u, 32 * et, l);   // Q_i^T
-          dkT[et] = mfma32(aq, sb, dkT[et]);
-        }
+      for (int r = 0; r < 4; ++r) {
+        const float pv = kok ? fast_exp2(fmaf(sm[4 * r4 + r], sl2, -lq[r])) : 0.0f;
+        sm[4 * r4 + r] = pv;
+        dp[4 * r4 + r] = pv * (dp[4 * r4 + r] - dq[r]);
       }
     }
-    if (s + 1 < steps) store_step(buf ^ 1);
-    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const bf16x8 pb = c_to_operand(sm, u);
+      const bf16x8 sb = c_to_operand(dp, u);
+#pragma unroll
+      for (int et = 0; et < NT; ++et) {
+        dvT[et] = mfma32(read_tr_swz<D>(Gs, 32 * qh + 16 * u, et, l), pb, dvT[et]);   // dO_i^T P
+        dkT[et] = mfma32(read_tr_swz<D>(Qs, 32 * qh + 16 * u, et, l), sb, dkT[et]);   // Q_i^T dS
+      }
+    }
+    if (s + 1 < cnt && tid < 128) stats[(buf ^ 1) * 2 * kBlk + tid] = streg;
   }
-  // ---- add the two query-tile streams, then the linear-branch parts, and store
+  // ---- add the two query halves, then the linear-branch parts, and store
+  __syncthreads();
   float* myx = xch + (size_t)kh * (2 * NT * 16) * 64;
-  if (par == 1) {
+  if (qh == 1) {
 #pragma unroll
     for (int et = 0; et < NT; ++et)
 #pragma unroll
@@ -194,7 +145,7 @@ __global__ __launch_bounds__(256) void bwd_dkdv_mfma_kernel(
       }
   }
   __syncthreads();
-  if (par == 0 && kok) {
+  if (qh == 0 && kok) {
 #pragma unroll
     for (int et = 0; et < NT; ++et)
 #pragma unroll
@@ -217,21 +168,21 @@ __global__ __launch_bounds__(256) void bwd_dkdv_mfma_kernel(
 }
 
 // ------------------------------------------------------------------ dQ
-// Wavefront (qh, par) as in the forward kernel; S^T and dP^T are [key][query], one query per
-// lane, so L and D^s are per-lane scalars and dS^T feeds dQ^T = K^T dS^T from registers.
+// Wave (qh, kh): S^T and dP^T are [key][query], one query per lane, so L and D^s are per-lane
+// scalars and dS^T feeds dQ^T = K^T dS^T from registers.  The two kh waves hold partial sums
+// over their keys and are added at the end.
 template <int D>
-__global__ __launch_bounds__(256) void bwd_dq_mfma_kernel(
+__global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
     const bf16* __restrict__ dO, const float* __restrict__ L, const float* __restrict__ Ds,
     const int32_t* __restrict__ row_idx, const float* __restrict__ dQlin, int N, int Tn, int n_h,
     float scale, bf16* __restrict__ dQ) {
-  using Lds = StreamLds<D>;
-  constexpr int RS = Lds::RS, NT = D / 32, KT = D / 16, CH = D / 32;
+  using Lds = PairLds<D>;
+  constexpr int NT = D / 32, KT = D / 16;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  bf16* tiles = reinterpret_cast<bf16*>(smem);
   float* xch = reinterpret_cast<float*>(smem);
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
-  const int qh = w & 1, par = w >> 1;
+  const int qh = w & 1, kh = w >> 1;
   const int i = blockIdx.x, bh = blockIdx.y;
   const int q0 = i * kBlk, rows = min(kBlk, N - q0);
   const int qrow = qh * 32 + ln;
@@ -252,84 +203,52 @@ __global__ __launch_bounds__(256) void bwd_dq_mfma_kernel(
   const bf16* Kb = K + (size_t)bh * N * D;
   const bf16* Vb = V + (size_t)bh * N * D;
   const float sl2 = scale * kLog2e;
-  const int steps = (n_h + 1) >> 1;
-  u32x4 kreg[2][CH], vreg[2][CH];
-  auto load_step = [&](int s) {
-    const bool two = 2 * s + 1 < n_h;
-    const int j0 = lut[2 * s];
-    const int j1 = two ? lut[2 * s + 1] : j0;
-    const int c0 = min(kBlk, N - j0 * kBlk), c1 = two ? min(kBlk, N - j1 * kBlk) : 0;
-    load_tile_regs<D>(Kb + (size_t)j0 * kBlk * D, c0, kreg[0]);
-    load_tile_regs<D>(Vb + (size_t)j0 * kBlk * D, c0, vreg[0]);
-    load_tile_regs<D>(Kb + (size_t)j1 * kBlk * D, c1, kreg[1]);
-    load_tile_regs<D>(Vb + (size_t)j1 * kBlk * D, c1, vreg[1]);
+  auto issue = [&](int s) {
+    const int jj = lut[s];
+    const int cols = min(kBlk, N - jj * kBlk);
+    const int off = (s & 1) * Lds::BUF;
+    issue_tile_load<D>(Kb + (size_t)jj * kBlk * D, cols, smem, off, w, l);
+    issue_tile_load<D>(Vb + (size_t)jj * kBlk * D, cols, smem, off + Lds::TILE, w, l);
   };
-  auto store_step = [&](int buf) {
-    bf16* base = tiles + buf * Lds::STEP;
-    store_tile_regs<D>(base, kreg[0]);
-    store_tile_regs<D>(base + Lds::TILE, vreg[0]);
-    store_tile_regs<D>(base + 2 * Lds::TILE, kreg[1]);
-    store_tile_regs<D>(base + 3 * Lds::TILE, vreg[1]);
-  };
-  if (steps > 0) {
-    load_step(0);
-    store_step(0);
+  if (n_h > 0) issue(0);
+  for (int s = 0; s < n_h; ++s) {
+    const int buf = s & 1;
+    const int cols = min(kBlk, N - lut[s] * kBlk);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (s + 1 < n_h) issue(s + 1);
+    const unsigned char* Ks = smem + buf * Lds::BUF;
+    const unsigned char* Vs = Ks + Lds::TILE;
+    f32x16 sT = zero_f32x16(), dpT = zero_f32x16();
+#pragma unroll
+    for (int t = 0; t < KT; ++t) {
+      sT = mfma32(read_row_swz<D>(Ks, 32 * kh, t, l), qf[t], sT);
+      dpT = mfma32(read_row_swz<D>(Vs, 32 * kh, t, l), gf[t], dpT);
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      float pv = fast_exp2(fmaf(sT[r], sl2, -Lq));
+      if (cols < kBlk && 32 * kh + c_row(r, g) >= cols) pv = 0.0f;
+      dpT[r] = pv * (dpT[r] - Dq);
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const bf16x8 sb = c_to_operand(dpT, u);
+#pragma unroll
+      for (int dt = 0; dt < NT; ++dt)
+        dqT[dt] = mfma32(read_tr_swz<D>(Ks, 32 * kh + 16 * u, dt, l), sb, dqT[dt]);   // K_j^T dS^T
+    }
   }
   __syncthreads();
-  for (int s = 0; s < steps; ++s) {
-    const int buf = s & 1;
-    const bool two = 2 * s + 1 < n_h;
-    const int jmine = lut[par && two ? 2 * s + 1 : 2 * s];
-    const int cols = min(kBlk, N - jmine * kBlk);
-    if (s + 1 < steps) load_step(s + 1);
-    if (par == 0 || two) {
-      const bf16* Ks = tiles + buf * Lds::STEP + par * 2 * Lds::TILE;
-      const bf16* Vs = Ks + Lds::TILE;
-      f32x16 sT[2], dpT[2];
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
-        sT[mt] = zero_f32x16();
-        dpT[mt] = zero_f32x16();
-      }
-#pragma unroll
-      for (int t = 0; t < KT; ++t)
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
-          const bf16x8 ak = *reinterpret_cast<const bf16x8*>(Ks + (32 * mt + ln) * RS + 16 * t + 8 * g);
-          sT[mt] = mfma32(ak, qf[t], sT[mt]);
-          const bf16x8 av = *reinterpret_cast<const bf16x8*>(Vs + (32 * mt + ln) * RS + 16 * t + 8 * g);
-          dpT[mt] = mfma32(av, gf[t], dpT[mt]);
-        }
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float pv = fast_exp2(fmaf(sT[mt][r], sl2, -Lq));
-          if (cols < kBlk && 32 * mt + c_row(r, g) >= cols) pv = 0.0f;
-          dpT[mt][r] = pv * (dpT[mt][r] - Dq);
-        }
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const bf16x8 sb = c_to_operand(dpT[u >> 1], u & 1);
-#pragma unroll
-        for (int dt = 0; dt < NT; ++dt) {
-          const bf16x8 ak = read_tr_operand(Ks, RS, 16 * u, 32 * dt, l);   // K_j^T
-          dqT[dt] = mfma32(ak, sb, dqT[dt]);
-        }
-      }
-    }
-    if (s + 1 < steps) store_step(buf ^ 1);
-    __syncthreads();
-  }
   float* myx = xch + (size_t)qh * (NT * 16) * 64;
-  if (par == 1) {
+  if (kh == 1) {
 #pragma unroll
     for (int dt = 0; dt < NT; ++dt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) myx[(dt * 16 + r) * 64 + l] = dqT[dt][r];
   }
   __syncthreads();
-  if (par == 0 && qok) {
+  if (kh == 0 && qok) {
 #pragma unroll
     for (int dt = 0; dt < NT; ++dt)
 #pragma unroll
@@ -357,8 +276,7 @@ __global__ __launch_bounds__(256) void bwd_dq_mfma_kernel(
 template <int D>
 hipError_t sparse_impl(const Shape& s, const BwdArgs& a, const float* Ds, const float* dQlin,
                        const float* dKlin, const float* dVlin, hipStream_t st) {
-  const dim3 grid(s.T, s.BH);
-  constexpr int lds = StreamLds<D>::BYTES;
+  constexpr int lds = PairLds<D>::BYTES;
   SLA_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dkdv_mfma_kernel<D>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, lds));
   {
@@ -371,7 +289,7 @@ hipError_t sparse_impl(const Shape& s, const BwdArgs& a, const float* Ds, const 
                               hipFuncAttributeMaxDynamicSharedMemorySize, lds));
   {
     KernelTimer kt("bwd_sparse_q", st);
-    bwd_dq_mfma_kernel<D><<<grid, 256, lds, st>>>(
+    bwd_dq_mfma_kernel<D><<<dim3(s.T, s.BH), 256, lds, st>>>(
         (const bf16*)a.Q, (const bf16*)a.K, (const bf16*)a.V, (const bf16*)a.dO, a.L, Ds, a.row_idx,
         dQlin, s.N, s.T, s.n_h, s.scale, (bf16*)a.dQ);
   }

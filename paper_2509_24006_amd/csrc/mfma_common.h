@@ -177,6 +177,81 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const void* p, int b
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
 }
 
+// ---- swizzled row-major tiles filled by direct global -> LDS loads
+// A 64 x D bf16 tile lives in LDS unpadded (row = 2 D bytes); the 16-byte chunk c of row r sits
+// at chunk position c ^ swz(r).  With swz(r) = 4 (r % 4) + (r / 4) % 4 both access patterns of
+// the kernels are spread over the banks: one row per lane at a fixed chunk (16 consecutive rows
+// hit 16 different chunk positions) and the transposing read (4 consecutive rows x 64 bytes).
+// The tile is written by buffer loads that deposit 16 bytes per lane straight into LDS: lane L of
+// a wave-wide load fills LDS chunk L of a 1 KB run, and fetches the global chunk that belongs
+// there.  Loads beyond the tile's valid rows deposit zeros.
+template <int D>
+struct SwzTile {
+  static constexpr int CPR = D / 8;             // chunks per row
+  static constexpr int ROW_BYTES = 2 * D;
+  static constexpr int BYTES = kBlk * ROW_BYTES;
+  static constexpr int RPI = 1024 / ROW_BYTES;  // rows per wave-wide load
+  static constexpr int IPW = kBlk / RPI / 4;    // loads per wave (4 waves share a tile)
+};
+
+template <int D>
+__device__ __forceinline__ int swz(int row) {
+  return (((row & 3) << 2) | ((row >> 2) & 3)) & (D / 8 - 1);
+}
+
+typedef __attribute__((address_space(3))) void lds_void;
+
+// All four waves of a workgroup: enqueue the loads of one tile.  lds_tile: byte offset of the
+// tile inside the dynamic LDS array `smem`.
+template <int D>
+__device__ __forceinline__ void issue_tile_load(const bf16* gbase, int valid_rows, unsigned char* smem,
+                                                int lds_tile, int w, int l) {
+  using T = SwzTile<D>;
+  const __amdgpu_buffer_rsrc_t rsrc = tile_rsrc(gbase, valid_rows * T::ROW_BYTES);
+#pragma unroll
+  for (int k = 0; k < T::IPW; ++k) {
+    const int rg = 4 * k + w;
+    const int row = T::RPI * rg + l / T::CPR, pc = l % T::CPR;
+    const int voff = row * T::ROW_BYTES + ((pc ^ swz<D>(row)) << 4);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(smem + lds_tile + rg * 1024), 16, voff, 0, 0, 0);
+  }
+}
+
+// byte offset (inside a tile) of the 16-byte chunk `c` of row `row`
+template <int D>
+__device__ __forceinline__ int swz_chunk_off(int row, int c) {
+  return row * SwzTile<D>::ROW_BYTES + ((c ^ swz<D>(row)) << 4);
+}
+
+// A operand whose 32 rows are tile rows r0 + (l % 32) and whose k-values are features 16 t + 8 g ..
+template <int D>
+__device__ __forceinline__ bf16x8 read_row_swz(const unsigned char* tile, int r0, int t, int l) {
+  return *reinterpret_cast<const bf16x8*>(tile + swz_chunk_off<D>(r0 + (l & 31), 2 * t + (l >> 5)));
+}
+
+// A operand with rows = features 32 et .. and k = tile rows r0 .. r0 + 15 (r0 a multiple of 16) in
+// the order a C tile hands them over, via the transposing read (see read_tr_operand).
+template <int D>
+__device__ __forceinline__ bf16x8 read_tr_swz(const unsigned char* tile, int r0, int et, int l) {
+  typedef __attribute__((ext_vector_type(4))) short s16x4;
+  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+  const int G = l >> 4, e = (l >> 2) & 3, a = l & 3;
+  const int chunk = 4 * et + 2 * (G & 1) + (a >> 1);
+  const int row0 = r0 + 4 * (G >> 1) + e;
+  const unsigned char* p0 = tile + swz_chunk_off<D>(row0, chunk) + 8 * (a & 1);
+  const unsigned char* p1 = tile + swz_chunk_off<D>(row0 + 8, chunk) + 8 * (a & 1);
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p0));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p1));
+  const bf16x4 lo4 = *reinterpret_cast<const bf16x4*>(&lo), hi4 = *reinterpret_cast<const bf16x4*>(&hi);
+  bf16x8 r;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    r[i] = lo4[i];
+    r[4 + i] = hi4[i];
+  }
+  return r;
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 constexpr float kLog2e = 1.4426950408889634f;
