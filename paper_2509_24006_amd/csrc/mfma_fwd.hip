@@ -251,19 +251,19 @@ __global__ __launch_bounds__(256) void aggregate_mfma_kernel(const TIN* __restri
 }
 
 // ------------------------------------------------------------------ forward main kernel
-// One workgroup (4 wavefronts) per query block.  Wavefront (qh, par): qh = which 32 of the 64
-// query rows, par = which of the two key tiles of a step.  Everything is held transposed
-// (S^T = K Q^T, O^T = V^T P^T) so that each lane owns one query: softmax statistics are
-// per-lane scalars and P goes from C registers straight into the B operand of the second
-// product.
+// One workgroup (4 wavefronts) per query block, one critical key block per step.  Wavefront
+// (qh, par): qh = which 32 of the 64 query rows, par = which 32 of the step's 64 keys.
+// Everything is held transposed (S^T = K Q^T, O^T = V^T P^T) so that each lane owns one query:
+// softmax statistics are per-lane scalars and P goes from C registers straight into the B
+// operand of the second product.  Each wave runs its own online softmax over its key halves;
+// the two streams of a query half are merged at the end.  K_j and V_j go global -> LDS
+// directly (swizzled, double-buffered, one barrier per step); V is read transposed.
 template <int D>
 struct FwdLds {
-  static constexpr int KS = D + 8;                       // K tile row stride (elements)
-  static constexpr int K_ELEMS = 2 * kBlk * KS;          // two K tiles
-  static constexpr int VS = D + 32;                      // V tile row stride: rows 64 B apart modulo 256 B
-  static constexpr int V_ELEMS = 2 * kBlk * VS;          // two row-major V tiles (read transposed)
-  static constexpr int XCH_BYTES = 2 * (D / 2) * 64 * 4; // exchange of C registers between par 0/1
-  static constexpr int TILE_BYTES = (K_ELEMS + V_ELEMS) * 2;
+  static constexpr int TILE = SwzTile<D>::BYTES;
+  static constexpr int BUF = 2 * TILE;                    // K_j and V_j
+  static constexpr int XCH_BYTES = 2 * (D / 2) * 64 * 4;  // exchange of C registers between par 0/1
+  static constexpr int TILE_BYTES = 2 * BUF;
   static constexpr int BYTES = (TILE_BYTES > XCH_BYTES ? TILE_BYTES : XCH_BYTES) + 1024;
 };
 
@@ -274,10 +274,8 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
     int N, int Tn, int n_h, int n_0, int phi, float scale_log2e, bf16* __restrict__ O,
     bf16* __restrict__ Os, bf16* __restrict__ Ol, float* __restrict__ L) {
   using Lds = FwdLds<D>;
-  constexpr int KS = Lds::KS, NT = D / 32, KT = D / 16;
+  constexpr int NT = D / 32, KT = D / 16;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  bf16* Ks = reinterpret_cast<bf16*>(smem);
-  bf16* Vs = Ks + Lds::K_ELEMS;
   float* xch = reinterpret_cast<float*>(smem);
   float* ml = reinterpret_cast<float*>(smem + Lds::BYTES - 1024);   // [par][qh][32][2]
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
@@ -298,109 +296,61 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
   const int32_t* lut = row_idx + ((size_t)bh * Tn + i) * n_h;
   const bf16* Kb = K + (size_t)bh * N * D;
   const bf16* Vb = V + (size_t)bh * N * D;
-  const int steps = (n_h + 1) >> 1;
   const float c2 = scale_log2e;                    // exp(x / sqrt(d)) = exp2(x * c2)
-  constexpr int KCH = 2 * kBlk * (D / 8) / 256;    // 16-byte K chunks per thread and step
-  constexpr int VS = Lds::VS;
-  u32x4 kreg[KCH], vreg[KCH];
-  // Global loads of one step (two K tiles, two V tiles) into registers.  Buffer loads return
-  // zero past the end of a tile's valid rows, so tails and a missing second tile need no branch.
-  auto load_step = [&](int s) {
-    const int j0 = lut[2 * s];
-    const bool two = 2 * s + 1 < n_h;
-    const int j1 = two ? lut[2 * s + 1] : j0;
-    const int cols0 = min(kBlk, N - j0 * kBlk), cols1 = two ? min(kBlk, N - j1 * kBlk) : 0;
-    const __amdgpu_buffer_rsrc_t rk0 = tile_rsrc(Kb + (size_t)j0 * kBlk * D, cols0 * D * 2);
-    const __amdgpu_buffer_rsrc_t rk1 = tile_rsrc(Kb + (size_t)j1 * kBlk * D, cols1 * D * 2);
-    const __amdgpu_buffer_rsrc_t rv0 = tile_rsrc(Vb + (size_t)j0 * kBlk * D, cols0 * D * 2);
-    const __amdgpu_buffer_rsrc_t rv1 = tile_rsrc(Vb + (size_t)j1 * kBlk * D, cols1 * D * 2);
-#pragma unroll
-    for (int r = 0; r < KCH; ++r) {
-      const int c = tid + 256 * r;
-      const int p = c / (kBlk * (D / 8)), cc = c - p * (kBlk * (D / 8));   // p is a constant per r
-      kreg[r] = __builtin_amdgcn_raw_buffer_load_b128(p ? rk1 : rk0, cc * 16, 0, 0);
-    }
-#pragma unroll
-    for (int r = 0; r < KCH; ++r) {
-      const int c = tid + 256 * r;
-      const int p = c / (kBlk * (D / 8)), cc = c - p * (kBlk * (D / 8));
-      vreg[r] = __builtin_amdgcn_raw_buffer_load_b128(p ? rv1 : rv0, cc * 16, 0, 0);
-    }
+  auto issue = [&](int s) {
+    const int jj = lut[s];
+    const int cols = min(kBlk, N - jj * kBlk);
+    const int off = (s & 1) * Lds::BUF;
+    issue_tile_load<D>(Kb + (size_t)jj * kBlk * D, cols, smem, off, w, l);
+    issue_tile_load<D>(Vb + (size_t)jj * kBlk * D, cols, smem, off + Lds::TILE, w, l);
   };
-  if (steps > 0) load_step(0);
-  for (int s = 0; s < steps; ++s) {
-    const bool two = 2 * s + 1 < n_h;
-    const int jmine = lut[par && two ? 2 * s + 1 : 2 * s];
-    const int cols = min(kBlk, N - jmine * kBlk);
-    __syncthreads();   // every wave is done reading the previous step's tiles
+  if (n_h > 0) issue(0);
+  for (int s = 0; s < n_h; ++s) {
+    const int cols = min(kBlk, N - lut[s] * kBlk);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();   // tiles of step s have landed for every wave; step s-1 is fully consumed
+    if (s + 1 < n_h) issue(s + 1);
+    const unsigned char* Ks = smem + (s & 1) * Lds::BUF;
+    const unsigned char* Vs = Ks + Lds::TILE;
+    f32x16 sT = zero_f32x16();
 #pragma unroll
-    for (int r = 0; r < KCH; ++r) {
-      const int c = tid + 256 * r;
-      const int p = c / (kBlk * (D / 8)), cc = c - p * (kBlk * (D / 8));
-      const int row = cc / (D / 8), c8 = cc - row * (D / 8);
-      *reinterpret_cast<u32x4*>(Ks + (p * kBlk + row) * KS + 8 * c8) = kreg[r];
-      *reinterpret_cast<u32x4*>(Vs + (p * kBlk + row) * VS + 8 * c8) = vreg[r];
+    for (int t = 0; t < KT; ++t) sT = mfma32(read_row_swz<D>(Ks, 32 * par, t, l), qf[t], sT);
+    // ---- online softmax on raw scores (the 1/sqrt(d) and log2 e factors ride on the exp2
+    // argument); one query per lane
+    if (cols < kBlk) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (32 * par + c_row(r, g) >= cols) sT[r] = -INFINITY;
     }
-    __syncthreads();   // tiles visible
-    if (s + 1 < steps) load_step(s + 1);   // in flight during this step's arithmetic
-    if (par == 0 || two) {
-      f32x16 sT[2];
-      sT[0] = zero_f32x16();
-      sT[1] = zero_f32x16();
+    float mx = sT[0];
 #pragma unroll
-      for (int t = 0; t < KT; ++t) {
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sT[r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float mnew = fmaxf(m, mx);
+    const float moff = mnew == -INFINITY ? 0.0f : -mnew * c2;   // a half with no valid key yet
+    float psum = 0.0f;
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(Ks + (par * kBlk + 32 * mt + ln) * KS + 16 * t + 8 * g);
-          sT[mt] = mfma32(a, qf[t], sT[mt]);
-        }
-      }
-      // ---- online softmax on raw scores (the 1/sqrt(d) and log2 e factors ride on the exp2
-      // argument); one query per lane
-      if (cols < kBlk) {
+    for (int r = 0; r < 16; ++r) {
+      const float pv = fast_exp2(fmaf(sT[r], c2, moff));
+      sT[r] = pv;
+      psum += pv;
+    }
+    if (__any(mnew != m)) {   // rescale only when some query's running maximum moved
+      const float alpha = fast_exp2((m - mnew) * c2);
+      lsum *= alpha;
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
+      for (int et = 0; et < NT; ++et)
 #pragma unroll
-          for (int r = 0; r < 16; ++r)
-            if (32 * mt + c_row(r, g) >= cols) sT[mt][r] = -INFINITY;
-      }
-      float mx = sT[0][0];
+        for (int r = 0; r < 16; ++r) oT[et][r] *= alpha;
+      m = mnew;
+    }
+    lsum += psum;
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
+    for (int u = 0; u < 2; ++u) {
+      const bf16x8 pf = c_to_operand(sT, u);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sT[mt][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float mnew = fmaxf(m, mx);
-      const float moff = -mnew * c2;
-      float psum = 0.0f;
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float pv = fast_exp2(fmaf(sT[mt][r], c2, moff));
-          sT[mt][r] = pv;
-          psum += pv;
-        }
-      if (__any(mnew != m)) {   // rescale only when some query's running maximum moved
-        const float alpha = fast_exp2((m - mnew) * c2);
-        lsum *= alpha;
-#pragma unroll
-        for (int et = 0; et < NT; ++et)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) oT[et][r] *= alpha;
-        m = mnew;
-      }
-      lsum += psum;
-      bf16x8 pf[4];
-#pragma unroll
-      for (int t = 0; t < 4; ++t) pf[t] = c_to_operand(sT[t >> 1], t & 1);
-#pragma unroll
-      for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int et = 0; et < NT; ++et) {
-          const bf16x8 a = read_tr_operand(Vs + par * kBlk * VS, VS, 16 * t, 32 * et, l);
-          oT[et] = mfma32(a, pf[t], oT[et]);
-        }
+      for (int et = 0; et < NT; ++et)
+        oT[et] = mfma32(read_tr_swz<D>(Vs, 32 * par + 16 * u, et, l), pf, oT[et]);
     }
   }
   // ---- merge the two key-tile streams (par 0 / par 1) of each query half
