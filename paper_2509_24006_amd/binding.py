@@ -32,7 +32,7 @@ class sla_params(ctypes.Structure):
 class sla_sizes_t(ctypes.Structure):
     _fields_ = [("T", ctypes.c_int32), ("n_h", ctypes.c_int32), ("n_l", ctypes.c_int32),
                 ("n_0", ctypes.c_int32)] + [(n, ctypes.c_uint64) for n in (
-                    "mask_bytes", "luts_bytes", "lut_row_idx", "lut_col_ptr", "lut_col_rows", "lut_mask_t", "lut_col_order",
+                    "mask_bytes", "luts_bytes", "lut_row_idx", "lut_col_ptr", "lut_col_rows", "lut_ind", "lut_ind_t", "lut_col_order",
                     "saved_bytes", "saved_Os", "saved_Ol", "saved_L", "saved_HZ",
                     "ws_mask_bytes", "ws_mask_qbar", "ws_mask_kbar", "ws_mask_scores",
                     "ws_forward_bytes", "ws_backward_bytes")]
@@ -211,7 +211,8 @@ def lut_views(p: sla_params, luts: torch.Tensor) -> Dict[str, torch.Tensor]:
     return {"row_idx": _view(luts, z.lut_row_idx, (p.B, p.H, z.T, z.n_h), torch.int32),
             "col_ptr": _view(luts, z.lut_col_ptr, (p.B, p.H, z.T + 1), torch.int32),
             "col_rows": _view(luts, z.lut_col_rows, (p.B, p.H, z.T * z.n_h), torch.int32),
-            "mask_t": _view(luts, z.lut_mask_t, (p.B, p.H, z.T, z.T), torch.int8),
+            "ind": _view(luts, z.lut_ind, (p.B, p.H, z.T, (z.T + 15) // 16 * 16), torch.int8),
+            "ind_t": _view(luts, z.lut_ind_t, (p.B, p.H, z.T, (z.T + 15) // 16 * 16), torch.int8),
             "col_order": _view(luts, z.lut_col_order, (p.B, p.H, z.T), torch.int32)}
 
 

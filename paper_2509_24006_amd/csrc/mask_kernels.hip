@@ -215,19 +215,28 @@ __global__ void col_fill_kernel(const int8_t* __restrict__ Mc, int T, int n_h,
     if (m[(size_t)i * T] == 1) out[w++] = i;
 }
 
-// McT[j][i] = Mc[i][j], 32 x 32 tiles through LDS
-__global__ __launch_bounds__(256) void mask_transpose_kernel(const int8_t* __restrict__ Mc, int T,
-                                                             int8_t* __restrict__ McT) {
+// Marginal indicator ind[i][j] = (Mc[i][j] == 0) and its transpose, both with rows padded to Tp
+// bytes (zeros), 32 x 32 tiles through LDS.
+__global__ __launch_bounds__(256) void indicator_kernel(const int8_t* __restrict__ Mc, int T, int Tp,
+                                                        int8_t* __restrict__ ind,
+                                                        int8_t* __restrict__ indT) {
   __shared__ int8_t tile[32][33];
   const int bh = blockIdx.z, i0 = blockIdx.y * 32, j0 = blockIdx.x * 32;
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
   const int8_t* src = Mc + (size_t)bh * T * T;
-  int8_t* dst = McT + (size_t)bh * T * T;
-  for (int r = ty; r < 32; r += 8)
-    if (i0 + r < T && j0 + tx < T) tile[r][tx] = src[(size_t)(i0 + r) * T + j0 + tx];
+  int8_t* d0 = ind + (size_t)bh * T * Tp;
+  int8_t* d1 = indT + (size_t)bh * T * Tp;
+  for (int r = ty; r < 32; r += 8) {
+    const int i = i0 + r, j = j0 + tx;
+    const int8_t v = (i < T && j < T && src[(size_t)i * T + j] == 0) ? 1 : 0;
+    tile[r][tx] = v;
+    if (i < T && j < Tp) d0[(size_t)i * Tp + j] = v;
+  }
   __syncthreads();
-  for (int r = ty; r < 32; r += 8)
-    if (j0 + r < T && i0 + tx < T) dst[(size_t)(j0 + r) * T + i0 + tx] = tile[tx][r];
+  for (int r = ty; r < 32; r += 8) {
+    const int j = j0 + r, i = i0 + tx;
+    if (j < T && i < Tp) d1[(size_t)j * Tp + i] = tile[tx][r];
+  }
 }
 
 // col_order[rank] = j with rank = position of column j under (count descending, index ascending):
@@ -285,10 +294,11 @@ hipError_t launch_classify(const float* scores, const Shape& s, int8_t* Mc, int3
 }
 
 hipError_t launch_csc(const int8_t* Mc, const Shape& s, int32_t* col_ptr, int32_t* col_rows,
-                      int8_t* McT, int32_t* col_order, hipStream_t st) {
+                      int8_t* ind, int8_t* indT, int32_t* col_order, hipStream_t st) {
   {
-    KernelTimer kt("mask_transpose", st);
-    mask_transpose_kernel<<<dim3((s.T + 31) / 32, (s.T + 31) / 32, s.BH), 256, 0, st>>>(Mc, s.T, McT);
+    const int Tp = (s.T + 15) / 16 * 16;
+    KernelTimer kt("indicator", st);
+    indicator_kernel<<<dim3((Tp + 31) / 32, (Tp + 31) / 32, s.BH), 256, 0, st>>>(Mc, s.T, Tp, ind, indT);
   }
   dim3 grid((s.T + 255) / 256, s.BH);
   {

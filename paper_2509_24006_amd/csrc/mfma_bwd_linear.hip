@@ -72,7 +72,7 @@ template <int D>
 __global__ __launch_bounds__(256) void bwd_pre_mfma_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ dO, const bf16* __restrict__ W,
     const bf16* __restrict__ Os, const bf16* __restrict__ Ol, const float* __restrict__ HZ, int N,
-    int Tn, int n_0, int phi, float* __restrict__ Ds, float* __restrict__ dHZ,
+    int Tn, int n_0, int phi, float* __restrict__ Ds, bf16* __restrict__ dHZ,
     float* __restrict__ dQlin) {
   using Lds = PreLds<D>;
   constexpr int RS = Lds::RS, NT = D / 32, KT = D / 16, HT = NT / 2;
@@ -172,7 +172,7 @@ __global__ __launch_bounds__(256) void bwd_pre_mfma_kernel(
   }
   __syncthreads();
   const float Dl = dlp[qrow] + dlp[kBlk + qrow];
-  float* out = dHZ + ((size_t)bh * Tn + i) * (D * D + D);
+  bf16* out = dHZ + ((size_t)bh * Tn + i) * (D * D + D);
   // dH_i^T[b][c] = sum_q dO^l[q][b] a[q][c]; wave w owns b-tiles w, w+4, ...
   for (int bt = w; bt < NT; bt += 4) {
     f32x16 acc[NT];
@@ -190,14 +190,15 @@ __global__ __launch_bounds__(256) void bwd_pre_mfma_kernel(
 #pragma unroll
     for (int ct = 0; ct < NT; ++ct)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) out[(size_t)(32 * bt + c_row(r, g)) * D + 32 * ct + ln] = acc[ct][r];
+      for (int r = 0; r < 16; ++r)
+        out[(size_t)(32 * bt + c_row(r, g)) * D + 32 * ct + ln] = __float2bfloat16(acc[ct][r]);
   }
   // dZ_i[c] = - sum_q a[q][c] D^l_q
   if (tid < D) {
     float z = 0.0f;
     for (int q = 0; q < kBlk; ++q)
       z = fmaf(__bfloat162float(At[tid * kVS + q]), dlp[q] + dlp[kBlk + q], z);
-    out[(size_t)D * D + tid] = -z;
+    out[(size_t)D * D + tid] = __float2bfloat16(-z);
   }
   // dQ^phi^T[c][q] = (sum_b H[c][b] dO^l[q][b] - D^l_q Z[c]) / den_q; this wave: c-tiles of par
   f32x16 dq[HT];
@@ -420,7 +421,7 @@ __global__ __launch_bounds__(256) void dw_mfma_kernel(const bf16* __restrict__ O
   } while (0)
 
 template <int D>
-hipError_t pre_impl(const Shape& s, const BwdArgs& a, float* Ds, float* dHZ, float* dQlin,
+hipError_t pre_impl(const Shape& s, const BwdArgs& a, float* Ds, bf16* dHZ, float* dQlin,
                     float* dWpart, int nparts, hipStream_t st) {
   constexpr int lds = PreLds<D>::BYTES;
   SLA_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_pre_mfma_kernel<D>),
@@ -452,8 +453,9 @@ hipError_t link_impl(const Shape& s, const BwdArgs& a, const float* dHZcol, floa
 
 }  // namespace
 
-hipError_t mfma_backward_pre(const Shape& s, const BwdArgs& a, float* Ds, float* dHZ, float* dQlin,
+hipError_t mfma_backward_pre(const Shape& s, const BwdArgs& a, float* Ds, void* dHZ16, float* dQlin,
                              float* dWpart, int nparts, hipStream_t st) {
+  bf16* dHZ = reinterpret_cast<bf16*>(dHZ16);
   return s.d == 64 ? pre_impl<64>(s, a, Ds, dHZ, dQlin, dWpart, nparts, st)
                    : pre_impl<128>(s, a, Ds, dHZ, dQlin, dWpart, nparts, st);
 }

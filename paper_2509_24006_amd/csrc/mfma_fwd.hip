@@ -147,109 +147,6 @@ __global__ __launch_bounds__(256) void states_mfma_kernel(const bf16* __restrict
   }
 }
 
-// ------------------------------------------------------------------ state aggregation GEMM
-// out[i][col] = sum_k ind(i, k) in[k][col], ind(i, k) = (M[i][k] == 0), for one head:
-// a T x T by T x row_len product.  M is the mask (rows = query blocks) for H_i, Z_i, or its
-// transpose for the column sums of the backward pass.  Workgroup tile 256 x 128, k-step 32;
-// the indicator operand is built in registers from the int8 mask, the state operand is
-// staged transposed through LDS (double-buffered).
-constexpr int kAggBS = 32 + 8;  // LDS stride of the [col][32 k] tile
-
-__device__ __forceinline__ u32x2 load4_bf16(const bf16* p) { return *reinterpret_cast<const u32x2*>(p); }
-__device__ __forceinline__ u32x2 load4_bf16(const float* p) {
-  const f32x4 v = *reinterpret_cast<const f32x4*>(p);
-  bf16x4 b;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) b[i] = (__bf16)v[i];
-  return *reinterpret_cast<u32x2*>(&b);
-}
-
-template <typename TIN>
-__global__ __launch_bounds__(256) void aggregate_mfma_kernel(const TIN* __restrict__ in,
-                                                             const int8_t* __restrict__ M, int T,
-                                                             int row_len,
-                                                             float* __restrict__ out) {
-  __shared__ __attribute__((aligned(16))) bf16 Bt[2][128 * kAggBS];
-  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
-  const int n0 = blockIdx.x * 128, m0 = blockIdx.y * 256, bh = blockIdx.z;
-  const int8_t* Mb = M + (size_t)bh * T * T;
-  const TIN* inb = in + (size_t)bh * T * row_len;
-  f32x16 acc[2][4];
-#pragma unroll
-  for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-    for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = zero_f32x16();
-  // staging patch of this thread: 4 k-rows x 4 columns
-  const int fg = tid & 31, kg = tid >> 5;             // columns 4fg.., k-rows 4kg..
-  const int ksteps = (T + 31) / 32;
-  auto stage = [&](int ks, int buf) {
-    u32x2 x[4];
-    const int k0 = ks * 32 + 4 * kg;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      if (k0 + kk < T && n0 + 4 * fg + 3 < row_len)
-        x[kk] = load4_bf16(inb + (size_t)(k0 + kk) * row_len + n0 + 4 * fg);
-      else
-        x[kk] = u32x2{0u, 0u};
-    }
-    store_patch_t(Bt[buf], kAggBS, 4 * fg, 4 * kg, x);
-  };
-  stage(0, 0);
-  __syncthreads();
-  for (int ks = 0; ks < ksteps; ++ks) {
-    const int buf = ks & 1;
-    if (ks + 1 < ksteps) stage(ks + 1, buf ^ 1);
-    // indicator operand: rows m0 + 64 w + 32 mt + ln, k = 32 ks + 16 tt + 8 g + s
-    bf16x8 a[2][2];
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
-      const int i = m0 + 64 * w + 32 * mt + ln;
-#pragma unroll
-      for (int tt = 0; tt < 2; ++tt) {
-        const int k = 32 * ks + 16 * tt + 8 * g;
-        unsigned long long bytes = 0x0101010101010101ull;   // non-zero labels: indicator 0
-        if (i < T && k < T) {
-          if (k + 8 <= T && (T & 7) == 0) {
-            bytes = *reinterpret_cast<const unsigned long long*>(Mb + (size_t)i * T + k);
-          } else {
-            bytes = 0;
-#pragma unroll
-            for (int s = 0; s < 8; ++s) {
-              const unsigned long long v = (k + s < T) ? (unsigned char)Mb[(size_t)i * T + k + s] : 1u;
-              bytes |= v << (8 * s);
-            }
-          }
-        }
-#pragma unroll
-        for (int s = 0; s < 8; ++s)
-          a[mt][tt][s] = (__bf16)((((bytes >> (8 * s)) & 0xffull) == 0ull) ? 1.0f : 0.0f);
-      }
-    }
-#pragma unroll
-    for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-      for (int nt = 0; nt < 4; ++nt) {
-        const bf16x8 b =
-            *reinterpret_cast<const bf16x8*>(Bt[buf] + (32 * nt + ln) * kAggBS + 16 * tt + 8 * g);
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt) acc[mt][nt] = mfma32(a[mt][tt], b, acc[mt][nt]);
-      }
-    __syncthreads();
-  }
-  float* outb = out + (size_t)bh * T * row_len;
-#pragma unroll
-  for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-    for (int nt = 0; nt < 4; ++nt) {
-      const int col = n0 + 32 * nt + ln;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int row = m0 + 64 * w + 32 * mt + c_row(i, g);
-        if (row < T && col < row_len) outb[(size_t)row * row_len + col] = acc[mt][nt][i];
-      }
-    }
-}
-
 // ------------------------------------------------------------------ forward main kernel
 // One workgroup (4 wavefronts) per query block, one critical key block per step.  Wavefront
 // (qh, par): qh = which 32 of the 64 query rows, par = which 32 of the step's 64 keys.
@@ -534,11 +431,7 @@ hipError_t forward_impl(const Shape& s, const FwdArgs& a, bf16* hz16, bf16* WTp,
       states_mfma_kernel<D><<<dim3(s.T, s.BH), 256, 0, st>>>((const bf16*)a.K, (const bf16*)a.V, s.N, s.T,
                                                            s.phi, hz16);
     }
-    {
-      KernelTimer kt("aggregate", st);
-      aggregate_mfma_kernel<bf16><<<dim3((row_len + 127) / 128, (s.T + 255) / 256, s.BH), 256, 0, st>>>(
-          hz16, a.Mc, s.T, row_len, a.HZ);
-    }
+    SLA_TRY(mfma_aggregate(hz16, a.ind, s, a.HZ, st));
   } else if (a.Os) {   // saved states must read as zero
     KernelTimer kt("fill_zero", st);
     fill_zero_f32_kernel<<<1024, 256, 0, st>>>(a.HZ, (size_t)s.BH * s.T * row_len);
@@ -556,15 +449,6 @@ hipError_t forward_impl(const Shape& s, const FwdArgs& a, bf16* hz16, bf16* WTp,
 }
 
 }  // namespace
-
-hipError_t mfma_aggregate_f32(const float* in, const int8_t* M, const Shape& s, float* out,
-                              hipStream_t st) {
-  const int row_len = s.state_row();
-  KernelTimer kt("aggregate", st);
-  aggregate_mfma_kernel<float><<<dim3((row_len + 127) / 128, (s.T + 255) / 256, s.BH), 256, 0, st>>>(
-      in, M, s.T, row_len, out);
-  return hipGetLastError();
-}
 
 size_t mfma_forward_ws_bytes(const Shape& s) {
   return align_up((size_t)s.BH * s.T * s.state_row() * 2) + align_up((size_t)s.d * s.d * 2);

@@ -860,9 +860,7 @@ hipError_t backward_impl(const Shape& s, const BwdArgs& a, hipStream_t st) {
       bwd_linear_q_kernel<T, D><<<grid, kThreads, lds, st>>>((const T*)a.Q, w.dOl, w.Dl, a.HZ, s.N, s.T,
                                                           s.phi, w.dHZ, w.dQlin);
     }
-    if constexpr (sizeof(T) == 2) {
-      SLA_TRY(mfma_aggregate_f32(w.dHZ, a.McT, s, w.dHZcol, st));
-    } else {
+    {
       KernelTimer kt("aggregate", st);
       aggregate_kernel<<<dim3((row_len + kThreads - 1) / kThreads, s.T, s.BH), kThreads, 0, st>>>(
         w.dHZ, a.Mc, s.T, row_len, 1, w.dHZcol);
@@ -875,10 +873,7 @@ hipError_t backward_impl(const Shape& s, const BwdArgs& a, hipStream_t st) {
                                                            s.T, s.phi, w.dKlin, w.dVlin);
     }
   }
-  if constexpr (sizeof(T) == 2) {
-    SLA_TRY(mfma_backward_sparse(s, a, w.Ds, lin ? w.dQlin : nullptr, lin ? w.dKlin : nullptr,
-                                 lin ? w.dVlin : nullptr, st));
-  } else {
+  {
     const size_t lds = sizeof(float) * (3 * kBlk * LD + 2 * kBlk * 65);
     SLA_TRY(set_lds(bwd_sparse_kv_kernel<T, D>, lds));
     {
@@ -903,13 +898,13 @@ hipError_t backward_impl(const Shape& s, const BwdArgs& a, hipStream_t st) {
 hipError_t backward_bf16(const Shape& s, const BwdArgs& a, hipStream_t st) {
   const BwdWs w = carve_bwd(s, a.ws);
   const bool lin = s.n_0 > 0;
-  SLA_TRY(mfma_backward_pre(s, a, w.Ds, w.dHZ, w.dQlin, w.dWpart, w.nparts, st));
+  SLA_TRY(mfma_backward_pre(s, a, w.Ds, w.dHZ, w.dQlin, w.dWpart, w.nparts, st));   // dHZ holds bf16 rows
   {
     KernelTimer kt("dw_reduce", st);
     dw_reduce_kernel<<<(s.d * s.d + 255) / 256, 256, 0, st>>>(w.dWpart, w.nparts, s.d * s.d, a.dW);
   }
   if (lin) {
-    SLA_TRY(mfma_aggregate_f32(w.dHZ, a.McT, s, w.dHZcol, st));
+    SLA_TRY(mfma_aggregate(w.dHZ, a.indT, s, w.dHZcol, st));
     SLA_TRY(mfma_backward_link(s, a, w.dHZcol, w.dKlin, w.dVlin, st));
   }
   return mfma_backward_sparse(s, a, w.Ds, lin ? w.dQlin : nullptr, lin ? w.dKlin : nullptr,

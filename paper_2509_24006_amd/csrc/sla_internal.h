@@ -31,12 +31,13 @@ hipError_t launch_scores(const float* qbar, const float* kbar, const Shape& s, f
 hipError_t launch_classify(const float* scores, const Shape& s, int8_t* Mc, int32_t* row_idx,
                            hipStream_t st);
 hipError_t launch_csc(const int8_t* Mc, const Shape& s, int32_t* col_ptr, int32_t* col_rows,
-                      int8_t* McT, int32_t* col_order, hipStream_t st);
+                      int8_t* ind, int8_t* indT, int32_t* col_order, hipStream_t st);
 
 // ---- float-arithmetic path (simt_kernels.hip): every contraction in fp32 FMA
 struct FwdArgs {
   const void *Q, *K, *V, *W;
   const int8_t* Mc;
+  const int8_t* ind;   // marginal indicator, padded
   const int32_t* row_idx;
   void* O;
   void *Os, *Ol;   // may be null (inference)
@@ -49,7 +50,7 @@ hipError_t simt_forward(const Shape& s, const FwdArgs& a, hipStream_t st);
 struct BwdArgs {
   const void *Q, *K, *V, *W, *dO;
   const int8_t* Mc;
-  const int8_t* McT;   // transposed mask
+  const int8_t* indT;  // marginal indicator, transposed and padded
   const int32_t *row_idx, *col_ptr, *col_rows, *col_order;
   const void *Os, *Ol;
   const float *L, *HZ;
@@ -67,12 +68,11 @@ hipError_t simt_backward(const Shape& s, const BwdArgs& a, hipStream_t st);
 // ---- bf16 matrix-core path (mfma_fwd.hip)
 size_t mfma_forward_ws_bytes(const Shape& s);
 hipError_t mfma_forward(const Shape& s, const FwdArgs& a, char* ws, hipStream_t st);
-// out[i] = sum of the float state rows in[k] with M[i][k] == 0 (bf16 products, float sums)
-hipError_t mfma_aggregate_f32(const float* in, const int8_t* M, const Shape& s, float* out,
-                              hipStream_t st);
+// out[i] = sum over k with ind[i][k] = 1 of the bf16 state rows in[k] (mfma_aggregate.hip)
+hipError_t mfma_aggregate(const void* in, const int8_t* ind, const Shape& s, float* out, hipStream_t st);
 
 // linear branch and Proj gradients on the matrix cores (mfma_bwd_linear.hip)
-hipError_t mfma_backward_pre(const Shape& s, const BwdArgs& a, float* Ds, float* dHZ, float* dQlin,
+hipError_t mfma_backward_pre(const Shape& s, const BwdArgs& a, float* Ds, void* dHZ16, float* dQlin,
                              float* dWpart, int nparts, hipStream_t st);
 hipError_t mfma_backward_link(const Shape& s, const BwdArgs& a, const float* dHZcol, float* dKlin,
                               float* dVlin, hipStream_t st);

@@ -41,10 +41,15 @@ def run_gpu(x, dtype: str, k_h: float, k_l: float, phi: int = 0, backward: bool 
 
 
 def check_luts(Mc: np.ndarray, row_idx: np.ndarray, col_ptr: np.ndarray, col_rows: np.ndarray,
-               mask_t: np.ndarray = None, col_order: np.ndarray = None):
+               ind: np.ndarray = None, ind_t: np.ndarray = None, col_order: np.ndarray = None):
     B, H, T, _ = Mc.shape
-    if mask_t is not None:
-        assert np.array_equal(mask_t, np.swapaxes(Mc, -1, -2))
+    if ind is not None:
+        Tp = ind.shape[-1]
+        want = np.zeros((B, H, T, Tp), np.int8)
+        want[..., :T] = (Mc == 0)
+        assert np.array_equal(ind, want)
+        want[..., :T] = np.swapaxes(Mc == 0, -1, -2)
+        assert np.array_equal(ind_t, want)
     if col_order is not None:
         cnt = (Mc == 1).sum(-2)
         for b in range(B):

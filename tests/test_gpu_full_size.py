@@ -35,7 +35,7 @@ def test_wan_shaped_layer_against_oracle(oracle):
     assert np.array_equal(sla.mask_ws_views(p, ws)["scores"].cpu().numpy(), so)
     assert np.array_equal(Mc.cpu().numpy(), Mo)
     v = {k: t.cpu().numpy() for k, t in sla.lut_views(p, luts).items()}
-    check_luts(Mo[:, :2], v["row_idx"][:, :2], v["col_ptr"][:, :2], v["col_rows"][:, :2], v["mask_t"][:, :2])
+    check_luts(Mo[:, :2], v["row_idx"][:, :2], v["col_ptr"][:, :2], v["col_rows"][:, :2], v["ind"][:, :2], v["ind_t"][:, :2], v["col_order"][:, :2])
     print("masks of 12 heads identical", flush=True)
     # the same two heads as a call of their own: identical results, and dW to compare
     xs = {k: (np.ascontiguousarray(a[:, heads]) if a.ndim == 4 else a) for k, a in x_all.items()}

@@ -46,7 +46,7 @@ def _full_case(oracle, x, dtype, k_h, k_l, phi=0, floor_rms=0.0):
     # mask step: bit-exact
     assert np.array_equal(r["scores"], s), "pooled scores differ bitwise"
     assert np.array_equal(r["Mc"], Mc), "mask differs"
-    check_luts(r["Mc"], r["row_idx"], r["col_ptr"], r["col_rows"], r["mask_t"], r["col_order"])
+    check_luts(r["Mc"], r["row_idx"], r["col_ptr"], r["col_rows"], r["ind"], r["ind_t"], r["col_order"])
     tol = TOL[dtype]
     for k in ("O", "Os", "Ol", "Hi", "Zi"):
         _compare(k, r[k], f[k], tol)
@@ -106,7 +106,7 @@ def test_classify_given_scores_with_ties(oracle):
     torch.cuda.synchronize()
     assert np.array_equal(Mc.cpu().numpy(), ref)
     v = {k: t.cpu().numpy() for k, t in sla.lut_views(p, luts).items()}
-    check_luts(ref, v["row_idx"], v["col_ptr"], v["col_rows"], v["mask_t"], v["col_order"])
+    check_luts(ref, v["row_idx"], v["col_ptr"], v["col_rows"], v["ind"], v["ind_t"], v["col_order"])
 
 
 def test_forward_without_saved_matches(oracle):
