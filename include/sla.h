@@ -73,7 +73,10 @@ typedef struct sla_sizes_t {
   uint64_t saved_Os;          /* dtype [B,H,N,d]     O^s                                    */
   uint64_t saved_Ol;          /* dtype [B,H,N,d]     O^l                                    */
   uint64_t saved_L;           /* float [B,H,N]       L = m + log l                          */
-  uint64_t saved_HZ;          /* float [B,H,T] state rows: H_i (transposed), Z_i            */
+  uint64_t saved_HZ;          /* float tensors: float [B,H,T] state rows (H_i transposed, then Z_i);
+                                 bf16 tensors: bf16 [B,H,T,d*d] (H_i transposed) here and ...   */
+  uint64_t saved_Z;           /* ... float [B,H,T,d] (Z_i) here; float tensors: = saved_HZ + 4 d d,
+                                 rows d*d + d floats apart                                       */
   uint64_t ws_mask_bytes;
   uint64_t ws_mask_qbar;      /* float [B,H,T,d]     pool(Q), left in the workspace         */
   uint64_t ws_mask_kbar;      /* float [B,H,T,d]     pool(K)                                */

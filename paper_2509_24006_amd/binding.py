@@ -33,7 +33,7 @@ class sla_sizes_t(ctypes.Structure):
     _fields_ = [("T", ctypes.c_int32), ("n_h", ctypes.c_int32), ("n_l", ctypes.c_int32),
                 ("n_0", ctypes.c_int32)] + [(n, ctypes.c_uint64) for n in (
                     "mask_bytes", "luts_bytes", "lut_row_idx", "lut_col_ptr", "lut_col_rows", "lut_ind", "lut_ind_t", "lut_col_order",
-                    "saved_bytes", "saved_Os", "saved_Ol", "saved_L", "saved_HZ",
+                    "saved_bytes", "saved_Os", "saved_Ol", "saved_L", "saved_HZ", "saved_Z",
                     "ws_mask_bytes", "ws_mask_qbar", "ws_mask_kbar", "ws_mask_scores",
                     "ws_forward_bytes", "ws_backward_bytes")]
 
@@ -197,13 +197,18 @@ def saved_views(p: sla_params, saved: torch.Tensor) -> Dict[str, torch.Tensor]:
     z = sla_sizes(p)
     dt = torch.float32 if p.dtype == SLA_F32 else torch.bfloat16
     d = p.d
-    HZ = _view(saved, z.saved_HZ, (p.B, p.H, z.T, d * d + d), torch.float32)
+    if p.dtype == SLA_F32:
+        HZ = _view(saved, z.saved_HZ, (p.B, p.H, z.T, d * d + d), torch.float32)
+        Hi = HZ[..., :d * d].view(p.B, p.H, z.T, d, d).transpose(-1, -2)
+        Zi = HZ[..., d * d:]
+    else:
+        Hi = _view(saved, z.saved_HZ, (p.B, p.H, z.T, d, d), torch.bfloat16).transpose(-1, -2)
+        Zi = _view(saved, z.saved_Z, (p.B, p.H, z.T, d), torch.float32)
     return {"Os": _view(saved, z.saved_Os, (p.B, p.H, p.N, d), dt),
             "Ol": _view(saved, z.saved_Ol, (p.B, p.H, p.N, d), dt),
             "L": _view(saved, z.saved_L, (p.B, p.H, p.N), torch.float32),
             # H_i[c][e] is stored transposed: element e*d + c
-            "Hi": HZ[..., :d * d].view(p.B, p.H, z.T, d, d).transpose(-1, -2),
-            "Zi": HZ[..., d * d:]}
+            "Hi": Hi, "Zi": Zi}
 
 
 def lut_views(p: sla_params, luts: torch.Tensor) -> Dict[str, torch.Tensor]:

@@ -72,6 +72,7 @@ void fill_sizes(const Shape& s, sla_sizes_t* o) {
   o->saved_L = off;
   off += align_up(BH * N * 4);
   o->saved_HZ = off;
+  o->saved_Z = s.dtype == SLA_BF16 ? off + state_z_offset(s) : off + d * d * 4;
   const size_t state = align_up(BH * T * (size_t)s.state_row() * 4);
   off += state;
   o->saved_bytes = off;

@@ -26,8 +26,9 @@ __device__ __forceinline__ void ind4(unsigned x, unsigned& lo, unsigned& hi) {
 
 __global__ __launch_bounds__(256, 2) void aggregate_mfma_kernel(const bf16* __restrict__ in,
                                                                 const int8_t* __restrict__ ind,
-                                                                int T, int Tp, int row_len,
-                                                                float* __restrict__ out) {
+                                                                int T, int Tp, int row_len, int dd,
+                                                                bf16* __restrict__ outH,
+                                                                float* __restrict__ outZ) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
   const int n0 = blockIdx.x * 128, m0 = blockIdx.y * 256, bh = blockIdx.z;
@@ -92,7 +93,9 @@ __global__ __launch_bounds__(256, 2) void aggregate_mfma_kernel(const bf16* __re
       }
     }
   }
-  float* outb = out + (size_t)bh * T * row_len;
+  // matrix part in bf16 (it is consumed as a bf16 MFMA operand), vector part in float
+  bf16* oh = outH + (size_t)bh * T * dd;
+  float* oz = outZ + (size_t)bh * T * (row_len - dd);
 #pragma unroll
   for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
@@ -101,15 +104,18 @@ __global__ __launch_bounds__(256, 2) void aggregate_mfma_kernel(const bf16* __re
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int row = m0 + 64 * w + 32 * mt + c_row(i, g);
-        if (row < T && col < row_len) outb[(size_t)row * row_len + col] = acc[mt][nt][i];
+        if (row < T && col < dd) oh[(size_t)row * dd + col] = __float2bfloat16(acc[mt][nt][i]);
+        else if (row < T && col < row_len) oz[(size_t)row * (row_len - dd) + col - dd] = acc[mt][nt][i];
       }
     }
 }
 
 }  // namespace
 
-// out[i] = sum over k with ind[i][k] = 1 of the bf16 state rows in[k]; ind is [BH][T][Tp] int8
-hipError_t mfma_aggregate(const void* in, const int8_t* ind, const Shape& s, float* out, hipStream_t st) {
+// out[i] = sum over k with ind[i][k] = 1 of the bf16 state rows in[k] (d*d + d values each); ind is
+// [BH][T][Tp] int8.  The d x d part goes to outH (bf16 [BH][T][d*d]), the d part to outZ (float).
+hipError_t mfma_aggregate(const void* in, const int8_t* ind, const Shape& s, void* outH, float* outZ,
+                          hipStream_t st) {
   const int row_len = s.state_row();
   const int Tp = (s.T + 15) / 16 * 16;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(aggregate_mfma_kernel),
@@ -117,7 +123,7 @@ hipError_t mfma_aggregate(const void* in, const int8_t* ind, const Shape& s, flo
   if (e != hipSuccess) return e;
   KernelTimer kt("aggregate", st);
   aggregate_mfma_kernel<<<dim3((row_len + 127) / 128, (s.T + 255) / 256, s.BH), 256, 2 * kTileB, st>>>(
-      (const bf16*)in, ind, s.T, Tp, row_len, out);
+      (const bf16*)in, ind, s.T, Tp, row_len, s.d * s.d, (bf16*)outH, outZ);
   return hipGetLastError();
 }
 

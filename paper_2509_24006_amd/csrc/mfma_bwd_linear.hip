@@ -38,20 +38,15 @@ __device__ __forceinline__ float phi_val(float x, int phi, float mx, float inv) 
   return phi == 0 ? fast_exp2((x - mx) * kLog2e) * inv : (x > 0.0f ? x + 1.0f : fast_exp2(x * kLog2e));
 }
 
-// Stages a d x d float matrix stored [b][a] (b-major) into LDS as bf16 [a][b] (stride RS).
+// Stages a d x d bf16 matrix stored [b][a] (b-major) into LDS transposed, [a][b] (stride RS).
 template <int D>
-__device__ __forceinline__ void stage_matrix_t(const float* __restrict__ src, bf16* dst, int RS) {
+__device__ __forceinline__ void stage_matrix_t(const bf16* __restrict__ src, bf16* dst, int RS) {
   for (int pidx = threadIdx.x; pidx < (D / 4) * (D / 4); pidx += 256) {
     const int a4 = pidx % (D / 4), b4 = pidx / (D / 4);
     u32x2 x[4];
 #pragma unroll
-    for (int bb = 0; bb < 4; ++bb) {
-      const f32x4 v = *reinterpret_cast<const f32x4*>(src + (size_t)(4 * b4 + bb) * D + 4 * a4);
-      bf16x4 h;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) h[i] = (__bf16)v[i];
-      x[bb] = *reinterpret_cast<u32x2*>(&h);
-    }
+    for (int bb = 0; bb < 4; ++bb)
+      x[bb] = *reinterpret_cast<const u32x2*>(src + (size_t)(4 * b4 + bb) * D + 4 * a4);
     store_patch_t(dst, RS, 4 * a4, 4 * b4, x);
   }
 }
@@ -71,7 +66,8 @@ struct PreLds {
 template <int D>
 __global__ __launch_bounds__(256) void bwd_pre_mfma_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ dO, const bf16* __restrict__ W,
-    const bf16* __restrict__ Os, const bf16* __restrict__ Ol, const float* __restrict__ HZ, int N,
+    const bf16* __restrict__ Os, const bf16* __restrict__ Ol, const bf16* __restrict__ H16,
+    const float* __restrict__ Zs, int N,
     int Tn, int n_0, int phi, float* __restrict__ Ds, bf16* __restrict__ dHZ,
     float* __restrict__ dQlin) {
   using Lds = PreLds<D>;
@@ -109,8 +105,8 @@ __global__ __launch_bounds__(256) void bwd_pre_mfma_kernel(
     if (g == 0 && qok) Ds[(size_t)bh * N + q0 + qrow] = ds;
   }
   if (n_0 == 0) return;   // no linear branch: nothing else to do (uniform over the grid)
-  const float* Hrow = HZ + ((size_t)bh * Tn + i) * (D * D + D);
-  const float* Z = Hrow + D * D;
+  const bf16* Hrow = H16 + ((size_t)bh * Tn + i) * (D * D);
+  const float* Z = Zs + ((size_t)bh * Tn + i) * D;
   stage_matrix_t<D>(Hrow, Hs, RS);
   // dO^l^T[b][q] = sum_e W[b][e] dO[q][e]; this wave: b-tiles par*HT .. par*HT+HT-1
   f32x16 gl[HT];
@@ -262,7 +258,8 @@ struct LinkLds {
 
 template <int D>
 __global__ __launch_bounds__(256) void bwd_link_mfma_kernel(
-    const bf16* __restrict__ K, const bf16* __restrict__ V, const float* __restrict__ dHZcol, int N,
+    const bf16* __restrict__ K, const bf16* __restrict__ V, const bf16* __restrict__ dH16,
+    const float* __restrict__ dZs, int N,
     int Tn, int phi, float* __restrict__ dKlin, float* __restrict__ dVlin) {
   using Lds = LinkLds<D>;
   constexpr int RS = Lds::RS, NT = D / 32, KT = D / 16, HT = NT / 2;
@@ -276,8 +273,8 @@ __global__ __launch_bounds__(256) void bwd_link_mfma_kernel(
   const int nrow = nh * 32 + ln;
   const bool nok = nrow < cnt;
   const size_t noff = ((size_t)bh * N + n0 + nrow) * D;
-  const float* Hrow = dHZcol + ((size_t)bh * Tn + j) * (D * D + D);   // dH^T stored [b][a]
-  const float* dZ = Hrow + D * D;
+  const bf16* Hrow = dH16 + ((size_t)bh * Tn + j) * (D * D);   // dH^T stored [b][a]
+  const float* dZ = dZs + ((size_t)bh * Tn + j) * D;
   stage_matrix_t<D>(Hrow, Hs, RS);
   bf16x8 kf[KT], vf[KT];
 #pragma unroll
@@ -299,7 +296,7 @@ __global__ __launch_bounds__(256) void bwd_link_mfma_kernel(
     f32x16 acc = zero_f32x16();
 #pragma unroll
     for (int t = 0; t < KT; ++t) {
-      const bf16x8 a = cvt8(Hrow + (size_t)(32 * bt + ln) * D + 16 * t + 8 * g);
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(Hrow + (size_t)(32 * bt + ln) * D + 16 * t + 8 * g);
       acc = mfma32(a, kp[t], acc);
     }
     if (nok) {
@@ -430,7 +427,8 @@ hipError_t pre_impl(const Shape& s, const BwdArgs& a, float* Ds, bf16* dHZ, floa
     KernelTimer kt("bwd_pre", st);
     bwd_pre_mfma_kernel<D><<<dim3(s.T, s.BH), 256, lds, st>>>(
         (const bf16*)a.Q, (const bf16*)a.dO, (const bf16*)a.W, (const bf16*)a.Os, (const bf16*)a.Ol,
-        a.HZ, s.N, s.T, s.n_0, s.phi, Ds, dHZ, dQlin);
+        (const bf16*)a.HZ, (const float*)((const char*)a.HZ + state_z_offset(s)), s.N, s.T, s.n_0, s.phi,
+        Ds, dHZ, dQlin);
   }
   {
     KernelTimer kt("dw_partial", st);
@@ -440,13 +438,14 @@ hipError_t pre_impl(const Shape& s, const BwdArgs& a, float* Ds, bf16* dHZ, floa
 }
 
 template <int D>
-hipError_t link_impl(const Shape& s, const BwdArgs& a, const float* dHZcol, float* dKlin,
+hipError_t link_impl(const Shape& s, const BwdArgs& a, const void* dHZcol, float* dKlin,
                      float* dVlin, hipStream_t st) {
   constexpr int lds = LinkLds<D>::BYTES;
   SLA_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_link_mfma_kernel<D>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, lds));
   KernelTimer kt("bwd_link", st);
-  bwd_link_mfma_kernel<D><<<dim3(s.T, s.BH), 256, lds, st>>>((const bf16*)a.K, (const bf16*)a.V, dHZcol,
+  bwd_link_mfma_kernel<D><<<dim3(s.T, s.BH), 256, lds, st>>>((const bf16*)a.K, (const bf16*)a.V, (const bf16*)dHZcol,
+                                                           (const float*)((const char*)dHZcol + state_z_offset(s)),
                                                            s.N, s.T, s.phi, dKlin, dVlin);
   return hipGetLastError();
 }
@@ -460,7 +459,7 @@ hipError_t mfma_backward_pre(const Shape& s, const BwdArgs& a, float* Ds, void* 
                    : pre_impl<128>(s, a, Ds, dHZ, dQlin, dWpart, nparts, st);
 }
 
-hipError_t mfma_backward_link(const Shape& s, const BwdArgs& a, const float* dHZcol, float* dKlin,
+hipError_t mfma_backward_link(const Shape& s, const BwdArgs& a, const void* dHZcol, float* dKlin,
                               float* dVlin, hipStream_t st) {
   return s.d == 64 ? link_impl<64>(s, a, dHZcol, dKlin, dVlin, st)
                    : link_impl<128>(s, a, dHZcol, dKlin, dVlin, st);

@@ -167,7 +167,8 @@ struct FwdLds {
 template <int D>
 __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
-    const bf16* __restrict__ WTp, const int32_t* __restrict__ row_idx, const float* __restrict__ HZ,
+    const bf16* __restrict__ WTp, const int32_t* __restrict__ row_idx, const bf16* __restrict__ H16,
+    const float* __restrict__ Zs,
     int N, int Tn, int n_h, int n_0, int phi, float scale_log2e, bf16* __restrict__ O,
     bf16* __restrict__ Os, bf16* __restrict__ Ol, float* __restrict__ L) {
   using Lds = FwdLds<D>;
@@ -322,8 +323,8 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
       sum += __shfl_xor(sum, 32, 64);
       qinv = 1.0f / sum;
     }
-    const float* Hrow = HZ + ((size_t)bh * Tn + i) * (D * D + D);
-    const float* Z = Hrow + D * D;
+    const bf16* Hrow = H16 + ((size_t)bh * Tn + i) * (D * D);
+    const float* Z = Zs + ((size_t)bh * Tn + i) * D;
     bf16x8 qp[KT];
     float den = 0.0f;
 #pragma unroll
@@ -348,7 +349,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
       f32x16 acc = zero_f32x16();
 #pragma unroll
       for (int t = 0; t < KT; ++t) {
-        const bf16x8 a = cvt8(Hrow + (size_t)(32 * et + ln) * D + 16 * t + 8 * g);
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(Hrow + (size_t)(32 * et + ln) * D + 16 * t + 8 * g);
         acc = mfma32(a, qp[t], acc);
       }
 #pragma unroll
@@ -421,6 +422,7 @@ __global__ void fill_zero_f32_kernel(float* __restrict__ p, size_t n) {
 template <int D>
 hipError_t forward_impl(const Shape& s, const FwdArgs& a, bf16* hz16, bf16* WTp, hipStream_t st) {
   const int row_len = s.state_row();
+  float* Zs = reinterpret_cast<float*>(reinterpret_cast<char*>(a.HZ) + state_z_offset(s));
   if (s.n_0 > 0) {
     {
       KernelTimer kt("prep_w", st);
@@ -431,7 +433,7 @@ hipError_t forward_impl(const Shape& s, const FwdArgs& a, bf16* hz16, bf16* WTp,
       states_mfma_kernel<D><<<dim3(s.T, s.BH), 256, 0, st>>>((const bf16*)a.K, (const bf16*)a.V, s.N, s.T,
                                                            s.phi, hz16);
     }
-    SLA_TRY(mfma_aggregate(hz16, a.ind, s, a.HZ, st));
+    SLA_TRY(mfma_aggregate(hz16, a.ind, s, a.HZ, Zs, st));
   } else if (a.Os) {   // saved states must read as zero
     KernelTimer kt("fill_zero", st);
     fill_zero_f32_kernel<<<1024, 256, 0, st>>>(a.HZ, (size_t)s.BH * s.T * row_len);
@@ -442,7 +444,7 @@ hipError_t forward_impl(const Shape& s, const FwdArgs& a, bf16* hz16, bf16* WTp,
   {
     KernelTimer kt("fwd_sparse", st);
     fwd_mfma_kernel<D><<<dim3(s.T, s.BH), 256, lds, st>>>(
-        (const bf16*)a.Q, (const bf16*)a.K, (const bf16*)a.V, WTp, a.row_idx, a.HZ, s.N, s.T, s.n_h,
+        (const bf16*)a.Q, (const bf16*)a.K, (const bf16*)a.V, WTp, a.row_idx, (const bf16*)a.HZ, Zs, s.N, s.T, s.n_h,
         s.n_0, s.phi, s.scale * kLog2e, (bf16*)a.O, (bf16*)a.Os, (bf16*)a.Ol, a.L);
   }
   return hipGetLastError();

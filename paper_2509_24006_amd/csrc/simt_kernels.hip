@@ -904,7 +904,8 @@ hipError_t backward_bf16(const Shape& s, const BwdArgs& a, hipStream_t st) {
     dw_reduce_kernel<<<(s.d * s.d + 255) / 256, 256, 0, st>>>(w.dWpart, w.nparts, s.d * s.d, a.dW);
   }
   if (lin) {
-    SLA_TRY(mfma_aggregate(w.dHZ, a.indT, s, w.dHZcol, st));
+    SLA_TRY(mfma_aggregate(w.dHZ, a.indT, s, w.dHZcol,
+                           reinterpret_cast<float*>(reinterpret_cast<char*>(w.dHZcol) + state_z_offset(s)), st));
     SLA_TRY(mfma_backward_link(s, a, w.dHZcol, w.dKlin, w.dVlin, st));
   }
   return mfma_backward_sparse(s, a, w.Ds, lin ? w.dQlin : nullptr, lin ? w.dKlin : nullptr,

@@ -69,12 +69,16 @@ hipError_t simt_backward(const Shape& s, const BwdArgs& a, hipStream_t st);
 size_t mfma_forward_ws_bytes(const Shape& s);
 hipError_t mfma_forward(const Shape& s, const FwdArgs& a, char* ws, hipStream_t st);
 // out[i] = sum over k with ind[i][k] = 1 of the bf16 state rows in[k] (mfma_aggregate.hip)
-hipError_t mfma_aggregate(const void* in, const int8_t* ind, const Shape& s, float* out, hipStream_t st);
+hipError_t mfma_aggregate(const void* in, const int8_t* ind, const Shape& s, void* outH, float* outZ,
+                          hipStream_t st);
+// bf16 tensors keep the aggregated states as a bf16 block [BH][T][d*d] (matrices, transposed)
+// followed by a float block [BH][T][d] (vectors); this is the byte offset of the second block.
+inline size_t state_z_offset(const Shape& s) { return ((size_t)s.BH * s.T * s.d * s.d * 2 + 255) / 256 * 256; }
 
 // linear branch and Proj gradients on the matrix cores (mfma_bwd_linear.hip)
 hipError_t mfma_backward_pre(const Shape& s, const BwdArgs& a, float* Ds, void* dHZ16, float* dQlin,
                              float* dWpart, int nparts, hipStream_t st);
-hipError_t mfma_backward_link(const Shape& s, const BwdArgs& a, const float* dHZcol, float* dKlin,
+hipError_t mfma_backward_link(const Shape& s, const BwdArgs& a, const void* dHZcol, float* dKlin,
                               float* dVlin, hipStream_t st);
 
 // Brackets one kernel launch with events when profiling is on (profile.hip).

@@ -23,7 +23,7 @@ def test_exports_match_header():
 
 def test_struct_layout_matches_header():
     assert ctypes.sizeof(sla.sla_params) == 48
-    assert ctypes.sizeof(sla.sla_sizes_t) == 16 + 19 * 8
+    assert ctypes.sizeof(sla.sla_sizes_t) == 16 + 20 * 8
 
 
 def test_sizes_and_counts():
