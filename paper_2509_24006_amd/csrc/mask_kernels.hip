@@ -167,13 +167,26 @@ __global__ __launch_bounds__(256) void classify_kernel(const float* __restrict__
 }
 
 // ---------------------------------------------------------------- column tables (CSC)
-__global__ void col_count_kernel(const int8_t* __restrict__ Mc, int T, int32_t* __restrict__ cnt) {
-  const int j = blockIdx.x * blockDim.x + threadIdx.x, bh = blockIdx.y;
-  if (j >= T) return;
+// Both column kernels: a workgroup owns 32 columns, its 8 wavefront-halves own 8 row ranges;
+// threads of a row range read 32 adjacent bytes of a mask row.
+__global__ __launch_bounds__(256) void col_count_kernel(const int8_t* __restrict__ Mc, int T,
+                                                        int32_t* __restrict__ cnt) {
+  __shared__ int part[8][32];
+  const int c = threadIdx.x & 31, rp = threadIdx.x >> 5;
+  const int j = blockIdx.x * 32 + c, bh = blockIdx.y;
+  const int chunk = (T + 7) / 8, lo = min(T, rp * chunk), hi = min(T, lo + chunk);
   const int8_t* m = Mc + (size_t)bh * T * T + j;
-  int c = 0;
-  for (int i = 0; i < T; ++i) c += (m[(size_t)i * T] == 1);
-  cnt[(size_t)bh * (T + 1) + j] = c;
+  int n = 0;
+  if (j < T)
+    for (int i = lo; i < hi; ++i) n += (m[(size_t)i * T] == 1);
+  part[rp][c] = n;
+  __syncthreads();
+  if (rp == 0 && j < T) {
+    int sum = 0;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) sum += part[r][c];
+    cnt[(size_t)bh * (T + 1) + j] = sum;
+  }
 }
 
 // In-place exclusive scan of T counts per head -> T+1 pointers.
@@ -204,14 +217,24 @@ __global__ __launch_bounds__(256) void col_scan_kernel(int32_t* __restrict__ ptr
   }
 }
 
-__global__ void col_fill_kernel(const int8_t* __restrict__ Mc, int T, int n_h,
-                                const int32_t* __restrict__ ptr, int32_t* __restrict__ rows) {
-  const int j = blockIdx.x * blockDim.x + threadIdx.x, bh = blockIdx.y;
-  if (j >= T) return;
+__global__ __launch_bounds__(256) void col_fill_kernel(const int8_t* __restrict__ Mc, int T, int n_h,
+                                                       const int32_t* __restrict__ ptr,
+                                                       int32_t* __restrict__ rows) {
+  __shared__ int part[8][32];
+  const int c = threadIdx.x & 31, rp = threadIdx.x >> 5;
+  const int j = blockIdx.x * 32 + c, bh = blockIdx.y;
+  const int chunk = (T + 7) / 8, lo = min(T, rp * chunk), hi = min(T, lo + chunk);
   const int8_t* m = Mc + (size_t)bh * T * T + j;
-  int32_t* out = rows + (size_t)bh * T * n_h;
+  int n = 0;
+  if (j < T)
+    for (int i = lo; i < hi; ++i) n += (m[(size_t)i * T] == 1);
+  part[rp][c] = n;
+  __syncthreads();
+  if (j >= T) return;
   int w = ptr[(size_t)bh * (T + 1) + j];
-  for (int i = 0; i < T; ++i)
+  for (int r = 0; r < rp; ++r) w += part[r][c];   // rows of earlier ranges come first: ascending order
+  int32_t* out = rows + (size_t)bh * T * n_h;
+  for (int i = lo; i < hi; ++i)
     if (m[(size_t)i * T] == 1) out[w++] = i;
 }
 
@@ -300,7 +323,7 @@ hipError_t launch_csc(const int8_t* Mc, const Shape& s, int32_t* col_ptr, int32_
     KernelTimer kt("indicator", st);
     indicator_kernel<<<dim3((Tp + 31) / 32, (Tp + 31) / 32, s.BH), 256, 0, st>>>(Mc, s.T, Tp, ind, indT);
   }
-  dim3 grid((s.T + 255) / 256, s.BH);
+  dim3 grid((s.T + 31) / 32, s.BH);
   {
     KernelTimer kt("col_count", st);
     col_count_kernel<<<grid, 256, 0, st>>>(Mc, s.T, col_ptr);

@@ -53,23 +53,34 @@ __global__ __launch_bounds__(256, 2) void aggregate_mfma_kernel(const bf16* __re
                                                voff, 0, 0, 0);
     }
   };
-  issue(0);
-  for (int ks = 0; ks < ksteps; ++ks) {
-    // indicator pieces of this k-step: rows m0 + 64 w + 32 mt + ln, 16 bytes per 16 k
-    u32x4 ib16[2][4];
+  // indicator pieces of a k-step: rows m0 + 64 w + 32 mt + ln, 16 bytes per 16 k
+  u32x4 ibn[2][4];
+  auto load_ind = [&](int ks) {
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
       const int i = m0 + 64 * w + 32 * mt + ln;
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int k = ks * kBlk + 16 * u;
-        ib16[mt][u] = (i < T && k < Tp) ? *reinterpret_cast<const u32x4*>(ib + (size_t)i * Tp + k)
-                                        : u32x4{0u, 0u, 0u, 0u};
+        ibn[mt][u] = (i < T && k < Tp) ? *reinterpret_cast<const u32x4*>(ib + (size_t)i * Tp + k)
+                                       : u32x4{0u, 0u, 0u, 0u};
       }
     }
+  };
+  issue(0);
+  load_ind(0);
+  for (int ks = 0; ks < ksteps; ++ks) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (ks + 1 < ksteps) issue(ks + 1);
+    u32x4 ib16[2][4];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int u = 0; u < 4; ++u) ib16[mt][u] = ibn[mt][u];
+    if (ks + 1 < ksteps) {   // next step's tile and indicator pieces fly during this step's products
+      issue(ks + 1);
+      load_ind(ks + 1);
+    }
     const unsigned char* Bs = smem + (ks & 1) * kTileB;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {

@@ -58,13 +58,14 @@ struct PreLds {
   static constexpr int G_ELEMS = kBlk * RS;     // dO^l row-major [q][b]
   static constexpr int GT_ELEMS = D * kVS;      // dO^l transposed [b][q]
   static constexpr int AT_ELEMS = D * kVS;      // (phi(Q)/den)^T [c][q]
-  static constexpr int H_ELEMS = D * RS;        // H_i [a][b]
-  static constexpr int F_OFF = (G_ELEMS + GT_ELEMS + AT_ELEMS + H_ELEMS) * 2;
+  static constexpr int H_ELEMS = D * RS;        // H_i [a][b]; reuses the two transposed tiles
+  static_assert(H_ELEMS <= GT_ELEMS + AT_ELEMS, "H_i must fit over the transposed tiles");
+  static constexpr int F_OFF = (G_ELEMS + GT_ELEMS + AT_ELEMS) * 2;
   static constexpr int BYTES = F_OFF + 4 * kBlk * 4;   // Dl partial [par][q], dot partial [par][q]
 };
 
 template <int D>
-__global__ __launch_bounds__(256) void bwd_pre_mfma_kernel(
+__global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ dO, const bf16* __restrict__ W,
     const bf16* __restrict__ Os, const bf16* __restrict__ Ol, const bf16* __restrict__ H16,
     const float* __restrict__ Zs, int N,
@@ -76,7 +77,7 @@ __global__ __launch_bounds__(256) void bwd_pre_mfma_kernel(
   bf16* Gs = reinterpret_cast<bf16*>(smem);
   bf16* Gt = Gs + Lds::G_ELEMS;
   bf16* At = Gt + Lds::GT_ELEMS;
-  bf16* Hs = At + Lds::AT_ELEMS;
+  bf16* Hs = Gt;   // staged once dH_i, dZ_i no longer need the transposed tiles
   float* dlp = reinterpret_cast<float*>(smem + Lds::F_OFF);   // [par][64]
   float* dotp = dlp + 2 * kBlk;                               // [par][64]
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
@@ -107,7 +108,6 @@ __global__ __launch_bounds__(256) void bwd_pre_mfma_kernel(
   if (n_0 == 0) return;   // no linear branch: nothing else to do (uniform over the grid)
   const bf16* Hrow = H16 + ((size_t)bh * Tn + i) * (D * D);
   const float* Z = Zs + ((size_t)bh * Tn + i) * D;
-  stage_matrix_t<D>(Hrow, Hs, RS);
   // dO^l^T[b][q] = sum_e W[b][e] dO[q][e]; this wave: b-tiles par*HT .. par*HT+HT-1
   f32x16 gl[HT];
   float dl = 0.0f;
@@ -196,6 +196,9 @@ __global__ __launch_bounds__(256) void bwd_pre_mfma_kernel(
       z = fmaf(__bfloat162float(At[tid * kVS + q]), dlp[q] + dlp[kBlk + q], z);
     out[(size_t)D * D + tid] = __float2bfloat16(-z);
   }
+  __syncthreads();
+  stage_matrix_t<D>(Hrow, Hs, RS);
+  __syncthreads();
   // dQ^phi^T[c][q] = (sum_b H[c][b] dO^l[q][b] - D^l_q Z[c]) / den_q; this wave: c-tiles of par
   f32x16 dq[HT];
   float dot = 0.0f;
