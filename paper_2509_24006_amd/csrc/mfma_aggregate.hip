@@ -70,7 +70,7 @@ __global__ __launch_bounds__(256, 2) void aggregate_mfma_kernel(const bf16* __re
   issue(0);
   load_ind(0);
   for (int ks = 0; ks < ksteps; ++ks) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    wait_vm0();
     __syncthreads();
     u32x4 ib16[2][4];
 #pragma unroll

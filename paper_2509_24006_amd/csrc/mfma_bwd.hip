@@ -76,12 +76,30 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
   const float* Lb = L + (size_t)bh * N;
   const float* Dsb = Ds + (size_t)bh * N;
   float streg = 0.0f;
-  auto issue = [&](int s) {
+  // per-lane addresses, fixed for the whole kernel
+  using T = SwzTile<D>;
+  TileAddr<D> ad;
+  ad.init(32 * qh, l);
+  int ldv[T::IPW];   // byte offset inside a tile of the chunk this lane fetches with load k
+#pragma unroll
+  for (int k = 0; k < T::IPW; ++k) {
+    const int row = T::RPI * (4 * k + w) + l / T::CPR;
+    ldv[k] = swz_chunk_off<D>(row, l % T::CPR);
+  }
+  const int wlds = wave_uniform(w) * 1024;
+  // (issue and step are inlined at call sites with a literal buffer index, which turns every
+  // LDS offset below into register + constant)
+  auto issue = [&](int s, const int bufi) __attribute__((always_inline)) {
+    const int off = bufi * Lds::BUF;
     const int ii = list[beg + s];
     const int rows = min(kBlk, N - ii * kBlk);
-    const int off = (s & 1) * Lds::BUF;
-    issue_tile_load<D>(Qb + (size_t)ii * kBlk * D, rows, smem, off, w, l);
-    issue_tile_load<D>(dOb + (size_t)ii * kBlk * D, rows, smem, off + Lds::TILE, w, l);
+    const __amdgpu_buffer_rsrc_t rq = tile_rsrc(Qb + (size_t)ii * kBlk * D, rows * T::ROW_BYTES);
+    const __amdgpu_buffer_rsrc_t rg = tile_rsrc(dOb + (size_t)ii * kBlk * D, rows * T::ROW_BYTES);
+#pragma unroll
+    for (int k = 0; k < T::IPW; ++k) {
+      load_to_lds16(rq, ldv[k], smem, off + 4096 * k + wlds);
+      load_to_lds16(rg, ldv[k], smem, off + Lds::TILE + 4096 * k + wlds);
+    }
     if (tid < 128) {   // per-query statistics; rows past the end give P = 0
       const int q = tid & 63;
       const bool ok = q < rows;
@@ -89,24 +107,18 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
       else streg = ok ? Dsb[ii * kBlk + q] : 0.0f;
     }
   };
-  if (cnt > 0) {
-    issue(0);
-    if (tid < 128) stats[tid] = streg;
-  }
-  for (int s = 0; s < cnt; ++s) {
-    const int buf = s & 1;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  auto step = [&](int s, const int buf) __attribute__((always_inline)) {
+    const int QO = buf * Lds::BUF, GO = QO + Lds::TILE;
+    wait_vm0();
     __syncthreads();   // tiles of step s have landed for every wave; step s-1 is fully consumed
-    if (s + 1 < cnt) issue(s + 1);
-    const unsigned char* Qs = smem + buf * Lds::BUF;
-    const unsigned char* Gs = Qs + Lds::TILE;
+    if (s + 1 < cnt) issue(s + 1, buf ^ 1);
     const float* Ls = stats + buf * 2 * kBlk;
     const float* Dq = Ls + kBlk;
     f32x16 sm = zero_f32x16(), dp = zero_f32x16();
 #pragma unroll
     for (int t = 0; t < KT; ++t) {
-      sm = mfma32(read_row_swz<D>(Qs, 32 * qh, t, l), kf[t], sm);
-      dp = mfma32(read_row_swz<D>(Gs, 32 * qh, t, l), vf[t], dp);
+      sm = mfma32(lds_row(smem, ad.row[t] + QO), kf[t], sm);
+      dp = mfma32(lds_row(smem, ad.row[t] + GO), vf[t], dp);
     }
     // P[q][key] = exp(S - L_q), dS = P (dP - D^s_q); rows q = 32 qh + c_row(r, g)
 #pragma unroll
@@ -124,13 +136,23 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
     for (int u = 0; u < 2; ++u) {
       const bf16x8 pb = c_to_operand(sm, u);
       const bf16x8 sb = c_to_operand(dp, u);
+      constexpr int RB = 16 * T::ROW_BYTES;
 #pragma unroll
       for (int et = 0; et < NT; ++et) {
-        dvT[et] = mfma32(read_tr_swz<D>(Gs, 32 * qh + 16 * u, et, l), pb, dvT[et]);   // dO_i^T P
-        dkT[et] = mfma32(read_tr_swz<D>(Qs, 32 * qh + 16 * u, et, l), sb, dkT[et]);   // Q_i^T dS
+        const int o0 = ad.trb[0] + ad.trx[et], o1 = ad.trb[1] + ad.trx[et];
+        dvT[et] = mfma32(lds_tr<D>(smem, o0 + GO + u * RB, o1 + GO + u * RB), pb, dvT[et]);   // dO_i^T P
+        dkT[et] = mfma32(lds_tr<D>(smem, o0 + QO + u * RB, o1 + QO + u * RB), sb, dkT[et]);   // Q_i^T dS
       }
     }
     if (s + 1 < cnt && tid < 128) stats[(buf ^ 1) * 2 * kBlk + tid] = streg;
+  };
+  if (cnt > 0) {
+    issue(0, 0);
+    if (tid < 128) stats[tid] = streg;
+  }
+  for (int s = 0; s < cnt; s += 2) {
+    step(s, 0);
+    if (s + 1 < cnt) step(s + 1, 1);
   }
   // ---- add the two query halves, then the linear-branch parts, and store
   __syncthreads();
@@ -214,7 +236,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(
   for (int s = 0; s < n_h; ++s) {
     const int buf = s & 1;
     const int cols = min(kBlk, N - lut[s] * kBlk);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    wait_vm0();
     __syncthreads();
     if (s + 1 < n_h) issue(s + 1);
     const unsigned char* Ks = smem + buf * Lds::BUF;

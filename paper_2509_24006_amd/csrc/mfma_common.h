@@ -252,6 +252,70 @@ __device__ __forceinline__ bf16x8 read_tr_swz(const unsigned char* tile, int r0,
   return r;
 }
 
+// Per-lane byte offsets into a swizzled tile, computed once outside the step loop so that the
+// loop body addresses LDS as (register + compile-time constant):
+//   row[t]        16-byte chunk 2t + g of row r0 + (l % 32)          (operand read by rows)
+//   trb[h]+trx[et]  8 bytes of the transposing read h of feature tile et, tile rows r0 + 0..15;
+//                 rows r0 + 16u .. are a further 16u * ROW_BYTES away (the swizzle has period 16)
+template <int D>
+struct TileAddr {
+  int row[D / 16];
+  int trb[2];
+  int trx[D / 32];
+  __device__ __forceinline__ void init(int r0, int l) {
+    const int g = l >> 5, ln = l & 31;
+#pragma unroll
+    for (int t = 0; t < D / 16; ++t) row[t] = swz_chunk_off<D>(r0 + ln, 2 * t + g);
+    const int G = l >> 4, e = (l >> 2) & 3, a = l & 3;
+    const int cl = 2 * (G & 1) + (a >> 1);
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int rw = r0 + 8 * h + 4 * (G >> 1) + e;
+      // chunk = 4 et + cl; its swizzled position is 4 (et ^ fe) + (cl ^ fb), fe and fb from the row
+      const int f = swz<D>(rw);
+      trb[h] = rw * SwzTile<D>::ROW_BYTES + (((cl ^ f) & 3) << 4) + 8 * (a & 1);
+    }
+    const int fe = (swz<D>(r0 + e) >> 2);
+#pragma unroll
+    for (int et = 0; et < D / 32; ++et) trx[et] = (et ^ fe) << 6;
+  }
+};
+
+typedef __attribute__((ext_vector_type(4))) short lds_s16x4_val;
+typedef __attribute__((address_space(3))) lds_s16x4_val lds_s16x4_t;
+
+// operand read by rows at a precomputed offset
+__device__ __forceinline__ bf16x8 lds_row(const unsigned char* smem, int off) {
+  return *reinterpret_cast<const bf16x8*>(smem + off);
+}
+
+// transposed operand from the two precomputed read offsets (off, off + 8 rows)
+template <int D>
+__device__ __forceinline__ bf16x8 lds_tr(const unsigned char* smem, int off0, int off1) {
+  const lds_s16x4_val lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(smem + off0));
+  const lds_s16x4_val hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(smem + off1));
+  const bf16x4 lo4 = *reinterpret_cast<const bf16x4*>(&lo), hi4 = *reinterpret_cast<const bf16x4*>(&hi);
+  bf16x8 r;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    r[i] = lo4[i];
+    r[4 + i] = hi4[i];
+  }
+  return r;
+}
+
+// One wave-wide 16-byte-per-lane load global -> LDS: lane L's 16 bytes at byte offset voff of the
+// buffer land at LDS byte (lds_off + 16 L); lds_off must be the same for the whole wave.
+__device__ __forceinline__ void load_to_lds16(__amdgpu_buffer_rsrc_t rsrc, int voff, unsigned char* smem,
+                                              int lds_off) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(smem + lds_off), 16, voff, 0, 0, 0);
+}
+
+__device__ __forceinline__ int wave_uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
+
+// all outstanding global loads of this wave (including those that write LDS) have completed
+__device__ __forceinline__ void wait_vm0() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 constexpr float kLog2e = 1.4426950408889634f;

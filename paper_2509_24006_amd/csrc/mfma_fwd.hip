@@ -205,7 +205,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
   if (n_h > 0) issue(0);
   for (int s = 0; s < n_h; ++s) {
     const int cols = min(kBlk, N - lut[s] * kBlk);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    wait_vm0();
     __syncthreads();   // tiles of step s have landed for every wave; step s-1 is fully consumed
     if (s + 1 < n_h) issue(s + 1);
     const unsigned char* Ks = smem + (s & 1) * Lds::BUF;
