@@ -48,6 +48,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
   const int kh = w & 1, qh = w >> 1;
   // longest column lists first, across all heads: the r-th heaviest key block of every head
   // precedes the (r+1)-th of any head, so the tail of the launch is made of short lists
+  // (grouping an XCD's workgroups by head for L2 reuse was measured slower than this order)
   const int BH = gridDim.x / Tn;
   const int bh = blockIdx.x % BH;
   const int j = col_order[(size_t)bh * Tn + blockIdx.x / BH];
@@ -205,7 +206,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(
   float* xch = reinterpret_cast<float*>(smem);
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
   const int qh = w & 1, kh = w >> 1;
-  const int i = blockIdx.x, bh = blockIdx.y;
+  const int i = xcd_local_block(blockIdx.x, Tn), bh = blockIdx.y;
+  if (i < 0) return;
   const int q0 = i * kBlk, rows = min(kBlk, N - q0);
   const int qrow = qh * 32 + ln;
   const bool qok = qrow < rows;
@@ -311,7 +313,7 @@ hipError_t sparse_impl(const Shape& s, const BwdArgs& a, const float* Ds, const 
                               hipFuncAttributeMaxDynamicSharedMemorySize, lds));
   {
     KernelTimer kt("bwd_sparse_q", st);
-    bwd_dq_mfma_kernel<D><<<dim3(s.T, s.BH), 256, lds, st>>>(
+    bwd_dq_mfma_kernel<D><<<dim3(xcd_grid(s.T), s.BH), 256, lds, st>>>(
         (const bf16*)a.Q, (const bf16*)a.K, (const bf16*)a.V, (const bf16*)a.dO, a.L, Ds, a.row_idx,
         dQlin, s.N, s.T, s.n_h, s.scale, (bf16*)a.dQ);
   }

@@ -313,6 +313,18 @@ __device__ __forceinline__ void load_to_lds16(__amdgpu_buffer_rsrc_t rsrc, int v
 
 __device__ __forceinline__ int wave_uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
+// Workgroups are dealt to the 8 XCDs (each with its own L2) round-robin by linear index.  With a
+// grid of 8 * ceil(T / 8) workgroups per head, XCD x gets the contiguous blocks
+// [x ceil(T/8), (x+1) ceil(T/8)) in ascending order, so that neighbouring query blocks -- which
+// share many of their critical key blocks -- run on the same L2 at about the same time.
+// Returns the block index, or -1 for a padding workgroup.
+__device__ __forceinline__ int xcd_local_block(int bx, int T) {
+  const int C = (T + 7) >> 3;
+  const int i = (bx & 7) * C + (bx >> 3);
+  return i < T ? i : -1;
+}
+inline int xcd_grid(int T) { return 8 * ((T + 7) / 8); }
+
 // all outstanding global loads of this wave (including those that write LDS) have completed
 __device__ __forceinline__ void wait_vm0() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 

@@ -178,7 +178,8 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
   float* ml = reinterpret_cast<float*>(smem + Lds::BYTES - 1024);   // [par][qh][32][2]
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
   const int qh = w & 1, par = w >> 1;
-  const int i = blockIdx.x, bh = blockIdx.y;
+  const int i = xcd_local_block(blockIdx.x, Tn), bh = blockIdx.y;
+  if (i < 0) return;
   const int q0 = i * kBlk, rows = min(kBlk, N - q0);
   const int qrow = qh * 32 + ln;                  // this lane's query inside the block
   const bool qok = qrow < rows;
@@ -443,7 +444,7 @@ hipError_t forward_impl(const Shape& s, const FwdArgs& a, bf16* hz16, bf16* WTp,
                               hipFuncAttributeMaxDynamicSharedMemorySize, lds));
   {
     KernelTimer kt("fwd_sparse", st);
-    fwd_mfma_kernel<D><<<dim3(s.T, s.BH), 256, lds, st>>>(
+    fwd_mfma_kernel<D><<<dim3(xcd_grid(s.T), s.BH), 256, lds, st>>>(
         (const bf16*)a.Q, (const bf16*)a.K, (const bf16*)a.V, WTp, a.row_idx, (const bf16*)a.HZ, Zs, s.N, s.T, s.n_h,
         s.n_0, s.phi, s.scale * kLog2e, (bf16*)a.O, (bf16*)a.Os, (bf16*)a.Ol, a.L);
   }
