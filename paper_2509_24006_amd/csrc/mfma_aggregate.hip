@@ -34,8 +34,9 @@ __global__ __launch_bounds__(256, 2) void aggregate_mfma_kernel(const bf16* __re
   const int n0 = blockIdx.x * 128, m0 = blockIdx.y * 256, bh = blockIdx.z;
   const int8_t* ib = ind + (size_t)bh * T * Tp;
   const bf16* inb = in + (size_t)bh * T * row_len;
-  const __amdgpu_buffer_rsrc_t rsrc = tile_rsrc(inb, T * row_len * 2);
+  const BufDesc rsrc = tile_rsrc(inb, T * row_len * 2);
   const int pitch = row_len * 2;
+  const unsigned lds0 = lds_base(smem);
   f32x16 acc[2][4];
 #pragma unroll
   for (int mt = 0; mt < 2; ++mt)
@@ -49,8 +50,7 @@ __global__ __launch_bounds__(256, 2) void aggregate_mfma_kernel(const bf16* __re
       const int rg = 4 * k + w;
       const int row = 4 * rg + (l >> 4), pc = l & 15;
       const int voff = (ks * kBlk + row) * pitch + n0 * 2 + ((pc ^ swz<128>(row)) << 4);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(smem + (ks & 1) * kTileB + rg * 1024), 16,
-                                               voff, 0, 0, 0);
+      load_to_lds16(rsrc, voff, 0, lds0 + (ks & 1) * kTileB + rg * 1024);
     }
   };
   // indicator pieces of a k-step: rows m0 + 64 w + 32 mt + ln, 16 bytes per 16 k

@@ -25,6 +25,10 @@ struct PairLds {
   static constexpr int XCH = 2 * 2 * (D / 32) * 16 * 64 * 4;   // final exchange (dK/dV kernel)
   static constexpr int TILES = 2 * BUF > XCH ? 2 * BUF : XCH;
   static constexpr int BYTES = TILES + 2 * 2 * kBlk * 4; // + [buf][L, D^s][64]
+  static constexpr int VPARK = D >= 128 ? 2 * (D / 32) * 64 * 16 : 0;   // parked V operand (dK/dV kernel)
+  static constexpr int SP = D + 4;                        // row pitch (floats) of the output staging
+  static constexpr int STAGE = 2 * kBlk * SP * 4;         // [dV | dK][64][SP] floats (dK/dV kernel)
+  static constexpr int DKDV = BYTES + VPARK > STAGE ? BYTES + VPARK : STAGE;
 };
 
 // ------------------------------------------------------------------ dK, dV
@@ -43,7 +47,6 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
   constexpr int NT = D / 32, KT = D / 16;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   float* stats = reinterpret_cast<float*>(smem + Lds::TILES);   // [buf][2][64]
-  float* xch = reinterpret_cast<float*>(smem);
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
   const int kh = w & 1, qh = w >> 1;
   // longest column lists first, across all heads: the r-th heaviest key block of every head
@@ -55,13 +58,12 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
   const int k0 = j * kBlk, cols = min(kBlk, N - k0);
   const int krow = kh * 32 + ln;
   const bool kok = krow < cols;
-  const size_t koff = ((size_t)bh * N + k0 + krow) * D;
-  bf16x8 kf[KT], vf[KT];
-#pragma unroll
-  for (int t = 0; t < KT; ++t) {
-    kf[t] = kok ? *reinterpret_cast<const bf16x8*>(K + koff + 16 * t + 8 * g) : zero_bf16x8();
-    vf[t] = kok ? *reinterpret_cast<const bf16x8*>(V + koff + 16 * t + 8 * g) : zero_bf16x8();
-  }
+  // At d = 128 the accumulators and both key-side operands do not fit the register budget of
+  // two workgroups per CU.  The upper half of the V operand is parked in LDS (each kh half once,
+  // in operand layout: 16 bytes per lane and k-step) and re-read every step.
+  constexpr int VL = D >= 128 ? KT / 2 : 0, VR = KT - VL;
+  const int vpark = Lds::BYTES + (kh * VL * 64 + l) * 16;
+  bf16x8 kf[KT], vf[VR > 0 ? VR : 1];
   f32x16 dvT[NT], dkT[NT];
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
@@ -81,46 +83,73 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
   using T = SwzTile<D>;
   TileAddr<D> ad;
   ad.init(32 * qh, l);
-  int ldv[T::IPW];   // byte offset inside a tile of the chunk this lane fetches with load k
-#pragma unroll
-  for (int k = 0; k < T::IPW; ++k) {
-    const int row = T::RPI * (4 * k + w) + l / T::CPR;
-    ldv[k] = swz_chunk_off<D>(row, l % T::CPR);
-  }
-  const int wlds = wave_uniform(w) * 1024;
+  // load k of a tile fetches, for this lane, the chunk 4096 k bytes after that of load 0 (the
+  // swizzle has period 16 rows), so one per-lane offset serves all of them
+  const int ldv = swz_chunk_off<D>(T::RPI * w + l / T::CPR, l % T::CPR);
+  const int wu = wave_uniform(w);
+  const unsigned lds0 = lds_base(smem) + wu * 1024;
   // (issue and step are inlined at call sites with a literal buffer index, which turns every
   // LDS offset below into register + constant)
+  // the row index of a step is fetched two steps ahead, so the tile loads never wait for it
+  int inext = cnt > 0 ? list[beg] : 0;
   auto issue = [&](int s, const int bufi) __attribute__((always_inline)) {
     const int off = bufi * Lds::BUF;
-    const int ii = list[beg + s];
+    const int ii = inext;
+    inext = list[beg + min(s + 1, cnt - 1)];
     const int rows = min(kBlk, N - ii * kBlk);
-    const __amdgpu_buffer_rsrc_t rq = tile_rsrc(Qb + (size_t)ii * kBlk * D, rows * T::ROW_BYTES);
-    const __amdgpu_buffer_rsrc_t rg = tile_rsrc(dOb + (size_t)ii * kBlk * D, rows * T::ROW_BYTES);
+    const BufDesc rq = tile_rsrc(Qb + (size_t)ii * kBlk * D, rows * T::ROW_BYTES);
+    const BufDesc rg = tile_rsrc(dOb + (size_t)ii * kBlk * D, rows * T::ROW_BYTES);
 #pragma unroll
     for (int k = 0; k < T::IPW; ++k) {
-      load_to_lds16(rq, ldv[k], smem, off + 4096 * k + wlds);
-      load_to_lds16(rg, ldv[k], smem, off + Lds::TILE + 4096 * k + wlds);
+      load_to_lds16(rq, ldv, 4096 * k, lds0 + off + 4096 * k);
+      load_to_lds16(rg, ldv, 4096 * k, lds0 + off + Lds::TILE + 4096 * k);
     }
-    if (tid < 128) {   // per-query statistics; rows past the end give P = 0
-      const int q = tid & 63;
-      const bool ok = q < rows;
-      if (tid < 64) streg = ok ? Lb[ii * kBlk + q] * kLog2e : INFINITY;
-      else streg = ok ? Dsb[ii * kBlk + q] : 0.0f;
-    }
+    // per-query statistics: wave 0 fetches L, wave 1 D^s.  Rows past the end read as 0; their Q
+    // and dO rows are zero too, so whatever finite P they get adds nothing to dK and dV.
+    if (wu < 2) streg = load_f32_or_zero((wu == 0 ? Lb : Dsb) + (size_t)ii * kBlk, rows, lane_id());
   };
   auto step = [&](int s, const int buf) __attribute__((always_inline)) {
     const int QO = buf * Lds::BUF, GO = QO + Lds::TILE;
+    ad.refresh();
     wait_vm0();
     __syncthreads();   // tiles of step s have landed for every wave; step s-1 is fully consumed
     if (s + 1 < cnt) issue(s + 1, buf ^ 1);
     const float* Ls = stats + buf * 2 * kBlk;
     const float* Dq = Ls + kBlk;
+    // LDS reads run PF operand sets ahead of the products that consume them (software pipeline
+    // written out by hand: left alone, the compiler reads each operand right before its product
+    // and every product then waits a full LDS latency).
+    constexpr int PF = 2;
+    constexpr int RB = 16 * T::ROW_BYTES;
+    bf16x8 qa[PF], ga[PF], pa[PF];
+    auto read_s = [&](int t) __attribute__((always_inline)) {
+      qa[t % PF] = lds_row(smem, ad.row(t) + QO);
+      ga[t % PF] = lds_row(smem, ad.row(t) + GO);
+      if (t >= VR) pa[t % PF] = lds_row(smem, vpark + (t - VR) * 1024);
+    };
+    // operand i of the second pair of products: i = 2 NT u + 2 et + which; which 0: dO^T rows of
+    // feature tile et (for dV), which 1: Q^T (for dK); k = pair rows 32 qh + 16 u ..
+    constexpr int PT = D >= 128 ? 2 : 4;   // what the register budget allows
+    bf16x8 ta[PT];
+    auto read_t = [&](int i) __attribute__((always_inline)) {
+      const int u = i / (2 * NT), et = (i % (2 * NT)) / 2, base = (i % 2 ? QO : GO) + u * RB;
+      ta[i % PT] = lds_tr<D>(smem, ad.tr(0, et) + base, ad.tr(1, et) + base);
+    };
+#pragma unroll
+    for (int t = 0; t < PF; ++t) read_s(t);
+    sched_fence();
     f32x16 sm = zero_f32x16(), dp = zero_f32x16();
 #pragma unroll
     for (int t = 0; t < KT; ++t) {
-      sm = mfma32(lds_row(smem, ad.row[t] + QO), kf[t], sm);
-      dp = mfma32(lds_row(smem, ad.row[t] + GO), vf[t], dp);
+      sm = mfma32(qa[t % PF], kf[t], sm);
+      dp = mfma32(ga[t % PF], t < VR ? vf[t] : pa[t % PF], dp);
+      if (t + PF < KT) read_s(t + PF);
+      sched_fence();
     }
+    // the first transposed operands arrive under the softmax arithmetic
+#pragma unroll
+    for (int i = 0; i < PT; ++i) read_t(i);
+    sched_fence();
     // P[q][key] = exp(S - L_q), dS = P (dP - D^s_q); rows q = 32 qh + c_row(r, g)
 #pragma unroll
     for (int r4 = 0; r4 < 4; ++r4) {
@@ -133,60 +162,115 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
         dp[4 * r4 + r] = pv * (dp[4 * r4 + r] - dq[r]);
       }
     }
+    sched_fence();
+    bf16x8 pb, sb;
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const bf16x8 pb = c_to_operand(sm, u);
-      const bf16x8 sb = c_to_operand(dp, u);
-      constexpr int RB = 16 * T::ROW_BYTES;
-#pragma unroll
-      for (int et = 0; et < NT; ++et) {
-        const int o0 = ad.trb[0] + ad.trx[et], o1 = ad.trb[1] + ad.trx[et];
-        dvT[et] = mfma32(lds_tr<D>(smem, o0 + GO + u * RB, o1 + GO + u * RB), pb, dvT[et]);   // dO_i^T P
-        dkT[et] = mfma32(lds_tr<D>(smem, o0 + QO + u * RB, o1 + QO + u * RB), sb, dkT[et]);   // Q_i^T dS
+    for (int i = 0; i < 4 * NT; ++i) {
+      const int u = i / (2 * NT), et = (i % (2 * NT)) / 2;
+      if (i % (2 * NT) == 0) {
+        pb = c_to_operand(sm, u);
+        sb = c_to_operand(dp, u);
       }
+      if (i % 2 == 0) dvT[et] = mfma32(ta[i % PT], pb, dvT[et]);   // dO_i^T P
+      else dkT[et] = mfma32(ta[i % PT], sb, dkT[et]);              // Q_i^T dS
+      if (i + PT < 4 * NT) read_t(i + PT);
+      sched_fence();
     }
-    if (s + 1 < cnt && tid < 128) stats[(buf ^ 1) * 2 * kBlk + tid] = streg;
+    if (s + 1 < cnt && wu < 2) stats[(buf ^ 1) * 2 * kBlk + wu * kBlk + lane_id()] = wu == 0 ? streg * kLog2e : streg;
   };
-  if (cnt > 0) {
-    issue(0, 0);
-    if (tid < 128) stats[tid] = streg;
+  // K_j and V_j come in as tiles through the second pair buffer (whole rows per load, zeros past
+  // the end of the sequence) and are picked up from there in operand layout
+  {
+    const BufDesc rk = tile_rsrc(K + ((size_t)bh * N + k0) * D, cols * T::ROW_BYTES);
+    const BufDesc rv = tile_rsrc(V + ((size_t)bh * N + k0) * D, cols * T::ROW_BYTES);
+#pragma unroll
+    for (int k = 0; k < T::IPW; ++k) {
+      load_to_lds16(rk, ldv, 4096 * k, lds0 + Lds::BUF + 4096 * k);
+      load_to_lds16(rv, ldv, 4096 * k, lds0 + Lds::BUF + Lds::TILE + 4096 * k);
+    }
   }
+  if (cnt > 0) issue(0, 0);
+  wait_vm0();
+  __syncthreads();
+  if (cnt > 0 && wu < 2) stats[wu * kBlk + lane_id()] = wu == 0 ? streg * kLog2e : streg;
+  {
+    TileAddr<D> ka;
+    ka.init(32 * kh, l);
+#pragma unroll
+    for (int t = 0; t < KT; ++t) {
+      kf[t] = lds_row(smem, ka.row(t) + Lds::BUF);
+      const bf16x8 v = lds_row(smem, ka.row(t) + Lds::BUF + Lds::TILE);
+      if (t < VR) vf[t] = v;
+      else if (qh == 0) *reinterpret_cast<bf16x8*>(smem + vpark + (t - VR) * 1024) = v;
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < KT; ++t) {
+    pin_loaded(kf[t]);
+    if (t < VR) pin_loaded(vf[t]);
+  }
+  // (the first step's barrier orders these reads before the loads that reuse the buffer)
   for (int s = 0; s < cnt; s += 2) {
     step(s, 0);
     if (s + 1 < cnt) step(s + 1, 1);
   }
-  // ---- add the two query halves, then the linear-branch parts, and store
-  __syncthreads();
-  float* myx = xch + (size_t)kh * (2 * NT * 16) * 64;
+  // ---- add the two query halves in a row-major staging area, then every thread takes 16-byte
+  // pieces of whole rows: adds the linear-branch parts and stores (coalesced both ways)
+  __syncthreads();   // every wave is done with the tiles
+  constexpr int SP = Lds::SP;
+  float* stg = reinterpret_cast<float*>(smem);   // [dV | dK][64 keys][SP]
+  const int srow = krow * SP + 4 * g;
   if (qh == 1) {
 #pragma unroll
     for (int et = 0; et < NT; ++et)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        myx[(et * 16 + r) * 64 + l] = dvT[et][r];
-        myx[((NT + et) * 16 + r) * 64 + l] = dkT[et][r];
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int o = srow + 32 * et + 8 * r4;
+        *reinterpret_cast<f32x4*>(stg + o) =
+            f32x4{dvT[et][4 * r4], dvT[et][4 * r4 + 1], dvT[et][4 * r4 + 2], dvT[et][4 * r4 + 3]};
+        *reinterpret_cast<f32x4*>(stg + kBlk * SP + o) =
+            f32x4{dkT[et][4 * r4], dkT[et][4 * r4 + 1], dkT[et][4 * r4 + 2], dkT[et][4 * r4 + 3]};
       }
   }
   __syncthreads();
-  if (qh == 0 && kok) {
+  if (qh == 0) {
 #pragma unroll
     for (int et = 0; et < NT; ++et)
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
-        const size_t o = koff + 32 * et + 8 * r4 + 4 * g;
-        f32x4 lv = {0.0f, 0.0f, 0.0f, 0.0f}, lk = {0.0f, 0.0f, 0.0f, 0.0f};
-        if (dVlin) lv = *reinterpret_cast<const f32x4*>(dVlin + o);
-        if (dKlin) lk = *reinterpret_cast<const f32x4*>(dKlin + o);
-        bf16x4 pv, pk;
+        const int o = srow + 32 * et + 8 * r4;
+        f32x4 a = *reinterpret_cast<const f32x4*>(stg + o);
+        f32x4 b = *reinterpret_cast<const f32x4*>(stg + kBlk * SP + o);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const int rr = 4 * r4 + r;
-          pv[r] = (__bf16)(dvT[et][rr] + myx[(et * 16 + rr) * 64 + l] + lv[r]);
-          pk[r] = (__bf16)((dkT[et][rr] + myx[((NT + et) * 16 + rr) * 64 + l]) * scale + lk[r]);
+          a[r] += dvT[et][4 * r4 + r];
+          b[r] += dkT[et][4 * r4 + r];
         }
-        *reinterpret_cast<bf16x4*>(dV + o) = pv;
-        *reinterpret_cast<bf16x4*>(dK + o) = pk;
+        *reinterpret_cast<f32x4*>(stg + o) = a;
+        *reinterpret_cast<f32x4*>(stg + kBlk * SP + o) = b;
       }
+  }
+  __syncthreads();
+  constexpr int C4 = D / 4;   // 16-byte pieces per row
+#pragma unroll
+  for (int it = 0; it < kBlk * C4 / 256; ++it) {
+    const int idx = it * 256 + tid, row = idx / C4, c4 = idx % C4;
+    if (row < cols) {
+      const size_t o = ((size_t)bh * N + k0 + row) * D + 4 * c4;
+      const f32x4 sv = *reinterpret_cast<const f32x4*>(stg + row * SP + 4 * c4);
+      const f32x4 sk = *reinterpret_cast<const f32x4*>(stg + (kBlk + row) * SP + 4 * c4);
+      f32x4 lv = {0.0f, 0.0f, 0.0f, 0.0f}, lk = {0.0f, 0.0f, 0.0f, 0.0f};
+      if (dVlin) lv = *reinterpret_cast<const f32x4*>(dVlin + o);
+      if (dKlin) lk = *reinterpret_cast<const f32x4*>(dKlin + o);
+      bf16x4 pv, pk;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        pv[r] = (__bf16)(sv[r] + lv[r]);
+        pk[r] = (__bf16)(sk[r] * scale + lk[r]);
+      }
+      *reinterpret_cast<bf16x4*>(dV + o) = pv;
+      *reinterpret_cast<bf16x4*>(dK + o) = pk;
+    }
   }
 }
 
@@ -235,6 +319,11 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(
     issue_tile_load<D>(Vb + (size_t)jj * kBlk * D, cols, smem, off + Lds::TILE, w, l);
   };
   if (n_h > 0) issue(0);
+#pragma unroll
+  for (int t = 0; t < KT; ++t) {
+    pin_loaded(qf[t]);
+    pin_loaded(gf[t]);
+  }
   for (int s = 0; s < n_h; ++s) {
     const int buf = s & 1;
     const int cols = min(kBlk, N - lut[s] * kBlk);
@@ -302,10 +391,10 @@ hipError_t sparse_impl(const Shape& s, const BwdArgs& a, const float* Ds, const 
                        const float* dKlin, const float* dVlin, hipStream_t st) {
   constexpr int lds = PairLds<D>::BYTES;
   SLA_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dkdv_mfma_kernel<D>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+                              hipFuncAttributeMaxDynamicSharedMemorySize, PairLds<D>::DKDV));
   {
     KernelTimer kt("bwd_sparse_kv", st);
-    bwd_dkdv_mfma_kernel<D><<<dim3(s.T * s.BH), 256, lds, st>>>(
+    bwd_dkdv_mfma_kernel<D><<<dim3(s.T * s.BH), 256, PairLds<D>::DKDV, st>>>(
         (const bf16*)a.Q, (const bf16*)a.K, (const bf16*)a.V, (const bf16*)a.dO, a.L, Ds, a.col_ptr,
         a.col_rows, a.col_order, dKlin, dVlin, s.N, s.T, s.n_h, s.scale, (bf16*)a.dK, (bf16*)a.dV);
   }

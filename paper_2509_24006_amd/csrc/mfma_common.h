@@ -172,9 +172,59 @@ __device__ __forceinline__ bf16x8 read_tr_operand(const bf16* tile, int stride, 
   return r;
 }
 
-// Buffer resource over `bytes` bytes starting at p: loads through it return zero beyond the end.
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const void* p, int bytes) {
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
+// Raw buffer descriptor (base address, no stride, byte count, 32-bit raw format) over `bytes`
+// bytes starting at p: loads through it return zero beyond the end.  p must be wave-uniform.
+typedef u32x4 BufDesc;
+__device__ __forceinline__ BufDesc tile_rsrc(const void* p, int bytes) {
+  const unsigned long long a = reinterpret_cast<unsigned long long>(p);
+  return BufDesc{(unsigned)a, (unsigned)(a >> 32) & 0xffffu, (unsigned)bytes, 0x00020000u};
+}
+
+typedef __attribute__((address_space(3))) void lds_void;
+
+// One wave-wide 16-byte-per-lane load global -> LDS: lane L's 16 bytes at byte offset voff of the
+// buffer plus the wave-uniform soff land at LDS byte address (lds_addr + 16 L), lds_addr uniform.
+// Written as assembly on purpose: the compiler cannot tell which LDS bytes such a load writes,
+// so for its own form of this load it waits for every outstanding one before the next LDS-writing
+// load and before the next LDS read, which serialises the loads and exposes their whole latency.
+// Here the ordering is the caller's job: wait_vm0() and a barrier before a tile is read, a
+// barrier after its last read before it is overwritten.
+__device__ __forceinline__ void load_to_lds16(BufDesc desc, int voff, int soff, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(desc), "s"(soff) : "memory");
+}
+
+// LDS byte address of the dynamic LDS array, as a wave-uniform integer
+__device__ __forceinline__ unsigned lds_base(unsigned char* smem) {
+  return __builtin_amdgcn_readfirstlane((unsigned)reinterpret_cast<size_t>((lds_void*)smem));
+}
+
+// p[idx] for 0 <= idx < count, else 0, without a branch (range-checked buffer load); p uniform
+__device__ __forceinline__ float load_f32_or_zero(const float* p, int count, int idx) {
+  const __amdgpu_buffer_rsrc_t r =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p), 0, count * 4, 0x00020000);
+  return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, idx * 4, 0, 0));
+}
+
+// lane index inside the wave, recomputed at every use (volatile: the compiler would otherwise
+// hoist it out of a loop and may then spill it) instead of held in a register
+__device__ __forceinline__ int lane_id() {
+  int x;
+  asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(x));
+  return x;
+}
+
+// Nothing is scheduled across this point.  Used to keep the LDS reads of a step together and
+// ahead of the matrix products that consume them, so that one LDS latency is exposed per group
+// instead of one per product.
+__device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0); }
+
+// Makes the compiler finish the loads that produce x here.  Used on operand registers that are
+// loaded before a pipelined loop: otherwise the wait for them lands at their first use inside the
+// loop body, where it also waits -- on every trip -- for the tile loads just put in flight.
+template <class T>
+__device__ __forceinline__ void pin_loaded(T& x) {
+  asm volatile("" : "+v"(x));
 }
 
 // ---- swizzled row-major tiles filled by direct global -> LDS loads
@@ -199,7 +249,6 @@ __device__ __forceinline__ int swz(int row) {
   return (((row & 3) << 2) | ((row >> 2) & 3)) & (D / 8 - 1);
 }
 
-typedef __attribute__((address_space(3))) void lds_void;
 
 // All four waves of a workgroup: enqueue the loads of one tile.  lds_tile: byte offset of the
 // tile inside the dynamic LDS array `smem`.
@@ -207,13 +256,13 @@ template <int D>
 __device__ __forceinline__ void issue_tile_load(const bf16* gbase, int valid_rows, unsigned char* smem,
                                                 int lds_tile, int w, int l) {
   using T = SwzTile<D>;
-  const __amdgpu_buffer_rsrc_t rsrc = tile_rsrc(gbase, valid_rows * T::ROW_BYTES);
+  const BufDesc rsrc = tile_rsrc(gbase, valid_rows * T::ROW_BYTES);
 #pragma unroll
   for (int k = 0; k < T::IPW; ++k) {
     const int rg = 4 * k + w;
     const int row = T::RPI * rg + l / T::CPR, pc = l % T::CPR;
     const int voff = row * T::ROW_BYTES + ((pc ^ swz<D>(row)) << 4);
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(smem + lds_tile + rg * 1024), 16, voff, 0, 0, 0);
+    load_to_lds16(rsrc, voff, 0, lds_base(smem) + lds_tile + rg * 1024);
   }
 }
 
@@ -252,20 +301,23 @@ __device__ __forceinline__ bf16x8 read_tr_swz(const unsigned char* tile, int r0,
   return r;
 }
 
-// Per-lane byte offsets into a swizzled tile, computed once outside the step loop so that the
-// loop body addresses LDS as (register + compile-time constant):
-//   row[t]        16-byte chunk 2t + g of row r0 + (l % 32)          (operand read by rows)
-//   trb[h]+trx[et]  8 bytes of the transposing read h of feature tile et, tile rows r0 + 0..15;
-//                 rows r0 + 16u .. are a further 16u * ROW_BYTES away (the swizzle has period 16)
+// Per-lane byte offsets into a swizzled tile, kept as a handful of registers:
+//   row(t)     16-byte chunk 2t + g of row r0 + (l % 32)                 (operand read by rows)
+//   tr(h, et)  8 bytes of the transposing read h of feature tile et, tile rows r0 + 0..15; rows
+//              r0 + 16u .. are a further 16u * ROW_BYTES away (the swizzle has period 16)
+// Each offset is base + (constant ^ per-lane swizzle), one VALU operation at the point of use.
+// Holding all of them in registers across the step loop costs more registers than the dK/dV
+// kernel has, and what spills is reloaded from scratch with a wait that also drains the tile
+// loads in flight.  refresh() at the top of a step keeps the compiler from hoisting them again.
 template <int D>
 struct TileAddr {
-  int row[D / 16];
-  int trb[2];
-  int trx[D / 32];
+  int rb, sx;     // row reads: base, swizzle of the chunk-pair index
+  int tb[2], fx;  // transposing reads: the two 8-row bases, swizzle of the feature tile index
   __device__ __forceinline__ void init(int r0, int l) {
-    const int g = l >> 5, ln = l & 31;
-#pragma unroll
-    for (int t = 0; t < D / 16; ++t) row[t] = swz_chunk_off<D>(r0 + ln, 2 * t + g);
+    const int g = l >> 5, r = r0 + (l & 31);
+    const int sw = swz<D>(r);
+    rb = r * SwzTile<D>::ROW_BYTES + (((g ^ sw) & 1) << 4);
+    sx = (sw & ~1) << 4;
     const int G = l >> 4, e = (l >> 2) & 3, a = l & 3;
     const int cl = 2 * (G & 1) + (a >> 1);
 #pragma unroll
@@ -273,12 +325,13 @@ struct TileAddr {
       const int rw = r0 + 8 * h + 4 * (G >> 1) + e;
       // chunk = 4 et + cl; its swizzled position is 4 (et ^ fe) + (cl ^ fb), fe and fb from the row
       const int f = swz<D>(rw);
-      trb[h] = rw * SwzTile<D>::ROW_BYTES + (((cl ^ f) & 3) << 4) + 8 * (a & 1);
+      tb[h] = rw * SwzTile<D>::ROW_BYTES + (((cl ^ f) & 3) << 4) + 8 * (a & 1);
     }
-    const int fe = (swz<D>(r0 + e) >> 2);
-#pragma unroll
-    for (int et = 0; et < D / 32; ++et) trx[et] = (et ^ fe) << 6;
+    fx = (swz<D>(r0 + e) >> 2) << 6;
   }
+  __device__ __forceinline__ void refresh() { asm volatile("" : "+v"(sx), "+v"(fx)); }
+  __device__ __forceinline__ int row(int t) const { return rb + ((t << 5) ^ sx); }
+  __device__ __forceinline__ int tr(int h, int et) const { return tb[h] + ((et << 6) ^ fx); }
 };
 
 typedef __attribute__((ext_vector_type(4))) short lds_s16x4_val;
@@ -302,13 +355,6 @@ __device__ __forceinline__ bf16x8 lds_tr(const unsigned char* smem, int off0, in
     r[4 + i] = hi4[i];
   }
   return r;
-}
-
-// One wave-wide 16-byte-per-lane load global -> LDS: lane L's 16 bytes at byte offset voff of the
-// buffer land at LDS byte (lds_off + 16 L); lds_off must be the same for the whole wave.
-__device__ __forceinline__ void load_to_lds16(__amdgpu_buffer_rsrc_t rsrc, int voff, unsigned char* smem,
-                                              int lds_off) {
-  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(smem + lds_off), 16, voff, 0, 0, 0);
 }
 
 __device__ __forceinline__ int wave_uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }

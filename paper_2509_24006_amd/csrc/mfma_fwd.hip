@@ -204,6 +204,8 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
     issue_tile_load<D>(Vb + (size_t)jj * kBlk * D, cols, smem, off + Lds::TILE, w, l);
   };
   if (n_h > 0) issue(0);
+#pragma unroll
+  for (int t = 0; t < KT; ++t) pin_loaded(qf[t]);
   for (int s = 0; s < n_h; ++s) {
     const int cols = min(kBlk, N - lut[s] * kBlk);
     wait_vm0();
@@ -211,9 +213,20 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
     if (s + 1 < n_h) issue(s + 1);
     const unsigned char* Ks = smem + (s & 1) * Lds::BUF;
     const unsigned char* Vs = Ks + Lds::TILE;
+    // every LDS read of the step is issued first; the V operands arrive under the score
+    // products and the softmax
+    bf16x8 ka[KT], va[2][NT];
+#pragma unroll
+    for (int t = 0; t < KT; ++t) ka[t] = read_row_swz<D>(Ks, 32 * par, t, l);
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int et = 0; et < NT; ++et) va[u][et] = read_tr_swz<D>(Vs, 32 * par + 16 * u, et, l);
+    sched_fence();
     f32x16 sT = zero_f32x16();
 #pragma unroll
-    for (int t = 0; t < KT; ++t) sT = mfma32(read_row_swz<D>(Ks, 32 * par, t, l), qf[t], sT);
+    for (int t = 0; t < KT; ++t) sT = mfma32(ka[t], qf[t], sT);
+    sched_fence();
     // ---- online softmax on raw scores (the 1/sqrt(d) and log2 e factors ride on the exp2
     // argument); one query per lane
     if (cols < kBlk) {
@@ -248,8 +261,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
     for (int u = 0; u < 2; ++u) {
       const bf16x8 pf = c_to_operand(sT, u);
 #pragma unroll
-      for (int et = 0; et < NT; ++et)
-        oT[et] = mfma32(read_tr_swz<D>(Vs, 32 * par + 16 * u, et, l), pf, oT[et]);
+      for (int et = 0; et < NT; ++et) oT[et] = mfma32(va[u][et], pf, oT[et]);
     }
   }
   // ---- merge the two key-tile streams (par 0 / par 1) of each query half
