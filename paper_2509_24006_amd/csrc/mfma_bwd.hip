@@ -40,9 +40,9 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
     const bf16* __restrict__ dO, const float* __restrict__ L, const float* __restrict__ Ds,
     const int32_t* __restrict__ col_ptr, const int32_t* __restrict__ col_rows,
-    const int32_t* __restrict__ col_order, const float* __restrict__ dKlin,
-    const float* __restrict__ dVlin, int N, int Tn, int n_h, float scale, bf16* __restrict__ dK,
-    bf16* __restrict__ dV) {
+    const int32_t* __restrict__ col_order, const bf16* __restrict__ dHcol,
+    const float* __restrict__ dZcol, int phi, int N, int Tn, int n_h, float scale,
+    bf16* __restrict__ dK, bf16* __restrict__ dV) {
   using Lds = PairLds<D>;
   constexpr int NT = D / 32, KT = D / 16;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -179,7 +179,9 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
     if (s + 1 < cnt && wu < 2) stats[(buf ^ 1) * 2 * kBlk + wu * kBlk + lane_id()] = wu == 0 ? streg * kLog2e : streg;
   };
   // K_j and V_j come in as tiles through the second pair buffer (whole rows per load, zeros past
-  // the end of the sequence) and are picked up from there in operand layout
+  // the end of the sequence) and are picked up from there in operand layout.  With a linear
+  // branch, the aggregated dH^T of this key block (d x d, stored [b][a]) comes in through the
+  // first pair buffer: rows 0..63 in the Q slot, the rest in the dO slot.
   {
     const BufDesc rk = tile_rsrc(K + ((size_t)bh * N + k0) * D, cols * T::ROW_BYTES);
     const BufDesc rv = tile_rsrc(V + ((size_t)bh * N + k0) * D, cols * T::ROW_BYTES);
@@ -189,33 +191,123 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
       load_to_lds16(rv, ldv, 4096 * k, lds0 + Lds::BUF + Lds::TILE + 4096 * k);
     }
   }
-  if (cnt > 0) issue(0, 0);
+  if (dHcol) {
+    const bf16* M = dHcol + ((size_t)bh * Tn + j) * (D * D);
+#pragma unroll
+    for (int h = 0; h < (D + kBlk - 1) / kBlk; ++h) {
+      const BufDesc rm = tile_rsrc(M + (size_t)h * kBlk * D, min(kBlk, D - h * kBlk) * T::ROW_BYTES);
+#pragma unroll
+      for (int k = 0; k < T::IPW; ++k) load_to_lds16(rm, ldv, 4096 * k, lds0 + h * Lds::TILE + 4096 * k);
+    }
+  } else if (cnt > 0) {
+    issue(0, 0);
+  }
   wait_vm0();
   __syncthreads();
-  if (cnt > 0 && wu < 2) stats[wu * kBlk + lane_id()] = wu == 0 ? streg * kLog2e : streg;
-  {
-    TileAddr<D> ka;
-    ka.init(32 * kh, l);
+  TileAddr<D> ka;
+  ka.init(32 * kh, l);
 #pragma unroll
-    for (int t = 0; t < KT; ++t) {
-      kf[t] = lds_row(smem, ka.row(t) + Lds::BUF);
-      const bf16x8 v = lds_row(smem, ka.row(t) + Lds::BUF + Lds::TILE);
-      if (t < VR) vf[t] = v;
-      else if (qh == 0) *reinterpret_cast<bf16x8*>(smem + vpark + (t - VR) * 1024) = v;
-    }
+  for (int t = 0; t < KT; ++t) {
+    kf[t] = lds_row(smem, ka.row(t) + Lds::BUF);
+    const bf16x8 v = lds_row(smem, ka.row(t) + Lds::BUF + Lds::TILE);
+    if (t < VR) vf[t] = v;
+    else if (qh == 0) *reinterpret_cast<bf16x8*>(smem + vpark + (t - VR) * 1024) = v;
   }
 #pragma unroll
   for (int t = 0; t < KT; ++t) {
     pin_loaded(kf[t]);
     if (t < VR) pin_loaded(vf[t]);
   }
-  // (the first step's barrier orders these reads before the loads that reuse the buffer)
+  if (dHcol) {
+    // ---- linear branch of Alg. 2 for key block j, as the start value of the accumulators:
+    // the qh = 0 waves take dV += phi(K_j) dH_j, the qh = 1 waves dK += d phi(K_j) / d K_j applied to
+    // (V_j dH_j^T + dZ_j); each pair of waves adds its halves up at the end anyway.
+    constexpr int RB = 16 * T::ROW_BYTES;
+    float kmx, kinv;
+    phi_stats<KT>(kf, phi, kmx, kinv);
+    if (wu < 2) {
+      // dV^T[b][n] = sum_a M[b][a] phi(K)[n][a]: rows b of M are the A operand
+      bf16x8 kp[KT];
+#pragma unroll
+      for (int t = 0; t < KT; ++t)
+#pragma unroll
+        for (int s2 = 0; s2 < 8; ++s2)
+          kp[t][s2] = (__bf16)(kok ? phi_val((float)kf[t][s2], phi, kmx, kinv) : 0.0f);
+      TileAddr<D> ma;
+      ma.init(0, l);
+#pragma unroll
+      for (int bt = 0; bt < NT; ++bt)
+#pragma unroll
+        for (int t = 0; t < KT; ++t)
+          dvT[bt] = mfma32(lds_row(smem, ma.row(t) + (bt / 2) * Lds::TILE + (bt % 2) * 2 * RB), kp[t], dvT[bt]);
+    } else {
+      // d phi(K)^T[a][n] = sum_b M[b][a] V[n][b] + dZ[a]: M^T through the transposing read, whose
+      // k order is the one a C tile hands over, so V is picked up in that order too (two 8-byte
+      // pieces per k-step: features 16 t + 4 g .. and 16 t + 8 + 4 g ..)
+      TileAddr<D> ma;
+      ma.init(0, l);
+      const int vrow = Lds::BUF + Lds::TILE + krow * T::ROW_BYTES + 8 * g;
+      const int krw = Lds::BUF + krow * T::ROW_BYTES + 8 * g;
+      const int ksw = swz<D>(krow);
+#pragma unroll
+      for (int t = 0; t < KT; ++t) {
+        const bf16x4 v0 = *reinterpret_cast<const bf16x4*>(smem + vrow + (((2 * t) ^ ksw) << 4));
+        const bf16x4 v1 = *reinterpret_cast<const bf16x4*>(smem + vrow + (((2 * t + 1) ^ ksw) << 4));
+        bf16x8 vb;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          vb[e] = v0[e];
+          vb[4 + e] = v1[e];
+        }
+        const int base = (t / 4) * Lds::TILE + (t % 4) * RB;   // rows b = 16 t .. of M
+#pragma unroll
+        for (int at = 0; at < NT; ++at)
+          dkT[at] = mfma32(lds_tr<D>(smem, ma.tr(0, at) + base, ma.tr(1, at) + base), vb, dkT[at]);
+      }
+      const float* dZ = dZcol + ((size_t)bh * Tn + j) * D;
+      float dot = 0.0f;
+#pragma unroll
+      for (int at = 0; at < NT; ++at)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const f32x4 z4 = *reinterpret_cast<const f32x4*>(dZ + 32 * at + 8 * r4 + 4 * g);
+          const bf16x4 k4 = *reinterpret_cast<const bf16x4*>(smem + krw + (((4 * at + r4) ^ ksw) << 4));
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const float x = (float)k4[r];
+            const float y = phi == 0 ? phi_val(x, 0, kmx, kinv) : (x > 0.0f ? 1.0f : fast_exp2(x * kLog2e));
+            const float v = dkT[at][4 * r4 + r] + z4[r];
+            dkT[at][4 * r4 + r] = v;
+            dot = fmaf(v, y, dot);
+          }
+        }
+      dot += __shfl_xor(dot, 32, 64);
+      const float dtot = phi == 0 ? dot : 0.0f;
+      const float rs = 1.0f / scale;   // the epilogue multiplies the whole dK sum by scale
+#pragma unroll
+      for (int at = 0; at < NT; ++at)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const bf16x4 k4 = *reinterpret_cast<const bf16x4*>(smem + krw + (((4 * at + r4) ^ ksw) << 4));
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const float x = (float)k4[r];
+            const float y = phi == 0 ? phi_val(x, 0, kmx, kinv) : (x > 0.0f ? 1.0f : fast_exp2(x * kLog2e));
+            dkT[at][4 * r4 + r] = kok ? y * (dkT[at][4 * r4 + r] - dtot) * rs : 0.0f;
+          }
+        }
+    }
+    __syncthreads();   // both pair buffers are free again
+    if (cnt > 0) issue(0, 0);
+  }
+  if (cnt > 0 && wu < 2) stats[wu * kBlk + lane_id()] = wu == 0 ? streg * kLog2e : streg;
+  // (the first step's barrier orders the reads above before the loads that reuse the buffers)
   for (int s = 0; s < cnt; s += 2) {
     step(s, 0);
     if (s + 1 < cnt) step(s + 1, 1);
   }
   // ---- add the two query halves in a row-major staging area, then every thread takes 16-byte
-  // pieces of whole rows: adds the linear-branch parts and stores (coalesced both ways)
+  // pieces of whole rows and stores them (coalesced)
   __syncthreads();   // every wave is done with the tiles
   constexpr int SP = Lds::SP;
   float* stg = reinterpret_cast<float*>(smem);   // [dV | dK][64 keys][SP]
@@ -259,14 +351,11 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
       const size_t o = ((size_t)bh * N + k0 + row) * D + 4 * c4;
       const f32x4 sv = *reinterpret_cast<const f32x4*>(stg + row * SP + 4 * c4);
       const f32x4 sk = *reinterpret_cast<const f32x4*>(stg + (kBlk + row) * SP + 4 * c4);
-      f32x4 lv = {0.0f, 0.0f, 0.0f, 0.0f}, lk = {0.0f, 0.0f, 0.0f, 0.0f};
-      if (dVlin) lv = *reinterpret_cast<const f32x4*>(dVlin + o);
-      if (dKlin) lk = *reinterpret_cast<const f32x4*>(dKlin + o);
       bf16x4 pv, pk;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        pv[r] = (__bf16)(sv[r] + lv[r]);
-        pk[r] = (__bf16)(sk[r] * scale + lk[r]);
+        pv[r] = (__bf16)sv[r];
+        pk[r] = (__bf16)(sk[r] * scale);
       }
       *reinterpret_cast<bf16x4*>(dV + o) = pv;
       *reinterpret_cast<bf16x4*>(dK + o) = pk;
@@ -388,7 +477,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(
 
 template <int D>
 hipError_t sparse_impl(const Shape& s, const BwdArgs& a, const float* Ds, const float* dQlin,
-                       const float* dKlin, const float* dVlin, hipStream_t st) {
+                       const void* dHZcol, hipStream_t st) {
+  const float* dZcol = dHZcol ? reinterpret_cast<const float*>((const char*)dHZcol + state_z_offset(s)) : nullptr;
   constexpr int lds = PairLds<D>::BYTES;
   SLA_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dkdv_mfma_kernel<D>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, PairLds<D>::DKDV));
@@ -396,7 +486,8 @@ hipError_t sparse_impl(const Shape& s, const BwdArgs& a, const float* Ds, const 
     KernelTimer kt("bwd_sparse_kv", st);
     bwd_dkdv_mfma_kernel<D><<<dim3(s.T * s.BH), 256, PairLds<D>::DKDV, st>>>(
         (const bf16*)a.Q, (const bf16*)a.K, (const bf16*)a.V, (const bf16*)a.dO, a.L, Ds, a.col_ptr,
-        a.col_rows, a.col_order, dKlin, dVlin, s.N, s.T, s.n_h, s.scale, (bf16*)a.dK, (bf16*)a.dV);
+        a.col_rows, a.col_order, (const bf16*)dHZcol, dZcol, s.phi, s.N, s.T, s.n_h, s.scale, (bf16*)a.dK,
+        (bf16*)a.dV);
   }
   SLA_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dq_mfma_kernel<D>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, lds));
@@ -412,10 +503,9 @@ hipError_t sparse_impl(const Shape& s, const BwdArgs& a, const float* Ds, const 
 }  // namespace
 
 hipError_t mfma_backward_sparse(const Shape& s, const BwdArgs& a, const float* Ds,
-                                const float* dQlin, const float* dKlin, const float* dVlin,
-                                hipStream_t st) {
-  return s.d == 64 ? sparse_impl<64>(s, a, Ds, dQlin, dKlin, dVlin, st)
-                   : sparse_impl<128>(s, a, Ds, dQlin, dKlin, dVlin, st);
+                                const float* dQlin, const void* dHZcol, hipStream_t st) {
+  return s.d == 64 ? sparse_impl<64>(s, a, Ds, dQlin, dHZcol, st)
+                   : sparse_impl<128>(s, a, Ds, dQlin, dHZcol, st);
 }
 
 }  // namespace sla

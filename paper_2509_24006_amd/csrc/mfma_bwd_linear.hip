@@ -12,32 +12,6 @@ namespace {
 
 constexpr int kRSl(int D) { return D + 8; }
 
-// phi statistics of a token whose features sit in B-operand fragments (lane holds features
-// 16 t + 8 g + s, its partner lane l ^ 32 the others): softmax max and 1 / sum.
-template <int KT>
-__device__ __forceinline__ void phi_stats(const bf16x8 (&xf)[KT], int phi, float& mx, float& inv) {
-  mx = 0.0f;
-  inv = 1.0f;
-  if (phi != 0) return;
-  mx = -INFINITY;
-#pragma unroll
-  for (int t = 0; t < KT; ++t)
-#pragma unroll
-    for (int s = 0; s < 8; ++s) mx = fmaxf(mx, (float)xf[t][s]);
-  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-  float sum = 0.0f;
-#pragma unroll
-  for (int t = 0; t < KT; ++t)
-#pragma unroll
-    for (int s = 0; s < 8; ++s) sum += fast_exp2(((float)xf[t][s] - mx) * kLog2e);
-  sum += __shfl_xor(sum, 32, 64);
-  inv = 1.0f / sum;
-}
-
-__device__ __forceinline__ float phi_val(float x, int phi, float mx, float inv) {
-  return phi == 0 ? fast_exp2((x - mx) * kLog2e) * inv : (x > 0.0f ? x + 1.0f : fast_exp2(x * kLog2e));
-}
-
 // Stages a d x d bf16 matrix stored [b][a] (b-major) into LDS transposed, [a][b] (stride RS).
 template <int D>
 __device__ __forceinline__ void stage_matrix_t(const bf16* __restrict__ src, bf16* dst, int RS) {
@@ -251,119 +225,6 @@ __global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
   }
 }
 
-// ------------------------------------------------------------------ key side
-template <int D>
-struct LinkLds {
-  static constexpr int RS = kRSl(D);
-  static constexpr int H_ELEMS = D * RS;   // dH [a][b]
-  static constexpr int BYTES = H_ELEMS * 2 + 2 * kBlk * 4;
-};
-
-template <int D>
-__global__ __launch_bounds__(256) void bwd_link_mfma_kernel(
-    const bf16* __restrict__ K, const bf16* __restrict__ V, const bf16* __restrict__ dH16,
-    const float* __restrict__ dZs, int N,
-    int Tn, int phi, float* __restrict__ dKlin, float* __restrict__ dVlin) {
-  using Lds = LinkLds<D>;
-  constexpr int RS = Lds::RS, NT = D / 32, KT = D / 16, HT = NT / 2;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  bf16* Hs = reinterpret_cast<bf16*>(smem);
-  float* dotp = reinterpret_cast<float*>(smem + Lds::H_ELEMS * 2);
-  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
-  const int nh = w & 1, par = w >> 1;
-  const int j = blockIdx.x, bh = blockIdx.y;
-  const int n0 = j * kBlk, cnt = min(kBlk, N - n0);
-  const int nrow = nh * 32 + ln;
-  const bool nok = nrow < cnt;
-  const size_t noff = ((size_t)bh * N + n0 + nrow) * D;
-  const bf16* Hrow = dH16 + ((size_t)bh * Tn + j) * (D * D);   // dH^T stored [b][a]
-  const float* dZ = dZs + ((size_t)bh * Tn + j) * D;
-  stage_matrix_t<D>(Hrow, Hs, RS);
-  bf16x8 kf[KT], vf[KT];
-#pragma unroll
-  for (int t = 0; t < KT; ++t) {
-    kf[t] = nok ? *reinterpret_cast<const bf16x8*>(K + noff + 16 * t + 8 * g) : zero_bf16x8();
-    vf[t] = nok ? *reinterpret_cast<const bf16x8*>(V + noff + 16 * t + 8 * g) : zero_bf16x8();
-  }
-  float kmx, kinv;
-  phi_stats<KT>(kf, phi, kmx, kinv);
-  bf16x8 kp[KT];
-#pragma unroll
-  for (int t = 0; t < KT; ++t)
-#pragma unroll
-    for (int s = 0; s < 8; ++s) kp[t][s] = (__bf16)(nok ? phi_val((float)kf[t][s], phi, kmx, kinv) : 0.0f);
-  // linear part of dV^T[b][n] = sum_a dH[a][b] phi(K)[n][a]; rows b of the stored matrix are the A operand
-#pragma unroll
-  for (int h2 = 0; h2 < HT; ++h2) {
-    const int bt = par * HT + h2;
-    f32x16 acc = zero_f32x16();
-#pragma unroll
-    for (int t = 0; t < KT; ++t) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(Hrow + (size_t)(32 * bt + ln) * D + 16 * t + 8 * g);
-      acc = mfma32(a, kp[t], acc);
-    }
-    if (nok) {
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        f32x4 o4;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) o4[r] = acc[4 * r4 + r];
-        *reinterpret_cast<f32x4*>(dVlin + noff + 32 * bt + 8 * r4 + 4 * g) = o4;
-      }
-    }
-  }
-  __syncthreads();
-  // dK^phi^T[a][n] = sum_b dH[a][b] V[n][b] + dZ[a]; then through phi
-  f32x16 dk[HT];
-  float yc[HT][16];
-  float dot = 0.0f;
-#pragma unroll
-  for (int h2 = 0; h2 < HT; ++h2) {
-    const int at = par * HT + h2;
-    dk[h2] = zero_f32x16();
-#pragma unroll
-    for (int t = 0; t < KT; ++t) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(Hs + (32 * at + ln) * RS + 16 * t + 8 * g);
-      dk[h2] = mfma32(a, vf[t], dk[h2]);
-    }
-#pragma unroll
-    for (int r4 = 0; r4 < 4; ++r4) {
-      const int a0 = 32 * at + 8 * r4 + 4 * g;
-      const f32x4 z4 = *reinterpret_cast<const f32x4*>(dZ + a0);
-      bf16x4 k4;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) k4[r] = (__bf16)0.0f;
-      if (nok) k4 = *reinterpret_cast<const bf16x4*>(K + noff + a0);
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float v = dk[h2][4 * r4 + r] + z4[r];
-        const float x = (float)k4[r];
-        const float y = phi == 0 ? phi_val(x, 0, kmx, kinv) : (x > 0.0f ? 1.0f : fast_exp2(x * kLog2e));
-        dk[h2][4 * r4 + r] = v;
-        yc[h2][4 * r4 + r] = y;
-        dot = fmaf(v, y, dot);
-      }
-    }
-  }
-  dot += __shfl_xor(dot, 32, 64);
-  if (g == 0) dotp[par * kBlk + nrow] = dot;
-  __syncthreads();
-  const float dtot = phi == 0 ? dotp[nrow] + dotp[kBlk + nrow] : 0.0f;
-  if (nok) {
-#pragma unroll
-    for (int h2 = 0; h2 < HT; ++h2) {
-      const int at = par * HT + h2;
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        f32x4 o4;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) o4[r] = yc[h2][4 * r4 + r] * (dk[h2][4 * r4 + r] - dtot);
-        *reinterpret_cast<f32x4*>(dKlin + noff + 32 * at + 8 * r4 + 4 * g) = o4;
-      }
-    }
-  }
-}
-
 // ------------------------------------------------------------------ dW partial sums
 // Workgroup g sums (O^l)^T dO over token tiles g, g + G, ...; wave w owns rows 32w.. of dW.
 template <int D>
@@ -440,19 +301,6 @@ hipError_t pre_impl(const Shape& s, const BwdArgs& a, float* Ds, bf16* dHZ, floa
   return hipGetLastError();
 }
 
-template <int D>
-hipError_t link_impl(const Shape& s, const BwdArgs& a, const void* dHZcol, float* dKlin,
-                     float* dVlin, hipStream_t st) {
-  constexpr int lds = LinkLds<D>::BYTES;
-  SLA_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_link_mfma_kernel<D>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-  KernelTimer kt("bwd_link", st);
-  bwd_link_mfma_kernel<D><<<dim3(s.T, s.BH), 256, lds, st>>>((const bf16*)a.K, (const bf16*)a.V, (const bf16*)dHZcol,
-                                                           (const float*)((const char*)dHZcol + state_z_offset(s)),
-                                                           s.N, s.T, s.phi, dKlin, dVlin);
-  return hipGetLastError();
-}
-
 }  // namespace
 
 hipError_t mfma_backward_pre(const Shape& s, const BwdArgs& a, float* Ds, void* dHZ16, float* dQlin,
@@ -460,12 +308,6 @@ hipError_t mfma_backward_pre(const Shape& s, const BwdArgs& a, float* Ds, void* 
   bf16* dHZ = reinterpret_cast<bf16*>(dHZ16);
   return s.d == 64 ? pre_impl<64>(s, a, Ds, dHZ, dQlin, dWpart, nparts, st)
                    : pre_impl<128>(s, a, Ds, dHZ, dQlin, dWpart, nparts, st);
-}
-
-hipError_t mfma_backward_link(const Shape& s, const BwdArgs& a, const void* dHZcol, float* dKlin,
-                              float* dVlin, hipStream_t st) {
-  return s.d == 64 ? link_impl<64>(s, a, dHZcol, dKlin, dVlin, st)
-                   : link_impl<128>(s, a, dHZcol, dKlin, dVlin, st);
 }
 
 }  // namespace sla

@@ -379,5 +379,31 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
+// phi statistics of a token whose features sit in B-operand fragments (lane holds features
+// 16 t + 8 g + s, its partner lane l ^ 32 the others): softmax max and 1 / sum.
+template <int KT>
+__device__ __forceinline__ void phi_stats(const bf16x8 (&xf)[KT], int phi, float& mx, float& inv) {
+  mx = 0.0f;
+  inv = 1.0f;
+  if (phi != 0) return;
+  mx = -INFINITY;
+#pragma unroll
+  for (int t = 0; t < KT; ++t)
+#pragma unroll
+    for (int s = 0; s < 8; ++s) mx = fmaxf(mx, (float)xf[t][s]);
+  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  float sum = 0.0f;
+#pragma unroll
+  for (int t = 0; t < KT; ++t)
+#pragma unroll
+    for (int s = 0; s < 8; ++s) sum += fast_exp2(((float)xf[t][s] - mx) * kLog2e);
+  sum += __shfl_xor(sum, 32, 64);
+  inv = 1.0f / sum;
+}
+
+__device__ __forceinline__ float phi_val(float x, int phi, float mx, float inv) {
+  return phi == 0 ? fast_exp2((x - mx) * kLog2e) * inv : (x > 0.0f ? x + 1.0f : fast_exp2(x * kLog2e));
+}
+
 }  // namespace sla
 #endif

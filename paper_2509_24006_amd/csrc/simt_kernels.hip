@@ -906,10 +906,8 @@ hipError_t backward_bf16(const Shape& s, const BwdArgs& a, hipStream_t st) {
   if (lin) {
     SLA_TRY(mfma_aggregate(w.dHZ, a.indT, s, w.dHZcol,
                            reinterpret_cast<float*>(reinterpret_cast<char*>(w.dHZcol) + state_z_offset(s)), st));
-    SLA_TRY(mfma_backward_link(s, a, w.dHZcol, w.dKlin, w.dVlin, st));
   }
-  return mfma_backward_sparse(s, a, w.Ds, lin ? w.dQlin : nullptr, lin ? w.dKlin : nullptr,
-                              lin ? w.dVlin : nullptr, st);
+  return mfma_backward_sparse(s, a, w.Ds, lin ? w.dQlin : nullptr, lin ? w.dHZcol : nullptr, st);
 }
 
 }  // namespace

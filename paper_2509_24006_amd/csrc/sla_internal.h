@@ -59,10 +59,12 @@ struct BwdArgs {
   char* ws;  // workspace, ws_backward_bytes
 };
 size_t simt_backward_ws_bytes(const Shape& s);
-// critical-block gradients on the matrix cores (mfma_bwd.hip); the *lin pointers may be null
+// critical-block gradients on the matrix cores (mfma_bwd.hip).  dQlin: linear-branch part of dQ.
+// dHZcol: dH and dZ summed over the marginal blocks of each key block (bf16 matrices, then float
+// vectors at state_z_offset); the dK/dV kernel turns them into the linear-branch parts of dK and
+// dV itself.  Both may be null (no marginal block).
 hipError_t mfma_backward_sparse(const Shape& s, const BwdArgs& a, const float* Ds,
-                                const float* dQlin, const float* dKlin, const float* dVlin,
-                                hipStream_t st);
+                                const float* dQlin, const void* dHZcol, hipStream_t st);
 hipError_t simt_backward(const Shape& s, const BwdArgs& a, hipStream_t st);
 
 // ---- bf16 matrix-core path (mfma_fwd.hip)
@@ -78,8 +80,6 @@ inline size_t state_z_offset(const Shape& s) { return ((size_t)s.BH * s.T * s.d 
 // linear branch and Proj gradients on the matrix cores (mfma_bwd_linear.hip)
 hipError_t mfma_backward_pre(const Shape& s, const BwdArgs& a, float* Ds, void* dHZ16, float* dQlin,
                              float* dWpart, int nparts, hipStream_t st);
-hipError_t mfma_backward_link(const Shape& s, const BwdArgs& a, const void* dHZcol, float* dKlin,
-                              float* dVlin, hipStream_t st);
 
 // Brackets one kernel launch with events when profiling is on (profile.hip).
 class KernelTimer {
