@@ -359,6 +359,33 @@ __device__ __forceinline__ bf16x8 lds_tr(const unsigned char* smem, int off0, in
 
 __device__ __forceinline__ int wave_uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
+// Wave-local: NT C tiles of 32 rows (lane l % 32 = row, register r of tile t = column
+// 32 t + c_row(r, l / 32)) go to LDS as bf16 rows and from there to global memory in 16-byte
+// pieces of whole rows, instead of 8-byte pieces scattered over 32 rows.  `stage` is this wave's
+// own LDS area of 32 * (64 NT + 16) bytes; dst points at row 0, column 0 of the tiles; rows at and
+// beyond rows_valid are not written.
+template <int NT>
+__device__ __forceinline__ void store_rows_bf16(unsigned char* stage, const f32x16 (&c)[NT], bf16* dst,
+                                                int row_stride, int rows_valid, int l) {
+  constexpr int PB = 64 * NT + 16, PPR = 4 * NT;
+  const int g = l >> 5, ln = l & 31;
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+      bf16x4 pk;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) pk[r] = (__bf16)c[t][4 * r4 + r];
+      *reinterpret_cast<bf16x4*>(stage + ln * PB + (32 * t + 8 * r4 + 4 * g) * 2) = pk;
+    }
+#pragma unroll
+  for (int it = 0; it < 32 * PPR / 64; ++it) {
+    const int idx = it * 64 + l, row = idx / PPR, pc = idx % PPR;
+    const u32x4 v = *reinterpret_cast<const u32x4*>(stage + row * PB + pc * 16);
+    if (row < rows_valid) *reinterpret_cast<u32x4*>(dst + (size_t)row * row_stride + pc * 8) = v;
+  }
+}
+
 // Workgroups are dealt to the 8 XCDs (each with its own L2) round-robin by linear index.  With a
 // grid of 8 * ceil(T / 8) workgroups per head, XCD x gets the contiguous blocks
 // [x ceil(T/8), (x+1) ceil(T/8)) in ascending order, so that neighbouring query blocks -- which

@@ -174,7 +174,6 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
   using Lds = FwdLds<D>;
   constexpr int NT = D / 32, KT = D / 16;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  float* xch = reinterpret_cast<float*>(smem);
   float* ml = reinterpret_cast<float*>(smem + Lds::BYTES - 1024);   // [par][qh][32][2]
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
   const int qh = w & 1, par = w >> 1;
@@ -203,7 +202,19 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
     issue_tile_load<D>(Kb + (size_t)jj * kBlk * D, cols, smem, off, w, l);
     issue_tile_load<D>(Vb + (size_t)jj * kBlk * D, cols, smem, off + Lds::TILE, w, l);
   };
+  // aggregated state H_i (d x d bf16; rows 0..63 in the K slot, the rest in the V slot) and the
+  // prepared projection matrix go global -> LDS like the tiles
+  using T = SwzTile<D>;
+  auto issue_matrix = [&](const bf16* M, int off) {
+#pragma unroll
+    for (int h = 0; h < (D + kBlk - 1) / kBlk; ++h)
+      issue_tile_load<D>(M + (size_t)h * kBlk * D, min(kBlk, D - h * kBlk), smem, off + h * Lds::TILE, w, l);
+  };
+  const bf16* Hrow = H16 + ((size_t)bh * Tn + i) * (D * D);
+  // the pair buffer of the last step takes the exchanges afterwards, the other one H_i
+  const int xoff = ((n_h + 1) & 1) * Lds::BUF, hoff = Lds::BUF - xoff;
   if (n_h > 0) issue(0);
+  else if (n_0 > 0) issue_matrix(Hrow, hoff);
 #pragma unroll
   for (int t = 0; t < KT; ++t) pin_loaded(qf[t]);
   for (int s = 0; s < n_h; ++s) {
@@ -211,6 +222,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
     wait_vm0();
     __syncthreads();   // tiles of step s have landed for every wave; step s-1 is fully consumed
     if (s + 1 < n_h) issue(s + 1);
+    else if (n_0 > 0) issue_matrix(Hrow, hoff);   // arrives under the last step
     const unsigned char* Ks = smem + (s & 1) * Lds::BUF;
     const unsigned char* Vs = Ks + Lds::TILE;
     // every LDS read of the step is issued first; the V operands arrive under the score
@@ -265,11 +277,13 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
     }
   }
   // ---- merge the two key-tile streams (par 0 / par 1) of each query half
+  float* xch = reinterpret_cast<float*>(smem + xoff);
   lsum += __shfl_xor(lsum, 32, 64);
   if (g == 0) {
     ml[((par * 2 + qh) * 32 + ln) * 2 + 0] = m;
     ml[((par * 2 + qh) * 32 + ln) * 2 + 1] = lsum;
   }
+  wait_vm0();        // this wave's share of H_i has landed
   __syncthreads();   // also: all waves are done with the K / V tiles
   const float m_o = ml[(((par ^ 1) * 2 + qh) * 32 + ln) * 2 + 0];
   const float l_o = ml[(((par ^ 1) * 2 + qh) * 32 + ln) * 2 + 1];
@@ -285,7 +299,8 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
   for (int et = 0; et < NT; ++et)
 #pragma unroll
     for (int r = 0; r < 16; ++r) oT[et][r] *= cw;
-  float* myx = xch + (size_t)qh * (D / 2) * 64;
+  float* myx = xch + (size_t)qh * (D / 2) * 64;   // 64 D bytes: exchange, then this query half's staging
+  unsigned char* mystage = reinterpret_cast<unsigned char*>(myx);
   if (par == 1) {
 #pragma unroll
     for (int et = 0; et < NT; ++et)
@@ -293,24 +308,15 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
       for (int r = 0; r < 16; ++r) myx[(et * 16 + r) * 64 + l] = oT[et][r];
   }
   __syncthreads();
-  const size_t orow = ((size_t)bh * N + q0 + qrow) * D;
+  const size_t orow0 = ((size_t)bh * N + q0 + 32 * qh) * D;   // first query of this wave
+  const int wrows = rows - 32 * qh;                           // valid ones among its 32
   if (par == 0) {
 #pragma unroll
     for (int et = 0; et < NT; ++et)
 #pragma unroll
       for (int r = 0; r < 16; ++r) oT[et][r] += myx[(et * 16 + r) * 64 + l];
     if (L && g == 0 && qok) L[(size_t)bh * N + q0 + qrow] = Lval;
-    if (Os && qok) {
-#pragma unroll
-      for (int et = 0; et < NT; ++et)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          bf16x4 pk;
-#pragma unroll
-          for (int r = 0; r < 4; ++r) pk[r] = (__bf16)oT[et][4 * r4 + r];
-          *reinterpret_cast<bf16x4*>(Os + orow + 32 * et + 8 * r4 + 4 * g) = pk;
-        }
-    }
+    if (Os) store_rows_bf16<NT>(mystage, oT, Os + orow0, D, wrows, l);
   }
   // ---- linear branch: wave par computes O^l for features [par D/2, (par+1) D/2) of its queries
   // (both waves accumulate their share of O^l W into oT; par 1 starts again from zero)
@@ -319,24 +325,11 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
     for (int et = 0; et < NT; ++et) oT[et] = zero_f32x16();
   }
   if (n_0 > 0) {
+    __syncthreads();   // the exchange area is free: the projection matrix goes there
+    issue_matrix(WTp, xoff);
     // phi(Q) of this lane's query: the lane holds features 16 t + 8 g + s, its partner the rest
-    float qmx = 0.0f, qinv = 1.0f;
-    if (phi == 0) {
-      qmx = -INFINITY;
-#pragma unroll
-      for (int t = 0; t < KT; ++t)
-#pragma unroll
-        for (int s2 = 0; s2 < 8; ++s2) qmx = fmaxf(qmx, (float)qf[t][s2]);
-      qmx = fmaxf(qmx, __shfl_xor(qmx, 32, 64));
-      float sum = 0.0f;
-#pragma unroll
-      for (int t = 0; t < KT; ++t)
-#pragma unroll
-        for (int s2 = 0; s2 < 8; ++s2) sum += fast_exp2(((float)qf[t][s2] - qmx) * kLog2e);
-      sum += __shfl_xor(sum, 32, 64);
-      qinv = 1.0f / sum;
-    }
-    const bf16* Hrow = H16 + ((size_t)bh * Tn + i) * (D * D);
+    float qmx, qinv;
+    phi_stats<KT>(qf, phi, qmx, qinv);
     const float* Z = Zs + ((size_t)bh * Tn + i) * D;
     bf16x8 qp[KT];
     float den = 0.0f;
@@ -346,48 +339,43 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
       const f32x4 z1 = *reinterpret_cast<const f32x4*>(Z + 16 * t + 8 * g + 4);
 #pragma unroll
       for (int s2 = 0; s2 < 8; ++s2) {
-        const float x = (float)qf[t][s2];
-        const float y = phi == 0 ? fast_exp2((x - qmx) * kLog2e) * qinv
-                                 : (x > 0.0f ? x + 1.0f : fast_exp2(x * kLog2e));
-        qp[t][s2] = (__bf16)y;
+        qp[t][s2] = (__bf16)phi_val((float)qf[t][s2], phi, qmx, qinv);
         den = fmaf((float)qp[t][s2], s2 < 4 ? z0[s2] : z1[s2 - 4], den);
       }
     }
     den += __shfl_xor(den, 32, 64);
     const float dinv = 1.0f / den;
     constexpr int HT = NT / 2;     // e-tiles per wave
+    TileAddr<D> ma;                // rows 32 (et % 2) + ln of a 64-row tile: + 2 RB per odd tile
+    ma.init(0, l);
+    constexpr int RB = 16 * T::ROW_BYTES;
+    f32x16 ol[HT];
 #pragma unroll
     for (int h2 = 0; h2 < HT; ++h2) {
       const int et = par * HT + h2;
-      f32x16 acc = zero_f32x16();
+      ol[h2] = zero_f32x16();
 #pragma unroll
-      for (int t = 0; t < KT; ++t) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(Hrow + (size_t)(32 * et + ln) * D + 16 * t + 8 * g);
-        acc = mfma32(a, qp[t], acc);
-      }
+      for (int t = 0; t < KT; ++t)
+        ol[h2] = mfma32(lds_row(smem, ma.row(t) + hoff + (et / 2) * Lds::TILE + (et % 2) * 2 * RB), qp[t], ol[h2]);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[r] *= dinv;
-      if (Ol && qok) {
+      for (int r = 0; r < 16; ++r) ol[h2][r] *= dinv;
+    }
+    wait_vm0();
+    __syncthreads();   // the projection matrix has landed; H_i is no longer needed
+    // O^T[e'][q] += sum_{e in this wave's tiles} W[e][e'] O^l[q][e]
 #pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          bf16x4 pk;
-#pragma unroll
-          for (int r = 0; r < 4; ++r) pk[r] = (__bf16)acc[4 * r4 + r];
-          *reinterpret_cast<bf16x4*>(Ol + orow + 32 * et + 8 * r4 + 4 * g) = pk;
-        }
-      }
-      // O^T[e'][q] += sum_{e in this tile} W[e][e'] O^l[q][e]
+    for (int h2 = 0; h2 < HT; ++h2) {
+      const int et = par * HT + h2;
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
-        const bf16x8 b = c_to_operand(acc, u);
+        const bf16x8 b = c_to_operand(ol[h2], u);
 #pragma unroll
-        for (int ep = 0; ep < NT; ++ep) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(WTp + (size_t)(32 * ep + ln) * D + 32 * et + 16 * u + 8 * g);
-          oT[ep] = mfma32(a, b, oT[ep]);
-        }
+        for (int ep = 0; ep < NT; ++ep)
+          oT[ep] = mfma32(lds_row(smem, ma.row(2 * et + u) + xoff + (ep / 2) * Lds::TILE + (ep % 2) * 2 * RB), b, oT[ep]);
       }
     }
-    __syncthreads();   // par 0 has consumed the first exchange
+    if (Ol) store_rows_bf16<HT>(smem + hoff + w * (32 * (64 * HT + 16)), ol, Ol + orow0 + par * (D / 2), D, wrows, l);
+    __syncthreads();   // everyone is done with the projection matrix
     if (par == 1) {
 #pragma unroll
       for (int et = 0; et < NT; ++et)
@@ -402,22 +390,13 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
         for (int r = 0; r < 16; ++r) oT[et][r] += myx[(et * 16 + r) * 64 + l];
     }
   }
-  if (par == 0 && qok) {
+  if (par == 0) {
+    store_rows_bf16<NT>(mystage, oT, O + orow0, D, wrows, l);
+    if (n_0 == 0 && Ol) {   // no marginal block: O^l is identically zero
 #pragma unroll
-    for (int et = 0; et < NT; ++et)
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        bf16x4 pk;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) pk[r] = (__bf16)oT[et][4 * r4 + r];
-        *reinterpret_cast<bf16x4*>(O + orow + 32 * et + 8 * r4 + 4 * g) = pk;
-        if (n_0 == 0 && Ol) {   // no marginal block: O^l is identically zero
-          bf16x4 zz;
-#pragma unroll
-          for (int r = 0; r < 4; ++r) zz[r] = (__bf16)0.0f;
-          *reinterpret_cast<bf16x4*>(Ol + orow + 32 * et + 8 * r4 + 4 * g) = zz;
-        }
-      }
+      for (int et = 0; et < NT; ++et) oT[et] = zero_f32x16();
+      store_rows_bf16<NT>(mystage, oT, Ol + orow0, D, wrows, l);
+    }
   }
 }
 

@@ -448,13 +448,28 @@ __global__ void fill_zero_kernel(float* __restrict__ p, size_t n) {
     p[i] = 0.0f;
 }
 
-__global__ void dw_reduce_kernel(const float* __restrict__ part, int nparts, int dd,
-                                 float* __restrict__ dW) {
-  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= dd) return;
-  float s = 0.0f;
-  for (int p = 0; p < nparts; ++p) s += part[(size_t)p * dd + idx];
-  dW[idx] = s;
+// dW = sum of the partial d x d sums.  A workgroup owns 64 consecutive elements; its four waves
+// take every fourth partial each (one element per lane, 256 contiguous bytes per load) and meet
+// in LDS.
+__global__ __launch_bounds__(256) void dw_reduce_kernel(const float* __restrict__ part, int nparts, int dd,
+                                                        float* __restrict__ dW) {
+  __shared__ float red[4][64];
+  const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
+  const int idx = blockIdx.x * 64 + l;
+  float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+  if (idx < dd) {
+    int p = w;
+    for (; p + 12 < nparts; p += 16) {
+      s0 += part[(size_t)p * dd + idx];
+      s1 += part[(size_t)(p + 4) * dd + idx];
+      s2 += part[(size_t)(p + 8) * dd + idx];
+      s3 += part[(size_t)(p + 12) * dd + idx];
+    }
+    for (; p < nparts; p += 4) s0 += part[(size_t)p * dd + idx];
+  }
+  red[w][l] = (s0 + s1) + (s2 + s3);
+  __syncthreads();
+  if (w == 0 && idx < dd) dW[idx] = (red[0][l] + red[1][l]) + (red[2][l] + red[3][l]);
 }
 
 // ------------------------------------------------------------------ backward, linear, query side
@@ -849,7 +864,7 @@ hipError_t backward_impl(const Shape& s, const BwdArgs& a, hipStream_t st) {
     }
     {
       KernelTimer kt("dw_reduce", st);
-      dw_reduce_kernel<<<(D * D + 255) / 256, 256, 0, st>>>(w.dWpart, w.nparts, D * D, a.dW);
+      dw_reduce_kernel<<<(D * D + 63) / 64, 256, 0, st>>>(w.dWpart, w.nparts, D * D, a.dW);
     }
   }
   if (lin) {
@@ -901,7 +916,7 @@ hipError_t backward_bf16(const Shape& s, const BwdArgs& a, hipStream_t st) {
   SLA_TRY(mfma_backward_pre(s, a, w.Ds, w.dHZ, w.dQlin, w.dWpart, w.nparts, st));   // dHZ holds bf16 rows
   {
     KernelTimer kt("dw_reduce", st);
-    dw_reduce_kernel<<<(s.d * s.d + 255) / 256, 256, 0, st>>>(w.dWpart, w.nparts, s.d * s.d, a.dW);
+    dw_reduce_kernel<<<(s.d * s.d + 63) / 64, 256, 0, st>>>(w.dWpart, w.nparts, s.d * s.d, a.dW);
   }
   if (lin) {
     SLA_TRY(mfma_aggregate(w.dHZ, a.indT, s, w.dHZcol,
