@@ -143,26 +143,6 @@ __global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
   __syncthreads();
   const float Dl = dlp[qrow] + dlp[kBlk + qrow];
   bf16* out = dHZ + ((size_t)bh * Tn + i) * (D * D + D);
-  // dH_i^T[b][c] = sum_q dO^l[q][b] a[q][c]; wave w owns b-tiles w, w+4, ...
-  for (int bt = w; bt < NT; bt += 4) {
-    f32x16 acc[NT];
-#pragma unroll
-    for (int ct = 0; ct < NT; ++ct) acc[ct] = zero_f32x16();
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(Gt + (32 * bt + ln) * kVS + 16 * u + 8 * g);
-#pragma unroll
-      for (int ct = 0; ct < NT; ++ct) {
-        const bf16x8 b = *reinterpret_cast<const bf16x8*>(At + (32 * ct + ln) * kVS + 16 * u + 8 * g);
-        acc[ct] = mfma32(a, b, acc[ct]);
-      }
-    }
-#pragma unroll
-    for (int ct = 0; ct < NT; ++ct)
-#pragma unroll
-      for (int r = 0; r < 16; ++r)
-        out[(size_t)(32 * bt + c_row(r, g)) * D + 32 * ct + ln] = __float2bfloat16(acc[ct][r]);
-  }
   // dZ_i[c] = - sum_q a[q][c] D^l_q
   if (tid < D) {
     float z = 0.0f;
@@ -170,6 +150,28 @@ __global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
       z = fmaf(__bfloat162float(At[tid * kVS + q]), dlp[q] + dlp[kBlk + q], z);
     out[(size_t)D * D + tid] = __float2bfloat16(-z);
   }
+  // dH_i^T[b][c] = sum_q dO^l[q][b] a[q][c]; wave w owns b-tile w.  The product is formed with b
+  // along the lanes (C tile rows = c), so that a lane holds consecutive c of one stored row.
+  static_assert(NT <= 4, "one b-tile per wave");
+  f32x16 acc[NT];
+#pragma unroll
+  for (int ct = 0; ct < NT; ++ct) acc[ct] = zero_f32x16();
+  if (w < NT) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(Gt + (32 * w + ln) * kVS + 16 * u + 8 * g);
+#pragma unroll
+      for (int ct = 0; ct < NT; ++ct) {
+        const bf16x8 b = *reinterpret_cast<const bf16x8*>(At + (32 * ct + ln) * kVS + 16 * u + 8 * g);
+        acc[ct] = mfma32(b, a, acc[ct]);
+      }
+    }
+  }
+  __syncthreads();   // the transposed tiles are free: they stage the output rows, then H_i
+  static_assert(4 * 32 * (64 * NT + 16) <= (Lds::GT_ELEMS + Lds::AT_ELEMS) * 2, "staging fits over the transposed tiles");
+  if (w < NT)
+    store_rows_bf16<NT>(reinterpret_cast<unsigned char*>(Gt) + w * (32 * (64 * NT + 16)), acc, out + (size_t)(32 * w) * D, D,
+                        32, l);
   __syncthreads();
   stage_matrix_t<D>(Hrow, Hs, RS);
   __syncthreads();

@@ -400,6 +400,11 @@ inline int xcd_grid(int T) { return 8 * ((T + 7) / 8); }
 
 // all outstanding global loads of this wave (including those that write LDS) have completed
 __device__ __forceinline__ void wait_vm0() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// all but the N most recent ones have completed (loads complete in the order they were issued)
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 

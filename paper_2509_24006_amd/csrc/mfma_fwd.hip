@@ -157,11 +157,16 @@ __global__ __launch_bounds__(256) void states_mfma_kernel(const bf16* __restrict
 // directly (swizzled, double-buffered, one barrier per step); V is read transposed.
 template <int D>
 struct FwdLds {
+  // Five tile slots: K_j is needed at the start of a step and is fetched two steps ahead (ring of
+  // three), V_j only after the softmax and is fetched one step ahead (ring of two).  At d = 128
+  // that is all of a CU's LDS for two workgroups.  After the loop the slots hold the exchange
+  // between the two key streams, H_i, the projection matrix and the running-softmax statistics.
   static constexpr int TILE = SwzTile<D>::BYTES;
-  static constexpr int BUF = 2 * TILE;                    // K_j and V_j
-  static constexpr int XCH_BYTES = 2 * (D / 2) * 64 * 4;  // exchange of C registers between par 0/1
-  static constexpr int TILE_BYTES = 2 * BUF;
-  static constexpr int BYTES = (TILE_BYTES > XCH_BYTES ? TILE_BYTES : XCH_BYTES) + 1024;
+  static constexpr int XCH_HALF = (D / 2) * 64 * 4;       // C registers of one query half
+  static_assert(XCH_HALF <= TILE && 1024 <= TILE, "exchange areas are laid over tile slots");
+  static constexpr int BYTES = 5 * TILE;
+  __host__ __device__ static constexpr int kslot(int i) { return i * TILE; }
+  __host__ __device__ static constexpr int vslot(int i) { return (3 + i) * TILE; }
 };
 
 template <int D>
@@ -174,7 +179,6 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
   using Lds = FwdLds<D>;
   constexpr int NT = D / 32, KT = D / 16;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  float* ml = reinterpret_cast<float*>(smem + Lds::BYTES - 1024);   // [par][qh][32][2]
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
   const int qh = w & 1, par = w >> 1;
   const int i = xcd_local_block(blockIdx.x, Tn), bh = blockIdx.y;
@@ -195,36 +199,54 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
   const bf16* Kb = K + (size_t)bh * N * D;
   const bf16* Vb = V + (size_t)bh * N * D;
   const float c2 = scale_log2e;                    // exp(x / sqrt(d)) = exp2(x * c2)
-  auto issue = [&](int s) {
-    const int jj = lut[s];
-    const int cols = min(kBlk, N - jj * kBlk);
-    const int off = (s & 1) * Lds::BUF;
-    issue_tile_load<D>(Kb + (size_t)jj * kBlk * D, cols, smem, off, w, l);
-    issue_tile_load<D>(Vb + (size_t)jj * kBlk * D, cols, smem, off + Lds::TILE, w, l);
-  };
-  // aggregated state H_i (d x d bf16; rows 0..63 in the K slot, the rest in the V slot) and the
-  // prepared projection matrix go global -> LDS like the tiles
   using T = SwzTile<D>;
-  auto issue_matrix = [&](const bf16* M, int off) {
-#pragma unroll
-    for (int h = 0; h < (D + kBlk - 1) / kBlk; ++h)
-      issue_tile_load<D>(M + (size_t)h * kBlk * D, min(kBlk, D - h * kBlk), smem, off + h * Lds::TILE, w, l);
+  auto issue_k = [&](int s, int slot) {
+    const int jj = lut[s];
+    issue_tile_load<D>(Kb + (size_t)jj * kBlk * D, min(kBlk, N - jj * kBlk), smem, Lds::kslot(slot), w, l);
+  };
+  auto issue_v = [&](int s) {
+    const int jj = lut[s];
+    issue_tile_load<D>(Vb + (size_t)jj * kBlk * D, min(kBlk, N - jj * kBlk), smem, Lds::vslot(s & 1), w, l);
+  };
+  // a d x d bf16 matrix (aggregated state H_i, prepared projection matrix) goes global -> LDS like
+  // the tiles: rows 0..63 into the slot at off0, the rest into the one at off1
+  auto issue_matrix = [&](const bf16* M, int off0, int off1) {
+    issue_tile_load<D>(M, min(kBlk, D), smem, off0, w, l);
+    if (D > kBlk) issue_tile_load<D>(M + (size_t)kBlk * D, D - kBlk, smem, off1, w, l);
   };
   const bf16* Hrow = H16 + ((size_t)bh * Tn + i) * (D * D);
-  // the pair buffer of the last step takes the exchanges afterwards, the other one H_i
-  const int xoff = ((n_h + 1) & 1) * Lds::BUF, hoff = Lds::BUF - xoff;
-  if (n_h > 0) issue(0);
-  else if (n_0 > 0) issue_matrix(Hrow, hoff);
+  // K slot of the last step, where the exchanges go afterwards; H_i takes the other two K slots
+  const int lastk = n_h > 0 ? (n_h - 1) % 3 : 0;
+  const int x0 = Lds::kslot(lastk), x1 = Lds::vslot((n_h + 1) & 1);   // x1: V slot of the last step
+  const int h0 = Lds::kslot((lastk + 1) % 3), h1 = Lds::kslot((lastk + 2) % 3);
+  // [par][qh][32][2], written while slower waves may still read the last step's tiles: it sits
+  // in the V slot that step does not use
+  float* ml = reinterpret_cast<float*>(smem + Lds::vslot(n_h & 1));
+  if (n_h > 0) {
+    issue_k(0, 0);
+    issue_v(0);
+    if (n_h > 1) issue_k(1, 1);
+  } else if (n_0 > 0) {
+    issue_matrix(Hrow, h0, h1);
+  }
 #pragma unroll
   for (int t = 0; t < KT; ++t) pin_loaded(qf[t]);
+  int ks = 0;   // K slot of step s
   for (int s = 0; s < n_h; ++s) {
     const int cols = min(kBlk, N - lut[s] * kBlk);
-    wait_vm0();
+    // K_{s+1}, issued last, may stay in flight
+    if (s + 1 < n_h) wait_vm<T::IPW>();
+    else wait_vm0();
     __syncthreads();   // tiles of step s have landed for every wave; step s-1 is fully consumed
-    if (s + 1 < n_h) issue(s + 1);
-    else if (n_0 > 0) issue_matrix(Hrow, hoff);   // arrives under the last step
-    const unsigned char* Ks = smem + (s & 1) * Lds::BUF;
-    const unsigned char* Vs = Ks + Lds::TILE;
+    if (s + 1 < n_h) {
+      issue_v(s + 1);
+      if (s + 2 < n_h) issue_k(s + 2, ks == 0 ? 2 : ks - 1);
+    } else if (n_0 > 0) {
+      issue_matrix(Hrow, h0, h1);   // arrives under the last step
+    }
+    const unsigned char* Ks = smem + Lds::kslot(ks);
+    const unsigned char* Vs = smem + Lds::vslot(s & 1);
+    ks = ks == 2 ? 0 : ks + 1;
     // every LDS read of the step is issued first; the V operands arrive under the score
     // products and the softmax
     bf16x8 ka[KT], va[2][NT];
@@ -277,7 +299,6 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
     }
   }
   // ---- merge the two key-tile streams (par 0 / par 1) of each query half
-  float* xch = reinterpret_cast<float*>(smem + xoff);
   lsum += __shfl_xor(lsum, 32, 64);
   if (g == 0) {
     ml[((par * 2 + qh) * 32 + ln) * 2 + 0] = m;
@@ -299,7 +320,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
   for (int et = 0; et < NT; ++et)
 #pragma unroll
     for (int r = 0; r < 16; ++r) oT[et][r] *= cw;
-  float* myx = xch + (size_t)qh * (D / 2) * 64;   // 64 D bytes: exchange, then this query half's staging
+  float* myx = reinterpret_cast<float*>(smem + (qh ? x1 : x0));   // exchange, then this query half's staging
   unsigned char* mystage = reinterpret_cast<unsigned char*>(myx);
   if (par == 1) {
 #pragma unroll
@@ -326,7 +347,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
   }
   if (n_0 > 0) {
     __syncthreads();   // the exchange area is free: the projection matrix goes there
-    issue_matrix(WTp, xoff);
+    issue_matrix(WTp, x0, x1);
     // phi(Q) of this lane's query: the lane holds features 16 t + 8 g + s, its partner the rest
     float qmx, qinv;
     phi_stats<KT>(qf, phi, qmx, qinv);
@@ -356,7 +377,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
       ol[h2] = zero_f32x16();
 #pragma unroll
       for (int t = 0; t < KT; ++t)
-        ol[h2] = mfma32(lds_row(smem, ma.row(t) + hoff + (et / 2) * Lds::TILE + (et % 2) * 2 * RB), qp[t], ol[h2]);
+        ol[h2] = mfma32(lds_row(smem, ma.row(t) + (et / 2 ? h1 : h0) + (et % 2) * 2 * RB), qp[t], ol[h2]);
 #pragma unroll
       for (int r = 0; r < 16; ++r) ol[h2][r] *= dinv;
     }
@@ -371,10 +392,12 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
         const bf16x8 b = c_to_operand(ol[h2], u);
 #pragma unroll
         for (int ep = 0; ep < NT; ++ep)
-          oT[ep] = mfma32(lds_row(smem, ma.row(2 * et + u) + xoff + (ep / 2) * Lds::TILE + (ep % 2) * 2 * RB), b, oT[ep]);
+          oT[ep] = mfma32(lds_row(smem, ma.row(2 * et + u) + (ep / 2 ? x1 : x0) + (ep % 2) * 2 * RB), b, oT[ep]);
       }
     }
-    if (Ol) store_rows_bf16<HT>(smem + hoff + w * (32 * (64 * HT + 16)), ol, Ol + orow0 + par * (D / 2), D, wrows, l);
+    if (Ol)
+      store_rows_bf16<HT>(smem + (w < 2 ? h0 : h1) + (w & 1) * (32 * (64 * HT + 16)), ol, Ol + orow0 + par * (D / 2), D,
+                          wrows, l);
     __syncthreads();   // everyone is done with the projection matrix
     if (par == 1) {
 #pragma unroll
