@@ -157,16 +157,16 @@ __global__ __launch_bounds__(256) void states_mfma_kernel(const bf16* __restrict
 // directly (swizzled, double-buffered, one barrier per step); V is read transposed.
 template <int D>
 struct FwdLds {
-  // Five tile slots: K_j is needed at the start of a step and is fetched two steps ahead (ring of
-  // three), V_j only after the softmax and is fetched one step ahead (ring of two).  At d = 128
-  // that is all of a CU's LDS for two workgroups.  After the loop the slots hold the exchange
-  // between the two key streams, H_i, the projection matrix and the running-softmax statistics.
+  // Five tile slots used as one ring by the load sequence K_0 V_0 K_1 V_1 ...: load n goes to slot
+  // n % 5.  K_s is dead after the score products of step s and V_s after the step, so with one
+  // barrier in the middle of a step and one at its end each freed slot is refilled at once and
+  // every tile is requested two steps before it is needed (an L2 miss costs about two steps).  At
+  // d = 128 the ring is all of a CU's LDS for two workgroups.  After the loop the slots hold the
+  // exchange between the two key streams, H_i, the projection matrix and the softmax statistics.
   static constexpr int TILE = SwzTile<D>::BYTES;
   static constexpr int XCH_HALF = (D / 2) * 64 * 4;       // C registers of one query half
   static_assert(XCH_HALF <= TILE && 1024 <= TILE, "exchange areas are laid over tile slots");
   static constexpr int BYTES = 5 * TILE;
-  __host__ __device__ static constexpr int kslot(int i) { return i * TILE; }
-  __host__ __device__ static constexpr int vslot(int i) { return (3 + i) * TILE; }
 };
 
 template <int D>
@@ -200,13 +200,10 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
   const bf16* Vb = V + (size_t)bh * N * D;
   const float c2 = scale_log2e;                    // exp(x / sqrt(d)) = exp2(x * c2)
   using T = SwzTile<D>;
-  auto issue_k = [&](int s, int slot) {
-    const int jj = lut[s];
-    issue_tile_load<D>(Kb + (size_t)jj * kBlk * D, min(kBlk, N - jj * kBlk), smem, Lds::kslot(slot), w, l);
-  };
-  auto issue_v = [&](int s) {
-    const int jj = lut[s];
-    issue_tile_load<D>(Vb + (size_t)jj * kBlk * D, min(kBlk, N - jj * kBlk), smem, Lds::vslot(s & 1), w, l);
+  // load n of the sequence K_0 V_0 K_1 V_1 ... into slot n % 5
+  auto issue_load = [&](int n, int jj) {   // jj = lut[n / 2]
+    issue_tile_load<D>((n & 1 ? Vb : Kb) + (size_t)jj * kBlk * D, min(kBlk, N - jj * kBlk), smem, (n % 5) * Lds::TILE, w,
+                       l);
   };
   // a d x d bf16 matrix (aggregated state H_i, prepared projection matrix) goes global -> LDS like
   // the tiles: rows 0..63 into the slot at off0, the rest into the one at off1
@@ -215,51 +212,62 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
     if (D > kBlk) issue_tile_load<D>(M + (size_t)kBlk * D, D - kBlk, smem, off1, w, l);
   };
   const bf16* Hrow = H16 + ((size_t)bh * Tn + i) * (D * D);
-  // K slot of the last step, where the exchanges go afterwards; H_i takes the other two K slots
-  const int lastk = n_h > 0 ? (n_h - 1) % 3 : 0;
-  const int x0 = Lds::kslot(lastk), x1 = Lds::vslot((n_h + 1) & 1);   // x1: V slot of the last step
-  const int h0 = Lds::kslot((lastk + 1) % 3), h1 = Lds::kslot((lastk + 2) % 3);
-  // [par][qh][32][2], written while slower waves may still read the last step's tiles: it sits
-  // in the V slot that step does not use
-  float* ml = reinterpret_cast<float*>(smem + Lds::vslot(n_h & 1));
+  // Slots at the end of the loop, with b the slot of the last K tile: H_i goes to b and b + 4
+  // (free from the middle of the last step), b + 1 holds the last V tile and b + 2, b + 3 were
+  // never refilled.  The statistics are written while slower waves may still read V: slot b + 2.
+  const int bslot = n_h > 0 ? (2 * (n_h - 1)) % 5 : 0;
+  const int h0 = bslot * Lds::TILE, h1 = ((bslot + 4) % 5) * Lds::TILE;
+  const int x1 = ((bslot + 1) % 5) * Lds::TILE, x0 = ((bslot + 3) % 5) * Lds::TILE;
+  float* ml = reinterpret_cast<float*>(smem + ((bslot + 2) % 5) * Lds::TILE);   // [par][qh][32][2]
+  const int nloads = 2 * n_h;
+  // key block indices of steps s, s + 1, s + 2: fetched a step before the loads that need them,
+  // so that no wave ever waits for a table entry between a barrier and its loads
+  int j0 = 0, j1 = 0, j2 = 0;
   if (n_h > 0) {
-    issue_k(0, 0);
-    issue_v(0);
-    if (n_h > 1) issue_k(1, 1);
+    j0 = lut[0];
+    j1 = lut[min(1, n_h - 1)];
+    j2 = lut[min(2, n_h - 1)];
+    issue_load(0, j0);
+    issue_load(1, j0);
+    if (n_h > 1) {
+      issue_load(2, j1);
+      issue_load(3, j1);
+    }
   } else if (n_0 > 0) {
     issue_matrix(Hrow, h0, h1);
   }
 #pragma unroll
   for (int t = 0; t < KT; ++t) pin_loaded(qf[t]);
-  int ks = 0;   // K slot of step s
+  int kslot = 0;   // slot of K_s; V_s sits in the next one
   for (int s = 0; s < n_h; ++s) {
-    const int cols = min(kBlk, N - lut[s] * kBlk);
-    // K_{s+1}, issued last, may stay in flight
-    if (s + 1 < n_h) wait_vm<T::IPW>();
+    const int cols = min(kBlk, N - j0 * kBlk);
+    const int j3 = lut[min(s + 3, n_h - 1)];   // needed in the next step
+    // K_s has landed; the three loads issued after it may stay in flight
+    if (s + 2 <= n_h) wait_vm<3 * T::IPW>();
     else wait_vm0();
-    __syncthreads();   // tiles of step s have landed for every wave; step s-1 is fully consumed
-    if (s + 1 < n_h) {
-      issue_v(s + 1);
-      if (s + 2 < n_h) issue_k(s + 2, ks == 0 ? 2 : ks - 1);
-    } else if (n_0 > 0) {
-      issue_matrix(Hrow, h0, h1);   // arrives under the last step
-    }
-    const unsigned char* Ks = smem + Lds::kslot(ks);
-    const unsigned char* Vs = smem + Lds::vslot(s & 1);
-    ks = ks == 2 ? 0 : ks + 1;
-    // every LDS read of the step is issued first; the V operands arrive under the score
-    // products and the softmax
+    __syncthreads();   // ... for every wave; and V_{s-1} is fully consumed: its slot takes K_{s+2}
+    if (2 * s + 4 < nloads) issue_load(2 * s + 4, j2);
+    const unsigned char* Ks = smem + kslot * Lds::TILE;
+    const unsigned char* Vs = smem + (kslot == 4 ? 0 : kslot + 1) * Lds::TILE;
+    kslot = kslot >= 3 ? kslot - 3 : kslot + 2;
     bf16x8 ka[KT], va[2][NT];
 #pragma unroll
     for (int t = 0; t < KT; ++t) ka[t] = read_row_swz<D>(Ks, 32 * par, t, l);
-#pragma unroll
-    for (int u = 0; u < 2; ++u)
-#pragma unroll
-      for (int et = 0; et < NT; ++et) va[u][et] = read_tr_swz<D>(Vs, 32 * par + 16 * u, et, l);
     sched_fence();
     f32x16 sT = zero_f32x16();
 #pragma unroll
     for (int t = 0; t < KT; ++t) sT = mfma32(ka[t], qf[t], sT);
+    // V_s has landed (same three-load margin), K_s is consumed: its slot takes V_{s+2}
+    if (s + 3 <= n_h) wait_vm<3 * T::IPW>();
+    else wait_vm0();
+    __syncthreads();
+    if (2 * s + 5 < nloads) issue_load(2 * s + 5, j2);
+    else if (s + 1 == n_h && n_0 > 0) issue_matrix(Hrow, h0, h1);   // arrives under the rest of the last step
+    // the V operands arrive under the softmax
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int et = 0; et < NT; ++et) va[u][et] = read_tr_swz<D>(Vs, 32 * par + 16 * u, et, l);
     sched_fence();
     // ---- online softmax on raw scores (the 1/sqrt(d) and log2 e factors ride on the exp2
     // argument); one query per lane
@@ -297,6 +305,9 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
 #pragma unroll
       for (int et = 0; et < NT; ++et) oT[et] = mfma32(va[u][et], pf, oT[et]);
     }
+    j0 = j1;
+    j1 = j2;
+    j2 = j3;
   }
   // ---- merge the two key-tile streams (par 0 / par 1) of each query half
   lsum += __shfl_xor(lsum, 32, 64);
