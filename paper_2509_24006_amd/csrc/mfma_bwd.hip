@@ -281,7 +281,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
             dot = fmaf(v, y, dot);
           }
         }
-      dot += __shfl_xor(dot, 32, 64);
+      dot = half_sum(dot);
       const float dtot = phi == 0 ? dot : 0.0f;
       const float rs = 1.0f / scale;   // the epilogue multiplies the whole dK sum by scale
 #pragma unroll

@@ -76,7 +76,7 @@ __global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
         for (int s = 0; s < 8; ++s) ds = fmaf((float)gf[t][s], (float)o[s], ds);
       }
     }
-    ds += __shfl_xor(ds, 32, 64);
+    ds = half_sum(ds);
     if (g == 0 && qok) Ds[(size_t)bh * N + q0 + qrow] = ds;
   }
   if (n_0 == 0) return;   // no linear branch: nothing else to do (uniform over the grid)
@@ -110,7 +110,7 @@ __global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
       *reinterpret_cast<bf16x4*>(Gs + qrow * RS + b0) = pk;
     }
   }
-  dl += __shfl_xor(dl, 32, 64);
+  dl = half_sum(dl);
   if (g == 0) dlp[par * kBlk + qrow] = dl;
   // phi(Q), its normaliser, and a = phi(Q) / den transposed into LDS (this wave: half of the features)
   bf16x8 qf[KT];
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
       den = fmaf(y, s < 4 ? z0[s] : z1[s - 4], den);
     }
   }
-  den += __shfl_xor(den, 32, 64);
+  den = half_sum(den);
   const float dinv = qok ? 1.0f / den : 0.0f;
 #pragma unroll
   for (int t = 0; t < KT; ++t) {
@@ -208,7 +208,7 @@ __global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
       }
     }
   }
-  dot += __shfl_xor(dot, 32, 64);
+  dot = half_sum(dot);
   if (g == 0) dotp[par * kBlk + qrow] = dot;
   __syncthreads();
   const float dtot = phi == 0 ? dotp[qrow] + dotp[kBlk + qrow] : 0.0f;

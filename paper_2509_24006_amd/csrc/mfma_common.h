@@ -219,6 +219,18 @@ __device__ __forceinline__ int lane_id() {
 // instead of one per product.
 __device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0); }
 
+// Reductions over the two halves of a wave: every lane gets op(x of lane l % 32, x of lane
+// l % 32 + 32).  The swap of the upper half of one copy with the lower half of the other leaves
+// the two values side by side in every lane: one VALU instruction instead of a trip through LDS.
+__device__ __forceinline__ float half_sum(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float half_max(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 // Makes the compiler finish the loads that produce x here.  Used on operand registers that are
 // loaded before a pipelined loop: otherwise the wait for them lands at their first use inside the
 // loop body, where it also waits -- on every trip -- for the tile loads just put in flight.
@@ -332,6 +344,10 @@ struct TileAddr {
   __device__ __forceinline__ void refresh() { asm volatile("" : "+v"(sx), "+v"(fx)); }
   __device__ __forceinline__ int row(int t) const { return rb + ((t << 5) ^ sx); }
   __device__ __forceinline__ int tr(int h, int et) const { return tb[h] + ((et << 6) ^ fx); }
+  // the same with the per-lane base already moved to a tile slot: base = rb + slot (rows),
+  // base = tb[h] + slot (transposing reads)
+  __device__ __forceinline__ int row_at(int t, int base) const { return base + ((t << 5) ^ sx); }
+  __device__ __forceinline__ int tr_at(int et, int base) const { return base + ((et << 6) ^ fx); }
 };
 
 typedef __attribute__((ext_vector_type(4))) short lds_s16x4_val;
@@ -423,13 +439,13 @@ __device__ __forceinline__ void phi_stats(const bf16x8 (&xf)[KT], int phi, float
   for (int t = 0; t < KT; ++t)
 #pragma unroll
     for (int s = 0; s < 8; ++s) mx = fmaxf(mx, (float)xf[t][s]);
-  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  mx = half_max(mx);
   float sum = 0.0f;
 #pragma unroll
   for (int t = 0; t < KT; ++t)
 #pragma unroll
     for (int s = 0; s < 8; ++s) sum += fast_exp2(((float)xf[t][s] - mx) * kLog2e);
-  sum += __shfl_xor(sum, 32, 64);
+  sum = half_sum(sum);
   inv = 1.0f / sum;
 }
 

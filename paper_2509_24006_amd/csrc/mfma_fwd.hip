@@ -239,6 +239,8 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
 #pragma unroll
   for (int t = 0; t < KT; ++t) pin_loaded(qf[t]);
   int kslot = 0;   // slot of K_s; V_s sits in the next one
+  TileAddr<D> ad;  // this wave reads rows 32 par .. of both tiles
+  ad.init(32 * par, l);
   for (int s = 0; s < n_h; ++s) {
     const int cols = min(kBlk, N - j0 * kBlk);
     const int j3 = lut[min(s + 3, n_h - 1)];   // needed in the next step
@@ -247,12 +249,14 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
     else wait_vm0();
     __syncthreads();   // ... for every wave; and V_{s-1} is fully consumed: its slot takes K_{s+2}
     if (2 * s + 4 < nloads) issue_load(2 * s + 4, j2);
-    const unsigned char* Ks = smem + kslot * Lds::TILE;
-    const unsigned char* Vs = smem + (kslot == 4 ? 0 : kslot + 1) * Lds::TILE;
+    ad.refresh();
+    const int kb = ad.rb + kslot * Lds::TILE;
+    const int voff = (kslot == 4 ? 0 : kslot + 1) * Lds::TILE;
+    const int vb0 = ad.tb[0] + voff, vb1 = ad.tb[1] + voff;
     kslot = kslot >= 3 ? kslot - 3 : kslot + 2;
     bf16x8 ka[KT], va[2][NT];
 #pragma unroll
-    for (int t = 0; t < KT; ++t) ka[t] = read_row_swz<D>(Ks, 32 * par, t, l);
+    for (int t = 0; t < KT; ++t) ka[t] = lds_row(smem, ad.row_at(t, kb));
     sched_fence();
     f32x16 sT = zero_f32x16();
 #pragma unroll
@@ -267,7 +271,8 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
-      for (int et = 0; et < NT; ++et) va[u][et] = read_tr_swz<D>(Vs, 32 * par + 16 * u, et, l);
+      for (int et = 0; et < NT; ++et)
+        va[u][et] = lds_tr<D>(smem, ad.tr_at(et, vb0) + u * 16 * T::ROW_BYTES, ad.tr_at(et, vb1) + u * 16 * T::ROW_BYTES);
     sched_fence();
     // ---- online softmax on raw scores (the 1/sqrt(d) and log2 e factors ride on the exp2
     // argument); one query per lane
@@ -279,7 +284,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
     float mx = sT[0];
 #pragma unroll
     for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sT[r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    mx = half_max(mx);
     const float mnew = fmaxf(m, mx);
     const float moff = mnew == -INFINITY ? 0.0f : -mnew * c2;   // a half with no valid key yet
     float psum = 0.0f;
@@ -310,7 +315,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
     j2 = j3;
   }
   // ---- merge the two key-tile streams (par 0 / par 1) of each query half
-  lsum += __shfl_xor(lsum, 32, 64);
+  lsum = half_sum(lsum);
   if (g == 0) {
     ml[((par * 2 + qh) * 32 + ln) * 2 + 0] = m;
     ml[((par * 2 + qh) * 32 + ln) * 2 + 1] = lsum;
@@ -375,7 +380,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
         den = fmaf((float)qp[t][s2], s2 < 4 ? z0[s2] : z1[s2 - 4], den);
       }
     }
-    den += __shfl_xor(den, 32, 64);
+    den = half_sum(den);
     const float dinv = 1.0f / den;
     constexpr int HT = NT / 2;     // e-tiles per wave
     TileAddr<D> ma;                // rows 32 (et % 2) + ln of a 64-row tile: + 2 RB per odd tile
