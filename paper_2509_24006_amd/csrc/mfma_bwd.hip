@@ -85,7 +85,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
   ad.init(32 * qh, l);
   // load k of a tile fetches, for this lane, the chunk 4096 k bytes after that of load 0 (the
   // swizzle has period 16 rows), so one per-lane offset serves all of them
-  const int ldv = swz_chunk_off<D>(T::RPI * w + l / T::CPR, l % T::CPR);
+  const int ldv = tile_lane_offset<D>(w, l);
   const int wu = wave_uniform(w);
   const unsigned lds0 = lds_base(smem) + wu * 1024;
   // (issue and step are inlined at call sites with a literal buffer index, which turns every
@@ -374,9 +374,10 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(
     const int32_t* __restrict__ row_idx, const float* __restrict__ dQlin, int N, int Tn, int n_h,
     float scale, bf16* __restrict__ dQ) {
   using Lds = PairLds<D>;
+  using T = SwzTile<D>;
   constexpr int NT = D / 32, KT = D / 16;
+  constexpr int RB = 16 * T::ROW_BYTES;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  float* xch = reinterpret_cast<float*>(smem);
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
   const int qh = w & 1, kh = w >> 1;
   const int i = xcd_local_block(blockIdx.x, Tn), bh = blockIdx.y;
@@ -384,49 +385,86 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(
   const int q0 = i * kBlk, rows = min(kBlk, N - q0);
   const int qrow = qh * 32 + ln;
   const bool qok = qrow < rows;
-  const size_t qoff = ((size_t)bh * N + q0 + qrow) * D;
-  bf16x8 qf[KT], gf[KT];
-#pragma unroll
-  for (int t = 0; t < KT; ++t) {
-    qf[t] = qok ? *reinterpret_cast<const bf16x8*>(Q + qoff + 16 * t + 8 * g) : zero_bf16x8();
-    gf[t] = qok ? *reinterpret_cast<const bf16x8*>(dO + qoff + 16 * t + 8 * g) : zero_bf16x8();
+  const int32_t* lut = row_idx + ((size_t)bh * Tn + i) * n_h;
+  const bf16* Kb = K + (size_t)bh * N * D;
+  const bf16* Vb = V + (size_t)bh * N * D;
+  const float sl2 = scale * kLog2e;
+  const int ldv = tile_lane_offset<D>(w, l);
+  const unsigned lds0 = lds_base(smem) + wave_uniform(w) * 1024;
+  // key block indices of steps s, s + 1, s + 2, fetched a step before the loads that need them
+  int j0 = 0, j1 = 0, j2 = 0;
+  auto issue = [&](int jj, const int bufi) __attribute__((always_inline)) {
+    const int cols = min(kBlk, N - jj * kBlk);
+    issue_tile_load<D>(Kb + (size_t)jj * kBlk * D, cols, lds0, bufi * Lds::BUF, ldv);
+    issue_tile_load<D>(Vb + (size_t)jj * kBlk * D, cols, lds0, bufi * Lds::BUF + Lds::TILE, ldv);
+  };
+  // Q_i and dO_i come in as tiles through the second pair buffer (whole rows per load, zeros past
+  // the end of the sequence) and are picked up from there in operand layout
+  {
+    const size_t base = ((size_t)bh * N + q0) * D;
+    issue_tile_load<D>(Q + base, rows, lds0, Lds::BUF, ldv);
+    issue_tile_load<D>(dO + base, rows, lds0, Lds::BUF + Lds::TILE, ldv);
+  }
+  if (n_h > 0) {
+    j0 = lut[0];
+    j1 = lut[min(1, n_h - 1)];
+    j2 = lut[min(2, n_h - 1)];
+    issue(j0, 0);
   }
   const float Lq = qok ? L[(size_t)bh * N + q0 + qrow] * kLog2e : INFINITY;
   const float Dq = qok ? Ds[(size_t)bh * N + q0 + qrow] : 0.0f;
   f32x16 dqT[NT];
 #pragma unroll
   for (int t = 0; t < NT; ++t) dqT[t] = zero_f32x16();
-  const int32_t* lut = row_idx + ((size_t)bh * Tn + i) * n_h;
-  const bf16* Kb = K + (size_t)bh * N * D;
-  const bf16* Vb = V + (size_t)bh * N * D;
-  const float sl2 = scale * kLog2e;
-  auto issue = [&](int s) {
-    const int jj = lut[s];
-    const int cols = min(kBlk, N - jj * kBlk);
-    const int off = (s & 1) * Lds::BUF;
-    issue_tile_load<D>(Kb + (size_t)jj * kBlk * D, cols, smem, off, w, l);
-    issue_tile_load<D>(Vb + (size_t)jj * kBlk * D, cols, smem, off + Lds::TILE, w, l);
-  };
-  if (n_h > 0) issue(0);
+  wait_vm0();
+  __syncthreads();
+  bf16x8 qf[KT], gf[KT];
+  {
+    TileAddr<D> qa;
+    qa.init(32 * qh, l);
+#pragma unroll
+    for (int t = 0; t < KT; ++t) {
+      qf[t] = lds_row(smem, qa.row(t) + Lds::BUF);
+      gf[t] = lds_row(smem, qa.row(t) + Lds::BUF + Lds::TILE);
+    }
+  }
 #pragma unroll
   for (int t = 0; t < KT; ++t) {
     pin_loaded(qf[t]);
     pin_loaded(gf[t]);
   }
-  for (int s = 0; s < n_h; ++s) {
-    const int buf = s & 1;
-    const int cols = min(kBlk, N - lut[s] * kBlk);
+  // (the first step's barrier orders these reads before the loads that reuse the buffer)
+  TileAddr<D> ad;   // this wave reads rows 32 kh .. of K_j and V_j
+  ad.init(32 * kh, l);
+  auto step = [&](int s, const int buf) __attribute__((always_inline)) {
+    const int KO = buf * Lds::BUF, VO = KO + Lds::TILE;
+    const int cols = min(kBlk, N - j0 * kBlk);
+    const int j3 = lut[min(s + 3, n_h - 1)];
+    ad.refresh();
     wait_vm0();
-    __syncthreads();
-    if (s + 1 < n_h) issue(s + 1);
-    const unsigned char* Ks = smem + buf * Lds::BUF;
-    const unsigned char* Vs = Ks + Lds::TILE;
+    __syncthreads();   // tiles of step s have landed for every wave; step s-1 is fully consumed
+    if (s + 1 < n_h) issue(j1, buf ^ 1);
+    // all LDS reads of the first two products up front, then the products
+    bf16x8 ka[KT], va[KT], ta[2][NT];
+#pragma unroll
+    for (int t = 0; t < KT; ++t) {
+      ka[t] = lds_row(smem, ad.row(t) + KO);
+      va[t] = lds_row(smem, ad.row(t) + VO);
+    }
+    sched_fence();
     f32x16 sT = zero_f32x16(), dpT = zero_f32x16();
 #pragma unroll
     for (int t = 0; t < KT; ++t) {
-      sT = mfma32(read_row_swz<D>(Ks, 32 * kh, t, l), qf[t], sT);
-      dpT = mfma32(read_row_swz<D>(Vs, 32 * kh, t, l), gf[t], dpT);
+      sT = mfma32(ka[t], qf[t], sT);
+      dpT = mfma32(va[t], gf[t], dpT);
     }
+    // K_j^T for the third product arrives under the softmax arithmetic
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int dt = 0; dt < NT; ++dt)
+        ta[u][dt] = lds_tr<D>(smem, ad.tr(0, dt) + KO + u * RB, ad.tr(1, dt) + KO + u * RB);
+    sched_fence();
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       float pv = fast_exp2(fmaf(sT[r], sl2, -Lq));
@@ -437,35 +475,57 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(
     for (int u = 0; u < 2; ++u) {
       const bf16x8 sb = c_to_operand(dpT, u);
 #pragma unroll
-      for (int dt = 0; dt < NT; ++dt)
-        dqT[dt] = mfma32(read_tr_swz<D>(Ks, 32 * kh + 16 * u, dt, l), sb, dqT[dt]);   // K_j^T dS^T
+      for (int dt = 0; dt < NT; ++dt) dqT[dt] = mfma32(ta[u][dt], sb, dqT[dt]);   // K_j^T dS^T
     }
+    j0 = j1;
+    j1 = j2;
+    j2 = j3;
+  };
+  for (int s = 0; s < n_h; s += 2) {
+    step(s, 0);
+    if (s + 1 < n_h) step(s + 1, 1);
   }
-  __syncthreads();
-  float* myx = xch + (size_t)qh * (NT * 16) * 64;
+  // ---- add the two key halves in a row-major staging area, then every thread takes 16-byte
+  // pieces of whole rows: adds the linear-branch part and stores (coalesced both ways)
+  __syncthreads();   // every wave is done with the tiles
+  constexpr int SP = Lds::SP;
+  float* stg = reinterpret_cast<float*>(smem);   // [64 queries][SP]
+  const int srow = qrow * SP + 4 * g;
   if (kh == 1) {
 #pragma unroll
     for (int dt = 0; dt < NT; ++dt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) myx[(dt * 16 + r) * 64 + l] = dqT[dt][r];
+      for (int r4 = 0; r4 < 4; ++r4)
+        *reinterpret_cast<f32x4*>(stg + srow + 32 * dt + 8 * r4) =
+            f32x4{dqT[dt][4 * r4], dqT[dt][4 * r4 + 1], dqT[dt][4 * r4 + 2], dqT[dt][4 * r4 + 3]};
   }
   __syncthreads();
-  if (kh == 0 && qok) {
+  if (kh == 0) {
 #pragma unroll
     for (int dt = 0; dt < NT; ++dt)
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
-        const size_t o = qoff + 32 * dt + 8 * r4 + 4 * g;
-        f32x4 lq = {0.0f, 0.0f, 0.0f, 0.0f};
-        if (dQlin) lq = *reinterpret_cast<const f32x4*>(dQlin + o);
-        bf16x4 pk;
+        f32x4 a = *reinterpret_cast<const f32x4*>(stg + srow + 32 * dt + 8 * r4);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int rr = 4 * r4 + r;
-          pk[r] = (__bf16)((dqT[dt][rr] + myx[(dt * 16 + rr) * 64 + l]) * scale + lq[r]);
-        }
-        *reinterpret_cast<bf16x4*>(dQ + o) = pk;
+        for (int r = 0; r < 4; ++r) a[r] += dqT[dt][4 * r4 + r];
+        *reinterpret_cast<f32x4*>(stg + srow + 32 * dt + 8 * r4) = a;
       }
+  }
+  __syncthreads();
+  constexpr int C4 = D / 4;   // 16-byte pieces per row
+#pragma unroll
+  for (int it = 0; it < kBlk * C4 / 256; ++it) {
+    const int idx = it * 256 + tid, row = idx / C4, c4 = idx % C4;
+    if (row < rows) {
+      const size_t o = ((size_t)bh * N + q0 + row) * D + 4 * c4;
+      const f32x4 sv = *reinterpret_cast<const f32x4*>(stg + row * SP + 4 * c4);
+      f32x4 lq = {0.0f, 0.0f, 0.0f, 0.0f};
+      if (dQlin) lq = *reinterpret_cast<const f32x4*>(dQlin + o);
+      bf16x4 pk;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) pk[r] = (__bf16)(sv[r] * scale + lq[r]);
+      *reinterpret_cast<bf16x4*>(dQ + o) = pk;
+    }
   }
 }
 

@@ -262,26 +262,28 @@ __device__ __forceinline__ int swz(int row) {
 }
 
 
-// All four waves of a workgroup: enqueue the loads of one tile.  lds_tile: byte offset of the
-// tile inside the dynamic LDS array `smem`.
-template <int D>
-__device__ __forceinline__ void issue_tile_load(const bf16* gbase, int valid_rows, unsigned char* smem,
-                                                int lds_tile, int w, int l) {
-  using T = SwzTile<D>;
-  const BufDesc rsrc = tile_rsrc(gbase, valid_rows * T::ROW_BYTES);
-#pragma unroll
-  for (int k = 0; k < T::IPW; ++k) {
-    const int rg = 4 * k + w;
-    const int row = T::RPI * rg + l / T::CPR, pc = l % T::CPR;
-    const int voff = row * T::ROW_BYTES + ((pc ^ swz<D>(row)) << 4);
-    load_to_lds16(rsrc, voff, 0, lds_base(smem) + lds_tile + rg * 1024);
-  }
-}
-
 // byte offset (inside a tile) of the 16-byte chunk `c` of row `row`
 template <int D>
 __device__ __forceinline__ int swz_chunk_off(int row, int c) {
   return row * SwzTile<D>::ROW_BYTES + ((c ^ swz<D>(row)) << 4);
+}
+
+// All four waves of a workgroup enqueue the loads of one tile.  A wave-wide load deposits 1 KB;
+// wave w takes the 1 KB runs w, w + 4, ... of the tile.  Load k of a lane fetches the chunk 4096 k
+// bytes after that of load 0 (the swizzle has period 16 rows), so one per-lane offset serves all:
+//   ldv  = tile_lane_offset<D>(w, l)                       per lane, fixed
+//   lds0 = lds_base(smem) + 1024 * (wave index, uniform)   per wave, fixed
+template <int D>
+__device__ __forceinline__ int tile_lane_offset(int w, int l) {
+  using T = SwzTile<D>;
+  return swz_chunk_off<D>(T::RPI * w + l / T::CPR, l % T::CPR);
+}
+template <int D>
+__device__ __forceinline__ void issue_tile_load(const bf16* gbase, int valid_rows, unsigned lds0, int lds_tile, int ldv) {
+  using T = SwzTile<D>;
+  const BufDesc rsrc = tile_rsrc(gbase, valid_rows * T::ROW_BYTES);
+#pragma unroll
+  for (int k = 0; k < T::IPW; ++k) load_to_lds16(rsrc, ldv, 4096 * k, lds0 + lds_tile + 4096 * k);
 }
 
 // A operand whose 32 rows are tile rows r0 + (l % 32) and whose k-values are features 16 t + 8 g ..

@@ -200,16 +200,18 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
   const bf16* Vb = V + (size_t)bh * N * D;
   const float c2 = scale_log2e;                    // exp(x / sqrt(d)) = exp2(x * c2)
   using T = SwzTile<D>;
+  const int ldv = tile_lane_offset<D>(w, l);
+  const unsigned lds0 = lds_base(smem) + wave_uniform(w) * 1024;
   // load n of the sequence K_0 V_0 K_1 V_1 ... into slot n % 5
   auto issue_load = [&](int n, int jj) {   // jj = lut[n / 2]
-    issue_tile_load<D>((n & 1 ? Vb : Kb) + (size_t)jj * kBlk * D, min(kBlk, N - jj * kBlk), smem, (n % 5) * Lds::TILE, w,
-                       l);
+    issue_tile_load<D>((n & 1 ? Vb : Kb) + (size_t)jj * kBlk * D, min(kBlk, N - jj * kBlk), lds0, (n % 5) * Lds::TILE,
+                       ldv);
   };
   // a d x d bf16 matrix (aggregated state H_i, prepared projection matrix) goes global -> LDS like
   // the tiles: rows 0..63 into the slot at off0, the rest into the one at off1
   auto issue_matrix = [&](const bf16* M, int off0, int off1) {
-    issue_tile_load<D>(M, min(kBlk, D), smem, off0, w, l);
-    if (D > kBlk) issue_tile_load<D>(M + (size_t)kBlk * D, D - kBlk, smem, off1, w, l);
+    issue_tile_load<D>(M, min(kBlk, D), lds0, off0, ldv);
+    if (D > kBlk) issue_tile_load<D>(M + (size_t)kBlk * D, D - kBlk, lds0, off1, ldv);
   };
   const bf16* Hrow = H16 + ((size_t)bh * Tn + i) * (D * D);
   // Slots at the end of the loop, with b the slot of the last K tile: H_i goes to b and b + 4
