@@ -25,7 +25,7 @@ struct PairLds {
   static constexpr int XCH = 2 * 2 * (D / 32) * 16 * 64 * 4;   // final exchange (dK/dV kernel)
   static constexpr int TILES = 2 * BUF > XCH ? 2 * BUF : XCH;
   static constexpr int BYTES = TILES + 2 * 2 * kBlk * 4; // + [buf][L, D^s][64]
-  static constexpr int VPARK = D >= 128 ? 2 * (D / 32) * 64 * 16 : 0;   // parked V operand (dK/dV kernel)
+  static constexpr int VPARK = D >= 128 ? 2 * (3 * D / 64) * 64 * 16 : 0;   // parked V operand (dK/dV kernel)
   static constexpr int SP = D + 4;                        // row pitch (floats) of the output staging
   static constexpr int STAGE = 2 * kBlk * SP * 4;         // [dV | dK][64][SP] floats (dK/dV kernel)
   static constexpr int DKDV = BYTES + VPARK > STAGE ? BYTES + VPARK : STAGE;
@@ -59,9 +59,9 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
   const int krow = kh * 32 + ln;
   const bool kok = krow < cols;
   // At d = 128 the accumulators and both key-side operands do not fit the register budget of
-  // two workgroups per CU.  The upper half of the V operand is parked in LDS (each kh half once,
+  // two workgroups per CU.  Three quarters of the V operand are parked in LDS (each kh half once,
   // in operand layout: 16 bytes per lane and k-step) and re-read every step.
-  constexpr int VL = D >= 128 ? KT / 2 : 0, VR = KT - VL;
+  constexpr int VL = D >= 128 ? 3 * KT / 4 : 0, VR = KT - VL;
   const int vpark = Lds::BYTES + (kh * VL * 64 + l) * 16;
   bf16x8 kf[KT], vf[VR > 0 ? VR : 1];
   f32x16 dvT[NT], dkT[NT];
@@ -150,14 +150,16 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
 #pragma unroll
     for (int i = 0; i < PT; ++i) read_t(i);
     sched_fence();
-    // P[q][key] = exp(S - L_q), dS = P (dP - D^s_q); rows q = 32 qh + c_row(r, g)
+    // P[q][key] = exp(S - L_q), dS = P (dP - D^s_q); rows q = 32 qh + c_row(r, g).  A lane past the
+    // end of the key block (its K and V rows are zero) computes finite values that stay in its own
+    // columns of dK^T and dV^T, which are never stored.
 #pragma unroll
     for (int r4 = 0; r4 < 4; ++r4) {
       const f32x4 lq = *reinterpret_cast<const f32x4*>(Ls + 32 * qh + 8 * r4 + 4 * g);
       const f32x4 dq = *reinterpret_cast<const f32x4*>(Dq + 32 * qh + 8 * r4 + 4 * g);
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const float pv = kok ? fast_exp2(fmaf(sm[4 * r4 + r], sl2, -lq[r])) : 0.0f;
+        const float pv = fast_exp2(fmaf(sm[4 * r4 + r], sl2, -lq[r]));
         sm[4 * r4 + r] = pv;
         dp[4 * r4 + r] = pv * (dp[4 * r4 + r] - dq[r]);
       }
