@@ -288,15 +288,12 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
     for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sT[r]);
     mx = half_max(mx);
     const float mnew = fmaxf(m, mx);
-    const float moff = mnew == -INFINITY ? 0.0f : -mnew * c2;   // a half with no valid key yet
-    float psum = 0.0f;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const float pv = fast_exp2(fmaf(sT[r], c2, moff));
-      sT[r] = pv;
-      psum += pv;
-    }
-    if (__any(mnew != m)) {   // rescale only when some query's running maximum moved
+    // The reference point m of the exponentials follows the running maximum lazily: only when
+    // some query's maximum has moved up by more than 2^kLazy (always at its first valid key), so
+    // that the accumulators are rescaled on few steps.  P is then at most 2^kLazy instead of 1,
+    // which neither float nor bf16 mind, and L = m + log(sum) comes out the same.
+    constexpr float kLazy = 8.0f;
+    if (__any((mnew - m) * c2 > kLazy)) {
       const float alpha = fast_exp2((m - mnew) * c2);
       lsum *= alpha;
 #pragma unroll
@@ -304,6 +301,14 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) oT[et][r] *= alpha;
       m = mnew;
+    }
+    const float moff = m == -INFINITY ? 0.0f : -m * c2;   // a half with no valid key yet
+    float psum = 0.0f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float pv = fast_exp2(fmaf(sT[r], c2, moff));
+      sT[r] = pv;
+      psum += pv;
     }
     lsum += psum;
 #pragma unroll
