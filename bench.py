@@ -51,6 +51,9 @@ def main() -> int:
     ap.add_argument("--k-h", type=float, default=None)
     ap.add_argument("--dense-steps", type=int, default=1, help="0 skips the dense reference run")
     ap.add_argument("--cpu-heads", type=int, default=4, help="0 skips the CPU oracle baseline")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="run one float add over this many MiB first: a kernel of known HBM traffic that "
+                         "calibrates the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (heads shard trivially, see DESIGN.md); "
@@ -106,6 +109,13 @@ def main() -> int:
         torch.cuda.synchronize()
         return (time.perf_counter() - t) * 1e3 / n, e0.elapsed_time(e1) / n
 
+    if args.calib_copy_mib > 0:
+        src = torch.ones(args.calib_copy_mib << 18, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.add(src, 1.0, out=dst)    # reads and writes calib_copy_mib MiB each
+        torch.cuda.synchronize()
+        del src, dst
+
     p = sla.make_params(w.B, w.H, w.N, w.d, w.k_h, w.k_l, tdt)
     b = buffers(p)
     mask, fwd, bwd = phases(p, b)
@@ -156,6 +166,15 @@ def main() -> int:
                     "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "traffic": None,
                     "ms_per_launch": k["ms_per_launch"]}
         break
+
+    # HBM traffic of that kernel per launch, from the committed counter summary (two rocprofv3 --pmc
+    # runs of this command, FETCH_SIZE and WRITE_SIZE, scaled by the calibration kernel), if present
+    if roof is not None:
+        tpath = os.path.join(ROOT, "profiles", f"pmc_traffic_{roof['kernel']}_{w.name}.txt")
+        if os.path.exists(tpath):
+            for line in open(tpath):
+                if line.startswith("traffic_bytes_per_launch:"):
+                    roof["traffic"] = float(line.split(":")[1])
 
     # dense reference on the same GPU: the same library with every block critical
     dense = None
