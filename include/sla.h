@@ -66,8 +66,8 @@ typedef struct sla_sizes_t {
   uint64_t lut_row_idx;       /* int32 [B,H,T,n_h]   ascending critical key blocks per row  */
   uint64_t lut_col_ptr;       /* int32 [B,H,T+1]     CSC pointers of the critical entries   */
   uint64_t lut_col_rows;      /* int32 [B,H,T*n_h]   ascending query blocks per key block   */
-  uint64_t lut_ind;           /* int8  [B,H,T,Tp]    1 where M_c[i][j] = 0 (marginal), Tp = T rounded up to 16 */
-  uint64_t lut_ind_t;         /* int8  [B,H,T,Tp]    the same, transposed: [j][i]           */
+  uint64_t lut_ind;           /* uint64 [B,H,T,Tw]   bit b of word q: M_c[i][64q+b] = 0 (marginal), Tw = ceil(T/64) */
+  uint64_t lut_ind_t;         /* uint64 [B,H,T,Tw]   the same, transposed: bit b of [j][q]: M_c[64q+b][j] = 0 */
   uint64_t lut_col_order;     /* int32 [B,H,T]       key blocks by descending column count  */
   uint64_t saved_bytes;
   uint64_t saved_Os;          /* dtype [B,H,N,d]     O^s                                    */

@@ -216,8 +216,8 @@ def lut_views(p: sla_params, luts: torch.Tensor) -> Dict[str, torch.Tensor]:
     return {"row_idx": _view(luts, z.lut_row_idx, (p.B, p.H, z.T, z.n_h), torch.int32),
             "col_ptr": _view(luts, z.lut_col_ptr, (p.B, p.H, z.T + 1), torch.int32),
             "col_rows": _view(luts, z.lut_col_rows, (p.B, p.H, z.T * z.n_h), torch.int32),
-            "ind": _view(luts, z.lut_ind, (p.B, p.H, z.T, (z.T + 15) // 16 * 16), torch.int8),
-            "ind_t": _view(luts, z.lut_ind_t, (p.B, p.H, z.T, (z.T + 15) // 16 * 16), torch.int8),
+            "ind": _view(luts, z.lut_ind, (p.B, p.H, z.T, (z.T + 63) // 64), torch.int64),
+            "ind_t": _view(luts, z.lut_ind_t, (p.B, p.H, z.T, (z.T + 63) // 64), torch.int64),
             "col_order": _view(luts, z.lut_col_order, (p.B, p.H, z.T), torch.int32)}
 
 

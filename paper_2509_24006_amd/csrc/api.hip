@@ -56,11 +56,11 @@ void fill_sizes(const Shape& s, sla_sizes_t* o) {
   off += align_up(BH * (T + 1) * 4);
   o->lut_col_rows = off;
   off += align_up(BH * T * (size_t)s.n_h * 4 + 4);
-  const size_t Tp = (T + 15) / 16 * 16;
+  const size_t Tw = (T + 63) / 64;
   o->lut_ind = off;
-  off += align_up(BH * T * Tp);
+  off += align_up(BH * T * Tw * 8);
   o->lut_ind_t = off;
-  off += align_up(BH * T * Tp);
+  off += align_up(BH * T * Tw * 8);
   o->lut_col_order = off;
   off += align_up(BH * T * 4);
   o->luts_bytes = off;
@@ -120,7 +120,7 @@ int sla_classify_scores(const sla_params* p, const float* scores, int8_t* Mc, vo
   hipError_t e = launch_classify(scores, s, Mc, (int32_t*)(l + z.lut_row_idx), st);
   if (e == hipSuccess)
     e = launch_csc(Mc, s, (int32_t*)(l + z.lut_col_ptr), (int32_t*)(l + z.lut_col_rows),
-                   (int8_t*)(l + z.lut_ind), (int8_t*)(l + z.lut_ind_t),
+                   (unsigned long long*)(l + z.lut_ind), (unsigned long long*)(l + z.lut_ind_t),
                    (int32_t*)(l + z.lut_col_order), st);
   return hip_status(e);
 }
@@ -167,7 +167,7 @@ int sla_forward(const sla_params* p, const void* Q, const void* K, const void* V
   a.Q = Q; a.K = K; a.V = V; a.W = W;
   a.Mc = Mc;
   a.row_idx = (const int32_t*)(l + z.lut_row_idx);
-  a.ind = (const int8_t*)(l + z.lut_ind);
+  a.ind = (const unsigned long long*)(l + z.lut_ind);
   a.O = O;
   a.Os = sv ? sv + z.saved_Os : nullptr;
   a.Ol = sv ? sv + z.saved_Ol : nullptr;
@@ -203,7 +203,7 @@ int sla_backward(const sla_params* p, const void* Q, const void* K, const void* 
   a.row_idx = (const int32_t*)(l + z.lut_row_idx);
   a.col_ptr = (const int32_t*)(l + z.lut_col_ptr);
   a.col_rows = (const int32_t*)(l + z.lut_col_rows);
-  a.indT = (const int8_t*)(l + z.lut_ind_t);
+  a.indT = (const unsigned long long*)(l + z.lut_ind_t);
   a.col_order = (const int32_t*)(l + z.lut_col_order);
   a.Os = sv + z.saved_Os;
   a.Ol = sv + z.saved_Ol;

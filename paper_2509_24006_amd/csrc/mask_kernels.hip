@@ -238,27 +238,28 @@ __global__ __launch_bounds__(256) void col_fill_kernel(const int8_t* __restrict_
     if (m[(size_t)i * T] == 1) out[w++] = i;
 }
 
-// Marginal indicator ind[i][j] = (Mc[i][j] == 0) and its transpose, both with rows padded to Tp
-// bytes (zeros), 32 x 32 tiles through LDS.
-__global__ __launch_bounds__(256) void indicator_kernel(const int8_t* __restrict__ Mc, int T, int Tp,
-                                                        int8_t* __restrict__ ind,
-                                                        int8_t* __restrict__ indT) {
-  __shared__ int8_t tile[32][33];
-  const int bh = blockIdx.z, i0 = blockIdx.y * 32, j0 = blockIdx.x * 32;
-  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+// Marginal indicator as bit masks: bit b of ind[i][q] is set iff Mc[i][64 q + b] == 0 (and the
+// column exists), bit b of indT[j][q] iff Mc[64 q + b][j] == 0.  A workgroup takes a 64 x 64 tile
+// of Mc through LDS; each wave votes 16 rows and 16 columns of it into 64-bit words.
+__global__ __launch_bounds__(256) void indicator_kernel(const int8_t* __restrict__ Mc, int T, int Tw,
+                                                        unsigned long long* __restrict__ ind,
+                                                        unsigned long long* __restrict__ indT) {
+  __shared__ int8_t tile[64][68];
+  const int bh = blockIdx.z, i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
+  const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int8_t* src = Mc + (size_t)bh * T * T;
-  int8_t* d0 = ind + (size_t)bh * T * Tp;
-  int8_t* d1 = indT + (size_t)bh * T * Tp;
-  for (int r = ty; r < 32; r += 8) {
-    const int i = i0 + r, j = j0 + tx;
-    const int8_t v = (i < T && j < T && src[(size_t)i * T + j] == 0) ? 1 : 0;
-    tile[r][tx] = v;
-    if (i < T && j < Tp) d0[(size_t)i * Tp + j] = v;
+  for (int r = w; r < 64; r += 4) {
+    const int i = i0 + r, j = j0 + l;
+    tile[r][l] = (i < T && j < T && src[(size_t)i * T + j] == 0) ? 1 : 0;
   }
   __syncthreads();
-  for (int r = ty; r < 32; r += 8) {
-    const int j = j0 + r, i = i0 + tx;
-    if (j < T && i < Tp) d1[(size_t)j * Tp + i] = tile[tx][r];
+  for (int r = w; r < 64; r += 4) {
+    const unsigned long long rowbits = __ballot(tile[r][l] != 0);
+    const unsigned long long colbits = __ballot(tile[l][r] != 0);
+    if (l == 0) {
+      if (i0 + r < T) ind[((size_t)bh * T + i0 + r) * Tw + blockIdx.x] = rowbits;
+      if (j0 + r < T) indT[((size_t)bh * T + j0 + r) * Tw + blockIdx.y] = colbits;
+    }
   }
 }
 
@@ -317,11 +318,11 @@ hipError_t launch_classify(const float* scores, const Shape& s, int8_t* Mc, int3
 }
 
 hipError_t launch_csc(const int8_t* Mc, const Shape& s, int32_t* col_ptr, int32_t* col_rows,
-                      int8_t* ind, int8_t* indT, int32_t* col_order, hipStream_t st) {
+                      unsigned long long* ind, unsigned long long* indT, int32_t* col_order, hipStream_t st) {
   {
-    const int Tp = (s.T + 15) / 16 * 16;
+    const int Tw = (s.T + 63) / 64;
     KernelTimer kt("indicator", st);
-    indicator_kernel<<<dim3((Tp + 31) / 32, (Tp + 31) / 32, s.BH), 256, 0, st>>>(Mc, s.T, Tp, ind, indT);
+    indicator_kernel<<<dim3(Tw, Tw, s.BH), 256, 0, st>>>(Mc, s.T, Tw, ind, indT);
   }
   dim3 grid((s.T + 31) / 32, s.BH);
   {

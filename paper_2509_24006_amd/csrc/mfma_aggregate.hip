@@ -5,37 +5,51 @@
 //   out[i][:] = sum_k ind[i][k] in[k][:],   ind = 1 where the block is marginal, else 0,
 // a T x T by T x (d*d + d) product per head.  The indicator is exact in bf16, the products are
 // bf16 x bf16 with float accumulation.  Compared with adding the marginal blocks one by one
-// (or subtracting the others from the total, App. A.3) the state rows are read once per 256
+// (or subtracting the others from the total, App. A.3) the state rows are read once per 512
 // output rows instead of once per row.
 //
-// Workgroup tile 256 (rows) x 128 (columns), k-step 64.  The state operand goes global -> LDS
-// directly (row-major, swizzled, double-buffered) and is read with the transposing LDS read;
-// the indicator operand is built in registers from 16-byte pieces of the padded int8 indicator.
+// The kernel is bound by HBM traffic (one read of the states, one write of the sums), so the
+// design keeps everything else small: a workgroup of eight waves owns 512 output rows (all of
+// them for T <= 512) by 128 columns, so that the states are read once; the indicator comes as
+// bit masks, 8 bytes per row and k-step; the state tiles go global -> LDS directly (row-major,
+// swizzled) through a ring of stages and are read with the transposing LDS read; the product is formed
+// with the output rows along the lanes, so that the sums leave as whole 256-byte row pieces; and a
+// workgroup takes two column tiles in a row with the ring running on, so that the stores of the
+// first overlap the loads and products of the second (with one workgroup per CU nothing else would).
 #include "mfma_common.h"
 
 namespace sla {
 namespace {
 
-constexpr int kTileB = kBlk * 256;   // 64 k-rows x 128 columns of bf16
+constexpr int kStage = kBlk * 256;   // one k-step of states: 64 rows x 128 columns of bf16
+constexpr int kStages = 5;          // ring of state tiles
+constexpr int kPasses = 2;          // column tiles of 128 per workgroup, one after the other
+constexpr int kOutStage = 32 * (64 * 4 + 16);   // store_rows_bf16<4> area of one wave
+constexpr int kAggLds = kStages * kStage + 8 * kOutStage;   // the output staging is not laid over the ring
 
-// bytes (b0, b1, b2, b3) in {0,1} of `x` -> two dwords of bf16 pairs (1.0 or 0.0)
-__device__ __forceinline__ void ind4(unsigned x, unsigned& lo, unsigned& hi) {
-  lo = ((x & 0xffu) | ((x << 8) & 0xff0000u)) * 0x3f80u;
-  hi = (((x >> 16) & 0xffu) | ((x >> 8) & 0xff0000u)) * 0x3f80u;
+// two adjacent indicator bits (bits s, s + 1 of x) -> a dword holding two bf16 (1.0 or 0.0)
+__device__ __forceinline__ unsigned bits2bf(unsigned x, int s) {
+  const unsigned y = (x >> s) & 3u;
+  return (((y << 15) | y) & 0x00010001u) * 0x3f80u;
 }
 
-__global__ __launch_bounds__(256, 2) void aggregate_mfma_kernel(const bf16* __restrict__ in,
-                                                                const int8_t* __restrict__ ind,
-                                                                int T, int Tp, int row_len, int dd,
-                                                                bf16* __restrict__ outH,
-                                                                float* __restrict__ outZ) {
+// ZPART = false: the matrix part, columns [256 blockIdx.x, +256) of d*d, written in bf16.
+// ZPART = true: the vector part (the last d entries of a state row), one column tile, written in
+// float; launched on its own so that the matrix part fills the GPU in whole rounds.
+template <bool ZPART>
+__global__ __launch_bounds__(512, 1) void aggregate_mfma_kernel(const bf16* __restrict__ in,
+                                                                const unsigned long long* __restrict__ ind,
+                                                                int T, int Tw, int row_len, int dd,
+                                                                bf16* __restrict__ outH, float* __restrict__ outZ) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
-  const int n0 = blockIdx.x * 128, m0 = blockIdx.y * 256, bh = blockIdx.z;
-  const int8_t* ib = ind + (size_t)bh * T * Tp;
+  const int nbase = ZPART ? dd : blockIdx.x * 128 * kPasses, m0 = blockIdx.y * 512, bh = blockIdx.z;
+  const int passes = ZPART ? 1 : kPasses;
+  const unsigned long long* ib = ind + (size_t)bh * T * Tw;
   const bf16* inb = in + (size_t)bh * T * row_len;
   const BufDesc rsrc = tile_rsrc(inb, T * row_len * 2);
   const int pitch = row_len * 2;
+  const int wu = wave_uniform(w);
   const unsigned lds0 = lds_base(smem);
   f32x16 acc[2][4];
 #pragma unroll
@@ -43,98 +57,157 @@ __global__ __launch_bounds__(256, 2) void aggregate_mfma_kernel(const bf16* __re
 #pragma unroll
     for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = zero_f32x16();
   const int ksteps = (T + kBlk - 1) / kBlk;
-  // one wave-wide load deposits 4 rows x 256 bytes; wave w takes row groups w, w + 4, ...
-  auto issue = [&](int ks) {
+  // one wave-wide load deposits 4 rows x 256 bytes; wave w takes the 1 KB runs w and w + 8 of a
+  // stage; rows past T read as zeros
+  int vo[2];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const int rg = 4 * k + w;
-      const int row = 4 * rg + (l >> 4), pc = l & 15;
-      const int voff = (ks * kBlk + row) * pitch + n0 * 2 + ((pc ^ swz<128>(row)) << 4);
-      load_to_lds16(rsrc, voff, 0, lds0 + (ks & 1) * kTileB + rg * 1024);
+  for (int k = 0; k < 2; ++k) {
+    const int row = 4 * (8 * k + w) + (l >> 4), pc = l & 15;
+    vo[k] = row * pitch + nbase * 2 + ((pc ^ swz<128>(row)) << 4);
+  }
+  // the loads form one stream over (pass, k-step); ip, iks, istage: the next one to request
+  int ip = 0, iks = 0, istage = 0;
+  auto issue_next = [&]() {
+    if (ip >= passes) return;
+#pragma unroll
+    for (int k = 0; k < 2; ++k)
+      load_to_lds16(rsrc, vo[k], iks * kBlk * pitch + ip * 256, lds0 + istage * kStage + (8 * k + wu) * 1024);
+    istage = istage == kStages - 1 ? 0 : istage + 1;
+    if (++iks == ksteps) {
+      iks = 0;
+      ++ip;
     }
   };
-  // indicator pieces of a k-step: rows m0 + 64 w + 32 mt + ln, 16 bytes per 16 k
-  u32x4 ibn[2][4];
-  auto load_ind = [&](int ks) {
+  // per-lane offsets of the transposing reads inside a stage: [8-row half][column tile]
+  TileAddr<128> ad;
+  ad.init(0, l);
+  int tro[2][4];
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
-      const int i = m0 + 64 * w + 32 * mt + ln;
+  for (int h = 0; h < 2; ++h)
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int k = ks * kBlk + 16 * u;
-        ibn[mt][u] = (i < T && k < Tp) ? *reinterpret_cast<const u32x4*>(ib + (size_t)i * Tp + k)
-                                       : u32x4{0u, 0u, 0u, 0u};
-      }
-    }
-  };
-  issue(0);
-  load_ind(0);
-  for (int ks = 0; ks < ksteps; ++ks) {
-    wait_vm0();
-    __syncthreads();
-    u32x4 ib16[2][4];
+    for (int nt = 0; nt < 4; ++nt) tro[h][nt] = ad.tr(h, nt);
+  constexpr int RB = 16 * SwzTile<128>::ROW_BYTES;
+  const int row0 = m0 + 64 * w + ln;   // this lane's output rows: row0 and row0 + 32
+#pragma unroll
+  for (int k = 0; k < kStages - 1; ++k) issue_next();
+  const int total = passes * ksteps;
+  int gs = 0, stage = 0;   // position in the stream of the tile consumed next
+  for (int pass = 0; pass < passes; ++pass) {
+    const int n0 = nbase + 128 * pass;
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-      for (int u = 0; u < 4; ++u) ib16[mt][u] = ibn[mt][u];
-    if (ks + 1 < ksteps) {   // next step's tile and indicator pieces fly during this step's products
-      issue(ks + 1);
-      load_ind(ks + 1);
-    }
-    const unsigned char* Bs = smem + (ks & 1) * kTileB;
+      for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = zero_f32x16();
+    for (int ks0 = 0; ks0 < ksteps; ks0 += 8) {
+      // indicator words of the next eight k-steps for the lane's two rows
+      unsigned long long wb[2][8];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      // slots 0..3 <- k = 16u + 4g .. +3, slots 4..7 <- k = 16u + 8 + 4g .. +3
-      bf16x8 a[2];
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          const int i = row0 + 32 * mt;
+          wb[mt][q] = (i < T && ks0 + q < Tw) ? ib[(size_t)i * Tw + ks0 + q] : 0ull;
+        }
+      // (waited for here, once per eight k-steps, rather than at each first use below, where the
+      // wait would also drain the tile loads in flight)
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int q = 0; q < 8; ++q) pin_loaded(wb[mt][q]);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const int ks = ks0 + q;
+        if (ks >= ksteps) break;
+        // the lane's bits of this k-step, moved so that k = 16 u + 4 g sits at bit 16 u
+        const unsigned long long x0 = wb[0][q] >> (4 * g), x1 = wb[1][q] >> (4 * g);
+        // the tile has landed; the kStages - 2 tiles requested after it may still be in flight
+        if (gs + kStages - 2 < total) wait_vm<2 * (kStages - 2)>();
+        else wait_vm0();
+        __syncthreads();   // ... for every wave, and the stage of the previous tile is free
+        issue_next();
+        const int so = stage * kStage;
+        stage = stage == kStages - 1 ? 0 : stage + 1;
+        ++gs;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          // slots 0..3 <- k = 16 u + 4 g .. + 3, slots 4..7 <- k = 16 u + 8 + 4 g .. + 3: the order
+          // in which the transposing read hands over the state rows
+          bf16x8 b[2];
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt) {
+            const unsigned long long x = mt ? x1 : x0;
+            const unsigned half = u < 2 ? (unsigned)x : (unsigned)(x >> 32);
+            const int sh = 16 * (u & 1);
+            u32x4 packed = {bits2bf(half, sh), bits2bf(half, sh + 2), bits2bf(half, sh + 8), bits2bf(half, sh + 10)};
+            b[mt] = *reinterpret_cast<bf16x8*>(&packed);
+          }
+#pragma unroll
+          for (int nt = 0; nt < 4; ++nt) {
+            const bf16x8 a = lds_tr<128>(smem, tro[0][nt] + so + u * RB, tro[1][nt] + so + u * RB);
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt) acc[mt][nt] = mfma32(a, b[mt], acc[mt][nt]);
+          }
+        }
+      }
+    }
+    // C tiles: lane = output row, registers = columns 32 nt + c_row(r, g)
+    if (ZPART) {
+      const int dz = row_len - dd;
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt) {
-        const unsigned b0 = g ? ib16[mt][u].y : ib16[mt][u].x;
-        const unsigned b1 = g ? ib16[mt][u].w : ib16[mt][u].z;
-        unsigned p0, p1, p2, p3;
-        ind4(b0, p0, p1);
-        ind4(b1, p2, p3);
-        u32x4 packed = {p0, p1, p2, p3};
-        a[mt] = *reinterpret_cast<bf16x8*>(&packed);
+        const int row = row0 + 32 * mt;
+        if (row >= T) continue;
+        float* o = outZ + ((size_t)bh * T + row) * dz;
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+          for (int r4 = 0; r4 < 4; ++r4) {
+            const int c = 32 * nt + 8 * r4 + 4 * g;
+            if (c < dz)
+              *reinterpret_cast<f32x4*>(o + c) = f32x4{acc[mt][nt][4 * r4], acc[mt][nt][4 * r4 + 1],
+                                                        acc[mt][nt][4 * r4 + 2], acc[mt][nt][4 * r4 + 3]};
+          }
       }
+    } else {
+      // through this wave's own staging area (no barrier: LDS serves a wave's accesses in order)
 #pragma unroll
-      for (int nt = 0; nt < 4; ++nt) {
-        const bf16x8 b = read_tr_swz<128>(Bs, 16 * u, nt, l);
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt) acc[mt][nt] = mfma32(a[mt], b, acc[mt][nt]);
+      for (int mt = 0; mt < 2; ++mt) {
+        const int r0 = m0 + 64 * w + 32 * mt;
+        if (r0 < T)
+          store_rows_bf16<4>(smem + kStages * kStage + wu * kOutStage, acc[mt], outH + ((size_t)bh * T + r0) * dd + n0, dd,
+                             T - r0, l);
       }
     }
   }
-  // matrix part in bf16 (it is consumed as a bf16 MFMA operand), vector part in float
-  bf16* oh = outH + (size_t)bh * T * dd;
-  float* oz = outZ + (size_t)bh * T * (row_len - dd);
-#pragma unroll
-  for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-    for (int nt = 0; nt < 4; ++nt) {
-      const int col = n0 + 32 * nt + ln;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int row = m0 + 64 * w + 32 * mt + c_row(i, g);
-        if (row < T && col < dd) oh[(size_t)row * dd + col] = __float2bfloat16(acc[mt][nt][i]);
-        else if (row < T && col < row_len) oz[(size_t)row * (row_len - dd) + col - dd] = acc[mt][nt][i];
-      }
-    }
 }
 
 }  // namespace
 
-// out[i] = sum over k with ind[i][k] = 1 of the bf16 state rows in[k] (d*d + d values each); ind is
-// [BH][T][Tp] int8.  The d x d part goes to outH (bf16 [BH][T][d*d]), the d part to outZ (float).
-hipError_t mfma_aggregate(const void* in, const int8_t* ind, const Shape& s, void* outH, float* outZ,
-                          hipStream_t st) {
-  const int row_len = s.state_row();
-  const int Tp = (s.T + 15) / 16 * 16;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(aggregate_mfma_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kTileB);
+// out[i] = sum over k with bit k of ind[i] set of the bf16 state rows in[k] (d*d + d values each);
+// ind is [BH][T][ceil(T/64)] 64-bit masks.  The d x d part goes to outH (bf16 [BH][T][d*d]), the d
+// part to outZ (float).
+hipError_t mfma_aggregate(const void* in, const unsigned long long* ind, const Shape& s, void* outH,
+                          float* outZ, hipStream_t st) {
+  const int row_len = s.state_row(), dd = s.d * s.d;
+  const int Tw = (s.T + 63) / 64;
+  if (dd % (128 * kPasses) != 0) return hipErrorInvalidValue;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(aggregate_mfma_kernel<false>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, kAggLds);
   if (e != hipSuccess) return e;
-  KernelTimer kt("aggregate", st);
-  aggregate_mfma_kernel<<<dim3((row_len + 127) / 128, (s.T + 255) / 256, s.BH), 256, 2 * kTileB, st>>>(
-      (const bf16*)in, ind, s.T, Tp, row_len, s.d * s.d, (bf16*)outH, outZ);
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(aggregate_mfma_kernel<true>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kAggLds);
+  if (e != hipSuccess) return e;
+  const int mtiles = (s.T + 511) / 512;
+  {
+    KernelTimer kt("aggregate_z", st);
+    aggregate_mfma_kernel<true><<<dim3(1, mtiles, s.BH), 512, kAggLds, st>>>((const bf16*)in, ind, s.T, Tw, row_len, dd,
+                                                                           nullptr, outZ);
+  }
+  {
+    KernelTimer kt("aggregate", st);
+    aggregate_mfma_kernel<false><<<dim3(dd / (128 * kPasses), mtiles, s.BH), 512, kAggLds, st>>>((const bf16*)in, ind, s.T, Tw,
+                                                                                  row_len, dd, (bf16*)outH, nullptr);
+  }
   return hipGetLastError();
 }
 

@@ -191,7 +191,8 @@ typedef __attribute__((address_space(3))) void lds_void;
 // barrier after its last read before it is overwritten.
 __device__ __forceinline__ void load_to_lds16(BufDesc desc, int voff, int soff, unsigned lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-               :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(desc), "s"(soff) : "memory");
+               :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(desc), "s"(__builtin_amdgcn_readfirstlane(soff))
+               : "memory");
 }
 
 // LDS byte address of the dynamic LDS array, as a wave-uniform integer

@@ -31,13 +31,13 @@ hipError_t launch_scores(const float* qbar, const float* kbar, const Shape& s, f
 hipError_t launch_classify(const float* scores, const Shape& s, int8_t* Mc, int32_t* row_idx,
                            hipStream_t st);
 hipError_t launch_csc(const int8_t* Mc, const Shape& s, int32_t* col_ptr, int32_t* col_rows,
-                      int8_t* ind, int8_t* indT, int32_t* col_order, hipStream_t st);
+                      unsigned long long* ind, unsigned long long* indT, int32_t* col_order, hipStream_t st);
 
 // ---- float-arithmetic path (simt_kernels.hip): every contraction in fp32 FMA
 struct FwdArgs {
   const void *Q, *K, *V, *W;
   const int8_t* Mc;
-  const int8_t* ind;   // marginal indicator, padded
+  const unsigned long long* ind;   // marginal indicator bit masks
   const int32_t* row_idx;
   void* O;
   void *Os, *Ol;   // may be null (inference)
@@ -50,7 +50,7 @@ hipError_t simt_forward(const Shape& s, const FwdArgs& a, hipStream_t st);
 struct BwdArgs {
   const void *Q, *K, *V, *W, *dO;
   const int8_t* Mc;
-  const int8_t* indT;  // marginal indicator, transposed and padded
+  const unsigned long long* indT;  // marginal indicator bit masks, transposed
   const int32_t *row_idx, *col_ptr, *col_rows, *col_order;
   const void *Os, *Ol;
   const float *L, *HZ;
@@ -70,8 +70,8 @@ hipError_t simt_backward(const Shape& s, const BwdArgs& a, hipStream_t st);
 // ---- bf16 matrix-core path (mfma_fwd.hip)
 size_t mfma_forward_ws_bytes(const Shape& s);
 hipError_t mfma_forward(const Shape& s, const FwdArgs& a, char* ws, hipStream_t st);
-// out[i] = sum over k with ind[i][k] = 1 of the bf16 state rows in[k] (mfma_aggregate.hip)
-hipError_t mfma_aggregate(const void* in, const int8_t* ind, const Shape& s, void* outH, float* outZ,
+// out[i] = sum over k with bit k of ind[i] set of the bf16 state rows in[k] (mfma_aggregate.hip)
+hipError_t mfma_aggregate(const void* in, const unsigned long long* ind, const Shape& s, void* outH, float* outZ,
                           hipStream_t st);
 // bf16 tensors keep the aggregated states as a bf16 block [BH][T][d*d] (matrices, transposed)
 // followed by a float block [BH][T][d] (vectors); this is the byte offset of the second block.

@@ -44,12 +44,17 @@ def check_luts(Mc: np.ndarray, row_idx: np.ndarray, col_ptr: np.ndarray, col_row
                ind: np.ndarray = None, ind_t: np.ndarray = None, col_order: np.ndarray = None):
     B, H, T, _ = Mc.shape
     if ind is not None:
-        Tp = ind.shape[-1]
-        want = np.zeros((B, H, T, Tp), np.int8)
-        want[..., :T] = (Mc == 0)
-        assert np.array_equal(ind, want)
-        want[..., :T] = np.swapaxes(Mc == 0, -1, -2)
-        assert np.array_equal(ind_t, want)
+        # bit b of word q of row i: block (i, 64 q + b) is marginal; bits past T are clear
+        Tw = ind.shape[-1]
+        assert Tw == (T + 63) // 64
+
+        def pack(m):
+            bits = np.zeros((B, H, T, Tw * 64), np.uint8)
+            bits[..., :T] = m
+            return np.packbits(bits.reshape(B, H, T, Tw, 64), axis=-1, bitorder="little").view(np.uint64)[..., 0]
+
+        assert np.array_equal(ind.view(np.uint64), pack(Mc == 0))
+        assert np.array_equal(ind_t.view(np.uint64), pack(np.swapaxes(Mc == 0, -1, -2)))
     if col_order is not None:
         cnt = (Mc == 1).sum(-2)
         for b in range(B):
