@@ -29,7 +29,7 @@ __device__ __forceinline__ void stage_matrix_t(const bf16* __restrict__ src, bf1
 template <int D>
 struct PreLds {
   static constexpr int RS = kRSl(D);
-  static constexpr int G_ELEMS = kBlk * RS;     // dO^l row-major [q][b]
+  static constexpr int G_ELEMS = kBlk * D;      // dO^l row-major [q][b], unpadded, 16-byte chunks swizzled
   static constexpr int GT_ELEMS = D * kVS;      // dO^l transposed [b][q]
   static constexpr int AT_ELEMS = D * kVS;      // (phi(Q)/den)^T [c][q]
   static constexpr int H_ELEMS = D * RS;        // H_i [a][b]; reuses the two transposed tiles
@@ -38,8 +38,10 @@ struct PreLds {
   static constexpr int BYTES = F_OFF + 4 * kBlk * 4;   // Dl partial [par][q], dot partial [par][q]
 };
 
+// (three workgroups per CU: the kernel is a chain of short phases that wait on memory, and the
+// LDS footprint is kept just under a third of a CU's for that)
 template <int D>
-__global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
+__global__ __launch_bounds__(256, 3) void bwd_pre_mfma_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ dO, const bf16* __restrict__ W,
     const bf16* __restrict__ Os, const bf16* __restrict__ Ol, const bf16* __restrict__ H16,
     const float* __restrict__ Zs, int N,
@@ -107,7 +109,7 @@ __global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
         if (qok) dl = fmaf(v, (float)ol4[r], dl);
         Gt[(b0 + r) * kVS + qrow] = __float2bfloat16(v);
       }
-      *reinterpret_cast<bf16x4*>(Gs + qrow * RS + b0) = pk;
+      *reinterpret_cast<bf16x4*>(Gs + qrow * D + (((b0 >> 3) ^ swz<D>(qrow)) << 3) + (b0 & 7)) = pk;
     }
   }
   dl = half_sum(dl);
@@ -186,7 +188,7 @@ __global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
 #pragma unroll
     for (int t = 0; t < KT; ++t) {
       const bf16x8 a = *reinterpret_cast<const bf16x8*>(Hs + (32 * ct + ln) * RS + 16 * t + 8 * g);
-      const bf16x8 b = *reinterpret_cast<const bf16x8*>(Gs + qrow * RS + 16 * t + 8 * g);
+      const bf16x8 b = *reinterpret_cast<const bf16x8*>(Gs + qrow * D + (((2 * t + g) ^ swz<D>(qrow)) << 3));
       dq[h2] = mfma32(a, b, dq[h2]);
     }
 #pragma unroll
