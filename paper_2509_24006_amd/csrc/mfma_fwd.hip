@@ -25,126 +25,98 @@ __global__ void prep_w_kernel(const bf16* __restrict__ W, bf16* __restrict__ WTp
 
 // ------------------------------------------------------------------ key-block states
 
+// h_j^T[e][c] = sum_keys V[key][e] phi(K)[key][c], z_j[c] = sum_keys phi(K)[key][c] for one key
+// block (Alg. 1, precompute line).  K_j and V_j come in as LDS tiles; phi is applied to the K tile
+// in place; both operands of the product are contracted over tile rows, i.e. read with the
+// transposing LDS read; the product is formed with e along the lanes so that the rows of h^T leave
+// whole.  Wave w owns rows e in [32 w, 32 w + 32).
 template <int D>
-__global__ __launch_bounds__(256) void states_mfma_kernel(const bf16* __restrict__ K,
-                                                          const bf16* __restrict__ V, int N, int Tn,
-                                                          int phi, bf16* __restrict__ hz) {
-  constexpr int OS = D + 8;             // stride of the output staging tile
-  constexpr int NT = D / 32;            // 32-wide tiles per feature dimension
-  __shared__ __attribute__((aligned(16))) bf16 Kt[D * kVS];   // phi(K)^T  [c][key pos]
-  __shared__ __attribute__((aligned(16))) bf16 Vt[D * kVS];   // V^T       [e][key pos]
-  __shared__ __attribute__((aligned(16))) bf16 Out[D * OS];   // h^T       [e][c]
-  __shared__ float stat_m[kBlk], stat_inv[kBlk];
-  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
+__global__ __launch_bounds__(256, 4) void states_mfma_kernel(const bf16* __restrict__ K,
+                                                             const bf16* __restrict__ V, int N, int Tn,
+                                                             int phi, bf16* __restrict__ hz) {
+  using T = SwzTile<D>;
+  constexpr int NT = D / 32;
+  constexpr int STG = 32 * (64 * NT + 16);           // store_rows_bf16<NT> area of one wave
+  constexpr int LDSB = 2 * T::BYTES > NT * STG ? 2 * T::BYTES : NT * STG;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[LDSB];
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5;
   const int j = blockIdx.x, bh = blockIdx.y;
   const int n0 = j * kBlk, cnt = min(kBlk, N - n0);
-  const bf16* Kb = K + ((size_t)bh * N + n0) * D;
-  const bf16* Vb = V + ((size_t)bh * N + n0) * D;
-  // pass 1: softmax statistics of each key row (four threads per row)
-  if (phi == 0) {
+  const int ldv = tile_lane_offset<D>(w, l);
+  const int wu = wave_uniform(w);
+  const unsigned lds0 = lds_base(smem) + wu * 1024;
+  issue_tile_load<D>(K + ((size_t)bh * N + n0) * D, cnt, lds0, 0, ldv);
+  issue_tile_load<D>(V + ((size_t)bh * N + n0) * D, cnt, lds0, T::BYTES, ldv);
+  wait_vm0();
+  __syncthreads();
+  // phi on the K tile in place: four threads per key row, a quarter of the features each
+  {
     const int row = tid >> 2, part = tid & 3;
-    float mx = -INFINITY, sum = 0.0f;
-    float v[D / 4];
-    if (row < cnt) {
+    constexpr int CPP = D / 32;   // 16-byte chunks per thread
+    bf16x8 x[CPP];
 #pragma unroll
-      for (int c8 = 0; c8 < D / 32; ++c8) {
-        const bf16x8 x = *reinterpret_cast<const bf16x8*>(Kb + (size_t)row * D + part * (D / 4) + 8 * c8);
+    for (int c = 0; c < CPP; ++c) x[c] = *reinterpret_cast<const bf16x8*>(smem + swz_chunk_off<D>(row, part * CPP + c));
+    float mx = 0.0f, inv = 1.0f;
+    if (phi == 0) {
+      mx = -INFINITY;
 #pragma unroll
-        for (int s = 0; s < 8; ++s) {
-          v[8 * c8 + s] = (float)x[s];
-          mx = fmaxf(mx, v[8 * c8 + s]);
-        }
-      }
+      for (int c = 0; c < CPP; ++c)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) mx = fmaxf(mx, (float)x[c][e]);
+      mx = fmaxf(mx, __shfl_xor(mx, 1, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 2, 64));
+      float sum = 0.0f;
+#pragma unroll
+      for (int c = 0; c < CPP; ++c)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sum += fast_exp2(((float)x[c][e] - mx) * kLog2e);
+      sum += __shfl_xor(sum, 1, 64);
+      sum += __shfl_xor(sum, 2, 64);
+      inv = 1.0f / sum;
     }
-    mx = fmaxf(mx, __shfl_xor(mx, 1, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 2, 64));
-    if (row < cnt) {
+    const bool ok = row < cnt;   // rows past the end of the sequence contribute nothing, also to z_j
 #pragma unroll
-      for (int c = 0; c < D / 4; ++c) sum += fast_exp2((v[c] - mx) * kLog2e);
-    }
-    sum += __shfl_xor(sum, 1, 64);
-    sum += __shfl_xor(sum, 2, 64);
-    if (part == 0) {
-      stat_m[row] = row < cnt ? mx : 0.0f;
-      stat_inv[row] = row < cnt ? 1.0f / sum : 0.0f;
+    for (int c = 0; c < CPP; ++c) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x[c][e] = (__bf16)(ok ? phi_val((float)x[c][e], phi, mx, inv) : 0.0f);
+      *reinterpret_cast<bf16x8*>(smem + swz_chunk_off<D>(row, part * CPP + c)) = x[c];
     }
   }
   __syncthreads();
-  // pass 2: transposing stage of phi(K) and V
-  constexpr int UNITS = 16 * (D / 4);
+  bf16* out = hz + ((size_t)bh * Tn + j) * (D * D + D);
+  f32x16 acc[NT];
+  if (w < NT) {
+    TileAddr<D> ad;
+    ad.init(0, l);
+    constexpr int RB = 16 * T::ROW_BYTES;
+    bf16x8 ones;
 #pragma unroll
-  for (int r = 0; r < UNITS / 256; ++r) {
-    const int u = tid + 256 * r;
-    const int fg = u % (D / 4), kg = u / (D / 4);
-    u32x2 x[4];
-    load_patch(Vb, D, 4 * kg, 4 * fg, cnt, x);
-    store_patch_t(Vt, kVS, 4 * fg, pos_of_kg(kg), x);
-    load_patch(Kb, D, 4 * kg, 4 * fg, cnt, x);
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      const int key = 4 * kg + kk;
-      const bool ok = key < cnt;
-      float f[4];
-      f[0] = __uint_as_float(x[kk].x << 16);
-      f[1] = __uint_as_float(x[kk].x & 0xffff0000u);
-      f[2] = __uint_as_float(x[kk].y << 16);
-      f[3] = __uint_as_float(x[kk].y & 0xffff0000u);
-      if (phi == 0) {
-        const float m = stat_m[key], inv = stat_inv[key];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) f[i] = fast_exp2((f[i] - m) * kLog2e) * inv;
-      } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) f[i] = f[i] > 0.0f ? f[i] + 1.0f : fast_exp2(f[i] * kLog2e);
-      }
-      bf16x4 pk;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) pk[i] = (__bf16)(ok ? f[i] : 0.0f);
-      x[kk] = *reinterpret_cast<u32x2*>(&pk);
-    }
-    store_patch_t(Kt, kVS, 4 * fg, pos_of_kg(kg), x);
-  }
-  __syncthreads();
-  // h^T[e][c] = sum_keys V[key][e] phi(K)[key][c]; wave w owns e-tiles w, w+4, ...
-  bf16x8 ones;
-#pragma unroll
-  for (int s = 0; s < 8; ++s) ones[s] = (__bf16)1.0f;
-  for (int et = w; et < NT; et += 4) {
-    f32x16 acc[NT];
+    for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
+    f32x16 zc = zero_f32x16();
 #pragma unroll
     for (int ct = 0; ct < NT; ++ct) acc[ct] = zero_f32x16();
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(Vt + (32 * et + ln) * kVS + 16 * t + 8 * g);
+    for (int t = 0; t < kBlk / 16; ++t) {
+      const bf16x8 vb = lds_tr<D>(smem, ad.tr(0, w) + T::BYTES + t * RB, ad.tr(1, w) + T::BYTES + t * RB);   // V^T, rows e
 #pragma unroll
       for (int ct = 0; ct < NT; ++ct) {
-        const bf16x8 b = *reinterpret_cast<const bf16x8*>(Kt + (32 * ct + ln) * kVS + 16 * t + 8 * g);
-        acc[ct] = mfma32(a, b, acc[ct]);
+        const bf16x8 ka = lds_tr<D>(smem, ad.tr(0, ct) + t * RB, ad.tr(1, ct) + t * RB);   // phi(K)^T, rows c
+        acc[ct] = mfma32(ka, vb, acc[ct]);   // C[c][e]: lane = e, registers = c
+        if (ct == w) zc = mfma32(ka, ones, zc);   // every column of this C tile is z_j[32 w ..]
       }
     }
+    if ((l & 31) == 0) {
 #pragma unroll
-    for (int ct = 0; ct < NT; ++ct)
+      for (int r4 = 0; r4 < 4; ++r4) {
+        bf16x4 pk;
 #pragma unroll
-      for (int i = 0; i < 16; ++i)
-        Out[(32 * et + c_row(i, g)) * OS + 32 * ct + ln] = __float2bfloat16(acc[ct][i]);
-  }
-  bf16* out = hz + ((size_t)bh * Tn + j) * (D * D + D);
-  // z[c] = sum_keys phi(K)[key][c]: a ones operand against c-tile w
-  if (w < NT) {
-    f32x16 zc = zero_f32x16();
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const bf16x8 b = *reinterpret_cast<const bf16x8*>(Kt + (32 * w + ln) * kVS + 16 * t + 8 * g);
-      zc = mfma32(ones, b, zc);
+        for (int r = 0; r < 4; ++r) pk[r] = (__bf16)zc[4 * r4 + r];
+        *reinterpret_cast<bf16x4*>(out + (size_t)D * D + 32 * w + 8 * r4 + 4 * g) = pk;
+      }
     }
-    if (g == 0) out[(size_t)D * D + 32 * w + ln] = __float2bfloat16(zc[0]);
   }
-  __syncthreads();
-  for (int idx = tid; idx < D * (D / 8); idx += 256) {
-    const int e = idx / (D / 8), c8 = idx - e * (D / 8);
-    *reinterpret_cast<u32x4*>(out + (size_t)e * D + 8 * c8) =
-        *reinterpret_cast<const u32x4*>(Out + e * OS + 8 * c8);
-  }
+  __syncthreads();   // the tiles are free: each wave stages its rows over them
+  if (w < NT) store_rows_bf16<NT>(smem + wu * STG, acc, out + (size_t)(32 * w) * D, D, 32, l);
 }
 
 // ------------------------------------------------------------------ forward main kernel
