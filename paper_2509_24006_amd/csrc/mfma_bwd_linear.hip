@@ -230,41 +230,49 @@ __global__ __launch_bounds__(256, 3) void bwd_pre_mfma_kernel(
 }
 
 // ------------------------------------------------------------------ dW partial sums
-// Workgroup g sums (O^l)^T dO over token tiles g, g + G, ...; wave w owns rows 32w.. of dW.
+// dW = sum over tokens of O^l^T dO (gradient of Proj, Eq. 6).  Workgroup g sums over token tiles
+// g, g + G, ...; the two tiles of a step come in as LDS tiles, double-buffered, and both operands
+// are contracted over tile rows (transposing reads).  Wave w owns rows c in [32 w, 32 w + 32) of dW.
 template <int D>
-__global__ __launch_bounds__(256) void dw_mfma_kernel(const bf16* __restrict__ Ol,
-                                                      const bf16* __restrict__ dO, int BH, int N,
-                                                      int Tn, float* __restrict__ part) {
+__global__ __launch_bounds__(256, 2) void dw_mfma_kernel(const bf16* __restrict__ Ol,
+                                                         const bf16* __restrict__ dO, int BH, int N,
+                                                         int Tn, float* __restrict__ part) {
+  using T = SwzTile<D>;
   constexpr int NT = D / 32;
-  __shared__ __attribute__((aligned(16))) bf16 At[D * kVS];   // (O^l)^T [c][token pos]
-  __shared__ __attribute__((aligned(16))) bf16 Bt[D * kVS];   // dO^T    [e][token pos]
+  constexpr int BUF = 2 * T::BYTES;
+  constexpr int RB = 16 * T::ROW_BYTES;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * BUF];
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
+  const int ldv = tile_lane_offset<D>(w, l);
+  const unsigned lds0 = lds_base(smem) + wave_uniform(w) * 1024;
   f32x16 acc[NT];
 #pragma unroll
   for (int et = 0; et < NT; ++et) acc[et] = zero_f32x16();
-  for (int t = blockIdx.x; t < BH * Tn; t += gridDim.x) {
+  const int total = BH * Tn;
+  auto issue = [&](int t, int buf) {
     const int bh = t / Tn, i = t - bh * Tn;
     const int rows = min(kBlk, N - i * kBlk);
     const size_t base = ((size_t)bh * N + (size_t)i * kBlk) * D;
-    u32x4 xa[4], xb[4];
-    const int fg = tid % (D / 8), rg = tid / (D / 8);
-    if (rg < 16) {
-      load_unit(Ol + base, D, rg, fg, rows, xa);
-      load_unit(dO + base, D, rg, fg, rows, xb);
-    }
-    __syncthreads();
-    if (rg < 16) {
-      store_unit_t(At, rg, fg, xa);
-      store_unit_t(Bt, rg, fg, xb);
-    }
-    __syncthreads();
+    issue_tile_load<D>(Ol + base, rows, lds0, buf * BUF, ldv);
+    issue_tile_load<D>(dO + base, rows, lds0, buf * BUF + T::BYTES, ldv);
+  };
+  TileAddr<D> ad;
+  ad.init(0, l);
+  if ((int)blockIdx.x < total) issue(blockIdx.x, 0);
+  int buf = 0;
+  for (int t = blockIdx.x; t < total; t += gridDim.x) {
+    wait_vm0();
+    __syncthreads();   // this step's tiles have landed; the other buffer is fully consumed
+    if (t + (int)gridDim.x < total) issue(t + gridDim.x, buf ^ 1);
+    const int off = buf * BUF;
+    buf ^= 1;
     if (w < NT) {
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(At + (32 * w + ln) * kVS + 16 * u + 8 * g);
+      for (int u = 0; u < kBlk / 16; ++u) {
+        const bf16x8 a = lds_tr<D>(smem, ad.tr(0, w) + off + u * RB, ad.tr(1, w) + off + u * RB);   // O^l^T rows c
 #pragma unroll
         for (int et = 0; et < NT; ++et) {
-          const bf16x8 b = *reinterpret_cast<const bf16x8*>(Bt + (32 * et + ln) * kVS + 16 * u + 8 * g);
+          const bf16x8 b = lds_tr<D>(smem, ad.tr(0, et) + off + T::BYTES + u * RB, ad.tr(1, et) + off + T::BYTES + u * RB);
           acc[et] = mfma32(a, b, acc[et]);
         }
       }

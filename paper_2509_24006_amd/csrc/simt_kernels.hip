@@ -827,7 +827,7 @@ BwdWs carve_bwd(const Shape& s, char* ws) {
   };
   const size_t nd = (size_t)s.BH * s.N * s.d, n = (size_t)s.BH * s.N;
   const size_t st = (size_t)s.BH * s.T * s.state_row();
-  w.nparts = s.BH * s.T < 256 ? s.BH * s.T : 256;
+  w.nparts = s.BH * s.T < 512 ? s.BH * s.T : 512;   // two workgroups per CU
   w.dOl = take(nd);
   w.Ds = take(n);
   w.Dl = take(n);
