@@ -1,7 +1,7 @@
 // bf16 matrix-core backward kernels of the linear branch and of Proj (Algorithm 2 first loop and
 // last line, Eq. 8, plus the chain rule of Eq. 6 and through phi):
 //   bwd_pre_mfma    per query block: dO^l = dO W^T, D^s, D^l, dH_i, dZ_i, dQ^phi_i -> dQ (linear part)
-//   bwd_link_mfma   per key block:   dK^phi_j = V_j dH^T + 1 dZ^T -> dK (linear part), dV_j (linear part)
+//                   (the key-side counterpart is the prologue of the dK/dV kernel)
 //   dw_mfma         dW = sum_n (O^l_n)^T dO_n, per-workgroup partial sums
 // One lane owns one token (query or key) in every product whose result is per token, so the
 // row-wise quantities (softmax statistics of phi, D^l, the normaliser phi(Q) Z) are per-lane scalars.
@@ -10,50 +10,38 @@
 namespace sla {
 namespace {
 
-constexpr int kRSl(int D) { return D + 8; }
-
-// Stages a d x d bf16 matrix stored [b][a] (b-major) into LDS transposed, [a][b] (stride RS).
-template <int D>
-__device__ __forceinline__ void stage_matrix_t(const bf16* __restrict__ src, bf16* dst, int RS) {
-  for (int pidx = threadIdx.x; pidx < (D / 4) * (D / 4); pidx += 256) {
-    const int a4 = pidx % (D / 4), b4 = pidx / (D / 4);
-    u32x2 x[4];
-#pragma unroll
-    for (int bb = 0; bb < 4; ++bb)
-      x[bb] = *reinterpret_cast<const u32x2*>(src + (size_t)(4 * b4 + bb) * D + 4 * a4);
-    store_patch_t(dst, RS, 4 * a4, 4 * b4, x);
-  }
-}
-
 // ------------------------------------------------------------------ query side
+// Per query block i (Alg. 2, first loop; Eq. 8 and the chain rule of Eq. 6):
+//   D^s = rowsum(dO * O^s);  dO^l = dO W^T;  D^l = rowsum(dO^l * O^l);  a = phi(Q) / (phi(Q) Z_i)
+//   dH_i = a^T dO^l (stored transposed, [b][c]);  dZ_i = -a^T D^l
+//   dQ^phi = (dO^l H_i^T - D^l Z_i^T) / (phi(Q) Z_i), then through the Jacobian of phi
+// Every input tile (dO, O^s, O^l, Q, H_i) comes in as an LDS tile; dO^l and a are written back as
+// row-major tiles so that products contracted over the queries read them with the transposing
+// read; dH rows and the dQ part leave as whole rows.
 template <int D>
 struct PreLds {
-  static constexpr int RS = kRSl(D);
-  static constexpr int G_ELEMS = kBlk * D;      // dO^l row-major [q][b], unpadded, 16-byte chunks swizzled
-  static constexpr int GT_ELEMS = D * kVS;      // dO^l transposed [b][q]
-  static constexpr int AT_ELEMS = D * kVS;      // (phi(Q)/den)^T [c][q]
-  static constexpr int H_ELEMS = D * RS;        // H_i [a][b]; reuses the two transposed tiles
-  static_assert(H_ELEMS <= GT_ELEMS + AT_ELEMS, "H_i must fit over the transposed tiles");
-  static constexpr int F_OFF = (G_ELEMS + GT_ELEMS + AT_ELEMS) * 2;
-  static constexpr int BYTES = F_OFF + 4 * kBlk * 4;   // Dl partial [par][q], dot partial [par][q]
+  static constexpr int TILE = SwzTile<D>::BYTES;
+  // slots: 0 dO, then dO^l | 1 O^s, then a, then rows 0..63 of H_i | 2 O^l, then rows 64.. of H_i | 3 Q
+  // (a fifth slot for H_i would let it arrive earlier, but 5 tiles + 1 KB is just over half a CU's LDS)
+  static constexpr int F_OFF = 4 * TILE;
+  static constexpr int BYTES = F_OFF + 4 * kBlk * 4;   // D^l partial [par][q], dot partial [par][q]
+  static constexpr int STG = 32 * (64 * (D / 32) + 16);   // staging of one wave, laid over slots 1..3
+  static_assert(4 * STG <= 3 * TILE, "output staging fits over three slots");
 };
 
-// (three workgroups per CU: the kernel is a chain of short phases that wait on memory, and the
-// LDS footprint is kept just under a third of a CU's for that)
 template <int D>
-__global__ __launch_bounds__(256, 3) void bwd_pre_mfma_kernel(
+__global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ dO, const bf16* __restrict__ W,
     const bf16* __restrict__ Os, const bf16* __restrict__ Ol, const bf16* __restrict__ H16,
     const float* __restrict__ Zs, int N,
     int Tn, int n_0, int phi, float* __restrict__ Ds, bf16* __restrict__ dHZ,
     float* __restrict__ dQlin) {
   using Lds = PreLds<D>;
-  constexpr int RS = Lds::RS, NT = D / 32, KT = D / 16, HT = NT / 2;
+  using T = SwzTile<D>;
+  constexpr int NT = D / 32, KT = D / 16, HT = NT / 2;
+  constexpr int RB = 16 * T::ROW_BYTES;
+  constexpr int S0 = 0, S1 = Lds::TILE, S2 = 2 * Lds::TILE, S3 = 3 * Lds::TILE;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  bf16* Gs = reinterpret_cast<bf16*>(smem);
-  bf16* Gt = Gs + Lds::G_ELEMS;
-  bf16* At = Gt + Lds::GT_ELEMS;
-  bf16* Hs = Gt;   // staged once dH_i, dZ_i no longer need the transposed tiles
   float* dlp = reinterpret_cast<float*>(smem + Lds::F_OFF);   // [par][64]
   float* dotp = dlp + 2 * kBlk;                               // [par][64]
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
@@ -62,63 +50,72 @@ __global__ __launch_bounds__(256, 3) void bwd_pre_mfma_kernel(
   const int q0 = i * kBlk, rows = min(kBlk, N - q0);
   const int qrow = qh * 32 + ln;
   const bool qok = qrow < rows;
-  const size_t qoff = ((size_t)bh * N + q0 + qrow) * D;
+  const size_t base = ((size_t)bh * N + q0) * D;
+  const int ldv = tile_lane_offset<D>(w, l);
+  const int wu = wave_uniform(w);
+  const unsigned lds0 = lds_base(smem) + wu * 1024;
+  const bf16* Hrow = H16 + ((size_t)bh * Tn + i) * (D * D);   // stored [b][c] = H_i[c][b]
+  issue_tile_load<D>(dO + base, rows, lds0, S0, ldv);
+  issue_tile_load<D>(Os + base, rows, lds0, S1, ldv);
+  if (n_0 > 0) {
+    issue_tile_load<D>(Ol + base, rows, lds0, S2, ldv);
+    issue_tile_load<D>(Q + base, rows, lds0, S3, ldv);
+  }
+  wait_vm0();
+  __syncthreads();
+  TileAddr<D> qa;   // rows 32 qh + ln of a tile
+  qa.init(32 * qh, l);
   bf16x8 gf[KT];
 #pragma unroll
-  for (int t = 0; t < KT; ++t)
-    gf[t] = qok ? *reinterpret_cast<const bf16x8*>(dO + qoff + 16 * t + 8 * g) : zero_bf16x8();
+  for (int t = 0; t < KT; ++t) gf[t] = lds_row(smem, qa.row(t) + S0);
   // D^s = rowsum(dO * O^s)
   if (par == 0) {
     float ds = 0.0f;
-    if (qok) {
 #pragma unroll
-      for (int t = 0; t < KT; ++t) {
-        const bf16x8 o = *reinterpret_cast<const bf16x8*>(Os + qoff + 16 * t + 8 * g);
+    for (int t = 0; t < KT; ++t) {
+      const bf16x8 o = lds_row(smem, qa.row(t) + S1);
 #pragma unroll
-        for (int s = 0; s < 8; ++s) ds = fmaf((float)gf[t][s], (float)o[s], ds);
-      }
+      for (int s = 0; s < 8; ++s) ds = fmaf((float)gf[t][s], (float)o[s], ds);
     }
     ds = half_sum(ds);
     if (g == 0 && qok) Ds[(size_t)bh * N + q0 + qrow] = ds;
   }
   if (n_0 == 0) return;   // no linear branch: nothing else to do (uniform over the grid)
-  const bf16* Hrow = H16 + ((size_t)bh * Tn + i) * (D * D);
+  bf16x8 qf[KT];
+#pragma unroll
+  for (int t = 0; t < KT; ++t) qf[t] = lds_row(smem, qa.row(t) + S3);
   const float* Z = Zs + ((size_t)bh * Tn + i) * D;
+  __syncthreads();   // dO and O^s are consumed: their slots take dO^l and a
+  const int rowb = qrow * T::ROW_BYTES, rsw = swz<D>(qrow);
   // dO^l^T[b][q] = sum_e W[b][e] dO[q][e]; this wave: b-tiles par*HT .. par*HT+HT-1
-  f32x16 gl[HT];
   float dl = 0.0f;
 #pragma unroll
   for (int h2 = 0; h2 < HT; ++h2) {
     const int bt = par * HT + h2;
-    gl[h2] = zero_f32x16();
+    f32x16 gl = zero_f32x16();
 #pragma unroll
     for (int t = 0; t < KT; ++t) {
       const bf16x8 a = *reinterpret_cast<const bf16x8*>(W + (size_t)(32 * bt + ln) * D + 16 * t + 8 * g);
-      gl[h2] = mfma32(a, gf[t], gl[h2]);
+      gl = mfma32(a, gf[t], gl);
     }
 #pragma unroll
     for (int r4 = 0; r4 < 4; ++r4) {
       const int b0 = 32 * bt + 8 * r4 + 4 * g;
-      bf16x4 ol4;
-      if (qok) ol4 = *reinterpret_cast<const bf16x4*>(Ol + qoff + b0);
+      const int off = rowb + (((b0 >> 3) ^ rsw) << 4) + (b0 & 7) * 2;
+      const bf16x4 ol4 = *reinterpret_cast<const bf16x4*>(smem + S2 + off);
       bf16x4 pk;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const float v = gl[h2][4 * r4 + r];
+        const float v = gl[4 * r4 + r];
         pk[r] = (__bf16)v;
-        if (qok) dl = fmaf(v, (float)ol4[r], dl);
-        Gt[(b0 + r) * kVS + qrow] = __float2bfloat16(v);
+        dl = fmaf(v, (float)ol4[r], dl);
       }
-      *reinterpret_cast<bf16x4*>(Gs + qrow * D + (((b0 >> 3) ^ swz<D>(qrow)) << 3) + (b0 & 7)) = pk;
+      *reinterpret_cast<bf16x4*>(smem + S0 + off) = pk;
     }
   }
   dl = half_sum(dl);
   if (g == 0) dlp[par * kBlk + qrow] = dl;
-  // phi(Q), its normaliser, and a = phi(Q) / den transposed into LDS (this wave: half of the features)
-  bf16x8 qf[KT];
-#pragma unroll
-  for (int t = 0; t < KT; ++t)
-    qf[t] = qok ? *reinterpret_cast<const bf16x8*>(Q + qoff + 16 * t + 8 * g) : zero_bf16x8();
+  // phi(Q), its normaliser, and a = phi(Q) / den as a row-major tile (this wave: half of the features)
   float qmx, qinv;
   phi_stats<KT>(qf, phi, qmx, qinv);
   float den = 0.0f;
@@ -139,66 +136,81 @@ __global__ __launch_bounds__(256, 3) void bwd_pre_mfma_kernel(
 #pragma unroll
   for (int t = 0; t < KT; ++t) {
     if ((t >= KT / 2) != (par == 1)) continue;
+    bf16x8 av;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) At[(16 * t + 8 * g + s) * kVS + qrow] = __float2bfloat16(yq[t][s] * dinv);
+    for (int s = 0; s < 8; ++s) av[s] = (__bf16)(yq[t][s] * dinv);
+    *reinterpret_cast<bf16x8*>(smem + S1 + rowb + (((2 * t + g) ^ rsw) << 4)) = av;
   }
-  __syncthreads();
+  __syncthreads();   // dO^l and a are complete
   const float Dl = dlp[qrow] + dlp[kBlk + qrow];
   bf16* out = dHZ + ((size_t)bh * Tn + i) * (D * D + D);
   // dZ_i[c] = - sum_q a[q][c] D^l_q
   if (tid < D) {
     float z = 0.0f;
-    for (int q = 0; q < kBlk; ++q)
-      z = fmaf(__bfloat162float(At[tid * kVS + q]), dlp[q] + dlp[kBlk + q], z);
+    for (int q = 0; q < kBlk; ++q) {
+      const bf16 av = *reinterpret_cast<const bf16*>(smem + S1 + swz_chunk_off<D>(q, tid >> 3) + (tid & 7) * 2);
+      z = fmaf(__bfloat162float(av), dlp[q] + dlp[kBlk + q], z);
+    }
     out[(size_t)D * D + tid] = __float2bfloat16(-z);
   }
-  // dH_i^T[b][c] = sum_q dO^l[q][b] a[q][c]; wave w owns b-tile w.  The product is formed with b
+  // dH_i^T[b][c] = sum_q dO^l[q][b] a[q][c]: both operands contracted over tile rows; formed with b
   // along the lanes (C tile rows = c), so that a lane holds consecutive c of one stored row.
+  // Wave w owns b-tile w.
   static_assert(NT <= 4, "one b-tile per wave");
+  TileAddr<D> ad;
+  ad.init(0, l);
   f32x16 acc[NT];
 #pragma unroll
   for (int ct = 0; ct < NT; ++ct) acc[ct] = zero_f32x16();
   if (w < NT) {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(Gt + (32 * w + ln) * kVS + 16 * u + 8 * g);
+    for (int u = 0; u < kBlk / 16; ++u) {
+      const bf16x8 bo = lds_tr<D>(smem, ad.tr(0, w) + S0 + u * RB, ad.tr(1, w) + S0 + u * RB);
 #pragma unroll
       for (int ct = 0; ct < NT; ++ct) {
-        const bf16x8 b = *reinterpret_cast<const bf16x8*>(At + (32 * ct + ln) * kVS + 16 * u + 8 * g);
-        acc[ct] = mfma32(b, a, acc[ct]);
+        const bf16x8 ao = lds_tr<D>(smem, ad.tr(0, ct) + S1 + u * RB, ad.tr(1, ct) + S1 + u * RB);
+        acc[ct] = mfma32(ao, bo, acc[ct]);
       }
     }
   }
-  __syncthreads();   // the transposed tiles are free: they stage the output rows, then H_i
-  static_assert(4 * 32 * (64 * NT + 16) <= (Lds::GT_ELEMS + Lds::AT_ELEMS) * 2, "staging fits over the transposed tiles");
-  if (w < NT)
-    store_rows_bf16<NT>(reinterpret_cast<unsigned char*>(Gt) + w * (32 * (64 * NT + 16)), acc, out + (size_t)(32 * w) * D, D,
-                        32, l);
+  __syncthreads();   // a and O^l are consumed: their slots take H_i
+  issue_tile_load<D>(Hrow, min(kBlk, D), lds0, S1, ldv);
+  if (D > kBlk) issue_tile_load<D>(Hrow + (size_t)kBlk * D, D - kBlk, lds0, S2, ldv);
+  wait_vm0();
   __syncthreads();
-  stage_matrix_t<D>(Hrow, Hs, RS);
-  __syncthreads();
-  // dQ^phi^T[c][q] = (sum_b H[c][b] dO^l[q][b] - D^l_q Z[c]) / den_q; this wave: c-tiles of par
+  // dQ^phi^T[c][q] = (sum_b H[c][b] dO^l[q][b] - D^l_q Z[c]) / den_q; this wave: c-tiles of par.  H^T is
+  // read with the transposing read, whose k order is the one a C tile hands over, so dO^l is picked
+  // up in that order too (two 8-byte pieces per k-step: features 16 t + 4 g .. and 16 t + 8 + 4 g ..)
   f32x16 dq[HT];
   float dot = 0.0f;
   float yc[HT][16];
 #pragma unroll
+  for (int h2 = 0; h2 < HT; ++h2) dq[h2] = zero_f32x16();
+#pragma unroll
+  for (int t = 0; t < KT; ++t) {
+    const bf16x4 v0 = *reinterpret_cast<const bf16x4*>(smem + S0 + rowb + (((2 * t) ^ rsw) << 4) + 8 * g);
+    const bf16x4 v1 = *reinterpret_cast<const bf16x4*>(smem + S0 + rowb + (((2 * t + 1) ^ rsw) << 4) + 8 * g);
+    bf16x8 gb;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      gb[e] = v0[e];
+      gb[4 + e] = v1[e];
+    }
+    const int mbase = (t / 4 ? S2 : S1) + (t % 4) * RB;   // rows b = 16 t .. of the stored matrix
+#pragma unroll
+    for (int h2 = 0; h2 < HT; ++h2) {
+      const int ct = par * HT + h2;
+      dq[h2] = mfma32(lds_tr<D>(smem, ad.tr(0, ct) + mbase, ad.tr(1, ct) + mbase), gb, dq[h2]);
+    }
+  }
+#pragma unroll
   for (int h2 = 0; h2 < HT; ++h2) {
     const int ct = par * HT + h2;
-    dq[h2] = zero_f32x16();
-#pragma unroll
-    for (int t = 0; t < KT; ++t) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(Hs + (32 * ct + ln) * RS + 16 * t + 8 * g);
-      const bf16x8 b = *reinterpret_cast<const bf16x8*>(Gs + qrow * D + (((2 * t + g) ^ swz<D>(qrow)) << 3));
-      dq[h2] = mfma32(a, b, dq[h2]);
-    }
 #pragma unroll
     for (int r4 = 0; r4 < 4; ++r4) {
       const int c0 = 32 * ct + 8 * r4 + 4 * g;
       const f32x4 z4 = *reinterpret_cast<const f32x4*>(Z + c0);
-      bf16x4 q4;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) q4[r] = (__bf16)0.0f;
-      if (qok) q4 = *reinterpret_cast<const bf16x4*>(Q + qoff + c0);
+      const bf16x4 q4 = *reinterpret_cast<const bf16x4*>(smem + S3 + rowb + (((c0 >> 3) ^ rsw) << 4) + (c0 & 7) * 2);
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const float v = (dq[h2][4 * r4 + r] - Dl * z4[r]) * dinv;
@@ -212,21 +224,15 @@ __global__ __launch_bounds__(256, 3) void bwd_pre_mfma_kernel(
   }
   dot = half_sum(dot);
   if (g == 0) dotp[par * kBlk + qrow] = dot;
-  __syncthreads();
+  __syncthreads();   // also: every wave is done with the tiles, slots 1..3 become the output staging
   const float dtot = phi == 0 ? dotp[qrow] + dotp[kBlk + qrow] : 0.0f;
-  if (qok) {
+  unsigned char* stage = smem + S1 + wu * Lds::STG;
+  if (w < NT) store_rows_bf16<NT>(stage, acc, out + (size_t)(32 * w) * D, D, 32, l);
 #pragma unroll
-    for (int h2 = 0; h2 < HT; ++h2) {
-      const int ct = par * HT + h2;
+  for (int h2 = 0; h2 < HT; ++h2)
 #pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        f32x4 o4;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) o4[r] = yc[h2][4 * r4 + r] * (dq[h2][4 * r4 + r] - dtot);
-        *reinterpret_cast<f32x4*>(dQlin + qoff + 32 * ct + 8 * r4 + 4 * g) = o4;
-      }
-    }
-  }
+    for (int r = 0; r < 16; ++r) dq[h2][r] = yc[h2][r] * (dq[h2][r] - dtot);
+  store_rows_f32<HT>(stage, dq, dQlin + base + (size_t)(32 * qh) * D + par * (D / 2), D, rows - 32 * qh, l);
 }
 
 // ------------------------------------------------------------------ dW partial sums

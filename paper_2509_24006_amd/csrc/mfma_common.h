@@ -405,6 +405,26 @@ __device__ __forceinline__ void store_rows_bf16(unsigned char* stage, const f32x
   }
 }
 
+// The float counterpart of store_rows_bf16: `stage` needs 32 * (128 NT + 16) bytes.
+template <int NT>
+__device__ __forceinline__ void store_rows_f32(unsigned char* stage, const f32x16 (&c)[NT], float* dst,
+                                               int row_stride, int rows_valid, int l) {
+  constexpr int PB = 128 * NT + 16, PPR = 8 * NT;
+  const int g = l >> 5, ln = l & 31;
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4)
+      *reinterpret_cast<f32x4*>(stage + ln * PB + (32 * t + 8 * r4 + 4 * g) * 4) =
+          f32x4{c[t][4 * r4], c[t][4 * r4 + 1], c[t][4 * r4 + 2], c[t][4 * r4 + 3]};
+#pragma unroll
+  for (int it = 0; it < 32 * PPR / 64; ++it) {
+    const int idx = it * 64 + l, row = idx / PPR, pc = idx % PPR;
+    const u32x4 v = *reinterpret_cast<const u32x4*>(stage + row * PB + pc * 16);
+    if (row < rows_valid) *reinterpret_cast<u32x4*>(dst + (size_t)row * row_stride + pc * 4) = v;
+  }
+}
+
 // Workgroups are dealt to the 8 XCDs (each with its own L2) round-robin by linear index.  With a
 // grid of 8 * ceil(T / 8) workgroups per head, XCD x gets the contiguous blocks
 // [x ceil(T/8), (x+1) ceil(T/8)) in ascending order, so that neighbouring query blocks -- which
