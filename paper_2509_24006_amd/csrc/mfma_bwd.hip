@@ -35,16 +35,17 @@ struct PairLds {
 // Wave (kh, qh): keys 32 kh .., queries 32 qh .. of the pair.  S and dP are [query][key] so
 // that each lane owns one key; P and dS feed the second products from registers.  The two qh
 // waves hold partial sums over their queries and are added at the end.
-template <int D>
+template <int D, int PHI>
 __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
     const bf16* __restrict__ dO, const float* __restrict__ L, const float* __restrict__ Ds,
     const int32_t* __restrict__ col_ptr, const int32_t* __restrict__ col_rows,
     const int32_t* __restrict__ col_order, const bf16* __restrict__ dHcol,
-    const float* __restrict__ dZcol, int phi, int N, int Tn, int n_h, float scale,
+    const float* __restrict__ dZcol, int N, int Tn, int n_h, float scale,
     bf16* __restrict__ dK, bf16* __restrict__ dV) {
   using Lds = PairLds<D>;
   constexpr int NT = D / 32, KT = D / 16;
+  constexpr int phi = PHI;   // feature map: 0 softmax over the features, 1 elu + 1
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   float* stats = reinterpret_cast<float*>(smem + Lds::TILES);   // [buf][2][64]
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
@@ -542,15 +543,16 @@ hipError_t sparse_impl(const Shape& s, const BwdArgs& a, const float* Ds, const 
                        const void* dHZcol, hipStream_t st) {
   const float* dZcol = dHZcol ? reinterpret_cast<const float*>((const char*)dHZcol + state_z_offset(s)) : nullptr;
   constexpr int lds = PairLds<D>::BYTES;
-  SLA_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dkdv_mfma_kernel<D>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, PairLds<D>::DKDV));
-  {
+  auto launch_kv = [&](auto kern) -> hipError_t {
+    SLA_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                PairLds<D>::DKDV));
     KernelTimer kt("bwd_sparse_kv", st);
-    bwd_dkdv_mfma_kernel<D><<<dim3(s.T * s.BH), 256, PairLds<D>::DKDV, st>>>(
-        (const bf16*)a.Q, (const bf16*)a.K, (const bf16*)a.V, (const bf16*)a.dO, a.L, Ds, a.col_ptr,
-        a.col_rows, a.col_order, (const bf16*)dHZcol, dZcol, s.phi, s.N, s.T, s.n_h, s.scale, (bf16*)a.dK,
-        (bf16*)a.dV);
-  }
+    kern<<<dim3(s.T * s.BH), 256, PairLds<D>::DKDV, st>>>(
+        (const bf16*)a.Q, (const bf16*)a.K, (const bf16*)a.V, (const bf16*)a.dO, a.L, Ds, a.col_ptr, a.col_rows,
+        a.col_order, (const bf16*)dHZcol, dZcol, s.N, s.T, s.n_h, s.scale, (bf16*)a.dK, (bf16*)a.dV);
+    return hipSuccess;
+  };
+  SLA_TRY(s.phi == 0 ? launch_kv(bwd_dkdv_mfma_kernel<D, 0>) : launch_kv(bwd_dkdv_mfma_kernel<D, 1>));
   SLA_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dq_mfma_kernel<D>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, lds));
   {
