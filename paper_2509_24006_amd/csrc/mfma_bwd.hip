@@ -32,9 +32,27 @@ struct PairLds {
 };
 
 // ------------------------------------------------------------------ dK, dV
-// Wave (kh, qh): keys 32 kh .., queries 32 qh .. of the pair.  S and dP are [query][key] so
-// that each lane owns one key; P and dS feed the second products from registers.  The two qh
-// waves hold partial sums over their queries and are added at the end.
+// First products (S, dP): wave (kh, x) takes keys 32 kh .., queries 32 x .. of the pair; S and dP
+// are [query][key], one key per lane.  Second products (dV^T = dO^T P, dK^T = Q^T dS): the same wave
+// takes keys 32 kh .. and the feature half x, over all 64 queries.  P and dS therefore cross
+// between the two waves of a key half, through LDS in operand layout (16 bytes per lane and
+// k-step).  Each wave owns its quarter of dK_j, dV_j outright: 64 accumulator registers at d = 128
+// instead of 128 for per-query-half partial sums, which is what leaves room to run the LDS reads
+// several operands ahead of the products, and no summation at the end.
+// L_q and D^s_q enter the first products as one more k-step: the A operand carries (L_q / scale)
+// resp. D^s_q split into two bf16 terms, the B operand -1, so that the accumulators come out as
+// S - L / scale and dP - D^s (error of the split: 2^-17 relative).  No per-step table in LDS, and
+// P = exp2(c (S - L / scale)), dS = P (dP - D^s) cost one multiplication each.
+template <int D>
+struct KvLds {
+  static constexpr int TILE = SwzTile<D>::BYTES;
+  static constexpr int BUF = 2 * TILE;                   // Q_i and dO_i of a pair
+  static constexpr int XOFF = 2 * BUF;                   // exchange: [kh][k-step 0..3][P | dS][lane] x 16 bytes
+  static constexpr int XBYTES = 2 * 4 * 2 * 64 * 16;
+  static constexpr int BYTES = XOFF + XBYTES;            // 80 KB at d = 128: half a CU
+  static constexpr int STG = 32 * (64 * (D / 64) + 16);  // output staging of one wave, laid over the tiles
+};
+
 template <int D, int PHI>
 __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
@@ -43,13 +61,14 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
     const int32_t* __restrict__ col_order, const bf16* __restrict__ dHcol,
     const float* __restrict__ dZcol, int N, int Tn, int n_h, float scale,
     bf16* __restrict__ dK, bf16* __restrict__ dV) {
-  using Lds = PairLds<D>;
-  constexpr int NT = D / 32, KT = D / 16;
+  using Lds = KvLds<D>;
+  using T = SwzTile<D>;
+  constexpr int NT = D / 32, KT = D / 16, HT = NT / 2;
+  constexpr int RB = 16 * T::ROW_BYTES;
   constexpr int phi = PHI;   // feature map: 0 softmax over the features, 1 elu + 1
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  float* stats = reinterpret_cast<float*>(smem + Lds::TILES);   // [buf][2][64]
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
-  const int kh = w & 1, qh = w >> 1;
+  const int kh = w & 1, xh = w >> 1;
   // longest column lists first, across all heads: the r-th heaviest key block of every head
   // precedes the (r+1)-th of any head, so the tail of the launch is made of short lists
   // (grouping an XCD's workgroups by head for L2 reuse was measured slower than this order)
@@ -59,38 +78,27 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
   const int k0 = j * kBlk, cols = min(kBlk, N - k0);
   const int krow = kh * 32 + ln;
   const bool kok = krow < cols;
-  // At d = 128 the accumulators and both key-side operands do not fit the register budget of
-  // two workgroups per CU.  Three quarters of the V operand are parked in LDS (each kh half once,
-  // in operand layout: 16 bytes per lane and k-step) and re-read every step.
-  constexpr int VL = D >= 128 ? 3 * KT / 4 : 0, VR = KT - VL;
-  const int vpark = Lds::BYTES + (kh * VL * 64 + l) * 16;
-  bf16x8 kf[KT], vf[VR > 0 ? VR : 1];
-  f32x16 dvT[NT], dkT[NT];
+  bf16x8 kf[KT], vf[KT];
+  f32x16 dvT[HT], dkT[HT];
 #pragma unroll
-  for (int t = 0; t < NT; ++t) {
+  for (int t = 0; t < HT; ++t) {
     dvT[t] = zero_f32x16();
     dkT[t] = zero_f32x16();
   }
   const int32_t* ptr = col_ptr + (size_t)bh * (Tn + 1);
   const int32_t* list = col_rows + (size_t)bh * Tn * n_h;
   const int beg = ptr[j], cnt = ptr[j + 1] - beg;
-  const float sl2 = scale * kLog2e;
+  const float sl2 = scale * kLog2e, rscale = 1.0f / scale;
   const bf16* Qb = Q + (size_t)bh * N * D;
   const bf16* dOb = dO + (size_t)bh * N * D;
   const float* Lb = L + (size_t)bh * N;
   const float* Dsb = Ds + (size_t)bh * N;
-  float streg = 0.0f;
-  // per-lane addresses, fixed for the whole kernel
-  using T = SwzTile<D>;
-  TileAddr<D> ad;
-  ad.init(32 * qh, l);
-  // load k of a tile fetches, for this lane, the chunk 4096 k bytes after that of load 0 (the
-  // swizzle has period 16 rows), so one per-lane offset serves all of them
   const int ldv = tile_lane_offset<D>(w, l);
   const int wu = wave_uniform(w);
   const unsigned lds0 = lds_base(smem) + wu * 1024;
-  // (issue and step are inlined at call sites with a literal buffer index, which turns every
-  // LDS offset below into register + constant)
+  // L and D^s of the query (32 x + l % 32) of the pair whose tiles are in flight.  Rows past the
+  // end read as 0; their Q and dO rows are zero too, so the finite P they get adds nothing.
+  float lreg = 0.0f, dreg = 0.0f;
   // the row index of a step is fetched two steps ahead, so the tile loads never wait for it
   int inext = cnt > 0 ? list[beg] : 0;
   auto issue = [&](int s, const int bufi) __attribute__((always_inline)) {
@@ -98,137 +106,50 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
     const int ii = inext;
     inext = list[beg + min(s + 1, cnt - 1)];
     const int rows = min(kBlk, N - ii * kBlk);
-    const BufDesc rq = tile_rsrc(Qb + (size_t)ii * kBlk * D, rows * T::ROW_BYTES);
-    const BufDesc rg = tile_rsrc(dOb + (size_t)ii * kBlk * D, rows * T::ROW_BYTES);
-#pragma unroll
-    for (int k = 0; k < T::IPW; ++k) {
-      load_to_lds16(rq, ldv, 4096 * k, lds0 + off + 4096 * k);
-      load_to_lds16(rg, ldv, 4096 * k, lds0 + off + Lds::TILE + 4096 * k);
-    }
-    // per-query statistics: wave 0 fetches L, wave 1 D^s.  Rows past the end read as 0; their Q
-    // and dO rows are zero too, so whatever finite P they get adds nothing to dK and dV.
-    if (wu < 2) streg = load_f32_or_zero((wu == 0 ? Lb : Dsb) + (size_t)ii * kBlk, rows, lane_id());
-  };
-  auto step = [&](int s, const int buf) __attribute__((always_inline)) {
-    const int QO = buf * Lds::BUF, GO = QO + Lds::TILE;
-    ad.refresh();
-    wait_vm0();
-    __syncthreads();   // tiles of step s have landed for every wave; step s-1 is fully consumed
-    if (s + 1 < cnt) issue(s + 1, buf ^ 1);
-    const float* Ls = stats + buf * 2 * kBlk;
-    const float* Dq = Ls + kBlk;
-    // LDS reads run PF operand sets ahead of the products that consume them (software pipeline
-    // written out by hand: left alone, the compiler reads each operand right before its product
-    // and every product then waits a full LDS latency).
-    constexpr int PF = 2;
-    constexpr int RB = 16 * T::ROW_BYTES;
-    bf16x8 qa[PF], ga[PF], pa[PF];
-    auto read_s = [&](int t) __attribute__((always_inline)) {
-      qa[t % PF] = lds_row(smem, ad.row(t) + QO);
-      ga[t % PF] = lds_row(smem, ad.row(t) + GO);
-      if (t >= VR) pa[t % PF] = lds_row(smem, vpark + (t - VR) * 1024);
-    };
-    // operand i of the second pair of products: i = 2 NT u + 2 et + which; which 0: dO^T rows of
-    // feature tile et (for dV), which 1: Q^T (for dK); k = pair rows 32 qh + 16 u ..
-    constexpr int PT = D >= 128 ? 2 : 4;   // what the register budget allows
-    bf16x8 ta[PT];
-    auto read_t = [&](int i) __attribute__((always_inline)) {
-      const int u = i / (2 * NT), et = (i % (2 * NT)) / 2, base = (i % 2 ? QO : GO) + u * RB;
-      ta[i % PT] = lds_tr<D>(smem, ad.tr(0, et) + base, ad.tr(1, et) + base);
-    };
-#pragma unroll
-    for (int t = 0; t < PF; ++t) read_s(t);
-    sched_fence();
-    f32x16 sm = zero_f32x16(), dp = zero_f32x16();
-#pragma unroll
-    for (int t = 0; t < KT; ++t) {
-      sm = mfma32(qa[t % PF], kf[t], sm);
-      dp = mfma32(ga[t % PF], t < VR ? vf[t] : pa[t % PF], dp);
-      if (t + PF < KT) read_s(t + PF);
-      sched_fence();
-    }
-    // the first transposed operands arrive under the softmax arithmetic
-#pragma unroll
-    for (int i = 0; i < PT; ++i) read_t(i);
-    sched_fence();
-    // P[q][key] = exp(S - L_q), dS = P (dP - D^s_q); rows q = 32 qh + c_row(r, g).  A lane past the
-    // end of the key block (its K and V rows are zero) computes finite values that stay in its own
-    // columns of dK^T and dV^T, which are never stored.
-#pragma unroll
-    for (int r4 = 0; r4 < 4; ++r4) {
-      const f32x4 lq = *reinterpret_cast<const f32x4*>(Ls + 32 * qh + 8 * r4 + 4 * g);
-      const f32x4 dq = *reinterpret_cast<const f32x4*>(Dq + 32 * qh + 8 * r4 + 4 * g);
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float pv = fast_exp2(fmaf(sm[4 * r4 + r], sl2, -lq[r]));
-        sm[4 * r4 + r] = pv;
-        dp[4 * r4 + r] = pv * (dp[4 * r4 + r] - dq[r]);
-      }
-    }
-    sched_fence();
-    bf16x8 pb, sb;
-#pragma unroll
-    for (int i = 0; i < 4 * NT; ++i) {
-      const int u = i / (2 * NT), et = (i % (2 * NT)) / 2;
-      if (i % (2 * NT) == 0) {
-        pb = c_to_operand(sm, u);
-        sb = c_to_operand(dp, u);
-      }
-      if (i % 2 == 0) dvT[et] = mfma32(ta[i % PT], pb, dvT[et]);   // dO_i^T P
-      else dkT[et] = mfma32(ta[i % PT], sb, dkT[et]);              // Q_i^T dS
-      if (i + PT < 4 * NT) read_t(i + PT);
-      sched_fence();
-    }
-    if (s + 1 < cnt && wu < 2) stats[(buf ^ 1) * 2 * kBlk + wu * kBlk + lane_id()] = wu == 0 ? streg * kLog2e : streg;
+    issue_tile_load<D>(Qb + (size_t)ii * kBlk * D, rows, lds0, off, ldv);
+    issue_tile_load<D>(dOb + (size_t)ii * kBlk * D, rows, lds0, off + Lds::TILE, ldv);
+    const int qq = 32 * xh + (lane_id() & 31);
+    lreg = load_f32_or_zero(Lb + (size_t)ii * kBlk, rows, qq);
+    dreg = load_f32_or_zero(Dsb + (size_t)ii * kBlk, rows, qq);
   };
   // K_j and V_j come in as tiles through the second pair buffer (whole rows per load, zeros past
   // the end of the sequence) and are picked up from there in operand layout.  With a linear
   // branch, the aggregated dH^T of this key block (d x d, stored [b][a]) comes in through the
   // first pair buffer: rows 0..63 in the Q slot, the rest in the dO slot.
-  {
-    const BufDesc rk = tile_rsrc(K + ((size_t)bh * N + k0) * D, cols * T::ROW_BYTES);
-    const BufDesc rv = tile_rsrc(V + ((size_t)bh * N + k0) * D, cols * T::ROW_BYTES);
-#pragma unroll
-    for (int k = 0; k < T::IPW; ++k) {
-      load_to_lds16(rk, ldv, 4096 * k, lds0 + Lds::BUF + 4096 * k);
-      load_to_lds16(rv, ldv, 4096 * k, lds0 + Lds::BUF + Lds::TILE + 4096 * k);
-    }
-  }
+  issue_tile_load<D>(K + ((size_t)bh * N + k0) * D, cols, lds0, Lds::BUF, ldv);
+  issue_tile_load<D>(V + ((size_t)bh * N + k0) * D, cols, lds0, Lds::BUF + Lds::TILE, ldv);
   if (dHcol) {
     const bf16* M = dHcol + ((size_t)bh * Tn + j) * (D * D);
-#pragma unroll
-    for (int h = 0; h < (D + kBlk - 1) / kBlk; ++h) {
-      const BufDesc rm = tile_rsrc(M + (size_t)h * kBlk * D, min(kBlk, D - h * kBlk) * T::ROW_BYTES);
-#pragma unroll
-      for (int k = 0; k < T::IPW; ++k) load_to_lds16(rm, ldv, 4096 * k, lds0 + h * Lds::TILE + 4096 * k);
-    }
+    issue_tile_load<D>(M, min(kBlk, D), lds0, 0, ldv);
+    if (D > kBlk) issue_tile_load<D>(M + (size_t)kBlk * D, D - kBlk, lds0, Lds::TILE, ldv);
   } else if (cnt > 0) {
     issue(0, 0);
   }
   wait_vm0();
   __syncthreads();
-  TileAddr<D> ka;
-  ka.init(32 * kh, l);
+  {
+    TileAddr<D> ka;
+    ka.init(32 * kh, l);
 #pragma unroll
-  for (int t = 0; t < KT; ++t) {
-    kf[t] = lds_row(smem, ka.row(t) + Lds::BUF);
-    const bf16x8 v = lds_row(smem, ka.row(t) + Lds::BUF + Lds::TILE);
-    if (t < VR) vf[t] = v;
-    else if (qh == 0) *reinterpret_cast<bf16x8*>(smem + vpark + (t - VR) * 1024) = v;
+    for (int t = 0; t < KT; ++t) {
+      kf[t] = lds_row(smem, ka.row(t) + Lds::BUF);
+      vf[t] = lds_row(smem, ka.row(t) + Lds::BUF + Lds::TILE);
+    }
   }
 #pragma unroll
   for (int t = 0; t < KT; ++t) {
     pin_loaded(kf[t]);
-    if (t < VR) pin_loaded(vf[t]);
+    pin_loaded(vf[t]);
   }
   if (dHcol) {
     // ---- linear branch of Alg. 2 for key block j, as the start value of the accumulators:
-    // the qh = 0 waves take dV += phi(K_j) dH_j, the qh = 1 waves dK += d phi(K_j) / d K_j applied to
-    // (V_j dH_j^T + dZ_j); each pair of waves adds its halves up at the end anyway.
-    constexpr int RB = 16 * T::ROW_BYTES;
+    // dV += phi(K_j) dH_j and dK += d phi(K_j) / d K_j applied to (V_j dH_j^T + dZ_j), this wave's
+    // feature half of each.
     float kmx, kinv;
     phi_stats<KT>(kf, phi, kmx, kinv);
-    if (wu < 2) {
+    TileAddr<D> ma;
+    ma.init(0, l);
+    {
       // dV^T[b][n] = sum_a M[b][a] phi(K)[n][a]: rows b of M are the A operand
       bf16x8 kp[KT];
 #pragma unroll
@@ -236,134 +157,184 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
 #pragma unroll
         for (int s2 = 0; s2 < 8; ++s2)
           kp[t][s2] = (__bf16)(kok ? phi_val((float)kf[t][s2], phi, kmx, kinv) : 0.0f);
-      TileAddr<D> ma;
-      ma.init(0, l);
 #pragma unroll
-      for (int bt = 0; bt < NT; ++bt)
+      for (int dt = 0; dt < HT; ++dt) {
+        const int bt = xh * HT + dt;
 #pragma unroll
         for (int t = 0; t < KT; ++t)
-          dvT[bt] = mfma32(lds_row(smem, ma.row(t) + (bt / 2) * Lds::TILE + (bt % 2) * 2 * RB), kp[t], dvT[bt]);
-    } else {
-      // d phi(K)^T[a][n] = sum_b M[b][a] V[n][b] + dZ[a]: M^T through the transposing read, whose
-      // k order is the one a C tile hands over, so V is picked up in that order too (two 8-byte
-      // pieces per k-step: features 16 t + 4 g .. and 16 t + 8 + 4 g ..)
-      TileAddr<D> ma;
-      ma.init(0, l);
-      const int vrow = Lds::BUF + Lds::TILE + krow * T::ROW_BYTES + 8 * g;
-      const int krw = Lds::BUF + krow * T::ROW_BYTES + 8 * g;
-      const int ksw = swz<D>(krow);
-#pragma unroll
-      for (int t = 0; t < KT; ++t) {
-        const bf16x4 v0 = *reinterpret_cast<const bf16x4*>(smem + vrow + (((2 * t) ^ ksw) << 4));
-        const bf16x4 v1 = *reinterpret_cast<const bf16x4*>(smem + vrow + (((2 * t + 1) ^ ksw) << 4));
-        bf16x8 vb;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          vb[e] = v0[e];
-          vb[4 + e] = v1[e];
-        }
-        const int base = (t / 4) * Lds::TILE + (t % 4) * RB;   // rows b = 16 t .. of M
-#pragma unroll
-        for (int at = 0; at < NT; ++at)
-          dkT[at] = mfma32(lds_tr<D>(smem, ma.tr(0, at) + base, ma.tr(1, at) + base), vb, dkT[at]);
+          dvT[dt] = mfma32(lds_row(smem, ma.row(t) + (bt / 2) * Lds::TILE + (bt % 2) * 2 * RB), kp[t], dvT[dt]);
       }
-      const float* dZ = dZcol + ((size_t)bh * Tn + j) * D;
-      float dot = 0.0f;
-#pragma unroll
-      for (int at = 0; at < NT; ++at)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          const f32x4 z4 = *reinterpret_cast<const f32x4*>(dZ + 32 * at + 8 * r4 + 4 * g);
-          const bf16x4 k4 = *reinterpret_cast<const bf16x4*>(smem + krw + (((4 * at + r4) ^ ksw) << 4));
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const float x = (float)k4[r];
-            const float y = phi == 0 ? phi_val(x, 0, kmx, kinv) : (x > 0.0f ? 1.0f : fast_exp2(x * kLog2e));
-            const float v = dkT[at][4 * r4 + r] + z4[r];
-            dkT[at][4 * r4 + r] = v;
-            dot = fmaf(v, y, dot);
-          }
-        }
-      dot = half_sum(dot);
-      const float dtot = phi == 0 ? dot : 0.0f;
-      const float rs = 1.0f / scale;   // the epilogue multiplies the whole dK sum by scale
-#pragma unroll
-      for (int at = 0; at < NT; ++at)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          const bf16x4 k4 = *reinterpret_cast<const bf16x4*>(smem + krw + (((4 * at + r4) ^ ksw) << 4));
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const float x = (float)k4[r];
-            const float y = phi == 0 ? phi_val(x, 0, kmx, kinv) : (x > 0.0f ? 1.0f : fast_exp2(x * kLog2e));
-            dkT[at][4 * r4 + r] = kok ? y * (dkT[at][4 * r4 + r] - dtot) * rs : 0.0f;
-          }
-        }
     }
-    __syncthreads();   // both pair buffers are free again
+    // d phi(K)^T[a][n] = sum_b M[b][a] V[n][b] + dZ[a]: M^T through the transposing read, whose
+    // k order is the one a C tile hands over, so V is picked up in that order too (two 8-byte
+    // pieces per k-step: features 16 t + 4 g .. and 16 t + 8 + 4 g ..)
+    const int vrow = Lds::BUF + Lds::TILE + krow * T::ROW_BYTES + 8 * g;
+    const int krw = Lds::BUF + krow * T::ROW_BYTES + 8 * g;
+    const int ksw = swz<D>(krow);
+#pragma unroll
+    for (int t = 0; t < KT; ++t) {
+      const bf16x4 v0 = *reinterpret_cast<const bf16x4*>(smem + vrow + (((2 * t) ^ ksw) << 4));
+      const bf16x4 v1 = *reinterpret_cast<const bf16x4*>(smem + vrow + (((2 * t + 1) ^ ksw) << 4));
+      bf16x8 vb;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        vb[e] = v0[e];
+        vb[4 + e] = v1[e];
+      }
+      const int mb = (t / 4) * Lds::TILE + (t % 4) * RB;   // rows b = 16 t .. of M
+#pragma unroll
+      for (int dt = 0; dt < HT; ++dt) {
+        const int at = xh * HT + dt;
+        dkT[dt] = mfma32(lds_tr<D>(smem, ma.tr(0, at) + mb, ma.tr(1, at) + mb), vb, dkT[dt]);
+      }
+    }
+    const float* dZ = dZcol + ((size_t)bh * Tn + j) * D;
+    float dot = 0.0f;
+#pragma unroll
+    for (int dt = 0; dt < HT; ++dt)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int a0 = 32 * (xh * HT + dt) + 8 * r4 + 4 * g;
+        const f32x4 z4 = *reinterpret_cast<const f32x4*>(dZ + a0);
+        const bf16x4 k4 = *reinterpret_cast<const bf16x4*>(smem + krw + (((a0 >> 3) ^ ksw) << 4));
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float x = (float)k4[r];
+          const float y = phi == 0 ? phi_val(x, 0, kmx, kinv) : (x > 0.0f ? 1.0f : fast_exp2(x * kLog2e));
+          const float v = dkT[dt][4 * r4 + r] + z4[r];
+          dkT[dt][4 * r4 + r] = v;
+          dot = fmaf(v, y, dot);
+        }
+      }
+    dot = half_sum(dot);
+    float* dotx = reinterpret_cast<float*>(smem + Lds::XOFF);   // [x][64 keys]
+    if (g == 0) dotx[xh * kBlk + krow] = dot;
+    __syncthreads();   // also: dH^T is consumed, the first pair buffer is free
     if (cnt > 0) issue(0, 0);
+    const float dtot = phi == 0 ? dotx[krow] + dotx[kBlk + krow] : 0.0f;
+#pragma unroll
+    for (int dt = 0; dt < HT; ++dt)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int a0 = 32 * (xh * HT + dt) + 8 * r4 + 4 * g;
+        const bf16x4 k4 = *reinterpret_cast<const bf16x4*>(smem + krw + (((a0 >> 3) ^ ksw) << 4));
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float x = (float)k4[r];
+          const float y = phi == 0 ? phi_val(x, 0, kmx, kinv) : (x > 0.0f ? 1.0f : fast_exp2(x * kLog2e));
+          // the epilogue multiplies the whole dK sum by scale
+          dkT[dt][4 * r4 + r] = kok ? y * (dkT[dt][4 * r4 + r] - dtot) * rscale : 0.0f;
+        }
+      }
+    __syncthreads();   // the sums above are read before the first step writes the exchange area
   }
-  if (cnt > 0 && wu < 2) stats[wu * kBlk + lane_id()] = wu == 0 ? streg * kLog2e : streg;
-  // (the first step's barrier orders the reads above before the loads that reuse the buffers)
+  // (the first step's barrier orders the reads above before the loads that reuse the second buffer)
+  TileAddr<D> ad;   // first products: rows 32 x .. of Q_i, dO_i by rows
+  ad.init(32 * xh, l);
+  TileAddr<D> at;   // second products: transposing reads, feature tiles x HT ..
+  at.init(0, l);
+  // B operand of the extra k-step: -1 at k = 0, 1
+  bf16x8 bneg;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) bneg[e] = (__bf16)((g == 0 && e < 2) ? -1.0f : 0.0f);
+  const int xw = Lds::XOFF + ((kh * 4 + 2 * xh) * 2 * 64 + l) * 16;   // this wave's exchange writes
+  const int xr = Lds::XOFF + (kh * 4 * 2 * 64 + l) * 16;              // ... and reads
+  auto step = [&](int s, const int buf) __attribute__((always_inline)) {
+    const int QO = buf * Lds::BUF, GO = QO + Lds::TILE;
+    ad.refresh();
+    at.refresh();
+    wait_vm0();
+    __syncthreads();   // tiles of step s have landed for every wave; step s-1 is fully consumed
+    const float lcur = lreg * rscale, dcur = dreg;
+    if (s + 1 < cnt) issue(s + 1, buf ^ 1);
+    // A operands of the extra k-step: (hi, lo) at k = 0, 1 of the lanes with g = 0
+    bf16x8 aL = zero_bf16x8(), aD = zero_bf16x8();
+    {
+      const __bf16 lh = (__bf16)lcur, dh = (__bf16)dcur;
+      const __bf16 ll = (__bf16)(lcur - (float)lh), dl = (__bf16)(dcur - (float)dh);
+      aL[0] = g == 0 ? lh : (__bf16)0.0f;
+      aL[1] = g == 0 ? ll : (__bf16)0.0f;
+      aD[0] = g == 0 ? dh : (__bf16)0.0f;
+      aD[1] = g == 0 ? dl : (__bf16)0.0f;
+    }
+    // LDS reads run PF operand pairs ahead of the products that consume them (software pipeline
+    // written out by hand: left alone, the compiler reads each operand right before its product
+    // and every product then waits a full LDS latency).
+    constexpr int PF = 4;
+    bf16x8 qa[PF], ga[PF];
+    auto read_s = [&](int t) __attribute__((always_inline)) {
+      qa[t % PF] = lds_row(smem, ad.row(t) + QO);
+      ga[t % PF] = lds_row(smem, ad.row(t) + GO);
+    };
+#pragma unroll
+    for (int t = 0; t < PF; ++t) read_s(t);
+    sched_fence();
+    f32x16 sm = mfma32(aL, bneg, zero_f32x16()), dp = mfma32(aD, bneg, zero_f32x16());
+#pragma unroll
+    for (int t = 0; t < KT; ++t) {
+      sm = mfma32(qa[t % PF], kf[t], sm);
+      dp = mfma32(ga[t % PF], vf[t], dp);
+      if (t + PF < KT) read_s(t + PF);
+      sched_fence();
+    }
+    // operand i of the second products: i = 2 HT ks + 2 dt + which; which 0: dO^T rows of feature
+    // tile x HT + dt (for dV), which 1: Q^T (for dK); k = pair rows 16 ks ..
+    constexpr int PT = 6, NOP = 8 * HT;
+    bf16x8 ta[PT];
+    auto read_t = [&](int i) __attribute__((always_inline)) {
+      const int ks = i / (2 * HT), et = xh * HT + (i % (2 * HT)) / 2, base = (i % 2 ? QO : GO) + ks * RB;
+      ta[i % PT] = lds_tr<D>(smem, at.tr(0, et) + base, at.tr(1, et) + base);
+    };
+    // the first transposed operands arrive under the softmax arithmetic
+#pragma unroll
+    for (int i = 0; i < PT; ++i) read_t(i);
+    sched_fence();
+    // P[q][key] = exp(S - L_q), dS = P (dP - D^s_q).  A lane past the end of the key block (its K
+    // and V rows are zero) computes finite values that stay in its own columns of dK^T and dV^T,
+    // which are never stored.
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float pv = fast_exp2(sm[r] * sl2);
+      sm[r] = pv;
+      dp[r] *= pv;
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      *reinterpret_cast<bf16x8*>(smem + xw + (2 * u) * 1024) = c_to_operand(sm, u);
+      *reinterpret_cast<bf16x8*>(smem + xw + (2 * u + 1) * 1024) = c_to_operand(dp, u);
+    }
+    __syncthreads();   // P and dS of all 64 queries are there for both waves of the key half
+    bf16x8 pb[4], sb[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      pb[ks] = lds_row(smem, xr + (2 * ks) * 1024);
+      sb[ks] = lds_row(smem, xr + (2 * ks + 1) * 1024);
+    }
+    sched_fence();
+#pragma unroll
+    for (int i = 0; i < NOP; ++i) {
+      const int ks = i / (2 * HT), dt = (i % (2 * HT)) / 2;
+      if (i % 2 == 0) dvT[dt] = mfma32(ta[i % PT], pb[ks], dvT[dt]);   // dO_i^T P
+      else dkT[dt] = mfma32(ta[i % PT], sb[ks], dkT[dt]);              // Q_i^T dS
+      if (i + PT < NOP) read_t(i + PT);
+      sched_fence();
+    }
+  };
   for (int s = 0; s < cnt; s += 2) {
     step(s, 0);
     if (s + 1 < cnt) step(s + 1, 1);
   }
-  // ---- add the two query halves in a row-major staging area, then every thread takes 16-byte
-  // pieces of whole rows and stores them (coalesced)
+  // ---- each wave owns keys 32 kh .., features (D / 2) x .. of dK_j and dV_j: whole-row stores
+  // through its own staging area
   __syncthreads();   // every wave is done with the tiles
-  constexpr int SP = Lds::SP;
-  float* stg = reinterpret_cast<float*>(smem);   // [dV | dK][64 keys][SP]
-  const int srow = krow * SP + 4 * g;
-  if (qh == 1) {
+  unsigned char* stage = smem + wu * Lds::STG;
+  const size_t o0 = ((size_t)bh * N + k0 + 32 * kh) * D + (D / 2) * xh;
+  store_rows_bf16<HT>(stage, dvT, dV + o0, D, cols - 32 * kh, l);
 #pragma unroll
-    for (int et = 0; et < NT; ++et)
+  for (int dt = 0; dt < HT; ++dt)
 #pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const int o = srow + 32 * et + 8 * r4;
-        *reinterpret_cast<f32x4*>(stg + o) =
-            f32x4{dvT[et][4 * r4], dvT[et][4 * r4 + 1], dvT[et][4 * r4 + 2], dvT[et][4 * r4 + 3]};
-        *reinterpret_cast<f32x4*>(stg + kBlk * SP + o) =
-            f32x4{dkT[et][4 * r4], dkT[et][4 * r4 + 1], dkT[et][4 * r4 + 2], dkT[et][4 * r4 + 3]};
-      }
-  }
-  __syncthreads();
-  if (qh == 0) {
-#pragma unroll
-    for (int et = 0; et < NT; ++et)
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const int o = srow + 32 * et + 8 * r4;
-        f32x4 a = *reinterpret_cast<const f32x4*>(stg + o);
-        f32x4 b = *reinterpret_cast<const f32x4*>(stg + kBlk * SP + o);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          a[r] += dvT[et][4 * r4 + r];
-          b[r] += dkT[et][4 * r4 + r];
-        }
-        *reinterpret_cast<f32x4*>(stg + o) = a;
-        *reinterpret_cast<f32x4*>(stg + kBlk * SP + o) = b;
-      }
-  }
-  __syncthreads();
-  constexpr int C4 = D / 4;   // 16-byte pieces per row
-#pragma unroll
-  for (int it = 0; it < kBlk * C4 / 256; ++it) {
-    const int idx = it * 256 + tid, row = idx / C4, c4 = idx % C4;
-    if (row < cols) {
-      const size_t o = ((size_t)bh * N + k0 + row) * D + 4 * c4;
-      const f32x4 sv = *reinterpret_cast<const f32x4*>(stg + row * SP + 4 * c4);
-      const f32x4 sk = *reinterpret_cast<const f32x4*>(stg + (kBlk + row) * SP + 4 * c4);
-      bf16x4 pv, pk;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        pv[r] = (__bf16)sv[r];
-        pk[r] = (__bf16)(sk[r] * scale);
-      }
-      *reinterpret_cast<bf16x4*>(dV + o) = pv;
-      *reinterpret_cast<bf16x4*>(dK + o) = pk;
-    }
-  }
+    for (int r = 0; r < 16; ++r) dkT[dt][r] *= scale;
+  store_rows_bf16<HT>(stage, dkT, dK + o0, D, cols - 32 * kh, l);
 }
 
 // ------------------------------------------------------------------ dQ
@@ -545,9 +516,9 @@ hipError_t sparse_impl(const Shape& s, const BwdArgs& a, const float* Ds, const 
   constexpr int lds = PairLds<D>::BYTES;
   auto launch_kv = [&](auto kern) -> hipError_t {
     SLA_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                PairLds<D>::DKDV));
+                                KvLds<D>::BYTES));
     KernelTimer kt("bwd_sparse_kv", st);
-    kern<<<dim3(s.T * s.BH), 256, PairLds<D>::DKDV, st>>>(
+    kern<<<dim3(s.T * s.BH), 256, KvLds<D>::BYTES, st>>>(
         (const bf16*)a.Q, (const bf16*)a.K, (const bf16*)a.V, (const bf16*)a.dO, a.L, Ds, a.col_ptr, a.col_rows,
         a.col_order, (const bf16*)dHZcol, dZcol, s.N, s.T, s.n_h, s.scale, (bf16*)a.dK, (bf16*)a.dV);
     return hipSuccess;
