@@ -112,28 +112,53 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
     lreg = load_f32_or_zero(Lb + (size_t)ii * kBlk, rows, qq);
     dreg = load_f32_or_zero(Dsb + (size_t)ii * kBlk, rows, qq);
   };
-  // K_j and V_j come in as tiles through the second pair buffer (whole rows per load, zeros past
-  // the end of the sequence) and are picked up from there in operand layout.  With a linear
-  // branch, the aggregated dH^T of this key block (d x d, stored [b][a]) comes in through the
-  // first pair buffer: rows 0..63 in the Q slot, the rest in the dO slot.
-  issue_tile_load<D>(K + ((size_t)bh * N + k0) * D, cols, lds0, Lds::BUF, ldv);
-  issue_tile_load<D>(V + ((size_t)bh * N + k0) * D, cols, lds0, Lds::BUF + Lds::TILE, ldv);
+  // K_j and V_j come in as tiles (whole rows per load, zeros past the end of the sequence) and are
+  // picked up from LDS in operand layout.  With a linear branch, the aggregated dH^T of this key
+  // block (d x d, stored [b][a]) comes in with them, through the second pair buffer (rows 0..63
+  // in the Q slot, the rest in the dO slot), K_j and V_j through the first, which is handed to the
+  // first pair's tiles as soon as the operands are in registers; dZ_j goes to registers directly.
+  const int kvoff = dHcol ? 0 : Lds::BUF;
+  issue_tile_load<D>(K + ((size_t)bh * N + k0) * D, cols, lds0, kvoff, ldv);
+  issue_tile_load<D>(V + ((size_t)bh * N + k0) * D, cols, lds0, kvoff + Lds::TILE, ldv);
+  f32x4 z4[HT][4];
   if (dHcol) {
     const bf16* M = dHcol + ((size_t)bh * Tn + j) * (D * D);
-    issue_tile_load<D>(M, min(kBlk, D), lds0, 0, ldv);
-    if (D > kBlk) issue_tile_load<D>(M + (size_t)kBlk * D, D - kBlk, lds0, Lds::TILE, ldv);
+    issue_tile_load<D>(M, min(kBlk, D), lds0, Lds::BUF, ldv);
+    if (D > kBlk) issue_tile_load<D>(M + (size_t)kBlk * D, D - kBlk, lds0, Lds::BUF + Lds::TILE, ldv);
+    const float* dZ = dZcol + ((size_t)bh * Tn + j) * D;
+#pragma unroll
+    for (int dt = 0; dt < HT; ++dt)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) z4[dt][r4] = *reinterpret_cast<const f32x4*>(dZ + 32 * (xh * HT + dt) + 8 * r4 + 4 * g);
   } else if (cnt > 0) {
     issue(0, 0);
   }
   wait_vm0();
+  if (dHcol) {   // (tell the compiler too, or it waits for dZ later, with the first pair's loads in flight)
+#pragma unroll
+    for (int dt = 0; dt < HT; ++dt)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) pin_loaded(z4[dt][r4]);
+  }
   __syncthreads();
+  bf16x4 kc[HT][4];   // K_j at the positions of this wave's dK^T registers (linear branch only)
   {
     TileAddr<D> ka;
     ka.init(32 * kh, l);
 #pragma unroll
     for (int t = 0; t < KT; ++t) {
-      kf[t] = lds_row(smem, ka.row(t) + Lds::BUF);
-      vf[t] = lds_row(smem, ka.row(t) + Lds::BUF + Lds::TILE);
+      kf[t] = lds_row(smem, ka.row(t) + kvoff);
+      vf[t] = lds_row(smem, ka.row(t) + kvoff + Lds::TILE);
+    }
+    if (dHcol) {
+      const int krw = krow * T::ROW_BYTES + 8 * g, ksw = swz<D>(krow);
+#pragma unroll
+      for (int dt = 0; dt < HT; ++dt)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const int a0 = 32 * (xh * HT + dt) + 8 * r4 + 4 * g;
+          kc[dt][r4] = *reinterpret_cast<const bf16x4*>(smem + krw + (((a0 >> 3) ^ ksw) << 4));
+        }
     }
   }
 #pragma unroll
@@ -145,6 +170,12 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
     // ---- linear branch of Alg. 2 for key block j, as the start value of the accumulators:
     // dV += phi(K_j) dH_j and dK += d phi(K_j) / d K_j applied to (V_j dH_j^T + dZ_j), this wave's
     // feature half of each.
+#pragma unroll
+    for (int dt = 0; dt < HT; ++dt)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) pin_loaded(kc[dt][r4]);
+    __syncthreads();   // K_j and V_j are in registers everywhere: their buffer takes the first pair
+    if (cnt > 0) issue(0, 0);
     float kmx, kinv;
     phi_stats<KT>(kf, phi, kmx, kinv);
     TileAddr<D> ma;
@@ -162,73 +193,52 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
         const int bt = xh * HT + dt;
 #pragma unroll
         for (int t = 0; t < KT; ++t)
-          dvT[dt] = mfma32(lds_row(smem, ma.row(t) + (bt / 2) * Lds::TILE + (bt % 2) * 2 * RB), kp[t], dvT[dt]);
+          dvT[dt] = mfma32(lds_row(smem, ma.row(t) + Lds::BUF + (bt / 2) * Lds::TILE + (bt % 2) * 2 * RB), kp[t], dvT[dt]);
       }
     }
     // d phi(K)^T[a][n] = sum_b M[b][a] V[n][b] + dZ[a]: M^T through the transposing read, whose
-    // k order is the one a C tile hands over, so V is picked up in that order too (two 8-byte
-    // pieces per k-step: features 16 t + 4 g .. and 16 t + 8 + 4 g ..)
-    const int vrow = Lds::BUF + Lds::TILE + krow * T::ROW_BYTES + 8 * g;
-    const int krw = Lds::BUF + krow * T::ROW_BYTES + 8 * g;
-    const int ksw = swz<D>(krow);
+    // k order is the one a C tile hands over, so the V operand is brought into that order too
 #pragma unroll
     for (int t = 0; t < KT; ++t) {
-      const bf16x4 v0 = *reinterpret_cast<const bf16x4*>(smem + vrow + (((2 * t) ^ ksw) << 4));
-      const bf16x4 v1 = *reinterpret_cast<const bf16x4*>(smem + vrow + (((2 * t + 1) ^ ksw) << 4));
-      bf16x8 vb;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        vb[e] = v0[e];
-        vb[4 + e] = v1[e];
-      }
-      const int mb = (t / 4) * Lds::TILE + (t % 4) * RB;   // rows b = 16 t .. of M
+      const bf16x8 vb = to_tr_order(vf[t]);
+      const int mb = Lds::BUF + (t / 4) * Lds::TILE + (t % 4) * RB;   // rows b = 16 t .. of M
 #pragma unroll
       for (int dt = 0; dt < HT; ++dt) {
         const int at = xh * HT + dt;
         dkT[dt] = mfma32(lds_tr<D>(smem, ma.tr(0, at) + mb, ma.tr(1, at) + mb), vb, dkT[dt]);
       }
     }
-    const float* dZ = dZcol + ((size_t)bh * Tn + j) * D;
     float dot = 0.0f;
 #pragma unroll
     for (int dt = 0; dt < HT; ++dt)
 #pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const int a0 = 32 * (xh * HT + dt) + 8 * r4 + 4 * g;
-        const f32x4 z4 = *reinterpret_cast<const f32x4*>(dZ + a0);
-        const bf16x4 k4 = *reinterpret_cast<const bf16x4*>(smem + krw + (((a0 >> 3) ^ ksw) << 4));
+      for (int r4 = 0; r4 < 4; ++r4)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const float x = (float)k4[r];
+          const float x = (float)kc[dt][r4][r];
           const float y = phi == 0 ? phi_val(x, 0, kmx, kinv) : (x > 0.0f ? 1.0f : fast_exp2(x * kLog2e));
-          const float v = dkT[dt][4 * r4 + r] + z4[r];
+          const float v = dkT[dt][4 * r4 + r] + z4[dt][r4][r];
           dkT[dt][4 * r4 + r] = v;
           dot = fmaf(v, y, dot);
         }
-      }
     dot = half_sum(dot);
     float* dotx = reinterpret_cast<float*>(smem + Lds::XOFF);   // [x][64 keys]
     if (g == 0) dotx[xh * kBlk + krow] = dot;
-    __syncthreads();   // also: dH^T is consumed, the first pair buffer is free
-    if (cnt > 0) issue(0, 0);
+    __syncthreads();   // (also: dH^T is consumed before the first step refills its buffer)
     const float dtot = phi == 0 ? dotx[krow] + dotx[kBlk + krow] : 0.0f;
 #pragma unroll
     for (int dt = 0; dt < HT; ++dt)
 #pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const int a0 = 32 * (xh * HT + dt) + 8 * r4 + 4 * g;
-        const bf16x4 k4 = *reinterpret_cast<const bf16x4*>(smem + krw + (((a0 >> 3) ^ ksw) << 4));
+      for (int r4 = 0; r4 < 4; ++r4)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const float x = (float)k4[r];
+          const float x = (float)kc[dt][r4][r];
           const float y = phi == 0 ? phi_val(x, 0, kmx, kinv) : (x > 0.0f ? 1.0f : fast_exp2(x * kLog2e));
           // the epilogue multiplies the whole dK sum by scale
           dkT[dt][4 * r4 + r] = kok ? y * (dkT[dt][4 * r4 + r] - dtot) * rscale : 0.0f;
         }
-      }
     __syncthreads();   // the sums above are read before the first step writes the exchange area
   }
-  // (the first step's barrier orders the reads above before the loads that reuse the second buffer)
   TileAddr<D> ad;   // first products: rows 32 x .. of Q_i, dO_i by rows
   ad.init(32 * xh, l);
   TileAddr<D> at;   // second products: transposing reads, feature tiles x HT ..

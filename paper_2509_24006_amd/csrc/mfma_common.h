@@ -232,6 +232,20 @@ __device__ __forceinline__ float half_max(float x) {
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
+// A B-operand fragment in natural order (lane half g holds k = 8 g .. 8 g + 7) -> the order in
+// which the transposing LDS read delivers the other operand (k = 4 g .. + 3 and 8 + 4 g .. + 3):
+// the g = 0 lanes trade their upper four values for the lower four of the g = 1 lanes.
+__device__ __forceinline__ bf16x8 to_tr_order(bf16x8 x) {
+  u32x4 v = *reinterpret_cast<u32x4*>(&x);
+  const auto r0 = __builtin_amdgcn_permlane32_swap(v.x, v.z, false, false);
+  const auto r1 = __builtin_amdgcn_permlane32_swap(v.y, v.w, false, false);
+  v.x = r0[0];
+  v.z = r0[1];
+  v.y = r1[0];
+  v.w = r1[1];
+  return *reinterpret_cast<bf16x8*>(&v);
+}
+
 // Makes the compiler finish the loads that produce x here.  Used on operand registers that are
 // loaded before a pipelined loop: otherwise the wait for them lands at their first use inside the
 // loop body, where it also waits -- on every trip -- for the tile loads just put in flight.
