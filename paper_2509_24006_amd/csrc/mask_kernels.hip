@@ -130,6 +130,67 @@ __device__ void mark_top(const uint32_t* keys, int8_t* lab, int T, int k, int8_t
   }
 }
 
+// The same with the row in registers (entry j = 64 i + lane in slot i, key 0 past the end): every
+// count is a handful of wave votes tallied on the scalar side, no LDS and no cross-lane shuffles.
+template <int KPL>
+__device__ __forceinline__ void mark_top_reg(const uint32_t (&key)[KPL], int8_t (&lab)[KPL], int k, int8_t label,
+                                             int lane) {
+  if (k <= 0) return;
+  uint32_t thr = 0;
+  for (int bit = 31; bit >= 0; --bit) {
+    const uint32_t cand = thr | (1u << bit);
+    int c = 0;
+#pragma unroll
+    for (int i = 0; i < KPL; ++i) c += __popcll(__ballot(key[i] >= cand));
+    if (c >= k) thr = cand;
+  }
+  int need = k;
+#pragma unroll
+  for (int i = 0; i < KPL; ++i) need -= __popcll(__ballot(key[i] > thr));
+#pragma unroll
+  for (int i = 0; i < KPL; ++i) {   // ascending index: slot by slot, lane by lane
+    const bool eq = key[i] == thr;
+    const unsigned long long m = __ballot(eq);
+    const int before = __popcll(m & ((1ull << lane) - 1ull));
+    if (key[i] > thr || (eq && before < need)) lab[i] = label;
+    need -= __popcll(m);
+  }
+}
+
+// One wavefront per row of the score matrix, rows of at most 64 KPL entries.
+template <int KPL>
+__global__ __launch_bounds__(256) void classify_reg_kernel(const float* __restrict__ s, int rows, int T,
+                                                           int n_h, int n_l, int8_t* __restrict__ Mc,
+                                                           int32_t* __restrict__ row_idx) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const long row = (long)blockIdx.x * 4 + wave;
+  if (row >= rows) return;   // (no barriers in this kernel)
+  const float* sr = s + (size_t)row * T;
+  uint32_t key[KPL];
+  int8_t lab[KPL];
+#pragma unroll
+  for (int i = 0; i < KPL; ++i) {
+    const int j = 64 * i + lane;
+    key[i] = j < T ? order_key(sr[j]) : 0u;
+    lab[i] = 0;
+  }
+  mark_top_reg<KPL>(key, lab, n_h, (int8_t)1, lane);
+  // negligible: lowest scores among the rest = largest inverted keys; critical entries and the
+  // slots past the end get key 0 and drop out
+#pragma unroll
+  for (int i = 0; i < KPL; ++i) key[i] = (lab[i] == 1 || 64 * i + lane >= T) ? 0u : ~key[i];
+  mark_top_reg<KPL>(key, lab, n_l, (int8_t)-1, lane);
+  int base = 0;
+#pragma unroll
+  for (int i = 0; i < KPL; ++i) {
+    const int j = 64 * i + lane;
+    if (j < T) Mc[(size_t)row * T + j] = lab[i];
+    const unsigned long long m = __ballot(lab[i] == 1);
+    if (lab[i] == 1) row_idx[(size_t)row * n_h + base + __popcll(m & ((1ull << lane) - 1ull))] = j;
+    base += __popcll(m);
+  }
+}
+
 // One wavefront per row of the score matrix.
 __global__ __launch_bounds__(256) void classify_kernel(const float* __restrict__ s, int rows, int T,
                                                        int n_h, int n_l, int8_t* __restrict__ Mc,
@@ -267,16 +328,24 @@ __global__ __launch_bounds__(256) void indicator_kernel(const int8_t* __restrict
 // workgroups of the column-wise backward kernel take the longest lists first.
 __global__ __launch_bounds__(256) void col_order_kernel(const int32_t* __restrict__ ptr, int T,
                                                         int32_t* __restrict__ order) {
+  // a workgroup ranks 64 columns of one head; four threads share the comparisons of a column
   extern __shared__ int cnt[];
-  const int32_t* p = ptr + (size_t)blockIdx.x * (T + 1);
+  __shared__ int part[4][64];
+  const int32_t* p = ptr + (size_t)blockIdx.y * (T + 1);
   for (int j = threadIdx.x; j < T; j += 256) cnt[j] = p[j + 1] - p[j];
   __syncthreads();
-  for (int j = threadIdx.x; j < T; j += 256) {
+  const int col = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int j = blockIdx.x * 64 + col;
+  int rank = 0;
+  if (j < T) {
     const int c = cnt[j];
-    int rank = 0;
-    for (int k = 0; k < T; ++k) rank += (cnt[k] > c) || (cnt[k] == c && k < j);
-    order[(size_t)blockIdx.x * T + rank] = j;
+    const int chunk = (T + 3) / 4, lo = min(T, q * chunk), hi = min(T, lo + chunk);
+    for (int k = lo; k < hi; ++k) rank += (cnt[k] > c) || (cnt[k] == c && k < j);
   }
+  part[q][col] = rank;
+  __syncthreads();
+  if (q == 0 && j < T)
+    order[(size_t)blockIdx.y * T + part[0][col] + part[1][col] + part[2][col] + part[3][col]] = j;
 }
 
 }  // namespace
@@ -312,7 +381,12 @@ hipError_t launch_classify(const float* scores, const Shape& s, int8_t* Mc, int3
   const size_t lds = (size_t)4 * s.T * (sizeof(uint32_t) + 1);
   {
     KernelTimer kt("classify", st);
-    classify_kernel<<<(rows + 3) / 4, 256, lds, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx);
+    const dim3 grid((rows + 3) / 4);
+    if (s.T <= 64) classify_reg_kernel<1><<<grid, 256, 0, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx);
+    else if (s.T <= 128) classify_reg_kernel<2><<<grid, 256, 0, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx);
+    else if (s.T <= 256) classify_reg_kernel<4><<<grid, 256, 0, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx);
+    else if (s.T <= 512) classify_reg_kernel<8><<<grid, 256, 0, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx);
+    else classify_kernel<<<grid, 256, lds, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx);
   }
   return hipGetLastError();
 }
@@ -335,7 +409,7 @@ hipError_t launch_csc(const int8_t* Mc, const Shape& s, int32_t* col_ptr, int32_
   }
   {
     KernelTimer kt("col_order", st);
-    col_order_kernel<<<s.BH, 256, s.T * sizeof(int), st>>>(col_ptr, s.T, col_order);
+    col_order_kernel<<<dim3((s.T + 63) / 64, s.BH), 256, s.T * sizeof(int), st>>>(col_ptr, s.T, col_order);
   }
   if (s.n_h > 0) {
     KernelTimer kt("col_fill", st);
