@@ -69,9 +69,12 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
   const int kh = w & 1, xh = w >> 1;
-  // longest column lists first, across all heads: the r-th heaviest key block of every head
-  // precedes the (r+1)-th of any head, so the tail of the launch is made of short lists
-  // (grouping an XCD's workgroups by head for L2 reuse was measured slower than this order)
+  // Longest column lists first, across all heads: the r-th heaviest key block of every head
+  // precedes the (r+1)-th of any head.  The lists are very uneven (on video-like inputs the
+  // heaviest key block of a head serves a third of all query blocks, the median one a dozen), and
+  // the heaviest list alone lasts a good part of the launch, so every heavy list has to start at
+  // once.  Going head by head instead would let an XCD's workgroups share one head's Q and dO
+  // tiles in its L2, but it starts the last head's heavy lists late: measured 1.5x slower.
   const int BH = gridDim.x / Tn;
   const int bh = blockIdx.x % BH;
   const int j = col_order[(size_t)bh * Tn + blockIdx.x / BH];

@@ -212,36 +212,42 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
   }
 #pragma unroll
   for (int t = 0; t < KT; ++t) pin_loaded(qf[t]);
-  int kslot = 0;   // slot of K_s; V_s sits in the next one
+  int kslot = 0;   // slot of K_s; V_s sits in the next one, K_{s+1} in the one after
   TileAddr<D> ad;  // this wave reads rows 32 par .. of both tiles
   ad.init(32 * par, l);
+  // The scores of a step are formed one step ahead, so that their matrix products (a chain on
+  // one accumulator, during which the wave could issue nothing else) run under the exponentials
+  // of the current step: S_0 here, S_{s+1} inside step s.
+  f32x16 sT = zero_f32x16();
+  if (n_h > 0) {
+    if (n_h > 1) wait_vm<3 * T::IPW>();   // K_0 has landed; V_0, K_1, V_1 may stay in flight
+    else wait_vm0();
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < KT; ++t) sT = mfma32(lds_row(smem, ad.row(t)), qf[t], sT);
+  }
   for (int s = 0; s < n_h; ++s) {
     const int cols = min(kBlk, N - j0 * kBlk);
     const int j3 = lut[min(s + 3, n_h - 1)];   // needed in the next step
-    // K_s has landed; the three loads issued after it may stay in flight
-    if (s + 2 <= n_h) wait_vm<3 * T::IPW>();
+    // V_s and K_{s+1} have landed; the load issued after them (V_{s+1}) may stay in flight
+    if (s + 2 <= n_h) wait_vm<T::IPW>();
     else wait_vm0();
-    __syncthreads();   // ... for every wave; and V_{s-1} is fully consumed: its slot takes K_{s+2}
-    if (2 * s + 4 < nloads) issue_load(2 * s + 4, j2);
+    __syncthreads();   // ... for every wave; K_s and V_{s-1} are fully consumed: their slots are refilled
+    if (2 * s + 4 < nloads) {
+      issue_load(2 * s + 4, j2);
+      issue_load(2 * s + 5, j2);
+    } else if (s + 1 == n_h && n_0 > 0) {
+      issue_matrix(Hrow, h0, h1);   // arrives under the last step
+    }
     ad.refresh();
-    const int kb = ad.rb + kslot * Lds::TILE;
     const int voff = (kslot == 4 ? 0 : kslot + 1) * Lds::TILE;
     const int vb0 = ad.tb[0] + voff, vb1 = ad.tb[1] + voff;
-    kslot = kslot >= 3 ? kslot - 3 : kslot + 2;
+    kslot = kslot >= 3 ? kslot - 3 : kslot + 2;   // now the slot of K_{s+1}
+    const int kb = ad.rb + kslot * Lds::TILE;
+    // (in the last step this reads a slot that holds no tile: the products below are then unused)
     bf16x8 ka[KT], va[2][NT];
 #pragma unroll
     for (int t = 0; t < KT; ++t) ka[t] = lds_row(smem, ad.row_at(t, kb));
-    sched_fence();
-    f32x16 sT = zero_f32x16();
-#pragma unroll
-    for (int t = 0; t < KT; ++t) sT = mfma32(ka[t], qf[t], sT);
-    // V_s has landed (same three-load margin), K_s is consumed: its slot takes V_{s+2}
-    if (s + 3 <= n_h) wait_vm<3 * T::IPW>();
-    else wait_vm0();
-    __syncthreads();
-    if (2 * s + 5 < nloads) issue_load(2 * s + 5, j2);
-    else if (s + 1 == n_h && n_0 > 0) issue_matrix(Hrow, h0, h1);   // arrives under the rest of the last step
-    // the V operands arrive under the softmax
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
@@ -276,11 +282,17 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
     }
     const float moff = m == -INFINITY ? 0.0f : -m * c2;   // a half with no valid key yet
     float psum = 0.0f;
+    f32x16 sN = zero_f32x16();
+    static_assert(KT == 8 || KT == 4, "two or four exponentials per product of the next scores");
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const float pv = fast_exp2(fmaf(sT[r], c2, moff));
-      sT[r] = pv;
-      psum += pv;
+    for (int t = 0; t < KT; ++t) {
+      sN = mfma32(ka[t], qf[t], sN);   // S_{s+1}
+#pragma unroll
+      for (int r = t * (16 / KT); r < (t + 1) * (16 / KT); ++r) {
+        const float pv = fast_exp2(fmaf(sT[r], c2, moff));
+        sT[r] = pv;
+        psum += pv;
+      }
     }
     lsum += psum;
 #pragma unroll
@@ -289,6 +301,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
 #pragma unroll
       for (int et = 0; et < NT; ++et) oT[et] = mfma32(va[u][et], pf, oT[et]);
     }
+    sT = sN;
     j0 = j1;
     j1 = j2;
     j2 = j3;
