@@ -5,27 +5,30 @@
 //   out[i][:] = sum_k ind[i][k] in[k][:],   ind = 1 where the block is marginal, else 0,
 // a T x T by T x (d*d + d) product per head.  The indicator is exact in bf16, the products are
 // bf16 x bf16 with float accumulation.  Compared with adding the marginal blocks one by one
-// (or subtracting the others from the total, App. A.3) the state rows are read once per 512
+// (or subtracting the others from the total, App. A.3) the state rows are read once per 256
 // output rows instead of once per row.
 //
 // The kernel is bound by HBM traffic (one read of the states, one write of the sums), so the
-// design keeps everything else small: a workgroup of eight waves owns 512 output rows (all of
-// them for T <= 512) by 128 columns, so that the states are read once; the indicator comes as
-// bit masks, 8 bytes per row and k-step; the state tiles go global -> LDS directly (row-major,
-// swizzled) through a ring of stages and are read with the transposing LDS read; the product is formed
-// with the output rows along the lanes, so that the sums leave as whole 256-byte row pieces; and a
-// workgroup takes two column tiles in a row with the ring running on, so that the stores of the
-// first overlap the loads and products of the second (with one workgroup per CU nothing else would).
+// design keeps everything else small: the indicator comes as bit masks, 8 bytes per row and
+// k-step; the state tiles go global -> LDS directly (row-major, swizzled) through a ring of stages
+// and are read with the transposing LDS read; the product is formed with the output rows along the
+// lanes, so that the sums leave as whole 256-byte row pieces.  A workgroup of four waves owns 256
+// output rows by 128 columns and two of them share a CU: while one fills its ring or stores its
+// sums (a store drains the wave's whole memory queue: loads and stores complete in no fixed order
+// relative to each other, so nothing can be waited for selectively behind it), the other computes.
+// The workgroups that own the same columns run back to back on one XCD, so that the second read
+// of the states comes from its L2.
 #include "mfma_common.h"
 
 namespace sla {
 namespace {
 
 constexpr int kStage = kBlk * 256;   // one k-step of states: 64 rows x 128 columns of bf16
-constexpr int kStages = 5;          // ring of state tiles
-constexpr int kPasses = 2;          // column tiles of 128 per workgroup, one after the other
+constexpr int kStages = 4;           // ring of state tiles
 constexpr int kOutStage = 32 * (64 * 4 + 16);   // store_rows_bf16<4> area of one wave
-constexpr int kAggLds = kStages * kStage + 8 * kOutStage;   // the output staging is not laid over the ring
+constexpr int kAggLds = kStages * kStage;       // the output staging is laid over the ring
+constexpr int kAggRows = 256;        // output rows of one workgroup
+static_assert(4 * kOutStage <= kAggLds, "staging of four waves fits in the ring");
 
 // two adjacent indicator bits (bits s, s + 1 of x) -> a dword holding two bf16 (1.0 or 0.0)
 __device__ __forceinline__ unsigned bits2bf(unsigned x, int s) {
@@ -33,18 +36,21 @@ __device__ __forceinline__ unsigned bits2bf(unsigned x, int s) {
   return (((y << 15) | y) & 0x00010001u) * 0x3f80u;
 }
 
-// ZPART = false: the matrix part, columns [256 blockIdx.x, +256) of d*d, written in bf16.
-// ZPART = true: the vector part (the last d entries of a state row), one column tile, written in
-// float; launched on its own so that the matrix part fills the GPU in whole rounds.
-template <bool ZPART>
-__global__ __launch_bounds__(512, 1) void aggregate_mfma_kernel(const bf16* __restrict__ in,
+// Column tile ct < dd / 128: columns [128 ct, +128) of the matrix part, written in bf16; column
+// tile dd / 128: the vector part (the last d entries of a state row), written in float.
+// blockIdx.x = 8 (mtiles cg + mh) + x for column tile 8 cg + x and row tile mh: the round-robin
+// deal puts the row tiles of one column tile on the same XCD, one after the other.
+__global__ __launch_bounds__(256, 2) void aggregate_mfma_kernel(const bf16* __restrict__ in,
                                                                 const unsigned long long* __restrict__ ind,
-                                                                int T, int Tw, int row_len, int dd,
+                                                                int T, int Tw, int row_len, int dd, int mtiles,
                                                                 bf16* __restrict__ outH, float* __restrict__ outZ) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
-  const int nbase = ZPART ? dd : blockIdx.x * 128 * kPasses, m0 = blockIdx.y * 512, bh = blockIdx.z;
-  const int passes = ZPART ? 1 : kPasses;
+  const int rr = blockIdx.x >> 3;
+  const int ct = (rr / mtiles) * 8 + (blockIdx.x & 7), mh = rr % mtiles, bh = blockIdx.y;
+  if (ct > dd / 128) return;
+  const bool zpart = ct == dd / 128;
+  const int nbase = ct * 128, m0 = mh * kAggRows;
   const unsigned long long* ib = ind + (size_t)bh * T * Tw;
   const bf16* inb = in + (size_t)bh * T * row_len;
   const BufDesc rsrc = tile_rsrc(inb, T * row_len * 2);
@@ -57,26 +63,23 @@ __global__ __launch_bounds__(512, 1) void aggregate_mfma_kernel(const bf16* __re
 #pragma unroll
     for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = zero_f32x16();
   const int ksteps = (T + kBlk - 1) / kBlk;
-  // one wave-wide load deposits 4 rows x 256 bytes; wave w takes the 1 KB runs w and w + 8 of a
-  // stage; rows past T read as zeros
-  int vo[2];
+  // one wave-wide load deposits 4 rows x 256 bytes; wave w takes the 1 KB runs w, w + 4, w + 8 and
+  // w + 12 of a stage; rows past T read as zeros (the vector part of a narrow head reads on into
+  // the next row: those columns are not written)
+  int vo[4];
 #pragma unroll
-  for (int k = 0; k < 2; ++k) {
-    const int row = 4 * (8 * k + w) + (l >> 4), pc = l & 15;
+  for (int k = 0; k < 4; ++k) {
+    const int row = 4 * (4 * k + w) + (l >> 4), pc = l & 15;
     vo[k] = row * pitch + nbase * 2 + ((pc ^ swz<128>(row)) << 4);
   }
-  // the loads form one stream over (pass, k-step); ip, iks, istage: the next one to request
-  int ip = 0, iks = 0, istage = 0;
+  int iks = 0, istage = 0;   // the next tile to request and its stage
   auto issue_next = [&]() {
-    if (ip >= passes) return;
+    if (iks >= ksteps) return;
 #pragma unroll
-    for (int k = 0; k < 2; ++k)
-      load_to_lds16(rsrc, vo[k], iks * kBlk * pitch + ip * 256, lds0 + istage * kStage + (8 * k + wu) * 1024);
+    for (int k = 0; k < 4; ++k)
+      load_to_lds16(rsrc, vo[k], iks * kBlk * pitch, lds0 + istage * kStage + (4 * k + wu) * 1024);
     istage = istage == kStages - 1 ? 0 : istage + 1;
-    if (++iks == ksteps) {
-      iks = 0;
-      ++ip;
-    }
+    ++iks;
   };
   // per-lane offsets of the transposing reads inside a stage: [8-row half][column tile]
   TileAddr<128> ad;
@@ -90,93 +93,83 @@ __global__ __launch_bounds__(512, 1) void aggregate_mfma_kernel(const bf16* __re
   const int row0 = m0 + 64 * w + ln;   // this lane's output rows: row0 and row0 + 32
 #pragma unroll
   for (int k = 0; k < kStages - 1; ++k) issue_next();
-  const int total = passes * ksteps;
-  int gs = 0, stage = 0;   // position in the stream of the tile consumed next
-  for (int pass = 0; pass < passes; ++pass) {
-    const int n0 = nbase + 128 * pass;
+  int stage = 0;
+  for (int ks0 = 0; ks0 < ksteps; ks0 += 8) {
+    // indicator words of the next eight k-steps for the lane's two rows
+    unsigned long long wb[2][8];
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-      for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = zero_f32x16();
-    for (int ks0 = 0; ks0 < ksteps; ks0 += 8) {
-      // indicator words of the next eight k-steps for the lane's two rows
-      unsigned long long wb[2][8];
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-          const int i = row0 + 32 * mt;
-          wb[mt][q] = (i < T && ks0 + q < Tw) ? ib[(size_t)i * Tw + ks0 + q] : 0ull;
-        }
-      // (waited for here, once per eight k-steps, rather than at each first use below, where the
-      // wait would also drain the tile loads in flight)
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int q = 0; q < 8; ++q) pin_loaded(wb[mt][q]);
-#pragma unroll
       for (int q = 0; q < 8; ++q) {
-        const int ks = ks0 + q;
-        if (ks >= ksteps) break;
-        // the lane's bits of this k-step, moved so that k = 16 u + 4 g sits at bit 16 u
-        const unsigned long long x0 = wb[0][q] >> (4 * g), x1 = wb[1][q] >> (4 * g);
-        // the tile has landed; the kStages - 2 tiles requested after it may still be in flight
-        if (gs + kStages - 2 < total) wait_vm<2 * (kStages - 2)>();
-        else wait_vm0();
-        __syncthreads();   // ... for every wave, and the stage of the previous tile is free
-        issue_next();
-        const int so = stage * kStage;
-        stage = stage == kStages - 1 ? 0 : stage + 1;
-        ++gs;
+        const int i = row0 + 32 * mt;
+        wb[mt][q] = (i < T && ks0 + q < Tw) ? ib[(size_t)i * Tw + ks0 + q] : 0ull;
+      }
+    // (waited for here, once per eight k-steps, rather than at each first use below; the wait
+    // also drains the tile loads in flight, which at the start are the ones needed first anyway)
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          // slots 0..3 <- k = 16 u + 4 g .. + 3, slots 4..7 <- k = 16 u + 8 + 4 g .. + 3: the order
-          // in which the transposing read hands over the state rows
-          bf16x8 b[2];
+    for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-          for (int mt = 0; mt < 2; ++mt) {
-            const unsigned long long x = mt ? x1 : x0;
-            const unsigned half = u < 2 ? (unsigned)x : (unsigned)(x >> 32);
-            const int sh = 16 * (u & 1);
-            u32x4 packed = {bits2bf(half, sh), bits2bf(half, sh + 2), bits2bf(half, sh + 8), bits2bf(half, sh + 10)};
-            b[mt] = *reinterpret_cast<bf16x8*>(&packed);
-          }
+      for (int q = 0; q < 8; ++q) pin_loaded(wb[mt][q]);
 #pragma unroll
-          for (int nt = 0; nt < 4; ++nt) {
-            const bf16x8 a = lds_tr<128>(smem, tro[0][nt] + so + u * RB, tro[1][nt] + so + u * RB);
+    for (int q = 0; q < 8; ++q) {
+      const int ks = ks0 + q;
+      if (ks >= ksteps) break;
+      // the lane's bits of this k-step, moved so that k = 16 u + 4 g sits at bit 16 u
+      const unsigned long long x0 = wb[0][q] >> (4 * g), x1 = wb[1][q] >> (4 * g);
+      // the tile has landed; the kStages - 2 tiles requested after it may still be in flight
+      if (ks + kStages - 2 < ksteps) wait_vm<4 * (kStages - 2)>();
+      else wait_vm0();
+      __syncthreads();   // ... for every wave, and the stage of the previous tile is free
+      issue_next();
+      const int so = stage * kStage;
+      stage = stage == kStages - 1 ? 0 : stage + 1;
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt) acc[mt][nt] = mfma32(a, b[mt], acc[mt][nt]);
-          }
+      for (int u = 0; u < 4; ++u) {
+        // slots 0..3 <- k = 16 u + 4 g .. + 3, slots 4..7 <- k = 16 u + 8 + 4 g .. + 3: the order
+        // in which the transposing read hands over the state rows
+        bf16x8 b[2];
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+          const unsigned long long x = mt ? x1 : x0;
+          const unsigned half = u < 2 ? (unsigned)x : (unsigned)(x >> 32);
+          const int sh = 16 * (u & 1);
+          u32x4 packed = {bits2bf(half, sh), bits2bf(half, sh + 2), bits2bf(half, sh + 8), bits2bf(half, sh + 10)};
+          b[mt] = *reinterpret_cast<bf16x8*>(&packed);
+        }
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+          const bf16x8 a = lds_tr<128>(smem, tro[0][nt] + so + u * RB, tro[1][nt] + so + u * RB);
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt) acc[mt][nt] = mfma32(a, b[mt], acc[mt][nt]);
         }
       }
     }
-    // C tiles: lane = output row, registers = columns 32 nt + c_row(r, g)
-    if (ZPART) {
-      const int dz = row_len - dd;
+  }
+  // C tiles: lane = output row, registers = columns 32 nt + c_row(r, g)
+  if (zpart) {
+    const int dz = row_len - dd;
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
-        const int row = row0 + 32 * mt;
-        if (row >= T) continue;
-        float* o = outZ + ((size_t)bh * T + row) * dz;
+    for (int mt = 0; mt < 2; ++mt) {
+      const int row = row0 + 32 * mt;
+      if (row >= T) continue;
+      float* o = outZ + ((size_t)bh * T + row) * dz;
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt)
+      for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
-          for (int r4 = 0; r4 < 4; ++r4) {
-            const int c = 32 * nt + 8 * r4 + 4 * g;
-            if (c < dz)
-              *reinterpret_cast<f32x4*>(o + c) = f32x4{acc[mt][nt][4 * r4], acc[mt][nt][4 * r4 + 1],
-                                                        acc[mt][nt][4 * r4 + 2], acc[mt][nt][4 * r4 + 3]};
-          }
-      }
-    } else {
-      // through this wave's own staging area (no barrier: LDS serves a wave's accesses in order)
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const int c = 32 * nt + 8 * r4 + 4 * g;
+          if (c < dz)
+            *reinterpret_cast<f32x4*>(o + c) = f32x4{acc[mt][nt][4 * r4], acc[mt][nt][4 * r4 + 1],
+                                                      acc[mt][nt][4 * r4 + 2], acc[mt][nt][4 * r4 + 3]};
+        }
+    }
+  } else {
+    __syncthreads();   // every wave has read the last tile: the ring becomes the staging areas
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
-        const int r0 = m0 + 64 * w + 32 * mt;
-        if (r0 < T)
-          store_rows_bf16<4>(smem + kStages * kStage + wu * kOutStage, acc[mt], outH + ((size_t)bh * T + r0) * dd + n0, dd,
-                             T - r0, l);
-      }
+    for (int mt = 0; mt < 2; ++mt) {
+      const int r0 = m0 + 64 * w + 32 * mt;
+      if (r0 < T)
+        store_rows_bf16<4>(smem + wu * kOutStage, acc[mt], outH + ((size_t)bh * T + r0) * dd + nbase, dd, T - r0, l);
     }
   }
 }
@@ -190,23 +183,16 @@ hipError_t mfma_aggregate(const void* in, const unsigned long long* ind, const S
                           float* outZ, hipStream_t st) {
   const int row_len = s.state_row(), dd = s.d * s.d;
   const int Tw = (s.T + 63) / 64;
-  if (dd % (128 * kPasses) != 0) return hipErrorInvalidValue;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(aggregate_mfma_kernel<false>),
+  if (dd % 128 != 0 || row_len - dd > 128) return hipErrorInvalidValue;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(aggregate_mfma_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, kAggLds);
   if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(aggregate_mfma_kernel<true>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, kAggLds);
-  if (e != hipSuccess) return e;
-  const int mtiles = (s.T + 511) / 512;
-  {
-    KernelTimer kt("aggregate_z", st);
-    aggregate_mfma_kernel<true><<<dim3(1, mtiles, s.BH), 512, kAggLds, st>>>((const bf16*)in, ind, s.T, Tw, row_len, dd,
-                                                                           nullptr, outZ);
-  }
+  const int mtiles = (s.T + kAggRows - 1) / kAggRows;
+  const int ntile = dd / 128 + 1;
   {
     KernelTimer kt("aggregate", st);
-    aggregate_mfma_kernel<false><<<dim3(dd / (128 * kPasses), mtiles, s.BH), 512, kAggLds, st>>>((const bf16*)in, ind, s.T, Tw,
-                                                                                  row_len, dd, (bf16*)outH, nullptr);
+    aggregate_mfma_kernel<<<dim3(8 * ((ntile + 7) / 8) * mtiles, s.BH), 256, kAggLds, st>>>(
+        (const bf16*)in, ind, s.T, Tw, row_len, dd, mtiles, (bf16*)outH, outZ);
   }
   return hipGetLastError();
 }

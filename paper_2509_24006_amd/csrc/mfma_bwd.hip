@@ -73,11 +73,24 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
   // precedes the (r+1)-th of any head.  The lists are very uneven (on video-like inputs the
   // heaviest key block of a head serves a third of all query blocks, the median one a dozen), and
   // the heaviest list alone lasts a good part of the launch, so every heavy list has to start at
-  // once.  Going head by head instead would let an XCD's workgroups share one head's Q and dO
-  // tiles in its L2, but it starts the last head's heavy lists late: measured 1.5x slower.
+  // once.  (Going head by head instead would let an XCD's workgroups share one head's Q and dO
+  // tiles in its L2, but it starts the last head's heavy lists late: measured 1.5x slower.)
+  // Within that order the heads are dealt to the XCDs (workgroups go to them round robin) in
+  // halves -- the even or the odd ranks of a head -- so that an XCD's L2 serves the Q and dO tiles
+  // of few heads at a time; most tile loads of this kernel miss the L2.
   const int BH = gridDim.x / Tn;
-  const int bh = blockIdx.x % BH;
-  const int j = col_order[(size_t)bh * Tn + blockIdx.x / BH];
+  int bh, rank;
+  if ((2 * BH) % 8 == 0 && Tn % 2 == 0) {
+    const int upx = 2 * BH / 8;   // half-heads per XCD
+    const int x = blockIdx.x & 7, m = blockIdx.x >> 3;
+    const int u = upx * x + m % upx;
+    bh = u >> 1;
+    rank = 2 * (m / upx) + (u & 1);
+  } else {
+    bh = blockIdx.x % BH;
+    rank = blockIdx.x / BH;
+  }
+  const int j = col_order[(size_t)bh * Tn + rank];
   const int k0 = j * kBlk, cols = min(kBlk, N - k0);
   const int krow = kh * 32 + ln;
   const bool kok = krow < cols;
