@@ -172,18 +172,18 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
   const bf16* Vb = V + (size_t)bh * N * D;
   const float c2 = scale_log2e;                    // exp(x / sqrt(d)) = exp2(x * c2)
   using T = SwzTile<D>;
-  const int ldv = tile_lane_offset<D>(w, l);
-  const unsigned lds0 = lds_base(smem) + wave_uniform(w) * 1024;
-  // load n of the sequence K_0 V_0 K_1 V_1 ... into slot n % 5
-  auto issue_load = [&](int n, int jj) {   // jj = lut[n / 2]
-    issue_tile_load<D>((n & 1 ? Vb : Kb) + (size_t)jj * kBlk * D, min(kBlk, N - jj * kBlk), lds0, (n % 5) * Lds::TILE,
-                       ldv);
-  };
+  TileLoader<D> tl;
+  tl.init(lds_base(smem), w, l);
+  const BufDesc descK = tile_rsrc(Kb, N * D * 2), descV = tile_rsrc(Vb, N * D * 2);
+  // K (v = 0) or V (v = 1) tile of key block jj into a slot; the loads go K_0 V_0 K_1 V_1 ... and
+  // load n of that sequence uses slot n % 5
+  auto issue_load = [&](int v, int jj, int slot) { tl.load(v ? descV : descK, jj * Lds::TILE, slot * Lds::TILE); };
   // a d x d bf16 matrix (aggregated state H_i, prepared projection matrix) goes global -> LDS like
   // the tiles: rows 0..63 into the slot at off0, the rest into the one at off1
   auto issue_matrix = [&](const bf16* M, int off0, int off1) {
-    issue_tile_load<D>(M, min(kBlk, D), lds0, off0, ldv);
-    if (D > kBlk) issue_tile_load<D>(M + (size_t)kBlk * D, D - kBlk, lds0, off1, ldv);
+    const BufDesc dm = tile_rsrc(M, D * D * 2);
+    tl.load(dm, 0, off0);
+    if (D > kBlk) tl.load(dm, Lds::TILE, off1);
   };
   const bf16* Hrow = H16 + ((size_t)bh * Tn + i) * (D * D);
   // Slots at the end of the loop, with b the slot of the last K tile: H_i goes to b and b + 4
@@ -201,11 +201,11 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
     j0 = lut[0];
     j1 = lut[min(1, n_h - 1)];
     j2 = lut[min(2, n_h - 1)];
-    issue_load(0, j0);
-    issue_load(1, j0);
+    issue_load(0, j0, 0);
+    issue_load(1, j0, 1);
     if (n_h > 1) {
-      issue_load(2, j1);
-      issue_load(3, j1);
+      issue_load(0, j1, 2);
+      issue_load(1, j1, 3);
     }
   } else if (n_0 > 0) {
     issue_matrix(Hrow, h0, h1);
@@ -233,9 +233,9 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
     if (s + 2 <= n_h) wait_vm<T::IPW>();
     else wait_vm0();
     __syncthreads();   // ... for every wave; K_s and V_{s-1} are fully consumed: their slots are refilled
-    if (2 * s + 4 < nloads) {
-      issue_load(2 * s + 4, j2);
-      issue_load(2 * s + 5, j2);
+    if (2 * s + 4 < nloads) {   // K_{s+2}, V_{s+2} into the slots of V_{s-1} and K_s
+      issue_load(0, j2, kslot == 0 ? 4 : kslot - 1);
+      issue_load(1, j2, kslot);
     } else if (s + 1 == n_h && n_0 > 0) {
       issue_matrix(Hrow, h0, h1);   // arrives under the last step
     }
