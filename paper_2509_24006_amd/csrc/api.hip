@@ -63,6 +63,7 @@ void fill_sizes(const Shape& s, sla_sizes_t* o) {
   off += align_up(BH * T * Tw * 8);
   o->lut_col_order = off;
   off += align_up(BH * T * 4);
+  off += align_up(BH * T * 4);   // column counts: scratch of the table build, at the end of the buffer
   o->luts_bytes = off;
   off = 0;
   o->saved_Os = off;
@@ -117,9 +118,10 @@ int sla_classify_scores(const sla_params* p, const float* scores, int8_t* Mc, vo
   fill_sizes(s, &z);
   hipStream_t st = (hipStream_t)stream;
   char* l = (char*)luts;
-  hipError_t e = launch_classify(scores, s, Mc, (int32_t*)(l + z.lut_row_idx), st);
+  int32_t* col_cnt = (int32_t*)(l + z.luts_bytes - align_up((size_t)s.BH * s.T * 4));
+  hipError_t e = launch_classify(scores, s, Mc, (int32_t*)(l + z.lut_row_idx), col_cnt, st);
   if (e == hipSuccess)
-    e = launch_csc(Mc, s, (int32_t*)(l + z.lut_col_ptr), (int32_t*)(l + z.lut_col_rows),
+    e = launch_csc(Mc, s, col_cnt, (int32_t*)(l + z.lut_col_ptr), (int32_t*)(l + z.lut_col_rows),
                    (unsigned long long*)(l + z.lut_ind), (unsigned long long*)(l + z.lut_ind_t),
                    (int32_t*)(l + z.lut_col_order), st);
   return hip_status(e);

@@ -161,10 +161,12 @@ __device__ __forceinline__ void mark_top_reg(const uint32_t (&key)[KPL], int8_t 
 template <int KPL>
 __global__ __launch_bounds__(256) void classify_reg_kernel(const float* __restrict__ s, int rows, int T,
                                                            int n_h, int n_l, int8_t* __restrict__ Mc,
-                                                           int32_t* __restrict__ row_idx) {
+                                                           int32_t* __restrict__ row_idx,
+                                                           int32_t* __restrict__ col_cnt) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const long row = (long)blockIdx.x * 4 + wave;
   if (row >= rows) return;   // (no barriers in this kernel)
+  if (lane == 0) col_cnt[row] = 0;   // one counter per (head, block), cleared for the column count that follows
   const float* sr = s + (size_t)row * T;
   uint32_t key[KPL];
   int8_t lab[KPL];
@@ -194,13 +196,15 @@ __global__ __launch_bounds__(256) void classify_reg_kernel(const float* __restri
 // One wavefront per row of the score matrix.
 __global__ __launch_bounds__(256) void classify_kernel(const float* __restrict__ s, int rows, int T,
                                                        int n_h, int n_l, int8_t* __restrict__ Mc,
-                                                       int32_t* __restrict__ row_idx) {
+                                                       int32_t* __restrict__ row_idx,
+                                                       int32_t* __restrict__ col_cnt) {
   extern __shared__ unsigned char smem[];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   uint32_t* keys = reinterpret_cast<uint32_t*>(smem) + (size_t)wave * T;
   int8_t* lab = reinterpret_cast<int8_t*>(smem + (size_t)4 * T * sizeof(uint32_t)) + (size_t)wave * T;
   const long row_raw = (long)blockIdx.x * 4 + wave;
   const bool live = row_raw < rows;  // surplus wavefronts redo the last row and store nothing
+  if (live && lane == 0) col_cnt[row_raw] = 0;   // cleared for the column count that follows
   const long row = live ? row_raw : rows - 1;
   const float* sr = s + (size_t)row * T;
   for (int j = lane; j < T; j += 64) {
@@ -228,124 +232,156 @@ __global__ __launch_bounds__(256) void classify_kernel(const float* __restrict__
 }
 
 // ---------------------------------------------------------------- column tables (CSC)
-// Both column kernels: a workgroup owns 32 columns, its 8 wavefront-halves own 8 row ranges;
-// threads of a row range read 32 adjacent bytes of a mask row.
-__global__ __launch_bounds__(256) void col_count_kernel(const int8_t* __restrict__ Mc, int T,
-                                                        int32_t* __restrict__ cnt) {
-  __shared__ int part[8][32];
-  const int c = threadIdx.x & 31, rp = threadIdx.x >> 5;
-  const int j = blockIdx.x * 32 + c, bh = blockIdx.y;
-  const int chunk = (T + 7) / 8, lo = min(T, rp * chunk), hi = min(T, lo + chunk);
-  const int8_t* m = Mc + (size_t)bh * T * T + j;
-  int n = 0;
-  if (j < T)
-    for (int i = lo; i < hi; ++i) n += (m[(size_t)i * T] == 1);
-  part[rp][c] = n;
-  __syncthreads();
-  if (rp == 0 && j < T) {
-    int sum = 0;
-#pragma unroll
-    for (int r = 0; r < 8; ++r) sum += part[r][c];
-    cnt[(size_t)bh * (T + 1) + j] = sum;
+
+// tile[r][c] = Mc[i0 + r][j0 + c] for a 64 x 64 tile, 2 outside the matrix.  When rows are 16-byte
+// aligned (T % 16 == 0) thread t brings piece t % 4 (16 bytes) of row t / 4 in one load.
+__device__ __forceinline__ uint4 mask_piece(const int8_t* __restrict__ src, int T, int i0, int j0, int tid) {
+  const int r = tid >> 2, p = tid & 3;
+  const int i = i0 + r, j = j0 + 16 * p;
+  uint4 v = {0x02020202u, 0x02020202u, 0x02020202u, 0x02020202u};
+  if (i < T && j < T) v = *reinterpret_cast<const uint4*>(src + (size_t)i * T + j);   // (j + 15 < T: T % 16 == 0)
+  return v;
+}
+__device__ __forceinline__ void put_piece(int8_t (*tile)[68], uint4 v, int tid) {
+  uint32_t* dst = reinterpret_cast<uint32_t*>(&tile[tid >> 2][16 * (tid & 3)]);
+  dst[0] = v.x;
+  dst[1] = v.y;
+  dst[2] = v.z;
+  dst[3] = v.w;
+}
+__device__ __forceinline__ void load_mask_tile_bytes(int8_t (*tile)[68], const int8_t* __restrict__ src, int T, int i0,
+                                                     int j0, int l, int w) {
+  for (int r = w; r < 64; r += 4) {
+    const int i = i0 + r, j = j0 + l;
+    tile[r][l] = (i < T && j < T) ? src[(size_t)i * T + j] : (int8_t)2;
   }
 }
 
-// In-place exclusive scan of T counts per head -> T+1 pointers.
-__global__ __launch_bounds__(256) void col_scan_kernel(int32_t* __restrict__ ptr, int T) {
-  __shared__ int part[256];
-  int32_t* p = ptr + (size_t)blockIdx.x * (T + 1);
-  const int tid = threadIdx.x, chunk = (T + 255) / 256;
-  const int lo = min(T, tid * chunk), hi = min(T, lo + chunk);
-  int sum = 0;
-  for (int j = lo; j < hi; ++j) sum += p[j];
-  part[tid] = sum;
-  __syncthreads();
-  if (tid == 0) {
-    int run = 0;
-    for (int t = 0; t < 256; ++t) {
-      const int v = part[t];
-      part[t] = run;
-      run += v;
-    }
-    p[T] = run;
-  }
-  __syncthreads();
-  int run = part[tid];
-  for (int j = lo; j < hi; ++j) {
-    const int v = p[j];
-    p[j] = run;
-    run += v;
-  }
-}
-
-__global__ __launch_bounds__(256) void col_fill_kernel(const int8_t* __restrict__ Mc, int T, int n_h,
-                                                       const int32_t* __restrict__ ptr,
-                                                       int32_t* __restrict__ rows) {
-  __shared__ int part[8][32];
-  const int c = threadIdx.x & 31, rp = threadIdx.x >> 5;
-  const int j = blockIdx.x * 32 + c, bh = blockIdx.y;
-  const int chunk = (T + 7) / 8, lo = min(T, rp * chunk), hi = min(T, lo + chunk);
-  const int8_t* m = Mc + (size_t)bh * T * T + j;
-  int n = 0;
-  if (j < T)
-    for (int i = lo; i < hi; ++i) n += (m[(size_t)i * T] == 1);
-  part[rp][c] = n;
-  __syncthreads();
-  if (j >= T) return;
-  int w = ptr[(size_t)bh * (T + 1) + j];
-  for (int r = 0; r < rp; ++r) w += part[r][c];   // rows of earlier ranges come first: ascending order
-  int32_t* out = rows + (size_t)bh * T * n_h;
-  for (int i = lo; i < hi; ++i)
-    if (m[(size_t)i * T] == 1) out[w++] = i;
-}
-
-// Marginal indicator as bit masks: bit b of ind[i][q] is set iff Mc[i][64 q + b] == 0 (and the
-// column exists), bit b of indT[j][q] iff Mc[64 q + b][j] == 0.  A workgroup takes a 64 x 64 tile
-// of Mc through LDS; each wave votes 16 rows and 16 columns of it into 64-bit words.
+// Marginal indicator as bit masks and the column counts.  Bit b of ind[i][q] is set iff
+// Mc[i][64 q + b] == 0 (and the column exists), bit b of indT[j][q] iff Mc[64 q + b][j] == 0;
+// cnt[j] (cleared by the classification kernel) receives the number of critical blocks of column
+// j.  A workgroup takes a 64 x 64 tile of Mc through LDS; each wave votes 16 rows and 16 columns
+// of it into 64-bit words.
 __global__ __launch_bounds__(256) void indicator_kernel(const int8_t* __restrict__ Mc, int T, int Tw,
                                                         unsigned long long* __restrict__ ind,
-                                                        unsigned long long* __restrict__ indT) {
+                                                        unsigned long long* __restrict__ indT,
+                                                        int32_t* __restrict__ cnt) {
   __shared__ int8_t tile[64][68];
   const int bh = blockIdx.z, i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
   const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int8_t* src = Mc + (size_t)bh * T * T;
-  for (int r = w; r < 64; r += 4) {
-    const int i = i0 + r, j = j0 + l;
-    tile[r][l] = (i < T && j < T && src[(size_t)i * T + j] == 0) ? 1 : 0;
-  }
+  if (T % 16 == 0) put_piece(tile, mask_piece(src, T, i0, j0, threadIdx.x), threadIdx.x);
+  else load_mask_tile_bytes(tile, src, T, i0, j0, l, w);
   __syncthreads();
   for (int r = w; r < 64; r += 4) {
-    const unsigned long long rowbits = __ballot(tile[r][l] != 0);
-    const unsigned long long colbits = __ballot(tile[l][r] != 0);
+    const unsigned long long rowbits = __ballot(tile[r][l] == 0);
+    const int8_t cv = tile[l][r];
+    const unsigned long long colbits = __ballot(cv == 0);
+    const int ncrit = __popcll(__ballot(cv == 1));
     if (l == 0) {
       if (i0 + r < T) ind[((size_t)bh * T + i0 + r) * Tw + blockIdx.x] = rowbits;
-      if (j0 + r < T) indT[((size_t)bh * T + j0 + r) * Tw + blockIdx.y] = colbits;
+      if (j0 + r < T) {
+        indT[((size_t)bh * T + j0 + r) * Tw + blockIdx.y] = colbits;
+        if (ncrit) atomicAdd(cnt + (size_t)bh * T + j0 + r, ncrit);
+      }
     }
   }
 }
 
-// col_order[rank] = j with rank = position of column j under (count descending, index ascending):
-// workgroups of the column-wise backward kernel take the longest lists first.
-__global__ __launch_bounds__(256) void col_order_kernel(const int32_t* __restrict__ ptr, int T,
-                                                        int32_t* __restrict__ order) {
-  // a workgroup ranks 64 columns of one head; four threads share the comparisons of a column
-  extern __shared__ int cnt[];
+// From the column counts of a head: col_ptr (exclusive prefix sums, T + 1 entries), col_order
+// (col_order[rank] = j, rank = position of column j under count descending, index ascending: the
+// column-wise backward kernel takes the longest lists first) and col_rows (the critical rows of
+// every column, ascending).  A workgroup owns 64 columns of one head; every workgroup forms the
+// prefix sum up to its columns from the head's counts by itself.
+__global__ __launch_bounds__(256) void col_tables_kernel(const int8_t* __restrict__ Mc, int T, int n_h,
+                                                         const int32_t* __restrict__ cnt_g,
+                                                         int32_t* __restrict__ ptr, int32_t* __restrict__ order,
+                                                         int32_t* __restrict__ rows) {
+  extern __shared__ int cnt[];          // T counts of the head
   __shared__ int part[4][64];
-  const int32_t* p = ptr + (size_t)blockIdx.y * (T + 1);
-  for (int j = threadIdx.x; j < T; j += 256) cnt[j] = p[j + 1] - p[j];
-  __syncthreads();
-  const int col = threadIdx.x & 63, q = threadIdx.x >> 6;
-  const int j = blockIdx.x * 64 + col;
-  int rank = 0;
-  if (j < T) {
-    const int c = cnt[j];
-    const int chunk = (T + 3) / 4, lo = min(T, q * chunk), hi = min(T, lo + chunk);
-    for (int k = lo; k < hi; ++k) rank += (cnt[k] > c) || (cnt[k] == c && k < j);
+  __shared__ int wsum[4];
+  __shared__ int cptr[64];
+  __shared__ int8_t tile[64][68];
+  const int bh = blockIdx.y, j0 = blockIdx.x * 64;
+  const int tid = threadIdx.x, l = tid & 63, w = tid >> 6;
+  const int32_t* cg = cnt_g + (size_t)bh * T;
+  int before = 0;   // this thread's share of the counts of the columns before j0
+  for (int j = tid; j < T; j += 256) {
+    const int c = cg[j];
+    cnt[j] = c;
+    if (j < j0) before += c;
   }
-  part[q][col] = rank;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) before += __shfl_xor(before, o);
+  if (l == 0) wsum[w] = before;
   __syncthreads();
-  if (q == 0 && j < T)
-    order[(size_t)blockIdx.y * T + part[0][col] + part[1][col] + part[2][col] + part[3][col]] = j;
+  // pointers of this workgroup's columns: wave 0 scans its 64 counts
+  if (w == 0) {
+    const int j = j0 + l;
+    const int c = j < T ? cnt[j] : 0;
+    int incl = c;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int v = __shfl_up(incl, o);
+      if (l >= o) incl += v;
+    }
+    const int p = wsum[0] + wsum[1] + wsum[2] + wsum[3] + incl - c;
+    cptr[l] = p;
+    if (j < T) ptr[(size_t)bh * (T + 1) + j] = p;
+    if (j == T - 1) ptr[(size_t)bh * (T + 1) + T] = p + c;
+  }
+  // rank of this workgroup's columns; four threads share the comparisons of a column
+  {
+    const int j = j0 + l;
+    int rank = 0;
+    if (j < T) {
+      const int c = cnt[j];
+      const int chunk = (T + 3) / 4, lo = min(T, w * chunk), hi = min(T, lo + chunk);
+      for (int k = lo; k < hi; ++k) rank += (cnt[k] > c) || (cnt[k] == c && k < j);
+    }
+    part[w][l] = rank;
+  }
+  __syncthreads();
+  if (w == 0 && j0 + l < T) order[(size_t)bh * T + part[0][l] + part[1][l] + part[2][l] + part[3][l]] = j0 + l;
+  if (n_h == 0) return;
+  // rows of the critical blocks: tiles of 64 rows, wave w votes columns 16 w .. 16 w + 15
+  const int8_t* src = Mc + (size_t)bh * T * T;
+  int32_t* out = rows + (size_t)bh * T * n_h;
+  int run[16];
+#pragma unroll
+  for (int c = 0; c < 16; ++c) run[c] = cptr[16 * w + c];
+  auto vote = [&](int i0) {
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+      const bool crit = tile[l][16 * w + c] == 1;
+      const unsigned long long m = __ballot(crit);
+      if (crit) out[run[c] + __popcll(m & ((1ull << l) - 1ull))] = i0 + l;
+      run[c] += __popcll(m);
+    }
+  };
+  if (T % 16 == 0) {
+    // eight tiles' loads in flight at a time
+    for (int ib = 0; ib < T; ib += 512) {
+      uint4 pre[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) pre[k] = mask_piece(src, T, ib + 64 * k, j0, tid);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        if (ib + 64 * k >= T) break;
+        __syncthreads();   // the previous tile has been read
+        put_piece(tile, pre[k], tid);
+        __syncthreads();
+        vote(ib + 64 * k);
+      }
+    }
+  } else {
+    for (int i0 = 0; i0 < T; i0 += 64) {
+      __syncthreads();   // the previous tile has been read
+      load_mask_tile_bytes(tile, src, T, i0, j0, l, w);
+      __syncthreads();
+      vote(i0);
+    }
+  }
 }
 
 }  // namespace
@@ -376,44 +412,32 @@ hipError_t launch_scores(const float* qbar, const float* kbar, const Shape& s, f
 }
 
 hipError_t launch_classify(const float* scores, const Shape& s, int8_t* Mc, int32_t* row_idx,
-                           hipStream_t st) {
+                           int32_t* col_cnt, hipStream_t st) {
   const int rows = s.BH * s.T;
   const size_t lds = (size_t)4 * s.T * (sizeof(uint32_t) + 1);
   {
     KernelTimer kt("classify", st);
     const dim3 grid((rows + 3) / 4);
-    if (s.T <= 64) classify_reg_kernel<1><<<grid, 256, 0, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx);
-    else if (s.T <= 128) classify_reg_kernel<2><<<grid, 256, 0, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx);
-    else if (s.T <= 256) classify_reg_kernel<4><<<grid, 256, 0, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx);
-    else if (s.T <= 512) classify_reg_kernel<8><<<grid, 256, 0, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx);
-    else classify_kernel<<<grid, 256, lds, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx);
+    if (s.T <= 64) classify_reg_kernel<1><<<grid, 256, 0, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx, col_cnt);
+    else if (s.T <= 128) classify_reg_kernel<2><<<grid, 256, 0, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx, col_cnt);
+    else if (s.T <= 256) classify_reg_kernel<4><<<grid, 256, 0, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx, col_cnt);
+    else if (s.T <= 512) classify_reg_kernel<8><<<grid, 256, 0, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx, col_cnt);
+    else classify_kernel<<<grid, 256, lds, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx, col_cnt);
   }
   return hipGetLastError();
 }
 
-hipError_t launch_csc(const int8_t* Mc, const Shape& s, int32_t* col_ptr, int32_t* col_rows,
+hipError_t launch_csc(const int8_t* Mc, const Shape& s, int32_t* col_cnt, int32_t* col_ptr, int32_t* col_rows,
                       unsigned long long* ind, unsigned long long* indT, int32_t* col_order, hipStream_t st) {
+  const int Tw = (s.T + 63) / 64;
   {
-    const int Tw = (s.T + 63) / 64;
     KernelTimer kt("indicator", st);
-    indicator_kernel<<<dim3(Tw, Tw, s.BH), 256, 0, st>>>(Mc, s.T, Tw, ind, indT);
-  }
-  dim3 grid((s.T + 31) / 32, s.BH);
-  {
-    KernelTimer kt("col_count", st);
-    col_count_kernel<<<grid, 256, 0, st>>>(Mc, s.T, col_ptr);
+    indicator_kernel<<<dim3(Tw, Tw, s.BH), 256, 0, st>>>(Mc, s.T, Tw, ind, indT, col_cnt);
   }
   {
-    KernelTimer kt("col_scan", st);
-    col_scan_kernel<<<s.BH, 256, 0, st>>>(col_ptr, s.T);
-  }
-  {
-    KernelTimer kt("col_order", st);
-    col_order_kernel<<<dim3((s.T + 63) / 64, s.BH), 256, s.T * sizeof(int), st>>>(col_ptr, s.T, col_order);
-  }
-  if (s.n_h > 0) {
-    KernelTimer kt("col_fill", st);
-    col_fill_kernel<<<grid, 256, 0, st>>>(Mc, s.T, s.n_h, col_ptr, col_rows);
+    KernelTimer kt("col_tables", st);
+    col_tables_kernel<<<dim3(Tw, s.BH), 256, s.T * sizeof(int), st>>>(Mc, s.T, s.n_h, col_cnt, col_ptr, col_order,
+                                                                      col_rows);
   }
   return hipGetLastError();
 }

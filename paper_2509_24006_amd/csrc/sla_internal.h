@@ -28,9 +28,10 @@ __device__ __forceinline__ void from_f32(__hip_bfloat16& dst, float x) { dst = _
 hipError_t launch_pool(const void* X, const Shape& s, float* out, hipStream_t st);
 hipError_t launch_scores(const float* qbar, const float* kbar, const Shape& s, float* scores,
                          hipStream_t st);
+// col_cnt: [BH][T] ints of scratch: cleared by the classification, filled by the table build
 hipError_t launch_classify(const float* scores, const Shape& s, int8_t* Mc, int32_t* row_idx,
-                           hipStream_t st);
-hipError_t launch_csc(const int8_t* Mc, const Shape& s, int32_t* col_ptr, int32_t* col_rows,
+                           int32_t* col_cnt, hipStream_t st);
+hipError_t launch_csc(const int8_t* Mc, const Shape& s, int32_t* col_cnt, int32_t* col_ptr, int32_t* col_rows,
                       unsigned long long* ind, unsigned long long* indT, int32_t* col_order, hipStream_t st);
 
 // ---- float-arithmetic path (simt_kernels.hip): every contraction in fp32 FMA
