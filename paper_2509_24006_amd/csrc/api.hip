@@ -142,8 +142,7 @@ int sla_build_mask(const sla_params* p, const void* Q, const void* K, int8_t* Mc
   float* qbar = (float*)(ws + z.ws_mask_qbar);
   float* kbar = (float*)(ws + z.ws_mask_kbar);
   float* sc = (float*)(ws + z.ws_mask_scores);
-  hipError_t e = launch_pool(Q, s, qbar, st);
-  if (e == hipSuccess) e = launch_pool(K, s, kbar, st);
+  hipError_t e = launch_pool(Q, K, s, qbar, kbar, st);
   if (e == hipSuccess) e = launch_scores(qbar, kbar, s, sc, st);
   if (e != hipSuccess) return SLA_EHIP;
   return sla_classify_scores(p, sc, Mc, luts, stream);

@@ -10,29 +10,39 @@ namespace sla {
 namespace {
 
 // ---------------------------------------------------------------- pool
-// One wavefront per token block; lane owns VEC adjacent feature columns and walks the
-// block's rows in order.  Rows are 64*VEC elements, so a wavefront reads whole rows.
-template <typename T, int VEC>
-__global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ X, int nblk, int N, int Tn,
-                                                   float* __restrict__ out) {
-  const int lane = threadIdx.x & 63;
-  const long blk = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+// A lane owns the 16 bytes of a token row that hold V adjacent features and walks the rows of
+// its block in order (the sum over a block's tokens is sequential, see above); D / V lanes cover
+// a block, so a wavefront pools 64 V / D blocks at once and each of its loads fetches whole
+// rows.  blockIdx.y selects the tensor (Q or K).
+template <typename T, int D>
+__global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ X0, const T* __restrict__ X1, int nblk,
+                                                   int N, int Tn, float* __restrict__ out0,
+                                                   float* __restrict__ out1) {
+  constexpr int V = 16 / sizeof(T), LPB = D / V, BPW = 64 / LPB;
+  const T* X = blockIdx.y ? X1 : X0;
+  float* out = blockIdx.y ? out1 : out0;
+  const int lane = threadIdx.x & 63, sub = lane / LPB, fl = lane % LPB;
+  const long blk = ((long)blockIdx.x * 4 + (threadIdx.x >> 6)) * BPW + sub;
   if (blk >= nblk) return;
-  const int d = 64 * VEC;
   const int bh = (int)(blk / Tn), i = (int)(blk % Tn);
   const int cnt = min(kBlk, N - i * kBlk);
-  const T* p = X + ((size_t)bh * N + (size_t)i * kBlk) * d + lane * VEC;
-  float s[VEC];
+  const T* p = X + ((size_t)bh * N + (size_t)i * kBlk) * D + fl * V;
+  float s[V];
 #pragma unroll
-  for (int v = 0; v < VEC; ++v) s[v] = 0.0f;
+  for (int v = 0; v < V; ++v) s[v] = 0.0f;
 #pragma unroll 8
   for (int r = 0; r < cnt; ++r) {
+    const uint4 raw = *reinterpret_cast<const uint4*>(p + (size_t)r * D);
+    const T* e = reinterpret_cast<const T*>(&raw);
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) s[v] = s[v] + to_f32(p[(size_t)r * d + v]);
+    for (int v = 0; v < V; ++v) s[v] = s[v] + to_f32(e[v]);
   }
   const float c = (float)cnt;
+  float* o = out + (size_t)blk * D + fl * V;
 #pragma unroll
-  for (int v = 0; v < VEC; ++v) out[(size_t)blk * d + lane * VEC + v] = __fdiv_rn(s[v], c);
+  for (int v = 0; v < V; v += 4)
+    *reinterpret_cast<float4*>(o + v) = float4{__fdiv_rn(s[v], c), __fdiv_rn(s[v + 1], c), __fdiv_rn(s[v + 2], c),
+                                               __fdiv_rn(s[v + 3], c)};
 }
 
 // ---------------------------------------------------------------- scores
@@ -386,18 +396,21 @@ __global__ __launch_bounds__(256) void col_tables_kernel(const int8_t* __restric
 
 }  // namespace
 
-hipError_t launch_pool(const void* X, const Shape& s, float* out, hipStream_t st) {
+// block means of Q and K (both [BH][N][d]) -> qbar, kbar (float [BH][T][d])
+hipError_t launch_pool(const void* Q, const void* K, const Shape& s, float* qbar, float* kbar, hipStream_t st) {
   const int nblk = s.BH * s.T;
-  dim3 grid((nblk + 3) / 4), block(256);
+  const int bpw = s.dtype == 0 ? 256 / s.d : 512 / s.d;   // blocks per wavefront
+  const dim3 grid((nblk + 4 * bpw - 1) / (4 * bpw), 2), block(256);
   KernelTimer kt("pool", st);
+  typedef __hip_bfloat16 bf;
   if (s.dtype == 0 && s.d == 64)
-    pool_kernel<float, 1><<<grid, block, 0, st>>>((const float*)X, nblk, s.N, s.T, out);
+    pool_kernel<float, 64><<<grid, block, 0, st>>>((const float*)Q, (const float*)K, nblk, s.N, s.T, qbar, kbar);
   else if (s.dtype == 0)
-    pool_kernel<float, 2><<<grid, block, 0, st>>>((const float*)X, nblk, s.N, s.T, out);
+    pool_kernel<float, 128><<<grid, block, 0, st>>>((const float*)Q, (const float*)K, nblk, s.N, s.T, qbar, kbar);
   else if (s.d == 64)
-    pool_kernel<__hip_bfloat16, 1><<<grid, block, 0, st>>>((const __hip_bfloat16*)X, nblk, s.N, s.T, out);
+    pool_kernel<bf, 64><<<grid, block, 0, st>>>((const bf*)Q, (const bf*)K, nblk, s.N, s.T, qbar, kbar);
   else
-    pool_kernel<__hip_bfloat16, 2><<<grid, block, 0, st>>>((const __hip_bfloat16*)X, nblk, s.N, s.T, out);
+    pool_kernel<bf, 128><<<grid, block, 0, st>>>((const bf*)Q, (const bf*)K, nblk, s.N, s.T, qbar, kbar);
   return hipGetLastError();
 }
 

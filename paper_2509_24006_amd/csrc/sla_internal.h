@@ -25,7 +25,7 @@ __device__ __forceinline__ void from_f32(float& dst, float x) { dst = x; }
 __device__ __forceinline__ void from_f32(__hip_bfloat16& dst, float x) { dst = __float2bfloat16(x); }
 
 // ---- mask step (mask_kernels.hip)
-hipError_t launch_pool(const void* X, const Shape& s, float* out, hipStream_t st);
+hipError_t launch_pool(const void* Q, const void* K, const Shape& s, float* qbar, float* kbar, hipStream_t st);
 hipError_t launch_scores(const float* qbar, const float* kbar, const Shape& s, float* scores,
                          hipStream_t st);
 // col_cnt: [BH][T] ints of scratch: cleared by the classification, filled by the table build
