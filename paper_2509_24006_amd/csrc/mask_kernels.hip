@@ -47,12 +47,13 @@ __global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ X0, con
 
 // ---------------------------------------------------------------- scores
 // 64x64 output tile per workgroup, 4x4 outputs per thread, features staged through LDS in
-// chunks of 64; each output keeps one fused multiply-add chain in ascending feature order.
+// chunks of 64 and read four at a time; each output keeps one fused multiply-add chain in
+// ascending feature order.
 __global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ qbar,
                                                     const float* __restrict__ kbar, int T, int d,
                                                     float scale, float* __restrict__ s) {
-  __shared__ float qs[64][65];
-  __shared__ float ks[64][65];
+  __shared__ __attribute__((aligned(16))) float qs[64][68];
+  __shared__ __attribute__((aligned(16))) float ks[64][68];
   const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
   const int bh = blockIdx.z, i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
   const float* qb = qbar + (size_t)bh * T * d;
@@ -63,22 +64,35 @@ __global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ qb
 #pragma unroll
     for (int b = 0; b < 4; ++b) acc[a][b] = 0.0f;
   for (int k0 = 0; k0 < d; k0 += 64) {
-    for (int idx = tid; idx < 64 * 64; idx += 256) {
-      const int r = idx >> 6, c = idx & 63;
-      qs[r][c] = (i0 + r < T) ? qb[(size_t)(i0 + r) * d + k0 + c] : 0.0f;
-      ks[r][c] = (j0 + r < T) ? kb[(size_t)(j0 + r) * d + k0 + c] : 0.0f;
+    // thread t brings 16 bytes: piece t % 16 of rows t / 16 + 16 q (d is a multiple of 64)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int r = (tid >> 4) + 16 * q, c = 4 * (tid & 15);
+      const float4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+      *reinterpret_cast<float4*>(&qs[r][c]) =
+          (i0 + r < T) ? *reinterpret_cast<const float4*>(qb + (size_t)(i0 + r) * d + k0 + c) : zero;
+      *reinterpret_cast<float4*>(&ks[r][c]) =
+          (j0 + r < T) ? *reinterpret_cast<const float4*>(kb + (size_t)(j0 + r) * d + k0 + c) : zero;
     }
     __syncthreads();
-    for (int k = 0; k < 64; ++k) {
-      float av[4], bv[4];
+#pragma unroll 4
+    for (int k = 0; k < 64; k += 4) {
+      float4 av[4], bv[4];
 #pragma unroll
-      for (int a = 0; a < 4; ++a) av[a] = qs[ty + 16 * a][k];
+      for (int a = 0; a < 4; ++a) av[a] = *reinterpret_cast<const float4*>(&qs[ty + 16 * a][k]);
 #pragma unroll
-      for (int b = 0; b < 4; ++b) bv[b] = ks[tx + 16 * b][k];
+      for (int b = 0; b < 4; ++b) bv[b] = *reinterpret_cast<const float4*>(&ks[tx + 16 * b][k]);
 #pragma unroll
       for (int a = 0; a < 4; ++a)
 #pragma unroll
-        for (int b = 0; b < 4; ++b) acc[a][b] = __fmaf_rn(av[a], bv[b], acc[a][b]);
+        for (int b = 0; b < 4; ++b) {
+          float x = acc[a][b];
+          x = __fmaf_rn(av[a].x, bv[b].x, x);
+          x = __fmaf_rn(av[a].y, bv[b].y, x);
+          x = __fmaf_rn(av[a].z, bv[b].z, x);
+          x = __fmaf_rn(av[a].w, bv[b].w, x);
+          acc[a][b] = x;
+        }
     }
     __syncthreads();
   }
