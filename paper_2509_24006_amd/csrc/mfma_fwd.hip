@@ -15,12 +15,13 @@ typedef __hip_bfloat16 bf16;
 // ------------------------------------------------------------------ W^T, k-permuted
 // WTp[e'][16 u + perm16(r)] = W[16 u + r][e']: the A operand of O^l W in the transposed
 // product (O^T = W^T (O^l)^T), whose B operand comes straight out of C registers.
+// (done by one extra workgroup of the state kernel's launch)
 template <int D>
-__global__ void prep_w_kernel(const bf16* __restrict__ W, bf16* __restrict__ WTp) {
-  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= D * D) return;
-  const int e = idx / D, ep = idx - e * D;
-  WTp[ep * D + (e & ~15) + perm16(e & 15)] = W[idx];
+__device__ __forceinline__ void prep_w(const bf16* __restrict__ W, bf16* __restrict__ WTp, int tid) {
+  for (int idx = tid; idx < D * D; idx += 256) {
+    const int e = idx / D, ep = idx - e * D;
+    WTp[ep * D + (e & ~15) + perm16(e & 15)] = W[idx];
+  }
 }
 
 // ------------------------------------------------------------------ key-block states
@@ -33,7 +34,8 @@ __global__ void prep_w_kernel(const bf16* __restrict__ W, bf16* __restrict__ WTp
 template <int D>
 __global__ __launch_bounds__(256, 4) void states_mfma_kernel(const bf16* __restrict__ K,
                                                              const bf16* __restrict__ V, int N, int Tn,
-                                                             int phi, bf16* __restrict__ hz) {
+                                                             int phi, bf16* __restrict__ hz,
+                                                             const bf16* __restrict__ W, bf16* __restrict__ WTp) {
   using T = SwzTile<D>;
   constexpr int NT = D / 32;
   constexpr int STG = 32 * (64 * NT + 16);           // store_rows_bf16<NT> area of one wave
@@ -41,6 +43,10 @@ __global__ __launch_bounds__(256, 4) void states_mfma_kernel(const bf16* __restr
   __shared__ __attribute__((aligned(16))) unsigned char smem[LDSB];
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5;
   const int j = blockIdx.x, bh = blockIdx.y;
+  if (j == Tn) {   // the extra column of the grid: head 0's workgroup prepares the projection matrix
+    if (bh == 0) prep_w<D>(W, WTp, tid);
+    return;
+  }
   const int n0 = j * kBlk, cnt = min(kBlk, N - n0);
   const int ldv = tile_lane_offset<D>(w, l);
   const int wu = wave_uniform(w);
@@ -448,13 +454,9 @@ hipError_t forward_impl(const Shape& s, const FwdArgs& a, bf16* hz16, bf16* WTp,
   float* Zs = reinterpret_cast<float*>(reinterpret_cast<char*>(a.HZ) + state_z_offset(s));
   if (s.n_0 > 0) {
     {
-      KernelTimer kt("prep_w", st);
-      prep_w_kernel<D><<<(D * D + 255) / 256, 256, 0, st>>>((const bf16*)a.W, WTp);
-    }
-    {
       KernelTimer kt("states", st);
-      states_mfma_kernel<D><<<dim3(s.T, s.BH), 256, 0, st>>>((const bf16*)a.K, (const bf16*)a.V, s.N, s.T,
-                                                           s.phi, hz16);
+      states_mfma_kernel<D><<<dim3(s.T + 1, s.BH), 256, 0, st>>>((const bf16*)a.K, (const bf16*)a.V, s.N, s.T,
+                                                               s.phi, hz16, (const bf16*)a.W, WTp);
     }
     SLA_TRY(mfma_aggregate(hz16, a.ind, s, a.HZ, Zs, st));
   } else if (a.Os) {   // saved states must read as zero
