@@ -35,7 +35,10 @@ def kernel_work(name, c):
         "bwd_sparse_kv": ("mfma", 8 * pair),        # S, dP, dV, dK
         "bwd_sparse_q": ("mfma", 2 * pair),         # dQ (S and dP are recomputed there)
         "bwd_sparse": ("mfma", 10 * pair),
-        "aggregate": ("mfma", 2 * c["BH"] * c["T"] * c["T"] * (c["d"] * c["d"] + c["d"])),
+        # indicator GEMM: priced against whichever of its two floors is the higher one
+        "aggregate": max(("mfma", 2 * c["BH"] * c["T"] * c["T"] * (c["d"] * c["d"] + c["d"])),
+                         ("hbm", c["BH"] * c["T"] * (c["d"] * c["d"] + c["d"]) * 2 * c["esize"]),
+                         key=lambda kw: kw[1] / (PEAK_BF16_TFLOPS * 1e12 if kw[0] == "mfma" else PEAK_HBM_GBS * 1e9)),
         "states": ("mfma", 2 * nd2),
         "pool": ("hbm", c["BH"] * c["N"] * c["d"] * c["esize"]),
     }

@@ -174,6 +174,88 @@ __global__ __launch_bounds__(256, 2) void aggregate_mfma_kernel(const bf16* __re
   }
 }
 
+// Short sequences (T <= 64: one k-step, one indicator word per row): a workgroup's four waves
+// take four column tiles of the same 32 MT output rows, each wave with a stage of its own, so
+// that no wave waits for another; the rows of the stage past T are fetched as zeros.
+template <int MT>
+__global__ __launch_bounds__(256, 2) void aggregate_short_kernel(const bf16* __restrict__ in,
+                                                                 const unsigned long long* __restrict__ ind,
+                                                                 int T, int row_len, int dd,
+                                                                 bf16* __restrict__ outH, float* __restrict__ outZ) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
+  const int ct = blockIdx.x * 4 + w, bh = blockIdx.y;
+  if (ct > dd / 128) return;   // (no barriers in this kernel)
+  const bool zpart = ct == dd / 128;
+  const int nbase = ct * 128;
+  const unsigned long long* ib = ind + (size_t)bh * T;
+  const bf16* inb = in + (size_t)bh * T * row_len;
+  const BufDesc rsrc = tile_rsrc(inb, T * row_len * 2);
+  const int pitch = row_len * 2;
+  const int wu = wave_uniform(w);
+  unsigned char* stage = smem + wu * kStage;
+  const unsigned lds0 = lds_base(smem) + wu * kStage;
+  const int nu = (T + 15) / 16;   // 16-row groups that hold valid rows
+  for (int k = 0; k < 4 * nu; ++k) {
+    const int row = 4 * k + (l >> 4), pc = l & 15;
+    load_to_lds16(rsrc, row * pitch + nbase * 2 + ((pc ^ swz<128>(row)) << 4), 0, lds0 + k * 1024);
+  }
+  unsigned long long wb[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) wb[mt] = (ln + 32 * mt < T) ? ib[ln + 32 * mt] : 0ull;
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) pin_loaded(wb[mt]);
+  wait_vm0();
+  TileAddr<128> ad;
+  ad.init(0, l);
+  constexpr int RB = 16 * SwzTile<128>::ROW_BYTES;
+  f32x16 acc[MT][4];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = zero_f32x16();
+  for (int u = 0; u < nu; ++u) {
+    bf16x8 b[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const unsigned long long x = wb[mt] >> (4 * g);
+      const unsigned half = (unsigned)(x >> (16 * u));   // u < 4: bits 16 u + 4 g ..
+      u32x4 packed = {bits2bf(half, 0), bits2bf(half, 2), bits2bf(half, 8), bits2bf(half, 10)};
+      b[mt] = *reinterpret_cast<bf16x8*>(&packed);
+    }
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) {
+      const bf16x8 a = lds_tr<128>(stage, ad.tr(0, nt) + u * RB, ad.tr(1, nt) + u * RB);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = mfma32(a, b[mt], acc[mt][nt]);
+    }
+  }
+  if (zpart) {
+    const int dz = row_len - dd;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int row = ln + 32 * mt;
+      if (row >= T) continue;
+      float* o = outZ + ((size_t)bh * T + row) * dz;
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const int c = 32 * nt + 8 * r4 + 4 * g;
+          if (c < dz)
+            *reinterpret_cast<f32x4*>(o + c) = f32x4{acc[mt][nt][4 * r4], acc[mt][nt][4 * r4 + 1],
+                                                      acc[mt][nt][4 * r4 + 2], acc[mt][nt][4 * r4 + 3]};
+        }
+    }
+  } else {
+    // the wave's own stage becomes its staging area (LDS serves a wave's accesses in order)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+      if (32 * mt < T)
+        store_rows_bf16<4>(stage, acc[mt], outH + ((size_t)bh * T + 32 * mt) * dd + nbase, dd, T - 32 * mt, l);
+  }
+}
+
 }  // namespace
 
 // out[i] = sum over k with bit k of ind[i] set of the bf16 state rows in[k] (d*d + d values each);
@@ -189,6 +271,14 @@ hipError_t mfma_aggregate(const void* in, const unsigned long long* ind, const S
   if (e != hipSuccess) return e;
   const int mtiles = (s.T + kAggRows - 1) / kAggRows;
   const int ntile = dd / 128 + 1;
+  if (s.T <= 64) {
+    auto kern = s.T <= 32 ? aggregate_short_kernel<1> : aggregate_short_kernel<2>;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kAggLds);
+    if (e != hipSuccess) return e;
+    KernelTimer kt("aggregate", st);
+    kern<<<dim3((ntile + 3) / 4, s.BH), 256, kAggLds, st>>>((const bf16*)in, ind, s.T, row_len, dd, (bf16*)outH, outZ);
+    return hipGetLastError();
+  }
   {
     KernelTimer kt("aggregate", st);
     aggregate_mfma_kernel<<<dim3(8 * ((ntile + 7) / 8) * mtiles, s.BH), 256, kAggLds, st>>>(

@@ -4,7 +4,7 @@ This module holds no arithmetic of the method itself: it only draws the tensors
 that both the HIP path and the CPU oracle are fed with.  The inputs stand in for
 the attention activations of a video diffusion transformer (Section 6.1 of the
 paper uses Wan2.1-1.3B: 12 heads of 128, about 32K tokens, 64x64 blocks,
-k_h=5%, k_l=10%): tokens live on a (t, h, w) grid in raster order, and Q/K/V are
+k_h=5%, k_l=10%; the appendix's image experiment has N = 1024 on a 2-D grid): tokens live on a (t, h, w) grid in raster order, and Q/K/V are
 smooth random Fourier features of the grid position plus white noise, so that
 neighbouring query blocks prefer overlapping key blocks the way real video
 attention does.
@@ -64,6 +64,9 @@ WORKLOADS: Dict[str, Workload] = {
     "wan": Workload("wan", 1, 12, 128, (21, 30, 52), "bf16", 0.05, 0.10, seed=BASE_SEED + 2),
     # long-sequence layer
     "long": Workload("long", 1, 40, 128, (21, 45, 80), "bf16", 0.05, 0.10, seed=BASE_SEED + 5),
+    # image-shaped layer (Appendix, image generation: 512 x 512 images -> a 32 x 32 latent grid,
+    # N = 1024, 87.5 % sparsity i.e. k_h = 12.5 %): short sequences, many (batch x head) problems
+    "image": Workload("image", 16, 16, 64, (1, 32, 32), "bf16", 0.125, 0.10, seed=BASE_SEED + 6),
     # reduced-size relatives used by the parity tests (ragged tails, several tiles)
     "small_bf16": Workload("small_bf16", 1, 2, 128, (3, 10, 37), "bf16", 0.10, 0.10,
                            seed=BASE_SEED + 11),

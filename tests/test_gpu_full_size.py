@@ -103,3 +103,33 @@ def test_long_sequence_masks_and_sampled_rows(oracle):
     assert np.isfinite(Og).all() and np.isfinite(f64(dQ)).all() and np.isfinite(f64(dK)).all()
     Vmax, Vmin = x["V"].max(axis=2, keepdims=True), x["V"].min(axis=2, keepdims=True)
     assert np.all(Os <= Vmax + 1e-2) and np.all(Os >= Vmin - 1e-2)   # convex combinations of V rows
+
+
+def test_image_shaped_batch_against_oracle(oracle):
+    # many short (batch x head) problems: all masks bit for bit, forward and backward of the whole
+    # call against the oracle on two batch entries
+    w = wl.WORKLOADS["image"]
+    x_all = wl.make_inputs(w)
+    p, Mc, luts, ws, O, saved, dQ, dK, dV, dW = _gpu_all(x_all, w, w.k_h, w.k_l, w.H)
+    Mo, so = oracle.build_mask(x_all["Q"], x_all["K"], w.k_h, w.k_l, return_scores=True)
+    assert np.array_equal(sla.mask_ws_views(p, ws)["scores"].cpu().numpy(), so)
+    assert np.array_equal(Mc.cpu().numpy(), Mo)
+    v = {k: t.cpu().numpy() for k, t in sla.lut_views(p, luts).items()}
+    check_luts(Mo, v["row_idx"], v["col_ptr"], v["col_rows"], v["ind"], v["ind_t"], v["col_order"])
+    bs = [0, w.B - 1]
+    xs = {k: (np.ascontiguousarray(a[bs]) if a.ndim == 4 else a) for k, a in x_all.items()}
+    f = oracle.forward(xs["Q"], xs["K"], xs["V"], xs["Proj"], Mo[bs])
+    g = oracle.backward(xs["Q"], xs["K"], xs["V"], xs["Proj"], Mo[bs], f, xs["dO"])
+    sv = sla.saved_views(p, saved)
+    tol = TOL["bf16"]
+    for name, got, ref in (("O", O[bs], f["O"]), ("Os", sv["Os"][bs], f["Os"]), ("Ol", sv["Ol"][bs], f["Ol"]),
+                           ("dQ", dQ[bs], g["dQ"]), ("dK", dK[bs], g["dK"]), ("dV", dV[bs], g["dV"])):
+        err = pins.rel_l2(f64(got), ref)
+        print(f"  image {name}: rel_l2 = {err:.3e}", flush=True)
+        assert err <= tol, name
+    # dW sums over every (batch, head): compare against the oracle run on the whole call
+    f_all = oracle.forward(x_all["Q"], x_all["K"], x_all["V"], x_all["Proj"], Mo)
+    g_all = oracle.backward(x_all["Q"], x_all["K"], x_all["V"], x_all["Proj"], Mo, f_all, x_all["dO"])
+    err = pins.rel_l2(f64(dW), g_all["dW"])
+    print(f"  image dW: rel_l2 = {err:.3e}", flush=True)
+    assert err <= tol

@@ -91,6 +91,16 @@ def test_short_sequences(oracle, N):
     _full_case(oracle, x, "fp32", 0.34, 0.34, floor_rms=0.05)
 
 
+@pytest.mark.parametrize("N,d", [(2565, 128), (4096, 64), (2048, 128)])
+def test_bf16_mid_length_sequences(oracle, N, d):
+    # 33..64 blocks: the short-sequence state aggregation with two row tiles, a ragged tail and
+    # an exact multiple of the block size
+    rng = np.random.default_rng(N + d)
+    x = {k: wl.round_to_bf16(rng.standard_normal((1, 2, N, d)).astype(np.float32)) for k in ("Q", "K", "V", "dO")}
+    x["Proj"] = wl.round_to_bf16((rng.standard_normal((d, d)) * 0.05).astype(np.float32))
+    _full_case(oracle, x, "bf16", 0.1, 0.2)
+
+
 def test_classify_given_scores_with_ties(oracle):
     from paper_2509_24006_amd import binding as sla
     rng = np.random.default_rng(0)
