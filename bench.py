@@ -54,6 +54,8 @@ def main() -> int:
     ap.add_argument("--k-h", type=float, default=None)
     ap.add_argument("--dense-steps", type=int, default=1, help="0 skips the dense reference run")
     ap.add_argument("--cpu-heads", type=int, default=4, help="0 skips the CPU oracle baseline")
+    ap.add_argument("--token-major", action="store_true",
+                    help="hand the library [B,N,H,d] tensors (SLA_BNHD) instead of [B,H,N,d]")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="run one float add over this many MiB first: a kernel of known HBM traffic that "
                          "calibrates the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -78,8 +80,12 @@ def main() -> int:
     t0 = time.time()
     x = wl.make_inputs(w)
     dev = {k: torch.from_numpy(v).to(tdt).cuda() for k, v in x.items()}
+    if args.token_major:
+        dev = {k: (v.transpose(1, 2).contiguous() if v.ndim == 4 else v) for k, v in dev.items()}
     Q, K, V, W, dO = dev["Q"], dev["K"], dev["V"], dev["Proj"], dev["dO"]
     t_gen = time.time() - t0
+
+    lay = sla.SLA_BNHD if args.token_major else sla.SLA_BHND
 
     def buffers(p):
         z = sla.sla_sizes(p)
@@ -119,7 +125,7 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    p = sla.make_params(w.B, w.H, w.N, w.d, w.k_h, w.k_l, tdt)
+    p = sla.make_params(w.B, w.H, w.N, w.d, w.k_h, w.k_l, tdt, layout=lay)
     b = buffers(p)
     mask, fwd, bwd = phases(p, b)
 
@@ -182,7 +188,7 @@ def main() -> int:
     # dense reference on the same GPU: the same library with every block critical
     dense = None
     if args.dense_steps > 0 and w.k_h < 1.0:
-        pd = sla.make_params(w.B, w.H, w.N, w.d, 1.0, 0.0, tdt)
+        pd = sla.make_params(w.B, w.H, w.N, w.d, 1.0, 0.0, tdt, layout=lay)
         bd = buffers(pd)
         dm, df, db = phases(pd, bd)
         dm(); torch.cuda.synchronize()
@@ -219,6 +225,7 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype,
         "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} H={w.H} d={w.d} N={w.N} grid={w.grid} block=64 "
+                               f"tensors={'[B,N,H,d]' if args.token_major else '[B,H,N,d]'} "
                                f"k_h={w.k_h} k_l={w.k_l} phi=softmax; n_h={z.n_h} n_l={z.n_l} "
                                f"n_0={z.n_0}; seeded Fourier-feature Q/K/V stand in for Wan2.1 activations"},
         "ms": {"step_wall": ms_step, "mask": ms_mask, "forward": ms_fwd, "backward": ms_bwd},

@@ -1,7 +1,7 @@
 /* sla.h - C ABI of the MI355X sparse-linear attention (SLA) library.
  *
  * SLA (arxiv 2509.24006) computes, per batch and head, for Q, K, V in R^{N x d}
- * (Section 2.1; tensors here are packed [B, H, N, d], d contiguous):
+ * (Section 2.1; tensors here are packed [B, H, N, d] or [B, N, H, d], d contiguous):
  *
  *   1. block scores  s = pool(Q) pool(K)^T / sqrt(d), pool = mean over each block of
  *      b = 64 consecutive tokens (Eq. 2; the last block may be short);
@@ -45,6 +45,7 @@ extern "C" {
 enum { SLA_OK = 0, SLA_EINVAL = -1, SLA_EUNSUPPORTED = -2, SLA_ENOSPACE = -3, SLA_EHIP = -4 };
 enum { SLA_PHI_SOFTMAX = 0, SLA_PHI_ELU1 = 1 };   /* feature map of the linear branch */
 enum { SLA_F32 = 0, SLA_BF16 = 1 };               /* storage type of Q,K,V,W,O,dO,dQ,dK,dV */
+enum { SLA_BHND = 0, SLA_BNHD = 1 };              /* memory order of Q,K,V,O,dO,dQ,dK,dV          */
 
 /* Problem statement (Alg. 1 input line: Q, K, V, block sizes, k_h, k_l; Section 6.1: phi). */
 typedef struct sla_params {
@@ -53,6 +54,10 @@ typedef struct sla_params {
   double k_h, k_l;    /* fractions in [0, 1] of critical / negligible blocks per row       */
   int32_t phi;        /* SLA_PHI_*                                                         */
   int32_t dtype;      /* SLA_F32 or SLA_BF16; statistics and dW are always float           */
+  int32_t layout;     /* SLA_BHND: Q,K,V,O,dO,dQ,dK,dV packed [B,H,N,d]; SLA_BNHD: packed
+                         [B,N,H,d] (token-major, as a transformer block's projections leave
+                         them; bf16 tensors only).  Masks, tables, saved tensors and
+                         workspaces are per (b, h) in either case.                          */
 } sla_params;
 
 /* Derived sizes and the layout of the opaque buffers (all offsets in bytes).
@@ -62,7 +67,7 @@ typedef struct sla_params {
 typedef struct sla_sizes_t {
   int32_t T, n_h, n_l, n_0;
   uint64_t mask_bytes;        /* int8  [B,H,T,T]                                            */
-  uint64_t luts_bytes;
+  uint64_t luts_bytes;        /* the buffer ends with scratch of the table build             */
   uint64_t lut_row_idx;       /* int32 [B,H,T,n_h]   ascending critical key blocks per row  */
   uint64_t lut_col_ptr;       /* int32 [B,H,T+1]     CSC pointers of the critical entries   */
   uint64_t lut_col_rows;      /* int32 [B,H,T*n_h]   ascending query blocks per key block   */
@@ -70,7 +75,7 @@ typedef struct sla_sizes_t {
   uint64_t lut_ind_t;         /* uint64 [B,H,T,Tw]   the same, transposed: bit b of [j][q]: M_c[64q+b][j] = 0 */
   uint64_t lut_col_order;     /* int32 [B,H,T]       key blocks by descending column count  */
   uint64_t saved_bytes;
-  uint64_t saved_Os;          /* dtype [B,H,N,d]     O^s                                    */
+  uint64_t saved_Os;          /* dtype [B,H,N,d]     O^s (this order whatever the layout)   */
   uint64_t saved_Ol;          /* dtype [B,H,N,d]     O^l                                    */
   uint64_t saved_L;           /* float [B,H,N]       L = m + log l                          */
   uint64_t saved_HZ;          /* float tensors: float [B,H,T] state rows (H_i transposed, then Z_i);
@@ -89,7 +94,7 @@ typedef struct sla_sizes_t {
 int sla_sizes(const sla_params* p, sla_sizes_t* out);
 
 /* Eq. 2 - Eq. 3 and the lookup tables of Appendix A.3.
- * Q, K: dtype [B,H,N,d].  Mc: int8 [B,H,T,T] (out).  luts: luts_bytes (out).
+ * Q, K: dtype [B,H,N,d] (or [B,N,H,d], see sla_params.layout).  Mc: int8 [B,H,T,T] (out).  luts: luts_bytes (out).
  * workspace: >= ws_mask_bytes; on return it holds pool(Q), pool(K) and s at the offsets
  * above.  Scores are computed in float in one fixed order (sequential sum over a block's
  * tokens, IEEE division by the token count, fused multiply-add chain over the features,
@@ -100,7 +105,7 @@ int sla_build_mask(const sla_params* p, const void* Q, const void* K, int8_t* Mc
 /* Eq. 3 alone: classify given float scores s [B,H,T,T] (device) and build the tables. */
 int sla_classify_scores(const sla_params* p, const float* s, int8_t* Mc, void* luts, void* stream);
 
-/* Algorithm 1 + Eq. 6.  Q, K, V, O: dtype [B,H,N,d]; W: dtype [d,d] row-major,
+/* Algorithm 1 + Eq. 6.  Q, K, V, O: dtype [B,H,N,d] (or [B,N,H,d]); W: dtype [d,d] row-major,
  * O = O^s + O^l W.  Mc, luts: from sla_build_mask for the same params.
  * saved: saved_bytes (out) for sla_backward, or NULL for inference.
  * workspace: >= ws_forward_bytes. */
@@ -109,7 +114,7 @@ int sla_forward(const sla_params* p, const void* Q, const void* K, const void* V
                 size_t workspace_bytes, void* stream);
 
 /* Algorithm 2, with dQ, dK scaled by 1/sqrt(d), dV accumulated over both branches, and the
- * chain rule through phi and W.  dO, dQ, dK, dV: dtype [B,H,N,d]; dW: float [d,d] (out,
+ * chain rule through phi and W.  dO, dQ, dK, dV: dtype [B,H,N,d] (or [B,N,H,d]); dW: float [d,d] (out,
  * summed over batch, heads and tokens).  saved: as written by sla_forward with the same
  * inputs.  workspace: >= ws_backward_bytes. */
 int sla_backward(const sla_params* p, const void* Q, const void* K, const void* V, const void* W,

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libsla_hip.so")
 
 SLA_F32, SLA_BF16 = 0, 1
 SLA_PHI_SOFTMAX, SLA_PHI_ELU1 = 0, 1
+SLA_BHND, SLA_BNHD = 0, 1
 EXPORTS = ("sla_sizes", "sla_build_mask", "sla_classify_scores", "sla_forward", "sla_backward",
            "sla_profile_enable", "sla_profile_read", "sla_strerror")
 
@@ -26,7 +27,7 @@ class sla_params(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32),
                 ("d", ctypes.c_int32), ("bq", ctypes.c_int32), ("bkv", ctypes.c_int32),
                 ("k_h", ctypes.c_double), ("k_l", ctypes.c_double), ("phi", ctypes.c_int32),
-                ("dtype", ctypes.c_int32)]
+                ("dtype", ctypes.c_int32), ("layout", ctypes.c_int32)]
 
 
 class sla_sizes_t(ctypes.Structure):
@@ -76,9 +77,11 @@ def _check(rc: int, what: str) -> None:
 
 
 def make_params(B: int, H: int, N: int, d: int, k_h: float, k_l: float, dtype: torch.dtype,
-                phi: int = SLA_PHI_SOFTMAX, bq: int = 64, bkv: int = 64) -> sla_params:
+                phi: int = SLA_PHI_SOFTMAX, bq: int = 64, bkv: int = 64,
+                layout: int = SLA_BHND) -> sla_params:
+    """layout: SLA_BHND ([B,H,N,d] tensors) or SLA_BNHD ([B,N,H,d], bf16 only)."""
     code = {torch.float32: SLA_F32, torch.bfloat16: SLA_BF16}[dtype]
-    return sla_params(B, H, N, d, bq, bkv, k_h, k_l, phi, code)
+    return sla_params(B, H, N, d, bq, bkv, k_h, k_l, phi, code, layout)
 
 
 def sla_sizes(p: sla_params) -> sla_sizes_t:
@@ -100,7 +103,7 @@ def _buf(nbytes: int, device) -> torch.Tensor:
 
 
 def _dense(t: torch.Tensor, p: sla_params, what: str) -> torch.Tensor:
-    want = (p.B, p.H, p.N, p.d)
+    want = (p.B, p.N, p.H, p.d) if p.layout == SLA_BNHD else (p.B, p.H, p.N, p.d)
     if tuple(t.shape) != want or not t.is_contiguous() or not t.is_cuda:
         raise SLAError(f"{what}: expected a contiguous device tensor of shape {want}")
     return t

@@ -20,6 +20,8 @@ int make_shape(const sla_params* p, Shape* s) {
   if (p->d != 64 && p->d != 128) return SLA_EUNSUPPORTED;
   if (p->phi != SLA_PHI_SOFTMAX && p->phi != SLA_PHI_ELU1) return SLA_EUNSUPPORTED;
   if (p->dtype != SLA_F32 && p->dtype != SLA_BF16) return SLA_EUNSUPPORTED;
+  if (p->layout != SLA_BHND && p->layout != SLA_BNHD) return SLA_EUNSUPPORTED;
+  if (p->layout == SLA_BNHD && p->dtype != SLA_BF16) return SLA_EUNSUPPORTED;
   const long long T = ((long long)p->N + kBlk - 1) / kBlk;
   if (T > kMaxT) return SLA_EUNSUPPORTED;
   if ((long long)p->B * p->H > 65535) return SLA_EUNSUPPORTED;  // grid.y / grid.z limit
@@ -36,6 +38,8 @@ int make_shape(const sla_params* p, Shape* s) {
   s->n_0 = (int)(T - nh - nl);
   s->phi = p->phi;
   s->dtype = p->dtype;
+  s->H = p->H;
+  s->layout = p->layout;
   s->scale = 1.0f / sqrtf((float)p->d);
   return SLA_OK;
 }

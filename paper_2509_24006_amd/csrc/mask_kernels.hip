@@ -16,7 +16,7 @@ namespace {
 // rows.  blockIdx.y selects the tensor (Q or K).
 template <typename T, int D>
 __global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ X0, const T* __restrict__ X1, int nblk,
-                                                   int N, int Tn, float* __restrict__ out0,
+                                                   int N, int Tn, Lay lay, float* __restrict__ out0,
                                                    float* __restrict__ out1) {
   constexpr int V = 16 / sizeof(T), LPB = D / V, BPW = 64 / LPB;
   const T* X = blockIdx.y ? X1 : X0;
@@ -26,13 +26,13 @@ __global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ X0, con
   if (blk >= nblk) return;
   const int bh = (int)(blk / Tn), i = (int)(blk % Tn);
   const int cnt = min(kBlk, N - i * kBlk);
-  const T* p = X + ((size_t)bh * N + (size_t)i * kBlk) * D + fl * V;
+  const T* p = X + lay.head(bh) + (size_t)i * kBlk * lay.ts + fl * V;
   float s[V];
 #pragma unroll
   for (int v = 0; v < V; ++v) s[v] = 0.0f;
 #pragma unroll 8
   for (int r = 0; r < cnt; ++r) {
-    const uint4 raw = *reinterpret_cast<const uint4*>(p + (size_t)r * D);
+    const uint4 raw = *reinterpret_cast<const uint4*>(p + (size_t)r * lay.ts);
     const T* e = reinterpret_cast<const T*>(&raw);
 #pragma unroll
     for (int v = 0; v < V; ++v) s[v] = s[v] + to_f32(e[v]);
@@ -418,13 +418,13 @@ hipError_t launch_pool(const void* Q, const void* K, const Shape& s, float* qbar
   KernelTimer kt("pool", st);
   typedef __hip_bfloat16 bf;
   if (s.dtype == 0 && s.d == 64)
-    pool_kernel<float, 64><<<grid, block, 0, st>>>((const float*)Q, (const float*)K, nblk, s.N, s.T, qbar, kbar);
+    pool_kernel<float, 64><<<grid, block, 0, st>>>((const float*)Q, (const float*)K, nblk, s.N, s.T, s.lay(), qbar, kbar);
   else if (s.dtype == 0)
-    pool_kernel<float, 128><<<grid, block, 0, st>>>((const float*)Q, (const float*)K, nblk, s.N, s.T, qbar, kbar);
+    pool_kernel<float, 128><<<grid, block, 0, st>>>((const float*)Q, (const float*)K, nblk, s.N, s.T, s.lay(), qbar, kbar);
   else if (s.d == 64)
-    pool_kernel<bf, 64><<<grid, block, 0, st>>>((const bf*)Q, (const bf*)K, nblk, s.N, s.T, qbar, kbar);
+    pool_kernel<bf, 64><<<grid, block, 0, st>>>((const bf*)Q, (const bf*)K, nblk, s.N, s.T, s.lay(), qbar, kbar);
   else
-    pool_kernel<bf, 128><<<grid, block, 0, st>>>((const bf*)Q, (const bf*)K, nblk, s.N, s.T, qbar, kbar);
+    pool_kernel<bf, 128><<<grid, block, 0, st>>>((const bf*)Q, (const bf*)K, nblk, s.N, s.T, s.lay(), qbar, kbar);
   return hipGetLastError();
 }
 

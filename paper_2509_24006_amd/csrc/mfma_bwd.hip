@@ -59,7 +59,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
     const bf16* __restrict__ dO, const float* __restrict__ L, const float* __restrict__ Ds,
     const int32_t* __restrict__ col_ptr, const int32_t* __restrict__ col_rows,
     const int32_t* __restrict__ col_order, const bf16* __restrict__ dHcol,
-    const float* __restrict__ dZcol, int N, int Tn, int n_h, float scale,
+    const float* __restrict__ dZcol, int N, int Tn, Lay lay, int n_h, float scale,
     bf16* __restrict__ dK, bf16* __restrict__ dV) {
   using Lds = KvLds<D>;
   using T = SwzTile<D>;
@@ -105,8 +105,10 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
   const int32_t* list = col_rows + (size_t)bh * Tn * n_h;
   const int beg = ptr[j], cnt = ptr[j + 1] - beg;
   const float sl2 = scale * kLog2e, rscale = 1.0f / scale;
-  const bf16* Qb = Q + (size_t)bh * N * D;
-  const bf16* dOb = dO + (size_t)bh * N * D;
+  TileLoader<D> tl;   // tiles of the caller's tensors (ldv, lds0 below: the library's packed ones)
+  tl.init(lds_base(smem), w, l, 2 * lay.ts);
+  const BufDesc descQ = head_rsrc<D>(Q + lay.head(bh), N, 2 * lay.ts);
+  const BufDesc descG = head_rsrc<D>(dO + lay.head(bh), N, 2 * lay.ts);
   const float* Lb = L + (size_t)bh * N;
   const float* Dsb = Ds + (size_t)bh * N;
   const int ldv = tile_lane_offset<D>(w, l);
@@ -122,8 +124,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
     const int ii = inext;
     inext = list[beg + min(s + 1, cnt - 1)];
     const int rows = min(kBlk, N - ii * kBlk);
-    issue_tile_load<D>(Qb + (size_t)ii * kBlk * D, rows, lds0, off, ldv);
-    issue_tile_load<D>(dOb + (size_t)ii * kBlk * D, rows, lds0, off + Lds::TILE, ldv);
+    tl.load(descQ, ii, off);
+    tl.load(descG, ii, off + Lds::TILE);
     const int qq = 32 * xh + (lane_id() & 31);
     lreg = load_f32_or_zero(Lb + (size_t)ii * kBlk, rows, qq);
     dreg = load_f32_or_zero(Dsb + (size_t)ii * kBlk, rows, qq);
@@ -134,8 +136,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
   // in the Q slot, the rest in the dO slot), K_j and V_j through the first, which is handed to the
   // first pair's tiles as soon as the operands are in registers; dZ_j goes to registers directly.
   const int kvoff = dHcol ? 0 : Lds::BUF;
-  issue_tile_load<D>(K + ((size_t)bh * N + k0) * D, cols, lds0, kvoff, ldv);
-  issue_tile_load<D>(V + ((size_t)bh * N + k0) * D, cols, lds0, kvoff + Lds::TILE, ldv);
+  tl.load(head_rsrc<D>(K + lay.head(bh), N, 2 * lay.ts), j, kvoff);
+  tl.load(head_rsrc<D>(V + lay.head(bh), N, 2 * lay.ts), j, kvoff + Lds::TILE);
   f32x4 z4[HT][4];
   if (dHcol) {
     const bf16* M = dHcol + ((size_t)bh * Tn + j) * (D * D);
@@ -354,13 +356,13 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
   // through its own staging area
   __syncthreads();   // every wave is done with the tiles
   unsigned char* stage = smem + wu * Lds::STG;
-  const size_t o0 = ((size_t)bh * N + k0 + 32 * kh) * D + (D / 2) * xh;
-  store_rows_bf16<HT>(stage, dvT, dV + o0, D, cols - 32 * kh, l);
+  const size_t o0 = lay.head(bh) + (size_t)(k0 + 32 * kh) * lay.ts + (D / 2) * xh;
+  store_rows_bf16<HT>(stage, dvT, dV + o0, lay.ts, cols - 32 * kh, l);
 #pragma unroll
   for (int dt = 0; dt < HT; ++dt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) dkT[dt][r] *= scale;
-  store_rows_bf16<HT>(stage, dkT, dK + o0, D, cols - 32 * kh, l);
+  store_rows_bf16<HT>(stage, dkT, dK + o0, lay.ts, cols - 32 * kh, l);
 }
 
 // ------------------------------------------------------------------ dQ
@@ -371,7 +373,7 @@ template <int D>
 __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
     const bf16* __restrict__ dO, const float* __restrict__ L, const float* __restrict__ Ds,
-    const int32_t* __restrict__ row_idx, const float* __restrict__ dQlin, int N, int Tn, int n_h,
+    const int32_t* __restrict__ row_idx, const float* __restrict__ dQlin, int N, int Tn, Lay lay, int n_h,
     float scale, bf16* __restrict__ dQ) {
   using Lds = PairLds<D>;
   using T = SwzTile<D>;
@@ -386,24 +388,22 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(
   const int qrow = qh * 32 + ln;
   const bool qok = qrow < rows;
   const int32_t* lut = row_idx + ((size_t)bh * Tn + i) * n_h;
-  const bf16* Kb = K + (size_t)bh * N * D;
-  const bf16* Vb = V + (size_t)bh * N * D;
   const float sl2 = scale * kLog2e;
-  const int ldv = tile_lane_offset<D>(w, l);
-  const unsigned lds0 = lds_base(smem) + wave_uniform(w) * 1024;
+  TileLoader<D> tl;
+  tl.init(lds_base(smem), w, l, 2 * lay.ts);
+  const BufDesc descK = head_rsrc<D>(K + lay.head(bh), N, 2 * lay.ts);
+  const BufDesc descV = head_rsrc<D>(V + lay.head(bh), N, 2 * lay.ts);
   // key block indices of steps s, s + 1, s + 2, fetched a step before the loads that need them
   int j0 = 0, j1 = 0, j2 = 0;
   auto issue = [&](int jj, const int bufi) __attribute__((always_inline)) {
-    const int cols = min(kBlk, N - jj * kBlk);
-    issue_tile_load<D>(Kb + (size_t)jj * kBlk * D, cols, lds0, bufi * Lds::BUF, ldv);
-    issue_tile_load<D>(Vb + (size_t)jj * kBlk * D, cols, lds0, bufi * Lds::BUF + Lds::TILE, ldv);
+    tl.load(descK, jj, bufi * Lds::BUF);
+    tl.load(descV, jj, bufi * Lds::BUF + Lds::TILE);
   };
   // Q_i and dO_i come in as tiles through the second pair buffer (whole rows per load, zeros past
   // the end of the sequence) and are picked up from there in operand layout
   {
-    const size_t base = ((size_t)bh * N + q0) * D;
-    issue_tile_load<D>(Q + base, rows, lds0, Lds::BUF, ldv);
-    issue_tile_load<D>(dO + base, rows, lds0, Lds::BUF + Lds::TILE, ldv);
+    tl.load(head_rsrc<D>(Q + lay.head(bh), N, 2 * lay.ts), i, Lds::BUF);
+    tl.load(head_rsrc<D>(dO + lay.head(bh), N, 2 * lay.ts), i, Lds::BUF + Lds::TILE);
   }
   if (n_h > 0) {
     j0 = lut[0];
@@ -520,11 +520,11 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(
       const size_t o = ((size_t)bh * N + q0 + row) * D + 4 * c4;
       const f32x4 sv = *reinterpret_cast<const f32x4*>(stg + row * SP + 4 * c4);
       f32x4 lq = {0.0f, 0.0f, 0.0f, 0.0f};
-      if (dQlin) lq = *reinterpret_cast<const f32x4*>(dQlin + o);
+      if (dQlin) lq = *reinterpret_cast<const f32x4*>(dQlin + o);   // (the library's own tensor: packed)
       bf16x4 pk;
 #pragma unroll
       for (int r = 0; r < 4; ++r) pk[r] = (__bf16)(sv[r] * scale + lq[r]);
-      *reinterpret_cast<bf16x4*>(dQ + o) = pk;
+      *reinterpret_cast<bf16x4*>(dQ + lay.head(bh) + (size_t)(q0 + row) * lay.ts + 4 * c4) = pk;
     }
   }
 }
@@ -546,7 +546,7 @@ hipError_t sparse_impl(const Shape& s, const BwdArgs& a, const float* Ds, const 
     KernelTimer kt("bwd_sparse_kv", st);
     kern<<<dim3(s.T * s.BH), 256, KvLds<D>::BYTES, st>>>(
         (const bf16*)a.Q, (const bf16*)a.K, (const bf16*)a.V, (const bf16*)a.dO, a.L, Ds, a.col_ptr, a.col_rows,
-        a.col_order, (const bf16*)dHZcol, dZcol, s.N, s.T, s.n_h, s.scale, (bf16*)a.dK, (bf16*)a.dV);
+        a.col_order, (const bf16*)dHZcol, dZcol, s.N, s.T, s.lay(), s.n_h, s.scale, (bf16*)a.dK, (bf16*)a.dV);
     return hipSuccess;
   };
   SLA_TRY(s.phi == 0 ? launch_kv(bwd_dkdv_mfma_kernel<D, 0>) : launch_kv(bwd_dkdv_mfma_kernel<D, 1>));
@@ -556,7 +556,7 @@ hipError_t sparse_impl(const Shape& s, const BwdArgs& a, const float* Ds, const 
     KernelTimer kt("bwd_sparse_q", st);
     bwd_dq_mfma_kernel<D><<<dim3(xcd_grid(s.T), s.BH), 256, lds, st>>>(
         (const bf16*)a.Q, (const bf16*)a.K, (const bf16*)a.V, (const bf16*)a.dO, a.L, Ds, a.row_idx,
-        dQlin, s.N, s.T, s.n_h, s.scale, (bf16*)a.dQ);
+        dQlin, s.N, s.T, s.lay(), s.n_h, s.scale, (bf16*)a.dQ);
   }
   return hipGetLastError();
 }

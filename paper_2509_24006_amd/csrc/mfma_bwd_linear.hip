@@ -34,7 +34,7 @@ __global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ dO, const bf16* __restrict__ W,
     const bf16* __restrict__ Os, const bf16* __restrict__ Ol, const bf16* __restrict__ H16,
     const float* __restrict__ Zs, int N,
-    int Tn, int n_0, int phi, float* __restrict__ Ds, bf16* __restrict__ dHZ,
+    int Tn, Lay lay, int n_0, int phi, float* __restrict__ Ds, bf16* __restrict__ dHZ,
     float* __restrict__ dQlin) {
   using Lds = PreLds<D>;
   using T = SwzTile<D>;
@@ -55,11 +55,13 @@ __global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
   const int wu = wave_uniform(w);
   const unsigned lds0 = lds_base(smem) + wu * 1024;
   const bf16* Hrow = H16 + ((size_t)bh * Tn + i) * (D * D);   // stored [b][c] = H_i[c][b]
-  issue_tile_load<D>(dO + base, rows, lds0, S0, ldv);
+  TileLoader<D> tl;   // tiles of the caller's dO and Q (base: the library's own packed tensors)
+  tl.init(lds_base(smem), w, l, 2 * lay.ts);
+  tl.load(head_rsrc<D>(dO + lay.head(bh), N, 2 * lay.ts), i, S0);
   issue_tile_load<D>(Os + base, rows, lds0, S1, ldv);
   if (n_0 > 0) {
     issue_tile_load<D>(Ol + base, rows, lds0, S2, ldv);
-    issue_tile_load<D>(Q + base, rows, lds0, S3, ldv);
+    tl.load(head_rsrc<D>(Q + lay.head(bh), N, 2 * lay.ts), i, S3);
   }
   wait_vm0();
   __syncthreads();
@@ -242,7 +244,7 @@ __global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
 template <int D>
 __global__ __launch_bounds__(256, 2) void dw_mfma_kernel(const bf16* __restrict__ Ol,
                                                          const bf16* __restrict__ dO, int BH, int N,
-                                                         int Tn, float* __restrict__ part) {
+                                                         int Tn, Lay lay, float* __restrict__ part) {
   using T = SwzTile<D>;
   constexpr int NT = D / 32;
   constexpr int BUF = 2 * T::BYTES;
@@ -251,6 +253,8 @@ __global__ __launch_bounds__(256, 2) void dw_mfma_kernel(const bf16* __restrict_
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
   const int ldv = tile_lane_offset<D>(w, l);
   const unsigned lds0 = lds_base(smem) + wave_uniform(w) * 1024;
+  TileLoader<D> tl;   // tiles of the caller's dO
+  tl.init(lds_base(smem), w, l, 2 * lay.ts);
   f32x16 acc[NT];
 #pragma unroll
   for (int et = 0; et < NT; ++et) acc[et] = zero_f32x16();
@@ -260,7 +264,7 @@ __global__ __launch_bounds__(256, 2) void dw_mfma_kernel(const bf16* __restrict_
     const int rows = min(kBlk, N - i * kBlk);
     const size_t base = ((size_t)bh * N + (size_t)i * kBlk) * D;
     issue_tile_load<D>(Ol + base, rows, lds0, buf * BUF, ldv);
-    issue_tile_load<D>(dO + base, rows, lds0, buf * BUF + T::BYTES, ldv);
+    tl.load(head_rsrc<D>(dO + lay.head(bh), N, 2 * lay.ts), i, buf * BUF + T::BYTES);
   };
   TileAddr<D> ad;
   ad.init(0, l);
@@ -309,12 +313,12 @@ hipError_t pre_impl(const Shape& s, const BwdArgs& a, float* Ds, bf16* dHZ, floa
     KernelTimer kt("bwd_pre", st);
     bwd_pre_mfma_kernel<D><<<dim3(s.T, s.BH), 256, lds, st>>>(
         (const bf16*)a.Q, (const bf16*)a.dO, (const bf16*)a.W, (const bf16*)a.Os, (const bf16*)a.Ol,
-        (const bf16*)a.HZ, (const float*)((const char*)a.HZ + state_z_offset(s)), s.N, s.T, s.n_0, s.phi,
+        (const bf16*)a.HZ, (const float*)((const char*)a.HZ + state_z_offset(s)), s.N, s.T, s.lay(), s.n_0, s.phi,
         Ds, dHZ, dQlin);
   }
   {
     KernelTimer kt("dw_partial", st);
-    dw_mfma_kernel<D><<<nparts, 256, 0, st>>>((const bf16*)a.Ol, (const bf16*)a.dO, s.BH, s.N, s.T, dWpart);
+    dw_mfma_kernel<D><<<nparts, 256, 0, st>>>((const bf16*)a.Ol, (const bf16*)a.dO, s.BH, s.N, s.T, s.lay(), dWpart);
   }
   return hipGetLastError();
 }

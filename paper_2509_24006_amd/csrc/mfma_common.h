@@ -301,45 +301,32 @@ __device__ __forceinline__ void issue_tile_load(const bf16* gbase, int valid_row
   for (int k = 0; k < T::IPW; ++k) load_to_lds16(rsrc, ldv, 4096 * k, lds0 + lds_tile + 4096 * k);
 }
 
-// The same tile load with fewer instructions: wave w fetches a contiguous quarter of the tile
-// (IPW KB) with IPW loads that share one LDS base (M0) and one scalar offset and differ in the
-// instruction's immediate offset, which advances the global and the LDS address alike; the per-lane
-// offsets differ between the loads (the swizzle depends on the row), hence IPW registers.  With a
-// descriptor that spans a whole [rows][D] array the scalar offset selects the tile and rows past
-// the array's end read as zeros.
+// The same for tiles whose rows lie tsB bytes apart in memory (a head of a [B,N,H,d] tensor; tsB =
+// 2 D for packed rows) behind a descriptor that spans the whole head: the scalar offset selects
+// the tile, and rows past the head's end read as zeros.
+template <int D>
+__device__ __forceinline__ BufDesc head_rsrc(const bf16* head_base, int N, int tsB) {
+  return tile_rsrc(head_base, (N - 1) * tsB + 2 * D);
+}
 template <int D>
 struct TileLoader {
   using T = SwzTile<D>;
-  int vo[T::IPW];
-  unsigned m0w;   // LDS address of this wave's quarter of the tile at LDS offset 0
-  __device__ __forceinline__ void init(unsigned lds_base_addr, int w, int l) {
+  int ldv;        // this lane's byte offset inside a tile's memory image
+  int kstep;      // bytes between the rows of two consecutive loads of a wave
+  unsigned ldsw;  // LDS address of this wave's first KB of the tile at LDS offset 0
+  int tile_step;  // bytes between consecutive 64-row tiles
+  __device__ __forceinline__ void init(unsigned lds_base_addr, int w, int l, int tsB) {
+    const int row = T::RPI * w + l / T::CPR;
+    ldv = row * tsB + (((l % T::CPR) ^ swz<D>(row)) << 4);
+    kstep = 4 * T::RPI * tsB;
+    tile_step = kBlk * tsB;
+    ldsw = lds_base_addr + __builtin_amdgcn_readfirstlane(w) * 1024;
+  }
+  // tile number `tile` of the head behind desc -> LDS offset lds_tile
+  __device__ __forceinline__ void load(BufDesc desc, int tile, int lds_tile) const {
 #pragma unroll
     for (int k = 0; k < T::IPW; ++k)
-      vo[k] = swz_chunk_off<D>(T::RPI * (T::IPW * w + k) + l / T::CPR, l % T::CPR) - 1024 * k;
-    m0w = lds_base_addr + __builtin_amdgcn_readfirstlane(w) * (T::IPW * 1024);
-  }
-  // tile at byte offset soff of the array behind desc -> LDS offset lds_tile
-  __device__ __forceinline__ void load(BufDesc desc, int soff, int lds_tile) const {
-    static_assert(T::IPW == 4 || T::IPW == 2, "d = 128 or 64");
-    if constexpr (T::IPW == 4) {
-      asm volatile(
-          "s_mov_b32 m0, %0\n\ts_nop 0\n\t"
-          "buffer_load_dwordx4 %1, %5, %6 offen lds\n\t"
-          "buffer_load_dwordx4 %2, %5, %6 offen offset:1024 lds\n\t"
-          "buffer_load_dwordx4 %3, %5, %6 offen offset:2048 lds\n\t"
-          "buffer_load_dwordx4 %4, %5, %6 offen offset:3072 lds"
-          ::"s"(__builtin_amdgcn_readfirstlane(m0w + lds_tile)), "v"(vo[0]), "v"(vo[1]), "v"(vo[2]), "v"(vo[3]), "s"(desc),
-          "s"(__builtin_amdgcn_readfirstlane(soff))
-          : "memory");
-    } else {
-      asm volatile(
-          "s_mov_b32 m0, %0\n\ts_nop 0\n\t"
-          "buffer_load_dwordx4 %1, %3, %4 offen lds\n\t"
-          "buffer_load_dwordx4 %2, %3, %4 offen offset:1024 lds"
-          ::"s"(__builtin_amdgcn_readfirstlane(m0w + lds_tile)), "v"(vo[0]), "v"(vo[1]), "s"(desc),
-          "s"(__builtin_amdgcn_readfirstlane(soff))
-          : "memory");
-    }
+      load_to_lds16(desc, ldv, tile * tile_step + k * kstep, ldsw + lds_tile + 4096 * k);
   }
 };
 

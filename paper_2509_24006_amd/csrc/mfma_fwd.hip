@@ -33,7 +33,7 @@ __device__ __forceinline__ void prep_w(const bf16* __restrict__ W, bf16* __restr
 // whole.  Wave w owns rows e in [32 w, 32 w + 32).
 template <int D>
 __global__ __launch_bounds__(256, 4) void states_mfma_kernel(const bf16* __restrict__ K,
-                                                             const bf16* __restrict__ V, int N, int Tn,
+                                                             const bf16* __restrict__ V, int N, int Tn, Lay lay,
                                                              int phi, bf16* __restrict__ hz,
                                                              const bf16* __restrict__ W, bf16* __restrict__ WTp) {
   using T = SwzTile<D>;
@@ -48,11 +48,13 @@ __global__ __launch_bounds__(256, 4) void states_mfma_kernel(const bf16* __restr
     return;
   }
   const int n0 = j * kBlk, cnt = min(kBlk, N - n0);
-  const int ldv = tile_lane_offset<D>(w, l);
   const int wu = wave_uniform(w);
-  const unsigned lds0 = lds_base(smem) + wu * 1024;
-  issue_tile_load<D>(K + ((size_t)bh * N + n0) * D, cnt, lds0, 0, ldv);
-  issue_tile_load<D>(V + ((size_t)bh * N + n0) * D, cnt, lds0, T::BYTES, ldv);
+  {
+    TileLoader<D> tl;
+    tl.init(lds_base(smem), w, l, 2 * lay.ts);
+    tl.load(head_rsrc<D>(K + lay.head(bh), N, 2 * lay.ts), j, 0);
+    tl.load(head_rsrc<D>(V + lay.head(bh), N, 2 * lay.ts), j, T::BYTES);
+  }
   wait_vm0();
   __syncthreads();
   // phi on the K tile in place: four threads per key row, a quarter of the features each
@@ -152,7 +154,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
     const bf16* __restrict__ WTp, const int32_t* __restrict__ row_idx, const bf16* __restrict__ H16,
     const float* __restrict__ Zs,
-    int N, int Tn, int n_h, int n_0, int phi, float scale_log2e, bf16* __restrict__ O,
+    int N, int Tn, Lay lay, int n_h, int n_0, int phi, float scale_log2e, bf16* __restrict__ O,
     bf16* __restrict__ Os, bf16* __restrict__ Ol, float* __restrict__ L) {
   using Lds = FwdLds<D>;
   constexpr int NT = D / 32, KT = D / 16;
@@ -164,7 +166,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
   const int q0 = i * kBlk, rows = min(kBlk, N - q0);
   const int qrow = qh * 32 + ln;                  // this lane's query inside the block
   const bool qok = qrow < rows;
-  const size_t qoff = ((size_t)bh * N + q0 + qrow) * D;
+  const size_t qoff = lay.head(bh) + (size_t)(q0 + qrow) * lay.ts;
   bf16x8 qf[KT];
 #pragma unroll
   for (int t = 0; t < KT; ++t)
@@ -174,22 +176,22 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
   for (int et = 0; et < NT; ++et) oT[et] = zero_f32x16();
   float m = -INFINITY, lsum = 0.0f;
   const int32_t* lut = row_idx + ((size_t)bh * Tn + i) * n_h;
-  const bf16* Kb = K + (size_t)bh * N * D;
-  const bf16* Vb = V + (size_t)bh * N * D;
   const float c2 = scale_log2e;                    // exp(x / sqrt(d)) = exp2(x * c2)
   using T = SwzTile<D>;
-  TileLoader<D> tl;
-  tl.init(lds_base(smem), w, l);
-  const BufDesc descK = tile_rsrc(Kb, N * D * 2), descV = tile_rsrc(Vb, N * D * 2);
+  TileLoader<D> tl, tm;   // tiles of the caller's K and V; packed d x d matrices
+  tl.init(lds_base(smem), w, l, 2 * lay.ts);
+  tm.init(lds_base(smem), w, l, 2 * D);
+  const BufDesc descK = head_rsrc<D>(K + lay.head(bh), N, 2 * lay.ts);
+  const BufDesc descV = head_rsrc<D>(V + lay.head(bh), N, 2 * lay.ts);
   // K (v = 0) or V (v = 1) tile of key block jj into a slot; the loads go K_0 V_0 K_1 V_1 ... and
   // load n of that sequence uses slot n % 5
-  auto issue_load = [&](int v, int jj, int slot) { tl.load(v ? descV : descK, jj * Lds::TILE, slot * Lds::TILE); };
+  auto issue_load = [&](int v, int jj, int slot) { tl.load(v ? descV : descK, jj, slot * Lds::TILE); };
   // a d x d bf16 matrix (aggregated state H_i, prepared projection matrix) goes global -> LDS like
   // the tiles: rows 0..63 into the slot at off0, the rest into the one at off1
   auto issue_matrix = [&](const bf16* M, int off0, int off1) {
     const BufDesc dm = tile_rsrc(M, D * D * 2);
-    tl.load(dm, 0, off0);
-    if (D > kBlk) tl.load(dm, Lds::TILE, off1);
+    tm.load(dm, 0, off0);
+    if (D > kBlk) tm.load(dm, 1, off1);
   };
   const bf16* Hrow = H16 + ((size_t)bh * Tn + i) * (D * D);
   // Slots at the end of the loop, with b the slot of the last K tile: H_i goes to b and b + 4
@@ -428,7 +430,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
     }
   }
   if (par == 0) {
-    store_rows_bf16<NT>(mystage, oT, O + orow0, D, wrows, l);
+    store_rows_bf16<NT>(mystage, oT, O + lay.head(bh) + (size_t)(q0 + 32 * qh) * lay.ts, lay.ts, wrows, l);
     if (n_0 == 0 && Ol) {   // no marginal block: O^l is identically zero
 #pragma unroll
       for (int et = 0; et < NT; ++et) oT[et] = zero_f32x16();
@@ -456,7 +458,7 @@ hipError_t forward_impl(const Shape& s, const FwdArgs& a, bf16* hz16, bf16* WTp,
     {
       KernelTimer kt("states", st);
       states_mfma_kernel<D><<<dim3(s.T + 1, s.BH), 256, 0, st>>>((const bf16*)a.K, (const bf16*)a.V, s.N, s.T,
-                                                               s.phi, hz16, (const bf16*)a.W, WTp);
+                                                               s.lay(), s.phi, hz16, (const bf16*)a.W, WTp);
     }
     SLA_TRY(mfma_aggregate(hz16, a.ind, s, a.HZ, Zs, st));
   } else if (a.Os) {   // saved states must read as zero
@@ -469,7 +471,8 @@ hipError_t forward_impl(const Shape& s, const FwdArgs& a, bf16* hz16, bf16* WTp,
   {
     KernelTimer kt("fwd_sparse", st);
     fwd_mfma_kernel<D><<<dim3(xcd_grid(s.T), s.BH), 256, lds, st>>>(
-        (const bf16*)a.Q, (const bf16*)a.K, (const bf16*)a.V, WTp, a.row_idx, (const bf16*)a.HZ, Zs, s.N, s.T, s.n_h,
+        (const bf16*)a.Q, (const bf16*)a.K, (const bf16*)a.V, WTp, a.row_idx, (const bf16*)a.HZ, Zs, s.N, s.T, s.lay(),
+        s.n_h,
         s.n_0, s.phi, s.scale * kLog2e, (bf16*)a.O, (bf16*)a.Os, (bf16*)a.Ol, a.L);
   }
   return hipGetLastError();

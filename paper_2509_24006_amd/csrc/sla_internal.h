@@ -10,13 +10,28 @@ namespace sla {
 
 constexpr int kBlk = 64;  // b_q = b_kv (Section 6.1 hyper-parameters)
 
+// Where the caller's Q, K, V, O, dO, dQ, dK, dV keep token n of head bh = b H + h: element
+// offset head(bh) + n ts.  [B,H,N,d]: ts = d; [B,N,H,d]: ts = H d.  (Everything the library
+// itself lays out -- saved tensors, workspaces -- is packed per head with rows d apart.)
+struct Lay {
+  long long bs, hs;   // elements between batches, between heads of a batch
+  int ts, H;          // elements between tokens of a head; heads per batch
+  __host__ __device__ size_t head(int bh) const { return (size_t)(bh / H) * bs + (size_t)(bh % H) * hs; }
+};
+
 // Shape of one call, derived on the host.
 struct Shape {
   int BH, N, d, T, n_h, n_l, n_0;
   int phi;    // 0 softmax over features, 1 elu+1
   int dtype;  // 0 float, 1 bf16
   float scale;  // float 1/sqrt(d)
+  int H;        // heads per batch
+  int layout;   // 0 [B,H,N,d], 1 [B,N,H,d]
   __host__ __device__ int state_row() const { return d * d + d; }
+  Lay lay() const {
+    if (layout == 1) return Lay{(long long)N * H * d, (long long)d, H * d, H};
+    return Lay{(long long)H * N * d, (long long)N * d, d, H};
+  }
 };
 
 __device__ __forceinline__ float to_f32(float x) { return x; }

@@ -16,27 +16,30 @@ def f64(t: torch.Tensor) -> np.ndarray:
     return t.detach().to(torch.float64).cpu().numpy()
 
 
-def run_gpu(x, dtype: str, k_h: float, k_l: float, phi: int = 0, backward: bool = True):
+def run_gpu(x, dtype: str, k_h: float, k_l: float, phi: int = 0, backward: bool = True,
+            token_major: bool = False):
     """x: dict of float32 arrays Q,K,V[,dO] [B,H,N,d] and Proj [d,d].  Runs mask, forward
-    and (optionally) backward through the C ABI and returns numpy results."""
+    and (optionally) backward through the C ABI and returns numpy results ([B,H,N,d] again).
+    token_major: hand the library [B,N,H,d] tensors (the same values, transposed on the device)."""
     B, H, N, d = x["Q"].shape
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
-    p = sla.make_params(B, H, N, d, k_h, k_l, tdt, phi)
-    Q, K, V = (to_dev(x[k], dtype) for k in ("Q", "K", "V"))
+    p = sla.make_params(B, H, N, d, k_h, k_l, tdt, phi, layout=sla.SLA_BNHD if token_major else sla.SLA_BHND)
+    tm = (lambda t: t.transpose(1, 2).contiguous()) if token_major else (lambda t: t)
+    Q, K, V = (tm(to_dev(x[k], dtype)) for k in ("Q", "K", "V"))
     W = to_dev(x["Proj"], dtype)
     Mc, luts, ws = sla.sla_build_mask(p, Q, K)
     O, saved = sla.sla_forward(p, Q, K, V, W, Mc, luts)
     torch.cuda.synchronize()
     sv = sla.saved_views(p, saved)
-    out = {"Mc": Mc.cpu().numpy(), "O": f64(O)}
+    out = {"Mc": Mc.cpu().numpy(), "O": f64(tm(O))}
     out.update({k: f64(v) for k, v in sv.items()})
     out.update({k: v.cpu().numpy() for k, v in sla.mask_ws_views(p, ws).items()})
     out.update({k: v.cpu().numpy() for k, v in sla.lut_views(p, luts).items()})
     if backward:
-        dO = to_dev(x["dO"], dtype)
+        dO = tm(to_dev(x["dO"], dtype))
         dQ, dK, dV, dW = sla.sla_backward(p, Q, K, V, W, Mc, luts, saved, dO)
         torch.cuda.synchronize()
-        out.update({"dQ": f64(dQ), "dK": f64(dK), "dV": f64(dV), "dW": f64(dW)})
+        out.update({"dQ": f64(tm(dQ)), "dK": f64(tm(dK)), "dV": f64(tm(dV)), "dW": f64(dW)})
     return out
 
 

@@ -22,7 +22,7 @@ def test_exports_match_header():
 
 
 def test_struct_layout_matches_header():
-    assert ctypes.sizeof(sla.sla_params) == 48
+    assert ctypes.sizeof(sla.sla_params) == 56
     assert ctypes.sizeof(sla.sla_sizes_t) == 16 + 20 * 8
 
 
@@ -69,3 +69,15 @@ def test_null_and_small_workspace_are_rejected():
     assert L.sla_backward(ctypes.byref(p), *([fake] * 13), 16, None) == -3
     assert L.sla_forward(ctypes.byref(p), ctypes.c_void_p(4097), fake, fake, fake, fake, fake, fake, None, fake, 1 << 40, None) == -1
     assert b"workspace" in L.sla_strerror(-3)
+
+
+def test_token_major_layout_is_bf16_only():
+    import torch
+    ok = sla.make_params(1, 2, 128, 64, 0.5, 0.1, torch.bfloat16, layout=sla.SLA_BNHD)
+    assert sla.sla_sizes(ok).T == 2
+    bad = sla.make_params(1, 2, 128, 64, 0.5, 0.1, torch.float32, layout=sla.SLA_BNHD)
+    with pytest.raises(sla.SLAError):
+        sla.sla_sizes(bad)
+    worse = sla.make_params(1, 2, 128, 64, 0.5, 0.1, torch.bfloat16, layout=7)
+    with pytest.raises(sla.SLAError):
+        sla.sla_sizes(worse)

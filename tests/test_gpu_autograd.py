@@ -35,3 +35,27 @@ def test_autograd_matches_oracle(oracle, name):
         err = pins.rel_l2(got.detach().float().cpu().numpy(), ref)
         print(f"  {name} {n}: rel_l2 = {err:.3e}", flush=True)
         assert err <= tol, f"{n}: {err:.3e}"
+
+
+def test_autograd_token_major(oracle):
+    # [B,N,H,d] tensors, as a transformer block's projections leave them
+    from paper_2509_24006_amd.autograd import sla_attention
+    w = wl.WORKLOADS["small_bf16"]
+    x = wl.make_inputs(w)
+    dev = torch.device("cuda:0")
+    tm = lambda a: torch.from_numpy(a).to(dev).to(torch.bfloat16).transpose(1, 2).contiguous()
+    Q, K, V = (tm(x[k]).requires_grad_(True) for k in ("Q", "K", "V"))
+    W = torch.from_numpy(x["Proj"]).to(dev).to(torch.bfloat16).requires_grad_(True)
+    O = sla_attention(Q, K, V, W, k_h=w.k_h, k_l=w.k_l, token_major=True)
+    assert O.shape == Q.shape
+    O.backward(tm(x["dO"]))
+    torch.cuda.synchronize()
+    Mc = oracle.build_mask(x["Q"], x["K"], w.k_h, w.k_l)
+    f = oracle.forward(x["Q"], x["K"], x["V"], x["Proj"], Mc)
+    g = oracle.backward(x["Q"], x["K"], x["V"], x["Proj"], Mc, f, x["dO"])
+    back = lambda t: t.detach().float().transpose(1, 2).cpu().numpy()
+    for n, got, ref in (("O", back(O), f["O"]), ("dQ", back(Q.grad), g["dQ"]), ("dK", back(K.grad), g["dK"]),
+                        ("dV", back(V.grad), g["dV"]), ("dW", W.grad.detach().float().cpu().numpy(), g["dW"])):
+        err = pins.rel_l2(got, ref)
+        print(f"  token-major {n}: rel_l2 = {err:.3e}", flush=True)
+        assert err <= TOL["bf16"], f"{n}: {err:.3e}"
