@@ -61,7 +61,7 @@ def main() -> int:
                          "calibrates the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (heads shard trivially, see DESIGN.md); "
+        print("bench.py: this build runs on ONE GPU only (every step is per head, so heads would shard trivially); "
               "--gpus must be 1", file=sys.stderr)
         return 2
 
