@@ -56,7 +56,7 @@ typedef struct sla_params {
   int32_t dtype;      /* SLA_F32 or SLA_BF16; statistics and dW are always float           */
   int32_t layout;     /* SLA_BHND: Q,K,V,O,dO,dQ,dK,dV packed [B,H,N,d]; SLA_BNHD: packed
                          [B,N,H,d] (token-major, as a transformer block's projections leave
-                         them; bf16 tensors only).  Masks, tables, saved tensors and
+                         them).  Masks, tables, saved tensors and
                          workspaces are per (b, h) in either case.                          */
 } sla_params;
 

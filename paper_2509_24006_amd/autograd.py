@@ -35,7 +35,7 @@ def build_mask(Q: torch.Tensor, K: torch.Tensor, k_h: float, k_l: float,
                phi: int = sla.SLA_PHI_SOFTMAX, token_major: bool = False
                ) -> Tuple[sla.sla_params, torch.Tensor, torch.Tensor]:
     """(params, M_c int8 [B,H,T,T], lookup tables) for contiguous [B,H,N,d] tensors, or
-    [B,N,H,d] ones with token_major (bf16 only)."""
+    [B,N,H,d] ones with token_major."""
     if token_major:
         B, N, H, d = Q.shape
     else:

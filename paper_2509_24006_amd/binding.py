@@ -79,7 +79,7 @@ def _check(rc: int, what: str) -> None:
 def make_params(B: int, H: int, N: int, d: int, k_h: float, k_l: float, dtype: torch.dtype,
                 phi: int = SLA_PHI_SOFTMAX, bq: int = 64, bkv: int = 64,
                 layout: int = SLA_BHND) -> sla_params:
-    """layout: SLA_BHND ([B,H,N,d] tensors) or SLA_BNHD ([B,N,H,d], bf16 only)."""
+    """layout: SLA_BHND ([B,H,N,d] tensors) or SLA_BNHD ([B,N,H,d])."""
     code = {torch.float32: SLA_F32, torch.bfloat16: SLA_BF16}[dtype]
     return sla_params(B, H, N, d, bq, bkv, k_h, k_l, phi, code, layout)
 

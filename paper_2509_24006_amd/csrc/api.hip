@@ -21,7 +21,6 @@ int make_shape(const sla_params* p, Shape* s) {
   if (p->phi != SLA_PHI_SOFTMAX && p->phi != SLA_PHI_ELU1) return SLA_EUNSUPPORTED;
   if (p->dtype != SLA_F32 && p->dtype != SLA_BF16) return SLA_EUNSUPPORTED;
   if (p->layout != SLA_BHND && p->layout != SLA_BNHD) return SLA_EUNSUPPORTED;
-  if (p->layout == SLA_BNHD && p->dtype != SLA_BF16) return SLA_EUNSUPPORTED;
   const long long T = ((long long)p->N + kBlk - 1) / kBlk;
   if (T > kMaxT) return SLA_EUNSUPPORTED;
   if ((long long)p->B * p->H > 65535) return SLA_EUNSUPPORTED;  // grid.y / grid.z limit

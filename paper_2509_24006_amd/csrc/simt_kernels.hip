@@ -15,10 +15,10 @@ constexpr int kThreads = 256;
 
 // ------------------------------------------------------------------ tile helpers
 template <typename T>
-__device__ __forceinline__ void load_tile(float* dst, int ld, const T* src, int rows_valid, int d) {
+__device__ __forceinline__ void load_tile(float* dst, int ld, const T* src, int rows_valid, int d, int src_ld) {
   for (int idx = threadIdx.x; idx < kBlk * d; idx += kThreads) {
     const int r = idx / d, c = idx - r * d;
-    dst[r * ld + c] = (r < rows_valid) ? to_f32(src[(size_t)r * d + c]) : 0.0f;
+    dst[r * ld + c] = (r < rows_valid) ? to_f32(src[(size_t)r * src_ld + c]) : 0.0f;
   }
 }
 
@@ -162,7 +162,7 @@ __device__ __forceinline__ void phi_backward(const float* X, const float* Y, int
 // block; stored as a state row (h transposed, then z).
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void states_kernel(const T* __restrict__ K,
-                                                          const T* __restrict__ V, int N, int Tn,
+                                                          const T* __restrict__ V, int N, int Tn, Lay lay,
                                                           int phi, float* __restrict__ hz) {
   extern __shared__ float lds[];
   constexpr int LD = D + 1;
@@ -170,9 +170,9 @@ __global__ __launch_bounds__(kThreads) void states_kernel(const T* __restrict__ 
   float* Vs = lds + kBlk * LD;
   const int j = blockIdx.x, bh = blockIdx.y;
   const int n0 = j * kBlk, cnt = min(kBlk, N - n0);
-  const size_t base = ((size_t)bh * N + n0) * D;
-  load_tile(Ks, LD, K + base, cnt, D);
-  load_tile(Vs, LD, V + base, cnt, D);
+  const size_t ubase = lay.head(bh) + (size_t)n0 * lay.ts;   // in the caller's tensors
+  load_tile(Ks, LD, K + ubase, cnt, D, lay.ts);
+  load_tile(Vs, LD, V + ubase, cnt, D, lay.ts);
   __syncthreads();
   phi_tile<D>(Ks, Ks, LD, cnt, phi);
   __syncthreads();
@@ -224,7 +224,7 @@ template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void forward_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const T* __restrict__ W, const int32_t* __restrict__ row_idx, const float* __restrict__ HZ,
-    int N, int Tn, int n_h, int n_0, int phi, float scale, T* __restrict__ O, T* __restrict__ Os,
+    int N, int Tn, Lay lay, int n_h, int n_0, int phi, float scale, T* __restrict__ O, T* __restrict__ Os,
     T* __restrict__ Ol, float* __restrict__ L) {
   extern __shared__ float lds[];
   constexpr int LD = D + 1, NB = D / 16;
@@ -234,8 +234,9 @@ __global__ __launch_bounds__(kThreads) void forward_kernel(
   const int i = blockIdx.x, bh = blockIdx.y;
   const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
   const int q0 = i * kBlk, rows = min(kBlk, N - q0);
-  const size_t qbase = ((size_t)bh * N + q0) * D;
-  load_tile(Qs, LD, Q + qbase, rows, D);
+  const size_t qbase = ((size_t)bh * N + q0) * D;                  // in the library's packed tensors
+  const size_t uq = lay.head(bh) + (size_t)q0 * lay.ts;            // in the caller's tensors
+  load_tile(Qs, LD, Q + uq, rows, D, lay.ts);
   float m[4], l[4], acc[4][NB];
 #pragma unroll
   for (int a = 0; a < 4; ++a) { m[a] = -INFINITY; l[a] = 0.0f; }
@@ -244,9 +245,9 @@ __global__ __launch_bounds__(kThreads) void forward_kernel(
   for (int t = 0; t < n_h; ++t) {
     const int j = lut[t];
     const int k0 = j * kBlk, cols = min(kBlk, N - k0);
-    const size_t kbase = ((size_t)bh * N + k0) * D;
+    const size_t kbase = lay.head(bh) + (size_t)k0 * lay.ts;
     __syncthreads();
-    load_tile(Xs, LD, K + kbase, cols, D);
+    load_tile(Xs, LD, K + kbase, cols, D, lay.ts);
     __syncthreads();
     float s[4][4];
     zero(s);
@@ -274,7 +275,7 @@ __global__ __launch_bounds__(kThreads) void forward_kernel(
       for (int b = 0; b < NB; ++b) acc[a][b] *= alpha;
     }
     __syncthreads();
-    load_tile(Xs, LD, V + kbase, cols, D);
+    load_tile(Xs, LD, V + kbase, cols, D, lay.ts);
     __syncthreads();
     mm_ab<NB>(Ps, 65, Xs, LD, kBlk, acc);
   }
@@ -347,7 +348,7 @@ __global__ __launch_bounds__(kThreads) void forward_kernel(
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
       const size_t o = qbase + (size_t)r * D + tx + 16 * b;
-      from_f32(O[o], os[a][b]);
+      from_f32(O[uq + (size_t)r * lay.ts + tx + 16 * b], os[a][b]);
       if (Ol) from_f32(Ol[o], ol[a][b]);
     }
   }
@@ -358,7 +359,7 @@ __global__ __launch_bounds__(kThreads) void forward_kernel(
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void bwd_prologue_kernel(
     const T* __restrict__ dO, const T* __restrict__ W, const T* __restrict__ Os,
-    const T* __restrict__ Ol, int N, float* __restrict__ dOl, float* __restrict__ Ds,
+    const T* __restrict__ Ol, int N, Lay lay, float* __restrict__ dOl, float* __restrict__ Ds,
     float* __restrict__ Dl) {
   extern __shared__ float lds[];
   constexpr int LD = D + 1, NB = D / 16;
@@ -368,7 +369,7 @@ __global__ __launch_bounds__(kThreads) void bwd_prologue_kernel(
   const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
   const int q0 = i * kBlk, rows = min(kBlk, N - q0);
   const size_t base = ((size_t)bh * N + q0) * D;
-  load_tile(Gs, LD, dO + base, rows, D);
+  load_tile(Gs, LD, dO + lay.head(bh) + (size_t)q0 * lay.ts, rows, D, lay.ts);
   __syncthreads();
   float ds[4], dl[4];
 #pragma unroll
@@ -384,7 +385,7 @@ __global__ __launch_bounds__(kThreads) void bwd_prologue_kernel(
   }
   for (int c0 = 0; c0 < D; c0 += 64) {
     __syncthreads();
-    load_tile(Ws, LD, W + (size_t)c0 * D, kBlk, D);
+    load_tile(Ws, LD, W + (size_t)c0 * D, kBlk, D, D);
     __syncthreads();
     float g[4][4];
     zero(g);
@@ -417,7 +418,7 @@ __global__ __launch_bounds__(kThreads) void bwd_prologue_kernel(
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void dw_partial_kernel(const T* __restrict__ Ol,
                                                               const T* __restrict__ dO, int BH,
-                                                              int N, int Tn,
+                                                              int N, int Tn, Lay lay,
                                                               float* __restrict__ part) {
   extern __shared__ float lds[];
   constexpr int LD = D + 1, NB = D / 16;
@@ -431,8 +432,8 @@ __global__ __launch_bounds__(kThreads) void dw_partial_kernel(const T* __restric
     const int q0 = i * kBlk, rows = min(kBlk, N - q0);
     const size_t base = ((size_t)bh * N + q0) * D;
     __syncthreads();
-    load_tile(As, LD, Ol + base, rows, D);
-    load_tile(Bs, LD, dO + base, rows, D);
+    load_tile(As, LD, Ol + base, rows, D, D);
+    load_tile(Bs, LD, dO + lay.head(bh) + (size_t)q0 * lay.ts, rows, D, lay.ts);
     __syncthreads();
     mm_atb<NB, NB>(As, LD, Bs, LD, kBlk, acc);
   }
@@ -477,7 +478,7 @@ __global__ __launch_bounds__(256) void dw_reduce_kernel(const float* __restrict_
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void bwd_linear_q_kernel(
     const T* __restrict__ Q, const float* __restrict__ dOl, const float* __restrict__ Dl,
-    const float* __restrict__ HZ, int N, int Tn, int phi, float* __restrict__ dHZ,
+    const float* __restrict__ HZ, int N, int Tn, Lay lay, int phi, float* __restrict__ dHZ,
     float* __restrict__ dQlin) {
   extern __shared__ float lds[];
   constexpr int LD = D + 1, NB = D / 16;
@@ -492,8 +493,8 @@ __global__ __launch_bounds__(kThreads) void bwd_linear_q_kernel(
   const size_t base = ((size_t)bh * N + q0) * D;
   const float* Hrow = HZ + ((size_t)bh * Tn + i) * (D * D + D);
   const float* Z = Hrow + D * D;
-  load_tile(Qs, LD, Q + base, rows, D);
-  load_tile(Gs, LD, dOl + base, rows, D);
+  load_tile(Qs, LD, Q + lay.head(bh) + (size_t)q0 * lay.ts, rows, D, lay.ts);
+  load_tile(Gs, LD, dOl + base, rows, D, D);
   __syncthreads();
   phi_tile<D>(Qs, Ys, LD, rows, phi);
   __syncthreads();
@@ -559,7 +560,7 @@ __global__ __launch_bounds__(kThreads) void bwd_linear_q_kernel(
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void bwd_linear_k_kernel(
     const T* __restrict__ K, const T* __restrict__ V, const float* __restrict__ dHZcol, int N,
-    int Tn, int phi, float* __restrict__ dKlin, float* __restrict__ dVlin) {
+    int Tn, Lay lay, int phi, float* __restrict__ dKlin, float* __restrict__ dVlin) {
   extern __shared__ float lds[];
   constexpr int LD = D + 1, NB = D / 16;
   float* Ks = lds;
@@ -572,8 +573,8 @@ __global__ __launch_bounds__(kThreads) void bwd_linear_k_kernel(
   const size_t base = ((size_t)bh * N + n0) * D;
   const float* Hrow = dHZcol + ((size_t)bh * Tn + j) * (D * D + D);
   const float* dZ = Hrow + D * D;
-  load_tile(Ks, LD, K + base, cnt, D);
-  load_tile(Vs, LD, V + base, cnt, D);
+  load_tile(Ks, LD, K + lay.head(bh) + (size_t)n0 * lay.ts, cnt, D, lay.ts);
+  load_tile(Vs, LD, V + lay.head(bh) + (size_t)n0 * lay.ts, cnt, D, lay.ts);
   __syncthreads();
   phi_tile<D>(Ks, Ys, LD, cnt, phi);
   float gk[4][NB];
@@ -620,7 +621,7 @@ __global__ __launch_bounds__(kThreads) void bwd_sparse_kv_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const T* __restrict__ dO, const float* __restrict__ L, const float* __restrict__ Ds,
     const int32_t* __restrict__ col_ptr, const int32_t* __restrict__ col_rows,
-    const float* __restrict__ dKlin, const float* __restrict__ dVlin, int N, int Tn, int n_h,
+    const float* __restrict__ dKlin, const float* __restrict__ dVlin, int N, int Tn, Lay lay, int n_h,
     float scale, T* __restrict__ dK, T* __restrict__ dV) {
   extern __shared__ float lds[];
   constexpr int LD = D + 1, NB = D / 16;
@@ -632,9 +633,10 @@ __global__ __launch_bounds__(kThreads) void bwd_sparse_kv_kernel(
   const int j = blockIdx.x, bh = blockIdx.y;
   const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
   const int k0 = j * kBlk, cols = min(kBlk, N - k0);
-  const size_t kbase = ((size_t)bh * N + k0) * D;
-  load_tile(Ks, LD, K + kbase, cols, D);
-  load_tile(Vs, LD, V + kbase, cols, D);
+  const size_t kbase = ((size_t)bh * N + k0) * D;              // in the library's packed tensors
+  const size_t uk = lay.head(bh) + (size_t)k0 * lay.ts;        // in the caller's tensors
+  load_tile(Ks, LD, K + uk, cols, D, lay.ts);
+  load_tile(Vs, LD, V + uk, cols, D, lay.ts);
   float dk[4][NB], dv[4][NB];
   zero(dk);
   zero(dv);
@@ -643,9 +645,9 @@ __global__ __launch_bounds__(kThreads) void bwd_sparse_kv_kernel(
   for (int t = ptr[j]; t < ptr[j + 1]; ++t) {
     const int i = list[t];
     const int q0 = i * kBlk, rows = min(kBlk, N - q0);
-    const size_t qbase = ((size_t)bh * N + q0) * D;
+    const size_t qbase = lay.head(bh) + (size_t)q0 * lay.ts;
     __syncthreads();
-    load_tile(Xs, LD, Q + qbase, rows, D);
+    load_tile(Xs, LD, Q + qbase, rows, D, lay.ts);
     __syncthreads();
     float p[4][4];
     zero(p);
@@ -661,7 +663,7 @@ __global__ __launch_bounds__(kThreads) void bwd_sparse_kv_kernel(
       }
     }
     __syncthreads();
-    load_tile(Xs, LD, dO + qbase, rows, D);
+    load_tile(Xs, LD, dO + qbase, rows, D, lay.ts);
     __syncthreads();
     float dp[4][4];
     zero(dp);
@@ -675,7 +677,7 @@ __global__ __launch_bounds__(kThreads) void bwd_sparse_kv_kernel(
     }
     mm_atb<4, NB>(Ps, 65, Xs, LD, kBlk, dv);   // dV_j += P^T dO_i
     __syncthreads();
-    load_tile(Xs, LD, Q + qbase, rows, D);
+    load_tile(Xs, LD, Q + qbase, rows, D, lay.ts);
     __syncthreads();
     mm_atb<4, NB>(dSs, 65, Xs, LD, kBlk, dk);  // dK_j += dS^T Q_i
   }
@@ -685,9 +687,9 @@ __global__ __launch_bounds__(kThreads) void bwd_sparse_kv_kernel(
     if (r >= cols) continue;
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
-      const size_t o = kbase + (size_t)r * D + tx + 16 * b;
-      from_f32(dK[o], dk[a][b] * scale + (dKlin ? dKlin[o] : 0.0f));
-      from_f32(dV[o], dv[a][b] + (dVlin ? dVlin[o] : 0.0f));
+      const size_t o = kbase + (size_t)r * D + tx + 16 * b, uo = uk + (size_t)r * lay.ts + tx + 16 * b;
+      from_f32(dK[uo], dk[a][b] * scale + (dKlin ? dKlin[o] : 0.0f));
+      from_f32(dV[uo], dv[a][b] + (dVlin ? dVlin[o] : 0.0f));
     }
   }
 }
@@ -699,7 +701,7 @@ template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void bwd_sparse_q_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const T* __restrict__ dO, const float* __restrict__ L, const float* __restrict__ Ds,
-    const int32_t* __restrict__ row_idx, const float* __restrict__ dQlin, int N, int Tn, int n_h,
+    const int32_t* __restrict__ row_idx, const float* __restrict__ dQlin, int N, int Tn, Lay lay, int n_h,
     float scale, T* __restrict__ dQ) {
   extern __shared__ float lds[];
   constexpr int LD = D + 1, NB = D / 16;
@@ -710,9 +712,10 @@ __global__ __launch_bounds__(kThreads) void bwd_sparse_q_kernel(
   const int i = blockIdx.x, bh = blockIdx.y;
   const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
   const int q0 = i * kBlk, rows = min(kBlk, N - q0);
-  const size_t qbase = ((size_t)bh * N + q0) * D;
-  load_tile(Qs, LD, Q + qbase, rows, D);
-  load_tile(Gs, LD, dO + qbase, rows, D);
+  const size_t qbase = ((size_t)bh * N + q0) * D;              // in the library's packed tensors
+  const size_t uq = lay.head(bh) + (size_t)q0 * lay.ts;        // in the caller's tensors
+  load_tile(Qs, LD, Q + uq, rows, D, lay.ts);
+  load_tile(Gs, LD, dO + uq, rows, D, lay.ts);
   float Lr[4], Dr[4];
 #pragma unroll
   for (int a = 0; a < 4; ++a) {
@@ -726,9 +729,9 @@ __global__ __launch_bounds__(kThreads) void bwd_sparse_q_kernel(
   for (int t = 0; t < n_h; ++t) {
     const int j = lut[t];
     const int k0 = j * kBlk, cols = min(kBlk, N - k0);
-    const size_t kbase = ((size_t)bh * N + k0) * D;
+    const size_t kbase = lay.head(bh) + (size_t)k0 * lay.ts;
     __syncthreads();
-    load_tile(Xs, LD, K + kbase, cols, D);
+    load_tile(Xs, LD, K + kbase, cols, D, lay.ts);
     __syncthreads();
     float p[4][4];
     zero(p);
@@ -739,7 +742,7 @@ __global__ __launch_bounds__(kThreads) void bwd_sparse_q_kernel(
       for (int b = 0; b < 4; ++b)
         p[a][b] = (ty + 16 * a < rows && tx + 16 * b < cols) ? expf(p[a][b] * scale - Lr[a]) : 0.0f;
     __syncthreads();
-    load_tile(Xs, LD, V + kbase, cols, D);
+    load_tile(Xs, LD, V + kbase, cols, D, lay.ts);
     __syncthreads();
     float dp[4][4];
     zero(dp);
@@ -749,7 +752,7 @@ __global__ __launch_bounds__(kThreads) void bwd_sparse_q_kernel(
 #pragma unroll
       for (int b = 0; b < 4; ++b) dSs[(ty + 16 * a) * 65 + tx + 16 * b] = p[a][b] * (dp[a][b] - Dr[a]);
     __syncthreads();
-    load_tile(Xs, LD, K + kbase, cols, D);
+    load_tile(Xs, LD, K + kbase, cols, D, lay.ts);
     __syncthreads();
     mm_ab<NB>(dSs, 65, Xs, LD, kBlk, dq);  // dQ_i += dS K_j
   }
@@ -760,7 +763,7 @@ __global__ __launch_bounds__(kThreads) void bwd_sparse_q_kernel(
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
       const size_t o = qbase + (size_t)r * D + tx + 16 * b;
-      from_f32(dQ[o], dq[a][b] * scale + (dQlin ? dQlin[o] : 0.0f));
+      from_f32(dQ[uq + (size_t)r * lay.ts + tx + 16 * b], dq[a][b] * scale + (dQlin ? dQlin[o] : 0.0f));
     }
   }
 }
@@ -787,7 +790,7 @@ hipError_t forward_impl(const Shape& s, const FwdArgs& a, hipStream_t st) {
     SLA_TRY(set_lds(states_kernel<T, D>, lds1));
     {
       KernelTimer kt("states", st);
-      states_kernel<T, D><<<grid, kThreads, lds1, st>>>((const T*)a.K, (const T*)a.V, s.N, s.T, s.phi, a.hz);
+      states_kernel<T, D><<<grid, kThreads, lds1, st>>>((const T*)a.K, (const T*)a.V, s.N, s.T, s.lay(), s.phi, a.hz);
     }
     {
       KernelTimer kt("aggregate", st);
@@ -805,7 +808,7 @@ hipError_t forward_impl(const Shape& s, const FwdArgs& a, hipStream_t st) {
   {
     KernelTimer kt("forward", st);
     forward_kernel<T, D><<<grid, kThreads, lds2, st>>>(
-      (const T*)a.Q, (const T*)a.K, (const T*)a.V, (const T*)a.W, a.row_idx, a.HZ, s.N, s.T, s.n_h,
+      (const T*)a.Q, (const T*)a.K, (const T*)a.V, (const T*)a.W, a.row_idx, a.HZ, s.N, s.T, s.lay(), s.n_h,
       s.n_0, s.phi, s.scale, (T*)a.O, (T*)a.Os, (T*)a.Ol, a.L);
   }
   return hipGetLastError();
@@ -854,13 +857,13 @@ hipError_t backward_impl(const Shape& s, const BwdArgs& a, hipStream_t st) {
     {
       KernelTimer kt("bwd_prologue", st);
       bwd_prologue_kernel<T, D><<<grid, kThreads, lds, st>>>((const T*)a.dO, (const T*)a.W, (const T*)a.Os,
-                                                          (const T*)a.Ol, s.N, w.dOl, w.Ds, w.Dl);
+                                                          (const T*)a.Ol, s.N, s.lay(), w.dOl, w.Ds, w.Dl);
     }
     SLA_TRY(set_lds(dw_partial_kernel<T, D>, lds));
     {
       KernelTimer kt("dw_partial", st);
       dw_partial_kernel<T, D><<<w.nparts, kThreads, lds, st>>>((const T*)a.Ol, (const T*)a.dO, s.BH, s.N,
-                                                            s.T, w.dWpart);
+                                                            s.T, s.lay(), w.dWpart);
     }
     {
       KernelTimer kt("dw_reduce", st);
@@ -873,7 +876,7 @@ hipError_t backward_impl(const Shape& s, const BwdArgs& a, hipStream_t st) {
     {
       KernelTimer kt("bwd_linear_q", st);
       bwd_linear_q_kernel<T, D><<<grid, kThreads, lds, st>>>((const T*)a.Q, w.dOl, w.Dl, a.HZ, s.N, s.T,
-                                                          s.phi, w.dHZ, w.dQlin);
+                                                          s.lay(), s.phi, w.dHZ, w.dQlin);
     }
     {
       KernelTimer kt("aggregate", st);
@@ -885,7 +888,7 @@ hipError_t backward_impl(const Shape& s, const BwdArgs& a, hipStream_t st) {
     {
       KernelTimer kt("bwd_linear_k", st);
       bwd_linear_k_kernel<T, D><<<grid, kThreads, lds2, st>>>((const T*)a.K, (const T*)a.V, w.dHZcol, s.N,
-                                                           s.T, s.phi, w.dKlin, w.dVlin);
+                                                           s.T, s.lay(), s.phi, w.dKlin, w.dVlin);
     }
   }
   {
@@ -895,7 +898,7 @@ hipError_t backward_impl(const Shape& s, const BwdArgs& a, hipStream_t st) {
       KernelTimer kt("bwd_sparse_kv", st);
       bwd_sparse_kv_kernel<T, D><<<grid, kThreads, lds, st>>>(
         (const T*)a.Q, (const T*)a.K, (const T*)a.V, (const T*)a.dO, a.L, w.Ds, a.col_ptr, a.col_rows,
-        lin ? w.dKlin : nullptr, lin ? w.dVlin : nullptr, s.N, s.T, s.n_h, s.scale, (T*)a.dK, (T*)a.dV);
+        lin ? w.dKlin : nullptr, lin ? w.dVlin : nullptr, s.N, s.T, s.lay(), s.n_h, s.scale, (T*)a.dK, (T*)a.dV);
     }
     const size_t lds2 = sizeof(float) * (3 * kBlk * LD + kBlk * 65);
     SLA_TRY(set_lds(bwd_sparse_q_kernel<T, D>, lds2));
@@ -903,7 +906,7 @@ hipError_t backward_impl(const Shape& s, const BwdArgs& a, hipStream_t st) {
       KernelTimer kt("bwd_sparse_q", st);
       bwd_sparse_q_kernel<T, D><<<grid, kThreads, lds2, st>>>(
         (const T*)a.Q, (const T*)a.K, (const T*)a.V, (const T*)a.dO, a.L, w.Ds, a.row_idx,
-        lin ? w.dQlin : nullptr, s.N, s.T, s.n_h, s.scale, (T*)a.dQ);
+        lin ? w.dQlin : nullptr, s.N, s.T, s.lay(), s.n_h, s.scale, (T*)a.dQ);
     }
   }
   return hipGetLastError();

@@ -71,13 +71,11 @@ def test_null_and_small_workspace_are_rejected():
     assert b"workspace" in L.sla_strerror(-3)
 
 
-def test_token_major_layout_is_bf16_only():
+def test_layout_field_is_checked():
     import torch
-    ok = sla.make_params(1, 2, 128, 64, 0.5, 0.1, torch.bfloat16, layout=sla.SLA_BNHD)
-    assert sla.sla_sizes(ok).T == 2
-    bad = sla.make_params(1, 2, 128, 64, 0.5, 0.1, torch.float32, layout=sla.SLA_BNHD)
+    for dt in (torch.bfloat16, torch.float32):
+        ok = sla.make_params(1, 2, 128, 64, 0.5, 0.1, dt, layout=sla.SLA_BNHD)
+        assert sla.sla_sizes(ok).T == 2
+    bad = sla.make_params(1, 2, 128, 64, 0.5, 0.1, torch.bfloat16, layout=7)
     with pytest.raises(sla.SLAError):
         sla.sla_sizes(bad)
-    worse = sla.make_params(1, 2, 128, 64, 0.5, 0.1, torch.bfloat16, layout=7)
-    with pytest.raises(sla.SLAError):
-        sla.sla_sizes(worse)

@@ -103,20 +103,20 @@ def test_bf16_mid_length_sequences(oracle, N, d):
     _full_case(oracle, x, "bf16", 0.1, 0.2)
 
 
-@pytest.mark.parametrize("name", ["small_bf16", "small_bf16_d64"])
+@pytest.mark.parametrize("name", ["small_bf16", "small_bf16_d64", "small_fp32"])
 def test_token_major_tensors(oracle, name):
     # [B,N,H,d] tensors: the same kernels walk the same values with another row pitch, so every
     # result equals the [B,H,N,d] call's bit for bit; one of the two is checked against the oracle
     w = wl.WORKLOADS[name]
     x = wl.make_inputs(replace(w, B=2))
-    a = run_gpu(x, "bf16", w.k_h, w.k_l)
-    b = run_gpu(x, "bf16", w.k_h, w.k_l, token_major=True)
+    a = run_gpu(x, w.dtype, w.k_h, w.k_l)
+    b = run_gpu(x, w.dtype, w.k_h, w.k_l, token_major=True)
     for k in a:
         assert np.array_equal(a[k], b[k]), f"{k} differs between the two memory orders"
     Mc, s, f, g = _oracle_all(oracle, x, w.k_h, w.k_l, 0)
     assert np.array_equal(b["Mc"], Mc)
     for k in ("O", "dQ", "dK", "dV", "dW"):
-        _compare(k, b[k], (f if k == "O" else g)[k], TOL["bf16"])
+        _compare(k, b[k], (f if k == "O" else g)[k], TOL[w.dtype])
 
 
 def test_classify_given_scores_with_ties(oracle):
