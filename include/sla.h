@@ -45,7 +45,7 @@ extern "C" {
 enum { SLA_OK = 0, SLA_EINVAL = -1, SLA_EUNSUPPORTED = -2, SLA_ENOSPACE = -3, SLA_EHIP = -4 };
 enum { SLA_PHI_SOFTMAX = 0, SLA_PHI_ELU1 = 1 };   /* feature map of the linear branch */
 enum { SLA_F32 = 0, SLA_BF16 = 1 };               /* storage type of Q,K,V,W,O,dO,dQ,dK,dV */
-enum { SLA_BHND = 0, SLA_BNHD = 1 };              /* memory order of Q,K,V,O,dO,dQ,dK,dV          */
+enum { SLA_BHND = 0, SLA_BNHD = 1, SLA_STRIDED = 2 }; /* memory order of Q,K,V,O,dO,dQ,dK,dV      */
 
 /* Problem statement (Alg. 1 input line: Q, K, V, block sizes, k_h, k_l; Section 6.1: phi). */
 typedef struct sla_params {
@@ -56,8 +56,15 @@ typedef struct sla_params {
   int32_t dtype;      /* SLA_F32 or SLA_BF16; statistics and dW are always float           */
   int32_t layout;     /* SLA_BHND: Q,K,V,O,dO,dQ,dK,dV packed [B,H,N,d]; SLA_BNHD: packed
                          [B,N,H,d] (token-major, as a transformer block's projections leave
-                         them).  Masks, tables, saved tensors and
-                         workspaces are per (b, h) in either case.                          */
+                         them); SLA_STRIDED: element (b, h, n, c) of each of these tensors
+                         sits stride_b b + stride_h h + stride_n n + c elements after its
+                         pointer, e.g. Q, K, V as the three slices of one fused projection
+                         output [B,N,3,H,d] (stride_b = 3 N H d, stride_h = d, stride_n =
+                         3 H d; K = Q + H d, V = Q + 2 H d).  Masks, tables, saved tensors
+                         and workspaces are packed per (b, h) in every case.               */
+  int64_t stride_b, stride_h, stride_n; /* SLA_STRIDED only: element strides, multiples of 16
+                         bytes, stride_n >= d, N stride_n elements below 2^31 bytes; rows of
+                         different (b, h, n) must not overlap                               */
 } sla_params;
 
 /* Derived sizes and the layout of the opaque buffers (all offsets in bytes).

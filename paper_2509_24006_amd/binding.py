@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libsla_hip.so")
 
 SLA_F32, SLA_BF16 = 0, 1
 SLA_PHI_SOFTMAX, SLA_PHI_ELU1 = 0, 1
-SLA_BHND, SLA_BNHD = 0, 1
+SLA_BHND, SLA_BNHD, SLA_STRIDED = 0, 1, 2
 EXPORTS = ("sla_sizes", "sla_build_mask", "sla_classify_scores", "sla_forward", "sla_backward",
            "sla_profile_enable", "sla_profile_read", "sla_strerror")
 
@@ -27,7 +27,8 @@ class sla_params(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32),
                 ("d", ctypes.c_int32), ("bq", ctypes.c_int32), ("bkv", ctypes.c_int32),
                 ("k_h", ctypes.c_double), ("k_l", ctypes.c_double), ("phi", ctypes.c_int32),
-                ("dtype", ctypes.c_int32), ("layout", ctypes.c_int32)]
+                ("dtype", ctypes.c_int32), ("layout", ctypes.c_int32),
+                ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64)]
 
 
 class sla_sizes_t(ctypes.Structure):
@@ -78,10 +79,12 @@ def _check(rc: int, what: str) -> None:
 
 def make_params(B: int, H: int, N: int, d: int, k_h: float, k_l: float, dtype: torch.dtype,
                 phi: int = SLA_PHI_SOFTMAX, bq: int = 64, bkv: int = 64,
-                layout: int = SLA_BHND) -> sla_params:
-    """layout: SLA_BHND ([B,H,N,d] tensors) or SLA_BNHD ([B,N,H,d])."""
+                layout: int = SLA_BHND, strides: Tuple[int, int, int] = (0, 0, 0)) -> sla_params:
+    """layout: SLA_BHND ([B,H,N,d] tensors), SLA_BNHD ([B,N,H,d]) or SLA_STRIDED with
+    strides = element strides (batch, head, token) of [B,H,N,d] views, e.g. of the slices of a
+    fused projection output."""
     code = {torch.float32: SLA_F32, torch.bfloat16: SLA_BF16}[dtype]
-    return sla_params(B, H, N, d, bq, bkv, k_h, k_l, phi, code, layout)
+    return sla_params(B, H, N, d, bq, bkv, k_h, k_l, phi, code, layout, *strides)
 
 
 def sla_sizes(p: sla_params) -> sla_sizes_t:
@@ -103,10 +106,22 @@ def _buf(nbytes: int, device) -> torch.Tensor:
 
 
 def _dense(t: torch.Tensor, p: sla_params, what: str) -> torch.Tensor:
+    if p.layout == SLA_STRIDED:
+        want, st = (p.B, p.H, p.N, p.d), (p.stride_b, p.stride_h, p.stride_n, 1)
+        if tuple(t.shape) != want or tuple(t.stride()) != st or not t.is_cuda:
+            raise SLAError(f"{what}: expected a device tensor (view) of shape {want} with strides {st}")
+        return t
     want = (p.B, p.N, p.H, p.d) if p.layout == SLA_BNHD else (p.B, p.H, p.N, p.d)
     if tuple(t.shape) != want or not t.is_contiguous() or not t.is_cuda:
         raise SLAError(f"{what}: expected a contiguous device tensor of shape {want}")
     return t
+
+
+def _like(t: torch.Tensor, p: sla_params) -> torch.Tensor:
+    """an output tensor laid out as the params say (for strided views: the same strides)"""
+    if p.layout == SLA_STRIDED:
+        return torch.empty_strided(tuple(t.shape), tuple(t.stride()), dtype=t.dtype, device=t.device)
+    return torch.empty_like(t)
 
 
 def sla_build_mask(p: sla_params, Q: torch.Tensor, K: torch.Tensor,
@@ -144,7 +159,7 @@ def sla_forward(p: sla_params, Q, K, V, W, Mc, luts, O: Optional[torch.Tensor] =
     for n, t in (("Q", Q), ("K", K), ("V", V)):
         _dense(t, p, n)
     if O is None:
-        O = torch.empty_like(Q)
+        O = _like(Q, p)
     if saved is None and need_saved:
         saved = _buf(z.saved_bytes, Q.device)
     ws = workspace if workspace is not None else _buf(z.ws_forward_bytes, Q.device)
@@ -160,7 +175,7 @@ def sla_backward(p: sla_params, Q, K, V, W, Mc, luts, saved, dO,
     z = sla_sizes(p)
     _dense(dO, p, "dO")
     if out is None:
-        dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+        dQ, dK, dV = _like(Q, p), _like(K, p), _like(V, p)
         dW = torch.empty((p.d, p.d), dtype=torch.float32, device=Q.device)
     else:
         dQ, dK, dV, dW = out

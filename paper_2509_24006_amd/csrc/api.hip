@@ -20,7 +20,7 @@ int make_shape(const sla_params* p, Shape* s) {
   if (p->d != 64 && p->d != 128) return SLA_EUNSUPPORTED;
   if (p->phi != SLA_PHI_SOFTMAX && p->phi != SLA_PHI_ELU1) return SLA_EUNSUPPORTED;
   if (p->dtype != SLA_F32 && p->dtype != SLA_BF16) return SLA_EUNSUPPORTED;
-  if (p->layout != SLA_BHND && p->layout != SLA_BNHD) return SLA_EUNSUPPORTED;
+  if (p->layout != SLA_BHND && p->layout != SLA_BNHD && p->layout != SLA_STRIDED) return SLA_EUNSUPPORTED;
   const long long T = ((long long)p->N + kBlk - 1) / kBlk;
   if (T > kMaxT) return SLA_EUNSUPPORTED;
   if ((long long)p->B * p->H > 65535) return SLA_EUNSUPPORTED;  // grid.y / grid.z limit
@@ -37,8 +37,24 @@ int make_shape(const sla_params* p, Shape* s) {
   s->n_0 = (int)(T - nh - nl);
   s->phi = p->phi;
   s->dtype = p->dtype;
-  s->H = p->H;
-  s->layout = p->layout;
+  {
+    const long long N = p->N, H = p->H, d = p->d, esz = p->dtype == SLA_F32 ? 4 : 2;
+    long long sb = H * N * d, sh = N * d, sn = d;
+    if (p->layout == SLA_BNHD) {
+      sb = N * H * d;
+      sh = d;
+      sn = H * d;
+    } else if (p->layout == SLA_STRIDED) {
+      sb = p->stride_b;
+      sh = p->stride_h;
+      sn = p->stride_n;
+      const long long q = 16 / esz;   // elements per 16 bytes
+      if (sb < 0 || sh < 0 || sn < d || sb % q || sh % q || sn % q) return SLA_EINVAL;
+    }
+    // tile offsets inside a head are 32-bit byte offsets
+    if (N * sn * esz >= (1ll << 31)) return SLA_EUNSUPPORTED;
+    s->layv = Lay{sb, sh, (int)sn, (int)H};
+  }
   s->scale = 1.0f / sqrtf((float)p->d);
   return SLA_OK;
 }

@@ -25,13 +25,9 @@ struct Shape {
   int phi;    // 0 softmax over features, 1 elu+1
   int dtype;  // 0 float, 1 bf16
   float scale;  // float 1/sqrt(d)
-  int H;        // heads per batch
-  int layout;   // 0 [B,H,N,d], 1 [B,N,H,d]
+  Lay layv;     // where the caller's tensors keep their rows
   __host__ __device__ int state_row() const { return d * d + d; }
-  Lay lay() const {
-    if (layout == 1) return Lay{(long long)N * H * d, (long long)d, H * d, H};
-    return Lay{(long long)H * N * d, (long long)N * d, d, H};
-  }
+  Lay lay() const { return layv; }
 };
 
 __device__ __forceinline__ float to_f32(float x) { return x; }

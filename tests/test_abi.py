@@ -22,7 +22,7 @@ def test_exports_match_header():
 
 
 def test_struct_layout_matches_header():
-    assert ctypes.sizeof(sla.sla_params) == 56
+    assert ctypes.sizeof(sla.sla_params) == 80
     assert ctypes.sizeof(sla.sla_sizes_t) == 16 + 20 * 8
 
 
@@ -79,3 +79,14 @@ def test_layout_field_is_checked():
     bad = sla.make_params(1, 2, 128, 64, 0.5, 0.1, torch.bfloat16, layout=7)
     with pytest.raises(sla.SLAError):
         sla.sla_sizes(bad)
+
+
+def test_strided_layout_is_validated():
+    import torch
+    mk = lambda st, dt=torch.bfloat16: sla.make_params(2, 3, 128, 64, 0.5, 0.1, dt, layout=sla.SLA_STRIDED, strides=st)
+    assert sla.sla_sizes(mk((128 * 9 * 64, 64, 9 * 64))).T == 2        # slices of a fused [B,N,3,H,d] tensor
+    for bad in ((128 * 9 * 64, 64, 32), (128 * 9 * 64, 60, 9 * 64), (-8, 64, 9 * 64)):
+        with pytest.raises(sla.SLAError):
+            sla.sla_sizes(mk(bad))
+    with pytest.raises(sla.SLAError):                                   # 16-byte pieces: 4 floats
+        sla.sla_sizes(mk((128 * 9 * 64, 64, 9 * 64 + 2), torch.float32))

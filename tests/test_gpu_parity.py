@@ -119,6 +119,37 @@ def test_token_major_tensors(oracle, name):
         _compare(k, b[k], (f if k == "O" else g)[k], TOL[w.dtype])
 
 
+@pytest.mark.parametrize("name", ["small_bf16", "small_fp32"])
+def test_slices_of_a_fused_projection(oracle, name):
+    # Q, K, V as views into one [B,N,3,H,d] tensor, dO / O and the gradients laid out the same way
+    from paper_2509_24006_amd import binding as sla
+    w = wl.WORKLOADS[name]
+    x = wl.make_inputs(w)
+    B, H, N, d = x["Q"].shape
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    dev = torch.device("cuda:0")
+    qkv = torch.empty((B, N, 3, H, d), dtype=tdt, device=dev)
+    gout = torch.empty((B, N, 3, H, d), dtype=tdt, device=dev)   # dO in slot 0
+    for s_, k in enumerate(("Q", "K", "V")):
+        qkv[:, :, s_] = torch.from_numpy(x[k]).to(dev).to(tdt).transpose(1, 2)
+    gout[:, :, 0] = torch.from_numpy(x["dO"]).to(dev).to(tdt).transpose(1, 2)
+    view = lambda t, s_: t[:, :, s_].permute(0, 2, 1, 3)          # [B,H,N,d], strides (3NHd, d, 3Hd, 1)
+    Q, K, V, dO = view(qkv, 0), view(qkv, 1), view(qkv, 2), view(gout, 0)
+    p = sla.make_params(B, H, N, d, w.k_h, w.k_l, tdt, layout=sla.SLA_STRIDED, strides=tuple(Q.stride()[:3]))
+    W = torch.from_numpy(x["Proj"]).to(dev).to(tdt)
+    Mc, luts, _ = sla.sla_build_mask(p, Q, K)
+    O, saved = sla.sla_forward(p, Q, K, V, W, Mc, luts)
+    dqkv = torch.zeros_like(qkv)
+    out = (view(dqkv, 0), view(dqkv, 1), view(dqkv, 2), torch.empty((d, d), dtype=torch.float32, device=dev))
+    sla.sla_backward(p, Q, K, V, W, Mc, luts, saved, dO, out=out)
+    torch.cuda.synchronize()
+    ref = run_gpu(x, w.dtype, w.k_h, w.k_l)
+    f64 = lambda t: t.detach().double().cpu().numpy()
+    assert np.array_equal(Mc.cpu().numpy(), ref["Mc"])
+    for k, got in (("O", O), ("dQ", out[0]), ("dK", out[1]), ("dV", out[2]), ("dW", out[3])):
+        assert np.array_equal(f64(got), ref[k]), f"{k} differs from the packed call"
+
+
 def test_classify_given_scores_with_ties(oracle):
     from paper_2509_24006_amd import binding as sla
     rng = np.random.default_rng(0)
