@@ -449,6 +449,8 @@ hipError_t launch_classify(const float* scores, const Shape& s, int8_t* Mc, int3
     else if (s.T <= 128) classify_reg_kernel<2><<<grid, 256, 0, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx, col_cnt);
     else if (s.T <= 256) classify_reg_kernel<4><<<grid, 256, 0, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx, col_cnt);
     else if (s.T <= 512) classify_reg_kernel<8><<<grid, 256, 0, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx, col_cnt);
+    else if (s.T <= 1024) classify_reg_kernel<16><<<grid, 256, 0, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx, col_cnt);
+    else if (s.T <= 2048) classify_reg_kernel<32><<<grid, 256, 0, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx, col_cnt);
     else classify_kernel<<<grid, 256, lds, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx, col_cnt);
   }
   return hipGetLastError();

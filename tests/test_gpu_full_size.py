@@ -133,3 +133,22 @@ def test_image_shaped_batch_against_oracle(oracle):
     err = pins.rel_l2(f64(dW), g_all["dW"])
     print(f"  image dW: rel_l2 = {err:.3e}", flush=True)
     assert err <= tol
+
+
+@pytest.mark.parametrize("T", [2050, 3072])
+def test_masks_of_very_long_sequences(oracle, T):
+    # beyond 2048 blocks the classification keeps a row's keys in LDS instead of registers;
+    # 3072 blocks is the longest sequence the library takes.  Masks and tables bit for bit.
+    N, d, H = 64 * T - 57, 64, 1
+    rng = np.random.default_rng(T)
+    base = rng.standard_normal((1, H, T, d)).astype(np.float32)            # one direction per block ...
+    Q = wl.round_to_bf16(np.repeat(base, 64, axis=2)[:, :, :N] + 0.5 * rng.standard_normal((1, H, N, d)).astype(np.float32))
+    K = wl.round_to_bf16(np.repeat(base[:, :, ::-1], 64, axis=2)[:, :, :N] + 0.5 * rng.standard_normal((1, H, N, d)).astype(np.float32))
+    p = sla.make_params(1, H, N, d, 0.03, 0.2, torch.bfloat16)
+    Mc, luts, ws = sla.sla_build_mask(p, to_dev(Q, "bf16"), to_dev(K, "bf16"))
+    torch.cuda.synchronize()
+    Mo, so = oracle.build_mask(Q, K, 0.03, 0.2, return_scores=True)
+    assert np.array_equal(sla.mask_ws_views(p, ws)["scores"].cpu().numpy(), so)
+    assert np.array_equal(Mc.cpu().numpy(), Mo)
+    v = {k: t.cpu().numpy() for k, t in sla.lut_views(p, luts).items()}
+    check_luts(Mo, v["row_idx"], v["col_ptr"], v["col_rows"], v["ind"], v["ind_t"], v["col_order"])
