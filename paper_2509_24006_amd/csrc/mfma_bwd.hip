@@ -80,7 +80,16 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
   // of few heads at a time; most tile loads of this kernel miss the L2.
   const int BH = gridDim.x / Tn;
   int bh, rank;
-  if ((2 * BH) % 8 == 0 && Tn % 2 == 0) {
+  if (BH % 8 == 0 && BH >= 32 && Tn >= 128) {
+    // Many long heads: every XCD takes its BH / 8 heads one after the other, each heaviest list first.
+    // Its workgroups then share one head's Q and dO tiles and, being neighbours in rank, walk
+    // their lists at about the same pace; a head is a small part of the launch, so the late start
+    // of the last head's heavy lists costs little.
+    const int hp = BH / 8;
+    const int x = blockIdx.x & 7, m = blockIdx.x >> 3;
+    bh = hp * x + m / Tn;
+    rank = m % Tn;
+  } else if ((2 * BH) % 8 == 0 && Tn % 2 == 0) {
     const int upx = 2 * BH / 8;   // half-heads per XCD
     const int x = blockIdx.x & 7, m = blockIdx.x >> 3;
     const int u = upx * x + m % upx;
