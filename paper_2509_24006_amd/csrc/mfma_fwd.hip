@@ -134,13 +134,14 @@ __global__ __launch_bounds__(256, 4) void states_mfma_kernel(const bf16* __restr
 // softmax statistics are per-lane scalars and P goes from C registers straight into the B
 // operand of the second product.  Each wave runs its own online softmax over its key halves;
 // the two streams of a query half are merged at the end.  K_j and V_j go global -> LDS
-// directly (swizzled, double-buffered, one barrier per step); V is read transposed.
+// directly (swizzled, through a ring of five slots, one barrier per step); V is read transposed.
+// The scores of step s + 1 are formed under the exponentials of step s.
 template <int D>
 struct FwdLds {
   // Five tile slots used as one ring by the load sequence K_0 V_0 K_1 V_1 ...: load n goes to slot
-  // n % 5.  K_s is dead after the score products of step s and V_s after the step, so with one
-  // barrier in the middle of a step and one at its end each freed slot is refilled at once and
-  // every tile is requested two steps before it is needed (an L2 miss costs about two steps).  At
+  // n % 5.  The scores S_s are formed during step s - 1, so at the barrier that opens step s the
+  // slots of K_s and V_{s-1} are free and take K_{s+2} and V_{s+2}: every tile is requested two
+  // steps before it is needed (an L2 miss costs about two steps).  At
   // d = 128 the ring is all of a CU's LDS for two workgroups.  After the loop the slots hold the
   // exchange between the two key streams, H_i, the projection matrix and the softmax statistics.
   static constexpr int TILE = SwzTile<D>::BYTES;
