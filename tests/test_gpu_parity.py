@@ -180,3 +180,19 @@ def test_forward_without_saved_matches(oracle):
     O2, sv = sla.sla_forward(p, Q, K, V, W, Mc, luts, need_saved=False)
     torch.cuda.synchronize()
     assert sv is None and torch.equal(O1, O2)
+
+
+def test_calls_follow_the_given_stream(oracle):
+    # every kernel of a call is enqueued on the stream handed in: the same results on a side
+    # stream (default priority) as on the current one, with no host synchronisation in between
+    from paper_2509_24006_amd import binding as sla
+    w = wl.WORKLOADS["small_bf16"]
+    x = wl.make_inputs(w)
+    ref = run_gpu(x, "bf16", w.k_h, w.k_l)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        got = run_gpu(x, "bf16", w.k_h, w.k_l)
+    torch.cuda.synchronize()
+    for k in ref:
+        assert np.array_equal(ref[k], got[k]), k
