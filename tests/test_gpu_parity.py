@@ -196,3 +196,29 @@ def test_calls_follow_the_given_stream(oracle):
     torch.cuda.synchronize()
     for k in ref:
         assert np.array_equal(ref[k], got[k]), k
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_small_problems(oracle, seed):
+    # a seeded draw over storage type, head size, batch, heads, (ragged) length, k_h, k_l, feature
+    # map and memory order
+    rng = np.random.default_rng(1000 + seed)
+    dtype = str(rng.choice(["bf16", "fp32"], p=[0.7, 0.3]))
+    d = int(rng.choice([64, 128])) if dtype == "bf16" else 64
+    B, H = int(rng.integers(1, 3)), int(rng.integers(1, 4))
+    N = int(rng.choice([rng.integers(1, 200), rng.integers(200, 1500), 64 * rng.integers(1, 20),
+                        64 * rng.integers(1, 20) + 1]))
+    k_h = float(rng.choice([0.0, 0.05, 0.1, 0.3, 0.5, 1.0]))
+    k_l = float(rng.choice([0.0, 0.1, 0.3, 0.9]))
+    phi, tm = int(rng.integers(0, 2)), bool(rng.integers(0, 2))
+    x = {k: rng.standard_normal((B, H, N, d)).astype(np.float32) for k in ("Q", "K", "V", "dO")}
+    x["Proj"] = (rng.standard_normal((d, d)) * 0.05).astype(np.float32)
+    if dtype == "bf16":
+        x = {k: wl.round_to_bf16(v) for k, v in x.items()}
+    print(f"{dtype} d={d} B={B} H={H} N={N} k_h={k_h} k_l={k_l} phi={phi} token_major={tm}", flush=True)
+    Mc, s, f, g = _oracle_all(oracle, x, k_h, k_l, phi)
+    r = run_gpu(x, dtype, k_h, k_l, phi, token_major=tm)
+    assert np.array_equal(r["scores"], s) and np.array_equal(r["Mc"], Mc)
+    check_luts(r["Mc"], r["row_idx"], r["col_ptr"], r["col_rows"], r["ind"], r["ind_t"], r["col_order"])
+    for k in ("O", "Os", "Ol", "dQ", "dK", "dV", "dW"):
+        _compare(k, r[k], (f if k in f else g)[k], TOL[dtype], floor_rms=0.05)
