@@ -21,10 +21,10 @@ namespace {
 template <int D>
 struct PreLds {
   static constexpr int TILE = SwzTile<D>::BYTES;
-  // slots: 0 dO, then dO^l | 1 O^s, then a, then rows 0..63 of H_i | 2 O^l, then rows 64.. of H_i | 3 Q
-  // (a fifth slot for H_i would let it arrive earlier, but 5 tiles + 1 KB is just over half a CU's LDS)
+  // slots: 0 dO, then dO^l | 1 O^s, then a, then rows 64.. of H_i | 2 O^l, then rows 0..63 of H_i | 3 Q
+  // (a fifth slot for H_i would let all of it arrive early, but 5 tiles + 1 KB is just over half a CU's LDS)
   static constexpr int F_OFF = 4 * TILE;
-  static constexpr int BYTES = F_OFF + 4 * kBlk * 4;   // D^l partial [par][q], dot partial [par][q]
+  static constexpr int BYTES = F_OFF + 4 * kBlk * 4 + D * 4;   // D^l partial [par][q], dot partial [par][q], Z_i
   static constexpr int STG = 32 * (64 * (D / 32) + 16);   // staging of one wave, laid over slots 1..3
   static_assert(4 * STG <= 3 * TILE, "output staging fits over three slots");
 };
@@ -44,6 +44,7 @@ __global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   float* dlp = reinterpret_cast<float*>(smem + Lds::F_OFF);   // [par][64]
   float* dotp = dlp + 2 * kBlk;                               // [par][64]
+  float* zl = dotp + 2 * kBlk;                                // Z_i [D]
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
   const int qh = w & 1, par = w >> 1;
   const int i = blockIdx.x, bh = blockIdx.y;
@@ -62,6 +63,16 @@ __global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
   if (n_0 > 0) {
     issue_tile_load<D>(Ol + base, rows, lds0, S2, ldv);
     tl.load(head_rsrc<D>(Q + lay.head(bh), N, 2 * lay.ts), i, S3);
+  }
+  // rows of W for this wave's dO^l tiles, and Z_i, requested together with the tiles
+  bf16x8 wfr[HT][KT];
+  if (n_0 > 0) {
+#pragma unroll
+    for (int h2 = 0; h2 < HT; ++h2)
+#pragma unroll
+      for (int t = 0; t < KT; ++t)
+        wfr[h2][t] = *reinterpret_cast<const bf16x8*>(W + (size_t)(32 * (par * HT + h2) + ln) * D + 16 * t + 8 * g);
+    if (tid < D) zl[tid] = Zs[((size_t)bh * Tn + i) * D + tid];
   }
   wait_vm0();
   __syncthreads();
@@ -86,7 +97,6 @@ __global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
   bf16x8 qf[KT];
 #pragma unroll
   for (int t = 0; t < KT; ++t) qf[t] = lds_row(smem, qa.row(t) + S3);
-  const float* Z = Zs + ((size_t)bh * Tn + i) * D;
   __syncthreads();   // dO and O^s are consumed: their slots take dO^l and a
   const int rowb = qrow * T::ROW_BYTES, rsw = swz<D>(qrow);
   // dO^l^T[b][q] = sum_e W[b][e] dO[q][e]; this wave: b-tiles par*HT .. par*HT+HT-1
@@ -96,10 +106,7 @@ __global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
     const int bt = par * HT + h2;
     f32x16 gl = zero_f32x16();
 #pragma unroll
-    for (int t = 0; t < KT; ++t) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(W + (size_t)(32 * bt + ln) * D + 16 * t + 8 * g);
-      gl = mfma32(a, gf[t], gl);
-    }
+    for (int t = 0; t < KT; ++t) gl = mfma32(wfr[h2][t], gf[t], gl);
 #pragma unroll
     for (int r4 = 0; r4 < 4; ++r4) {
       const int b0 = 32 * bt + 8 * r4 + 4 * g;
@@ -118,17 +125,35 @@ __global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
   dl = half_sum(dl);
   if (g == 0) dlp[par * kBlk + qrow] = dl;
   // phi(Q), its normaliser, and a = phi(Q) / den as a row-major tile (this wave: half of the features)
-  float qmx, qinv;
-  phi_stats<KT>(qf, phi, qmx, qinv);
+  float qmx = 0.0f, qinv = 1.0f;
   float den = 0.0f;
   float yq[KT][8];
+  if (phi == 0) {   // softmax over the features: the exponentials are formed once
+    qmx = -INFINITY;
+#pragma unroll
+    for (int t = 0; t < KT; ++t)
+#pragma unroll
+      for (int s = 0; s < 8; ++s) qmx = fmaxf(qmx, (float)qf[t][s]);
+    qmx = half_max(qmx);
+    float sum = 0.0f;
+#pragma unroll
+    for (int t = 0; t < KT; ++t)
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        yq[t][s] = fast_exp2(((float)qf[t][s] - qmx) * kLog2e);
+        sum += yq[t][s];
+      }
+    sum = half_sum(sum);
+    qinv = 1.0f / sum;
+  }
 #pragma unroll
   for (int t = 0; t < KT; ++t) {
-    const f32x4 z0 = *reinterpret_cast<const f32x4*>(Z + 16 * t + 8 * g);
-    const f32x4 z1 = *reinterpret_cast<const f32x4*>(Z + 16 * t + 8 * g + 4);
+    const f32x4 z0 = *reinterpret_cast<const f32x4*>(zl + 16 * t + 8 * g);
+    const f32x4 z1 = *reinterpret_cast<const f32x4*>(zl + 16 * t + 8 * g + 4);
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
-      const float y = (float)(__bf16)phi_val((float)qf[t][s], phi, qmx, qinv);
+      const float x = (float)qf[t][s];
+      const float y = (float)(__bf16)(phi == 0 ? yq[t][s] * qinv : (x > 0.0f ? x + 1.0f : fast_exp2(x * kLog2e)));
       yq[t][s] = y;
       den = fmaf(y, s < 4 ? z0[s] : z1[s - 4], den);
     }
@@ -143,21 +168,14 @@ __global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
     for (int s = 0; s < 8; ++s) av[s] = (__bf16)(yq[t][s] * dinv);
     *reinterpret_cast<bf16x8*>(smem + S1 + rowb + (((2 * t + g) ^ rsw) << 4)) = av;
   }
-  __syncthreads();   // dO^l and a are complete
+  __syncthreads();   // dO^l and a are complete; O^l is consumed: its slot takes rows 0..63 of H_i
+  issue_tile_load<D>(Hrow, min(kBlk, D), lds0, S2, ldv);
   const float Dl = dlp[qrow] + dlp[kBlk + qrow];
   bf16* out = dHZ + ((size_t)bh * Tn + i) * (D * D + D);
-  // dZ_i[c] = - sum_q a[q][c] D^l_q
-  if (tid < D) {
-    float z = 0.0f;
-    for (int q = 0; q < kBlk; ++q) {
-      const bf16 av = *reinterpret_cast<const bf16*>(smem + S1 + swz_chunk_off<D>(q, tid >> 3) + (tid & 7) * 2);
-      z = fmaf(__bfloat162float(av), dlp[q] + dlp[kBlk + q], z);
-    }
-    out[(size_t)D * D + tid] = __float2bfloat16(-z);
-  }
   // dH_i^T[b][c] = sum_q dO^l[q][b] a[q][c]: both operands contracted over tile rows; formed with b
   // along the lanes (C tile rows = c), so that a lane holds consecutive c of one stored row.
-  // Wave w owns b-tile w.
+  // Wave w owns b-tile w.  dZ_i[c] = - sum_q a[q][c] D^l_q rides along as one more column: the wave
+  // multiplies its own c-tile of a^T by D^l (in the k order of the transposing read).
   static_assert(NT <= 4, "one b-tile per wave");
   TileAddr<D> ad;
   ad.init(0, l);
@@ -165,19 +183,39 @@ __global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
 #pragma unroll
   for (int ct = 0; ct < NT; ++ct) acc[ct] = zero_f32x16();
   if (w < NT) {
+    f32x16 zacc = zero_f32x16();
 #pragma unroll
     for (int u = 0; u < kBlk / 16; ++u) {
       const bf16x8 bo = lds_tr<D>(smem, ad.tr(0, w) + S0 + u * RB, ad.tr(1, w) + S0 + u * RB);
+      // slots 0..3: queries 16 u + 4 g .., slots 4..7: queries 16 u + 8 + 4 g ..; D^l as the sum of two
+      // bf16 values (the terms of dZ cancel: one bf16 value per D^l would not do)
+      bf16x8 dlb, dlc;
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        const int qq = 16 * u + 4 * g + (s & 3) + 2 * (s & 4);
+        const float v = dlp[qq] + dlp[kBlk + qq];
+        dlb[s] = (__bf16)v;
+        dlc[s] = (__bf16)(v - (float)dlb[s]);
+      }
 #pragma unroll
       for (int ct = 0; ct < NT; ++ct) {
         const bf16x8 ao = lds_tr<D>(smem, ad.tr(0, ct) + S1 + u * RB, ad.tr(1, ct) + S1 + u * RB);
         acc[ct] = mfma32(ao, bo, acc[ct]);
+        if (ct == w) zacc = mfma32(ao, dlc, mfma32(ao, dlb, zacc));   // every column of this tile: sum_q a[q][c] D^l_q
+      }
+    }
+    if (ln == 0) {
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        bf16x4 pk;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) pk[r] = (__bf16)(-zacc[4 * r4 + r]);
+        *reinterpret_cast<bf16x4*>(out + (size_t)D * D + 32 * w + 8 * r4 + 4 * g) = pk;
       }
     }
   }
-  __syncthreads();   // a and O^l are consumed: their slots take H_i
-  issue_tile_load<D>(Hrow, min(kBlk, D), lds0, S1, ldv);
-  if (D > kBlk) issue_tile_load<D>(Hrow + (size_t)kBlk * D, D - kBlk, lds0, S2, ldv);
+  __syncthreads();   // a is consumed: its slot takes the other rows of H_i
+  if (D > kBlk) issue_tile_load<D>(Hrow + (size_t)kBlk * D, D - kBlk, lds0, S1, ldv);
   wait_vm0();
   __syncthreads();
   // dQ^phi^T[c][q] = (sum_b H[c][b] dO^l[q][b] - D^l_q Z[c]) / den_q; this wave: c-tiles of par.  H^T is
@@ -198,7 +236,7 @@ __global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
       gb[e] = v0[e];
       gb[4 + e] = v1[e];
     }
-    const int mbase = (t / 4 ? S2 : S1) + (t % 4) * RB;   // rows b = 16 t .. of the stored matrix
+    const int mbase = (t / 4 ? S1 : S2) + (t % 4) * RB;   // rows b = 16 t .. of the stored matrix
 #pragma unroll
     for (int h2 = 0; h2 < HT; ++h2) {
       const int ct = par * HT + h2;
@@ -211,7 +249,7 @@ __global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
 #pragma unroll
     for (int r4 = 0; r4 < 4; ++r4) {
       const int c0 = 32 * ct + 8 * r4 + 4 * g;
-      const f32x4 z4 = *reinterpret_cast<const f32x4*>(Z + c0);
+      const f32x4 z4 = *reinterpret_cast<const f32x4*>(zl + c0);
       const bf16x4 q4 = *reinterpret_cast<const bf16x4*>(smem + S3 + rowb + (((c0 >> 3) ^ rsw) << 4) + (c0 & 7) * 2);
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
