@@ -343,7 +343,9 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
 #pragma unroll
     for (int et = 0; et < NT; ++et)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) myx[(et * 16 + r) * 64 + l] = oT[et][r];
+      for (int r4 = 0; r4 < 4; ++r4)
+        *reinterpret_cast<f32x4*>(myx + ((et * 4 + r4) * 64 + l) * 4) =
+            f32x4{oT[et][4 * r4], oT[et][4 * r4 + 1], oT[et][4 * r4 + 2], oT[et][4 * r4 + 3]};
   }
   __syncthreads();
   const size_t orow0 = ((size_t)bh * N + q0 + 32 * qh) * D;   // first query of this wave
@@ -352,7 +354,11 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
 #pragma unroll
     for (int et = 0; et < NT; ++et)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) oT[et][r] += myx[(et * 16 + r) * 64 + l];
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const f32x4 xv = *reinterpret_cast<const f32x4*>(myx + ((et * 4 + r4) * 64 + l) * 4);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) oT[et][4 * r4 + r] += xv[r];
+      }
     if (L && g == 0 && qok) L[(size_t)bh * N + q0 + qrow] = Lval;
     if (Os) store_rows_bf16<NT>(mystage, oT, Os + orow0, D, wrows, l);
   }
@@ -420,14 +426,20 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
 #pragma unroll
       for (int et = 0; et < NT; ++et)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) myx[(et * 16 + r) * 64 + l] = oT[et][r];
+        for (int r4 = 0; r4 < 4; ++r4)
+          *reinterpret_cast<f32x4*>(myx + ((et * 4 + r4) * 64 + l) * 4) =
+              f32x4{oT[et][4 * r4], oT[et][4 * r4 + 1], oT[et][4 * r4 + 2], oT[et][4 * r4 + 3]};
     }
     __syncthreads();
     if (par == 0) {
 #pragma unroll
       for (int et = 0; et < NT; ++et)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) oT[et][r] += myx[(et * 16 + r) * 64 + l];
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const f32x4 xv = *reinterpret_cast<const f32x4*>(myx + ((et * 4 + r4) * 64 + l) * 4);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) oT[et][4 * r4 + r] += xv[r];
+        }
     }
   }
   if (par == 0) {
