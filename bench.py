@@ -54,6 +54,10 @@ def main() -> int:
     ap.add_argument("--k-h", type=float, default=None)
     ap.add_argument("--dense-steps", type=int, default=1, help="0 skips the dense reference run")
     ap.add_argument("--cpu-heads", type=int, default=4, help="0 skips the CPU oracle baseline")
+    ap.add_argument("--settle-ms", type=float, default=200.0,
+                    help="before the warm-up steps, run untimed steps for this long so that the GPU's clock "
+                         "has left its idle state (a cold start runs the same kernels at about 1.6 instead of "
+                         "2.0 GHz); 0 disables")
     ap.add_argument("--token-major", action="store_true",
                     help="hand the library [B,N,H,d] tensors (SLA_BNHD) instead of [B,H,N,d]")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -132,6 +136,13 @@ def main() -> int:
     def step():
         mask(); fwd(); bwd()
 
+    settle_steps = 0
+    if args.settle_ms > 0:
+        t_end = time.perf_counter() + args.settle_ms * 1e-3
+        while time.perf_counter() < t_end:
+            step()
+            torch.cuda.synchronize()
+            settle_steps += 1
     for _ in range(args.warmup):
         step()
     ms_step, ms_step_ev = timed(step, args.steps)
@@ -238,6 +249,7 @@ def main() -> int:
         "kernels": kernels,
         "roofline": roof,
         "cpu_baseline": cpu,
+        "settle_steps": settle_steps,
         "input_gen_s": t_gen,
     }
     print(json.dumps(out))
