@@ -90,3 +90,11 @@ def test_strided_layout_is_validated():
             sla.sla_sizes(mk(bad))
     with pytest.raises(sla.SLAError):                                   # 16-byte pieces: 4 floats
         sla.sla_sizes(mk((128 * 9 * 64, 64, 9 * 64 + 2), torch.float32))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
