@@ -222,3 +222,55 @@ def test_random_small_problems(oracle, seed):
     check_luts(r["Mc"], r["row_idx"], r["col_ptr"], r["col_rows"], r["ind"], r["ind_t"], r["col_order"])
     for k in ("O", "Os", "Ol", "dQ", "dK", "dV", "dW"):
         _compare(k, r[k], (f if k in f else g)[k], TOL[dtype], floor_rms=0.05)
+
+
+def test_a_captured_step_replays_to_the_eager_results():
+    # mask + forward + backward captured into one HIP graph (no allocation, no memset node, no host
+    # synchronisation inside the calls); every replay, with eager calls and synchronisations in
+    # between, gives what the eager calls gave
+    from paper_2509_24006_amd import binding as sla
+    w = wl.WORKLOADS["small_bf16"]
+    x = wl.make_inputs(w)
+    B, H, N, d = x["Q"].shape
+    dev = torch.device("cuda:0")
+    t = lambda a: torch.from_numpy(a).to(dev).to(torch.bfloat16)
+    Q, K, V, W, dO = t(x["Q"]), t(x["K"]), t(x["V"]), t(x["Proj"]), t(x["dO"])
+    p = sla.make_params(B, H, N, d, w.k_h, w.k_l, torch.bfloat16)
+    z = sla.sla_sizes(p)
+    u8 = lambda n: torch.empty(max(int(n), 256), dtype=torch.uint8, device=dev)
+    Mc = torch.empty((B, H, z.T, z.T), dtype=torch.int8, device=dev)
+    luts, ws_m, ws_f, ws_b, saved = (u8(n) for n in (z.luts_bytes, z.ws_mask_bytes, z.ws_forward_bytes,
+                                                    z.ws_backward_bytes, z.saved_bytes))
+    O = torch.empty_like(Q)
+    out = (torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V),
+           torch.empty((d, d), dtype=torch.float32, device=dev))
+
+    def step():
+        sla.sla_build_mask(p, Q, K, workspace=ws_m, Mc=Mc, luts=luts)
+        sla.sla_forward(p, Q, K, V, W, Mc, luts, O=O, saved=saved, workspace=ws_f)
+        sla.sla_backward(p, Q, K, V, W, Mc, luts, saved, dO, workspace=ws_b, out=out)
+
+    results = lambda: [a.clone() for a in (Mc, O) + out]
+    step()
+    torch.cuda.synchronize()
+    ref = results()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for rep in range(3):
+        for a in (Mc, O) + out:
+            a.zero_()
+        luts.zero_()
+        saved.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(ref, results()):
+            assert torch.equal(a, b), f"replay {rep} differs from the eager result"
+        step()   # eager work between the replays
+        torch.cuda.synchronize()
