@@ -235,7 +235,8 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
 #pragma unroll
     for (int t = 0; t < KT; ++t) sT = mfma32(lds_row(smem, ad.row(t)), qf[t], sT);
   }
-  for (int s = 0; s < n_h; ++s) {
+  // (two copies of the step with the roles of the two score tiles swapped: no register copies)
+  auto step = [&](int s, f32x16& sT, f32x16& sN) __attribute__((always_inline)) {
     const int cols = min(kBlk, N - j0 * kBlk);
     const int j3 = lut[min(s + 3, n_h - 1)];   // needed in the next step
     // V_s and K_{s+1} have landed; the load issued after them (V_{s+1}) may stay in flight
@@ -291,7 +292,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
     }
     const float moff = m == -INFINITY ? 0.0f : -m * c2;   // a half with no valid key yet
     float psum = 0.0f;
-    f32x16 sN = zero_f32x16();
+    sN = zero_f32x16();
     static_assert(KT == 8 || KT == 4, "two or four exponentials per product of the next scores");
 #pragma unroll
     for (int t = 0; t < KT; ++t) {
@@ -310,10 +311,14 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
 #pragma unroll
       for (int et = 0; et < NT; ++et) oT[et] = mfma32(va[u][et], pf, oT[et]);
     }
-    sT = sN;
     j0 = j1;
     j1 = j2;
     j2 = j3;
+  };
+  f32x16 sU = zero_f32x16();
+  for (int s = 0; s < n_h; s += 2) {
+    step(s, sT, sU);
+    if (s + 1 < n_h) step(s + 1, sU, sT);
   }
   // ---- merge the two key-tile streams (par 0 / par 1) of each query half
   lsum = half_sum(lsum);
