@@ -11,6 +11,7 @@ the CPU oracle timed on a bounded sample.
 from __future__ import annotations
 
 import argparse
+from dataclasses import replace
 import json
 import os
 import sys
@@ -52,12 +53,14 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="wan")
     ap.add_argument("--k-h", type=float, default=None)
+    ap.add_argument("--k-l", type=float, default=None, help="fraction of negligible blocks (changes the density of the linear branch's marginal blocks)")
     ap.add_argument("--dense-steps", type=int, default=1, help="0 skips the dense reference run")
     ap.add_argument("--cpu-heads", type=int, default=4, help="0 skips the CPU oracle baseline")
     ap.add_argument("--settle-ms", type=float, default=200.0,
                     help="before the warm-up steps, run untimed steps for this long so that the GPU's clock "
                          "has left its idle state (a cold start runs the same kernels at about 1.6 instead of "
                          "2.0 GHz); 0 disables")
+    ap.add_argument("--bq", type=int, default=64, help="query block size of the mask (64, 128, 192, 256)")
     ap.add_argument("--token-major", action="store_true",
                     help="hand the library [B,N,H,d] tensors (SLA_BNHD) instead of [B,H,N,d]")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -80,6 +83,8 @@ def main() -> int:
     w = wl.WORKLOADS[args.workload]
     if args.k_h is not None:
         w = wl.sweep(args.k_h) if args.workload == "wan" else w
+    if args.k_l is not None:
+        w = replace(w, name=f"{w.name}_kl{args.k_l:g}", k_l=args.k_l)
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
     t0 = time.time()
     x = wl.make_inputs(w)
@@ -94,7 +99,7 @@ def main() -> int:
     def buffers(p):
         z = sla.sla_sizes(p)
         u8 = lambda n: torch.empty(max(int(n), 256), dtype=torch.uint8, device="cuda")
-        return dict(z=z, Mc=torch.empty((p.B, p.H, z.T, z.T), dtype=torch.int8, device="cuda"),
+        return dict(z=z, Mc=torch.empty((p.B, p.H, z.Tq, z.T), dtype=torch.int8, device="cuda"),
                     luts=u8(z.luts_bytes), ws_m=u8(z.ws_mask_bytes), ws_f=u8(z.ws_forward_bytes),
                     ws_b=u8(z.ws_backward_bytes), saved=u8(z.saved_bytes), O=torch.empty_like(Q),
                     out=(torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V),
@@ -129,7 +134,7 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    p = sla.make_params(w.B, w.H, w.N, w.d, w.k_h, w.k_l, tdt, layout=lay)
+    p = sla.make_params(w.B, w.H, w.N, w.d, w.k_h, w.k_l, tdt, layout=lay, bq=args.bq)
     b = buffers(p)
     mask, fwd, bwd = phases(p, b)
 
@@ -162,9 +167,9 @@ def main() -> int:
 
     Mc = b["Mc"].cpu().numpy()
     z = b["z"]
-    f_fwd, f_bwd = fl.executed_flops(Mc, w.N, w.d)
+    f_fwd, f_bwd = fl.executed_flops(Mc, w.N, w.d, bq=args.bq)
     d_fwd, d_bwd = fl.dense_flops(w.B * w.H, w.N, w.d)
-    counts = dict(pair_elems=fl.critical_pair_elems(Mc, w.N), d=w.d, BH=w.B * w.H, N=w.N, T=z.T,
+    counts = dict(pair_elems=fl.critical_pair_elems(Mc, w.N, bq=args.bq), d=w.d, BH=w.B * w.H, N=w.N, T=z.T,
                   esize=2 if w.dtype == "bf16" else 4)
 
     # roofline of the dominant kernel (largest share of the step)
@@ -189,7 +194,7 @@ def main() -> int:
 
     # HBM traffic of that kernel per launch, from the committed counter summary (two rocprofv3 --pmc
     # runs of this command, FETCH_SIZE and WRITE_SIZE, scaled by the calibration kernel), if present
-    if roof is not None:
+    if roof is not None and args.bq == 64:
         tpath = os.path.join(ROOT, "profiles", f"pmc_traffic_{roof['kernel']}_{w.name}.txt")
         if os.path.exists(tpath):
             for line in open(tpath):
@@ -218,11 +223,11 @@ def main() -> int:
         xs = {k: (v[:, hs] if v.ndim == 4 else v) for k, v in x.items()}
         os.environ.setdefault("OMP_NUM_THREADS", str(len(hs)))
         t = time.perf_counter()
-        Mo = orc.build_mask(xs["Q"], xs["K"], w.k_h, w.k_l)
-        fo = orc.forward(xs["Q"], xs["K"], xs["V"], xs["Proj"], Mo, dtype=np.float32)
-        orc.backward(xs["Q"], xs["K"], xs["V"], xs["Proj"], Mo, fo, xs["dO"], dtype=np.float32)
+        Mo = orc.build_mask(xs["Q"], xs["K"], w.k_h, w.k_l, bq=args.bq)
+        fo = orc.forward(xs["Q"], xs["K"], xs["V"], xs["Proj"], Mo, bq=args.bq, dtype=np.float32)
+        orc.backward(xs["Q"], xs["K"], xs["V"], xs["Proj"], Mo, fo, xs["dO"], bq=args.bq, dtype=np.float32)
         sec = time.perf_counter() - t
-        sf, sb = fl.executed_flops(Mo, w.N, w.d)
+        sf, sb = fl.executed_flops(Mo, w.N, w.d, bq=args.bq)
         cpu = {"value": (sf + sb) / sec / 1e12, "unit": "TFLOP/s", "cores": len(hs) * w.B,
                "kind": "oracle", "seconds": sec,
                "sample": f"heads 0..{len(hs) - 1} of {w.H} (mask + forward + backward, float), "
@@ -235,7 +240,7 @@ def main() -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step_ev,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype,
         "data": "synthetic",
-        "config": {"workload": f"{w.name}: B={w.B} H={w.H} d={w.d} N={w.N} grid={w.grid} block=64 "
+        "config": {"workload": f"{w.name}: B={w.B} H={w.H} d={w.d} N={w.N} grid={w.grid} block={args.bq}x64 "
                                f"tensors={'[B,N,H,d]' if args.token_major else '[B,H,N,d]'} "
                                f"k_h={w.k_h} k_l={w.k_l} phi=softmax; n_h={z.n_h} n_l={z.n_l} "
                                f"n_0={z.n_0}; seeded Fourier-feature Q/K/V stand in for Wan2.1 activations"},

@@ -4,8 +4,9 @@
  * (Section 2.1; tensors here are packed [B, H, N, d] or [B, N, H, d], d contiguous):
  *
  *   1. block scores  s = pool(Q) pool(K)^T / sqrt(d), pool = mean over each block of
- *      b = 64 consecutive tokens (Eq. 2; the last block may be short);
- *   2. a three-way block mask M_c[i, j] in {1, 0, -1}: per query-block row the n_h
+ *      b_q (queries) or b_kv = 64 (keys) consecutive tokens (Eq. 2; the last block may be
+ *      short); T_q = ceil(N / b_q) query blocks, T = ceil(N / 64) key blocks;
+ *   2. a three-way block mask M_c[i, j] in {1, 0, -1}, T_q x T: per query-block row the n_h
  *      highest scores are critical (1), the n_l lowest of the rest negligible (-1),
  *      the others marginal (0) (Eq. 3, Alg. 1 mask line);
  *   3. O^s: online-softmax attention over the critical blocks only (Eq. 4);
@@ -25,7 +26,7 @@
  *   - Outputs are overwritten, never accumulated into.
  *   - Return value: SLA_OK, or a negative error code; nothing was enqueued when the code
  *     is SLA_EINVAL, SLA_EUNSUPPORTED or SLA_ENOSPACE.
- *   - Block counts: n_h = floor(k_h*T + 1/2) clamped to [0, T];
+ *   - Block counts (T = number of key blocks): n_h = floor(k_h*T + 1/2) clamped to [0, T];
  *     n_l = min(floor(k_l*T + 1/2), T - n_h); n_0 = T - n_h - n_l.  Every row of M_c has
  *     exactly n_h ones and n_l minus-ones.  Ties: critical = first n_h under (score
  *     descending, block index ascending); negligible = first n_l of the remaining
@@ -50,7 +51,10 @@ enum { SLA_BHND = 0, SLA_BNHD = 1, SLA_STRIDED = 2 }; /* memory order of Q,K,V,O
 /* Problem statement (Alg. 1 input line: Q, K, V, block sizes, k_h, k_l; Section 6.1: phi). */
 typedef struct sla_params {
   int32_t B, H, N, d; /* batch, heads, tokens, head dim; d in {64, 128}; N >= 1            */
-  int32_t bq, bkv;    /* query / key block size; only 64, 64 is supported                  */
+  int32_t bq, bkv;    /* query / key block size: bkv = 64; bq = 64, 128, 192 or 256.  The
+                         kernels work on 64-token tiles; a larger query block gives its
+                         mask row to each of its 64-token tiles, so tables and saved states
+                         are per tile (T rows) while M_c has T_q = ceil(N / bq) rows       */
   double k_h, k_l;    /* fractions in [0, 1] of critical / negligible blocks per row       */
   int32_t phi;        /* SLA_PHI_*                                                         */
   int32_t dtype;      /* SLA_F32 or SLA_BF16; statistics and dW are always float           */
@@ -72,10 +76,12 @@ typedef struct sla_params {
  * first the d x d matrix TRANSPOSED (element [c][e] of the paper's matrix at e*d + c),
  * then the d-vector. */
 typedef struct sla_sizes_t {
-  int32_t T, n_h, n_l, n_0;
-  uint64_t mask_bytes;        /* int8  [B,H,T,T]                                            */
+  int32_t T, n_h, n_l, n_0;   /* T = ceil(N / 64): key blocks = 64-token query tiles        */
+  int32_t Tq, reserved;       /* Tq = ceil(N / bq): rows of M_c (= T when bq = 64)          */
+  uint64_t mask_bytes;        /* int8  [B,H,Tq,T]                                           */
   uint64_t luts_bytes;        /* the buffer ends with scratch of the table build             */
-  uint64_t lut_row_idx;       /* int32 [B,H,T,n_h]   ascending critical key blocks per row  */
+  uint64_t lut_row_idx;       /* int32 [B,H,T,n_h]   ascending critical key blocks per query tile
+                                 (below, row i of M_c stands for query tile i: the row i / (bq/64)) */
   uint64_t lut_col_ptr;       /* int32 [B,H,T+1]     CSC pointers of the critical entries   */
   uint64_t lut_col_rows;      /* int32 [B,H,T*n_h]   ascending query blocks per key block   */
   uint64_t lut_ind;           /* uint64 [B,H,T,Tw]   bit b of word q: M_c[i][64q+b] = 0 (marginal), Tw = ceil(T/64) */
@@ -90,9 +96,9 @@ typedef struct sla_sizes_t {
   uint64_t saved_Z;           /* ... float [B,H,T,d] (Z_i) here; float tensors: = saved_HZ + 4 d d,
                                  rows d*d + d floats apart                                       */
   uint64_t ws_mask_bytes;
-  uint64_t ws_mask_qbar;      /* float [B,H,T,d]     pool(Q), left in the workspace         */
+  uint64_t ws_mask_qbar;      /* float [B,H,Tq,d]    pool(Q), left in the workspace         */
   uint64_t ws_mask_kbar;      /* float [B,H,T,d]     pool(K)                                */
-  uint64_t ws_mask_scores;    /* float [B,H,T,T]     pre-softmax block scores s             */
+  uint64_t ws_mask_scores;    /* float [B,H,Tq,T]    pre-softmax block scores s             */
   uint64_t ws_forward_bytes;
   uint64_t ws_backward_bytes;
 } sla_sizes_t;
@@ -101,7 +107,7 @@ typedef struct sla_sizes_t {
 int sla_sizes(const sla_params* p, sla_sizes_t* out);
 
 /* Eq. 2 - Eq. 3 and the lookup tables of Appendix A.3.
- * Q, K: dtype [B,H,N,d] (or [B,N,H,d], see sla_params.layout).  Mc: int8 [B,H,T,T] (out).  luts: luts_bytes (out).
+ * Q, K: dtype [B,H,N,d] (or [B,N,H,d], see sla_params.layout).  Mc: int8 [B,H,Tq,T] (out).  luts: luts_bytes (out).
  * workspace: >= ws_mask_bytes; on return it holds pool(Q), pool(K) and s at the offsets
  * above.  Scores are computed in float in one fixed order (sequential sum over a block's
  * tokens, IEEE division by the token count, fused multiply-add chain over the features,
@@ -109,7 +115,7 @@ int sla_sizes(const sla_params* p, sla_sizes_t* out);
 int sla_build_mask(const sla_params* p, const void* Q, const void* K, int8_t* Mc, void* luts,
                    void* workspace, size_t workspace_bytes, void* stream);
 
-/* Eq. 3 alone: classify given float scores s [B,H,T,T] (device) and build the tables. */
+/* Eq. 3 alone: classify given float scores s [B,H,Tq,T] (device) and build the tables. */
 int sla_classify_scores(const sla_params* p, const float* s, int8_t* Mc, void* luts, void* stream);
 
 /* Algorithm 1 + Eq. 6.  Q, K, V, O: dtype [B,H,N,d] (or [B,N,H,d]); W: dtype [d,d] row-major,

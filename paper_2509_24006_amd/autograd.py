@@ -32,15 +32,15 @@ class _SLAFunction(torch.autograd.Function):
 
 
 def build_mask(Q: torch.Tensor, K: torch.Tensor, k_h: float, k_l: float,
-               phi: int = sla.SLA_PHI_SOFTMAX, token_major: bool = False
+               phi: int = sla.SLA_PHI_SOFTMAX, token_major: bool = False, bq: int = 64
                ) -> Tuple[sla.sla_params, torch.Tensor, torch.Tensor]:
-    """(params, M_c int8 [B,H,T,T], lookup tables) for contiguous [B,H,N,d] tensors, or
-    [B,N,H,d] ones with token_major."""
+    """(params, M_c int8 [B,H,ceil(N/bq),ceil(N/64)], lookup tables) for contiguous [B,H,N,d]
+    tensors, or [B,N,H,d] ones with token_major.  bq: query block size of the mask (64 .. 256)."""
     if token_major:
         B, N, H, d = Q.shape
     else:
         B, H, N, d = Q.shape
-    p = sla.make_params(B, H, N, d, k_h, k_l, Q.dtype, phi=phi,
+    p = sla.make_params(B, H, N, d, k_h, k_l, Q.dtype, phi=phi, bq=bq,
                         layout=sla.SLA_BNHD if token_major else sla.SLA_BHND)
     Mc, luts, _ = sla.sla_build_mask(p, Q.detach(), K.detach())
     return p, Mc, luts
@@ -49,11 +49,11 @@ def build_mask(Q: torch.Tensor, K: torch.Tensor, k_h: float, k_l: float,
 def sla_attention(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, W: torch.Tensor,
                   k_h: float = 0.05, k_l: float = 0.10, phi: int = sla.SLA_PHI_SOFTMAX,
                   mask: Optional[Tuple[sla.sla_params, torch.Tensor, torch.Tensor]] = None,
-                  token_major: bool = False) -> torch.Tensor:
+                  token_major: bool = False, bq: int = 64) -> torch.Tensor:
     """O = O^s + Proj(O^l) (Eq. 6) with gradients to Q, K, V and the Proj weight W [d, d].
     Q, K, V (and O, and the gradients) are [B,H,N,d], or [B,N,H,d] with token_major -- the order
     in which a transformer block's projections leave them, no transpose needed."""
     if mask is None:
-        mask = build_mask(Q, K, k_h, k_l, phi, token_major)
+        mask = build_mask(Q, K, k_h, k_l, phi, token_major, bq)
     p, Mc, luts = mask
     return _SLAFunction.apply(Q, K, V, W, p, Mc, luts)

@@ -33,7 +33,7 @@ class sla_params(ctypes.Structure):
 
 class sla_sizes_t(ctypes.Structure):
     _fields_ = [("T", ctypes.c_int32), ("n_h", ctypes.c_int32), ("n_l", ctypes.c_int32),
-                ("n_0", ctypes.c_int32)] + [(n, ctypes.c_uint64) for n in (
+                ("n_0", ctypes.c_int32), ("Tq", ctypes.c_int32), ("reserved", ctypes.c_int32)] + [(n, ctypes.c_uint64) for n in (
                     "mask_bytes", "luts_bytes", "lut_row_idx", "lut_col_ptr", "lut_col_rows", "lut_ind", "lut_ind_t", "lut_col_order",
                     "saved_bytes", "saved_Os", "saved_Ol", "saved_L", "saved_HZ", "saved_Z",
                     "ws_mask_bytes", "ws_mask_qbar", "ws_mask_kbar", "ws_mask_scores",
@@ -82,7 +82,7 @@ def make_params(B: int, H: int, N: int, d: int, k_h: float, k_l: float, dtype: t
                 layout: int = SLA_BHND, strides: Tuple[int, int, int] = (0, 0, 0)) -> sla_params:
     """layout: SLA_BHND ([B,H,N,d] tensors), SLA_BNHD ([B,N,H,d]) or SLA_STRIDED with
     strides = element strides (batch, head, token) of [B,H,N,d] views, e.g. of the slices of a
-    fused projection output."""
+    fused projection output.  bq: query block size of the mask, a multiple of 64 up to 256."""
     code = {torch.float32: SLA_F32, torch.bfloat16: SLA_BF16}[dtype]
     return sla_params(B, H, N, d, bq, bkv, k_h, k_l, phi, code, layout, *strides)
 
@@ -128,11 +128,11 @@ def sla_build_mask(p: sla_params, Q: torch.Tensor, K: torch.Tensor,
                    workspace: Optional[torch.Tensor] = None, Mc: Optional[torch.Tensor] = None,
                    luts: Optional[torch.Tensor] = None
                    ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
-    """Returns (Mc int8 [B,H,T,T], luts, workspace); the workspace keeps pool(Q), pool(K), s."""
+    """Returns (Mc int8 [B,H,Tq,T], luts, workspace); the workspace keeps pool(Q), pool(K), s."""
     z = sla_sizes(p)
     _dense(Q, p, "Q"); _dense(K, p, "K")
     if Mc is None:
-        Mc = torch.empty((p.B, p.H, z.T, z.T), dtype=torch.int8, device=Q.device)
+        Mc = torch.empty((p.B, p.H, z.Tq, z.T), dtype=torch.int8, device=Q.device)
     if luts is None:
         luts = _buf(z.luts_bytes, Q.device)
     ws = workspace if workspace is not None else _buf(z.ws_mask_bytes, Q.device)
@@ -143,8 +143,8 @@ def sla_build_mask(p: sla_params, Q: torch.Tensor, K: torch.Tensor,
 
 def sla_classify_scores(p: sla_params, s: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor]:
     z = sla_sizes(p)
-    assert s.dtype == torch.float32 and s.is_contiguous() and tuple(s.shape) == (p.B, p.H, z.T, z.T)
-    Mc = torch.empty((p.B, p.H, z.T, z.T), dtype=torch.int8, device=s.device)
+    assert s.dtype == torch.float32 and s.is_contiguous() and tuple(s.shape) == (p.B, p.H, z.Tq, z.T)
+    Mc = torch.empty((p.B, p.H, z.Tq, z.T), dtype=torch.int8, device=s.device)
     luts = _buf(z.luts_bytes, s.device)
     _check(lib().sla_classify_scores(ctypes.byref(p), _ptr(s), _ptr(Mc), _ptr(luts), _stream()),
            "sla_classify_scores")
@@ -241,6 +241,6 @@ def lut_views(p: sla_params, luts: torch.Tensor) -> Dict[str, torch.Tensor]:
 
 def mask_ws_views(p: sla_params, ws: torch.Tensor) -> Dict[str, torch.Tensor]:
     z = sla_sizes(p)
-    return {"qbar": _view(ws, z.ws_mask_qbar, (p.B, p.H, z.T, p.d), torch.float32),
+    return {"qbar": _view(ws, z.ws_mask_qbar, (p.B, p.H, z.Tq, p.d), torch.float32),
             "kbar": _view(ws, z.ws_mask_kbar, (p.B, p.H, z.T, p.d), torch.float32),
-            "scores": _view(ws, z.ws_mask_scores, (p.B, p.H, z.T, z.T), torch.float32)}
+            "scores": _view(ws, z.ws_mask_scores, (p.B, p.H, z.Tq, z.T), torch.float32)}

@@ -16,7 +16,7 @@ int make_shape(const sla_params* p, Shape* s) {
   if (!p) return SLA_EINVAL;
   if (p->B <= 0 || p->H <= 0 || p->N <= 0 || p->d <= 0) return SLA_EINVAL;
   if (!(p->k_h >= 0.0 && p->k_h <= 1.0) || !(p->k_l >= 0.0 && p->k_l <= 1.0)) return SLA_EINVAL;
-  if (p->bq != kBlk || p->bkv != kBlk) return SLA_EUNSUPPORTED;
+  if (p->bkv != kBlk || p->bq < kBlk || p->bq % kBlk || p->bq > 4 * kBlk) return SLA_EUNSUPPORTED;
   if (p->d != 64 && p->d != 128) return SLA_EUNSUPPORTED;
   if (p->phi != SLA_PHI_SOFTMAX && p->phi != SLA_PHI_ELU1) return SLA_EUNSUPPORTED;
   if (p->dtype != SLA_F32 && p->dtype != SLA_BF16) return SLA_EUNSUPPORTED;
@@ -28,6 +28,8 @@ int make_shape(const sla_params* p, Shape* s) {
   s->N = p->N;
   s->d = p->d;
   s->T = (int)T;
+  s->rq = p->bq / kBlk;
+  s->Tq = (int)(((long long)p->N + p->bq - 1) / p->bq);
   long long nh = (long long)floor(p->k_h * (double)T + 0.5);
   nh = nh < 0 ? 0 : (nh > T ? T : nh);
   long long nl = (long long)floor(p->k_l * (double)T + 0.5);
@@ -61,13 +63,14 @@ int make_shape(const sla_params* p, Shape* s) {
 
 void fill_sizes(const Shape& s, sla_sizes_t* o) {
   memset(o, 0, sizeof(*o));
-  const size_t BH = s.BH, T = s.T, N = s.N, d = s.d;
+  const size_t BH = s.BH, T = s.T, Tq = s.Tq, N = s.N, d = s.d;
   const size_t esz = s.dtype == SLA_F32 ? 4 : 2;
   o->T = s.T;
+  o->Tq = s.Tq;
   o->n_h = s.n_h;
   o->n_l = s.n_l;
   o->n_0 = s.n_0;
-  o->mask_bytes = BH * T * T;
+  o->mask_bytes = BH * Tq * T;
   size_t off = 0;
   o->lut_row_idx = off;
   off += align_up(BH * T * (size_t)s.n_h * 4 + 4);
@@ -98,11 +101,11 @@ void fill_sizes(const Shape& s, sla_sizes_t* o) {
   o->saved_bytes = off;
   off = 0;
   o->ws_mask_qbar = off;
-  off += align_up(BH * T * d * 4);
+  off += align_up(BH * Tq * d * 4);
   o->ws_mask_kbar = off;
   off += align_up(BH * T * d * 4);
   o->ws_mask_scores = off;
-  off += align_up(BH * T * T * 4);
+  off += align_up(BH * Tq * T * 4);
   o->ws_mask_bytes = off;
   // [0, state): H_i, Z_i when the caller passes no `saved`; then the key-block states
   const size_t hz_ws = s.dtype == SLA_BF16 ? mfma_forward_ws_bytes(s) : state;

@@ -13,20 +13,22 @@ namespace {
 // A lane owns the 16 bytes of a token row that hold V adjacent features and walks the rows of
 // its block in order (the sum over a block's tokens is sequential, see above); D / V lanes cover
 // a block, so a wavefront pools 64 V / D blocks at once and each of its loads fetches whole
-// rows.  blockIdx.y selects the tensor (Q or K).
+// rows.  blockIdx.y selects the tensor (Q with blocks of len0 tokens, Tn0 per head, or K with
+// len1, Tn1).
 template <typename T, int D>
-__global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ X0, const T* __restrict__ X1, int nblk,
-                                                   int N, int Tn, Lay lay, float* __restrict__ out0,
-                                                   float* __restrict__ out1) {
+__global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ X0, const T* __restrict__ X1, int BH, int N,
+                                                   int Tn0, int len0, int Tn1, int len1, Lay lay,
+                                                   float* __restrict__ out0, float* __restrict__ out1) {
   constexpr int V = 16 / sizeof(T), LPB = D / V, BPW = 64 / LPB;
   const T* X = blockIdx.y ? X1 : X0;
   float* out = blockIdx.y ? out1 : out0;
+  const int Tn = blockIdx.y ? Tn1 : Tn0, len = blockIdx.y ? len1 : len0;
   const int lane = threadIdx.x & 63, sub = lane / LPB, fl = lane % LPB;
   const long blk = ((long)blockIdx.x * 4 + (threadIdx.x >> 6)) * BPW + sub;
-  if (blk >= nblk) return;
+  if (blk >= (long)BH * Tn) return;
   const int bh = (int)(blk / Tn), i = (int)(blk % Tn);
-  const int cnt = min(kBlk, N - i * kBlk);
-  const T* p = X + lay.head(bh) + (size_t)i * kBlk * lay.ts + fl * V;
+  const int cnt = min(len, N - i * len);
+  const T* p = X + lay.head(bh) + (size_t)i * len * lay.ts + fl * V;
   float s[V];
 #pragma unroll
   for (int v = 0; v < V; ++v) s[v] = 0.0f;
@@ -50,13 +52,13 @@ __global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ X0, con
 // chunks of 64 and read four at a time; each output keeps one fused multiply-add chain in
 // ascending feature order.
 __global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ qbar,
-                                                    const float* __restrict__ kbar, int T, int d,
+                                                    const float* __restrict__ kbar, int Tq, int T, int d,
                                                     float scale, float* __restrict__ s) {
   __shared__ __attribute__((aligned(16))) float qs[64][68];
   __shared__ __attribute__((aligned(16))) float ks[64][68];
   const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
   const int bh = blockIdx.z, i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
-  const float* qb = qbar + (size_t)bh * T * d;
+  const float* qb = qbar + (size_t)bh * Tq * d;
   const float* kb = kbar + (size_t)bh * T * d;
   float acc[4][4];
 #pragma unroll
@@ -70,7 +72,7 @@ __global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ qb
       const int r = (tid >> 4) + 16 * q, c = 4 * (tid & 15);
       const float4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
       *reinterpret_cast<float4*>(&qs[r][c]) =
-          (i0 + r < T) ? *reinterpret_cast<const float4*>(qb + (size_t)(i0 + r) * d + k0 + c) : zero;
+          (i0 + r < Tq) ? *reinterpret_cast<const float4*>(qb + (size_t)(i0 + r) * d + k0 + c) : zero;
       *reinterpret_cast<float4*>(&ks[r][c]) =
           (j0 + r < T) ? *reinterpret_cast<const float4*>(kb + (size_t)(j0 + r) * d + k0 + c) : zero;
     }
@@ -99,11 +101,11 @@ __global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ qb
 #pragma unroll
   for (int a = 0; a < 4; ++a) {
     const int i = i0 + ty + 16 * a;
-    if (i >= T) continue;
+    if (i >= Tq) continue;
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
       const int j = j0 + tx + 16 * b;
-      if (j < T) s[((size_t)bh * T + i) * T + j] = __fmul_rn(acc[a][b], scale);
+      if (j < T) s[((size_t)bh * Tq + i) * T + j] = __fmul_rn(acc[a][b], scale);
     }
   }
 }
@@ -183,14 +185,17 @@ __device__ __forceinline__ void mark_top_reg(const uint32_t (&key)[KPL], int8_t 
 
 // One wavefront per row of the score matrix, rows of at most 64 KPL entries.
 template <int KPL>
-__global__ __launch_bounds__(256) void classify_reg_kernel(const float* __restrict__ s, int rows, int T,
-                                                           int n_h, int n_l, int8_t* __restrict__ Mc,
+__global__ __launch_bounds__(256) void classify_reg_kernel(const float* __restrict__ s, int rows, int Tq, int rq,
+                                                           int T, int n_h, int n_l, int8_t* __restrict__ Mc,
                                                            int32_t* __restrict__ row_idx,
                                                            int32_t* __restrict__ col_cnt) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const long row = (long)blockIdx.x * 4 + wave;
   if (row >= rows) return;   // (no barriers in this kernel)
-  if (lane == 0) col_cnt[row] = 0;   // one counter per (head, block), cleared for the column count that follows
+  // the query tiles of this row of the mask: each gets a copy of the row's table entries
+  const size_t t0 = (size_t)(row / Tq) * T + (size_t)(row % Tq) * rq;
+  const int nrep = min(rq, T - (int)(row % Tq) * rq);
+  if (lane < nrep) col_cnt[t0 + lane] = 0;   // one counter per (head, key block), cleared for the column count that follows
   const float* sr = s + (size_t)row * T;
   uint32_t key[KPL];
   int8_t lab[KPL];
@@ -212,13 +217,16 @@ __global__ __launch_bounds__(256) void classify_reg_kernel(const float* __restri
     const int j = 64 * i + lane;
     if (j < T) Mc[(size_t)row * T + j] = lab[i];
     const unsigned long long m = __ballot(lab[i] == 1);
-    if (lab[i] == 1) row_idx[(size_t)row * n_h + base + __popcll(m & ((1ull << lane) - 1ull))] = j;
+    if (lab[i] == 1) {
+      const int pos = base + __popcll(m & ((1ull << lane) - 1ull));
+      for (int r = 0; r < nrep; ++r) row_idx[(t0 + r) * n_h + pos] = j;
+    }
     base += __popcll(m);
   }
 }
 
 // One wavefront per row of the score matrix.
-__global__ __launch_bounds__(256) void classify_kernel(const float* __restrict__ s, int rows, int T,
+__global__ __launch_bounds__(256) void classify_kernel(const float* __restrict__ s, int rows, int Tq, int rq, int T,
                                                        int n_h, int n_l, int8_t* __restrict__ Mc,
                                                        int32_t* __restrict__ row_idx,
                                                        int32_t* __restrict__ col_cnt) {
@@ -228,8 +236,10 @@ __global__ __launch_bounds__(256) void classify_kernel(const float* __restrict__
   int8_t* lab = reinterpret_cast<int8_t*>(smem + (size_t)4 * T * sizeof(uint32_t)) + (size_t)wave * T;
   const long row_raw = (long)blockIdx.x * 4 + wave;
   const bool live = row_raw < rows;  // surplus wavefronts redo the last row and store nothing
-  if (live && lane == 0) col_cnt[row_raw] = 0;   // cleared for the column count that follows
   const long row = live ? row_raw : rows - 1;
+  const size_t t0 = (size_t)(row / Tq) * T + (size_t)(row % Tq) * rq;   // first query tile of this row of the mask
+  const int nrep = min(rq, T - (int)(row % Tq) * rq);
+  if (live && lane < nrep) col_cnt[t0 + lane] = 0;   // cleared for the column count that follows
   const float* sr = s + (size_t)row * T;
   for (int j = lane; j < T; j += 64) {
     keys[j] = order_key(sr[j]);
@@ -250,20 +260,24 @@ __global__ __launch_bounds__(256) void classify_kernel(const float* __restrict__
     const int8_t v = (j < T) ? lab[j] : (int8_t)0;
     if (live && j < T) Mc[(size_t)row * T + j] = v;
     const unsigned long long m = __ballot(v == 1);
-    if (live && v == 1) row_idx[(size_t)row * n_h + base + __popcll(m & ((1ull << lane) - 1ull))] = j;
+    if (live && v == 1) {
+      const int pos = base + __popcll(m & ((1ull << lane) - 1ull));
+      for (int r = 0; r < nrep; ++r) row_idx[(t0 + r) * n_h + pos] = j;
+    }
     base += __popcll(m);
   }
 }
 
 // ---------------------------------------------------------------- column tables (CSC)
 
-// tile[r][c] = Mc[i0 + r][j0 + c] for a 64 x 64 tile, 2 outside the matrix.  When rows are 16-byte
-// aligned (T % 16 == 0) thread t brings piece t % 4 (16 bytes) of row t / 4 in one load.
-__device__ __forceinline__ uint4 mask_piece(const int8_t* __restrict__ src, int T, int i0, int j0, int tid) {
+// tile[r][c] = label of query tile i0 + r and key block j0 + c (row (i0 + r) / rq of the head's
+// M_c) for a 64 x 64 tile, 2 outside the matrix.  When rows are 16-byte aligned (T % 16 == 0)
+// thread t brings piece t % 4 (16 bytes) of row t / 4 in one load.
+__device__ __forceinline__ uint4 mask_piece(const int8_t* __restrict__ src, int T, int rq, int i0, int j0, int tid) {
   const int r = tid >> 2, p = tid & 3;
   const int i = i0 + r, j = j0 + 16 * p;
   uint4 v = {0x02020202u, 0x02020202u, 0x02020202u, 0x02020202u};
-  if (i < T && j < T) v = *reinterpret_cast<const uint4*>(src + (size_t)i * T + j);   // (j + 15 < T: T % 16 == 0)
+  if (i < T && j < T) v = *reinterpret_cast<const uint4*>(src + (size_t)(i / rq) * T + j);   // (j + 15 < T: T % 16 == 0)
   return v;
 }
 __device__ __forceinline__ void put_piece(int8_t (*tile)[68], uint4 v, int tid) {
@@ -273,29 +287,30 @@ __device__ __forceinline__ void put_piece(int8_t (*tile)[68], uint4 v, int tid) 
   dst[2] = v.z;
   dst[3] = v.w;
 }
-__device__ __forceinline__ void load_mask_tile_bytes(int8_t (*tile)[68], const int8_t* __restrict__ src, int T, int i0,
-                                                     int j0, int l, int w) {
+__device__ __forceinline__ void load_mask_tile_bytes(int8_t (*tile)[68], const int8_t* __restrict__ src, int T, int rq,
+                                                     int i0, int j0, int l, int w) {
   for (int r = w; r < 64; r += 4) {
     const int i = i0 + r, j = j0 + l;
-    tile[r][l] = (i < T && j < T) ? src[(size_t)i * T + j] : (int8_t)2;
+    tile[r][l] = (i < T && j < T) ? src[(size_t)(i / rq) * T + j] : (int8_t)2;
   }
 }
 
-// Marginal indicator as bit masks and the column counts.  Bit b of ind[i][q] is set iff
-// Mc[i][64 q + b] == 0 (and the column exists), bit b of indT[j][q] iff Mc[64 q + b][j] == 0;
+// Marginal indicator as bit masks and the column counts, over query tiles i (of 64 tokens: label
+// m(i, j) = Mc[i / rq][j]).  Bit b of ind[i][q] is set iff m(i, 64 q + b) == 0 (and the column
+// exists), bit b of indT[j][q] iff m(64 q + b, j) == 0;
 // cnt[j] (cleared by the classification kernel) receives the number of critical blocks of column
 // j.  A workgroup takes a 64 x 64 tile of Mc through LDS; each wave votes 16 rows and 16 columns
 // of it into 64-bit words.
-__global__ __launch_bounds__(256) void indicator_kernel(const int8_t* __restrict__ Mc, int T, int Tw,
+__global__ __launch_bounds__(256) void indicator_kernel(const int8_t* __restrict__ Mc, int Tq, int rq, int T, int Tw,
                                                         unsigned long long* __restrict__ ind,
                                                         unsigned long long* __restrict__ indT,
                                                         int32_t* __restrict__ cnt) {
   __shared__ int8_t tile[64][68];
   const int bh = blockIdx.z, i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
   const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int8_t* src = Mc + (size_t)bh * T * T;
-  if (T % 16 == 0) put_piece(tile, mask_piece(src, T, i0, j0, threadIdx.x), threadIdx.x);
-  else load_mask_tile_bytes(tile, src, T, i0, j0, l, w);
+  const int8_t* src = Mc + (size_t)bh * Tq * T;
+  if (T % 16 == 0) put_piece(tile, mask_piece(src, T, rq, i0, j0, threadIdx.x), threadIdx.x);
+  else load_mask_tile_bytes(tile, src, T, rq, i0, j0, l, w);
   __syncthreads();
   for (int r = w; r < 64; r += 4) {
     const unsigned long long rowbits = __ballot(tile[r][l] == 0);
@@ -317,7 +332,7 @@ __global__ __launch_bounds__(256) void indicator_kernel(const int8_t* __restrict
 // column-wise backward kernel takes the longest lists first) and col_rows (the critical rows of
 // every column, ascending).  A workgroup owns 64 columns of one head; every workgroup forms the
 // prefix sum up to its columns from the head's counts by itself.
-__global__ __launch_bounds__(256) void col_tables_kernel(const int8_t* __restrict__ Mc, int T, int n_h,
+__global__ __launch_bounds__(256) void col_tables_kernel(const int8_t* __restrict__ Mc, int Tq, int rq, int T, int n_h,
                                                          const int32_t* __restrict__ cnt_g,
                                                          int32_t* __restrict__ ptr, int32_t* __restrict__ order,
                                                          int32_t* __restrict__ rows) {
@@ -369,7 +384,7 @@ __global__ __launch_bounds__(256) void col_tables_kernel(const int8_t* __restric
   if (w == 0 && j0 + l < T) order[(size_t)bh * T + part[0][l] + part[1][l] + part[2][l] + part[3][l]] = j0 + l;
   if (n_h == 0) return;
   // rows of the critical blocks: tiles of 64 rows, wave w votes columns 16 w .. 16 w + 15
-  const int8_t* src = Mc + (size_t)bh * T * T;
+  const int8_t* src = Mc + (size_t)bh * Tq * T;
   int32_t* out = rows + (size_t)bh * T * n_h;
   int run[16];
 #pragma unroll
@@ -388,7 +403,7 @@ __global__ __launch_bounds__(256) void col_tables_kernel(const int8_t* __restric
     for (int ib = 0; ib < T; ib += 512) {
       uint4 pre[8];
 #pragma unroll
-      for (int k = 0; k < 8; ++k) pre[k] = mask_piece(src, T, ib + 64 * k, j0, tid);
+      for (int k = 0; k < 8; ++k) pre[k] = mask_piece(src, T, rq, ib + 64 * k, j0, tid);
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
         if (ib + 64 * k >= T) break;
@@ -401,7 +416,7 @@ __global__ __launch_bounds__(256) void col_tables_kernel(const int8_t* __restric
   } else {
     for (int i0 = 0; i0 < T; i0 += 64) {
       __syncthreads();   // the previous tile has been read
-      load_mask_tile_bytes(tile, src, T, i0, j0, l, w);
+      load_mask_tile_bytes(tile, src, T, rq, i0, j0, l, w);
       __syncthreads();
       vote(i0);
     }
@@ -410,21 +425,22 @@ __global__ __launch_bounds__(256) void col_tables_kernel(const int8_t* __restric
 
 }  // namespace
 
-// block means of Q and K (both [BH][N][d]) -> qbar, kbar (float [BH][T][d])
+// block means of Q (blocks of 64 rq tokens) and K (64) -> qbar (float [BH][Tq][d]), kbar (float [BH][T][d])
 hipError_t launch_pool(const void* Q, const void* K, const Shape& s, float* qbar, float* kbar, hipStream_t st) {
   const int nblk = s.BH * s.T;
   const int bpw = s.dtype == 0 ? 256 / s.d : 512 / s.d;   // blocks per wavefront
   const dim3 grid((nblk + 4 * bpw - 1) / (4 * bpw), 2), block(256);
+  const int lq = s.rq * kBlk;
   KernelTimer kt("pool", st);
   typedef __hip_bfloat16 bf;
   if (s.dtype == 0 && s.d == 64)
-    pool_kernel<float, 64><<<grid, block, 0, st>>>((const float*)Q, (const float*)K, nblk, s.N, s.T, s.lay(), qbar, kbar);
+    pool_kernel<float, 64><<<grid, block, 0, st>>>((const float*)Q, (const float*)K, s.BH, s.N, s.Tq, lq, s.T, kBlk, s.lay(), qbar, kbar);
   else if (s.dtype == 0)
-    pool_kernel<float, 128><<<grid, block, 0, st>>>((const float*)Q, (const float*)K, nblk, s.N, s.T, s.lay(), qbar, kbar);
+    pool_kernel<float, 128><<<grid, block, 0, st>>>((const float*)Q, (const float*)K, s.BH, s.N, s.Tq, lq, s.T, kBlk, s.lay(), qbar, kbar);
   else if (s.d == 64)
-    pool_kernel<bf, 64><<<grid, block, 0, st>>>((const bf*)Q, (const bf*)K, nblk, s.N, s.T, s.lay(), qbar, kbar);
+    pool_kernel<bf, 64><<<grid, block, 0, st>>>((const bf*)Q, (const bf*)K, s.BH, s.N, s.Tq, lq, s.T, kBlk, s.lay(), qbar, kbar);
   else
-    pool_kernel<bf, 128><<<grid, block, 0, st>>>((const bf*)Q, (const bf*)K, nblk, s.N, s.T, s.lay(), qbar, kbar);
+    pool_kernel<bf, 128><<<grid, block, 0, st>>>((const bf*)Q, (const bf*)K, s.BH, s.N, s.Tq, lq, s.T, kBlk, s.lay(), qbar, kbar);
   return hipGetLastError();
 }
 
@@ -433,25 +449,25 @@ hipError_t launch_scores(const float* qbar, const float* kbar, const Shape& s, f
   const int nt = (s.T + 63) / 64;
   {
     KernelTimer kt("score", st);
-    score_kernel<<<dim3(nt, nt, s.BH), 256, 0, st>>>(qbar, kbar, s.T, s.d, s.scale, scores);
+    score_kernel<<<dim3(nt, (s.Tq + 63) / 64, s.BH), 256, 0, st>>>(qbar, kbar, s.Tq, s.T, s.d, s.scale, scores);
   }
   return hipGetLastError();
 }
 
 hipError_t launch_classify(const float* scores, const Shape& s, int8_t* Mc, int32_t* row_idx,
                            int32_t* col_cnt, hipStream_t st) {
-  const int rows = s.BH * s.T;
+  const int rows = s.BH * s.Tq;
   const size_t lds = (size_t)4 * s.T * (sizeof(uint32_t) + 1);
   {
     KernelTimer kt("classify", st);
     const dim3 grid((rows + 3) / 4);
-    if (s.T <= 64) classify_reg_kernel<1><<<grid, 256, 0, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx, col_cnt);
-    else if (s.T <= 128) classify_reg_kernel<2><<<grid, 256, 0, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx, col_cnt);
-    else if (s.T <= 256) classify_reg_kernel<4><<<grid, 256, 0, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx, col_cnt);
-    else if (s.T <= 512) classify_reg_kernel<8><<<grid, 256, 0, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx, col_cnt);
-    else if (s.T <= 1024) classify_reg_kernel<16><<<grid, 256, 0, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx, col_cnt);
-    else if (s.T <= 2048) classify_reg_kernel<32><<<grid, 256, 0, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx, col_cnt);
-    else classify_kernel<<<grid, 256, lds, st>>>(scores, rows, s.T, s.n_h, s.n_l, Mc, row_idx, col_cnt);
+    if (s.T <= 64) classify_reg_kernel<1><<<grid, 256, 0, st>>>(scores, rows, s.Tq, s.rq, s.T, s.n_h, s.n_l, Mc, row_idx, col_cnt);
+    else if (s.T <= 128) classify_reg_kernel<2><<<grid, 256, 0, st>>>(scores, rows, s.Tq, s.rq, s.T, s.n_h, s.n_l, Mc, row_idx, col_cnt);
+    else if (s.T <= 256) classify_reg_kernel<4><<<grid, 256, 0, st>>>(scores, rows, s.Tq, s.rq, s.T, s.n_h, s.n_l, Mc, row_idx, col_cnt);
+    else if (s.T <= 512) classify_reg_kernel<8><<<grid, 256, 0, st>>>(scores, rows, s.Tq, s.rq, s.T, s.n_h, s.n_l, Mc, row_idx, col_cnt);
+    else if (s.T <= 1024) classify_reg_kernel<16><<<grid, 256, 0, st>>>(scores, rows, s.Tq, s.rq, s.T, s.n_h, s.n_l, Mc, row_idx, col_cnt);
+    else if (s.T <= 2048) classify_reg_kernel<32><<<grid, 256, 0, st>>>(scores, rows, s.Tq, s.rq, s.T, s.n_h, s.n_l, Mc, row_idx, col_cnt);
+    else classify_kernel<<<grid, 256, lds, st>>>(scores, rows, s.Tq, s.rq, s.T, s.n_h, s.n_l, Mc, row_idx, col_cnt);
   }
   return hipGetLastError();
 }
@@ -461,11 +477,11 @@ hipError_t launch_csc(const int8_t* Mc, const Shape& s, int32_t* col_cnt, int32_
   const int Tw = (s.T + 63) / 64;
   {
     KernelTimer kt("indicator", st);
-    indicator_kernel<<<dim3(Tw, Tw, s.BH), 256, 0, st>>>(Mc, s.T, Tw, ind, indT, col_cnt);
+    indicator_kernel<<<dim3(Tw, Tw, s.BH), 256, 0, st>>>(Mc, s.Tq, s.rq, s.T, Tw, ind, indT, col_cnt);
   }
   {
     KernelTimer kt("col_tables", st);
-    col_tables_kernel<<<dim3(Tw, s.BH), 256, s.T * sizeof(int), st>>>(Mc, s.T, s.n_h, col_cnt, col_ptr, col_order,
+    col_tables_kernel<<<dim3(Tw, s.BH), 256, s.T * sizeof(int), st>>>(Mc, s.Tq, s.rq, s.T, s.n_h, col_cnt, col_ptr, col_order,
                                                                       col_rows);
   }
   return hipGetLastError();

@@ -198,20 +198,21 @@ __global__ __launch_bounds__(kThreads) void states_kernel(const T* __restrict__ 
 
 // Alg. 1 accumulation line (and its column-wise twin in Alg. 2): out_row[i] = sum of the
 // state rows in[k] over the k with a marginal label, in ascending k.
-//   by_column = 0: label(i, k) = Mc[i][k]  (H_i, Z_i over key blocks)
-//   by_column = 1: label(i, k) = Mc[k][i]  (dH, dZ of key block i over query blocks)
+// With m(q, j) = Mc[q / rq][j] the label of query tile q (64 tokens) and key block j:
+//   by_column = 0: label(i, k) = m(i, k)  (H_i, Z_i of query tile i over key blocks)
+//   by_column = 1: label(i, k) = m(k, i)  (dH, dZ of key block i over query tiles)
 __global__ __launch_bounds__(kThreads) void aggregate_kernel(const float* __restrict__ in,
-                                                             const int8_t* __restrict__ Mc, int T,
+                                                             const int8_t* __restrict__ Mc, int Tq, int rq, int T,
                                                              int row_len, int by_column,
                                                              float* __restrict__ out) {
   const int col = blockIdx.x * kThreads + threadIdx.x;
   const int i = blockIdx.y, bh = blockIdx.z;
   if (col >= row_len) return;
-  const int8_t* m = Mc + (size_t)bh * T * T;
+  const int8_t* m = Mc + (size_t)bh * Tq * T;
   const float* src = in + (size_t)bh * T * row_len + col;
   float s = 0.0f;
   for (int k = 0; k < T; ++k) {
-    const int8_t lab = by_column ? m[(size_t)k * T + i] : m[(size_t)i * T + k];
+    const int8_t lab = by_column ? m[(size_t)(k / rq) * T + i] : m[(size_t)(i / rq) * T + k];
     if (lab == 0) s += src[(size_t)k * row_len];
   }
   out[((size_t)bh * T + i) * row_len + col] = s;
@@ -795,7 +796,7 @@ hipError_t forward_impl(const Shape& s, const FwdArgs& a, hipStream_t st) {
     {
       KernelTimer kt("aggregate", st);
       aggregate_kernel<<<dim3((row_len + kThreads - 1) / kThreads, s.T, s.BH), kThreads, 0, st>>>(
-        a.hz, a.Mc, s.T, row_len, 0, a.HZ);
+        a.hz, a.Mc, s.Tq, s.rq, s.T, row_len, 0, a.HZ);
     }
   } else {
     {
@@ -881,7 +882,7 @@ hipError_t backward_impl(const Shape& s, const BwdArgs& a, hipStream_t st) {
     {
       KernelTimer kt("aggregate", st);
       aggregate_kernel<<<dim3((row_len + kThreads - 1) / kThreads, s.T, s.BH), kThreads, 0, st>>>(
-        w.dHZ, a.Mc, s.T, row_len, 1, w.dHZcol);
+        w.dHZ, a.Mc, s.Tq, s.rq, s.T, row_len, 1, w.dHZcol);
     }
     const size_t lds2 = sizeof(float) * 4 * kBlk * LD;
     SLA_TRY(set_lds(bwd_linear_k_kernel<T, D>, lds2));

@@ -8,7 +8,7 @@
 
 namespace sla {
 
-constexpr int kBlk = 64;  // b_q = b_kv (Section 6.1 hyper-parameters)
+constexpr int kBlk = 64;  // tile of every kernel: b_kv, and b_q or the unit b_q is a multiple of (Section 6.1)
 
 // Where the caller's Q, K, V, O, dO, dQ, dK, dV keep token n of head bh = b H + h: element
 // offset head(bh) + n ts.  [B,H,N,d]: ts = d; [B,N,H,d]: ts = H d.  (Everything the library
@@ -22,6 +22,7 @@ struct Lay {
 // Shape of one call, derived on the host.
 struct Shape {
   int BH, N, d, T, n_h, n_l, n_0;
+  int Tq, rq;  // rows of M_c = query blocks of b_q = 64 rq tokens; row r of the 64-token grid has the labels of M_c row r / rq
   int phi;    // 0 softmax over features, 1 elu+1
   int dtype;  // 0 float, 1 bf16
   float scale;  // float 1/sqrt(d)

@@ -11,18 +11,22 @@ from __future__ import annotations
 import numpy as np
 
 
-def critical_pair_elems(Mc: np.ndarray, N: int, b: int = 64) -> int:
-    """Sum over critical pairs of (valid rows) x (valid columns); Mc is [..., T, T]."""
-    T = Mc.shape[-1]
+def critical_pair_elems(Mc: np.ndarray, N: int, b: int = 64, bq: int = 0) -> int:
+    """Sum over critical pairs of (valid rows) x (valid columns); Mc is [..., Tq, T] for query
+    blocks of bq (default b) and key blocks of b tokens."""
+    bq = bq or b
+    Tq, T = Mc.shape[-2:]
     valid = np.full(T, b, np.int64)
     valid[-1] = N - (T - 1) * b
-    crit = (Mc.reshape(-1, T, T) == 1)
-    return int(np.einsum("gij,i,j->", crit.astype(np.int64), valid, valid))
+    validq = np.full(Tq, bq, np.int64)
+    validq[-1] = N - (Tq - 1) * bq
+    crit = (Mc.reshape(-1, Tq, T) == 1)
+    return int(np.einsum("gij,i,j->", crit.astype(np.int64), validq, valid))
 
 
-def executed_flops(Mc: np.ndarray, N: int, d: int, b: int = 64):
+def executed_flops(Mc: np.ndarray, N: int, d: int, b: int = 64, bq: int = 0):
     """(forward, backward) FLOPs executed on the critical blocks of a whole call."""
-    e = critical_pair_elems(Mc, N, b)
+    e = critical_pair_elems(Mc, N, b, bq)
     return 4 * e * d, 10 * e * d
 
 

@@ -17,13 +17,14 @@ def f64(t: torch.Tensor) -> np.ndarray:
 
 
 def run_gpu(x, dtype: str, k_h: float, k_l: float, phi: int = 0, backward: bool = True,
-            token_major: bool = False):
+            token_major: bool = False, bq: int = 64):
     """x: dict of float32 arrays Q,K,V[,dO] [B,H,N,d] and Proj [d,d].  Runs mask, forward
     and (optionally) backward through the C ABI and returns numpy results ([B,H,N,d] again).
-    token_major: hand the library [B,N,H,d] tensors (the same values, transposed on the device)."""
+    token_major: hand the library [B,N,H,d] tensors (the same values, transposed on the device).
+    bq: query block size of the mask."""
     B, H, N, d = x["Q"].shape
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
-    p = sla.make_params(B, H, N, d, k_h, k_l, tdt, phi, layout=sla.SLA_BNHD if token_major else sla.SLA_BHND)
+    p = sla.make_params(B, H, N, d, k_h, k_l, tdt, phi, bq=bq, layout=sla.SLA_BNHD if token_major else sla.SLA_BHND)
     tm = (lambda t: t.transpose(1, 2).contiguous()) if token_major else (lambda t: t)
     Q, K, V = (tm(to_dev(x[k], dtype)) for k in ("Q", "K", "V"))
     W = to_dev(x["Proj"], dtype)
@@ -43,9 +44,17 @@ def run_gpu(x, dtype: str, k_h: float, k_l: float, phi: int = 0, backward: bool 
     return out
 
 
+def per_tile(a: np.ndarray, rq: int, T: int, axis: int = 2) -> np.ndarray:
+    """Rows of a per-query-block array given to each of the block's rq 64-token tiles (T in all)."""
+    return np.repeat(a, rq, axis=axis).take(np.arange(T), axis=axis)
+
+
 def check_luts(Mc: np.ndarray, row_idx: np.ndarray, col_ptr: np.ndarray, col_rows: np.ndarray,
                ind: np.ndarray = None, ind_t: np.ndarray = None, col_order: np.ndarray = None):
+    """The tables against the mask, both over 64-token query tiles: Mc is [B,H,T,T] (for larger
+    query blocks: per_tile(Mc, rq, T))."""
     B, H, T, _ = Mc.shape
+    assert Mc.shape[-1] == T
     if ind is not None:
         # bit b of word q of row i: block (i, 64 q + b) is marginal; bits past T are clear
         Tw = ind.shape[-1]

@@ -23,7 +23,7 @@ def test_exports_match_header():
 
 def test_struct_layout_matches_header():
     assert ctypes.sizeof(sla.sla_params) == 80
-    assert ctypes.sizeof(sla.sla_sizes_t) == 16 + 20 * 8
+    assert ctypes.sizeof(sla.sla_sizes_t) == 24 + 20 * 8
 
 
 def test_sizes_and_counts():
@@ -39,6 +39,21 @@ def test_sizes_and_counts():
     assert (z.n_h, z.n_l, z.n_0) == (16, 0, 0)
 
 
+def test_sizes_with_larger_query_blocks():
+    # b_q = 128: half as many rows of M_c and of the scores; tables and states stay per 64-token tile
+    p64 = sla.make_params(1, 12, 32760, 128, 0.05, 0.10, torch.bfloat16)
+    p = sla.make_params(1, 12, 32760, 128, 0.05, 0.10, torch.bfloat16, bq=128)
+    z64, z = sla.sla_sizes(p64), sla.sla_sizes(p)
+    assert (z64.T, z64.Tq) == (512, 512)
+    assert (z.T, z.Tq, z.n_h, z.n_l, z.n_0) == (512, 256, 26, 51, 435)
+    assert z.mask_bytes == 12 * 256 * 512
+    assert z.luts_bytes == z64.luts_bytes and z.saved_bytes == z64.saved_bytes
+    assert z.ws_mask_bytes < z64.ws_mask_bytes
+    # ragged: 15 tiles in blocks of three (192 tokens) and of four (256)
+    assert sla.sla_sizes(sla.make_params(1, 1, 902, 64, 0.1, 0.1, torch.float32, bq=192)).Tq == 5
+    assert sla.sla_sizes(sla.make_params(1, 1, 902, 64, 0.1, 0.1, torch.float32, bq=256)).Tq == 4
+
+
 def test_counts_agree_with_oracle(oracle):
     for N in (1, 64, 65, 1000, 32760, 75600):
         for kh, kl in ((0.05, 0.1), (0.1, 0.1), (0.025, 0.1), (0.2, 0.1), (1.0, 0.0), (0.0, 0.0), (0.5, 0.5)):
@@ -48,7 +63,7 @@ def test_counts_agree_with_oracle(oracle):
 
 @pytest.mark.parametrize("kw,code", [
     (dict(N=0), -1), (dict(k_h=1.5), -1), (dict(k_l=-0.1), -1), (dict(d=96), -2),
-    (dict(bq=128), -2), (dict(phi=7), -2), (dict(N=64 * 4000), -2),
+    (dict(bq=96), -2), (dict(bq=320), -2), (dict(bq=32), -2), (dict(bkv=128), -2), (dict(phi=7), -2), (dict(N=64 * 4000), -2),
 ])
 def test_bad_params_are_rejected(kw, code):
     base = dict(B=1, H=2, N=1024, d=64, bq=64, bkv=64, k_h=0.1, k_l=0.1, phi=0, dtype=0)

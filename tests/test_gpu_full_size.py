@@ -8,13 +8,13 @@ import torch
 from paper_2509_24006_amd import binding as sla
 from paper_2509_24006_amd import workloads as wl
 from tests import pins
-from tests.gpu_util import TOL, check_luts, f64, to_dev
+from tests.gpu_util import TOL, check_luts, f64, per_tile, to_dev
 
 pytestmark = pytest.mark.gpu
 
 
-def _gpu_all(x, w, k_h, k_l, H):
-    p = sla.make_params(w.B, H, w.N, w.d, k_h, k_l, torch.bfloat16)
+def _gpu_all(x, w, k_h, k_l, H, bq=64):
+    p = sla.make_params(w.B, H, w.N, w.d, k_h, k_l, torch.bfloat16, bq=bq)
     dev = {k: to_dev(v, "bf16") for k, v in x.items()}
     Mc, luts, ws = sla.sla_build_mask(p, dev["Q"], dev["K"])
     O, saved = sla.sla_forward(p, dev["Q"], dev["K"], dev["V"], dev["Proj"], Mc, luts)
@@ -53,6 +53,39 @@ def test_wan_shaped_layer_against_oracle(oracle):
         err = pins.rel_l2(f64(got), ref)
         print(f"  wan {name}: rel_l2 = {err:.3e}", flush=True)
         assert err <= tol, name
+
+
+@pytest.mark.timeout(600)
+def test_wan_shaped_layer_with_query_blocks_of_128(oracle):
+    # b_q = 128, b_kv = 64 at the full size: masks of all heads bit for bit (256 x 512 per head),
+    # the tables against the mask, and one head's forward and backward against the oracle, which
+    # computes with the 128 x 64 blocks directly
+    w = wl.WORKLOADS["wan"]
+    x_all = wl.make_inputs(w)
+    p, Mc, luts, ws, O, saved, dQ, dK, dV, dW = _gpu_all(x_all, w, w.k_h, w.k_l, w.H, bq=128)
+    Mo, so = oracle.build_mask(x_all["Q"], x_all["K"], w.k_h, w.k_l, bq=128, return_scores=True)
+    assert Mo.shape[-2:] == (256, 512)
+    assert np.array_equal(sla.mask_ws_views(p, ws)["scores"].cpu().numpy(), so)
+    assert np.array_equal(Mc.cpu().numpy(), Mo)
+    v = {k: t.cpu().numpy() for k, t in sla.lut_views(p, luts).items()}
+    check_luts(per_tile(Mo[:, :2], 2, 512), v["row_idx"][:, :2], v["col_ptr"][:, :2], v["col_rows"][:, :2],
+               v["ind"][:, :2], v["ind_t"][:, :2], v["col_order"][:, :2])
+    print("masks of 12 heads identical", flush=True)
+    heads = [5]
+    xs = {k: (np.ascontiguousarray(a[:, heads]) if a.ndim == 4 else a) for k, a in x_all.items()}
+    p2, Mc2, _, _, O2, saved2, dQ2, dK2, dV2, dW2 = _gpu_all(xs, w, w.k_h, w.k_l, 1, bq=128)
+    assert torch.equal(O[:, heads], O2) and torch.equal(dK[:, heads], dK2)
+    f = oracle.forward(xs["Q"], xs["K"], xs["V"], xs["Proj"], Mo[:, heads], bq=128)
+    g = oracle.backward(xs["Q"], xs["K"], xs["V"], xs["Proj"], Mo[:, heads], f, xs["dO"], bq=128)
+    sv = sla.saved_views(p2, saved2)
+    for name, got, ref in (("O", O2, f["O"]), ("Os", sv["Os"], f["Os"]), ("Ol", sv["Ol"], f["Ol"]),
+                           ("L", sv["L"], f["L"]), ("Hi", sv["Hi"], per_tile(f["Hi"], 2, 512)),
+                           ("Zi", sv["Zi"], per_tile(f["Zi"], 2, 512)),
+                           ("dQ", dQ2, g["dQ"]), ("dK", dK2, g["dK"]), ("dV", dV2, g["dV"]),
+                           ("dW", dW2, g["dW"])):
+        err = pins.rel_l2(f64(got), ref)
+        print(f"  wan b_q=128 {name}: rel_l2 = {err:.3e}", flush=True)
+        assert err <= TOL["bf16"], name
 
 
 @pytest.mark.timeout(600)

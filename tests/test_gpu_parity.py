@@ -9,15 +9,15 @@ import torch
 
 from paper_2509_24006_amd import workloads as wl
 from tests import pins
-from tests.gpu_util import TOL, check_luts, run_gpu
+from tests.gpu_util import TOL, check_luts, per_tile, run_gpu
 
 pytestmark = pytest.mark.gpu
 
 
-def _oracle_all(oracle, x, k_h, k_l, phi=0, backward=True):
-    Mc, s = oracle.build_mask(x["Q"], x["K"], k_h, k_l, return_scores=True)
-    f = oracle.forward(x["Q"], x["K"], x["V"], x["Proj"], Mc, phi=phi)
-    g = oracle.backward(x["Q"], x["K"], x["V"], x["Proj"], Mc, f, x["dO"], phi=phi) if backward else {}
+def _oracle_all(oracle, x, k_h, k_l, phi=0, backward=True, bq=64):
+    Mc, s = oracle.build_mask(x["Q"], x["K"], k_h, k_l, bq=bq, return_scores=True)
+    f = oracle.forward(x["Q"], x["K"], x["V"], x["Proj"], Mc, phi=phi, bq=bq)
+    g = oracle.backward(x["Q"], x["K"], x["V"], x["Proj"], Mc, f, x["dO"], phi=phi, bq=bq) if backward else {}
     return Mc, s, f, g
 
 
@@ -41,17 +41,22 @@ def _compare(name, got, ref, tol, floor_rms=0.0):
     assert err <= tol, f"{name}: rel L2 {err:.3e} > {tol:g}"
 
 
-def _full_case(oracle, x, dtype, k_h, k_l, phi=0, floor_rms=0.0):
-    print(f"case shape={x['Q'].shape} dtype={dtype} k_h={k_h} k_l={k_l} phi={phi}", flush=True)
-    Mc, s, f, g = _oracle_all(oracle, x, k_h, k_l, phi)
-    r = run_gpu(x, dtype, k_h, k_l, phi)
+def _full_case(oracle, x, dtype, k_h, k_l, phi=0, floor_rms=0.0, bq=64):
+    print(f"case shape={x['Q'].shape} dtype={dtype} k_h={k_h} k_l={k_l} phi={phi} bq={bq}", flush=True)
+    Mc, s, f, g = _oracle_all(oracle, x, k_h, k_l, phi, bq=bq)
+    r = run_gpu(x, dtype, k_h, k_l, phi, bq=bq)
     # mask step: bit-exact
     assert np.array_equal(r["scores"], s), "pooled scores differ bitwise"
     assert np.array_equal(r["Mc"], Mc), "mask differs"
-    check_luts(r["Mc"], r["row_idx"], r["col_ptr"], r["col_rows"], r["ind"], r["ind_t"], r["col_order"])
+    # tables and saved states are kept per 64-token query tile: a tile has its query block's row
+    T, rq = Mc.shape[-1], bq // 64
+    check_luts(per_tile(r["Mc"], rq, T), r["row_idx"], r["col_ptr"], r["col_rows"], r["ind"], r["ind_t"],
+               r["col_order"])
     tol = TOL[dtype]
-    for k in ("O", "Os", "Ol", "Hi", "Zi"):
+    for k in ("O", "Os", "Ol"):
         _compare(k, r[k], f[k], tol)
+    for k in ("Hi", "Zi"):
+        _compare(k, r[k], per_tile(f[k], rq, T), tol)
     fin = np.isfinite(f["L"])
     assert np.array_equal(np.isfinite(r["L"]), fin)
     if fin.any():
@@ -82,6 +87,34 @@ def test_elu_feature_map(oracle, name):
     w = wl.WORKLOADS[name]
     x = wl.make_inputs(w)
     _full_case(oracle, x, w.dtype, w.k_h, w.k_l, phi=1)
+
+
+@pytest.mark.parametrize("name,bq,k_h,k_l", [
+    ("small_bf16", 128, 0.10, 0.10),       # 18 tiles in 9 blocks; last block ragged inside its second tile
+    ("small_bf16_d64", 128, 0.12, 0.15),   # 15 tiles: the last block has one tile only
+    ("small_bf16_d64", 192, 0.12, 0.15),   # 5 blocks of 3 tiles
+    ("small_fp32", 128, 0.15, 0.20),
+    ("small_fp32", 256, 0.15, 0.20),       # 9 tiles in blocks of 4, 4, 1
+    ("small_bf16", 256, 0.0, 0.3),         # no critical block
+    ("small_bf16", 128, 0.4, 0.6),         # no marginal block
+])
+def test_query_blocks_of_several_tiles(oracle, name, bq, k_h, k_l):
+    # b_q = 128, 192, 256 with b_kv = 64: the mask is predicted per block of b_q queries (pooling,
+    # scores and classification on T_q rows); the oracle computes with the b_q x 64 blocks
+    # directly, the library gives every 64-token tile of a query block that block's mask row
+    w = wl.WORKLOADS[name]
+    x = wl.make_inputs(w)
+    _full_case(oracle, x, w.dtype, k_h, k_l, bq=bq)
+
+
+@pytest.mark.parametrize("bq", [128, 256])
+def test_query_blocks_of_several_tiles_mid_length(oracle, bq):
+    # 41 tiles (ragged tail of 5 tokens), enough key blocks for the matrix-core state aggregation
+    N, d = 2565, 128
+    rng = np.random.default_rng(N + bq)
+    x = {k: wl.round_to_bf16(rng.standard_normal((1, 2, N, d)).astype(np.float32)) for k in ("Q", "K", "V", "dO")}
+    x["Proj"] = wl.round_to_bf16((rng.standard_normal((d, d)) * 0.05).astype(np.float32))
+    _full_case(oracle, x, "bf16", 0.1, 0.2, bq=bq)
 
 
 @pytest.mark.parametrize("N", [1, 63, 64, 65, 130])
