@@ -37,6 +37,26 @@ def test_autograd_matches_oracle(oracle, name):
         assert err <= tol, f"{n}: {err:.3e}"
 
 
+def test_autograd_with_query_blocks_of_128(oracle):
+    from paper_2509_24006_amd.autograd import sla_attention
+    w = wl.WORKLOADS["small_bf16_d64"]
+    x = wl.make_inputs(w)
+    dev = torch.device("cuda:0")
+    Q, K, V = (torch.from_numpy(x[k]).to(dev).to(torch.bfloat16).requires_grad_(True) for k in ("Q", "K", "V"))
+    W = torch.from_numpy(x["Proj"]).to(dev).to(torch.bfloat16).requires_grad_(True)
+    O = sla_attention(Q, K, V, W, k_h=w.k_h, k_l=w.k_l, bq=128)
+    O.backward(torch.from_numpy(x["dO"]).to(dev).to(torch.bfloat16))
+    torch.cuda.synchronize()
+    Mc = oracle.build_mask(x["Q"], x["K"], w.k_h, w.k_l, bq=128)
+    f = oracle.forward(x["Q"], x["K"], x["V"], x["Proj"], Mc, bq=128)
+    g = oracle.backward(x["Q"], x["K"], x["V"], x["Proj"], Mc, f, x["dO"], bq=128)
+    for n, got, ref in (("O", O, f["O"]), ("dQ", Q.grad, g["dQ"]), ("dK", K.grad, g["dK"]),
+                        ("dV", V.grad, g["dV"]), ("dW", W.grad, g["dW"])):
+        err = pins.rel_l2(got.detach().float().cpu().numpy(), ref)
+        print(f"  b_q=128 {n}: rel_l2 = {err:.3e}", flush=True)
+        assert err <= TOL["bf16"], f"{n}: {err:.3e}"
+
+
 def test_autograd_token_major(oracle):
     # [B,N,H,d] tensors, as a transformer block's projections leave them
     from paper_2509_24006_amd.autograd import sla_attention

@@ -201,6 +201,28 @@ def test_classify_given_scores_with_ties(oracle):
     check_luts(ref, v["row_idx"], v["col_ptr"], v["col_rows"], v["ind"], v["ind_t"], v["col_order"])
 
 
+@pytest.mark.parametrize("bq,N", [(128, 130 * 64), (192, 130 * 64 - 40), (256, 33 * 64)])
+def test_classify_given_scores_with_ties_and_larger_query_blocks(oracle, bq, N):
+    # rectangular score matrices (one row per block of bq queries), heavy ties; N is chosen so that
+    # the last query block has fewer tiles than the others
+    from paper_2509_24006_amd import binding as sla
+    rng = np.random.default_rng(bq)
+    p = sla.make_params(1, 3, N, 64, 0.1, 0.2, torch.float32, bq=bq)
+    z = sla.sla_sizes(p)
+    s = rng.integers(-2, 3, size=(1, 3, z.Tq, z.T)).astype(np.float32)
+    s[0, 0, 0] = 0.0
+    s[0, 0, 1, ::2] = -0.0
+    s[0, 1] = rng.standard_normal((z.Tq, z.T)).astype(np.float32)
+    nh, nl = oracle.counts(z.T, 0.1, 0.2)
+    ref = oracle.classify(s, nh, nl)
+    Mc, luts = sla.sla_classify_scores(p, torch.from_numpy(s).cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(Mc.cpu().numpy(), ref)
+    v = {k: t.cpu().numpy() for k, t in sla.lut_views(p, luts).items()}
+    check_luts(per_tile(ref, bq // 64, z.T), v["row_idx"], v["col_ptr"], v["col_rows"], v["ind"], v["ind_t"],
+               v["col_order"])
+
+
 def test_forward_without_saved_matches(oracle):
     from paper_2509_24006_amd import binding as sla
     from tests.gpu_util import to_dev, f64
