@@ -140,6 +140,11 @@ int sla_classify_scores(const sla_params* p, const float* scores, int8_t* Mc, vo
   fill_sizes(s, &z);
   hipStream_t st = (hipStream_t)stream;
   char* l = (char*)luts;
+  if (s.T <= kBlk)
+    return hip_status(launch_mask_small(nullptr, nullptr, scores, s, nullptr, Mc, (int32_t*)(l + z.lut_row_idx),
+                                        (unsigned long long*)(l + z.lut_ind), (unsigned long long*)(l + z.lut_ind_t),
+                                        (int32_t*)(l + z.lut_col_ptr), (int32_t*)(l + z.lut_col_order),
+                                        (int32_t*)(l + z.lut_col_rows), st));
   int32_t* col_cnt = (int32_t*)(l + z.luts_bytes - align_up((size_t)s.BH * s.T * 4));
   hipError_t e = launch_classify(scores, s, Mc, (int32_t*)(l + z.lut_row_idx), col_cnt, st);
   if (e == hipSuccess)
@@ -165,6 +170,13 @@ int sla_build_mask(const sla_params* p, const void* Q, const void* K, int8_t* Mc
   float* kbar = (float*)(ws + z.ws_mask_kbar);
   float* sc = (float*)(ws + z.ws_mask_scores);
   hipError_t e = launch_pool(Q, K, s, qbar, kbar, st);
+  if (e == hipSuccess && s.T <= kBlk) {
+    char* l = (char*)luts;
+    return hip_status(launch_mask_small(qbar, kbar, nullptr, s, sc, Mc, (int32_t*)(l + z.lut_row_idx),
+                                        (unsigned long long*)(l + z.lut_ind), (unsigned long long*)(l + z.lut_ind_t),
+                                        (int32_t*)(l + z.lut_col_ptr), (int32_t*)(l + z.lut_col_order),
+                                        (int32_t*)(l + z.lut_col_rows), st));
+  }
   if (e == hipSuccess) e = launch_scores(qbar, kbar, s, sc, st);
   if (e != hipSuccess) return SLA_EHIP;
   return sla_classify_scores(p, sc, Mc, luts, stream);

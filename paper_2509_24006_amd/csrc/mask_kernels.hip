@@ -32,8 +32,20 @@ __global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ X0, con
   float s[V];
 #pragma unroll
   for (int v = 0; v < V; ++v) s[v] = 0.0f;
-#pragma unroll 8
-  for (int r = 0; r < cnt; ++r) {
+  // 16 rows are requested before the first is added (the sum itself stays in token order)
+  int r = 0;
+  for (; r + 16 <= cnt; r += 16) {
+    uint4 raw[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) raw[k] = *reinterpret_cast<const uint4*>(p + (size_t)(r + k) * lay.ts);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      const T* e = reinterpret_cast<const T*>(&raw[k]);
+#pragma unroll
+      for (int v = 0; v < V; ++v) s[v] = s[v] + to_f32(e[v]);
+    }
+  }
+  for (; r < cnt; ++r) {
     const uint4 raw = *reinterpret_cast<const uint4*>(p + (size_t)r * lay.ts);
     const T* e = reinterpret_cast<const T*>(&raw);
 #pragma unroll
@@ -51,16 +63,12 @@ __global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ X0, con
 // 64x64 output tile per workgroup, 4x4 outputs per thread, features staged through LDS in
 // chunks of 64 and read four at a time; each output keeps one fused multiply-add chain in
 // ascending feature order.
-__global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ qbar,
-                                                    const float* __restrict__ kbar, int Tq, int T, int d,
-                                                    float scale, float* __restrict__ s) {
-  __shared__ __attribute__((aligned(16))) float qs[64][68];
-  __shared__ __attribute__((aligned(16))) float ks[64][68];
+// acc[a][b] = sum over features (ascending, one fused multiply-add chain) of
+// qb[i0 + ty + 16 a][.] kb[j0 + tx + 16 b][.]; rows past Tq / T count as zeros.
+__device__ __forceinline__ void score_tile(const float* __restrict__ qb, const float* __restrict__ kb, int Tq, int T,
+                                           int d, int i0, int j0, float (*qs)[68], float (*ks)[68],
+                                           float (&acc)[4][4]) {
   const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
-  const int bh = blockIdx.z, i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
-  const float* qb = qbar + (size_t)bh * Tq * d;
-  const float* kb = kbar + (size_t)bh * T * d;
-  float acc[4][4];
 #pragma unroll
   for (int a = 0; a < 4; ++a)
 #pragma unroll
@@ -98,6 +106,17 @@ __global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ qb
     }
     __syncthreads();
   }
+}
+
+__global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ qbar,
+                                                    const float* __restrict__ kbar, int Tq, int T, int d,
+                                                    float scale, float* __restrict__ s) {
+  __shared__ __attribute__((aligned(16))) float qs[64][68];
+  __shared__ __attribute__((aligned(16))) float ks[64][68];
+  const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
+  const int bh = blockIdx.z, i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
+  float acc[4][4];
+  score_tile(qbar + (size_t)bh * Tq * d, kbar + (size_t)bh * T * d, Tq, T, d, i0, j0, qs, ks, acc);
 #pragma unroll
   for (int a = 0; a < 4; ++a) {
     const int i = i0 + ty + 16 * a;
@@ -423,6 +442,104 @@ __global__ __launch_bounds__(256) void col_tables_kernel(const int8_t* __restric
   }
 }
 
+
+// ---------------------------------------------------------------- short sequences
+// At most 64 key blocks: scores, classification and all tables of a head in one workgroup.  At
+// that size each of the four kernels above is a few microseconds of work behind as many
+// microseconds of launch.  Same arithmetic, same tables.  With `given` the scores are read
+// instead of computed (classification of given scores).
+__global__ __launch_bounds__(256) void mask_small_kernel(
+    const float* __restrict__ qbar, const float* __restrict__ kbar, const float* __restrict__ given, int Tq, int rq,
+    int T, int d, float scale, int n_h, int n_l, float* __restrict__ s_out, int8_t* __restrict__ Mc,
+    int32_t* __restrict__ row_idx, unsigned long long* __restrict__ ind, unsigned long long* __restrict__ indT,
+    int32_t* __restrict__ col_ptr, int32_t* __restrict__ col_order, int32_t* __restrict__ col_rows) {
+  __shared__ __attribute__((aligned(16))) float qs[64][68];
+  __shared__ __attribute__((aligned(16))) float ks[64][68];
+  __shared__ float sc[64][65];
+  __shared__ int8_t lab[64][68];   // labels of the rows of M_c; 2 past the end of a row
+  __shared__ int cnt[64], cptr[64];
+  const int bh = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const unsigned long long below = (1ull << lane) - 1ull;
+  if (given) {
+    const float* g = given + (size_t)bh * Tq * T;
+    for (int e = tid; e < Tq * T; e += 256) sc[e / T][e % T] = g[e];
+  } else {
+    float acc[4][4];
+    score_tile(qbar + (size_t)bh * Tq * d, kbar + (size_t)bh * T * d, Tq, T, d, 0, 0, qs, ks, acc);
+    const int ty = tid >> 4, tx = tid & 15;
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        const int i = ty + 16 * a, j = tx + 16 * b;
+        if (i < Tq && j < T) {
+          const float v = __fmul_rn(acc[a][b], scale);
+          sc[i][j] = v;
+          s_out[((size_t)bh * Tq + i) * T + j] = v;
+        }
+      }
+  }
+  __syncthreads();
+  // classification: a wave per row of M_c, the row in one register per lane
+  for (int i = wave; i < Tq; i += 4) {
+    uint32_t key[1];
+    int8_t lb[1];
+    key[0] = lane < T ? order_key(sc[i][lane]) : 0u;
+    lb[0] = 0;
+    mark_top_reg<1>(key, lb, n_h, (int8_t)1, lane);
+    key[0] = (lb[0] == 1 || lane >= T) ? 0u : ~key[0];
+    mark_top_reg<1>(key, lb, n_l, (int8_t)-1, lane);
+    if (lane < T) Mc[((size_t)bh * Tq + i) * T + lane] = lb[0];
+    lab[i][lane] = lane < T ? lb[0] : (int8_t)2;
+    const unsigned long long m = __ballot(lb[0] == 1);
+    if (lb[0] == 1) {
+      const int pos = __popcll(m & below);
+      const int nrep = min(rq, T - i * rq);   // the query tiles of this row
+      for (int r = 0; r < nrep; ++r) row_idx[((size_t)bh * T + i * rq + r) * n_h + pos] = lane;
+    }
+  }
+  __syncthreads();
+  // bit masks and column counts over query tiles: tile r has the labels of row r / rq
+  for (int r = wave; r < 64; r += 4) {
+    const int8_t rv = (r < T) ? lab[r / rq][lane] : (int8_t)2;                 // row r, column = lane
+    const int8_t cv = (r < T && lane < T) ? lab[lane / rq][r] : (int8_t)2;     // column r, query tile = lane
+    const unsigned long long rowbits = __ballot(rv == 0), colbits = __ballot(cv == 0);
+    const int ncrit = __popcll(__ballot(cv == 1));
+    if (lane == 0) {
+      cnt[r] = ncrit;
+      if (r < T) {
+        ind[(size_t)bh * T + r] = rowbits;
+        indT[(size_t)bh * T + r] = colbits;
+      }
+    }
+  }
+  __syncthreads();
+  if (wave == 0) {
+    const int c = cnt[lane];
+    int incl = c;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int v = __shfl_up(incl, o);
+      if (lane >= o) incl += v;
+    }
+    cptr[lane] = incl - c;
+    if (lane < T) {
+      col_ptr[(size_t)bh * (T + 1) + lane] = incl - c;
+      if (lane == T - 1) col_ptr[(size_t)bh * (T + 1) + T] = incl;
+      int rank = 0;
+      for (int k = 0; k < T; ++k) rank += (cnt[k] > c) || (cnt[k] == c && k < lane);
+      col_order[(size_t)bh * T + rank] = lane;
+    }
+  }
+  __syncthreads();
+  if (n_h == 0) return;
+  for (int j = wave; j < T; j += 4) {   // the critical query tiles of column j, ascending
+    const bool crit = lane < T && lab[lane / rq][j] == 1;
+    const unsigned long long m = __ballot(crit);
+    if (crit) col_rows[(size_t)bh * T * n_h + cptr[j] + __popcll(m & below)] = lane;
+  }
+}
+
 }  // namespace
 
 // block means of Q (blocks of 64 rq tokens) and K (64) -> qbar (float [BH][Tq][d]), kbar (float [BH][T][d])
@@ -484,6 +601,15 @@ hipError_t launch_csc(const int8_t* Mc, const Shape& s, int32_t* col_cnt, int32_
     col_tables_kernel<<<dim3(Tw, s.BH), 256, s.T * sizeof(int), st>>>(Mc, s.Tq, s.rq, s.T, s.n_h, col_cnt, col_ptr, col_order,
                                                                       col_rows);
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_mask_small(const float* qbar, const float* kbar, const float* given, const Shape& s, float* scores,
+                             int8_t* Mc, int32_t* row_idx, unsigned long long* ind, unsigned long long* indT,
+                             int32_t* col_ptr, int32_t* col_order, int32_t* col_rows, hipStream_t st) {
+  KernelTimer kt("mask_small", st);
+  mask_small_kernel<<<s.BH, 256, 0, st>>>(qbar, kbar, given, s.Tq, s.rq, s.T, s.d, s.scale, s.n_h, s.n_l, scores, Mc,
+                                          row_idx, ind, indT, col_ptr, col_order, col_rows);
   return hipGetLastError();
 }
 

@@ -46,6 +46,12 @@ hipError_t launch_classify(const float* scores, const Shape& s, int8_t* Mc, int3
 hipError_t launch_csc(const int8_t* Mc, const Shape& s, int32_t* col_cnt, int32_t* col_ptr, int32_t* col_rows,
                       unsigned long long* ind, unsigned long long* indT, int32_t* col_order, hipStream_t st);
 
+// T <= 64: scores (computed from qbar, kbar and written to `scores`, or read from `given`),
+// classification and all tables in one launch
+hipError_t launch_mask_small(const float* qbar, const float* kbar, const float* given, const Shape& s, float* scores,
+                             int8_t* Mc, int32_t* row_idx, unsigned long long* ind, unsigned long long* indT,
+                             int32_t* col_ptr, int32_t* col_order, int32_t* col_rows, hipStream_t st);
+
 // ---- float-arithmetic path (simt_kernels.hip): every contraction in fp32 FMA
 struct FwdArgs {
   const void *Q, *K, *V, *W;
