@@ -168,9 +168,10 @@ def test_image_shaped_batch_against_oracle(oracle):
     assert err <= tol
 
 
-@pytest.mark.parametrize("T", [2050, 3072])
+@pytest.mark.parametrize("T", [200, 700, 2050, 3072])
 def test_masks_of_very_long_sequences(oracle, T):
-    # beyond 2048 blocks the classification keeps a row's keys in LDS instead of registers;
+    # 200 and 700 blocks: 4 and 16 keys of a row per lane in registers (the other register widths are
+    # covered by the workloads); beyond 2048 blocks the classification keeps a row's keys in LDS instead of registers;
     # 3072 blocks is the longest sequence the library takes.  Masks and tables bit for bit.
     N, d, H = 64 * T - 57, 64, 1
     rng = np.random.default_rng(T)

@@ -154,6 +154,18 @@ def test_bf16_mid_length_sequences(oracle, N, d):
     _full_case(oracle, x, "bf16", 0.1, 0.2)
 
 
+@pytest.mark.timeout(300)
+def test_many_long_heads(oracle):
+    # 32 (batch x head) problems of 128 blocks: the launch order of the dK/dV kernel in which every
+    # XCD takes whole heads one after the other (chosen from 32 problems and 128 blocks on), with a
+    # ragged tail; all heads against the oracle
+    B, H, N, d = 4, 8, 128 * 64 - 17, 64
+    rng = np.random.default_rng(4128)
+    x = {k: wl.round_to_bf16(rng.standard_normal((B, H, N, d)).astype(np.float32)) for k in ("Q", "K", "V", "dO")}
+    x["Proj"] = wl.round_to_bf16((rng.standard_normal((d, d)) * 0.05).astype(np.float32))
+    _full_case(oracle, x, "bf16", 0.05, 0.10)
+
+
 @pytest.mark.parametrize("name", ["small_bf16", "small_bf16_d64", "small_fp32"])
 def test_token_major_tensors(oracle, name):
     # [B,N,H,d] tensors: the same kernels walk the same values with another row pitch, so every
