@@ -155,6 +155,18 @@ def test_bf16_mid_length_sequences(oracle, N, d):
 
 
 @pytest.mark.timeout(300)
+@pytest.mark.parametrize("N,d", [(300 * 64 - 9, 128), (71 * 64 + 3, 64)])
+def test_bf16_ragged_tiles_of_the_state_aggregation(oracle, N, d):
+    # 300 blocks: two row tiles of the aggregation GEMM, the second with 44 rows, five indicator
+    # words per row, the last with 44 bits; 72 blocks: one ragged row tile, two words.  Forward and
+    # backward (the column-wise aggregation uses the transposed indicator)
+    rng = np.random.default_rng(N + d)
+    x = {k: wl.round_to_bf16(rng.standard_normal((1, 2, N, d)).astype(np.float32)) for k in ("Q", "K", "V", "dO")}
+    x["Proj"] = wl.round_to_bf16((rng.standard_normal((d, d)) * 0.05).astype(np.float32))
+    _full_case(oracle, x, "bf16", 0.05, 0.15)
+
+
+@pytest.mark.timeout(300)
 def test_many_long_heads(oracle):
     # 32 (batch x head) problems of 128 blocks: the launch order of the dK/dV kernel in which every
     # XCD takes whole heads one after the other (chosen from 32 problems and 128 blocks on), with a
