@@ -456,6 +456,21 @@ void sla_oracle_pc(const float* s, int rows, int Tn, float* Pc) {
   }
 }
 
+// Alg. 1 accumulation line on its own: out[i][:] = sum, in ascending j, of the rows h[j][:] with
+// Mc[i][j] == 0 (marginal), for given rows h [BH, Tn, len] (double) and masks Mc [BH, Tm, Tn].
+void sla_oracle_accumulate(int BH, int Tm, int Tn, int len, const double* h, const int8_t* Mc, double* out) {
+  for (int g = 0; g < BH; ++g)
+    for (int i = 0; i < Tm; ++i) {
+      double* o = out + ((size_t)g * Tm + i) * len;
+      for (int c = 0; c < len; ++c) o[c] = 0.0;
+      for (int j = 0; j < Tn; ++j) {
+        if (Mc[((size_t)g * Tm + i) * Tn + j] != 0) continue;
+        const double* r = h + ((size_t)g * Tn + j) * len;
+        for (int c = 0; c < len; ++c) o[c] += r[c];
+      }
+    }
+}
+
 #define SLA_ORACLE_API(SUF, R)                                                                     \
   int sla_oracle_forward_##SUF(int BH, int N, int d, int bq, int bkv, int phi, const R* Q,          \
                                const R* K, const R* V, const R* W, const int8_t* Mc, R* O, R* Os,  \

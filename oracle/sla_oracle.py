@@ -99,6 +99,19 @@ def build_mask(Q: np.ndarray, K: np.ndarray, k_h: float, k_l: float, bq: int = 6
     return Mc
 
 
+def accumulate(h: np.ndarray, Mc: np.ndarray) -> np.ndarray:
+    """Alg. 1 accumulation line alone: out[..., i, :] = sum of h[..., j, :] over the marginal
+    blocks j of row i.  h: [..., Tn, len]; Mc: [..., Tm, Tn]; returns float64 [..., Tm, len]."""
+    Tn, ln = h.shape[-2:]
+    Tm = Mc.shape[-2]
+    hf = np.ascontiguousarray(h, np.float64).reshape(-1, Tn, ln)
+    mf = np.ascontiguousarray(Mc, np.int8).reshape(-1, Tm, Tn)
+    assert hf.shape[0] == mf.shape[0] and Mc.shape[-1] == Tn
+    out = np.empty((hf.shape[0], Tm, ln), np.float64)
+    lib().sla_oracle_accumulate(hf.shape[0], Tm, Tn, ln, _p(hf), _p(mf), _p(out))
+    return out.reshape(h.shape[:-2] + (Tm, ln))
+
+
 def forward(Q, K, V, W, Mc, phi: int = 0, bq: int = 64, bkv: int = 64,
             dtype=np.float64) -> Dict[str, np.ndarray]:
     """Algorithm 1 with a given mask.  Returns O, Os, Ol, L, Hi, Zi in `dtype`."""

@@ -139,6 +139,31 @@ def test_preaggregation_identity_and_saved_states(oracle):
         np.testing.assert_allclose(f["Zi"][i], Zi, rtol=1e-9, atol=1e-12)
 
 
+def test_accumulation_line_alone(oracle):
+    # The standalone accumulation (Alg. 1, line that adds h_j into H_i) against three things it does
+    # not share code with: a 0/1 matrix product, the identity of Appendix A.3 (total minus the
+    # non-marginal rows), and the H_i, Z_i the forward pass itself returns for the true states.
+    rng = np.random.default_rng(11)
+    Mc = rng.integers(-1, 2, size=(2, 3, 7, 9)).astype(np.int8)
+    Mc[0, 0, 0] = 1            # a row with no marginal block
+    Mc[0, 0, 1] = 0            # a row with every block marginal
+    h = rng.standard_normal((2, 3, 9, 5))
+    got = oracle.accumulate(h, Mc)
+    np.testing.assert_allclose(got, np.einsum("bhij,bhjc->bhic", (Mc == 0).astype(np.float64), h), rtol=1e-12, atol=1e-14)
+    total = h.sum(-2, keepdims=True)
+    other = np.einsum("bhij,bhjc->bhic", (Mc != 0).astype(np.float64), h)
+    np.testing.assert_allclose(got, total - other, rtol=1e-10, atol=1e-12)
+    assert np.all(got[0, 0, 0] == 0) and np.allclose(got[0, 0, 1], h[0, 0].sum(0))
+    Q, K, V, W, dO, Mq = _rand_case(6, 160, 8, 16, 0.2, 0.2, oracle)
+    f = oracle.forward(Q, K, V, W, Mq, bq=16, bkv=16)
+    kp = pins.phi_t(torch.tensor(K), 0).numpy()
+    hz = np.stack([np.concatenate([(kp[j * 16:(j + 1) * 16].T @ V[j * 16:(j + 1) * 16]).ravel(),
+                                   kp[j * 16:(j + 1) * 16].sum(0)]) for j in range(10)])
+    acc = oracle.accumulate(hz, Mq)
+    np.testing.assert_allclose(acc[:, :64].reshape(10, 8, 8), f["Hi"], rtol=1e-9, atol=1e-12)
+    np.testing.assert_allclose(acc[:, 64:], f["Zi"], rtol=1e-9, atol=1e-12)
+
+
 def test_key_block_permutation_leaves_output_unchanged(oracle):
     Q, K, V, W, dO, Mc = _rand_case(7, 128, 8, 16, 0.25, 0.25, oracle)
     perm = np.random.default_rng(0).permutation(8)
