@@ -61,6 +61,9 @@ def main() -> int:
                          "has left its idle state (a cold start runs the same kernels at about 1.6 instead of "
                          "2.0 GHz); 0 disables")
     ap.add_argument("--bq", type=int, default=64, help="query block size of the mask (64, 128, 192, 256)")
+    ap.add_argument("--agg-compare", action="store_true",
+                    help="also time the accumulation line of Alg. 1 alone (random bf16 states, this workload's mask) "
+                         "by the product the library uses and by the three forms the paper describes")
     ap.add_argument("--token-major", action="store_true",
                     help="hand the library [B,N,H,d] tensors (SLA_BNHD) instead of [B,H,N,d]")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -215,6 +218,23 @@ def main() -> int:
                  "speedup_bwd": dbw / ms_bwd, "speedup_fwd_bwd": (dfw + dbw) / (ms_fwd + ms_bwd)}
         del bd
 
+    # the accumulation line alone, by every method (same mask, random states: the time does not
+    # depend on the values)
+    agg = None
+    if args.agg_compare and w.dtype == "bf16":
+        hst = torch.randn((p.B, p.H, z.T, w.d * w.d + w.d), device="cuda").to(torch.bfloat16)
+        agg = {}
+        for method, name in ((sla.SLA_AGG_GEMM, "product"), (sla.SLA_AGG_ADD, "additions"),
+                             (sla.SLA_AGG_PREAGG, "pre_aggregation"), (sla.SLA_AGG_FOUR_RUSSIANS, "four_russians")):
+            need = sla.sla_aggregate_ws_bytes(p, method)
+            ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+            outb = sla.sla_aggregate_states(p, method, b["luts"], hst, workspace=ws)
+            run = lambda: sla.sla_aggregate_states(p, method, b["luts"], hst, workspace=ws, out=outb)
+            run(); torch.cuda.synchronize()
+            agg[name] = {"ms": timed(run, 5)[1], "workspace_bytes": need}
+            del ws, outb
+        del hst
+
     # CPU oracle on a bounded sample: the first heads of the same workload, one thread per head
     cpu = None
     if args.cpu_heads > 0:
@@ -255,6 +275,7 @@ def main() -> int:
         "roofline": roof,
         "cpu_baseline": cpu,
         "settle_steps": settle_steps,
+        "aggregation_methods": agg,
         "input_gen_s": t_gen,
     }
     print(json.dumps(out))

@@ -135,6 +135,23 @@ int sla_backward(const sla_params* p, const void* Q, const void* K, const void* 
                  void* dK, void* dV, float* dW, void* workspace, size_t workspace_bytes,
                  void* stream);
 
+/* Alg. 1's accumulation line on its own, by a chosen method:
+ *   H_i = sum of h_j over the marginal key blocks j of query tile i,  Z_i likewise from z_j.
+ * SLA_AGG_GEMM is what sla_forward and sla_backward use (a product with the 0/1 marginal
+ * indicator on the matrix cores); the others are the forms the paper describes, kept for
+ * comparison: SLA_AGG_ADD one addition per marginal block (Alg. 1 as written), SLA_AGG_PREAGG
+ * the sum over all blocks minus the non-marginal ones and SLA_AGG_FOUR_RUSSIANS tabulated
+ * subset sums of groups of four blocks (both Appendix A.3).
+ * bf16 only (p->dtype == SLA_BF16).  h: bf16 [B,H,T,d*d + d] state rows (the matrix
+ * transposed, then the vector, see "state row" above).  luts: from sla_build_mask or
+ * sla_classify_scores for the same params.  outH: bf16 [B,H,T,d*d]; outZ: float [B,H,T,d].
+ * workspace: >= the bytes sla_aggregate_ws_bytes reports for the method (may be NULL when
+ * that is 0). */
+enum { SLA_AGG_GEMM = 0, SLA_AGG_ADD = 1, SLA_AGG_PREAGG = 2, SLA_AGG_FOUR_RUSSIANS = 3 };
+int sla_aggregate_ws_bytes(const sla_params* p, int method, uint64_t* bytes);
+int sla_aggregate_states(const sla_params* p, int method, const void* luts, const void* h, void* outH,
+                         float* outZ, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Optional per-kernel timing for benchmarks.  While enabled, each kernel the library
  * launches is bracketed by a pair of HIP events on the caller's stream.
  * sla_profile_read waits for the recorded events, writes one line "name count total_ms"

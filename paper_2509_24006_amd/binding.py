@@ -19,7 +19,9 @@ LIB_PATH = os.path.join(_HERE, "libsla_hip.so")
 SLA_F32, SLA_BF16 = 0, 1
 SLA_PHI_SOFTMAX, SLA_PHI_ELU1 = 0, 1
 SLA_BHND, SLA_BNHD, SLA_STRIDED = 0, 1, 2
+SLA_AGG_GEMM, SLA_AGG_ADD, SLA_AGG_PREAGG, SLA_AGG_FOUR_RUSSIANS = 0, 1, 2, 3
 EXPORTS = ("sla_sizes", "sla_build_mask", "sla_classify_scores", "sla_forward", "sla_backward",
+           "sla_aggregate_ws_bytes", "sla_aggregate_states",
            "sla_profile_enable", "sla_profile_read", "sla_strerror")
 
 
@@ -62,6 +64,8 @@ def lib() -> ctypes.CDLL:
         L.sla_classify_scores.argtypes = [pp, vp, vp, vp, vp]
         L.sla_forward.argtypes = [pp] + [vp] * 9 + [sz, vp]
         L.sla_backward.argtypes = [pp] + [vp] * 13 + [sz, vp]
+        L.sla_aggregate_ws_bytes.argtypes = [pp, ctypes.c_int, ctypes.POINTER(ctypes.c_uint64)]
+        L.sla_aggregate_states.argtypes = [pp, ctypes.c_int, vp, vp, vp, vp, vp, sz, vp]
         L.sla_profile_enable.argtypes = [ctypes.c_int]
         L.sla_profile_read.argtypes = [ctypes.c_char_p, sz]
         L.sla_strerror.argtypes = [ctypes.c_int]
@@ -184,6 +188,32 @@ def sla_backward(p: sla_params, Q, K, V, W, Mc, luts, saved, dO,
                               _ptr(luts), _ptr(saved), _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV),
                               _ptr(dW), _ptr(ws), ws.numel(), _stream()), "sla_backward")
     return dQ, dK, dV, dW
+
+
+def sla_aggregate_ws_bytes(p: sla_params, method: int) -> int:
+    n = ctypes.c_uint64()
+    _check(lib().sla_aggregate_ws_bytes(ctypes.byref(p), method, ctypes.byref(n)), "sla_aggregate_ws_bytes")
+    return n.value
+
+
+def sla_aggregate_states(p: sla_params, method: int, luts: torch.Tensor, h: torch.Tensor,
+                         workspace: Optional[torch.Tensor] = None, out=None
+                         ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Alg. 1's accumulation line alone.  h: bf16 [B,H,T,d*d+d] state rows; returns
+    (H bf16 [B,H,T,d*d], Z float32 [B,H,T,d]).  method: one of SLA_AGG_*."""
+    z = sla_sizes(p)
+    want = (p.B, p.H, z.T, p.d * p.d + p.d)
+    if tuple(h.shape) != want or h.dtype != torch.bfloat16 or not h.is_contiguous() or not h.is_cuda:
+        raise SLAError(f"h: expected a contiguous bf16 device tensor of shape {want}")
+    if out is None:
+        out = (torch.empty((p.B, p.H, z.T, p.d * p.d), dtype=torch.bfloat16, device=h.device),
+               torch.empty((p.B, p.H, z.T, p.d), dtype=torch.float32, device=h.device))
+    need = sla_aggregate_ws_bytes(p, method)
+    ws = workspace if workspace is not None else (_buf(need, h.device) if need else None)
+    _check(lib().sla_aggregate_states(ctypes.byref(p), method, _ptr(luts), _ptr(h), _ptr(out[0]), _ptr(out[1]),
+                                      _ptr(ws), ws.numel() if ws is not None else 0, _stream()),
+           "sla_aggregate_states")
+    return out
 
 
 def sla_profile_enable(on: bool) -> None:

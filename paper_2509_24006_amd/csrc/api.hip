@@ -250,6 +250,35 @@ int sla_backward(const sla_params* p, const void* Q, const void* K, const void* 
   return hip_status(simt_backward(s, a, (hipStream_t)stream));
 }
 
+int sla_aggregate_ws_bytes(const sla_params* p, int method, uint64_t* bytes) {
+  Shape s;
+  if (!bytes) return SLA_EINVAL;
+  const int rc = make_shape(p, &s);
+  if (rc != SLA_OK) return rc;
+  if (s.dtype != SLA_BF16 || method < SLA_AGG_GEMM || method > SLA_AGG_FOUR_RUSSIANS) return SLA_EUNSUPPORTED;
+  *bytes = method == SLA_AGG_GEMM ? 0 : aggregate_alt_ws_bytes(s, method);
+  return SLA_OK;
+}
+
+int sla_aggregate_states(const sla_params* p, int method, const void* luts, const void* h, void* outH,
+                         float* outZ, void* workspace, size_t workspace_bytes, void* stream) {
+  uint64_t need = 0;
+  const int rc = sla_aggregate_ws_bytes(p, method, &need);
+  if (rc != SLA_OK) return rc;
+  if (!luts || !h || !outH || !outZ || (need && !workspace)) return SLA_EINVAL;
+  if (misaligned(luts) || misaligned(h) || misaligned(outH) || misaligned(outZ) || misaligned(workspace))
+    return SLA_EINVAL;
+  if (workspace_bytes < need) return SLA_ENOSPACE;
+  Shape s;
+  make_shape(p, &s);
+  sla_sizes_t z;
+  fill_sizes(s, &z);
+  const unsigned long long* ind = (const unsigned long long*)((const char*)luts + z.lut_ind);
+  hipStream_t st = (hipStream_t)stream;
+  if (method == SLA_AGG_GEMM) return hip_status(mfma_aggregate(h, ind, s, outH, outZ, st));
+  return hip_status(aggregate_alt(method, h, ind, s, outH, outZ, workspace, st));
+}
+
 const char* sla_strerror(int code) {
   switch (code) {
     case SLA_OK: return "ok";

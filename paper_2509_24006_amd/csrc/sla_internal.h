@@ -96,6 +96,12 @@ hipError_t mfma_aggregate(const void* in, const unsigned long long* ind, const S
 // followed by a float block [BH][T][d] (vectors); this is the byte offset of the second block.
 inline size_t state_z_offset(const Shape& s) { return ((size_t)s.BH * s.T * s.d * s.d * 2 + 255) / 256 * 256; }
 
+// the same sums by additions (method 1), pre-aggregation (2) or Four Russians tables (3), for
+// comparison (aggregate_alt.hip)
+size_t aggregate_alt_ws_bytes(const Shape& s, int method);
+hipError_t aggregate_alt(int method, const void* in, const unsigned long long* ind, const Shape& s, void* outH,
+                         float* outZ, void* ws, hipStream_t st);
+
 // linear branch and Proj gradients on the matrix cores (mfma_bwd_linear.hip)
 hipError_t mfma_backward_pre(const Shape& s, const BwdArgs& a, float* Ds, void* dHZ16, float* dQlin,
                              float* dWpart, int nparts, hipStream_t st);

@@ -54,6 +54,20 @@ def test_sizes_with_larger_query_blocks():
     assert sla.sla_sizes(sla.make_params(1, 1, 902, 64, 0.1, 0.1, torch.float32, bq=256)).Tq == 4
 
 
+def test_aggregation_workspace_sizes():
+    p = sla.make_params(1, 12, 32760, 128, 0.05, 0.10, torch.bfloat16)
+    row = 128 * 128 + 128
+    assert sla.sla_aggregate_ws_bytes(p, sla.SLA_AGG_GEMM) == 0
+    assert sla.sla_aggregate_ws_bytes(p, sla.SLA_AGG_ADD) == 0
+    assert sla.sla_aggregate_ws_bytes(p, sla.SLA_AGG_PREAGG) == 12 * row * 4
+    assert sla.sla_aggregate_ws_bytes(p, sla.SLA_AGG_FOUR_RUSSIANS) == 12 * 128 * 16 * row * 4   # 128 groups of 4 blocks
+    n = ctypes.c_uint64()
+    assert sla.lib().sla_aggregate_ws_bytes(ctypes.byref(p), 4, ctypes.byref(n)) == -2
+    pf = sla.make_params(1, 2, 1024, 64, 0.1, 0.1, torch.float32)
+    assert sla.lib().sla_aggregate_ws_bytes(ctypes.byref(pf), 0, ctypes.byref(n)) == -2          # bf16 only
+    assert sla.lib().sla_aggregate_states(ctypes.byref(p), 1, None, None, None, None, None, 0, None) == -1
+
+
 def test_counts_agree_with_oracle(oracle):
     for N in (1, 64, 65, 1000, 32760, 75600):
         for kh, kl in ((0.05, 0.1), (0.1, 0.1), (0.025, 0.1), (0.2, 0.1), (1.0, 0.0), (0.0, 0.0), (0.5, 0.5)):

@@ -265,6 +265,35 @@ def test_classify_given_scores_with_ties_and_larger_query_blocks(oracle, bq, N):
                v["col_order"])
 
 
+@pytest.mark.parametrize("T,d,k_h,k_l,bq", [(18, 64, 0.1, 0.1, 64), (71, 64, 0.05, 0.45, 64), (300, 128, 0.05, 0.10, 64),
+                                            (300, 128, 0.05, 0.85, 64), (41, 64, 0.1, 0.2, 128), (9, 128, 0.0, 0.0, 64),
+                                            (33, 64, 0.5, 0.5, 64)])
+def test_accumulation_line_by_every_method(oracle, T, d, k_h, k_l, bq):
+    # Alg. 1's accumulation line alone, by the matrix-core product the library uses and by the three
+    # forms the paper describes (one addition per block, pre-aggregation, Four Russians tables),
+    # on random bf16 states and the mask of random scores: each against the oracle's plain sum.
+    # Densities from every block marginal to none; a tile count that is no multiple of 4 or 64.
+    from paper_2509_24006_amd import binding as sla
+    B, H, N = 1, 2, T * 64 - 5
+    rng = np.random.default_rng(T + d)
+    p = sla.make_params(B, H, N, d, k_h, k_l, torch.bfloat16, bq=bq)
+    z = sla.sla_sizes(p)
+    assert z.T == T
+    s = rng.standard_normal((B, H, z.Tq, T)).astype(np.float32)
+    Mc, luts = sla.sla_classify_scores(p, torch.from_numpy(s).cuda())
+    h = wl.round_to_bf16(rng.standard_normal((B, H, T, d * d + d)).astype(np.float32))
+    ref = oracle.accumulate(h, per_tile(Mc.cpu().numpy(), bq // 64, T))
+    hd = torch.from_numpy(h).cuda().to(torch.bfloat16)
+    for method, name in ((sla.SLA_AGG_GEMM, "product"), (sla.SLA_AGG_ADD, "additions"),
+                         (sla.SLA_AGG_PREAGG, "pre-aggregation"), (sla.SLA_AGG_FOUR_RUSSIANS, "four russians")):
+        Hm, Zm = sla.sla_aggregate_states(p, method, luts, hd)
+        torch.cuda.synchronize()
+        print(f" {name}:", flush=True)
+        _compare("H", Hm.double().cpu().numpy(), ref[..., :d * d], TOL["bf16"])
+        # the vector part leaves in float; pre-aggregation subtracts two long float sums
+        _compare("Z", Zm.double().cpu().numpy(), ref[..., d * d:], 1e-4 if method == sla.SLA_AGG_PREAGG else 1e-5)
+
+
 def test_forward_without_saved_matches(oracle):
     from paper_2509_24006_amd import binding as sla
     from tests.gpu_util import to_dev, f64
