@@ -123,21 +123,13 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
   const int ldv = tile_lane_offset<D>(w, l);
   const int wu = wave_uniform(w);
   const unsigned lds0 = lds_base(smem) + wu * 1024;
-  // L and D^s of the query (32 x + l % 32) of the pair whose tiles are in flight.  Rows past the
-  // end read as 0; their Q and dO rows are zero too, so the finite P they get adds nothing.
-  float lreg = 0.0f, dreg = 0.0f;
-  // the row index of a step is fetched two steps ahead, so the tile loads never wait for it
-  int inext = cnt > 0 ? list[beg] : 0;
-  auto issue = [&](int s, const int bufi) __attribute__((always_inline)) {
+  // the row index of a step is fetched two steps ahead, so the tile loads never wait for it:
+  // icur = query block of the pair that is in flight or in use, inext = the one after it
+  int icur = cnt > 0 ? list[beg] : 0, inext = cnt > 1 ? list[beg + 1] : icur;
+  auto issue = [&](int ii, const int bufi) __attribute__((always_inline)) {
     const int off = bufi * Lds::BUF;
-    const int ii = inext;
-    inext = list[beg + min(s + 1, cnt - 1)];
-    const int rows = min(kBlk, N - ii * kBlk);
     tl.load(descQ, ii, off);
     tl.load(descG, ii, off + Lds::TILE);
-    const int qq = 32 * xh + (lane_id() & 31);
-    lreg = load_f32_or_zero(Lb + (size_t)ii * kBlk, rows, qq);
-    dreg = load_f32_or_zero(Dsb + (size_t)ii * kBlk, rows, qq);
   };
   // K_j and V_j come in as tiles (whole rows per load, zeros past the end of the sequence) and are
   // picked up from LDS in operand layout.  With a linear branch, the aggregated dH^T of this key
@@ -158,9 +150,9 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) z4[dt][r4] = *reinterpret_cast<const f32x4*>(dZ + 32 * (xh * HT + dt) + 8 * r4 + 4 * g);
   } else if (cnt > 0) {
-    issue(0, 0);
+    issue(icur, 0);
   }
-  wait_vm0();
+  wait_vm0_known();
   if (dHcol) {   // (tell the compiler too, or it waits for dZ later, with the first pair's loads in flight)
 #pragma unroll
     for (int dt = 0; dt < HT; ++dt)
@@ -202,7 +194,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) pin_loaded(kc[dt][r4]);
     __syncthreads();   // K_j and V_j are in registers everywhere: their buffer takes the first pair
-    if (cnt > 0) issue(0, 0);
+    if (cnt > 0) issue(icur, 0);
     float kmx, kinv;
     phi_stats<KT>(kf, phi, kmx, kinv);
     TileAddr<D> ma;
@@ -280,20 +272,24 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
     const int QO = buf * Lds::BUF, GO = QO + Lds::TILE;
     ad.refresh();
     at.refresh();
-    wait_vm0();
+    wait_vm0_known();
     __syncthreads();   // tiles of step s have landed for every wave; step s-1 is fully consumed
-    const float lcur = lreg * rscale, dcur = dreg;
-    if (s + 1 < cnt) issue(s + 1, buf ^ 1);
-    // A operands of the extra k-step: (hi, lo) at k = 0, 1 of the lanes with g = 0
-    bf16x8 aL = zero_bf16x8(), aD = zero_bf16x8();
+    // L and D^s of this step's query 32 x + l % 32 are requested now and picked up after the first
+    // products, ahead of the next pair's tile loads in the queue (loads return in order), by loads
+    // the compiler does not see: its own wait for them would come at once and would drain the
+    // tile loads with them.  Rows past the end read as 0; their Q and dO rows are zero too, so
+    // the finite P they get adds nothing.
+    float lreg, dreg;
     {
-      const __bf16 lh = (__bf16)lcur, dh = (__bf16)dcur;
-      const __bf16 ll = (__bf16)(lcur - (float)lh), dl = (__bf16)(dcur - (float)dh);
-      aL[0] = g == 0 ? lh : (__bf16)0.0f;
-      aL[1] = g == 0 ? ll : (__bf16)0.0f;
-      aD[0] = g == 0 ? dh : (__bf16)0.0f;
-      aD[1] = g == 0 ? dl : (__bf16)0.0f;
+      const int rows = min(kBlk, N - icur * kBlk), qq = 32 * xh + (lane_id() & 31);
+      load_f32_or_zero_async(Lb + (size_t)icur * kBlk, rows, qq, lreg);
+      load_f32_or_zero_async(Dsb + (size_t)icur * kBlk, rows, qq, dreg);
     }
+    // (the last step requests its own pair once more, so that every step has the same loads in
+    // flight and one wait serves all)
+    issue(inext, buf ^ 1);
+    icur = inext;
+    inext = list[beg + min(s + 2, cnt - 1)];
     // LDS reads run PF operand pairs ahead of the products that consume them (software pipeline
     // written out by hand: left alone, the compiler reads each operand right before its product
     // and every product then waits a full LDS latency).
@@ -306,13 +302,27 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
 #pragma unroll
     for (int t = 0; t < PF; ++t) read_s(t);
     sched_fence();
-    f32x16 sm = mfma32(aL, bneg, zero_f32x16()), dp = mfma32(aD, bneg, zero_f32x16());
+    f32x16 sm = zero_f32x16(), dp = zero_f32x16();
 #pragma unroll
     for (int t = 0; t < KT; ++t) {
       sm = mfma32(qa[t % PF], kf[t], sm);
       dp = mfma32(ga[t % PF], vf[t], dp);
       if (t + PF < KT) read_s(t + PF);
       sched_fence();
+    }
+    // the extra k-step: A operands (hi, lo) at k = 0, 1 of the lanes with g = 0
+    wait_vm_for<2 * T::IPW>(lreg, dreg);   // the statistics are there, the tile loads may still fly
+    {
+      const float lcur = lreg * rscale, dcur = dreg;
+      bf16x8 aL = zero_bf16x8(), aD = zero_bf16x8();
+      const __bf16 lh = (__bf16)lcur, dh = (__bf16)dcur;
+      const __bf16 ll = (__bf16)(lcur - (float)lh), dl = (__bf16)(dcur - (float)dh);
+      aL[0] = g == 0 ? lh : (__bf16)0.0f;
+      aL[1] = g == 0 ? ll : (__bf16)0.0f;
+      aD[0] = g == 0 ? dh : (__bf16)0.0f;
+      aD[1] = g == 0 ? dl : (__bf16)0.0f;
+      sm = mfma32(aL, bneg, sm);
+      dp = mfma32(aD, bneg, dp);
     }
     // operand i of the second products: i = 2 HT ks + 2 dt + which; which 0: dO^T rows of feature
     // tile x HT + dt (for dV), which 1: Q^T (for dK); k = pair rows 16 ks ..
@@ -363,6 +373,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
   }
   // ---- each wave owns keys 32 kh .., features (D / 2) x .. of dK_j and dV_j: whole-row stores
   // through its own staging area
+  wait_vm0_known();        // the last step's surplus request has landed
   __syncthreads();   // every wave is done with the tiles
   unsigned char* stage = smem + wu * Lds::STG;
   const size_t o0 = lay.head(bh) + (size_t)(k0 + 32 * kh) * lay.ts + (D / 2) * xh;
@@ -495,7 +506,18 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(
     if (s + 1 < n_h) step(s + 1, 1);
   }
   // ---- add the two key halves in a row-major staging area, then every thread takes 16-byte
-  // pieces of whole rows: adds the linear-branch part and stores (coalesced both ways)
+  // pieces of whole rows: adds the linear-branch part and stores (coalesced both ways).  The
+  // linear-branch pieces are requested first, all at once, and arrive under the exchange.
+  constexpr int C4 = D / 4;                  // 16-byte pieces per row
+  constexpr int NIT = kBlk * C4 / 256;       // pieces per thread
+  f32x4 lq[NIT];
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    const int idx = it * 256 + tid, row = idx / C4, c4 = idx % C4;
+    lq[it] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    if (dQlin && row < rows)   // (the library's own tensor: packed)
+      lq[it] = *reinterpret_cast<const f32x4*>(dQlin + ((size_t)bh * N + q0 + row) * D + 4 * c4);
+  }
   __syncthreads();   // every wave is done with the tiles
   constexpr int SP = Lds::SP;
   float* stg = reinterpret_cast<float*>(smem);   // [64 queries][SP]
@@ -521,18 +543,14 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(
       }
   }
   __syncthreads();
-  constexpr int C4 = D / 4;   // 16-byte pieces per row
 #pragma unroll
-  for (int it = 0; it < kBlk * C4 / 256; ++it) {
+  for (int it = 0; it < NIT; ++it) {
     const int idx = it * 256 + tid, row = idx / C4, c4 = idx % C4;
     if (row < rows) {
-      const size_t o = ((size_t)bh * N + q0 + row) * D + 4 * c4;
       const f32x4 sv = *reinterpret_cast<const f32x4*>(stg + row * SP + 4 * c4);
-      f32x4 lq = {0.0f, 0.0f, 0.0f, 0.0f};
-      if (dQlin) lq = *reinterpret_cast<const f32x4*>(dQlin + o);   // (the library's own tensor: packed)
       bf16x4 pk;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) pk[r] = (__bf16)(sv[r] * scale + lq[r]);
+      for (int r = 0; r < 4; ++r) pk[r] = (__bf16)(sv[r] * scale + lq[it][r]);
       *reinterpret_cast<bf16x4*>(dQ + lay.head(bh) + (size_t)(q0 + row) * lay.ts + 4 * c4) = pk;
     }
   }

@@ -207,6 +207,15 @@ __device__ __forceinline__ float load_f32_or_zero(const float* p, int count, int
   return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, idx * 4, 0, 0));
 }
 
+// The same, but the load is invisible to the compiler's own wait insertion (whose waits would also
+// drain the tile loads in flight): `out` is valid only after a wait_vm_for of the caller's that
+// covers this load and names `out`.  Issue and wait belong in the same loop iteration: across a
+// back edge the compiler may copy the register before the load has written it.
+__device__ __forceinline__ void load_f32_or_zero_async(const float* p, int count, int idx, float& out) {
+  const BufDesc r = tile_rsrc(p, count * 4);
+  asm volatile("buffer_load_dword %0, %1, %2, 0 offen" : "=v"(out) : "v"(idx * 4), "s"(r) : "memory");
+}
+
 // lane index inside the wave, recomputed at every use (volatile: the compiler would otherwise
 // hoist it out of a loop and may then spill it) instead of held in a register
 __device__ __forceinline__ int lane_id() {
@@ -482,10 +491,26 @@ inline int xcd_grid(int T) { return 8 * ((T + 7) / 8); }
 
 // all outstanding global loads of this wave (including those that write LDS) have completed
 __device__ __forceinline__ void wait_vm0() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// The same as an instruction the compiler sees, not as text: its own wait insertion then knows
+// that none of its loads is pending either.  For kernels that have compiler-visible loads before
+// a loop of tile loads: otherwise the compiler may guard a register of such a load, long
+// complete, with a wait inside the loop, which drains the tile loads in flight.
+__device__ __forceinline__ void wait_vm0_known() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0); expcnt and lgkmcnt at their maximum = not waited for
+  asm volatile("" ::: "memory");
+}
 // all but the N most recent ones have completed (loads complete in the order they were issued)
 template <int N>
 __device__ __forceinline__ void wait_vm() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// All loads but the N most recent ones have completed; a and b, which asynchronous loads older
+// than those write, may be read from here on (and not before: the operands order the reads).
+template <int N>
+__device__ __forceinline__ void wait_vm_for(float& a, float& b) {
+  asm volatile("s_waitcnt vmcnt(%2) ; %0 %1" : "+v"(a), "+v"(b) : "n"(N) : "memory");
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
