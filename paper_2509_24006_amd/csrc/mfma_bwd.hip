@@ -285,9 +285,10 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
       load_f32_or_zero_async(Lb + (size_t)icur * kBlk, rows, qq, lreg);
       load_f32_or_zero_async(Dsb + (size_t)icur * kBlk, rows, qq, dreg);
     }
-    // (the last step requests its own pair once more, so that every step has the same loads in
-    // flight and one wait serves all)
-    issue(inext, buf ^ 1);
+    // (the last step requests the tile past the end of the sequence, which the range check of the
+    // buffer descriptor answers with zeros without touching memory: every step then has the
+    // same number of loads in flight and one wait serves all)
+    issue(s + 1 < cnt ? inext : Tn, buf ^ 1);
     icur = inext;
     inext = list[beg + min(s + 2, cnt - 1)];
     // LDS reads run PF operand pairs ahead of the products that consume them (software pipeline
