@@ -74,7 +74,8 @@ __global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
         wfr[h2][t] = *reinterpret_cast<const bf16x8*>(W + (size_t)(32 * (par * HT + h2) + ln) * D + 16 * t + 8 * g);
     if (tid < D) zl[tid] = Zs[((size_t)bh * Tn + i) * D + tid];
   }
-  wait_vm0();
+  wait_vm0_known();   // (known to the compiler: it then adds no waits of its own for the W rows, which
+                      // would also wait for the D^s store below)
   __syncthreads();
   TileAddr<D> qa;   // rows 32 qh + ln of a tile
   qa.init(32 * qh, l);
