@@ -21,6 +21,23 @@ def test_exports_match_header():
         assert hasattr(L, name), name
 
 
+def test_constants_match_header():
+    # every enumerator of the header that the binding also defines has the same value there
+    import re
+    text = open(os.path.join(os.path.dirname(__file__), "..", "include", "sla.h")).read()
+    found = {}
+    for body in re.findall(r"enum\s*\{([^}]*)\}", text):
+        for name, val in re.findall(r"(SLA_\w+)\s*=\s*(-?\d+)", body):
+            found[name] = int(val)
+    assert {"SLA_OK", "SLA_BF16", "SLA_BNHD", "SLA_STRIDED", "SLA_PHI_ELU1", "SLA_AGG_FOUR_RUSSIANS"} <= set(found)
+    checked = 0
+    for name, val in found.items():
+        if hasattr(sla, name):
+            assert getattr(sla, name) == val, name
+            checked += 1
+    assert checked >= 11
+
+
 def test_struct_layout_matches_header():
     assert ctypes.sizeof(sla.sla_params) == 80
     assert ctypes.sizeof(sla.sla_sizes_t) == 24 + 20 * 8
