@@ -433,7 +433,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(
     issue(j0, 0);
   }
   const float Lq = qok ? L[(size_t)bh * N + q0 + qrow] * kLog2e : INFINITY;
-  const float Dq = qok ? Ds[(size_t)bh * N + q0 + qrow] : 0.0f;
+  const float nDq = qok ? -Ds[(size_t)bh * N + q0 + qrow] : 0.0f;
   f32x16 dqT[NT];
 #pragma unroll
   for (int t = 0; t < NT; ++t) dqT[t] = zero_f32x16();
@@ -473,7 +473,11 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(
       va[t] = lds_row(smem, ad.row(t) + VO);
     }
     sched_fence();
-    f32x16 sT = zero_f32x16(), dpT = zero_f32x16();
+    // a lane's 16 entries of dP^T belong to its one query: the accumulator starts at -D^s of that
+    // query instead of zero and comes out as dP - D^s
+    f32x16 sT = zero_f32x16(), dpT;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dpT[r] = nDq;
 #pragma unroll
     for (int t = 0; t < KT; ++t) {
       sT = mfma32(ka[t], qf[t], sT);
@@ -490,7 +494,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(
     for (int r = 0; r < 16; ++r) {
       float pv = fast_exp2(fmaf(sT[r], sl2, -Lq));
       if (cols < kBlk && 32 * kh + c_row(r, g) >= cols) pv = 0.0f;
-      dpT[r] = pv * (dpT[r] - Dq);
+      dpT[r] = pv * dpT[r];
     }
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
