@@ -19,6 +19,10 @@ from . import binding as sla
 class _SLAFunction(torch.autograd.Function):
     @staticmethod
     def forward(ctx, Q, K, V, W, p, Mc, luts):
+        # the library reads W in the storage type of Q, K, V (a float parameter next to bf16
+        # activations is cast here; its gradient goes back in the parameter's own type)
+        ctx.w_dtype = W.dtype
+        W = W.detach().to(Q.dtype).contiguous()
         O, saved = sla.sla_forward(p, Q, K, V, W, Mc, luts, need_saved=True)
         ctx.p = p
         ctx.save_for_backward(Q, K, V, W, Mc, luts, saved)
@@ -28,7 +32,7 @@ class _SLAFunction(torch.autograd.Function):
     def backward(ctx, dO):
         Q, K, V, W, Mc, luts, saved = ctx.saved_tensors
         dQ, dK, dV, dW = sla.sla_backward(ctx.p, Q, K, V, W, Mc, luts, saved, dO.contiguous())
-        return dQ, dK, dV, dW.to(W.dtype), None, None, None
+        return dQ, dK, dV, dW.to(ctx.w_dtype), None, None, None
 
 
 def build_mask(Q: torch.Tensor, K: torch.Tensor, k_h: float, k_l: float,

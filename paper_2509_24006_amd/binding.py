@@ -109,7 +109,15 @@ def _buf(nbytes: int, device) -> torch.Tensor:
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
 
 
+def _tdtype(p: sla_params) -> torch.dtype:
+    return torch.float32 if p.dtype == SLA_F32 else torch.bfloat16
+
+
 def _dense(t: torch.Tensor, p: sla_params, what: str) -> torch.Tensor:
+    """Q, K, V, O, dO, dQ, dK, dV: the storage type, shape and memory order the params state.  The
+    C ABI sees bare pointers, so a tensor of another type or shape would be read out of bounds."""
+    if not isinstance(t, torch.Tensor) or t.dtype != _tdtype(p):
+        raise SLAError(f"{what}: expected a {_tdtype(p)} tensor, got {getattr(t, 'dtype', type(t))}")
     if p.layout == SLA_STRIDED:
         want, st = (p.B, p.H, p.N, p.d), (p.stride_b, p.stride_h, p.stride_n, 1)
         if tuple(t.shape) != want or tuple(t.stride()) != st or not t.is_cuda:
@@ -118,6 +126,23 @@ def _dense(t: torch.Tensor, p: sla_params, what: str) -> torch.Tensor:
     want = (p.B, p.N, p.H, p.d) if p.layout == SLA_BNHD else (p.B, p.H, p.N, p.d)
     if tuple(t.shape) != want or not t.is_contiguous() or not t.is_cuda:
         raise SLAError(f"{what}: expected a contiguous device tensor of shape {want}")
+    return t
+
+
+def _packed(t: torch.Tensor, shape, dtype: torch.dtype, what: str) -> torch.Tensor:
+    """a contiguous device tensor of exactly this shape and type (W, M_c, dW, block scores)"""
+    if (not isinstance(t, torch.Tensor) or t.dtype != dtype or tuple(t.shape) != tuple(shape)
+            or not t.is_contiguous() or not t.is_cuda):
+        raise SLAError(f"{what}: expected a contiguous {dtype} device tensor of shape {tuple(shape)}, got "
+                       f"{getattr(t, 'dtype', type(t))} {tuple(getattr(t, 'shape', ()))}")
+    return t
+
+
+def _bytes(t: torch.Tensor, need: int, what: str) -> torch.Tensor:
+    """an opaque byte buffer (tables, saved tensors, workspace) of at least `need` bytes"""
+    if (not isinstance(t, torch.Tensor) or t.dtype != torch.uint8 or t.dim() != 1 or not t.is_contiguous()
+            or not t.is_cuda or t.numel() < need):
+        raise SLAError(f"{what}: expected a contiguous uint8 device buffer of at least {need} bytes")
     return t
 
 
@@ -140,6 +165,8 @@ def sla_build_mask(p: sla_params, Q: torch.Tensor, K: torch.Tensor,
     if luts is None:
         luts = _buf(z.luts_bytes, Q.device)
     ws = workspace if workspace is not None else _buf(z.ws_mask_bytes, Q.device)
+    _packed(Mc, (p.B, p.H, z.Tq, z.T), torch.int8, "Mc")
+    _bytes(luts, z.luts_bytes, "luts"); _bytes(ws, z.ws_mask_bytes, "workspace")
     _check(lib().sla_build_mask(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(Mc), _ptr(luts), _ptr(ws),
                                 ws.numel(), _stream()), "sla_build_mask")
     return Mc, luts, ws
@@ -147,7 +174,7 @@ def sla_build_mask(p: sla_params, Q: torch.Tensor, K: torch.Tensor,
 
 def sla_classify_scores(p: sla_params, s: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor]:
     z = sla_sizes(p)
-    assert s.dtype == torch.float32 and s.is_contiguous() and tuple(s.shape) == (p.B, p.H, z.Tq, z.T)
+    _packed(s, (p.B, p.H, z.Tq, z.T), torch.float32, "s")
     Mc = torch.empty((p.B, p.H, z.Tq, z.T), dtype=torch.int8, device=s.device)
     luts = _buf(z.luts_bytes, s.device)
     _check(lib().sla_classify_scores(ctypes.byref(p), _ptr(s), _ptr(Mc), _ptr(luts), _stream()),
@@ -167,6 +194,12 @@ def sla_forward(p: sla_params, Q, K, V, W, Mc, luts, O: Optional[torch.Tensor] =
     if saved is None and need_saved:
         saved = _buf(z.saved_bytes, Q.device)
     ws = workspace if workspace is not None else _buf(z.ws_forward_bytes, Q.device)
+    _dense(O, p, "O")
+    _packed(W, (p.d, p.d), _tdtype(p), "W")
+    _packed(Mc, (p.B, p.H, z.Tq, z.T), torch.int8, "Mc")
+    _bytes(luts, z.luts_bytes, "luts"); _bytes(ws, z.ws_forward_bytes, "workspace")
+    if saved is not None:
+        _bytes(saved, z.saved_bytes, "saved")
     _check(lib().sla_forward(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(W), _ptr(Mc),
                              _ptr(luts), _ptr(O), _ptr(saved), _ptr(ws), ws.numel(), _stream()),
            "sla_forward")
@@ -177,13 +210,21 @@ def sla_backward(p: sla_params, Q, K, V, W, Mc, luts, saved, dO,
                  workspace: Optional[torch.Tensor] = None, out=None):
     """Returns (dQ, dK, dV, dW); dW is float32 [d, d]."""
     z = sla_sizes(p)
-    _dense(dO, p, "dO")
+    for n, t in (("Q", Q), ("K", K), ("V", V), ("dO", dO)):
+        _dense(t, p, n)
     if out is None:
         dQ, dK, dV = _like(Q, p), _like(K, p), _like(V, p)
         dW = torch.empty((p.d, p.d), dtype=torch.float32, device=Q.device)
     else:
         dQ, dK, dV, dW = out
     ws = workspace if workspace is not None else _buf(z.ws_backward_bytes, Q.device)
+    for n, t in (("dQ", dQ), ("dK", dK), ("dV", dV)):
+        _dense(t, p, n)
+    _packed(W, (p.d, p.d), _tdtype(p), "W")
+    _packed(dW, (p.d, p.d), torch.float32, "dW")
+    _packed(Mc, (p.B, p.H, z.Tq, z.T), torch.int8, "Mc")
+    _bytes(luts, z.luts_bytes, "luts"); _bytes(saved, z.saved_bytes, "saved")
+    _bytes(ws, z.ws_backward_bytes, "workspace")
     _check(lib().sla_backward(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(W), _ptr(Mc),
                               _ptr(luts), _ptr(saved), _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV),
                               _ptr(dW), _ptr(ws), ws.numel(), _stream()), "sla_backward")
@@ -210,6 +251,11 @@ def sla_aggregate_states(p: sla_params, method: int, luts: torch.Tensor, h: torc
                torch.empty((p.B, p.H, z.T, p.d), dtype=torch.float32, device=h.device))
     need = sla_aggregate_ws_bytes(p, method)
     ws = workspace if workspace is not None else (_buf(need, h.device) if need else None)
+    _bytes(luts, z.luts_bytes, "luts")
+    _packed(out[0], (p.B, p.H, z.T, p.d * p.d), torch.bfloat16, "outH")
+    _packed(out[1], (p.B, p.H, z.T, p.d), torch.float32, "outZ")
+    if need:
+        _bytes(ws, need, "workspace")
     _check(lib().sla_aggregate_states(ctypes.byref(p), method, _ptr(luts), _ptr(h), _ptr(out[0]), _ptr(out[1]),
                                       _ptr(ws), ws.numel() if ws is not None else 0, _stream()),
            "sla_aggregate_states")

@@ -140,14 +140,27 @@ def make_proj(w: Workload) -> np.ndarray:
 
 def make_inputs(w: Workload, heads: Optional[Iterable[int]] = None,
                 with_dO: bool = True) -> Dict[str, np.ndarray]:
-    """All tensors of a workload as float32 arrays [B, H', N, d] (H' = selected heads)."""
+    """All tensors of a workload as float32 arrays [B, H', N, d] (H' = selected heads).
+    Every (batch, head) has its own generator, so the heads are drawn by a few threads."""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
     hs = list(range(w.H)) if heads is None else list(heads)
     names = ("Q", "K", "V") + (("dO",) if with_dO else ())
     out = {k: np.empty((w.B, len(hs), w.N, w.d), np.float32) for k in names}
-    for b in range(w.B):
-        for hi, h in enumerate(hs):
-            t = make_head(w, b, h, with_dO)
-            for k in names:
-                out[k][b, hi] = t[k]
+
+    def one(bh):
+        b, hi = bh
+        t = make_head(w, b, hs[hi], with_dO)
+        for k in names:
+            out[k][b, hi] = t[k]
+
+    jobs = [(b, hi) for b in range(w.B) for hi in range(len(hs))]
+    nthr = max(1, min(8, len(jobs), os.cpu_count() or 1))
+    if nthr == 1 or w.N * w.d < (1 << 20):
+        for j in jobs:
+            one(j)
+    else:
+        with ThreadPoolExecutor(nthr) as ex:
+            list(ex.map(one, jobs))
     out["Proj"] = make_proj(w)
     return out

@@ -17,3 +17,13 @@ def oracle():
     from oracle import sla_oracle
     sla_oracle.lib()
     return sla_oracle
+
+
+@pytest.fixture
+def say(capsys):
+    """Progress lines of the long tests: printed past pytest's capture, so that a run that is
+    merely busy on the CPU (the oracle at full size takes minutes) is seen to be alive."""
+    def _say(msg):
+        with capsys.disabled():
+            print(f"\n[{msg}]", end="", flush=True)
+    return _say

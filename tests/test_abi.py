@@ -144,3 +144,26 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
                        timeout=120)
     assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_binding_rejects_tensors_of_the_wrong_type_or_size():
+    # the C ABI takes bare pointers: the binding is where a tensor of another storage type, shape
+    # or size has to be caught (it would be read out of bounds on the device otherwise)
+    p = sla.make_params(1, 2, 256, 64, 0.1, 0.1, torch.bfloat16)
+    q32 = torch.zeros((1, 2, 256, 64), dtype=torch.float32)
+    with pytest.raises(sla.SLAError, match="bfloat16"):
+        sla.sla_build_mask(p, q32, q32)
+    with pytest.raises(sla.SLAError, match="bfloat16"):
+        sla.sla_forward(p, q32, q32, q32, None, None, None)
+    with pytest.raises(sla.SLAError, match="bfloat16"):
+        sla.sla_backward(p, q32, q32, q32, None, None, None, None, q32)
+    with pytest.raises(sla.SLAError, match="W"):
+        sla._packed(torch.zeros((64, 64), dtype=torch.float32), (64, 64), torch.bfloat16, "W")
+    with pytest.raises(sla.SLAError, match="W"):
+        sla._packed(torch.zeros((64, 64), dtype=torch.bfloat16).t()[:, :32], (64, 32), torch.bfloat16, "W")
+    with pytest.raises(sla.SLAError, match="Mc"):
+        sla._packed(torch.zeros((1, 2, 4, 4), dtype=torch.int32), (1, 2, 4, 4), torch.int8, "Mc")
+    with pytest.raises(sla.SLAError, match="luts"):
+        sla._bytes(torch.zeros(16, dtype=torch.uint8), 32, "luts")
+    with pytest.raises(sla.SLAError, match="saved"):
+        sla._bytes(torch.zeros(64, dtype=torch.float32), 32, "saved")

@@ -79,3 +79,28 @@ def test_autograd_token_major(oracle):
         err = pins.rel_l2(got, ref)
         print(f"  token-major {n}: rel_l2 = {err:.3e}", flush=True)
         assert err <= TOL["bf16"], f"{n}: {err:.3e}"
+
+
+def test_autograd_casts_a_float_projection_weight():
+    # a float32 parameter next to bf16 activations: the wrapper hands the library a bf16 copy
+    # (same values here) and returns the gradient in the parameter's own type; the raw binding
+    # refuses the mismatch instead of reading the float matrix as bf16
+    from paper_2509_24006_amd import binding as sla
+    from paper_2509_24006_amd.autograd import build_mask, sla_attention
+    w = wl.WORKLOADS["small_bf16_d64"]
+    x = wl.make_inputs(w)
+    dev = torch.device("cuda:0")
+    Q, K, V = (torch.from_numpy(x[k]).to(dev).to(torch.bfloat16).requires_grad_(True) for k in ("Q", "K", "V"))
+    dO = torch.from_numpy(x["dO"]).to(dev).to(torch.bfloat16)
+    W16 = torch.from_numpy(x["Proj"]).to(dev).to(torch.bfloat16).requires_grad_(True)
+    W32 = torch.from_numpy(x["Proj"]).to(dev).requires_grad_(True)      # bf16-representable values
+    mask = build_mask(Q, K, w.k_h, w.k_l)
+    O16 = sla_attention(Q, K, V, W16, mask=mask)
+    O16.backward(dO)
+    O32 = sla_attention(Q, K, V, W32, mask=mask)
+    O32.backward(dO)
+    torch.cuda.synchronize()
+    assert torch.equal(O16, O32)
+    assert W32.grad.dtype == torch.float32 and torch.equal(W32.grad.to(torch.bfloat16), W16.grad)
+    with pytest.raises(sla.SLAError, match="W"):
+        sla.sla_forward(mask[0], Q.detach(), K.detach(), V.detach(), W32.detach(), mask[1], mask[2])

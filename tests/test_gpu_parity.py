@@ -9,7 +9,7 @@ import torch
 
 from paper_2509_24006_amd import workloads as wl
 from tests import pins
-from tests.gpu_util import TOL, check_luts, per_tile, run_gpu
+from tests.gpu_util import BLOCK_TOL, TOL, check_luts, max_block_rel_l2, per_tile, run_gpu
 
 pytestmark = pytest.mark.gpu
 
@@ -21,7 +21,11 @@ def _oracle_all(oracle, x, k_h, k_l, phi=0, backward=True, bq=64):
     return Mc, s, f, g
 
 
-def _compare(name, got, ref, tol, floor_rms=0.0):
+def _compare(name, got, ref, tol, floor_rms=0.0, block_tol=None, token_axis=2, rows=64):
+    """Whole-tensor relative L2 <= tol and, with block_tol, the same measure on every block of
+    `rows` consecutive indices of token_axis <= block_tol (one bad row cannot hide in a long
+    tensor).  floor_rms > 0 (short sequences' gradients only, see the callers) measures the error
+    against a norm of at least floor_rms per element."""
     if np.all(ref == 0):
         assert np.all(got == 0), f"{name}: expected exact zeros"
         return
@@ -32,13 +36,17 @@ def _compare(name, got, ref, tol, floor_rms=0.0):
     if np.abs(ref).max() < 1e-12:
         assert np.abs(got).max() <= tol, f"{name}: expected ~0, got {np.abs(got).max():.3e}"
         return
-    # floor_rms: for cases where most rows' gradient cancels exactly (a block of one key gives
-    # P = 1 and dS = 0) the norm of the reference is set by a handful of rows while float
-    # rounding noise comes from all of them; the error is then measured against a norm of at
-    # least floor_rms per element (inputs have unit variance)
+    # floor_rms: where a key block holds one or a few keys, P is 1 (or close) and dS = P (dP - D)
+    # cancels exactly in most rows: the norm of the reference gradient is then set by a handful
+    # of rows while float rounding noise comes from all of them; the error is measured against a
+    # norm of at least floor_rms per element (inputs have unit variance)
     scale = max(np.linalg.norm(ref.ravel()), floor_rms * np.sqrt(ref.size))
     err = np.linalg.norm((got - ref).ravel()) / scale
     assert err <= tol, f"{name}: rel L2 {err:.3e} > {tol:g}"
+    if block_tol is not None and floor_rms == 0.0:
+        berr, where = max_block_rel_l2(got, ref, token_axis, rows)
+        print(f"  {name}: worst block rel_l2 = {berr:.3e} at {where} (tol {block_tol:g})", flush=True)
+        assert berr <= block_tol, f"{name}: block {where} rel L2 {berr:.3e} > {block_tol:g}"
 
 
 def _full_case(oracle, x, dtype, k_h, k_l, phi=0, floor_rms=0.0, bq=64, backward=True):
@@ -52,17 +60,17 @@ def _full_case(oracle, x, dtype, k_h, k_l, phi=0, floor_rms=0.0, bq=64, backward
     T, rq = Mc.shape[-1], bq // 64
     check_luts(per_tile(r["Mc"], rq, T), r["row_idx"], r["col_ptr"], r["col_rows"], r["ind"], r["ind_t"],
                r["col_order"])
-    tol = TOL[dtype]
+    tol, btol = TOL[dtype], BLOCK_TOL[dtype]
     for k in ("O", "Os", "Ol"):
-        _compare(k, r[k], f[k], tol)
-    for k in ("Hi", "Zi"):
-        _compare(k, r[k], per_tile(f[k], rq, T), tol)
+        _compare(k, r[k], f[k], tol, block_tol=btol)
+    for k in ("Hi", "Zi"):   # one state per 64-token tile: every state on its own
+        _compare(k, r[k], per_tile(f[k], rq, T), tol, block_tol=btol, rows=1)
     fin = np.isfinite(f["L"])
     assert np.array_equal(np.isfinite(r["L"]), fin)
     if fin.any():
         _compare("L", r["L"][fin], f["L"][fin], tol)
     for k in ("dQ", "dK", "dV", "dW") if backward else ():
-        _compare(k, r[k], g[k], tol, floor_rms)
+        _compare(k, r[k], g[k], tol, floor_rms, block_tol=None if k == "dW" else btol)
 
 
 @pytest.mark.parametrize("name", ["tiny", "small_fp32", "small_bf16", "small_bf16_d64"])
@@ -117,15 +125,17 @@ def test_query_blocks_of_several_tiles_mid_length(oracle, bq):
     _full_case(oracle, x, "bf16", 0.1, 0.2, bq=bq)
 
 
-@pytest.mark.parametrize("scale,backward", [(0.02, True), (2.0, True), (6.0, False)])
-@pytest.mark.parametrize("name", ["small_bf16", "small_fp32"])
+@pytest.mark.parametrize("name,scale,backward", [
+    ("small_bf16", 0.02, True), ("small_bf16", 2.0, True), ("small_bf16", 6.0, False),
+    ("small_fp32", 0.02, True), ("small_fp32", 2.0, True), ("small_fp32", 6.0, True)])
 def test_small_and_large_score_magnitudes(oracle, name, scale, backward):
     # nearly uniform attention (scores ~ 1e-3) and peaked attention (raw scores of a hundred and
     # more before the 1/sqrt(d): exponent range of the online softmax and of its lazy rescaling).
-    # At the largest scale only the forward pass is compared: with P close to one-hot,
+    # At the largest scale the bf16 case compares the forward pass only: with P close to one-hot,
     # dS = P (dP - D) is a small difference of terms of which D comes from the O^s saved in the
     # storage type, so in bf16 the gradients of any implementation that follows Alg. 2 lose
-    # digits there (1.6 % on dQ), which says nothing about the kernels.
+    # digits there (1.6 % on dQ), which says nothing about the kernels.  Float tensors save O^s
+    # in float and are compared in full.
     w = wl.WORKLOADS[name]
     x = wl.make_inputs(w)
     x["Q"] = x["Q"] * np.float32(scale)
@@ -346,8 +356,13 @@ def test_random_small_problems(oracle, seed):
     r = run_gpu(x, dtype, k_h, k_l, phi, token_major=tm)
     assert np.array_equal(r["scores"], s) and np.array_equal(r["Mc"], Mc)
     check_luts(r["Mc"], r["row_idx"], r["col_ptr"], r["col_rows"], r["ind"], r["ind_t"], r["col_order"])
+    # sequences of a few blocks at most: a key block of one or a few keys makes most rows' dS
+    # cancel exactly, see _compare; only the gradients of such draws get the floor
+    short = N < 200
     for k in ("O", "Os", "Ol", "dQ", "dK", "dV", "dW"):
-        _compare(k, r[k], (f if k in f else g)[k], TOL[dtype], floor_rms=0.05)
+        grad = k.startswith("d")
+        _compare(k, r[k], (f if k in f else g)[k], TOL[dtype], floor_rms=0.05 if (short and grad) else 0.0,
+                 block_tol=None if (k == "dW" or short) else BLOCK_TOL[dtype])
 
 
 def test_a_captured_step_replays_to_the_eager_results():

@@ -140,3 +140,18 @@ def test_build_mask_equals_its_parts(oracle):
     # the tail block's pooled vector is the mean of its 22 valid tokens
     np.testing.assert_allclose(oracle.pool(k, 64)[-1], k[17 * 64:].astype(np.float64).mean(0),
                                rtol=1e-5, atol=1e-6)
+
+
+def test_compressed_weights_are_the_row_softmax(oracle):
+    # P_c of Eq. 2 is the row softmax of the block scores: a row whose value is known in closed
+    # form (scores 0 and ln 2 -> 1/3 and 2/3; a constant row -> uniform; shifting a row by a
+    # constant changes nothing), and random rows against the library routine
+    import torch
+    s = np.array([[0.0, math.log(2.0)], [5.0, 5.0], [-3.0, -3.0 + math.log(3.0)]], np.float32)
+    np.testing.assert_allclose(oracle.compressed_weights(s), [[1 / 3, 2 / 3], [0.5, 0.5], [0.25, 0.75]], rtol=1e-6)
+    rng = np.random.default_rng(11)
+    r = (rng.standard_normal((7, 37)) * 4).astype(np.float32)
+    ref = torch.softmax(torch.from_numpy(r).double(), dim=-1).numpy()
+    np.testing.assert_allclose(oracle.compressed_weights(r), ref, rtol=2e-6, atol=1e-12)
+    np.testing.assert_allclose(oracle.compressed_weights(r + np.float32(64.0)), ref, rtol=2e-5, atol=1e-12)
+    # a wrong temperature (scores used twice, or halved) would fail the closed-form rows above
