@@ -266,14 +266,13 @@ hipError_t mfma_aggregate(const void* in, const unsigned long long* ind, const S
   const int row_len = s.state_row(), dd = s.d * s.d;
   const int Tw = (s.T + 63) / 64;
   if (dd % 128 != 0 || row_len - dd > 128) return hipErrorInvalidValue;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(aggregate_mfma_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, kAggLds);
+  hipError_t e = ensure_dyn_lds(aggregate_mfma_kernel, kAggLds);
   if (e != hipSuccess) return e;
   const int mtiles = (s.T + kAggRows - 1) / kAggRows;
   const int ntile = dd / 128 + 1;
   if (s.T <= 64) {
     auto kern = s.T <= 32 ? aggregate_short_kernel<1> : aggregate_short_kernel<2>;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kAggLds);
+    e = ensure_dyn_lds(kern, kAggLds);
     if (e != hipSuccess) return e;
     KernelTimer kt("aggregate", st);
     kern<<<dim3((ntile + 3) / 4, s.BH), 256, kAggLds, st>>>((const bf16*)in, ind, s.T, row_len, dd, (bf16*)outH, outZ);

@@ -285,10 +285,9 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
       load_f32_or_zero_async(Lb + (size_t)icur * kBlk, rows, qq, lreg);
       load_f32_or_zero_async(Dsb + (size_t)icur * kBlk, rows, qq, dreg);
     }
-    // (the last step requests the tile past the end of the sequence, which the range check of the
-    // buffer descriptor answers with zeros without touching memory: every step then has the
-    // same number of loads in flight and one wait serves all)
-    issue(s + 1 < cnt ? inext : Tn, buf ^ 1);
+    // (the last step requests its own pair once more, into the other buffer, where nobody reads
+    // it: every step then has the same number of loads in flight and one wait serves all)
+    issue(s + 1 < cnt ? inext : icur, buf ^ 1);
     icur = inext;
     inext = list[beg + min(s + 2, cnt - 1)];
     // LDS reads run PF operand pairs ahead of the products that consume them (software pipeline
@@ -573,8 +572,7 @@ hipError_t sparse_impl(const Shape& s, const BwdArgs& a, const float* Ds, const 
   const float* dZcol = dHZcol ? reinterpret_cast<const float*>((const char*)dHZcol + state_z_offset(s)) : nullptr;
   constexpr int lds = PairLds<D>::BYTES;
   auto launch_kv = [&](auto kern) -> hipError_t {
-    SLA_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                KvLds<D>::BYTES));
+    SLA_TRY(ensure_dyn_lds(kern, KvLds<D>::BYTES));
     KernelTimer kt("bwd_sparse_kv", st);
     kern<<<dim3(s.T * s.BH), 256, KvLds<D>::BYTES, st>>>(
         (const bf16*)a.Q, (const bf16*)a.K, (const bf16*)a.V, (const bf16*)a.dO, a.L, Ds, a.col_ptr, a.col_rows,
@@ -582,8 +580,7 @@ hipError_t sparse_impl(const Shape& s, const BwdArgs& a, const float* Ds, const 
     return hipSuccess;
   };
   SLA_TRY(s.phi == 0 ? launch_kv(bwd_dkdv_mfma_kernel<D, 0>) : launch_kv(bwd_dkdv_mfma_kernel<D, 1>));
-  SLA_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dq_mfma_kernel<D>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+  SLA_TRY(ensure_dyn_lds(bwd_dq_mfma_kernel<D>, lds));
   {
     KernelTimer kt("bwd_sparse_q", st);
     bwd_dq_mfma_kernel<D><<<dim3(xcd_grid(s.T), s.BH), 256, lds, st>>>(

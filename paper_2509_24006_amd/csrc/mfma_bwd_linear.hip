@@ -116,9 +116,11 @@ __global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
       bf16x4 pk;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const float v = gl[4 * r4 + r];
-        pk[r] = (__bf16)v;
-        dl = fmaf(v, (float)ol4[r], dl);
+        // D^l from the same rounded dO^l that enters the products below: in
+        // dO^l H_i^T - D^l Z_i^T the two terms nearly cancel, and a dO^l that differed between
+        // them by its rounding would leave an error of the size of the terms, not of the result
+        pk[r] = (__bf16)gl[4 * r4 + r];
+        dl = fmaf((float)pk[r], (float)ol4[r], dl);
       }
       *reinterpret_cast<bf16x4*>(smem + S0 + off) = pk;
     }
@@ -346,8 +348,7 @@ template <int D>
 hipError_t pre_impl(const Shape& s, const BwdArgs& a, float* Ds, bf16* dHZ, float* dQlin,
                     float* dWpart, int nparts, hipStream_t st) {
   constexpr int lds = PreLds<D>::BYTES;
-  SLA_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_pre_mfma_kernel<D>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+  SLA_TRY(ensure_dyn_lds(bwd_pre_mfma_kernel<D>, lds));
   {
     KernelTimer kt("bwd_pre", st);
     bwd_pre_mfma_kernel<D><<<dim3(s.T, s.BH), 256, lds, st>>>(

@@ -484,8 +484,7 @@ hipError_t forward_impl(const Shape& s, const FwdArgs& a, bf16* hz16, bf16* WTp,
     fill_zero_f32_kernel<<<1024, 256, 0, st>>>(a.HZ, (size_t)s.BH * s.T * row_len);
   }
   constexpr int lds = FwdLds<D>::BYTES;
-  SLA_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_mfma_kernel<D>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+  SLA_TRY(ensure_dyn_lds(fwd_mfma_kernel<D>, lds));
   {
     KernelTimer kt("fwd_sparse", st);
     fwd_mfma_kernel<D><<<dim3(xcd_grid(s.T), s.BH), 256, lds, st>>>(

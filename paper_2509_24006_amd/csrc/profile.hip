@@ -23,6 +23,20 @@ bool g_on = false;
 std::vector<Rec> g_recs;
 }  // namespace
 
+hipError_t ensure_dyn_lds(const void* kernel, int bytes) {
+  static std::mutex mu;
+  static std::map<std::pair<const void*, int>, int> done;   // (kernel, device) -> bytes granted
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  std::lock_guard<std::mutex> lk(mu);
+  auto it = done.find({kernel, dev});
+  if (it != done.end() && it->second >= bytes) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) done[{kernel, dev}] = bytes;
+  return e;
+}
+
 KernelTimer::KernelTimer(const char* name, hipStream_t st) : st_(st), idx_(-1) {
   std::lock_guard<std::mutex> lk(g_mu);
   if (!g_on) return;

@@ -771,8 +771,7 @@ __global__ __launch_bounds__(kThreads) void bwd_sparse_q_kernel(
 
 template <typename K>
 hipError_t set_lds(K kernel, size_t bytes) {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  return ensure_dyn_lds(kernel, bytes);
 }
 
 #define SLA_TRY(x)                      \

@@ -118,5 +118,13 @@ class KernelTimer {
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
+// Raises the dynamic-LDS limit of a kernel to `bytes`, once per kernel and device (profile.hip);
+// every later call is a table lookup on the host.
+hipError_t ensure_dyn_lds(const void* kernel, int bytes);
+template <typename K>
+hipError_t ensure_dyn_lds(K kernel, size_t bytes) {
+  return ensure_dyn_lds(reinterpret_cast<const void*>(kernel), (int)bytes);
+}
+
 }  // namespace sla
 #endif
