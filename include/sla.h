@@ -20,7 +20,8 @@
  * Conventions
  *   - Every pointer except `sla_params*` / `sla_sizes_t*` is DEVICE memory owned by the
  *     caller.  The library never allocates, frees or keeps device memory, and holds no
- *     state between calls.  Buffers must be 256-byte aligned (any allocator's default).
+ *     state between calls.  Pointers must be 16-byte aligned (a misaligned one is SLA_EINVAL);
+ *     any allocator's buffers are.
  *   - All work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the null
  *     stream); no call synchronises the host.
  *   - Outputs are overwritten, never accumulated into.
@@ -114,6 +115,20 @@ int sla_sizes(const sla_params* p, sla_sizes_t* out);
  * times the float 1/sqrt(d)), so the mask is reproducible bit for bit. */
 int sla_build_mask(const sla_params* p, const void* Q, const void* K, int8_t* Mc, void* luts,
                    void* workspace, size_t workspace_bytes, void* stream);
+
+/* sla_build_mask for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the same kernels, with the workspace in
+ * a device array that is part of the library image instead of a caller's buffer.  The call
+ * allocates nothing and frees nothing (keep sla_profile_enable off: its events are created per
+ * launch).  Limit: problems whose ws_mask_bytes (see sla_sizes) exceed SLA_STATIC_WS_BYTES are
+ * refused with SLA_ENOSPACE before anything is enqueued; the headline shape (12 heads, N = 32760)
+ * needs 18.9 MB.  Each GPU holds one copy of the array for the life of the process; all calls on
+ * a GPU share it, so two calls that may overlap on one GPU (different streams, or threads) race:
+ * serialise them.  The array keeps the last call's pool(Q), pool(K) and scores; no call reads
+ * them before writing them.  Q, K, Mc, luts, stream: as for sla_build_mask. */
+#define SLA_STATIC_WS_BYTES (32u << 20)
+int sla_build_mask_static(const sla_params* p, const void* Q, const void* K, int8_t* Mc, void* luts,
+                          void* stream);
 
 /* Eq. 3 alone: classify given float scores s [B,H,Tq,T] (device) and build the tables. */
 int sla_classify_scores(const sla_params* p, const float* s, int8_t* Mc, void* luts, void* stream);

@@ -20,7 +20,8 @@ SLA_F32, SLA_BF16 = 0, 1
 SLA_PHI_SOFTMAX, SLA_PHI_ELU1 = 0, 1
 SLA_BHND, SLA_BNHD, SLA_STRIDED = 0, 1, 2
 SLA_AGG_GEMM, SLA_AGG_ADD, SLA_AGG_PREAGG, SLA_AGG_FOUR_RUSSIANS = 0, 1, 2, 3
-EXPORTS = ("sla_sizes", "sla_build_mask", "sla_classify_scores", "sla_forward", "sla_backward",
+SLA_STATIC_WS_BYTES = 32 << 20
+EXPORTS = ("sla_sizes", "sla_build_mask", "sla_build_mask_static", "sla_classify_scores", "sla_forward", "sla_backward",
            "sla_aggregate_ws_bytes", "sla_aggregate_states",
            "sla_profile_enable", "sla_profile_read", "sla_strerror")
 
@@ -61,6 +62,7 @@ def lib() -> ctypes.CDLL:
         pp = ctypes.POINTER(sla_params)
         L.sla_sizes.argtypes = [pp, ctypes.POINTER(sla_sizes_t)]
         L.sla_build_mask.argtypes = [pp, vp, vp, vp, vp, vp, sz, vp]
+        L.sla_build_mask_static.argtypes = [pp, vp, vp, vp, vp, vp]
         L.sla_classify_scores.argtypes = [pp, vp, vp, vp, vp]
         L.sla_forward.argtypes = [pp] + [vp] * 9 + [sz, vp]
         L.sla_backward.argtypes = [pp] + [vp] * 13 + [sz, vp]
@@ -170,6 +172,18 @@ def sla_build_mask(p: sla_params, Q: torch.Tensor, K: torch.Tensor,
     _check(lib().sla_build_mask(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(Mc), _ptr(luts), _ptr(ws),
                                 ws.numel(), _stream()), "sla_build_mask")
     return Mc, luts, ws
+
+
+def sla_build_mask_static(p: sla_params, Q: torch.Tensor, K: torch.Tensor, Mc: torch.Tensor,
+                          luts: torch.Tensor) -> None:
+    """sla_build_mask with the workspace inside the library (no allocation in the call): the
+    caller passes the outputs Mc int8 [B,H,Tq,T] and luts (luts_bytes)."""
+    z = sla_sizes(p)
+    _dense(Q, p, "Q"); _dense(K, p, "K")
+    _packed(Mc, (p.B, p.H, z.Tq, z.T), torch.int8, "Mc")
+    _bytes(luts, z.luts_bytes, "luts")
+    _check(lib().sla_build_mask_static(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(Mc), _ptr(luts), _stream()),
+           "sla_build_mask_static")
 
 
 def sla_classify_scores(p: sla_params, s: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor]:

@@ -3,6 +3,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "../../include/sla.h"
 #include "sla_internal.h"
 
@@ -115,6 +117,32 @@ void fill_sizes(const Shape& s, sla_sizes_t* o) {
 
 inline bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
 
+// Workspace of sla_build_mask_static: pool(Q), pool(K) and the block scores of one call.  Every
+// GPU the library runs on holds its own copy of the array, at its own address, until the process
+// ends.  In host code the array's name is not a device address: the address is looked up once per
+// device and only that pointer is handed to kernels.
+static __device__ __align__(256) unsigned char scratch[SLA_STATIC_WS_BYTES];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+hipError_t scratch_of_current_device(void** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
 int hip_status(hipError_t e) { return e == hipSuccess ? SLA_OK : SLA_EHIP; }
 
 }  // namespace
@@ -180,6 +208,22 @@ int sla_build_mask(const sla_params* p, const void* Q, const void* K, int8_t* Mc
   if (e == hipSuccess) e = launch_scores(qbar, kbar, s, sc, st);
   if (e != hipSuccess) return SLA_EHIP;
   return sla_classify_scores(p, sc, Mc, luts, stream);
+}
+
+int sla_build_mask_static(const sla_params* p, const void* Q, const void* K, int8_t* Mc, void* luts,
+                          void* stream) {
+  Shape s;
+  const int rc = make_shape(p, &s);
+  if (rc != SLA_OK) return rc;
+  sla_sizes_t z;
+  fill_sizes(s, &z);
+  if (z.ws_mask_bytes > (uint64_t)SLA_STATIC_WS_BYTES) return SLA_ENOSPACE;
+  if (!Q || !K || !Mc || !luts) return SLA_EINVAL;
+  void* ws = nullptr;
+  if (scratch_of_current_device(&ws) != hipSuccess) return SLA_EHIP;
+  // every byte of the workspace that the mask kernels read is written earlier in the same call,
+  // so nothing has to be cleared between calls
+  return sla_build_mask(p, Q, K, Mc, luts, ws, (size_t)SLA_STATIC_WS_BYTES, stream);
 }
 
 int sla_forward(const sla_params* p, const void* Q, const void* K, const void* V, const void* W,
