@@ -359,9 +359,15 @@ def test_random_small_problems(oracle, seed):
     # sequences of a few blocks at most: a key block of one or a few keys makes most rows' dS
     # cancel exactly, see _compare; only the gradients of such draws get the floor
     short = N < 200
+    # no critical block at all (bf16): dQ and dK are the linear branch's alone, an order of magnitude
+    # smaller than with a sparse part, and dQ^phi = (dO^l H_i^T - D^l Z_i^T) / den is a difference of
+    # nearly equal terms when few blocks are marginal; the H_i saved in bf16 bounds its error
+    # relative to the terms (1.5e-2 of the result for one marginal block per row), so the error is
+    # measured against a gradient of at least floor_rms per element there too
+    lin_only = dtype == "bf16" and int((Mc == 1).sum()) == 0
     for k in ("O", "Os", "Ol", "dQ", "dK", "dV", "dW"):
-        grad = k.startswith("d")
-        _compare(k, r[k], (f if k in f else g)[k], TOL[dtype], floor_rms=0.05 if (short and grad) else 0.0,
+        floor = 0.05 if (k in ("dQ", "dK", "dV", "dW") and short) or (k in ("dQ", "dK") and lin_only) else 0.0
+        _compare(k, r[k], (f if k in f else g)[k], TOL[dtype], floor_rms=floor,
                  block_tol=None if (k == "dW" or short) else BLOCK_TOL[dtype])
 
 
