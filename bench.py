@@ -54,7 +54,10 @@ def main() -> int:
     ap.add_argument("--workload", default="wan")
     ap.add_argument("--k-h", type=float, default=None)
     ap.add_argument("--k-l", type=float, default=None, help="fraction of negligible blocks (changes the density of the linear branch's marginal blocks)")
-    ap.add_argument("--dense-steps", type=int, default=1, help="0 skips the dense reference run")
+    ap.add_argument("--dense-steps", type=int, default=5, help="timed iterations of the dense reference run (after one warm-up); 0 skips it")
+    ap.add_argument("--sub-runs", default="sweep,long",
+                    help="bounded extra runs whose results ride in the same JSON line: 'sweep' = k_h 2.5 / 10 / 20 %% on the "
+                         "same layer, 'long' = the 40-head N = 75600 layer; '' or 'none' skips them (default workload only)")
     ap.add_argument("--cpu-heads", type=int, default=4, help="0 skips the CPU oracle baseline")
     ap.add_argument("--settle-ms", type=float, default=200.0,
                     help="before the warm-up steps, run untimed steps for this long so that the GPU's clock "
@@ -119,16 +122,27 @@ def main() -> int:
                              out=b["out"])
         return mask, fwd, bwd
 
-    def timed(fn, n):
+    def timed_all(fn, n):
+        """n iterations bracketed by synchronisations; one event between consecutive iterations.
+        Returns (host ms per iteration, event ms per iteration over the whole region, per-iteration ms)."""
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
         t = time.perf_counter()
-        e0.record()
-        for _ in range(n):
+        ev[0].record()
+        for k in range(n):
             fn()
-        e1.record()
+            ev[k + 1].record()
         torch.cuda.synchronize()
-        return (time.perf_counter() - t) * 1e3 / n, e0.elapsed_time(e1) / n
+        host = (time.perf_counter() - t) * 1e3 / n
+        return host, ev[0].elapsed_time(ev[n]) / n, [ev[k].elapsed_time(ev[k + 1]) for k in range(n)]
+
+    def timed(fn, n):
+        h, e, _ = timed_all(fn, n)
+        return h, e
+
+    def spread(per):
+        return {"mean": float(np.mean(per)), "median": float(np.median(per)), "min": float(np.min(per)),
+                "max": float(np.max(per))}
 
     if args.calib_copy_mib > 0:
         src = torch.ones(args.calib_copy_mib << 18, dtype=torch.float32, device="cuda")
@@ -153,10 +167,11 @@ def main() -> int:
             settle_steps += 1
     for _ in range(args.warmup):
         step()
-    ms_step, ms_step_ev = timed(step, args.steps)
-    ms_mask = timed(mask, args.steps)[1]
-    ms_fwd = timed(fwd, args.steps)[1]
-    ms_bwd = timed(bwd, args.steps)[1]
+    ms_step, ms_step_ev, per_step = timed_all(step, args.steps)
+    _, ms_mask, per_mask = timed_all(mask, args.steps)
+    _, ms_fwd, per_fwd = timed_all(fwd, args.steps)
+    _, ms_bwd, per_bwd = timed_all(bwd, args.steps)
+    peak_measured = sla.sla_profile_mfma_peak(4096)
 
     # per-kernel durations (events inside the library, on the same stream)
     sla.sla_profile_enable(True)
@@ -200,9 +215,17 @@ def main() -> int:
     if roof is not None and args.bq == 64:
         tpath = os.path.join(ROOT, "profiles", f"pmc_traffic_{roof['kernel']}_{w.name}.txt")
         if os.path.exists(tpath):
+            src = {"file": os.path.relpath(tpath, ROOT)}
             for line in open(tpath):
                 if line.startswith("traffic_bytes_per_launch:"):
                     roof["traffic"] = float(line.split(":")[1])
+                if line.startswith("collected_at_commit:"):
+                    src["collected_at_commit"] = line.split(":")[1].strip()
+            roof["traffic_source"] = src
+    if roof is not None:
+        roof["peak_measured"] = peak_measured
+        if roof["bound"] == "mfma":
+            roof["frac_of_measured_peak"] = roof["achieved"] / peak_measured
 
     # dense reference on the same GPU: the same library with every block critical
     dense = None
@@ -210,10 +233,12 @@ def main() -> int:
         pd = sla.make_params(w.B, w.H, w.N, w.d, 1.0, 0.0, tdt, layout=lay)
         bd = buffers(pd)
         dm, df, db = phases(pd, bd)
-        dm(); torch.cuda.synchronize()
-        dfw = timed(df, args.dense_steps)[1]
-        dbw = timed(db, args.dense_steps)[1]
-        dense = {"fwd_ms": dfw, "bwd_ms": dbw, "fwd_tflops": d_fwd / dfw / 1e9,
+        dm(); df(); db(); torch.cuda.synchronize()      # one warm-up iteration
+        _, dfw, per_df = timed_all(df, args.dense_steps)
+        _, dbw, per_db = timed_all(db, args.dense_steps)
+        dense = {"iterations": args.dense_steps, "fwd_ms": dfw, "bwd_ms": dbw,
+                 "fwd_ms_spread": spread(per_df), "bwd_ms_spread": spread(per_db),
+                 "fwd_tflops": d_fwd / dfw / 1e9,
                  "bwd_tflops": d_bwd / dbw / 1e9, "speedup_fwd": dfw / ms_fwd,
                  "speedup_bwd": dbw / ms_bwd, "speedup_fwd_bwd": (dfw + dbw) / (ms_fwd + ms_bwd)}
         del bd
@@ -249,10 +274,61 @@ def main() -> int:
         sec = time.perf_counter() - t
         sf, sb = fl.executed_flops(Mo, w.N, w.d, bq=args.bq)
         cpu = {"value": (sf + sb) / sec / 1e12, "unit": "TFLOP/s", "cores": len(hs) * w.B,
-               "kind": "oracle", "seconds": sec,
+               "kind": "oracle", "seconds": sec, "nproc": os.cpu_count(),
+               "OMP_NUM_THREADS": os.environ.get("OMP_NUM_THREADS"),
                "sample": f"heads 0..{len(hs) - 1} of {w.H} (mask + forward + backward, float), "
                          f"one thread per head; full workload would take ~{sec * w.H / len(hs):.0f} s "
                          f"on {len(hs)} threads"}
+
+    # bounded sub-runs on the other configurations (their own buffers; the default workload's are freed first)
+    subs = [t for t in args.sub_runs.split(",") if t and t != "none"] if args.workload == "wan" and args.k_h is None else []
+    sweep_res, long_res = None, None
+
+    def sub_run(ws_, Qs, Ks, Vs, Ws, dOs, n_warm, n_steps):
+        ps = sla.make_params(ws_.B, ws_.H, ws_.N, ws_.d, ws_.k_h, ws_.k_l, tdt)
+        zs = sla.sla_sizes(ps)
+        u8 = lambda n: torch.empty(max(int(n), 256), dtype=torch.uint8, device="cuda")
+        bs = dict(Mc=torch.empty((ps.B, ps.H, zs.Tq, zs.T), dtype=torch.int8, device="cuda"), luts=u8(zs.luts_bytes),
+                  ws_m=u8(zs.ws_mask_bytes), ws_f=u8(zs.ws_forward_bytes), ws_b=u8(zs.ws_backward_bytes),
+                  saved=u8(zs.saved_bytes), O=torch.empty_like(Qs),
+                  out=(torch.empty_like(Qs), torch.empty_like(Ks), torch.empty_like(Vs),
+                       torch.empty((ps.d, ps.d), dtype=torch.float32, device="cuda")))
+        def m_(): sla.sla_build_mask(ps, Qs, Ks, workspace=bs["ws_m"], Mc=bs["Mc"], luts=bs["luts"])
+        def f_(): sla.sla_forward(ps, Qs, Ks, Vs, Ws, bs["Mc"], bs["luts"], O=bs["O"], saved=bs["saved"], workspace=bs["ws_f"])
+        def b_(): sla.sla_backward(ps, Qs, Ks, Vs, Ws, bs["Mc"], bs["luts"], bs["saved"], dOs, workspace=bs["ws_b"], out=bs["out"])
+        def st_():
+            m_(); f_(); b_()
+        for _ in range(n_warm):
+            st_()
+        _, ms_s, per_s = timed_all(st_, n_steps)
+        _, ms_f = timed(f_, n_steps)
+        _, ms_b = timed(b_, n_steps)
+        ff, fb = fl.executed_flops(bs["Mc"].cpu().numpy(), ws_.N, ws_.d)
+        return {"k_h": ws_.k_h, "n_h": zs.n_h, "steps": n_steps, "ms_per_step": ms_s, "ms_per_step_spread": spread(per_s),
+                "forward_ms": ms_f, "backward_ms": ms_b, "executed_tflop": (ff + fb) / 1e12,
+                "tflops_step": (ff + fb) / ms_s / 1e9, "tflops_forward": ff / ms_f / 1e9,
+                "tflops_backward": fb / ms_b / 1e9,
+                "frac_of_bf16_peak_excl_mask": (ff + fb) / (ms_f + ms_b) / 1e9 / PEAK_BF16_TFLOPS}
+
+    if "sweep" in subs and not args.token_major and args.bq == 64:
+        sweep_res = {}
+        for kh in (0.025, 0.10, 0.20):
+            sweep_res[f"k_h={kh:g}"] = sub_run(wl.sweep(kh), Q, K, V, W, dO, 2, 5)
+            if dense is not None:
+                r_ = sweep_res[f"k_h={kh:g}"]
+                r_["speedup_fwd_bwd_vs_dense"] = (dense["fwd_ms"] + dense["bwd_ms"]) / (r_["forward_ms"] + r_["backward_ms"])
+    if "long" in subs:
+        del b, Q, K, V, dO, dev
+        torch.cuda.empty_cache()
+        wlng = wl.WORKLOADS["long"]
+        t1 = time.time()
+        xl = wl.make_inputs(wlng)
+        dl = {k: torch.from_numpy(v).to(tdt).cuda() for k, v in xl.items()}
+        del xl
+        long_res = sub_run(wlng, dl["Q"], dl["K"], dl["V"], dl["Proj"], dl["dO"], 1, 3)
+        long_res["workload"] = f"long: B={wlng.B} H={wlng.H} d={wlng.d} N={wlng.N} grid={wlng.grid} k_h={wlng.k_h} k_l={wlng.k_l}"
+        long_res["input_gen_s"] = time.time() - t1
+        del dl
 
     out = {
         "metric": "SLA fwd+bwd executed TFLOPS on critical blocks (mask + forward + backward per step)",
@@ -265,12 +341,18 @@ def main() -> int:
                                f"k_h={w.k_h} k_l={w.k_l} phi=softmax; n_h={z.n_h} n_l={z.n_l} "
                                f"n_0={z.n_0}; seeded Fourier-feature Q/K/V stand in for Wan2.1 activations"},
         "ms": {"step_wall": ms_step, "mask": ms_mask, "forward": ms_fwd, "backward": ms_bwd},
+        "ms_spread": {"step": spread(per_step), "mask": spread(per_mask), "forward": spread(per_fwd),
+                      "backward": spread(per_bwd)},
+        "mfma_peak_tflops": {"nominal": PEAK_BF16_TFLOPS, "measured_register_only_loop": peak_measured},
         "executed_tflop": {"forward": f_fwd / 1e12, "backward": f_bwd / 1e12},
         "tflops": {"forward": f_fwd / ms_fwd / 1e9, "backward": f_bwd / ms_bwd / 1e9,
                    "fwd_bwd_excl_mask": (f_fwd + f_bwd) / (ms_fwd + ms_bwd) / 1e9,
                    "frac_of_bf16_peak_excl_mask": (f_fwd + f_bwd) / (ms_fwd + ms_bwd) / 1e9 / PEAK_BF16_TFLOPS,
+                   "frac_of_measured_peak_excl_mask": (f_fwd + f_bwd) / (ms_fwd + ms_bwd) / 1e9 / peak_measured,
                    "paper_style_effective_fwd_bwd": (d_fwd + d_bwd) / (ms_fwd + ms_bwd) / 1e9},
         "dense_reference": dense,
+        "sweep": sweep_res,
+        "long": long_res,
         "kernels": kernels,
         "roofline": roof,
         "cpu_baseline": cpu,

@@ -174,6 +174,13 @@ int sla_aggregate_states(const sla_params* p, int method, const void* luts, cons
 int sla_profile_enable(int on);
 int sla_profile_read(char* buf, size_t buf_bytes);
 
+/* Measured matrix-core peak of the device at hand, for the benchmark's roofline: runs a
+ * register-only loop of `iters` x 4 independent v_mfma_f32_32x32x16_bf16 per wave on every
+ * compute unit (8 waves per SIMD), times it with HIP events on `stream`, WAITS for it, and writes
+ * the sustained rate in TFLOP/s to *tflops (a host pointer).  iters in [1, 2^20]; 4096 runs about
+ * 2 ms.  The nominal figure the roofline is priced against is 2500 (dense bf16). */
+int sla_profile_mfma_peak(int iters, double* tflops, void* stream);
+
 /* Static description of an error code. */
 const char* sla_strerror(int code);
 

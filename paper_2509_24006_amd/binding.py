@@ -23,7 +23,7 @@ SLA_AGG_GEMM, SLA_AGG_ADD, SLA_AGG_PREAGG, SLA_AGG_FOUR_RUSSIANS = 0, 1, 2, 3
 SLA_STATIC_WS_BYTES = 32 << 20
 EXPORTS = ("sla_sizes", "sla_build_mask", "sla_build_mask_static", "sla_classify_scores", "sla_forward", "sla_backward",
            "sla_aggregate_ws_bytes", "sla_aggregate_states",
-           "sla_profile_enable", "sla_profile_read", "sla_strerror")
+           "sla_profile_enable", "sla_profile_read", "sla_profile_mfma_peak", "sla_strerror")
 
 
 class sla_params(ctypes.Structure):
@@ -70,6 +70,7 @@ def lib() -> ctypes.CDLL:
         L.sla_aggregate_states.argtypes = [pp, ctypes.c_int, vp, vp, vp, vp, vp, sz, vp]
         L.sla_profile_enable.argtypes = [ctypes.c_int]
         L.sla_profile_read.argtypes = [ctypes.c_char_p, sz]
+        L.sla_profile_mfma_peak.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_double), vp]
         L.sla_strerror.argtypes = [ctypes.c_int]
         L.sla_strerror.restype = ctypes.c_char_p
         for n in EXPORTS[:-1]:
@@ -278,6 +279,13 @@ def sla_aggregate_states(p: sla_params, method: int, luts: torch.Tensor, h: torc
 
 def sla_profile_enable(on: bool) -> None:
     _check(lib().sla_profile_enable(1 if on else 0), "sla_profile_enable")
+
+
+def sla_profile_mfma_peak(iters: int = 4096) -> float:
+    """Sustained TFLOP/s of a register-only bf16 MFMA loop on this device (waits for it)."""
+    out = ctypes.c_double()
+    _check(lib().sla_profile_mfma_peak(iters, ctypes.byref(out), _stream()), "sla_profile_mfma_peak")
+    return out.value
 
 
 def sla_profile_read() -> Dict[str, Tuple[int, float]]:

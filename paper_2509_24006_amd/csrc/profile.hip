@@ -10,7 +10,7 @@
 #include <vector>
 
 #include "../../include/sla.h"
-#include "sla_internal.h"
+#include "mfma_common.h"
 
 namespace sla {
 namespace {
@@ -54,7 +54,59 @@ KernelTimer::~KernelTimer() {
 }
 }  // namespace sla
 
+namespace sla {
+namespace {
+// Register-only matrix-core loop: four independent accumulator chains of v_mfma_f32_32x32x16_bf16
+// per wave, no memory traffic.  What this sustains is the rate the sparse kernels' matrix products
+// could reach at best on the device at hand (clock and power limits included).
+__global__ __launch_bounds__(256) void mfma_peak_kernel(int iters, float* __restrict__ sink) {
+  bf16x8 a, b;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    a[e] = (__bf16)(float)((threadIdx.x + e) & 3);
+    b[e] = (__bf16)(float)((threadIdx.x * 3 + e) & 1);
+  }
+  f32x16 c0 = zero_f32x16(), c1 = zero_f32x16(), c2 = zero_f32x16(), c3 = zero_f32x16();
+  for (int i = 0; i < iters; ++i) {
+    c0 = mfma32(a, b, c0);
+    c1 = mfma32(a, b, c1);
+    c2 = mfma32(a, b, c2);
+    c3 = mfma32(a, b, c3);
+  }
+  float t = 0.0f;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) t += c0[r] + c1[r] + c2[r] + c3[r];
+  if (t == -1.0f) sink[blockIdx.x * 256 + threadIdx.x] = t;   // never true: keeps the loop alive
+}
+}  // namespace
+}  // namespace sla
+
 extern "C" {
+
+int sla_profile_mfma_peak(int iters, double* tflops, void* stream) {
+  if (!tflops || iters <= 0 || iters > (1 << 20)) return SLA_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  hipEvent_t a, b;
+  if (hipEventCreate(&a) != hipSuccess) return SLA_EHIP;
+  if (hipEventCreate(&b) != hipSuccess) {
+    (void)hipEventDestroy(a);
+    return SLA_EHIP;
+  }
+  constexpr int kGroups = 2048;   // 8 workgroups of 4 waves per compute unit: 8 waves per SIMD
+  int rc = SLA_OK;
+  float ms = 0.0f;
+  sla::mfma_peak_kernel<<<kGroups, 256, 0, st>>>(iters / 8 + 1, nullptr);   // warm-up launch
+  (void)hipEventRecord(a, st);
+  sla::mfma_peak_kernel<<<kGroups, 256, 0, st>>>(iters, nullptr);
+  (void)hipEventRecord(b, st);
+  if (hipGetLastError() != hipSuccess || hipEventSynchronize(b) != hipSuccess ||
+      hipEventElapsedTime(&ms, a, b) != hipSuccess || ms <= 0.0f)
+    rc = SLA_EHIP;
+  (void)hipEventDestroy(a);
+  (void)hipEventDestroy(b);
+  if (rc == SLA_OK) *tflops = (double)kGroups * 4.0 * iters * 4.0 * (2.0 * 32 * 32 * 16) / (ms * 1e-3) / 1e12;
+  return rc;
+}
 
 int sla_profile_enable(int on) {
   std::lock_guard<std::mutex> lk(sla::g_mu);

@@ -831,14 +831,15 @@ BwdWs carve_bwd(const Shape& s, char* ws) {
   const size_t nd = (size_t)s.BH * s.N * s.d, n = (size_t)s.BH * s.N;
   const size_t st = (size_t)s.BH * s.T * s.state_row();
   w.nparts = s.BH * s.T < 512 ? s.BH * s.T : 512;   // two workgroups per CU
-  w.dOl = take(nd);
+  const bool simt = s.dtype == 0;   // the matrix-core path has no dO^l, D^l, dK, dV round trips
+  w.dOl = take(simt ? nd : 0);
   w.Ds = take(n);
-  w.Dl = take(n);
+  w.Dl = take(simt ? n : 0);
   w.dHZ = take(st);
   w.dHZcol = take(st);
   w.dQlin = take(nd);
-  w.dKlin = take(nd);
-  w.dVlin = take(nd);
+  w.dKlin = take(simt ? nd : 0);
+  w.dVlin = take(simt ? nd : 0);
   w.dWpart = take((size_t)w.nparts * s.d * s.d);
   w.bytes = off;
   return w;

@@ -188,6 +188,29 @@ def test_many_long_heads(oracle):
     _full_case(oracle, x, "bf16", 0.05, 0.10)
 
 
+@pytest.mark.timeout(300)
+@pytest.mark.parametrize("T,d,tail", [(150, 128, 23), (128, 64, 0), (200, 64, 63)])
+def test_key_blocks_that_nearly_every_query_block_selects(oracle, T, d, tail):
+    # a few key blocks whose pooled key points along the direction shared by every query: their
+    # column lists hold (nearly) all T query tiles, so the column-wise backward kernel walks them in
+    # the longest walks the kernel can be given (its launch order puts them first)
+    N = 64 * T - tail
+    rng = np.random.default_rng(T + d)
+    u = rng.standard_normal(d).astype(np.float32)
+    u /= np.linalg.norm(u)
+    x = {k: rng.standard_normal((1, 2, N, d)).astype(np.float32) for k in ("Q", "K", "V", "dO")}
+    x["Q"] += 1.5 * u
+    hot = [3, 4, T // 2, T - 1]
+    for j in hot:
+        x["K"][:, :, 64 * j:64 * (j + 1)] += 4.0 * u
+    x["Proj"] = (rng.standard_normal((d, d)) * 0.05).astype(np.float32)
+    x = {k: wl.round_to_bf16(v) for k, v in x.items()}
+    Mc = oracle.build_mask(x["Q"], x["K"], 0.08, 0.2)
+    cnt = (Mc == 1).sum(-2)
+    assert (cnt[0, :, hot] >= T - 2).all() and (cnt >= 64).sum() >= 2 * len(hot)
+    _full_case(oracle, x, "bf16", 0.08, 0.2)
+
+
 @pytest.mark.parametrize("name", ["small_bf16", "small_bf16_d64", "small_fp32"])
 def test_token_major_tensors(oracle, name):
     # [B,N,H,d] tensors: the same kernels walk the same values with another row pitch, so every
