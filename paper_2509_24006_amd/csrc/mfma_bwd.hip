@@ -29,6 +29,8 @@ struct PairLds {
   static constexpr int SP = D + 4;                        // row pitch (floats) of the output staging
   static constexpr int STAGE = 2 * kBlk * SP * 4;         // [dV | dK][64][SP] floats (dK/dV kernel)
   static constexpr int DKDV = BYTES + VPARK > STAGE ? BYTES + VPARK : STAGE;
+  // the second group of an eight-wave dQ workgroup: its Q_i, dO_i tiles, later its output staging
+  static constexpr int GROUP = (kBlk * SP * 4 > BUF ? kBlk * SP * 4 : BUF);
 };
 
 // ------------------------------------------------------------------ dK, dV
@@ -389,8 +391,12 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
 // Wave (qh, kh): S^T and dP^T are [key][query], one query per lane, so L and D^s are per-lane
 // scalars and dS^T feeds dQ^T = K^T dS^T from registers.  The two kh waves hold partial sums
 // over their keys and are added at the end.
-template <int D>
-__global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(
+// QT = 2 (query blocks of 128 or 256 tokens): two adjacent 64-query tiles, which walk the same
+// list of key blocks, share a workgroup of eight waves and every K_j, V_j tile it fetches; each
+// group of four waves has an LDS area of its own for its Q_i, dO_i tiles and its output staging
+// (the second group's lies behind the pair buffers).
+template <int D, int QT>
+__global__ __launch_bounds__(256 * QT, QT == 1 ? 2 : 1) void bwd_dq_mfma_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
     const bf16* __restrict__ dO, const float* __restrict__ L, const float* __restrict__ Ds,
     const int32_t* __restrict__ row_idx, const float* __restrict__ dQlin, int N, int Tn, Lay lay, int n_h,
@@ -399,18 +405,27 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(
   using T = SwzTile<D>;
   constexpr int NT = D / 32, KT = D / 16;
   constexpr int RB = 16 * T::ROW_BYTES;
+  constexpr int NW = 4 * QT;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
+  const int wall = threadIdx.x >> 6, l = threadIdx.x & 63, g = l >> 5, ln = l & 31;
+  const int grp = QT == 1 ? 0 : wave_uniform(wall >> 2), w = wall & 3, tid = threadIdx.x & 255;
   const int qh = w & 1, kh = w >> 1;
-  const int i = xcd_local_block(blockIdx.x, Tn), bh = blockIdx.y;
-  if (i < 0) return;
-  const int q0 = i * kBlk, rows = min(kBlk, N - q0);
+  const int ib = xcd_local_block(blockIdx.x, (Tn + QT - 1) / QT), bh = blockIdx.y;
+  if (ib < 0) return;
+  // (a last block of a single tile: the second group runs along with no valid query and stores nothing)
+  const int i = QT * ib + grp;
+  // group 0 takes Q_i, dO_i in through the second pair buffer and stages its output over the pair
+  // buffers; group 1 has DqLds<D>::GROUP bytes behind them for both
+  unsigned char* gsm = smem + (grp ? Lds::BYTES - Lds::BUF : 0);
+  const int q0 = i * kBlk, rows = max(0, min(kBlk, N - q0));
   const int qrow = qh * 32 + ln;
   const bool qok = qrow < rows;
-  const int32_t* lut = row_idx + ((size_t)bh * Tn + i) * n_h;
+  const int32_t* lut = row_idx + ((size_t)bh * Tn + QT * ib) * n_h;   // the same list for every tile of the block
   const float sl2 = scale * kLog2e;
-  TileLoader<D> tl;
-  tl.init(lds_base(smem), w, l, 2 * lay.ts);
+  TileLoader<D, NW> tl;   // K_j, V_j: all waves of the workgroup
+  TileLoader<D> tq;       // Q_i, dO_i: the four waves of a group, into the group's area
+  tl.init(lds_base(smem), wall, l, 2 * lay.ts);
+  tq.init(lds_base(smem) + (grp ? Lds::BYTES - Lds::BUF : 0), w, l, 2 * lay.ts);
   const BufDesc descK = head_rsrc<D>(K + lay.head(bh), N, 2 * lay.ts);
   const BufDesc descV = head_rsrc<D>(V + lay.head(bh), N, 2 * lay.ts);
   // key block indices of steps s, s + 1, s + 2, fetched a step before the loads that need them
@@ -422,8 +437,9 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(
   // Q_i and dO_i come in as tiles through the second pair buffer (whole rows per load, zeros past
   // the end of the sequence) and are picked up from there in operand layout
   {
-    tl.load(head_rsrc<D>(Q + lay.head(bh), N, 2 * lay.ts), i, Lds::BUF);
-    tl.load(head_rsrc<D>(dO + lay.head(bh), N, 2 * lay.ts), i, Lds::BUF + Lds::TILE);
+    const int it = min(i, Tn - 1);
+    tq.load(head_rsrc<D>(Q + lay.head(bh), N, 2 * lay.ts), it, Lds::BUF);
+    tq.load(head_rsrc<D>(dO + lay.head(bh), N, 2 * lay.ts), it, Lds::BUF + Lds::TILE);
   }
   if (n_h > 0) {
     j0 = lut[0];
@@ -444,8 +460,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(
     qa.init(32 * qh, l);
 #pragma unroll
     for (int t = 0; t < KT; ++t) {
-      qf[t] = lds_row(smem, qa.row(t) + Lds::BUF);
-      gf[t] = lds_row(smem, qa.row(t) + Lds::BUF + Lds::TILE);
+      qf[t] = lds_row(gsm, qa.row(t) + Lds::BUF);
+      gf[t] = lds_row(gsm, qa.row(t) + Lds::BUF + Lds::TILE);
     }
   }
 #pragma unroll
@@ -524,7 +540,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(
   }
   __syncthreads();   // every wave is done with the tiles
   constexpr int SP = Lds::SP;
-  float* stg = reinterpret_cast<float*>(smem);   // [64 queries][SP]
+  float* stg = reinterpret_cast<float*>(grp ? gsm + Lds::BUF : smem);   // [64 queries][SP]
   const int srow = qrow * SP + 4 * g;
   if (kh == 1) {
 #pragma unroll
@@ -580,13 +596,18 @@ hipError_t sparse_impl(const Shape& s, const BwdArgs& a, const float* Ds, const 
     return hipSuccess;
   };
   SLA_TRY(s.phi == 0 ? launch_kv(bwd_dkdv_mfma_kernel<D, 0>) : launch_kv(bwd_dkdv_mfma_kernel<D, 1>));
-  SLA_TRY(ensure_dyn_lds(bwd_dq_mfma_kernel<D>, lds));
-  {
+  auto launch_q = [&](auto kern, int qt) -> hipError_t {
+    const int bytes = lds + (qt - 1) * PairLds<D>::GROUP;
+    SLA_TRY(ensure_dyn_lds(kern, bytes));
     KernelTimer kt("bwd_sparse_q", st);
-    bwd_dq_mfma_kernel<D><<<dim3(xcd_grid(s.T), s.BH), 256, lds, st>>>(
+    kern<<<dim3(xcd_grid((s.T + qt - 1) / qt), s.BH), 256 * qt, bytes, st>>>(
         (const bf16*)a.Q, (const bf16*)a.K, (const bf16*)a.V, (const bf16*)a.dO, a.L, Ds, a.row_idx,
         dQlin, s.N, s.T, s.lay(), s.n_h, s.scale, (bf16*)a.dQ);
-  }
+    return hipSuccess;
+  };
+  // query blocks of an even number of tiles: tiles 2k and 2k + 1 have the same list
+  if (s.rq % 2 == 0) SLA_TRY(launch_q(bwd_dq_mfma_kernel<D, 2>, 2));
+  else SLA_TRY(launch_q(bwd_dq_mfma_kernel<D, 1>, 1));
   return hipGetLastError();
 }
 

@@ -317,25 +317,27 @@ template <int D>
 __device__ __forceinline__ BufDesc head_rsrc(const bf16* head_base, int N, int tsB) {
   return tile_rsrc(head_base, (N - 1) * tsB + 2 * D);
 }
-template <int D>
+template <int D, int NW = 4>
 struct TileLoader {
   using T = SwzTile<D>;
+  static constexpr int IPW = kBlk / T::RPI / NW;   // loads per wave (NW waves share a tile)
   int ldv;        // this lane's byte offset inside a tile's memory image
   int kstep;      // bytes between the rows of two consecutive loads of a wave
   unsigned ldsw;  // LDS address of this wave's first KB of the tile at LDS offset 0
   int tile_step;  // bytes between consecutive 64-row tiles
+  // w: this wave's index among the NW waves that fill a tile together
   __device__ __forceinline__ void init(unsigned lds_base_addr, int w, int l, int tsB) {
     const int row = T::RPI * w + l / T::CPR;
     ldv = row * tsB + (((l % T::CPR) ^ swz<D>(row)) << 4);
-    kstep = 4 * T::RPI * tsB;
+    kstep = NW * T::RPI * tsB;
     tile_step = kBlk * tsB;
     ldsw = lds_base_addr + __builtin_amdgcn_readfirstlane(w) * 1024;
   }
   // tile number `tile` of the head behind desc -> LDS offset lds_tile
   __device__ __forceinline__ void load(BufDesc desc, int tile, int lds_tile) const {
 #pragma unroll
-    for (int k = 0; k < T::IPW; ++k)
-      load_to_lds16(desc, ldv, tile * tile_step + k * kstep, ldsw + lds_tile + 4096 * k);
+    for (int k = 0; k < IPW; ++k)
+      load_to_lds16(desc, ldv, tile * tile_step + k * kstep, ldsw + lds_tile + 1024 * NW * k);
   }
 };
 

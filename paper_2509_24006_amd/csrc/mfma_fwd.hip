@@ -149,9 +149,14 @@ struct FwdLds {
   static_assert(XCH_HALF <= TILE && 1024 <= TILE, "exchange areas are laid over tile slots");
   static constexpr int BYTES = 5 * TILE;
 };
+// Query blocks of 128 (or 256) tokens: QT = 2 adjacent 64-query tiles, which have the same list of
+// critical key blocks, share one workgroup of eight waves.  K_j and V_j are then fetched into LDS
+// once for both tiles (half the L2 -> LDS traffic and half the load instructions per score); each
+// group of four waves works on its tile exactly as a four-wave workgroup does, and has an LDS area
+// of its own (the second group's lies behind the ring) for what follows the loop.
 
-template <int D>
-__global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
+template <int D, int QT>
+__global__ __launch_bounds__(256 * QT, QT == 1 ? 2 : 1) void fwd_mfma_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
     const bf16* __restrict__ WTp, const int32_t* __restrict__ row_idx, const bf16* __restrict__ H16,
     const float* __restrict__ Zs,
@@ -159,12 +164,18 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
     bf16* __restrict__ Os, bf16* __restrict__ Ol, float* __restrict__ L) {
   using Lds = FwdLds<D>;
   constexpr int NT = D / 32, KT = D / 16;
+  constexpr int NW = 4 * QT;   // waves that fill a K or V tile together
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
+  const int tid = threadIdx.x, wall = tid >> 6, l = tid & 63, g = l >> 5, ln = l & 31;
+  const int grp = QT == 1 ? 0 : wave_uniform(wall >> 2), w = wall & 3;   // tile of the workgroup, wave of the tile
   const int qh = w & 1, par = w >> 1;
-  const int i = xcd_local_block(blockIdx.x, Tn), bh = blockIdx.y;
-  if (i < 0) return;
-  const int q0 = i * kBlk, rows = min(kBlk, N - q0);
+  const int ib = xcd_local_block(blockIdx.x, (Tn + QT - 1) / QT), bh = blockIdx.y;
+  if (ib < 0) return;
+  // a last block of a single tile: the second group runs along (it shares the tile loads and the
+  // barriers) on the last tile's tables with no valid query, and stores nothing
+  const int i = QT * ib + grp, ic = min(i, Tn - 1);
+  unsigned char* gsm = smem + grp * Lds::BYTES;   // this group's area for everything behind the loop
+  const int q0 = i * kBlk, rows = max(0, min(kBlk, N - q0));
   const int qrow = qh * 32 + ln;                  // this lane's query inside the block
   const bool qok = qrow < rows;
   const size_t qoff = lay.head(bh) + (size_t)(q0 + qrow) * lay.ts;
@@ -176,12 +187,14 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
 #pragma unroll
   for (int et = 0; et < NT; ++et) oT[et] = zero_f32x16();
   float m = -INFINITY, lsum = 0.0f;
-  const int32_t* lut = row_idx + ((size_t)bh * Tn + i) * n_h;
+  const int32_t* lut = row_idx + ((size_t)bh * Tn + QT * ib) * n_h;   // the same list for every tile of the block
   const float c2 = scale_log2e;                    // exp(x / sqrt(d)) = exp2(x * c2)
   using T = SwzTile<D>;
-  TileLoader<D> tl, tm;   // tiles of the caller's K and V; packed d x d matrices
-  tl.init(lds_base(smem), w, l, 2 * lay.ts);
-  tm.init(lds_base(smem), w, l, 2 * D);
+  TileLoader<D, NW> tl;   // tiles of the caller's K and V: all waves of the workgroup, into the ring
+  TileLoader<D> tm;       // packed d x d matrices: the four waves of a group, into the group's area
+  tl.init(lds_base(smem), wall, l, 2 * lay.ts);
+  tm.init(lds_base(smem) + grp * Lds::BYTES, w, l, 2 * D);
+  constexpr int IPW = TileLoader<D, NW>::IPW;
   const BufDesc descK = head_rsrc<D>(K + lay.head(bh), N, 2 * lay.ts);
   const BufDesc descV = head_rsrc<D>(V + lay.head(bh), N, 2 * lay.ts);
   // K (v = 0) or V (v = 1) tile of key block jj into a slot; the loads go K_0 V_0 K_1 V_1 ... and
@@ -194,14 +207,14 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
     tm.load(dm, 0, off0);
     if (D > kBlk) tm.load(dm, 1, off1);
   };
-  const bf16* Hrow = H16 + ((size_t)bh * Tn + i) * (D * D);
+  const bf16* Hrow = H16 + ((size_t)bh * Tn + ic) * (D * D);
   // Slots at the end of the loop, with b the slot of the last K tile: H_i goes to b and b + 4
   // (free from the middle of the last step), b + 1 holds the last V tile and b + 2, b + 3 were
   // never refilled.  The statistics are written while slower waves may still read V: slot b + 2.
   const int bslot = n_h > 0 ? (2 * (n_h - 1)) % 5 : 0;
   const int h0 = bslot * Lds::TILE, h1 = ((bslot + 4) % 5) * Lds::TILE;
   const int x1 = ((bslot + 1) % 5) * Lds::TILE, x0 = ((bslot + 3) % 5) * Lds::TILE;
-  float* ml = reinterpret_cast<float*>(smem + ((bslot + 2) % 5) * Lds::TILE);   // [par][qh][32][2]
+  float* ml = reinterpret_cast<float*>(gsm + ((bslot + 2) % 5) * Lds::TILE);   // [par][qh][32][2]
   const int nloads = 2 * n_h;
   // key block indices of steps s, s + 1, s + 2: fetched a step before the loads that need them,
   // so that no wave ever waits for a table entry between a barrier and its loads
@@ -229,7 +242,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
   // of the current step: S_0 here, S_{s+1} inside step s.
   f32x16 sT = zero_f32x16();
   if (n_h > 0) {
-    if (n_h > 1) wait_vm<3 * T::IPW>();   // K_0 has landed; V_0, K_1, V_1 may stay in flight
+    if (n_h > 1) wait_vm<3 * IPW>();   // K_0 has landed; V_0, K_1, V_1 may stay in flight
     else wait_vm0();
     __syncthreads();
 #pragma unroll
@@ -240,7 +253,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
     const int cols = min(kBlk, N - j0 * kBlk);
     const int j3 = lut[min(s + 3, n_h - 1)];   // needed in the next step
     // V_s and K_{s+1} have landed; the load issued after them (V_{s+1}) may stay in flight
-    if (s + 2 <= n_h) wait_vm<T::IPW>();
+    if (s + 2 <= n_h) wait_vm<IPW>();
     else wait_vm0();
     __syncthreads();   // ... for every wave; K_s and V_{s-1} are fully consumed: their slots are refilled
     if (2 * s + 4 < nloads) {   // K_{s+2}, V_{s+2} into the slots of V_{s-1} and K_s
@@ -342,7 +355,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
   for (int et = 0; et < NT; ++et)
 #pragma unroll
     for (int r = 0; r < 16; ++r) oT[et][r] *= cw;
-  float* myx = reinterpret_cast<float*>(smem + (qh ? x1 : x0));   // exchange, then this query half's staging
+  float* myx = reinterpret_cast<float*>(gsm + (qh ? x1 : x0));   // exchange, then this query half's staging
   unsigned char* mystage = reinterpret_cast<unsigned char*>(myx);
   if (par == 1) {
 #pragma unroll
@@ -379,7 +392,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
     // phi(Q) of this lane's query: the lane holds features 16 t + 8 g + s, its partner the rest
     float qmx, qinv;
     phi_stats<KT>(qf, phi, qmx, qinv);
-    const float* Z = Zs + ((size_t)bh * Tn + i) * D;
+    const float* Z = Zs + ((size_t)bh * Tn + ic) * D;
     bf16x8 qp[KT];
     float den = 0.0f;
 #pragma unroll
@@ -405,7 +418,7 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
       ol[h2] = zero_f32x16();
 #pragma unroll
       for (int t = 0; t < KT; ++t)
-        ol[h2] = mfma32(lds_row(smem, ma.row(t) + (et / 2 ? h1 : h0) + (et % 2) * 2 * RB), qp[t], ol[h2]);
+        ol[h2] = mfma32(lds_row(gsm, ma.row(t) + (et / 2 ? h1 : h0) + (et % 2) * 2 * RB), qp[t], ol[h2]);
 #pragma unroll
       for (int r = 0; r < 16; ++r) ol[h2][r] *= dinv;
     }
@@ -420,11 +433,11 @@ __global__ __launch_bounds__(256, 2) void fwd_mfma_kernel(
         const bf16x8 b = c_to_operand(ol[h2], u);
 #pragma unroll
         for (int ep = 0; ep < NT; ++ep)
-          oT[ep] = mfma32(lds_row(smem, ma.row(2 * et + u) + (ep / 2 ? x1 : x0) + (ep % 2) * 2 * RB), b, oT[ep]);
+          oT[ep] = mfma32(lds_row(gsm, ma.row(2 * et + u) + (ep / 2 ? x1 : x0) + (ep % 2) * 2 * RB), b, oT[ep]);
       }
     }
     if (Ol)
-      store_rows_bf16<HT>(smem + (w < 2 ? h0 : h1) + (w & 1) * (32 * (64 * HT + 16)), ol, Ol + orow0 + par * (D / 2), D,
+      store_rows_bf16<HT>(gsm + (w < 2 ? h0 : h1) + (w & 1) * (32 * (64 * HT + 16)), ol, Ol + orow0 + par * (D / 2), D,
                           wrows, l);
     __syncthreads();   // everyone is done with the projection matrix
     if (par == 1) {
@@ -484,14 +497,17 @@ hipError_t forward_impl(const Shape& s, const FwdArgs& a, bf16* hz16, bf16* WTp,
     fill_zero_f32_kernel<<<1024, 256, 0, st>>>(a.HZ, (size_t)s.BH * s.T * row_len);
   }
   constexpr int lds = FwdLds<D>::BYTES;
-  SLA_TRY(ensure_dyn_lds(fwd_mfma_kernel<D>, lds));
-  {
+  auto launch = [&](auto kern, int qt) -> hipError_t {
+    SLA_TRY(ensure_dyn_lds(kern, qt * lds));
     KernelTimer kt("fwd_sparse", st);
-    fwd_mfma_kernel<D><<<dim3(xcd_grid(s.T), s.BH), 256, lds, st>>>(
+    kern<<<dim3(xcd_grid((s.T + qt - 1) / qt), s.BH), 256 * qt, qt * lds, st>>>(
         (const bf16*)a.Q, (const bf16*)a.K, (const bf16*)a.V, WTp, a.row_idx, (const bf16*)a.HZ, Zs, s.N, s.T, s.lay(),
-        s.n_h,
-        s.n_0, s.phi, s.scale * kLog2e, (bf16*)a.O, (bf16*)a.Os, (bf16*)a.Ol, a.L);
-  }
+        s.n_h, s.n_0, s.phi, s.scale * kLog2e, (bf16*)a.O, (bf16*)a.Os, (bf16*)a.Ol, a.L);
+    return hipSuccess;
+  };
+  // query blocks of an even number of tiles: tiles 2k and 2k + 1 have the same list
+  if (s.rq % 2 == 0) SLA_TRY(launch(fwd_mfma_kernel<D, 2>, 2));
+  else SLA_TRY(launch(fwd_mfma_kernel<D, 1>, 1));
   return hipGetLastError();
 }
 
