@@ -270,22 +270,25 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
   for (int e = 0; e < 8; ++e) bneg[e] = (__bf16)((g == 0 && e < 2) ? -1.0f : 0.0f);
   const int xw = Lds::XOFF + ((kh * 4 + 2 * xh) * 2 * 64 + l) * 16;   // this wave's exchange writes
   const int xr = Lds::XOFF + (kh * 4 * 2 * 64 + l) * 16;              // ... and reads
+  const int xwave = Lds::XOFF + (kh * 4 + 2 * xh) * 2 * 64 * 16;      // start of this wave's part (uniform)
+  const unsigned xstat = lds_base(smem) + wave_uniform(xwave);
   auto step = [&](int s, const int buf) __attribute__((always_inline)) {
     const int QO = buf * Lds::BUF, GO = QO + Lds::TILE;
     ad.refresh();
     at.refresh();
     wait_vm0_known();
     __syncthreads();   // tiles of step s have landed for every wave; step s-1 is fully consumed
-    // L and D^s of this step's query 32 x + l % 32 are requested now and picked up after the first
-    // products, ahead of the next pair's tile loads in the queue (loads return in order), by loads
-    // the compiler does not see: its own wait for them would come at once and would drain the
-    // tile loads with them.  Rows past the end read as 0; their Q and dO rows are zero too, so
-    // the finite P they get adds nothing.
-    float lreg, dreg;
+    // L and D^s of this step's 64 queries are requested now, ahead of the next pair's tile loads in
+    // the queue (loads return in order), and picked up after the first products.  They go global ->
+    // LDS like the tiles (nothing the compiler could wait for, copy or spill), into the first 512
+    // bytes of this wave's own part of the exchange area: the last reads of that part (the second
+    // products of the previous step) are behind the barrier above, and the wave overwrites it with
+    // P and dS only after it has read the statistics back.  Rows past the end read as 0; their Q
+    // and dO rows are zero too, so the finite P they get adds nothing.
     {
-      const int rows = min(kBlk, N - icur * kBlk), qq = 32 * xh + (lane_id() & 31);
-      load_f32_or_zero_async(Lb + (size_t)icur * kBlk, rows, qq, lreg);
-      load_f32_or_zero_async(Dsb + (size_t)icur * kBlk, rows, qq, dreg);
+      const int rows = min(kBlk, N - icur * kBlk), lo = lane_id() * 4;
+      load_to_lds4(tile_rsrc(Lb + (size_t)icur * kBlk, rows * 4), lo, xstat);
+      load_to_lds4(tile_rsrc(Dsb + (size_t)icur * kBlk, rows * 4), lo, xstat + 256);
     }
     // (the last step requests its own pair once more, into the other buffer, where nobody reads
     // it: every step then has the same number of loads in flight and one wait serves all)
@@ -313,9 +316,11 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
       sched_fence();
     }
     // the extra k-step: A operands (hi, lo) at k = 0, 1 of the lanes with g = 0
-    wait_vm_for<2 * T::IPW>(lreg, dreg);   // the statistics are there, the tile loads may still fly
+    wait_vm<2 * T::IPW>();   // the statistics are there, the tile loads may still fly
     {
-      const float lcur = lreg * rscale, dcur = dreg;
+      const int qo = (32 * xh + (lane_id() & 31)) * 4;
+      const float lcur = *reinterpret_cast<const float*>(smem + xwave + qo) * rscale;
+      const float dcur = *reinterpret_cast<const float*>(smem + xwave + 256 + qo);
       bf16x8 aL = zero_bf16x8(), aD = zero_bf16x8();
       const __bf16 lh = (__bf16)lcur, dh = (__bf16)dcur;
       const __bf16 ll = (__bf16)(lcur - (float)lh), dl = (__bf16)(dcur - (float)dh);

@@ -207,13 +207,15 @@ __device__ __forceinline__ float load_f32_or_zero(const float* p, int count, int
   return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, idx * 4, 0, 0));
 }
 
-// The same, but the load is invisible to the compiler's own wait insertion (whose waits would also
-// drain the tile loads in flight): `out` is valid only after a wait_vm_for of the caller's that
-// covers this load and names `out`.  Issue and wait belong in the same loop iteration: across a
-// back edge the compiler may copy the register before the load has written it.
-__device__ __forceinline__ void load_f32_or_zero_async(const float* p, int count, int idx, float& out) {
-  const BufDesc r = tile_rsrc(p, count * 4);
-  asm volatile("buffer_load_dword %0, %1, %2, 0 offen" : "=v"(out) : "v"(idx * 4), "s"(r) : "memory");
+// One wave-wide 4-byte-per-lane load global -> LDS: lane L's dword at byte offset voff of the buffer
+// lands at LDS byte address lds_addr + 4 L (lds_addr wave-uniform); beyond the buffer's end it
+// deposits zero.  Like load_to_lds16 it is invisible to the compiler's wait insertion; the data
+// may be read from LDS after a wait_vm of the caller's that covers it.  Nothing lands in a
+// register, so there is no register the compiler could copy or spill before the data has arrived.
+__device__ __forceinline__ void load_to_lds4(BufDesc desc, int voff, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
+               :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(desc)
+               : "memory");
 }
 
 // lane index inside the wave, recomputed at every use (volatile: the compiler would otherwise
@@ -506,13 +508,6 @@ __device__ __forceinline__ void wait_vm0_known() {
 template <int N>
 __device__ __forceinline__ void wait_vm() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
-// All loads but the N most recent ones have completed; a and b, which asynchronous loads older
-// than those write, may be read from here on (and not before: the operands order the reads).
-template <int N>
-__device__ __forceinline__ void wait_vm_for(float& a, float& b) {
-  asm volatile("s_waitcnt vmcnt(%2) ; %0 %1" : "+v"(a), "+v"(b) : "n"(N) : "memory");
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
