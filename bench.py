@@ -67,6 +67,9 @@ def main() -> int:
     ap.add_argument("--agg-compare", action="store_true",
                     help="also time the accumulation line of Alg. 1 alone (random bf16 states, this workload's mask) "
                          "by the product the library uses and by the three forms the paper describes")
+    ap.add_argument("--dq-atomics-probe", action="store_true",
+                    help="also time the float atomics that accumulating dQ inside the column-wise backward kernel "
+                         "would issue (one 64 x d tile per critical pair), next to the row-wise dQ kernel's time")
     ap.add_argument("--token-major", action="store_true",
                     help="hand the library [B,N,H,d] tensors (SLA_BNHD) instead of [B,H,N,d]")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -260,6 +263,17 @@ def main() -> int:
             del ws, outb
         del hst
 
+    atomics = None
+    if args.dq_atomics_probe and args.bq == 64:
+        accb = torch.zeros((p.B, p.H, p.N, p.d), dtype=torch.float32, device="cuda")
+        sla.sla_profile_dq_atomics(p, b["luts"], accb)      # warm-up
+        accb.zero_()
+        ms_a = [sla.sla_profile_dq_atomics(p, b["luts"], accb) for _ in range(5)]
+        ok = bool((accb[:, :, :, 0] == 5.0 * z.n_h).all().item())   # every row got n_h additions per launch
+        atomics = {"ms": spread(ms_a), "adds_per_launch": w.B * w.H * w.N * z.n_h * w.d, "counts_ok": ok,
+                   "bwd_sparse_q_ms": kernels.get("bwd_sparse_q", {}).get("ms_per_launch")}
+        del accb
+
     # CPU oracle on a bounded sample: the first heads of the same workload, one thread per head
     cpu = None
     if args.cpu_heads > 0:
@@ -358,6 +372,7 @@ def main() -> int:
         "cpu_baseline": cpu,
         "settle_steps": settle_steps,
         "aggregation_methods": agg,
+        "dq_atomics_probe": atomics,
         "input_gen_s": t_gen,
     }
     print(json.dumps(out))

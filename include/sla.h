@@ -181,6 +181,15 @@ int sla_profile_read(char* buf, size_t buf_bytes);
  * 2 ms.  The nominal figure the roofline is priced against is 2500 (dense bf16). */
 int sla_profile_mfma_peak(int iters, double* tflops, void* stream);
 
+/* Measurement behind a design decision (dQ by a second, row-wise kernel that recomputes S and dP,
+ * not by atomics from the column-wise kernel as Alg. 2's loop is written): issues exactly the
+ * float atomic additions the fused form would make -- one workgroup per key block walks its column
+ * list (luts from sla_build_mask for p) and adds a 64 x d tile of ones into acc (float [B,H,N,d],
+ * device) per critical pair -- times the launch with HIP events on `stream`, WAITS for it and
+ * writes the milliseconds to *ms (host).  acc ends up holding, per query row, its number of
+ * critical key blocks (n_h) if it was zero before. */
+int sla_profile_dq_atomics(const sla_params* p, const void* luts, float* acc, double* ms, void* stream);
+
 /* Static description of an error code. */
 const char* sla_strerror(int code);
 

@@ -23,7 +23,7 @@ SLA_AGG_GEMM, SLA_AGG_ADD, SLA_AGG_PREAGG, SLA_AGG_FOUR_RUSSIANS = 0, 1, 2, 3
 SLA_STATIC_WS_BYTES = 32 << 20
 EXPORTS = ("sla_sizes", "sla_build_mask", "sla_build_mask_static", "sla_classify_scores", "sla_forward", "sla_backward",
            "sla_aggregate_ws_bytes", "sla_aggregate_states",
-           "sla_profile_enable", "sla_profile_read", "sla_profile_mfma_peak", "sla_strerror")
+           "sla_profile_enable", "sla_profile_read", "sla_profile_mfma_peak", "sla_profile_dq_atomics", "sla_strerror")
 
 
 class sla_params(ctypes.Structure):
@@ -71,6 +71,7 @@ def lib() -> ctypes.CDLL:
         L.sla_profile_enable.argtypes = [ctypes.c_int]
         L.sla_profile_read.argtypes = [ctypes.c_char_p, sz]
         L.sla_profile_mfma_peak.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_double), vp]
+        L.sla_profile_dq_atomics.argtypes = [pp, vp, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.sla_strerror.argtypes = [ctypes.c_int]
         L.sla_strerror.restype = ctypes.c_char_p
         for n in EXPORTS[:-1]:
@@ -285,6 +286,18 @@ def sla_profile_mfma_peak(iters: int = 4096) -> float:
     """Sustained TFLOP/s of a register-only bf16 MFMA loop on this device (waits for it)."""
     out = ctypes.c_double()
     _check(lib().sla_profile_mfma_peak(iters, ctypes.byref(out), _stream()), "sla_profile_mfma_peak")
+    return out.value
+
+
+def sla_profile_dq_atomics(p: sla_params, luts: torch.Tensor, acc: torch.Tensor) -> float:
+    """ms of the float atomics that accumulating dQ inside the column-wise kernel would issue
+    (acc: float32 [B,H,N,d], receives one addition of 1 per critical pair and element)."""
+    z = sla_sizes(p)
+    _bytes(luts, z.luts_bytes, "luts")
+    _packed(acc, (p.B, p.H, p.N, p.d), torch.float32, "acc")
+    out = ctypes.c_double()
+    _check(lib().sla_profile_dq_atomics(ctypes.byref(p), _ptr(luts), _ptr(acc), ctypes.byref(out), _stream()),
+           "sla_profile_dq_atomics")
     return out.value
 
 

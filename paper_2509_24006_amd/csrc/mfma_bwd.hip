@@ -404,7 +404,7 @@ template <int D, int QT>
 __global__ __launch_bounds__(256 * QT, QT == 1 ? 2 : 1) void bwd_dq_mfma_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
     const bf16* __restrict__ dO, const float* __restrict__ L, const float* __restrict__ Ds,
-    const int32_t* __restrict__ row_idx, const float* __restrict__ dQlin, int N, int Tn, Lay lay, int n_h,
+    const int32_t* __restrict__ row_idx, const bf16* __restrict__ dQlin, int N, int Tn, Lay lay, int n_h,
     float scale, bf16* __restrict__ dQ) {
   using Lds = PairLds<D>;
   using T = SwzTile<D>;
@@ -535,13 +535,14 @@ __global__ __launch_bounds__(256 * QT, QT == 1 ? 2 : 1) void bwd_dq_mfma_kernel(
   // linear-branch pieces are requested first, all at once, and arrive under the exchange.
   constexpr int C4 = D / 4;                  // 16-byte pieces per row
   constexpr int NIT = kBlk * C4 / 256;       // pieces per thread
-  f32x4 lq[NIT];
+  bf16x4 lq[NIT];
 #pragma unroll
   for (int it = 0; it < NIT; ++it) {
     const int idx = it * 256 + tid, row = idx / C4, c4 = idx % C4;
-    lq[it] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-    if (dQlin && row < rows)   // (the library's own tensor: packed)
-      lq[it] = *reinterpret_cast<const f32x4*>(dQlin + ((size_t)bh * N + q0 + row) * D + 4 * c4);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) lq[it][r] = (__bf16)0.0f;
+    if (dQlin && row < rows)   // (the library's own tensor: packed bf16 rows)
+      lq[it] = *reinterpret_cast<const bf16x4*>(dQlin + ((size_t)bh * N + q0 + row) * D + 4 * c4);
   }
   __syncthreads();   // every wave is done with the tiles
   constexpr int SP = Lds::SP;
@@ -575,7 +576,7 @@ __global__ __launch_bounds__(256 * QT, QT == 1 ? 2 : 1) void bwd_dq_mfma_kernel(
       const f32x4 sv = *reinterpret_cast<const f32x4*>(stg + row * SP + 4 * c4);
       bf16x4 pk;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) pk[r] = (__bf16)(sv[r] * scale + lq[it][r]);
+      for (int r = 0; r < 4; ++r) pk[r] = (__bf16)(sv[r] * scale + (float)lq[it][r]);
       *reinterpret_cast<bf16x4*>(dQ + lay.head(bh) + (size_t)(q0 + row) * lay.ts + 4 * c4) = pk;
     }
   }
@@ -607,7 +608,7 @@ hipError_t sparse_impl(const Shape& s, const BwdArgs& a, const float* Ds, const 
     KernelTimer kt("bwd_sparse_q", st);
     kern<<<dim3(xcd_grid((s.T + qt - 1) / qt), s.BH), 256 * qt, bytes, st>>>(
         (const bf16*)a.Q, (const bf16*)a.K, (const bf16*)a.V, (const bf16*)a.dO, a.L, Ds, a.row_idx,
-        dQlin, s.N, s.T, s.lay(), s.n_h, s.scale, (bf16*)a.dQ);
+        reinterpret_cast<const bf16*>(dQlin), s.N, s.T, s.lay(), s.n_h, s.scale, (bf16*)a.dQ);
     return hipSuccess;
   };
   // query blocks of an even number of tiles: tiles 2k and 2k + 1 have the same list

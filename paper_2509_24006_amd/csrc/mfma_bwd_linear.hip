@@ -35,7 +35,7 @@ __global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
     const bf16* __restrict__ Os, const bf16* __restrict__ Ol, const bf16* __restrict__ H16,
     const float* __restrict__ Zs, int N,
     int Tn, Lay lay, int n_0, int phi, float* __restrict__ Ds, bf16* __restrict__ dHZ,
-    float* __restrict__ dQlin) {
+    bf16* __restrict__ dQlin) {
   using Lds = PreLds<D>;
   using T = SwzTile<D>;
   constexpr int NT = D / 32, KT = D / 16, HT = NT / 2;
@@ -275,7 +275,9 @@ __global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
   for (int h2 = 0; h2 < HT; ++h2)
 #pragma unroll
     for (int r = 0; r < 16; ++r) dq[h2][r] = yc[h2][r] * (dq[h2][r] - dtot);
-  store_rows_f32<HT>(stage, dq, dQlin + base + (size_t)(32 * qh) * D + par * (D / 2), D, rows - 32 * qh, l);
+  // (bf16: the row-wise kernel adds this part to its float sum and rounds once more; a float
+  // round trip would move 2 x 4 bytes per element instead of 2 x 2)
+  store_rows_bf16<HT>(stage, dq, dQlin + base + (size_t)(32 * qh) * D + par * (D / 2), D, rows - 32 * qh, l);
 }
 
 // ------------------------------------------------------------------ dW partial sums
@@ -345,7 +347,7 @@ __global__ __launch_bounds__(256, 2) void dw_mfma_kernel(const bf16* __restrict_
   } while (0)
 
 template <int D>
-hipError_t pre_impl(const Shape& s, const BwdArgs& a, float* Ds, bf16* dHZ, float* dQlin,
+hipError_t pre_impl(const Shape& s, const BwdArgs& a, float* Ds, bf16* dHZ, bf16* dQlin,
                     float* dWpart, int nparts, hipStream_t st) {
   constexpr int lds = PreLds<D>::BYTES;
   SLA_TRY(ensure_dyn_lds(bwd_pre_mfma_kernel<D>, lds));
@@ -368,8 +370,9 @@ hipError_t pre_impl(const Shape& s, const BwdArgs& a, float* Ds, bf16* dHZ, floa
 hipError_t mfma_backward_pre(const Shape& s, const BwdArgs& a, float* Ds, void* dHZ16, float* dQlin,
                              float* dWpart, int nparts, hipStream_t st) {
   bf16* dHZ = reinterpret_cast<bf16*>(dHZ16);
-  return s.d == 64 ? pre_impl<64>(s, a, Ds, dHZ, dQlin, dWpart, nparts, st)
-                   : pre_impl<128>(s, a, Ds, dHZ, dQlin, dWpart, nparts, st);
+  bf16* dQl = reinterpret_cast<bf16*>(dQlin);   // bf16 rows in the float-sized buffer
+  return s.d == 64 ? pre_impl<64>(s, a, Ds, dHZ, dQl, dWpart, nparts, st)
+                   : pre_impl<128>(s, a, Ds, dHZ, dQl, dWpart, nparts, st);
 }
 
 }  // namespace sla

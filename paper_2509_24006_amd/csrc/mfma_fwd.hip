@@ -241,6 +241,7 @@ __global__ __launch_bounds__(256 * QT, QT == 1 ? 2 : 1) void fwd_mfma_kernel(
   // one accumulator, during which the wave could issue nothing else) run under the exponentials
   // of the current step: S_0 here, S_{s+1} inside step s.
   f32x16 sT = zero_f32x16();
+  const bf16x2 ones2 = {(__bf16)1.0f, (__bf16)1.0f};
   if (n_h > 0) {
     if (n_h > 1) wait_vm<3 * IPW>();   // K_0 has landed; V_0, K_1, V_1 may stay in flight
     else wait_vm0();
@@ -304,26 +305,27 @@ __global__ __launch_bounds__(256 * QT, QT == 1 ? 2 : 1) void fwd_mfma_kernel(
       m = mnew;
     }
     const float moff = m == -INFINITY ? 0.0f : -m * c2;   // a half with no valid key yet
-    float psum = 0.0f;
     sN = zero_f32x16();
     static_assert(KT == 8 || KT == 4, "two or four exponentials per product of the next scores");
 #pragma unroll
     for (int t = 0; t < KT; ++t) {
       sN = mfma32(ka[t], qf[t], sN);   // S_{s+1}
 #pragma unroll
-      for (int r = t * (16 / KT); r < (t + 1) * (16 / KT); ++r) {
-        const float pv = fast_exp2(fmaf(sT[r], c2, moff));
-        sT[r] = pv;
-        psum += pv;
-      }
+      for (int r = t * (16 / KT); r < (t + 1) * (16 / KT); ++r) sT[r] = fast_exp2(fmaf(sT[r], c2, moff));
     }
-    lsum += psum;
+    // The row sum is taken over the bf16 values that enter the product with V (numerator and
+    // denominator of O^s see the same P), two per instruction: a dot product of each packed pair
+    // with (1, 1) accumulates in float.
+    float psum = 0.0f;
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       const bf16x8 pf = c_to_operand(sT, u);
 #pragma unroll
+      for (int j2 = 0; j2 < 4; ++j2) psum = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{pf[2 * j2], pf[2 * j2 + 1]}, ones2, psum, false);
+#pragma unroll
       for (int et = 0; et < NT; ++et) oT[et] = mfma32(va[u][et], pf, oT[et]);
     }
+    lsum += psum;
     j0 = j1;
     j1 = j2;
     j2 = j3;

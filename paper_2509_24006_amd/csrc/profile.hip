@@ -78,10 +78,65 @@ __global__ __launch_bounds__(256) void mfma_peak_kernel(int iters, float* __rest
   for (int r = 0; r < 16; ++r) t += c0[r] + c1[r] + c2[r] + c3[r];
   if (t == -1.0f) sink[blockIdx.x * 256 + threadIdx.x] = t;   // never true: keeps the loop alive
 }
+// The atomic traffic of a backward pass that would accumulate dQ inside the column-wise kernel
+// (Alg. 2 as written: dQ_i += dS_ij K_j inside the loop over key blocks) instead of recomputing S
+// and dP in a row-wise kernel: one workgroup per key block walks its list of critical query tiles
+// and adds a 64 x d float tile into dQ rows of the query tile, one hardware float atomic per
+// element -- and nothing else.  What this launch costs is a lower bound of what the fused form
+// would add to the column-wise kernel.
+__global__ __launch_bounds__(256) void dq_atomics_probe_kernel(const int32_t* __restrict__ col_ptr,
+                                                               const int32_t* __restrict__ col_rows,
+                                                               const int32_t* __restrict__ col_order, int N, int Tn,
+                                                               int n_h, int d, float* __restrict__ acc) {
+  const int BH = gridDim.x / Tn, bh = blockIdx.x % BH, rank = blockIdx.x / BH;   // longest lists first
+  const int j = col_order[(size_t)bh * Tn + rank];
+  const int32_t* ptr = col_ptr + (size_t)bh * (Tn + 1);
+  const int32_t* list = col_rows + (size_t)bh * Tn * n_h;
+  const int beg = ptr[j], end = ptr[j + 1];
+  const int per = kBlk * d / 256;   // elements per thread and step
+  for (int e = beg; e < end; ++e) {
+    const int i = list[e];
+    float* tile = acc + ((size_t)bh * N + (size_t)i * kBlk) * d;
+    const int rows = min(kBlk, N - i * kBlk);
+    for (int k = 0; k < per; ++k) {
+      const int idx = k * 256 + threadIdx.x;   // consecutive lanes, consecutive addresses
+      if (idx < rows * d) unsafeAtomicAdd(tile + idx, 1.0f);
+    }
+  }
+}
 }  // namespace
 }  // namespace sla
 
 extern "C" {
+
+int sla_profile_dq_atomics(const sla_params* p, const void* luts, float* acc, double* ms_out, void* stream) {
+  sla_sizes_t z;
+  const int rc = sla_sizes(p, &z);
+  if (rc != SLA_OK) return rc;
+  if (!luts || !acc || !ms_out) return SLA_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  const char* l = (const char*)luts;
+  hipEvent_t a, b;
+  if (hipEventCreate(&a) != hipSuccess) return SLA_EHIP;
+  if (hipEventCreate(&b) != hipSuccess) {
+    (void)hipEventDestroy(a);
+    return SLA_EHIP;
+  }
+  int ret = SLA_OK;
+  float ms = 0.0f;
+  (void)hipEventRecord(a, st);
+  sla::dq_atomics_probe_kernel<<<(unsigned)((size_t)p->B * p->H * z.T), 256, 0, st>>>(
+      (const int32_t*)(l + z.lut_col_ptr), (const int32_t*)(l + z.lut_col_rows), (const int32_t*)(l + z.lut_col_order),
+      p->N, z.T, z.n_h, p->d, acc);
+  (void)hipEventRecord(b, st);
+  if (hipGetLastError() != hipSuccess || hipEventSynchronize(b) != hipSuccess ||
+      hipEventElapsedTime(&ms, a, b) != hipSuccess)
+    ret = SLA_EHIP;
+  (void)hipEventDestroy(a);
+  (void)hipEventDestroy(b);
+  *ms_out = ms;
+  return ret;
+}
 
 int sla_profile_mfma_peak(int iters, double* tflops, void* stream) {
   if (!tflops || iters <= 0 || iters > (1 << 20)) return SLA_EINVAL;
