@@ -198,17 +198,16 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
     __syncthreads();   // K_j and V_j are in registers everywhere: their buffer takes the first pair
     if (cnt > 0) issue(icur, 0);
     float kmx, kinv;
-    phi_stats<KT>(kf, phi, kmx, kinv);
     TileAddr<D> ma;
     ma.init(0, l);
     {
       // dV^T[b][n] = sum_a M[b][a] phi(K)[n][a]: rows b of M are the A operand
       bf16x8 kp[KT];
+      phi_fragments<KT>(kf, phi, kp, kmx, kinv);
+      if (!kok) {
 #pragma unroll
-      for (int t = 0; t < KT; ++t)
-#pragma unroll
-        for (int s2 = 0; s2 < 8; ++s2)
-          kp[t][s2] = (__bf16)(kok ? phi_val((float)kf[t][s2], phi, kmx, kinv) : 0.0f);
+        for (int t = 0; t < KT; ++t) kp[t] = zero_bf16x8();
+      }
 #pragma unroll
       for (int dt = 0; dt < HT; ++dt) {
         const int bt = xh * HT + dt;
@@ -229,6 +228,9 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
         dkT[dt] = mfma32(lds_tr<D>(smem, ma.tr(0, at) + mb, ma.tr(1, at) + mb), vb, dkT[dt]);
       }
     }
+    // y = phi(K) (softmax map) or d phi / d K (the other one) at the positions of the dK^T
+    // registers, formed once
+    float yk[HT][16];
     float dot = 0.0f;
 #pragma unroll
     for (int dt = 0; dt < HT; ++dt)
@@ -240,6 +242,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
           const float y = phi == 0 ? phi_val(x, 0, kmx, kinv) : (x > 0.0f ? 1.0f : fast_exp2(x * kLog2e));
           const float v = dkT[dt][4 * r4 + r] + z4[dt][r4][r];
           dkT[dt][4 * r4 + r] = v;
+          yk[dt][4 * r4 + r] = y;
           dot = fmaf(v, y, dot);
         }
     dot = half_sum(dot);
@@ -250,14 +253,9 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
 #pragma unroll
     for (int dt = 0; dt < HT; ++dt)
 #pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const float x = (float)kc[dt][r4][r];
-          const float y = phi == 0 ? phi_val(x, 0, kmx, kinv) : (x > 0.0f ? 1.0f : fast_exp2(x * kLog2e));
-          // the epilogue multiplies the whole dK sum by scale
-          dkT[dt][4 * r4 + r] = kok ? y * (dkT[dt][4 * r4 + r] - dtot) * rscale : 0.0f;
-        }
+      for (int r = 0; r < 16; ++r)
+        // the epilogue multiplies the whole dK sum by scale
+        dkT[dt][r] = kok ? yk[dt][r] * (dkT[dt][r] - dtot) * rscale : 0.0f;
     __syncthreads();   // the sums above are read before the first step writes the exchange area
   }
   TileAddr<D> ad;   // first products: rows 32 x .. of Q_i, dO_i by rows
@@ -511,11 +509,19 @@ __global__ __launch_bounds__(256 * QT, QT == 1 ? 2 : 1) void bwd_dq_mfma_kernel(
         ta[u][dt] = lds_tr<D>(smem, ad.tr(0, dt) + KO + u * RB, ad.tr(1, dt) + KO + u * RB);
     sched_fence();
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      float pv = fast_exp2(fmaf(sT[r], sl2, -Lq));
-      if (cols < kBlk && 32 * kh + c_row(r, g) >= cols) pv = 0.0f;
-      dpT[r] = pv * dpT[r];
+    for (int r = 0; r < 16; ++r) sT[r] = fast_exp2(fmaf(sT[r], sl2, -Lq));
+    // keys past the end of the sequence (last key block only): P = 0.  A branch of the whole wave,
+    // taken on one step per row at most; written into the exponential loop it costs three vector
+    // instructions per score on every step.
+    if (wave_uniform(cols) < kBlk) {
+      int first_invalid = wave_uniform(cols - 32 * kh);   // (opaque to the compiler: the comparisons below stay inside the branch)
+      asm volatile("" : "+s"(first_invalid));
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (c_row(r, g) >= first_invalid) sT[r] = 0.0f;
     }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dpT[r] = sT[r] * dpT[r];
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       const bf16x8 sb = c_to_operand(dpT, u);

@@ -537,6 +537,51 @@ __device__ __forceinline__ void phi_stats(const bf16x8 (&xf)[KT], int phi, float
   inv = 1.0f / sum;
 }
 
+// phi of a token whose features sit in B-operand fragments, as bf16 operand fragments; for the
+// softmax map every exponential is formed once (kept in registers between the sum and the values).
+// mx, inv: the softmax statistics (0 and 1 for the other map), as phi_stats returns them.
+template <int KT>
+__device__ __forceinline__ void phi_fragments(const bf16x8 (&xf)[KT], int phi, bf16x8 (&out)[KT], float& mx, float& inv) {
+  mx = 0.0f;
+  inv = 1.0f;
+  if (phi != 0) {
+#pragma unroll
+    for (int t = 0; t < KT; ++t)
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        const float x = (float)xf[t][s];
+        out[t][s] = (__bf16)(x > 0.0f ? x + 1.0f : fast_exp2(x * kLog2e));
+      }
+    return;
+  }
+  mx = -INFINITY;
+#pragma unroll
+  for (int t = 0; t < KT; ++t)
+#pragma unroll
+    for (int s = 0; s < 8; ++s) mx = fmaxf(mx, (float)xf[t][s]);
+  mx = half_max(mx);
+  float e[KT][8];
+  float sum = 0.0f;
+#pragma unroll
+  for (int t = 0; t < KT; ++t)
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      e[t][s] = fast_exp2(((float)xf[t][s] - mx) * kLog2e);
+      sum += e[t][s];
+    }
+  sum = half_sum(sum);
+  inv = 1.0f / sum;
+#pragma unroll
+  for (int t = 0; t < KT; ++t)
+#pragma unroll
+    for (int s = 0; s < 8; ++s) out[t][s] = (__bf16)(e[t][s] * inv);
+}
+template <int KT>
+__device__ __forceinline__ void phi_fragments(const bf16x8 (&xf)[KT], int phi, bf16x8 (&out)[KT]) {
+  float mx, inv;
+  phi_fragments<KT>(xf, phi, out, mx, inv);
+}
+
 __device__ __forceinline__ float phi_val(float x, int phi, float mx, float inv) {
   return phi == 0 ? fast_exp2((x - mx) * kLog2e) * inv : (x > 0.0f ? x + 1.0f : fast_exp2(x * kLog2e));
 }

@@ -392,20 +392,16 @@ __global__ __launch_bounds__(256 * QT, QT == 1 ? 2 : 1) void fwd_mfma_kernel(
     __syncthreads();   // the exchange area is free: the projection matrix goes there
     issue_matrix(WTp, x0, x1);
     // phi(Q) of this lane's query: the lane holds features 16 t + 8 g + s, its partner the rest
-    float qmx, qinv;
-    phi_stats<KT>(qf, phi, qmx, qinv);
     const float* Z = Zs + ((size_t)bh * Tn + ic) * D;
     bf16x8 qp[KT];
+    phi_fragments<KT>(qf, phi, qp);
     float den = 0.0f;
 #pragma unroll
     for (int t = 0; t < KT; ++t) {
       const f32x4 z0 = *reinterpret_cast<const f32x4*>(Z + 16 * t + 8 * g);
       const f32x4 z1 = *reinterpret_cast<const f32x4*>(Z + 16 * t + 8 * g + 4);
 #pragma unroll
-      for (int s2 = 0; s2 < 8; ++s2) {
-        qp[t][s2] = (__bf16)phi_val((float)qf[t][s2], phi, qmx, qinv);
-        den = fmaf((float)qp[t][s2], s2 < 4 ? z0[s2] : z1[s2 - 4], den);
-      }
+      for (int s2 = 0; s2 < 8; ++s2) den = fmaf((float)qp[t][s2], s2 < 4 ? z0[s2] : z1[s2 - 4], den);
     }
     den = half_sum(den);
     const float dinv = 1.0f / den;
