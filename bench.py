@@ -35,6 +35,7 @@ def kernel_work(name, c):
         "fwd_sparse": ("mfma", 4 * pair),
         "bwd_sparse_kv": ("mfma", 8 * pair),        # S, dP, dV, dK
         "bwd_sparse_q": ("mfma", 2 * pair),         # dQ (S and dP are recomputed there)
+        "bwd_query": ("mfma", 2 * pair),            # the same, preceded by the linear branch's query side
         "bwd_sparse": ("mfma", 10 * pair),
         # indicator GEMM: priced against whichever of its two floors is the higher one
         "aggregate": max(("mfma", 2 * c["BH"] * c["T"] * c["T"] * (c["d"] * c["d"] + c["d"])),

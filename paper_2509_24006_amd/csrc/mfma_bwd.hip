@@ -1,9 +1,8 @@
-// bf16 matrix-core backward kernels for the critical blocks (Algorithm 2, M_c = 1 branch;
-// Eq. 7 with the 1/sqrt(d) factor on dQ and dK):
+// bf16 matrix-core backward kernel of the key side (Algorithm 2, M_c = 1 branch, and its last line;
+// Eq. 7 with the 1/sqrt(d) factor on dK):
 //   bwd_dkdv_mfma  one workgroup per key block j, walking the column table:
-//                  dV_j += P^T dO_i, dK_j += dS^T Q_i / sqrt(d)
-//   bwd_dq_mfma    one workgroup per query block i, walking the row table:
-//                  dQ_i += dS K_j / sqrt(d)   (S, dP are recomputed; no atomics, one owner)
+//                  dV_j += P^T dO_i, dK_j += dS^T Q_i / sqrt(d), started from the linear branch's
+//                  dK_j, dV_j (the row-wise dQ kernel lives in mfma_bwd_query.hip)
 // P = exp(S - L) and dS = P (dP - D^s) are formed in float from MFMA accumulators.
 //
 // One critical pair per step.  The two streaming tiles of a pair go global -> LDS directly
@@ -16,22 +15,6 @@
 
 namespace sla {
 namespace {
-
-template <int D>
-struct PairLds {
-  static constexpr int TILE = SwzTile<D>::BYTES;
-  static constexpr int BUF = 2 * TILE;                   // the two tiles of a pair
-  static constexpr int STAT_OFF = 2 * BUF;
-  static constexpr int XCH = 2 * 2 * (D / 32) * 16 * 64 * 4;   // final exchange (dK/dV kernel)
-  static constexpr int TILES = 2 * BUF > XCH ? 2 * BUF : XCH;
-  static constexpr int BYTES = TILES + 2 * 2 * kBlk * 4; // + [buf][L, D^s][64]
-  static constexpr int VPARK = D >= 128 ? 2 * (3 * D / 64) * 64 * 16 : 0;   // parked V operand (dK/dV kernel)
-  static constexpr int SP = D + 4;                        // row pitch (floats) of the output staging
-  static constexpr int STAGE = 2 * kBlk * SP * 4;         // [dV | dK][64][SP] floats (dK/dV kernel)
-  static constexpr int DKDV = BYTES + VPARK > STAGE ? BYTES + VPARK : STAGE;
-  // the second group of an eight-wave dQ workgroup: its Q_i, dO_i tiles, later its output staging
-  static constexpr int GROUP = (kBlk * SP * 4 > BUF ? kBlk * SP * 4 : BUF);
-};
 
 // ------------------------------------------------------------------ dK, dV
 // First products (S, dP): wave (kh, x) takes keys 32 kh .., queries 32 x .. of the pair; S and dP
@@ -390,204 +373,6 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_mfma_kernel(
   store_rows_bf16<HT>(stage, dkT, dK + o0, lay.ts, cols - 32 * kh, l);
 }
 
-// ------------------------------------------------------------------ dQ
-// Wave (qh, kh): S^T and dP^T are [key][query], one query per lane, so L and D^s are per-lane
-// scalars and dS^T feeds dQ^T = K^T dS^T from registers.  The two kh waves hold partial sums
-// over their keys and are added at the end.
-// QT = 2 (query blocks of 128 or 256 tokens): two adjacent 64-query tiles, which walk the same
-// list of key blocks, share a workgroup of eight waves and every K_j, V_j tile it fetches; each
-// group of four waves has an LDS area of its own for its Q_i, dO_i tiles and its output staging
-// (the second group's lies behind the pair buffers).
-template <int D, int QT>
-__global__ __launch_bounds__(256 * QT, QT == 1 ? 2 : 1) void bwd_dq_mfma_kernel(
-    const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
-    const bf16* __restrict__ dO, const float* __restrict__ L, const float* __restrict__ Ds,
-    const int32_t* __restrict__ row_idx, const bf16* __restrict__ dQlin, int N, int Tn, Lay lay, int n_h,
-    float scale, bf16* __restrict__ dQ) {
-  using Lds = PairLds<D>;
-  using T = SwzTile<D>;
-  constexpr int NT = D / 32, KT = D / 16;
-  constexpr int RB = 16 * T::ROW_BYTES;
-  constexpr int NW = 4 * QT;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  const int wall = threadIdx.x >> 6, l = threadIdx.x & 63, g = l >> 5, ln = l & 31;
-  const int grp = QT == 1 ? 0 : wave_uniform(wall >> 2), w = wall & 3, tid = threadIdx.x & 255;
-  const int qh = w & 1, kh = w >> 1;
-  const int ib = xcd_local_block(blockIdx.x, (Tn + QT - 1) / QT), bh = blockIdx.y;
-  if (ib < 0) return;
-  // (a last block of a single tile: the second group runs along with no valid query and stores nothing)
-  const int i = QT * ib + grp;
-  // group 0 takes Q_i, dO_i in through the second pair buffer and stages its output over the pair
-  // buffers; group 1 has DqLds<D>::GROUP bytes behind them for both
-  unsigned char* gsm = smem + (grp ? Lds::BYTES - Lds::BUF : 0);
-  const int q0 = i * kBlk, rows = max(0, min(kBlk, N - q0));
-  const int qrow = qh * 32 + ln;
-  const bool qok = qrow < rows;
-  const int32_t* lut = row_idx + ((size_t)bh * Tn + QT * ib) * n_h;   // the same list for every tile of the block
-  const float sl2 = scale * kLog2e;
-  TileLoader<D, NW> tl;   // K_j, V_j: all waves of the workgroup
-  TileLoader<D> tq;       // Q_i, dO_i: the four waves of a group, into the group's area
-  tl.init(lds_base(smem), wall, l, 2 * lay.ts);
-  tq.init(lds_base(smem) + (grp ? Lds::BYTES - Lds::BUF : 0), w, l, 2 * lay.ts);
-  const BufDesc descK = head_rsrc<D>(K + lay.head(bh), N, 2 * lay.ts);
-  const BufDesc descV = head_rsrc<D>(V + lay.head(bh), N, 2 * lay.ts);
-  // key block indices of steps s, s + 1, s + 2, fetched a step before the loads that need them
-  int j0 = 0, j1 = 0, j2 = 0;
-  auto issue = [&](int jj, const int bufi) __attribute__((always_inline)) {
-    tl.load(descK, jj, bufi * Lds::BUF);
-    tl.load(descV, jj, bufi * Lds::BUF + Lds::TILE);
-  };
-  // Q_i and dO_i come in as tiles through the second pair buffer (whole rows per load, zeros past
-  // the end of the sequence) and are picked up from there in operand layout
-  {
-    const int it = min(i, Tn - 1);
-    tq.load(head_rsrc<D>(Q + lay.head(bh), N, 2 * lay.ts), it, Lds::BUF);
-    tq.load(head_rsrc<D>(dO + lay.head(bh), N, 2 * lay.ts), it, Lds::BUF + Lds::TILE);
-  }
-  if (n_h > 0) {
-    j0 = lut[0];
-    j1 = lut[min(1, n_h - 1)];
-    j2 = lut[min(2, n_h - 1)];
-    issue(j0, 0);
-  }
-  const float Lq = qok ? L[(size_t)bh * N + q0 + qrow] * kLog2e : INFINITY;
-  const float nDq = qok ? -Ds[(size_t)bh * N + q0 + qrow] : 0.0f;
-  f32x16 dqT[NT];
-#pragma unroll
-  for (int t = 0; t < NT; ++t) dqT[t] = zero_f32x16();
-  wait_vm0();
-  __syncthreads();
-  bf16x8 qf[KT], gf[KT];
-  {
-    TileAddr<D> qa;
-    qa.init(32 * qh, l);
-#pragma unroll
-    for (int t = 0; t < KT; ++t) {
-      qf[t] = lds_row(gsm, qa.row(t) + Lds::BUF);
-      gf[t] = lds_row(gsm, qa.row(t) + Lds::BUF + Lds::TILE);
-    }
-  }
-#pragma unroll
-  for (int t = 0; t < KT; ++t) {
-    pin_loaded(qf[t]);
-    pin_loaded(gf[t]);
-  }
-  // (the first step's barrier orders these reads before the loads that reuse the buffer)
-  TileAddr<D> ad;   // this wave reads rows 32 kh .. of K_j and V_j
-  ad.init(32 * kh, l);
-  auto step = [&](int s, const int buf) __attribute__((always_inline)) {
-    const int KO = buf * Lds::BUF, VO = KO + Lds::TILE;
-    const int cols = min(kBlk, N - j0 * kBlk);
-    const int j3 = lut[min(s + 3, n_h - 1)];
-    ad.refresh();
-    wait_vm0();
-    __syncthreads();   // tiles of step s have landed for every wave; step s-1 is fully consumed
-    if (s + 1 < n_h) issue(j1, buf ^ 1);
-    // all LDS reads of the first two products up front, then the products
-    bf16x8 ka[KT], va[KT], ta[2][NT];
-#pragma unroll
-    for (int t = 0; t < KT; ++t) {
-      ka[t] = lds_row(smem, ad.row(t) + KO);
-      va[t] = lds_row(smem, ad.row(t) + VO);
-    }
-    sched_fence();
-    // a lane's 16 entries of dP^T belong to its one query: the accumulator starts at -D^s of that
-    // query instead of zero and comes out as dP - D^s
-    f32x16 sT = zero_f32x16(), dpT;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) dpT[r] = nDq;
-#pragma unroll
-    for (int t = 0; t < KT; ++t) {
-      sT = mfma32(ka[t], qf[t], sT);
-      dpT = mfma32(va[t], gf[t], dpT);
-    }
-    // K_j^T for the third product arrives under the softmax arithmetic
-#pragma unroll
-    for (int u = 0; u < 2; ++u)
-#pragma unroll
-      for (int dt = 0; dt < NT; ++dt)
-        ta[u][dt] = lds_tr<D>(smem, ad.tr(0, dt) + KO + u * RB, ad.tr(1, dt) + KO + u * RB);
-    sched_fence();
-#pragma unroll
-    for (int r = 0; r < 16; ++r) sT[r] = fast_exp2(fmaf(sT[r], sl2, -Lq));
-    // keys past the end of the sequence (last key block only): P = 0.  A branch of the whole wave,
-    // taken on one step per row at most; written into the exponential loop it costs three vector
-    // instructions per score on every step.
-    if (wave_uniform(cols) < kBlk) {
-      int first_invalid = wave_uniform(cols - 32 * kh);   // (opaque to the compiler: the comparisons below stay inside the branch)
-      asm volatile("" : "+s"(first_invalid));
-#pragma unroll
-      for (int r = 0; r < 16; ++r)
-        if (c_row(r, g) >= first_invalid) sT[r] = 0.0f;
-    }
-#pragma unroll
-    for (int r = 0; r < 16; ++r) dpT[r] = sT[r] * dpT[r];
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const bf16x8 sb = c_to_operand(dpT, u);
-#pragma unroll
-      for (int dt = 0; dt < NT; ++dt) dqT[dt] = mfma32(ta[u][dt], sb, dqT[dt]);   // K_j^T dS^T
-    }
-    j0 = j1;
-    j1 = j2;
-    j2 = j3;
-  };
-  for (int s = 0; s < n_h; s += 2) {
-    step(s, 0);
-    if (s + 1 < n_h) step(s + 1, 1);
-  }
-  // ---- add the two key halves in a row-major staging area, then every thread takes 16-byte
-  // pieces of whole rows: adds the linear-branch part and stores (coalesced both ways).  The
-  // linear-branch pieces are requested first, all at once, and arrive under the exchange.
-  constexpr int C4 = D / 4;                  // 16-byte pieces per row
-  constexpr int NIT = kBlk * C4 / 256;       // pieces per thread
-  bf16x4 lq[NIT];
-#pragma unroll
-  for (int it = 0; it < NIT; ++it) {
-    const int idx = it * 256 + tid, row = idx / C4, c4 = idx % C4;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) lq[it][r] = (__bf16)0.0f;
-    if (dQlin && row < rows)   // (the library's own tensor: packed bf16 rows)
-      lq[it] = *reinterpret_cast<const bf16x4*>(dQlin + ((size_t)bh * N + q0 + row) * D + 4 * c4);
-  }
-  __syncthreads();   // every wave is done with the tiles
-  constexpr int SP = Lds::SP;
-  float* stg = reinterpret_cast<float*>(grp ? gsm + Lds::BUF : smem);   // [64 queries][SP]
-  const int srow = qrow * SP + 4 * g;
-  if (kh == 1) {
-#pragma unroll
-    for (int dt = 0; dt < NT; ++dt)
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4)
-        *reinterpret_cast<f32x4*>(stg + srow + 32 * dt + 8 * r4) =
-            f32x4{dqT[dt][4 * r4], dqT[dt][4 * r4 + 1], dqT[dt][4 * r4 + 2], dqT[dt][4 * r4 + 3]};
-  }
-  __syncthreads();
-  if (kh == 0) {
-#pragma unroll
-    for (int dt = 0; dt < NT; ++dt)
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        f32x4 a = *reinterpret_cast<const f32x4*>(stg + srow + 32 * dt + 8 * r4);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) a[r] += dqT[dt][4 * r4 + r];
-        *reinterpret_cast<f32x4*>(stg + srow + 32 * dt + 8 * r4) = a;
-      }
-  }
-  __syncthreads();
-#pragma unroll
-  for (int it = 0; it < NIT; ++it) {
-    const int idx = it * 256 + tid, row = idx / C4, c4 = idx % C4;
-    if (row < rows) {
-      const f32x4 sv = *reinterpret_cast<const f32x4*>(stg + row * SP + 4 * c4);
-      bf16x4 pk;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) pk[r] = (__bf16)(sv[r] * scale + (float)lq[it][r]);
-      *reinterpret_cast<bf16x4*>(dQ + lay.head(bh) + (size_t)(q0 + row) * lay.ts + 4 * c4) = pk;
-    }
-  }
-}
-
 #define SLA_TRY(x)                   \
   do {                               \
     hipError_t e_ = (x);             \
@@ -595,10 +380,8 @@ __global__ __launch_bounds__(256 * QT, QT == 1 ? 2 : 1) void bwd_dq_mfma_kernel(
   } while (0)
 
 template <int D>
-hipError_t sparse_impl(const Shape& s, const BwdArgs& a, const float* Ds, const float* dQlin,
-                       const void* dHZcol, hipStream_t st) {
+hipError_t sparse_impl(const Shape& s, const BwdArgs& a, const float* Ds, const void* dHZcol, hipStream_t st) {
   const float* dZcol = dHZcol ? reinterpret_cast<const float*>((const char*)dHZcol + state_z_offset(s)) : nullptr;
-  constexpr int lds = PairLds<D>::BYTES;
   auto launch_kv = [&](auto kern) -> hipError_t {
     SLA_TRY(ensure_dyn_lds(kern, KvLds<D>::BYTES));
     KernelTimer kt("bwd_sparse_kv", st);
@@ -608,27 +391,13 @@ hipError_t sparse_impl(const Shape& s, const BwdArgs& a, const float* Ds, const 
     return hipSuccess;
   };
   SLA_TRY(s.phi == 0 ? launch_kv(bwd_dkdv_mfma_kernel<D, 0>) : launch_kv(bwd_dkdv_mfma_kernel<D, 1>));
-  auto launch_q = [&](auto kern, int qt) -> hipError_t {
-    const int bytes = lds + (qt - 1) * PairLds<D>::GROUP;
-    SLA_TRY(ensure_dyn_lds(kern, bytes));
-    KernelTimer kt("bwd_sparse_q", st);
-    kern<<<dim3(xcd_grid((s.T + qt - 1) / qt), s.BH), 256 * qt, bytes, st>>>(
-        (const bf16*)a.Q, (const bf16*)a.K, (const bf16*)a.V, (const bf16*)a.dO, a.L, Ds, a.row_idx,
-        reinterpret_cast<const bf16*>(dQlin), s.N, s.T, s.lay(), s.n_h, s.scale, (bf16*)a.dQ);
-    return hipSuccess;
-  };
-  // query blocks of an even number of tiles: tiles 2k and 2k + 1 have the same list
-  if (s.rq % 2 == 0) SLA_TRY(launch_q(bwd_dq_mfma_kernel<D, 2>, 2));
-  else SLA_TRY(launch_q(bwd_dq_mfma_kernel<D, 1>, 1));
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t mfma_backward_sparse(const Shape& s, const BwdArgs& a, const float* Ds,
-                                const float* dQlin, const void* dHZcol, hipStream_t st) {
-  return s.d == 64 ? sparse_impl<64>(s, a, Ds, dQlin, dHZcol, st)
-                   : sparse_impl<128>(s, a, Ds, dQlin, dHZcol, st);
+hipError_t mfma_backward_sparse(const Shape& s, const BwdArgs& a, const float* Ds, const void* dHZcol, hipStream_t st) {
+  return s.d == 64 ? sparse_impl<64>(s, a, Ds, dHZcol, st) : sparse_impl<128>(s, a, Ds, dHZcol, st);
 }
 
 }  // namespace sla

@@ -917,7 +917,8 @@ hipError_t backward_impl(const Shape& s, const BwdArgs& a, hipStream_t st) {
 hipError_t backward_bf16(const Shape& s, const BwdArgs& a, hipStream_t st) {
   const BwdWs w = carve_bwd(s, a.ws);
   const bool lin = s.n_0 > 0;
-  SLA_TRY(mfma_backward_pre(s, a, w.Ds, w.dHZ, w.dQlin, w.dWpart, w.nparts, st));   // dHZ holds bf16 rows
+  SLA_TRY(mfma_backward_query(s, a, w.Ds, w.dHZ, w.dQlin, st));   // dHZ holds bf16 rows
+  SLA_TRY(mfma_backward_dw(s, a, w.dWpart, w.nparts, st));
   {
     KernelTimer kt("dw_reduce", st);
     dw_reduce_kernel<<<(s.d * s.d + 63) / 64, 256, 0, st>>>(w.dWpart, w.nparts, s.d * s.d, a.dW);
@@ -926,7 +927,7 @@ hipError_t backward_bf16(const Shape& s, const BwdArgs& a, hipStream_t st) {
     SLA_TRY(mfma_aggregate(w.dHZ, a.indT, s, w.dHZcol,
                            reinterpret_cast<float*>(reinterpret_cast<char*>(w.dHZcol) + state_z_offset(s)), st));
   }
-  return mfma_backward_sparse(s, a, w.Ds, lin ? w.dQlin : nullptr, lin ? w.dHZcol : nullptr, st);
+  return mfma_backward_sparse(s, a, w.Ds, lin ? w.dHZcol : nullptr, st);
 }
 
 }  // namespace

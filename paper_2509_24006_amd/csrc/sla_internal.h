@@ -82,8 +82,7 @@ size_t simt_backward_ws_bytes(const Shape& s);
 // dHZcol: dH and dZ summed over the marginal blocks of each key block (bf16 matrices, then float
 // vectors at state_z_offset); the dK/dV kernel turns them into the linear-branch parts of dK and
 // dV itself.  Both may be null (no marginal block).
-hipError_t mfma_backward_sparse(const Shape& s, const BwdArgs& a, const float* Ds,
-                                const float* dQlin, const void* dHZcol, hipStream_t st);
+hipError_t mfma_backward_sparse(const Shape& s, const BwdArgs& a, const float* Ds, const void* dHZcol, hipStream_t st);
 hipError_t simt_backward(const Shape& s, const BwdArgs& a, hipStream_t st);
 
 // ---- bf16 matrix-core path (mfma_fwd.hip)
@@ -102,9 +101,11 @@ size_t aggregate_alt_ws_bytes(const Shape& s, int method);
 hipError_t aggregate_alt(int method, const void* in, const unsigned long long* ind, const Shape& s, void* outH,
                          float* outZ, void* ws, hipStream_t st);
 
-// linear branch and Proj gradients on the matrix cores (mfma_bwd_linear.hip)
-hipError_t mfma_backward_pre(const Shape& s, const BwdArgs& a, float* Ds, void* dHZ16, float* dQlin,
-                             float* dWpart, int nparts, hipStream_t st);
+// query side on the matrix cores (mfma_bwd_query.hip): D^s, dH_i / dZ_i rows (dHZ16), dQ.  dQlin:
+// scratch for the linear part of dQ (only used with query blocks of two or four tiles).
+hipError_t mfma_backward_query(const Shape& s, const BwdArgs& a, float* Ds, void* dHZ16, float* dQlin, hipStream_t st);
+// partial sums of dW = sum O^l^T dO
+hipError_t mfma_backward_dw(const Shape& s, const BwdArgs& a, float* dWpart, int nparts, hipStream_t st);
 
 // Brackets one kernel launch with events when profiling is on (profile.hip).
 class KernelTimer {
