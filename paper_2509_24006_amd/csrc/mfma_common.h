@@ -343,6 +343,66 @@ struct TileLoader {
   }
 };
 
+// The loader of the step loops, built for few instructions per tile: a wave (one of NW that fill a
+// tile together) fills a run of consecutive rows, IPW KB that are contiguous in LDS, so that one
+// value of M0 serves all its loads of a tile and the instruction's immediate offset (which moves
+// the LDS address and the memory address alike) steps through the run.  The swizzle of a row
+// differs from load to load, hence one per-lane offset per load, each with the immediate taken
+// out again (the rows of a load are at least 1 KB apart in memory, so none goes negative).
+// Per tile: one scalar instruction for M0, the wait state it needs, IPW loads.
+template <int D, int NW = 4>
+struct RunLoader {
+  using T = SwzTile<D>;
+  static constexpr int IPW = kBlk / T::RPI / NW;
+  static_assert(IPW == 1 || IPW == 2 || IPW == 4, "loads per wave and tile");
+  int voff[IPW];
+  unsigned ldsw;  // LDS address of this wave's run of the tile at LDS offset 0
+  int tile_step;  // bytes between consecutive 64-row tiles in memory
+  __device__ __forceinline__ void init(unsigned lds_base_addr, int w, int l, int tsB) {
+#pragma unroll
+    for (int k = 0; k < IPW; ++k) {
+      const int row = T::RPI * (IPW * w + k) + l / T::CPR;
+      voff[k] = row * tsB + (((l % T::CPR) ^ swz<D>(row)) << 4) - 1024 * k;
+    }
+    tile_step = __builtin_amdgcn_readfirstlane(kBlk * tsB);
+    ldsw = lds_base_addr + __builtin_amdgcn_readfirstlane(w) * (1024 * IPW);
+  }
+  // keeps the per-lane offsets in their registers (the compiler would otherwise re-derive them
+  // inside the loop, or spill them)
+  __device__ __forceinline__ void pin() {
+#pragma unroll
+    for (int k = 0; k < IPW; ++k) asm volatile("" : "+v"(voff[k]));
+  }
+  // the tile at byte offset soff (wave-uniform) of the buffer -> the tile slot at LDS offset LDS_OFF
+  template <int LDS_OFF>
+  __device__ __forceinline__ void load(BufDesc desc, int soff_in) const {
+    const int soff = __builtin_amdgcn_readfirstlane(soff_in);
+    if constexpr (IPW == 4) {
+      asm volatile(
+          "s_add_u32 m0, %0, %1\n\ts_nop 0\n\t"
+          "buffer_load_dwordx4 %2, %6, %7 offen lds\n\t"
+          "buffer_load_dwordx4 %3, %6, %7 offen offset:1024 lds\n\t"
+          "buffer_load_dwordx4 %4, %6, %7 offen offset:2048 lds\n\t"
+          "buffer_load_dwordx4 %5, %6, %7 offen offset:3072 lds"
+          ::"s"(ldsw), "n"(LDS_OFF), "v"(voff[0]), "v"(voff[1]), "v"(voff[2]), "v"(voff[3]), "s"(desc), "s"(soff)
+          : "memory", "scc");
+    } else if constexpr (IPW == 2) {
+      asm volatile(
+          "s_add_u32 m0, %0, %1\n\ts_nop 0\n\t"
+          "buffer_load_dwordx4 %2, %4, %5 offen lds\n\t"
+          "buffer_load_dwordx4 %3, %4, %5 offen offset:1024 lds"
+          ::"s"(ldsw), "n"(LDS_OFF), "v"(voff[0]), "v"(voff[1]), "s"(desc), "s"(soff)
+          : "memory", "scc");
+    } else {
+      asm volatile(
+          "s_add_u32 m0, %0, %1\n\ts_nop 0\n\t"
+          "buffer_load_dwordx4 %2, %3, %4 offen lds"
+          ::"s"(ldsw), "n"(LDS_OFF), "v"(voff[0]), "s"(desc), "s"(soff)
+          : "memory", "scc");
+    }
+  }
+};
+
 // A operand whose 32 rows are tile rows r0 + (l % 32) and whose k-values are features 16 t + 8 g ..
 template <int D>
 __device__ __forceinline__ bf16x8 read_row_swz(const unsigned char* tile, int r0, int t, int l) {

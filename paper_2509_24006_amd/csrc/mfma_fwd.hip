@@ -5,6 +5,7 @@
 //   fwd_mfma        online-softmax attention over the critical blocks of a query block,
 //                   the closing line (O^s, L, O^l) and O = O^s + O^l W
 // All contractions run on v_mfma_f32_32x32x16_bf16 with float accumulation.
+#include <type_traits>
 #include "mfma_common.h"
 
 namespace sla {
@@ -134,26 +135,35 @@ __global__ __launch_bounds__(256, 4) void states_mfma_kernel(const bf16* __restr
 // softmax statistics are per-lane scalars and P goes from C registers straight into the B
 // operand of the second product.  Each wave runs its own online softmax over its key halves;
 // the two streams of a query half are merged at the end.  K_j and V_j go global -> LDS
-// directly (swizzled, through a ring of five slots, one barrier per step); V is read transposed.
+// directly (swizzled, one barrier per step); V is read transposed.
 // The scores of step s + 1 are formed under the exponentials of step s.
+//
+// The step loop is written for few instructions: a wave issues one instruction every five (vector)
+// to eight (scalar) cycles whatever its kind, and with two waves per SIMD that rate, not the matrix
+// pipe, bounds the loop.  Hence: tile slots fixed per step parity (two copies of the step, every LDS
+// offset an immediate), per-lane LDS addresses held in registers, one M0 value per tile
+// (RunLoader), the key block table read one entry per step through a running offset, the last
+// two steps as copies of their own instead of conditions inside the step.
 template <int D>
 struct FwdLds {
-  // Five tile slots used as one ring by the load sequence K_0 V_0 K_1 V_1 ...: load n goes to slot
-  // n % 5.  The scores S_s are formed during step s - 1, so at the barrier that opens step s the
-  // slots of K_s and V_{s-1} are free and take K_{s+2} and V_{s+2}: every tile is requested two
-  // steps before it is needed (an L2 miss costs about two steps).  At
-  // d = 128 the ring is all of a CU's LDS for two workgroups.  After the loop the slots hold the
-  // exchange between the two key streams, H_i, the projection matrix and the softmax statistics.
+  // Slot 2p holds the K tile and slot 2p + 1 the V tile of the steps of parity p.  The scores S_s
+  // are formed during step s - 1.  A wave copies its operands of step s (rows of K_{s+1}, V_s) to
+  // registers at the top of the step; after a barrier of its own the two slots take K_{s+3} and
+  // V_{s+2}: every tile is requested two steps before it is needed (an L2 miss costs more than
+  // one step) although only two tiles of each kind have a slot.
+  // After the loop the slots hold the exchange between the two key streams, H_i and the
+  // projection matrix; the softmax statistics have a KB of their own behind the slots.
   static constexpr int TILE = SwzTile<D>::BYTES;
   static constexpr int XCH_HALF = (D / 2) * 64 * 4;       // C registers of one query half
-  static_assert(XCH_HALF <= TILE && 1024 <= TILE, "exchange areas are laid over tile slots");
-  static constexpr int BYTES = 5 * TILE;
+  static_assert(XCH_HALF <= TILE, "exchange areas are laid over tile slots");
+  static constexpr int STAT = 4 * TILE;
+  static constexpr int BYTES = 4 * TILE + 1024;
 };
 // Query blocks of 128 (or 256) tokens: QT = 2 adjacent 64-query tiles, which have the same list of
 // critical key blocks, share one workgroup of eight waves.  K_j and V_j are then fetched into LDS
 // once for both tiles (half the L2 -> LDS traffic and half the load instructions per score); each
 // group of four waves works on its tile exactly as a four-wave workgroup does, and has an LDS area
-// of its own (the second group's lies behind the ring) for what follows the loop.
+// of its own (the second group's lies behind the first's) for what follows the loop.
 
 template <int D, int QT>
 __global__ __launch_bounds__(256 * QT, QT == 1 ? 2 : 1) void fwd_mfma_kernel(
@@ -190,16 +200,13 @@ __global__ __launch_bounds__(256 * QT, QT == 1 ? 2 : 1) void fwd_mfma_kernel(
   const int32_t* lut = row_idx + ((size_t)bh * Tn + QT * ib) * n_h;   // the same list for every tile of the block
   const float c2 = scale_log2e;                    // exp(x / sqrt(d)) = exp2(x * c2)
   using T = SwzTile<D>;
-  TileLoader<D, NW> tl;   // tiles of the caller's K and V: all waves of the workgroup, into the ring
+  RunLoader<D, NW> tl;    // tiles of the caller's K and V: all waves of the workgroup, into the slots
   TileLoader<D> tm;       // packed d x d matrices: the four waves of a group, into the group's area
   tl.init(lds_base(smem), wall, l, 2 * lay.ts);
   tm.init(lds_base(smem) + grp * Lds::BYTES, w, l, 2 * D);
-  constexpr int IPW = TileLoader<D, NW>::IPW;
+  constexpr int IPW = RunLoader<D, NW>::IPW;
   const BufDesc descK = head_rsrc<D>(K + lay.head(bh), N, 2 * lay.ts);
   const BufDesc descV = head_rsrc<D>(V + lay.head(bh), N, 2 * lay.ts);
-  // K (v = 0) or V (v = 1) tile of key block jj into a slot; the loads go K_0 V_0 K_1 V_1 ... and
-  // load n of that sequence uses slot n % 5
-  auto issue_load = [&](int v, int jj, int slot) { tl.load(v ? descV : descK, jj, slot * Lds::TILE); };
   // a d x d bf16 matrix (aggregated state H_i, prepared projection matrix) goes global -> LDS like
   // the tiles: rows 0..63 into the slot at off0, the rest into the one at off1
   auto issue_matrix = [&](const bf16* M, int off0, int off1) {
@@ -208,82 +215,97 @@ __global__ __launch_bounds__(256 * QT, QT == 1 ? 2 : 1) void fwd_mfma_kernel(
     if (D > kBlk) tm.load(dm, 1, off1);
   };
   const bf16* Hrow = H16 + ((size_t)bh * Tn + ic) * (D * D);
-  // Slots at the end of the loop, with b the slot of the last K tile: H_i goes to b and b + 4
-  // (free from the middle of the last step), b + 1 holds the last V tile and b + 2, b + 3 were
-  // never refilled.  The statistics are written while slower waves may still read V: slot b + 2.
-  const int bslot = n_h > 0 ? (2 * (n_h - 1)) % 5 : 0;
-  const int h0 = bslot * Lds::TILE, h1 = ((bslot + 4) % 5) * Lds::TILE;
-  const int x1 = ((bslot + 1) % 5) * Lds::TILE, x0 = ((bslot + 3) % 5) * Lds::TILE;
-  float* ml = reinterpret_cast<float*>(gsm + ((bslot + 2) % 5) * Lds::TILE);   // [par][qh][32][2]
-  const int nloads = 2 * n_h;
-  // key block indices of steps s, s + 1, s + 2: fetched a step before the loads that need them,
-  // so that no wave ever waits for a table entry between a barrier and its loads
-  int j0 = 0, j1 = 0, j2 = 0;
+  // Slots at the end of the loop, with p the parity of the last step: H_i goes to the slots of
+  // K_{last+1} (never filled) and V_last, both free from the last step's second barrier on, the
+  // exchange areas to the other two once the loop is over.
+  const int pl = n_h > 0 ? (n_h - 1) & 1 : 0;
+  const int h0 = (2 - 2 * pl) * Lds::TILE, h1 = (2 * pl + 1) * Lds::TILE;
+  const int x0 = 2 * pl * Lds::TILE, x1 = (3 - 2 * pl) * Lds::TILE;
+  float* ml = reinterpret_cast<float*>(gsm + Lds::STAT);   // [par][qh][32][2]
+  // byte offsets (inside a head) of the key blocks of steps s .. s + 3; the table entry behind the
+  // fourth is fetched a step before the load that needs it
+  int kb0 = 0, kb1 = 0, kb2 = 0, kb3 = 0;
   if (n_h > 0) {
-    j0 = lut[0];
-    j1 = lut[min(1, n_h - 1)];
-    j2 = lut[min(2, n_h - 1)];
-    issue_load(0, j0, 0);
-    issue_load(1, j0, 1);
+    kb0 = lut[0] * tl.tile_step;
+    kb1 = lut[min(1, n_h - 1)] * tl.tile_step;
+    kb2 = lut[min(2, n_h - 1)] * tl.tile_step;
+    kb3 = lut[min(3, n_h - 1)] * tl.tile_step;
+    tl.template load<0>(descK, kb0);
+    tl.template load<Lds::TILE>(descV, kb0);
     if (n_h > 1) {
-      issue_load(0, j1, 2);
-      issue_load(1, j1, 3);
+      tl.template load<2 * Lds::TILE>(descK, kb1);
+      tl.template load<3 * Lds::TILE>(descV, kb1);
     }
   } else if (n_0 > 0) {
     issue_matrix(Hrow, h0, h1);
   }
+  unsigned lo = 16;                                  // byte offset of the next table entry to fetch
+  const unsigned lomax = 4u * (unsigned)max(n_h - 1, 0);
+  // a sequence whose last key block is partial: its offset and its number of keys
+  const int off_tail = (N % kBlk) ? (Tn - 1) * tl.tile_step : -1;
+  const int tail_cols = N - (N / kBlk) * kBlk;
 #pragma unroll
   for (int t = 0; t < KT; ++t) pin_loaded(qf[t]);
-  int kslot = 0;   // slot of K_s; V_s sits in the next one, K_{s+1} in the one after
-  TileAddr<D> ad;  // this wave reads rows 32 par .. of both tiles
-  ad.init(32 * par, l);
+  // per-lane LDS offsets of this wave's operand reads inside a tile (rows 32 par .. of both tiles)
+  int kaddr[KT], vaddr[2][NT];
+  {
+    TileAddr<D> ad;
+    ad.init(32 * par, l);
+#pragma unroll
+    for (int t = 0; t < KT; ++t) {
+      kaddr[t] = ad.row(t);
+      asm volatile("" : "+v"(kaddr[t]));
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int et = 0; et < NT; ++et) {
+        vaddr[h][et] = ad.tr(h, et);
+        asm volatile("" : "+v"(vaddr[h][et]));
+      }
+  }
+  tl.pin();
   // The scores of a step are formed one step ahead, so that their matrix products (a chain on
   // one accumulator, during which the wave could issue nothing else) run under the exponentials
   // of the current step: S_0 here, S_{s+1} inside step s.
   f32x16 sT = zero_f32x16();
-  const bf16x2 ones2 = {(__bf16)1.0f, (__bf16)1.0f};
   if (n_h > 0) {
-    if (n_h > 1) wait_vm<3 * IPW>();   // K_0 has landed; V_0, K_1, V_1 may stay in flight
+    if (n_h > 1) wait_vm<3 * IPW>();   // K_0 has landed; V_0, K_1 and V_1 may stay in flight
+    else wait_vm<IPW>();
+    __syncthreads();
+    bf16x8 k0[KT];
+#pragma unroll
+    for (int t = 0; t < KT; ++t) k0[t] = lds_row(smem, kaddr[t]);
+    __syncthreads();                   // every wave holds its rows of K_0: the slot takes K_2
+    if (n_h > 2) tl.template load<0>(descK, kb2);
+#pragma unroll
+    for (int t = 0; t < KT; ++t) sT = mfma32(k0[t], qf[t], sT);
+    if (n_h > 2) wait_vm<2 * IPW>();   // V_0 and K_1 have landed
     else wait_vm0();
     __syncthreads();
-#pragma unroll
-    for (int t = 0; t < KT; ++t) sT = mfma32(lds_row(smem, ad.row(t)), qf[t], sT);
   }
-  // (two copies of the step with the roles of the two score tiles swapped: no register copies)
-  auto step = [&](int s, f32x16& sT, f32x16& sN) __attribute__((always_inline)) {
-    const int cols = min(kBlk, N - j0 * kBlk);
-    const int j3 = lut[min(s + 3, n_h - 1)];   // needed in the next step
-    // V_s and K_{s+1} have landed; the load issued after them (V_{s+1}) may stay in flight
-    if (s + 2 <= n_h) wait_vm<IPW>();
-    else wait_vm0();
-    __syncthreads();   // ... for every wave; K_s and V_{s-1} are fully consumed: their slots are refilled
-    if (2 * s + 4 < nloads) {   // K_{s+2}, V_{s+2} into the slots of V_{s-1} and K_s
-      issue_load(0, j2, kslot == 0 ? 4 : kslot - 1);
-      issue_load(1, j2, kslot);
-    } else if (s + 1 == n_h && n_0 > 0) {
-      issue_matrix(Hrow, h0, h1);   // arrives under the last step
-    }
-    ad.refresh();
-    const int voff = (kslot == 4 ? 0 : kslot + 1) * Lds::TILE;
-    const int vb0 = ad.tb[0] + voff, vb1 = ad.tb[1] + voff;
-    kslot = kslot >= 3 ? kslot - 3 : kslot + 2;   // now the slot of K_{s+1}
-    const int kb = ad.rb + kslot * Lds::TILE;
-    // (in the last step this reads a slot that holds no tile: the products below are then unused)
+  // One step; P = parity of s.  On entry K_{s+1} and V_s are in their slots for every wave, sT
+  // holds S_s; sN receives S_{s+1}.  The wave copies its operands of the step to registers first;
+  // a second barrier then frees both slots for K_{s+3} and V_{s+2}, two steps before they are
+  // needed.  The few conditions are wave-uniform branches (two scalar instructions each).
+  auto step = [&](auto Pc, int s, f32x16& sT, f32x16& sN) __attribute__((always_inline)) {
+    constexpr int P = decltype(Pc)::value;
+    constexpr int VS = (2 * P + 1) * Lds::TILE;    // V_s, then V_{s+2}
+    constexpr int KN = 2 * (1 - P) * Lds::TILE;    // K_{s+1}, then K_{s+3}
     bf16x8 ka[KT], va[2][NT];
 #pragma unroll
-    for (int t = 0; t < KT; ++t) ka[t] = lds_row(smem, ad.row_at(t, kb));
+    for (int t = 0; t < KT; ++t) ka[t] = lds_row(smem, kaddr[t] + KN);
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
       for (int et = 0; et < NT; ++et)
-        va[u][et] = lds_tr<D>(smem, ad.tr_at(et, vb0) + u * 16 * T::ROW_BYTES, ad.tr_at(et, vb1) + u * 16 * T::ROW_BYTES);
-    sched_fence();
+        va[u][et] = lds_tr<D>(smem, vaddr[0][et] + VS + u * 16 * T::ROW_BYTES, vaddr[1][et] + VS + u * 16 * T::ROW_BYTES);
     // ---- online softmax on raw scores (the 1/sqrt(d) and log2 e factors ride on the exp2
     // argument); one query per lane
-    if (cols < kBlk) {
+    if (kb0 == off_tail) {
 #pragma unroll
       for (int r = 0; r < 16; ++r)
-        if (32 * par + c_row(r, g) >= cols) sT[r] = -INFINITY;
+        if (32 * par + c_row(r, g) >= tail_cols) sT[r] = -INFINITY;
     }
     float mx = sT[0];
 #pragma unroll
@@ -305,35 +327,53 @@ __global__ __launch_bounds__(256 * QT, QT == 1 ? 2 : 1) void fwd_mfma_kernel(
       m = mnew;
     }
     const float moff = m == -INFINITY ? 0.0f : -m * c2;   // a half with no valid key yet
-    sN = zero_f32x16();
+    __syncthreads();   // every wave holds its operands of this step: both slots are refilled
+    if (s + 3 < n_h) tl.template load<KN>(descK, kb3);
+    if (s + 2 < n_h) tl.template load<VS>(descV, kb2);
+    else if (s + 1 == n_h && n_0 > 0) issue_matrix(Hrow, h0, h1);   // arrives under the last step
+    const int jn = *reinterpret_cast<const int32_t*>(reinterpret_cast<const char*>(lut) + min(lo, lomax));
+    lo += 4;
+    sched_fence();
     static_assert(KT == 8 || KT == 4, "two or four exponentials per product of the next scores");
+    sN = zero_f32x16();
 #pragma unroll
     for (int t = 0; t < KT; ++t) {
-      sN = mfma32(ka[t], qf[t], sN);   // S_{s+1}
+      sN = mfma32(ka[t], qf[t], sN);   // S_{s+1} (in the last step: of a slot that holds no tile, unused)
 #pragma unroll
       for (int r = t * (16 / KT); r < (t + 1) * (16 / KT); ++r) sT[r] = fast_exp2(fmaf(sT[r], c2, moff));
     }
-    // The row sum is taken over the bf16 values that enter the product with V (numerator and
-    // denominator of O^s see the same P), two per instruction: a dot product of each packed pair
-    // with (1, 1) accumulates in float.
+    // The row sum is taken over the float exponentials by plain additions (the packed dot
+    // product that would add two bf16 values per instruction runs on the matrix pipe and holds
+    // up the products).
     float psum = 0.0f;
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       const bf16x8 pf = c_to_operand(sT, u);
 #pragma unroll
-      for (int j2 = 0; j2 < 4; ++j2) psum = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{pf[2 * j2], pf[2 * j2 + 1]}, ones2, psum, false);
+      for (int e = 0; e < 8; ++e) psum += sT[8 * u + e];
 #pragma unroll
       for (int et = 0; et < NT; ++et) oT[et] = mfma32(va[u][et], pf, oT[et]);
     }
     lsum += psum;
-    j0 = j1;
-    j1 = j2;
-    j2 = j3;
+    kb0 = kb1;
+    kb1 = kb2;
+    kb2 = kb3;
+    kb3 = jn * tl.tile_step;
+    sched_fence();     // (the matrix products above are issued before this wait)
+    // K_{s+2} and V_{s+1}, requested a step ago, have landed; the two tiles requested in this
+    // step may stay in flight (near the end fewer were requested: everything is waited for)
+    if (s + 4 < n_h) wait_vm<2 * IPW>();
+    else wait_vm0();
+    __syncthreads();
   };
-  f32x16 sU = zero_f32x16();
-  for (int s = 0; s < n_h; s += 2) {
-    step(s, sT, sU);
-    if (s + 1 < n_h) step(s + 1, sU, sT);
+  {
+    const std::integral_constant<int, 0> p0;
+    const std::integral_constant<int, 1> p1;
+    f32x16 sU = zero_f32x16();
+    for (int s = 0; s < n_h; s += 2) {
+      step(p0, s, sT, sU);
+      if (s + 1 < n_h) step(p1, s + 1, sU, sT);
+    }
   }
   // ---- merge the two key-tile streams (par 0 / par 1) of each query half
   lsum = half_sum(lsum);
