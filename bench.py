@@ -65,6 +65,8 @@ def main() -> int:
                          "has left its idle state (a cold start runs the same kernels at about 1.6 instead of "
                          "2.0 GHz); 0 disables")
     ap.add_argument("--bq", type=int, default=64, help="query block size of the mask (64, 128, 192, 256)")
+    ap.add_argument("--wide-query-tiles", action="store_true",
+                    help="with --bq 128 / 256: the eight-wave kernels (one workgroup per pair of query tiles)")
     ap.add_argument("--agg-compare", action="store_true",
                     help="also time the accumulation line of Alg. 1 alone (random bf16 states, this workload's mask) "
                          "by the product the library uses and by the three forms the paper describes")
@@ -155,6 +157,7 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
+    sla.sla_wide_query_tiles(args.wide_query_tiles)
     p = sla.make_params(w.B, w.H, w.N, w.d, w.k_h, w.k_l, tdt, layout=lay, bq=args.bq)
     b = buffers(p)
     mask, fwd, bwd = phases(p, b)

@@ -174,6 +174,14 @@ int sla_aggregate_states(const sla_params* p, int method, const void* luts, cons
 int sla_profile_enable(int on);
 int sla_profile_read(char* buf, size_t buf_bytes);
 
+/* Query blocks of 128 or 256 tokens (Section 2.1's b_q): with on != 0 the forward and the row-wise
+ * backward kernel run one workgroup of eight waves per pair of adjacent 64-query tiles of a block,
+ * which fetches each K_j, V_j tile into LDS once for both tiles.  Off by default: measured on the
+ * headline shape the eight-wave kernels are 8 % (forward) to 15 % (dQ) slower than two four-wave
+ * workgroups that share the tiles through the L2, at every density.  Process-wide; results are the
+ * same either way up to rounding order.  Returns SLA_OK. */
+int sla_wide_query_tiles(int on);
+
 /* Measured matrix-core peak of the device at hand, for the benchmark's roofline: runs a
  * register-only loop of `iters` x 4 independent v_mfma_f32_32x32x16_bf16 per wave on every
  * compute unit (8 waves per SIMD), times it with HIP events on `stream`, WAITS for it, and writes

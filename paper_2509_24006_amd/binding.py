@@ -22,7 +22,7 @@ SLA_BHND, SLA_BNHD, SLA_STRIDED = 0, 1, 2
 SLA_AGG_GEMM, SLA_AGG_ADD, SLA_AGG_PREAGG, SLA_AGG_FOUR_RUSSIANS = 0, 1, 2, 3
 SLA_STATIC_WS_BYTES = 32 << 20
 EXPORTS = ("sla_sizes", "sla_build_mask", "sla_build_mask_static", "sla_classify_scores", "sla_forward", "sla_backward",
-           "sla_aggregate_ws_bytes", "sla_aggregate_states",
+           "sla_aggregate_ws_bytes", "sla_aggregate_states", "sla_wide_query_tiles",
            "sla_profile_enable", "sla_profile_read", "sla_profile_mfma_peak", "sla_profile_dq_atomics", "sla_strerror")
 
 
@@ -69,6 +69,7 @@ def lib() -> ctypes.CDLL:
         L.sla_aggregate_ws_bytes.argtypes = [pp, ctypes.c_int, ctypes.POINTER(ctypes.c_uint64)]
         L.sla_aggregate_states.argtypes = [pp, ctypes.c_int, vp, vp, vp, vp, vp, sz, vp]
         L.sla_profile_enable.argtypes = [ctypes.c_int]
+        L.sla_wide_query_tiles.argtypes = [ctypes.c_int]
         L.sla_profile_read.argtypes = [ctypes.c_char_p, sz]
         L.sla_profile_mfma_peak.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_double), vp]
         L.sla_profile_dq_atomics.argtypes = [pp, vp, vp, ctypes.POINTER(ctypes.c_double), vp]
@@ -276,6 +277,11 @@ def sla_aggregate_states(p: sla_params, method: int, luts: torch.Tensor, h: torc
                                       _ptr(ws), ws.numel() if ws is not None else 0, _stream()),
            "sla_aggregate_states")
     return out
+
+
+def sla_wide_query_tiles(on: bool) -> None:
+    """Eight-wave kernels for query blocks of 128 / 256 tokens (off by default: slower)."""
+    _check(lib().sla_wide_query_tiles(1 if on else 0), "sla_wide_query_tiles")
 
 
 def sla_profile_enable(on: bool) -> None:

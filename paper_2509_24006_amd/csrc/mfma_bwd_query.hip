@@ -641,7 +641,7 @@ hipError_t query_impl(const Shape& s, const BwdArgs& a, float* Ds, bf16* dHZ, bf
   const float* Zs = (const float*)((const char*)a.HZ + state_z_offset(s));
   const PreArgs pa{(const bf16*)a.W, (const bf16*)a.Os, (const bf16*)a.Ol, (const bf16*)a.HZ, Zs, s.n_0, s.phi, Ds, dHZ};
   constexpr int lds_q = PairLds<D>::BYTES, lds_p = PreLds<D>::BYTES;
-  if (s.rq % 2 == 0) {
+  if (s.rq % 2 == 0 && wide_query_tiles()) {
     SLA_TRY(ensure_dyn_lds(bwd_pre_mfma_kernel<D>, lds_p));
     {
       KernelTimer kt("bwd_pre", st);

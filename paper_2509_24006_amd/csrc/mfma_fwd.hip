@@ -543,8 +543,9 @@ hipError_t forward_impl(const Shape& s, const FwdArgs& a, bf16* hz16, bf16* WTp,
         s.n_h, s.n_0, s.phi, s.scale * kLog2e, (bf16*)a.O, (bf16*)a.Os, (bf16*)a.Ol, a.L);
     return hipSuccess;
   };
-  // query blocks of an even number of tiles: tiles 2k and 2k + 1 have the same list
-  if (s.rq % 2 == 0) SLA_TRY(launch(fwd_mfma_kernel<D, 2>, 2));
+  // query blocks of an even number of tiles: tiles 2k and 2k + 1 have the same list and may share a
+  // workgroup of eight waves (slower than two workgroups of four, hence on request only)
+  if (s.rq % 2 == 0 && wide_query_tiles()) SLA_TRY(launch(fwd_mfma_kernel<D, 2>, 2));
   else SLA_TRY(launch(fwd_mfma_kernel<D, 1>, 1));
   return hipGetLastError();
 }

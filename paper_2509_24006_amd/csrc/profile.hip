@@ -4,6 +4,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <atomic>
 #include <map>
 #include <mutex>
 #include <string>
@@ -21,7 +22,10 @@ struct Rec {
 std::mutex g_mu;
 bool g_on = false;
 std::vector<Rec> g_recs;
+std::atomic<bool> g_wide{false};
 }  // namespace
+
+bool wide_query_tiles() { return g_wide.load(); }
 
 hipError_t ensure_dyn_lds(const void* kernel, int bytes) {
   static std::mutex mu;
@@ -161,6 +165,11 @@ int sla_profile_mfma_peak(int iters, double* tflops, void* stream) {
   (void)hipEventDestroy(b);
   if (rc == SLA_OK) *tflops = (double)kGroups * 4.0 * iters * 4.0 * (2.0 * 32 * 32 * 16) / (ms * 1e-3) / 1e12;
   return rc;
+}
+
+int sla_wide_query_tiles(int on) {
+  sla::g_wide.store(on != 0);
+  return SLA_OK;
 }
 
 int sla_profile_enable(int on) {

@@ -127,5 +127,9 @@ hipError_t ensure_dyn_lds(K kernel, size_t bytes) {
   return ensure_dyn_lds(reinterpret_cast<const void*>(kernel), (int)bytes);
 }
 
+// Whether query blocks of an even number of tiles run the eight-wave kernels (sla_wide_query_tiles;
+// profile.hip holds the flag).
+bool wide_query_tiles();
+
 }  // namespace sla
 #endif

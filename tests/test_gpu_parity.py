@@ -97,6 +97,16 @@ def test_elu_feature_map(oracle, name):
     _full_case(oracle, x, w.dtype, w.k_h, w.k_l, phi=1)
 
 
+@pytest.fixture(params=[False, True], ids=["four_wave_kernels", "eight_wave_kernels"])
+def wide_tiles(request):
+    """Both kernel choices for query blocks of an even number of tiles: two four-wave workgroups
+    per pair of tiles (the default) and one eight-wave workgroup that loads K_j, V_j once."""
+    from paper_2509_24006_amd import binding as sla
+    sla.sla_wide_query_tiles(request.param)
+    yield request.param
+    sla.sla_wide_query_tiles(False)
+
+
 @pytest.mark.parametrize("name,bq,k_h,k_l", [
     ("small_bf16", 128, 0.10, 0.10),       # 18 tiles in 9 blocks; last block ragged inside its second tile
     ("small_bf16_d64", 128, 0.12, 0.15),   # 15 tiles: the last block has one tile only
@@ -106,7 +116,7 @@ def test_elu_feature_map(oracle, name):
     ("small_bf16", 256, 0.0, 0.3),         # no critical block
     ("small_bf16", 128, 0.4, 0.6),         # no marginal block
 ])
-def test_query_blocks_of_several_tiles(oracle, name, bq, k_h, k_l):
+def test_query_blocks_of_several_tiles(oracle, wide_tiles, name, bq, k_h, k_l):
     # b_q = 128, 192, 256 with b_kv = 64: the mask is predicted per block of b_q queries (pooling,
     # scores and classification on T_q rows); the oracle computes with the b_q x 64 blocks
     # directly, the library gives every 64-token tile of a query block that block's mask row
@@ -116,7 +126,7 @@ def test_query_blocks_of_several_tiles(oracle, name, bq, k_h, k_l):
 
 
 @pytest.mark.parametrize("bq", [128, 256])
-def test_query_blocks_of_several_tiles_mid_length(oracle, bq):
+def test_query_blocks_of_several_tiles_mid_length(oracle, wide_tiles, bq):
     # 41 tiles (ragged tail of 5 tokens), enough key blocks for the matrix-core state aggregation
     N, d = 2565, 128
     rng = np.random.default_rng(N + bq)
