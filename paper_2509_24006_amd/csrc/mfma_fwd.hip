@@ -62,9 +62,13 @@ __global__ __launch_bounds__(256, 4) void states_mfma_kernel(const bf16* __restr
   {
     const int row = tid >> 2, part = tid & 3;
     constexpr int CPP = D / 32;   // 16-byte chunks per thread
+    // (a thread visits its chunks in an order rotated by its row: the sixteen lanes that access LDS
+    // together, four rows of four parts, then touch sixteen different chunk positions)
+    const int rot = row & (CPP - 1);
     bf16x8 x[CPP];
 #pragma unroll
-    for (int c = 0; c < CPP; ++c) x[c] = *reinterpret_cast<const bf16x8*>(smem + swz_chunk_off<D>(row, part * CPP + c));
+    for (int c = 0; c < CPP; ++c)
+      x[c] = *reinterpret_cast<const bf16x8*>(smem + swz_chunk_off<D>(row, part * CPP + ((c + rot) & (CPP - 1))));
     float mx = 0.0f, inv = 1.0f;
     if (phi == 0) {
       mx = -INFINITY;
@@ -88,7 +92,7 @@ __global__ __launch_bounds__(256, 4) void states_mfma_kernel(const bf16* __restr
     for (int c = 0; c < CPP; ++c) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) x[c][e] = (__bf16)(ok ? phi_val((float)x[c][e], phi, mx, inv) : 0.0f);
-      *reinterpret_cast<bf16x8*>(smem + swz_chunk_off<D>(row, part * CPP + c)) = x[c];
+      *reinterpret_cast<bf16x8*>(smem + swz_chunk_off<D>(row, part * CPP + ((c + rot) & (CPP - 1)))) = x[c];
     }
   }
   __syncthreads();
