@@ -139,15 +139,14 @@ __global__ __launch_bounds__(256, 4) void states_mfma_kernel(const bf16* __restr
 // softmax statistics are per-lane scalars and P goes from C registers straight into the B
 // operand of the second product.  Each wave runs its own online softmax over its key halves;
 // the two streams of a query half are merged at the end.  K_j and V_j go global -> LDS
-// directly (swizzled, one barrier per step); V is read transposed.
+// directly (swizzled, two barriers per step); V is read transposed.
 // The scores of step s + 1 are formed under the exponentials of step s.
 //
-// The step loop is written for few instructions: a wave issues one instruction every five (vector)
-// to eight (scalar) cycles whatever its kind, and with two waves per SIMD that rate, not the matrix
-// pipe, bounds the loop.  Hence: tile slots fixed per step parity (two copies of the step, every LDS
-// offset an immediate), per-lane LDS addresses held in registers, one M0 value per tile
-// (RunLoader), the key block table read one entry per step through a running offset, the last
-// two steps as copies of their own instead of conditions inside the step.
+// The step loop is written for few instructions (a wave issues one every five to eight cycles
+// whatever its kind, and a SIMD has two waves): tile slots fixed per step parity (two copies of
+// the step, every LDS offset an immediate), per-lane LDS addresses held in registers, one M0 value
+// per tile (RunLoader), the key block table read one entry per step through a running offset, the
+// few conditions as branches of the whole wave.
 template <int D>
 struct FwdLds {
   // Slot 2p holds the K tile and slot 2p + 1 the V tile of the steps of parity p.  The scores S_s
