@@ -159,8 +159,9 @@ struct FwdLds {
   static constexpr int TILE = SwzTile<D>::BYTES;
   static constexpr int XCH_HALF = (D / 2) * 64 * 4;       // C registers of one query half
   static_assert(XCH_HALF <= TILE, "exchange areas are laid over tile slots");
-  static constexpr int STAT = 4 * TILE;
-  static constexpr int BYTES = 4 * TILE + 1024;
+  static constexpr int STAT = 4 * TILE;                  // softmax statistics of the four waves (1 KB)
+  static constexpr int ZOFF = STAT + 1024;               // Z_i (D floats)
+  static constexpr int BYTES = ZOFF + D * 4;
 };
 // Query blocks of 128 (or 256) tokens: QT = 2 adjacent 64-query tiles, which have the same list of
 // critical key blocks, share one workgroup of eight waves.  K_j and V_j are then fetched into LDS
@@ -217,7 +218,15 @@ __global__ __launch_bounds__(256 * QT, QT == 1 ? 2 : 1) void fwd_mfma_kernel(
     tm.load(dm, 0, off0);
     if (D > kBlk) tm.load(dm, 1, off1);
   };
-  const bf16* Hrow = H16 + ((size_t)bh * Tn + ic) * (D * D);
+  // H_i together with Z_i (one dword per lane of the first D / 64 waves, global -> LDS like the tiles:
+  // a load the compiler sees would be waited for behind the projection matrix's loads, which
+  // are requested before it is used)
+  auto issue_state = [&](int off0, int off1) {
+    issue_matrix(H16 + ((size_t)bh * Tn + ic) * (D * D), off0, off1);
+    if (w < D / 64)
+      load_to_lds4(tile_rsrc(Zs + ((size_t)bh * Tn + ic) * D, D * 4), (w * 64 + l) * 4,
+                   lds_base(smem) + grp * Lds::BYTES + Lds::ZOFF + w * 256);
+  };
   // Slots at the end of the loop, with p the parity of the last step: H_i goes to the slots of
   // K_{last+1} (never filled) and V_last, both free from the last step's second barrier on, the
   // exchange areas to the other two once the loop is over.
@@ -240,7 +249,7 @@ __global__ __launch_bounds__(256 * QT, QT == 1 ? 2 : 1) void fwd_mfma_kernel(
       tl.template load<3 * Lds::TILE>(descV, kb1);
     }
   } else if (n_0 > 0) {
-    issue_matrix(Hrow, h0, h1);
+    issue_state(h0, h1);
   }
   unsigned lo = 16;                                  // byte offset of the next table entry to fetch
   const unsigned lomax = 4u * (unsigned)max(n_h - 1, 0);
@@ -333,7 +342,7 @@ __global__ __launch_bounds__(256 * QT, QT == 1 ? 2 : 1) void fwd_mfma_kernel(
     __syncthreads();   // every wave holds its operands of this step: both slots are refilled
     if (s + 3 < n_h) tl.template load<KN>(descK, kb3);
     if (s + 2 < n_h) tl.template load<VS>(descV, kb2);
-    else if (s + 1 == n_h && n_0 > 0) issue_matrix(Hrow, h0, h1);   // arrives under the last step
+    else if (s + 1 == n_h && n_0 > 0) issue_state(h0, h1);   // arrives under the last step
     const int jn = *reinterpret_cast<const int32_t*>(reinterpret_cast<const char*>(lut) + min(lo, lomax));
     lo += 4;
     sched_fence();
@@ -435,7 +444,7 @@ __global__ __launch_bounds__(256 * QT, QT == 1 ? 2 : 1) void fwd_mfma_kernel(
     __syncthreads();   // the exchange area is free: the projection matrix goes there
     issue_matrix(WTp, x0, x1);
     // phi(Q) of this lane's query: the lane holds features 16 t + 8 g + s, its partner the rest
-    const float* Z = Zs + ((size_t)bh * Tn + ic) * D;
+    const float* Z = reinterpret_cast<const float*>(gsm + Lds::ZOFF);
     bf16x8 qp[KT];
     phi_fragments<KT>(qf, phi, qp);
     float den = 0.0f;
