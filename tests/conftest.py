@@ -27,3 +27,14 @@ def say(capsys):
         with capsys.disabled():
             print(f"\n[{msg}]", end="", flush=True)
     return _say
+
+
+@pytest.fixture(params=[False, True], ids=["four_wave_kernels", "eight_wave_kernels"])
+def wide_tiles(request):
+    """Both kernel choices for query blocks of an even number of tiles: two four-wave workgroups
+    per pair of tiles (the default) and one eight-wave workgroup that loads K_j, V_j once."""
+    from paper_2509_24006_amd import binding as sla
+    sla.sla_wide_query_tiles(request.param)
+    yield request.param
+    sla.sla_wide_query_tiles(False)
+

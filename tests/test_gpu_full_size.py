@@ -67,7 +67,7 @@ def test_wan_shaped_layer_against_oracle(oracle):
 
 
 @pytest.mark.timeout(600)
-def test_wan_shaped_layer_with_query_blocks_of_128(oracle):
+def test_wan_shaped_layer_with_query_blocks_of_128(oracle, wide_tiles):
     # b_q = 128, b_kv = 64 at the full size: masks of all heads bit for bit (256 x 512 per head),
     # the tables against the mask, and one head's forward and backward against the oracle, which
     # computes with the 128 x 64 blocks directly

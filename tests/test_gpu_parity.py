@@ -97,16 +97,6 @@ def test_elu_feature_map(oracle, name):
     _full_case(oracle, x, w.dtype, w.k_h, w.k_l, phi=1)
 
 
-@pytest.fixture(params=[False, True], ids=["four_wave_kernels", "eight_wave_kernels"])
-def wide_tiles(request):
-    """Both kernel choices for query blocks of an even number of tiles: two four-wave workgroups
-    per pair of tiles (the default) and one eight-wave workgroup that loads K_j, V_j once."""
-    from paper_2509_24006_amd import binding as sla
-    sla.sla_wide_query_tiles(request.param)
-    yield request.param
-    sla.sla_wide_query_tiles(False)
-
-
 @pytest.mark.parametrize("name,bq,k_h,k_l", [
     ("small_bf16", 128, 0.10, 0.10),       # 18 tiles in 9 blocks; last block ragged inside its second tile
     ("small_bf16_d64", 128, 0.12, 0.15),   # 15 tiles: the last block has one tile only
