@@ -307,19 +307,17 @@ __global__ __launch_bounds__(256, 2) void bwd_pre_mfma_kernel(
                      gf, ds, lin);
 }
 
+// LDS of the row-wise dQ kernel: two pair buffers (K_j and V_j of the step in use and of the next
+// one); Q_i and dO_i come in through the second buffer before the loop, the output staging is laid
+// over the buffers after it.
 template <int D>
 struct PairLds {
   static constexpr int TILE = SwzTile<D>::BYTES;
   static constexpr int BUF = 2 * TILE;                   // the two tiles of a pair
-  static constexpr int STAT_OFF = 2 * BUF;
-  static constexpr int XCH = 2 * 2 * (D / 32) * 16 * 64 * 4;   // final exchange (dK/dV kernel)
-  static constexpr int TILES = 2 * BUF > XCH ? 2 * BUF : XCH;
-  static constexpr int BYTES = TILES + 2 * 2 * kBlk * 4; // + [buf][L, D^s][64]
-  static constexpr int VPARK = D >= 128 ? 2 * (3 * D / 64) * 64 * 16 : 0;   // parked V operand (dK/dV kernel)
+  static constexpr int BYTES = 2 * BUF;
   static constexpr int SP = D + 4;                        // row pitch (floats) of the output staging
-  static constexpr int STAGE = 2 * kBlk * SP * 4;         // [dV | dK][64][SP] floats (dK/dV kernel)
-  static constexpr int DKDV = BYTES + VPARK > STAGE ? BYTES + VPARK : STAGE;
-  // the second group of an eight-wave dQ workgroup: its Q_i, dO_i tiles, later its output staging
+  static_assert(kBlk * SP * 4 <= BYTES, "the output staging of a tile fits over the pair buffers");
+  // the second group of an eight-wave workgroup: its Q_i, dO_i tiles, later its output staging
   static constexpr int GROUP = (kBlk * SP * 4 > BUF ? kBlk * SP * 4 : BUF);
 };
 
