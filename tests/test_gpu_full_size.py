@@ -97,6 +97,41 @@ def test_wan_shaped_layer_with_query_blocks_of_128(oracle, wide_tiles):
     _check("wan b_q=128", "dW", dW2, g["dW"], rows=0)
 
 
+@pytest.mark.timeout(600)
+def test_dense_reference_is_softmax_attention(say):
+    # k_h = 100 %, k_l = 0: every block critical, no linear branch -- the configuration the
+    # benchmark times as its dense reference.  One head of the wan layer at full length against
+    # textbook softmax attention and its gradients, computed in float64 with matrix products over
+    # chunks of query rows (Eq. 4 and Eq. 7 with every block in the sums).
+    w = wl.WORKLOADS["wan"]
+    x_all = wl.make_inputs(w)
+    head = 5
+    x = {k: (np.ascontiguousarray(a[:, [head]]) if a.ndim == 4 else a) for k, a in x_all.items()}
+    p, Mc, luts, ws, O, saved, dQ, dK, dV, dW = _gpu_all(x, w, 1.0, 0.0, 1)
+    assert bool((Mc == 1).all()), "every block is critical"
+    say("dense: GPU call done")
+    t64 = lambda a: torch.from_numpy(a[0, 0]).to(torch.float64)
+    Q, K, V, dO = t64(x["Q"]), t64(x["K"]), t64(x["V"]), t64(x["dO"])
+    N, d = Q.shape
+    scale = 1.0 / np.sqrt(d)
+    Oref, dQref = torch.empty_like(Q), torch.empty_like(Q)
+    dKref, dVref = torch.zeros_like(K), torch.zeros_like(V)
+    for r0 in range(0, N, 2048):
+        r1 = min(N, r0 + 2048)
+        P = torch.softmax((Q[r0:r1] @ K.T) * scale, dim=1)
+        Oc = P @ V
+        Oref[r0:r1] = Oc
+        dP = dO[r0:r1] @ V.T
+        dS = P * (dP - (dO[r0:r1] * Oc).sum(1, keepdim=True))
+        dQref[r0:r1] = (dS @ K) * scale
+        dKref += (dS.T @ Q[r0:r1]) * scale
+        dVref += P.T @ dO[r0:r1]
+    say("dense: reference done")
+    for name, got, ref in (("O", O, Oref), ("dQ", dQ, dQref), ("dK", dK, dKref), ("dV", dV, dVref)):
+        _check("dense", name, got, ref.numpy()[None, None])
+    assert float(dW.abs().max()) == 0.0, "no marginal block: no gradient for the projection"
+
+
 @pytest.mark.timeout(900)
 def test_sweep_masks_forward_and_backward(oracle, say):
     # sparsity sweep on the Wan-shaped layer: bit-exact masks at every k_h; forward and backward
