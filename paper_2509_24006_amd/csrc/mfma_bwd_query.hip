@@ -341,7 +341,7 @@ struct PreArgs {
   bf16* dHZ;
 };
 template <int D, int QT, bool FUSED>
-__global__ __launch_bounds__(256 * QT, QT == 1 ? 2 : 1) void bwd_dq_mfma_kernel(
+__global__ __launch_bounds__(256 * QT, QT == 1 ? (D == 64 ? 3 : 2) : 1) void bwd_dq_mfma_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
     const bf16* __restrict__ dO, const float* __restrict__ L, const float* __restrict__ Ds,
     const int32_t* __restrict__ row_idx, const bf16* __restrict__ dQlin, int N, int Tn, Lay lay, int n_h,
